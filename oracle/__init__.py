@@ -1,0 +1,173 @@
+"""ctypes front end of the fp64 CPU oracle in ``ciar_oracle.c`` (TEST INFRASTRUCTURE).
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may
+import this package.  It shares nothing with the HIP library: it compiles its own C file with
+gcc and talks to it through numpy arrays.
+
+Logit arrays are ``numpy.float32`` (dtype code 0) or ``numpy.uint16`` holding raw bfloat16 bits
+(dtype code 1), shape [N, row_stride] or [N, V], C-contiguous.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ciar_oracle.c")
+_LIB = os.path.join(_HERE, "libciar_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc -O2 (OpenMP only spreads rows over threads)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class _CParams(ctypes.Structure):
+    _fields_ = [("vocab", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("row_stride", ctypes.c_int64), ("kappa", ctypes.c_double),
+                ("confidence", ctypes.c_double), ("radius_max", ctypes.c_double),
+                ("tau", ctypes.c_double), ("lower_cap", ctypes.c_double),
+                ("upper_cap", ctypes.c_double), ("normalize", ctypes.c_int32),
+                ("window", ctypes.c_int32)]
+
+
+@dataclass
+class Params:
+    """Parameters of the pass.  ``kappa < 0`` derives the radius from ``confidence``."""
+    confidence: float = 0.9
+    kappa: float = -1.0
+    radius_max: float = 10.0
+    tau: float = 0.30
+    lower_cap: float = 0.99
+    upper_cap: float = 1.01
+    normalize: bool = True
+    window: int = 8
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        pp = ctypes.POINTER(_CParams)
+        lib.ciar_oracle_kappa.restype = ctypes.c_double
+        lib.ciar_oracle_kappa.argtypes = [ctypes.c_double]
+        lib.ciar_oracle_quantify.restype = i32
+        lib.ciar_oracle_quantify.argtypes = [vp, vp, i64, pp] + [vp] * 7 + [i32]
+        lib.ciar_oracle_dense_intervals.restype = i32
+        lib.ciar_oracle_dense_intervals.argtypes = [vp, i64, pp, vp, vp, vp]
+        lib.ciar_oracle_residual_cdf.restype = ctypes.c_double
+        lib.ciar_oracle_residual_cdf.argtypes = [vp, vp, i64, pp, vp]
+        lib.ciar_oracle_verify.restype = i32
+        lib.ciar_oracle_verify.argtypes = [vp, vp, vp, vp, vp, i64, pp] + [vp] * 6 + [i32]
+        _lib = lib
+    return _lib
+
+
+def _logits(a) -> np.ndarray:
+    """Accept numpy float32 / uint16(bf16 bits) or a CPU torch tensor (float32 / bfloat16)."""
+    if not isinstance(a, np.ndarray):
+        import torch
+        assert isinstance(a, torch.Tensor) and a.device.type == "cpu"
+        if a.dtype == torch.bfloat16:
+            a = a.contiguous().view(torch.int16).numpy().view(np.uint16)
+        else:
+            a = a.contiguous().numpy()
+    assert a.dtype in (np.float32, np.uint16), a.dtype
+    assert a.ndim == 2 and a.flags.c_contiguous
+    return a
+
+
+def _cparams(p: Params, logits: np.ndarray, vocab: int | None) -> _CParams:
+    V = int(vocab if vocab is not None else logits.shape[1])
+    assert 1 <= V <= logits.shape[1]
+    return _CParams(V, 0 if logits.dtype == np.float32 else 1, logits.shape[1],
+                    float(p.kappa), float(p.confidence), float(p.radius_max), float(p.tau),
+                    float(p.lower_cap), float(p.upper_cap), int(bool(p.normalize)), int(p.window))
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def kappa(confidence: float) -> float:
+    return float(_load().ciar_oracle_kappa(float(confidence)))
+
+
+def default_threads() -> int:
+    return max(1, min(len(os.sched_getaffinity(0)), int(os.environ.get("OMP_NUM_THREADS", "1024"))))
+
+
+def quantify(draft, ids, params: Params, vocab: int | None = None, threads: int | None = None):
+    """Returns dict of fp64 arrays p_lo, p_mid, p_hi, omega, sigma, score and uint8 flags, each [N]."""
+    c = _logits(draft)
+    N = c.shape[0]
+    cp = _cparams(params, c, vocab)
+    ids32 = None if ids is None else np.ascontiguousarray(np.asarray(ids), dtype=np.int32)
+    if ids32 is not None:
+        assert ids32.shape == (N,) and (N == 0 or (ids32.min() >= 0 and ids32.max() < cp.vocab))
+    out = {k: np.empty(N, dtype=np.float64) for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score")}
+    out["flags"] = np.empty(N, dtype=np.uint8)
+    rc = _load().ciar_oracle_quantify(_ptr(c), _ptr(ids32), N, ctypes.byref(cp),
+                                      _ptr(out["p_lo"]), _ptr(out["p_mid"]), _ptr(out["p_hi"]),
+                                      _ptr(out["omega"]), _ptr(out["sigma"]), _ptr(out["score"]),
+                                      _ptr(out["flags"]), threads or default_threads())
+    assert rc == 0
+    return out
+
+
+def dense_intervals(draft, params: Params, vocab: int | None = None):
+    """Returns (p_lo, p_mid, p_hi), fp64 [N, V]."""
+    c = _logits(draft)
+    cp = _cparams(params, c, vocab)
+    N, V = c.shape[0], cp.vocab
+    lo, mid, hi = (np.empty((N, V), dtype=np.float64) for _ in range(3))
+    rc = _load().ciar_oracle_dense_intervals(_ptr(c), N, ctypes.byref(cp), _ptr(lo), _ptr(mid), _ptr(hi))
+    assert rc == 0
+    return lo, mid, hi
+
+
+def residual_cdf(draft, target, row: int, params: Params, vocab: int | None = None):
+    """Inclusive running sum of max(0, q - p) over the vocabulary of one row, and its total R."""
+    c, t = _logits(draft), _logits(target)
+    assert c.shape == t.shape and c.dtype == t.dtype
+    cp = _cparams(params, c, vocab)
+    cdf = np.empty(cp.vocab, dtype=np.float64)
+    R = _load().ciar_oracle_residual_cdf(_ptr(c), _ptr(t), int(row), ctypes.byref(cp), _ptr(cdf))
+    return cdf, float(R)
+
+
+def verify(draft, target, ids, u_accept, u_resample, params: Params, vocab: int | None = None,
+           threads: int | None = None):
+    """Returns dict: accept uint8 [N], row_id int32 [N], accept_len / resampled_id int32 [W],
+    log_ratio / res_margin fp64 [N] (diagnostics for the margin rule)."""
+    c, t = _logits(draft), _logits(target)
+    assert c.shape == t.shape and c.dtype == t.dtype
+    N = c.shape[0]
+    cp = _cparams(params, c, vocab)
+    ids32 = np.ascontiguousarray(np.asarray(ids), dtype=np.int32)
+    ua = np.ascontiguousarray(np.asarray(u_accept), dtype=np.float32)
+    ur = np.ascontiguousarray(np.asarray(u_resample), dtype=np.float32)
+    assert ids32.shape == (N,) and ua.shape == (N,) and ur.shape == (N,)
+    assert N == 0 or (ids32.min() >= 0 and ids32.max() < cp.vocab)
+    W = (N + cp.window - 1) // cp.window
+    out = {"accept": np.empty(N, dtype=np.uint8), "row_id": np.empty(N, dtype=np.int32),
+           "accept_len": np.empty(W, dtype=np.int32), "resampled_id": np.empty(W, dtype=np.int32),
+           "log_ratio": np.empty(N, dtype=np.float64), "res_margin": np.empty(N, dtype=np.float64)}
+    rc = _load().ciar_oracle_verify(_ptr(c), _ptr(t), _ptr(ids32), _ptr(ua), _ptr(ur), N, ctypes.byref(cp),
+                                    _ptr(out["accept"]), _ptr(out["row_id"]), _ptr(out["accept_len"]),
+                                    _ptr(out["resampled_id"]), _ptr(out["log_ratio"]),
+                                    _ptr(out["res_margin"]), threads or default_threads())
+    assert rc == 0
+    return out

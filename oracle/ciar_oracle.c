@@ -1,0 +1,353 @@
+/*
+ * CIAR quantify + verify -- reference oracle (TEST INFRASTRUCTURE, not product code).
+ *
+ * A plain, slow, fp64 CPU evaluation of what the device-side self-verification pass
+ * of CIAR computes for every drafted image-token position, written from the paper:
+ *
+ *   - softmax of the centre logits with the max-trick      (Sec. 3.2.3 "p = softmax(o)";
+ *                                                            App. "Proof of Interval Validity", last paragraph)
+ *   - InterFuse lower / upper probability bounds            (App. "Proof of Interval Validity", the two
+ *                                                            equations that define p^l_i and p^u_i)
+ *   - the 0.99 / 1.01 normalisation of the bounds           (same appendix, the two scaling equations)
+ *   - widths delta, Total Ambiguity Omega, Confidence
+ *     Disparity Sigma (population std), score U = Omega*Sigma (Eq. "uncertainty_score"; App. "Analysis of the
+ *                                                            Uncertainty Quantification", first three equations)
+ *   - the threshold rule  "accept locally iff U <= tau"     (Algorithm 1, the test on U_t)
+ *   - cloud verification of a window of K drafted tokens and resampling (Algorithm 1, the "Cloud verification"
+ *     step and the following resample / advance steps).  The paper names this step as speculative decoding
+ *     (Introduction) without writing the test down; this file uses the standard speculative-sampling rule:
+ *     accept x ~ p with probability min(1, q(x)/p(x)), otherwise draw from (q - p)^+ / ||(q - p)^+||_1,
+ *     p = softmax(centre logits), q = softmax(target logits).
+ *
+ * Every sum runs sequentially in index order, in double precision.  There is no blocking,
+ * no fusion and no reordering.  Only tests/, __graft_entry__.smoke() and the cpu_baseline
+ * leg of bench.py may call this file; the product path never does.  It shares no code with
+ * the HIP kernels.
+ *
+ * Parity pins: every function here is pinned by tests/test_oracle_pins.py (library softmax,
+ * logistic sigmoid for V = 2, closed forms for uniform and one-hot rows, the appendix's
+ * claims and propositions, brute-force enumeration of the acceptance law for V <= 8).
+ *
+ * Parameters not fixed by the paper (stated as readings where this repo documents them):
+ *   - kappa: the logit half-width r.  The paper's radius comes from a trained head; here a
+ *     scalar radius is either given directly or derived from an "interval confidence" gamma
+ *     as the two-sided standard-normal quantile kappa = sqrt(2) * erfinv(gamma).
+ *   - radius_max: the clamp on the radius (the paper clamps but gives no value).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct ciar_oracle_params {
+    int32_t vocab;        /* V >= 1 */
+    int32_t dtype;        /* 0 = float32 logits, 1 = bfloat16 logits (raw uint16) */
+    int64_t row_stride;   /* elements between consecutive rows, >= V */
+    double  kappa;        /* scalar logit radius before the clamp; if < 0 it is derived from confidence */
+    double  confidence;   /* gamma in (0,1), used only when kappa < 0 */
+    double  radius_max;   /* clamp on the radius */
+    double  tau;          /* threshold on U */
+    double  lower_cap;    /* 0.99 in the paper */
+    double  upper_cap;    /* 1.01 in the paper */
+    int32_t normalize;    /* 1 = apply the caps, 0 = raw InterFuse */
+    int32_t window;       /* K >= 1: drafted tokens per cloud verification call */
+} ciar_oracle_params;
+
+/* ---- input widening ------------------------------------------------------------------ */
+
+static double load_logit(const void* base, int32_t dtype, int64_t index)
+{
+    if (dtype == 0) {
+        return (double)((const float*)base)[index];
+    } else {
+        /* bfloat16 is the upper half of an IEEE float32: widening is exact. */
+        uint32_t bits = ((uint32_t)((const uint16_t*)base)[index]) << 16;
+        float f;
+        memcpy(&f, &bits, sizeof f);
+        return (double)f;
+    }
+}
+
+/* ---- radius ------------------------------------------------------------------------- */
+
+/* kappa(gamma) = sqrt(2) * erfinv(gamma): the z with P(|Z| <= z) = gamma for Z ~ N(0,1).
+ * Solved by bisection on erf (monotone), which needs no inverse-erf routine. */
+double ciar_oracle_kappa(double gamma)
+{
+    if (!(gamma > 0.0)) return 0.0;
+    if (!(gamma < 1.0)) return INFINITY;
+    double lo = 0.0, hi = 40.0;
+    for (int it = 0; it < 200; ++it) {
+        double mid = 0.5 * (lo + hi);
+        if (erf(mid / sqrt(2.0)) < gamma) lo = mid; else hi = mid;
+    }
+    return 0.5 * (lo + hi);
+}
+
+static double scalar_radius(const ciar_oracle_params* P)
+{
+    double kappa = P->kappa >= 0.0 ? P->kappa : ciar_oracle_kappa(P->confidence);
+    return kappa < P->radius_max ? kappa : P->radius_max;
+}
+
+/* ---- one row of the quantifier -------------------------------------------------------- */
+
+/* Fills e[i] = exp(c_i - max c) and returns S = sum_i e[i]; *m_out = max c. */
+static double row_exponentials(const void* logits, const ciar_oracle_params* P, int64_t row,
+                               double* e, double* m_out)
+{
+    const int64_t off = row * P->row_stride;
+    const int V = P->vocab;
+    double m = -INFINITY;
+    for (int i = 0; i < V; ++i) {
+        double c = load_logit(logits, P->dtype, off + i);
+        if (c > m) m = c;
+    }
+    double S = 0.0;
+    for (int i = 0; i < V; ++i) {
+        double c = load_logit(logits, P->dtype, off + i);
+        e[i] = exp(c - m);
+        S += e[i];
+    }
+    *m_out = m;
+    return S;
+}
+
+/* InterFuse bounds for the whole row, normalised if requested.
+ * In: e[i], S.  Out: pl[i], pu[i] (the final, possibly scaled, bounds). */
+static void row_interfuse(const double* e, double S, const ciar_oracle_params* P,
+                          double* pl, double* pu)
+{
+    const int V = P->vocab;
+    const double r = scalar_radius(P);
+    double Sl = 0.0, Su = 0.0;
+    for (int i = 0; i < V; ++i) {
+        double down = e[i] * exp(-r);   /* exp(c_i - r_i) up to the common shift */
+        double up   = e[i] * exp(r);    /* exp(c_i + r_i) up to the common shift */
+        pl[i] = down / (S - e[i] + down);
+        pu[i] = up / (S - e[i] + up);
+        Sl += pl[i];
+        Su += pu[i];
+    }
+    if (P->normalize) {
+        double fl = P->lower_cap / Sl; if (fl > 1.0) fl = 1.0;   /* min(1, 0.99/S_l) */
+        double fu = P->upper_cap / Su; if (fu < 1.0) fu = 1.0;   /* max(1, 1.01/S_u) */
+        for (int i = 0; i < V; ++i) { pl[i] *= fl; pu[i] *= fu; }
+    }
+}
+
+static int lowest_argmax(const double* x, int V)
+{
+    int k = 0;
+    for (int i = 1; i < V; ++i) if (x[i] > x[k]) k = i;
+    return k;
+}
+
+/*
+ * Quantifier for rows [0, N).  Outputs are fp64; any output pointer may be NULL.
+ *   ids == NULL: the reported token is the lowest-index argmax of the centre logits.
+ *   flags[i] = 1 means "uncertain, send to the cloud" = (U > tau); U == tau is not flagged.
+ * Returns 0, or -1 on allocation failure.
+ */
+int ciar_oracle_quantify(const void* draft, const int32_t* ids, int64_t N,
+                         const ciar_oracle_params* P,
+                         double* p_lo, double* p_mid, double* p_hi,
+                         double* omega, double* sigma, double* score, uint8_t* flags,
+                         int threads)
+{
+    const int V = P->vocab;
+    int failed = 0;
+    if (threads < 1) threads = 1;
+#pragma omp parallel num_threads(threads)
+    {
+        double* e  = (double*)malloc(sizeof(double) * (size_t)V);
+        double* pl = (double*)malloc(sizeof(double) * (size_t)V);
+        double* pu = (double*)malloc(sizeof(double) * (size_t)V);
+        if (!e || !pl || !pu) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+#pragma omp for schedule(static)
+            for (int64_t row = 0; row < N; ++row) {
+                double m;
+                double S = row_exponentials(draft, P, row, e, &m);
+                row_interfuse(e, S, P, pl, pu);
+
+                /* widths, L1 norm, population standard deviation (two passes) */
+                double Om = 0.0;
+                for (int i = 0; i < V; ++i) Om += pu[i] - pl[i];
+                double mean = Om / (double)V;
+                double ss = 0.0;
+                for (int i = 0; i < V; ++i) {
+                    double d = (pu[i] - pl[i]) - mean;
+                    ss += d * d;
+                }
+                double Sg = sqrt(ss / (double)V);
+                double U = Om * Sg;
+
+                int x = ids ? ids[row] : lowest_argmax(e, V);
+                if (p_lo)  p_lo[row]  = pl[x];
+                if (p_mid) p_mid[row] = e[x] / S;
+                if (p_hi)  p_hi[row]  = pu[x];
+                if (omega) omega[row] = Om;
+                if (sigma) sigma[row] = Sg;
+                if (score) score[row] = U;
+                if (flags) flags[row] = (uint8_t)(U > P->tau);
+            }
+        }
+        free(e); free(pl); free(pu);
+    }
+    return failed ? -1 : 0;
+}
+
+/* Dense export of the three per-token curves, [N, V] each, for tests. */
+int ciar_oracle_dense_intervals(const void* draft, int64_t N, const ciar_oracle_params* P,
+                                double* p_lo, double* p_mid, double* p_hi)
+{
+    const int V = P->vocab;
+    double* e = (double*)malloc(sizeof(double) * (size_t)V);
+    if (!e) return -1;
+    for (int64_t row = 0; row < N; ++row) {
+        double m;
+        double S = row_exponentials(draft, P, row, e, &m);
+        row_interfuse(e, S, P, p_lo + row * (int64_t)V, p_hi + row * (int64_t)V);
+        for (int i = 0; i < V; ++i) p_mid[row * (int64_t)V + i] = e[i] / S;
+    }
+    free(e);
+    return 0;
+}
+
+/* ---- verification -------------------------------------------------------------------- */
+
+/*
+ * Residual distribution of one row: res_i = max(0, q_i - p_i) and its inclusive running
+ * sum C_j in index order.  cdf must hold V doubles.  Returns R = C_{V-1}.
+ */
+double ciar_oracle_residual_cdf(const void* draft, const void* target, int64_t row,
+                                const ciar_oracle_params* P, double* cdf)
+{
+    const int V = P->vocab;
+    double* e  = (double*)malloc(sizeof(double) * (size_t)V);
+    double* et = (double*)malloc(sizeof(double) * (size_t)V);
+    if (!e || !et) { free(e); free(et); return NAN; }
+    double m, mt;
+    double S = row_exponentials(draft, P, row, e, &m);
+    double Z = row_exponentials(target, P, row, et, &mt);
+    double run = 0.0;
+    for (int i = 0; i < V; ++i) {
+        double res = et[i] / Z - e[i] / S;
+        if (res < 0.0) res = 0.0;
+        run += res;
+        cdf[i] = run;
+    }
+    free(e); free(et);
+    return run;
+}
+
+/*
+ * Speculative verification of rows [0, N) in windows of K consecutive rows.
+ *   accept[i]      = 1 iff ln(u_accept[i]) < min(0, ln q_x - ln p_x), x = ids[i]  (ln 0 = -inf: accept)
+ *   row_id[i]      = -1 if accepted, else the residual sample:
+ *                    the smallest j with C_j > u_resample[i] * R; if rounding leaves none, the largest j
+ *                    with res_j > 0; if R == 0, the lowest-index argmax of q
+ *   accept_len[w]  = number of leading accepted rows of window w = rows [wK, min((w+1)K, N))
+ *   resampled[w]   = row_id of the first rejected row of the window, -1 if none
+ * Diagnostics for the comparison's margin rule (any may be NULL):
+ *   log_ratio[i]   = ln q_x - ln p_x
+ *   res_margin[i]  = for rejected rows min(|C_id - T|, |C_{id-1} - T|) / R with T = u*R (C_{-1} = 0);
+ *                    +inf for accepted rows and for R == 0
+ */
+int ciar_oracle_verify(const void* draft, const void* target, const int32_t* ids,
+                       const float* u_accept, const float* u_resample, int64_t N,
+                       const ciar_oracle_params* P,
+                       uint8_t* accept, int32_t* row_id,
+                       int32_t* accept_len, int32_t* resampled,
+                       double* log_ratio, double* res_margin, int threads)
+{
+    const int V = P->vocab;
+    const int64_t K = P->window;
+    int failed = 0;
+    if (threads < 1) threads = 1;
+    uint8_t* acc_all = (uint8_t*)malloc((size_t)(N > 0 ? N : 1));
+    int32_t* id_all  = (int32_t*)malloc(sizeof(int32_t) * (size_t)(N > 0 ? N : 1));
+    if (!acc_all || !id_all) { free(acc_all); free(id_all); return -1; }
+
+#pragma omp parallel num_threads(threads)
+    {
+        double* e  = (double*)malloc(sizeof(double) * (size_t)V);
+        double* et = (double*)malloc(sizeof(double) * (size_t)V);
+        if (!e || !et) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+#pragma omp for schedule(static)
+            for (int64_t row = 0; row < N; ++row) {
+                double m, mt;
+                double S = row_exponentials(draft, P, row, e, &m);
+                double Z = row_exponentials(target, P, row, et, &mt);
+                const int x = ids[row];
+                const double cx = load_logit(draft, P->dtype, row * P->row_stride + x);
+                const double tx = load_logit(target, P->dtype, row * P->row_stride + x);
+                const double ell = (tx - mt - log(Z)) - (cx - m - log(S));
+                const double lnu = log((double)u_accept[row]);        /* log(0) = -inf */
+                const double bar = ell < 0.0 ? ell : 0.0;
+                const int ok = lnu < bar;
+                int id = -1;
+                double margin = INFINITY;
+                if (!ok) {
+                    /* residual inverse-CDF draw, index order */
+                    double R = 0.0;
+                    for (int i = 0; i < V; ++i) {
+                        double res = et[i] / Z - e[i] / S;
+                        if (res > 0.0) R += res;
+                    }
+                    if (R > 0.0) {
+                        const double T = (double)u_resample[row] * R;
+                        double run = 0.0, prev = 0.0;
+                        int last_positive = -1;
+                        for (int i = 0; i < V; ++i) {
+                            double res = et[i] / Z - e[i] / S;
+                            if (res < 0.0) res = 0.0;
+                            prev = run;
+                            run += res;
+                            if (res > 0.0) last_positive = i;
+                            if (run > T) {
+                                id = i;
+                                double a = fabs(run - T), b = fabs(prev - T);
+                                margin = (a < b ? a : b) / R;
+                                break;
+                            }
+                        }
+                        if (id < 0) { id = last_positive; margin = 0.0; }
+                    } else {
+                        id = lowest_argmax(et, V);
+                    }
+                }
+                acc_all[row] = (uint8_t)ok;
+                id_all[row] = id;
+                if (log_ratio)  log_ratio[row] = ell;
+                if (res_margin) res_margin[row] = margin;
+            }
+        }
+        free(e); free(et);
+    }
+
+    if (!failed) {
+        if (accept) memcpy(accept, acc_all, (size_t)N);
+        if (row_id) memcpy(row_id, id_all, sizeof(int32_t) * (size_t)N);
+        const int64_t W = (N + K - 1) / K;
+        for (int64_t w = 0; w < W; ++w) {
+            const int64_t lo = w * K, hi = (lo + K < N) ? lo + K : N;
+            int64_t n = 0;
+            while (lo + n < hi && acc_all[lo + n]) ++n;
+            if (accept_len) accept_len[w] = (int32_t)n;
+            if (resampled)  resampled[w] = (lo + n < hi) ? id_all[lo + n] : -1;
+        }
+    }
+    free(acc_all); free(id_all);
+    return failed ? -1 : 0;
+}

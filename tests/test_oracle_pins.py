@@ -1,0 +1,504 @@
+"""Pins of the fp64 CPU oracle against what the paper and the mathematics fix.
+
+None of these tests touches the GPU or the HIP library.  Each pin compares the oracle with
+something other than itself: a library routine (scipy softmax / expit / erfinv, numpy std),
+a closed form, a bound or identity proved in the paper's appendix, or brute-force enumeration
+on a tiny vocabulary.  Citations name the paper's sections, equations and claims.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special as sps
+import scipy.stats as spst
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "closed_forms.txt")
+
+
+def _golden():
+    vals = {}
+    with open(GOLDEN) as f:
+        for line in f:
+            line = line.split("#", 1)[0].strip()
+            if line:
+                k, v = line.split("=")
+                vals[k.strip()] = float(v)
+    return vals
+
+
+def _rows(rng, n, V, scale=2.0):
+    return (rng.standard_normal((n, V)) * scale).astype(np.float32)
+
+
+# ---- radius from the interval confidence -------------------------------------------------
+
+def test_kappa_is_the_two_sided_normal_quantile(oracle):
+    g = _golden()
+    # textbook z-table values (two-sided 80 / 90 / 95 % intervals)
+    assert abs(oracle.kappa(0.80) - g["kappa_0.80"]) < 5e-5
+    assert abs(oracle.kappa(0.90) - g["kappa_0.90"]) < 5e-5
+    assert abs(oracle.kappa(0.95) - g["kappa_0.95"]) < 5e-5
+    for gam in (0.1, 0.5, 0.8, 0.9, 0.95, 0.999):
+        assert abs(oracle.kappa(gam) - math.sqrt(2.0) * sps.erfinv(gam)) < 1e-12
+        assert abs(oracle.kappa(gam) - spst.norm.ppf(0.5 + gam / 2)) < 1e-10
+
+
+# ---- softmax and InterFuse --------------------------------------------------------------
+
+def test_zero_radius_reduces_to_library_softmax(oracle):
+    """r = 0, no caps: p^l = p^u = softmax(c); Omega = Sigma = U = 0.  (InterFuse equations with r_i = 0)"""
+    rng = np.random.default_rng(1)
+    c = _rows(rng, 5, 97, 3.0)
+    P = oracle.Params(kappa=0.0, normalize=False)
+    lo, mid, hi = oracle.dense_intervals(c, P)
+    ref = sps.softmax(c.astype(np.float64), axis=1)
+    np.testing.assert_allclose(mid, ref, rtol=1e-13, atol=0)
+    np.testing.assert_allclose(lo, ref, rtol=1e-13, atol=0)
+    np.testing.assert_allclose(hi, ref, rtol=1e-13, atol=0)
+    np.testing.assert_allclose(mid.sum(1), 1.0, rtol=1e-13)
+    q = oracle.quantify(c, None, P)
+    assert np.all(np.abs(q["omega"]) < 1e-14) and np.all(q["score"] < 1e-15)
+
+
+def test_zero_radius_with_caps_scales_by_099_and_101(oracle):
+    """r = 0 with the normalisation on: S_l = S_u = 1, so p^l = 0.99 p, p^u = 1.01 p,
+    Omega = 0.02 and Sigma = 0.02 std(p).  (normalisation equations of the validity appendix)"""
+    rng = np.random.default_rng(2)
+    c = _rows(rng, 4, 64, 2.0)
+    P = oracle.Params(kappa=0.0, normalize=True)
+    lo, mid, hi = oracle.dense_intervals(c, P)
+    ref = sps.softmax(c.astype(np.float64), axis=1)
+    np.testing.assert_allclose(lo, 0.99 * ref, rtol=1e-12)
+    np.testing.assert_allclose(hi, 1.01 * ref, rtol=1e-12)
+    q = oracle.quantify(c, None, P)
+    np.testing.assert_allclose(q["omega"], 0.02, rtol=1e-10)
+    np.testing.assert_allclose(q["sigma"], 0.02 * ref.std(axis=1), rtol=1e-9)
+
+
+def test_two_token_vocabulary_is_the_logistic_sigmoid(oracle):
+    """V = 2: p_1 = sigma(c1 - c2), p^u_1 = sigma(c1 - c2 + r), p^l_1 = sigma(c1 - c2 - r)."""
+    rng = np.random.default_rng(3)
+    c = _rows(rng, 50, 2, 3.0)
+    r = 0.7
+    lo, mid, hi = oracle.dense_intervals(c, oracle.Params(kappa=r, normalize=False))
+    d = c[:, 0].astype(np.float64) - c[:, 1].astype(np.float64)
+    np.testing.assert_allclose(mid[:, 0], sps.expit(d), rtol=1e-13)
+    np.testing.assert_allclose(hi[:, 0], sps.expit(d + r), rtol=1e-13)
+    np.testing.assert_allclose(lo[:, 0], sps.expit(d - r), rtol=1e-13)
+    np.testing.assert_allclose(hi[:, 1], sps.expit(-d + r), rtol=1e-13)
+    np.testing.assert_allclose(lo[:, 1], sps.expit(-d - r), rtol=1e-13)
+
+
+def test_interfuse_equals_softmax_of_the_row_with_one_logit_shifted(oracle):
+    """The denominator of p^u_i is the partition sum of the row whose i-th logit is raised by r
+    (and lowered by r for p^l_i): brute force with a library softmax, one perturbed row per token."""
+    rng = np.random.default_rng(4)
+    V, r = 11, 1.3
+    c = _rows(rng, 3, V, 2.5)
+    lo, mid, hi = oracle.dense_intervals(c, oracle.Params(kappa=r, normalize=False))
+    for n in range(c.shape[0]):
+        for i in range(V):
+            up = c[n].astype(np.float64).copy(); up[i] += r
+            dn = c[n].astype(np.float64).copy(); dn[i] -= r
+            assert abs(hi[n, i] - sps.softmax(up)[i]) < 1e-14
+            assert abs(lo[n, i] - sps.softmax(dn)[i]) < 1e-14
+
+
+def test_radius_clamp_and_confidence_mapping(oracle):
+    rng = np.random.default_rng(5)
+    c = _rows(rng, 2, 33)
+    a = oracle.dense_intervals(c, oracle.Params(kappa=50.0, radius_max=1.5, normalize=False))
+    b = oracle.dense_intervals(c, oracle.Params(kappa=1.5, radius_max=10.0, normalize=False))
+    for x, y in zip(a, b):
+        np.testing.assert_array_equal(x, y)
+    g = oracle.dense_intervals(c, oracle.Params(confidence=0.9, normalize=False))
+    k = oracle.dense_intervals(c, oracle.Params(kappa=math.sqrt(2) * sps.erfinv(0.9), normalize=False))
+    for x, y in zip(g, k):
+        np.testing.assert_allclose(x, y, rtol=1e-12)
+
+
+def test_validity_and_ordering_invariants(oracle):
+    """p^l <= p_mid <= p^u, S_l <= 1 <= S_u raw; S_l <= 0.99 and S_u >= 1.01 after the caps."""
+    rng = np.random.default_rng(6)
+    for V, scale in ((7, 1.0), (256, 0.2), (256, 4.0), (1000, 8.0)):
+        c = _rows(rng, 6, V, scale)
+        c[0, :] = 0.0                      # uniform
+        c[1, :] = 0.0; c[1, 3] = 40.0      # one-hot
+        for kap in (0.0, 0.3, 1.6449, 10.0):
+            lo, mid, hi = oracle.dense_intervals(c, oracle.Params(kappa=kap, normalize=False))
+            assert np.all(lo >= 0) and np.all(hi <= 1.0 + 1e-15)
+            assert np.all(lo <= mid * (1 + 1e-14)) and np.all(mid <= hi * (1 + 1e-14))
+            assert np.all(lo.sum(1) <= 1 + 1e-12) and np.all(hi.sum(1) >= 1 - 1e-12)
+            lo, mid, hi = oracle.dense_intervals(c, oracle.Params(kappa=kap, normalize=True))
+            assert np.all(lo.sum(1) <= 0.99 * (1 + 1e-12))
+            assert np.all(hi.sum(1) >= 1.01 * (1 - 1e-12))
+            np.testing.assert_allclose(mid.sum(1), 1.0, rtol=1e-12)
+
+
+def test_uniform_row_closed_form(oracle):
+    """c = const, radius r: p^u = a/(V-1+a), p^l = b/(V-1+b), a = e^r, b = e^-r; Sigma = U = 0."""
+    g = _golden()
+    V = 16384
+    c = np.full((1, V), 0.37, dtype=np.float32)
+    P = oracle.Params(confidence=0.9, normalize=True)
+    q = oracle.quantify(c, np.array([5]), P)
+    r = math.sqrt(2) * sps.erfinv(0.9)
+    a, b = math.exp(r), math.exp(-r)
+    pu, pl = a / (V - 1 + a), b / (V - 1 + b)
+    assert V * pl < 0.99 and V * pu > 1.01          # caps inactive for this row
+    np.testing.assert_allclose(q["p_hi"], pu, rtol=1e-12)
+    np.testing.assert_allclose(q["p_lo"], pl, rtol=1e-12)
+    np.testing.assert_allclose(q["p_mid"], 1.0 / V, rtol=1e-12)
+    np.testing.assert_allclose(q["omega"], V * (pu - pl), rtol=1e-12)
+    assert abs(q["omega"][0] - g["omega_uniform_V16384_conf0.9"]) < 1e-6
+    assert q["sigma"][0] < 1e-12 and q["score"][0] < 1e-12
+    assert q["flags"][0] == 0
+
+
+def test_one_hot_row_closed_form(oracle):
+    """One logit far above the rest.  Raw: Omega -> 0 (local-certainty proposition).
+    With the caps: delta = 0.02 on that token only, so Omega = 0.02 and
+    U = 0.02^2 sqrt(V-1)/V, the equality case of the Sigma <= sqrt(n-1)/n Omega claim."""
+    g = _golden()
+    V = 16384
+    c = np.zeros((1, V), dtype=np.float32)
+    c[0, 77] = 80.0
+    raw = oracle.quantify(c, np.array([77]), oracle.Params(confidence=0.9, normalize=False))
+    assert raw["omega"][0] < 1e-25 and raw["score"][0] < 1e-40
+    np.testing.assert_allclose(raw["p_lo"], 1.0, rtol=1e-12)
+    np.testing.assert_allclose(raw["p_hi"], 1.0, rtol=1e-12)
+    q = oracle.quantify(c, np.array([77]), oracle.Params(confidence=0.9, normalize=True))
+    np.testing.assert_allclose(q["omega"], 0.02, rtol=1e-9)
+    np.testing.assert_allclose(q["score"], 0.02 ** 2 * math.sqrt(V - 1) / V, rtol=1e-9)
+    assert abs(q["score"][0] - g["score_onehot_V16384"]) < 1e-10
+    np.testing.assert_allclose(q["p_lo"], 0.99, rtol=1e-12)
+    np.testing.assert_allclose(q["p_hi"], 1.01, rtol=1e-12)   # the caps may lift p^u above 1
+
+
+# ---- the score -----------------------------------------------------------------------------
+
+def test_omega_sigma_score_against_numpy_on_the_dense_curves(oracle):
+    """Omega = ||delta||_1, Sigma = population std of delta (numpy.std, ddof = 0), U = Omega Sigma.
+    (Eq. uncertainty_score)"""
+    rng = np.random.default_rng(7)
+    c = _rows(rng, 8, 311, 2.0)
+    for norm in (False, True):
+        P = oracle.Params(confidence=0.9, normalize=norm)
+        lo, mid, hi = oracle.dense_intervals(c, P)
+        d = hi - lo
+        q = oracle.quantify(c, None, P)
+        np.testing.assert_allclose(q["omega"], d.sum(1), rtol=1e-12)
+        np.testing.assert_allclose(q["sigma"], d.std(axis=1, ddof=0), rtol=1e-10)
+        np.testing.assert_allclose(q["score"], d.sum(1) * d.std(axis=1), rtol=1e-10)
+        # a sample (ddof = 1) standard deviation must be told apart
+        assert np.all(np.abs(q["sigma"] - d.std(axis=1, ddof=1)) > 1e-6 * q["sigma"])
+        # reported token defaults to the lowest-index argmax
+        am = c.argmax(1)
+        np.testing.assert_allclose(q["p_mid"], mid[np.arange(8), am], rtol=1e-13)
+        np.testing.assert_allclose(q["p_lo"], lo[np.arange(8), am], rtol=1e-13)
+        np.testing.assert_allclose(q["p_hi"], hi[np.arange(8), am], rtol=1e-13)
+
+
+def test_appendix_bounds_and_rewrites(oracle):
+    """Sigma <= sqrt(n-1)/n Omega; U <= sum(delta^2)/2; U = n mu^2 CV; U(alpha delta) = alpha^2 U."""
+    rng = np.random.default_rng(8)
+    for V, scale in ((16, 1.0), (500, 3.0), (4096, 0.5)):
+        c = _rows(rng, 10, V, scale)
+        P = oracle.Params(confidence=0.95, normalize=True)
+        q = oracle.quantify(c, None, P)
+        lo, _, hi = oracle.dense_intervals(c, P)
+        d = hi - lo
+        assert np.all(q["score"] >= 0)
+        assert np.all(q["sigma"] <= math.sqrt(V - 1) / V * q["omega"] * (1 + 1e-12))
+        assert np.all(q["score"] <= 0.5 * (d ** 2).sum(1) * (1 + 1e-12))
+        mu = q["omega"] / V
+        np.testing.assert_allclose(q["score"], V * mu ** 2 * (q["sigma"] / mu), rtol=1e-12)
+    # scaling claim: with r = 0 and the caps on, delta = (hi_cap - lo_cap) p, so widening the
+    # caps from (0.99, 1.01) to (0.98, 1.02) doubles delta and must quadruple U.
+    c = _rows(rng, 5, 128, 2.0)
+    u1 = oracle.quantify(c, None, oracle.Params(kappa=0.0, lower_cap=0.99, upper_cap=1.01))["score"]
+    u2 = oracle.quantify(c, None, oracle.Params(kappa=0.0, lower_cap=0.98, upper_cap=1.02))["score"]
+    np.testing.assert_allclose(u2, 4.0 * u1, rtol=1e-9)
+
+
+def test_feasible_set_diameter(oracle):
+    """||p - q||_1 <= Omega for distributions inside the interval box (diameter proposition)."""
+    rng = np.random.default_rng(9)
+    V = 12
+    c = _rows(rng, 1, V, 1.5)
+    lo, mid, hi = oracle.dense_intervals(c, oracle.Params(kappa=0.8, normalize=False))
+    lo, mid, hi = lo[0], mid[0], hi[0]
+    omega = oracle.quantify(c, None, oracle.Params(kappa=0.8, normalize=False))["omega"][0]
+    pts = []
+    for _ in range(200):
+        p = mid.copy()
+        for _ in range(30):     # move mass between random pairs while staying inside the box
+            i, j = rng.choice(V, 2, replace=False)
+            room = min(hi[i] - p[i], p[j] - lo[j])
+            step = rng.random() * room
+            p[i] += step; p[j] -= step
+        assert abs(p.sum() - 1) < 1e-12 and np.all(p >= lo - 1e-15) and np.all(p <= hi + 1e-15)
+        pts.append(p)
+    pts = np.array(pts)
+    diam = np.abs(pts[:, None, :] - pts[None, :, :]).sum(-1).max()
+    assert 0 < diam <= omega
+
+
+def test_width_identity_for_a_constant_radius(oracle):
+    """delta_i = x(1-x)(a-b) / [(1+(a-1)x)(1-(1-b)x)], x = p_mid,i, a = e^r, b = e^-r."""
+    rng = np.random.default_rng(10)
+    c = _rows(rng, 4, 200, 3.0)
+    r = 1.1
+    lo, mid, hi = oracle.dense_intervals(c, oracle.Params(kappa=r, normalize=False))
+    a, b = math.exp(r), math.exp(-r)
+    x = mid
+    ident = x * (1 - x) * (a - b) / ((1 + (a - 1) * x) * (1 - (1 - b) * x))
+    np.testing.assert_allclose(hi - lo, ident, rtol=1e-11, atol=1e-300)
+
+
+def test_intervals_are_nested_and_monotone_in_the_confidence(oracle):
+    """Raw InterFuse: gamma1 < gamma2 gives [p^l, p^u](gamma1) inside [p^l, p^u](gamma2); Omega grows."""
+    rng = np.random.default_rng(11)
+    c = _rows(rng, 6, 300, 2.0)
+    prev = None
+    for gam in (0.5, 0.8, 0.9, 0.95, 0.99):
+        P = oracle.Params(confidence=gam, normalize=False)
+        lo, _, hi = oracle.dense_intervals(c, P)
+        om = oracle.quantify(c, None, P)["omega"]
+        if prev is not None:
+            assert np.all(lo <= prev[0]) and np.all(hi >= prev[1]) and np.all(om > prev[2])
+        prev = (lo, hi, om)
+
+
+def test_total_ambiguity_is_maximal_at_the_uniform_row(oracle):
+    """With one radius for all tokens the width is a concave function of p_mid, so Omega is
+    Schur-concave and the uniform row maximises it (U itself is zero there by design)."""
+    rng = np.random.default_rng(12)
+    V = 64
+    P = oracle.Params(confidence=0.9, normalize=False)
+    uni = oracle.quantify(np.zeros((1, V), np.float32), None, P)["omega"][0]
+    c = np.concatenate([_rows(rng, 100, V, s) for s in (0.05, 0.5, 2.0)])
+    om = oracle.quantify(c, None, P)["omega"]
+    assert np.all(om < uni)
+    assert om[:100].max() > 0.99 * uni     # nearly flat rows come close
+
+
+def test_threshold_polarity_and_equality(oracle):
+    """Algorithm 1: accept locally iff U <= tau; the flag marks the other branch."""
+    rng = np.random.default_rng(13)
+    c = _rows(rng, 6, 100, 2.0)
+    U = oracle.quantify(c, None, oracle.Params(tau=0.0))["score"]
+    for n in range(6):
+        row = c[n:n + 1]
+        assert oracle.quantify(row, None, oracle.Params(tau=float(U[n])))["flags"][0] == 0
+        assert oracle.quantify(row, None, oracle.Params(tau=float(np.nextafter(U[n], 0))))["flags"][0] == 1
+        assert oracle.quantify(row, None, oracle.Params(tau=float(np.nextafter(U[n], 1))))["flags"][0] == 0
+
+
+# ---- input handling ------------------------------------------------------------------------
+
+def test_bf16_rows_are_widened_exactly_and_stride_padding_is_ignored(oracle):
+    import torch
+    rng = np.random.default_rng(14)
+    V, stride = 50, 56
+    c32 = _rows(rng, 3, stride, 2.0)
+    cb = torch.from_numpy(c32).to(torch.bfloat16)
+    widened = cb.to(torch.float32).numpy()
+    P = oracle.Params(confidence=0.9)
+    a = oracle.quantify(cb, None, P, vocab=V)
+    b = oracle.quantify(np.ascontiguousarray(widened[:, :V]), None, P)
+    for k in a:
+        np.testing.assert_array_equal(a[k], b[k])
+    poisoned = widened.copy()
+    poisoned[:, V:] = 1e30
+    d = oracle.quantify(poisoned, None, P, vocab=V)
+    for k in a:
+        np.testing.assert_array_equal(a[k], d[k])
+
+
+def test_masked_tokens_have_zero_probability_and_zero_width(oracle):
+    """A -inf logit is a masked token: e = 0, p^l = p_mid = p^u = 0; the other tokens are unchanged."""
+    rng = np.random.default_rng(15)
+    c = _rows(rng, 2, 40, 2.0)
+    keep = np.ones(40, bool); keep[[3, 17, 39]] = False
+    cm = c.copy(); cm[:, ~keep] = -np.inf
+    P = oracle.Params(confidence=0.9, normalize=False)
+    lo, mid, hi = oracle.dense_intervals(cm, P)
+    lo2, mid2, hi2 = oracle.dense_intervals(np.ascontiguousarray(c[:, keep]), P)
+    assert np.all(lo[:, ~keep] == 0) and np.all(mid[:, ~keep] == 0) and np.all(hi[:, ~keep] == 0)
+    np.testing.assert_allclose(lo[:, keep], lo2, rtol=1e-14)
+    np.testing.assert_allclose(hi[:, keep], hi2, rtol=1e-14)
+    q = oracle.quantify(cm, None, P)
+    d = hi - lo
+    np.testing.assert_allclose(q["sigma"], d.std(axis=1), rtol=1e-12)   # masked tokens still count in V
+
+
+# ---- verification --------------------------------------------------------------------------
+
+def _verify_grid(oracle, c_row, t_row, x, ua, ur, K=1):
+    n = len(ua)
+    c = np.repeat(c_row[None, :], n, 0).astype(np.float32)
+    t = np.repeat(t_row[None, :], n, 0).astype(np.float32)
+    return oracle.verify(c, t, np.full(n, x), np.asarray(ua, np.float32), np.asarray(ur, np.float32),
+                         oracle.Params(window=K))
+
+
+@pytest.mark.parametrize("V", [2, 3, 8])
+def test_speculative_sampling_law_by_enumeration(oracle, V):
+    """Brute force on a tiny vocabulary: integrating the accept test over u_accept and the residual
+    draw over u_resample, the emitted token is distributed exactly as the target q:
+      sum_x p_x [ min(1, q_x/p_x) 1[x=j] + (1 - min(1, q_x/p_x)) res_j / R ] = q_j,
+    and the set of u_resample mapped to token j is the interval [C_{j-1}/R, C_j/R)."""
+    rng = np.random.default_rng(100 + V)
+    G = 1 << 12
+    grid = (np.arange(G) + 0.5) / G
+    for trial in range(3):
+        c = (rng.standard_normal(V) * 1.5).astype(np.float32)
+        t = (c + rng.standard_normal(V)).astype(np.float32)
+        p = sps.softmax(c.astype(np.float64)); q = sps.softmax(t.astype(np.float64))
+        res = np.maximum(q - p, 0); R = res.sum()
+        out = np.zeros(V)
+        for x in range(V):
+            # measure of accepted u_accept
+            acc = _verify_grid(oracle, c, t, x, grid, np.zeros(G))["accept"].mean()
+            beta = min(1.0, q[x] / p[x])
+            assert abs(acc - beta) <= 1.0 / G
+            out[x] += p[x] * beta
+            if beta < 1.0:
+                # always rejected at u_accept -> 1; distribution of the residual draw
+                v = _verify_grid(oracle, c, t, x, np.full(G, 1 - 2.0 ** -24), grid)
+                assert not v["accept"].any()
+                freq = np.bincount(v["row_id"], minlength=V) / G
+                assert np.all(np.abs(freq - res / R) <= 2.0 / G)
+                out += p[x] * (1 - beta) * freq
+                # interval end points: just below / above each C_j / R
+                cdf = np.cumsum(res) / R
+                for j in range(V):
+                    if res[j] / R < 1e-3:
+                        continue
+                    lo_u = (cdf[j - 1] if j else 0.0) + 1e-5
+                    hi_u = cdf[j] - 1e-5
+                    vv = _verify_grid(oracle, c, t, x, [1 - 2.0 ** -24] * 2, [lo_u, hi_u])
+                    assert list(vv["row_id"]) == [j, j]
+        np.testing.assert_allclose(out, q, atol=3.0 / G)
+
+
+def test_accept_test_takes_target_over_draft(oracle):
+    """A token the target likes less than the draft is rejected with probability 1 - q_x/p_x, one it
+    likes more is always accepted (swapping the two distributions would invert this)."""
+    c = np.array([2.0, 0.0, 0.0, 0.0], np.float32)
+    t = np.array([0.0, 2.0, 0.0, 0.0], np.float32)
+    p = sps.softmax(c.astype(np.float64)); q = sps.softmax(t.astype(np.float64))
+    ua = np.array([0.0, 0.1, 0.5, 0.9, 0.999], np.float32)
+    v0 = _verify_grid(oracle, c, t, 0, ua, np.zeros(5))
+    assert list(v0["accept"]) == [int(u < q[0] / p[0]) for u in ua]
+    np.testing.assert_allclose(v0["log_ratio"], math.log(q[0] / p[0]), rtol=1e-12)
+    v1 = _verify_grid(oracle, c, t, 1, ua, np.zeros(5))
+    assert v1["accept"].all() and np.all(v1["row_id"] == -1)
+    # the only token with positive residual mass is token 1
+    assert np.all(v0["row_id"][v0["accept"] == 0] == 1)
+
+
+def test_identical_rows_always_accept(oracle):
+    rng = np.random.default_rng(16)
+    N, V, K = 37, 129, 8
+    c = _rows(rng, N, V, 3.0)
+    ua = rng.random(N).astype(np.float32)
+    ua[:3] = [0.0, 1 - 2.0 ** -24, 0.5]
+    v = oracle.verify(c, c.copy(), rng.integers(0, V, N), ua, rng.random(N).astype(np.float32),
+                      oracle.Params(window=K))
+    assert v["accept"].all() and np.all(v["row_id"] == -1)
+    W = (N + K - 1) // K
+    assert list(v["accept_len"]) == [K] * (W - 1) + [N - K * (W - 1)]
+    assert np.all(v["resampled_id"] == -1)
+
+
+def test_window_outputs_on_a_hand_built_pattern(oracle):
+    """accept_len = leading accepted rows of each window of K; resampled id = draw of the first
+    rejected row; a fully accepted window reports -1; the last window may be ragged."""
+    V, K = 4, 4
+    c_rej = np.array([9.0, 0, 0, 0], np.float32)      # drafted token 0, target hates it
+    t_rej = np.array([-9.0, 5.0, 0, 0], np.float32)   # residual mass almost all on token 1
+    c_acc = np.array([0.0, 1, 2, 3], np.float32)
+    pattern = [1, 1, 0, 1,   0, 0, 1, 1,   1, 1, 1, 1,   1, 0]    # 1 = accepted; N = 14, W = 4
+    N = len(pattern)
+    c = np.stack([c_acc if a else c_rej for a in pattern])
+    t = np.stack([c_acc if a else t_rej for a in pattern])
+    ids = np.zeros(N, np.int64)
+    ua = np.full(N, 0.5, np.float32)
+    ur = np.full(N, 0.5, np.float32)
+    ur[4] = 1 - 2.0 ** -24     # the tail of the residual: the last token with positive mass
+    v = oracle.verify(c, t, ids, ua, ur, oracle.Params(window=K))
+    assert list(v["accept"]) == pattern
+    assert list(v["accept_len"]) == [2, 0, 4, 1]
+    q = sps.softmax(t_rej.astype(np.float64)); p = sps.softmax(c_rej.astype(np.float64))
+    res = np.maximum(q - p, 0)
+    tail = int(np.nonzero(np.cumsum(res) > (1 - 2.0 ** -24) * res.sum())[0][0])
+    assert list(v["resampled_id"]) == [1, tail, -1, 1]
+    assert [int(i) for i in v["row_id"]] == [-1, -1, 1, -1, tail, 1, -1, -1, -1, -1, -1, -1, -1, 1]
+
+
+def test_residual_cdf_and_margin_diagnostics(oracle):
+    rng = np.random.default_rng(17)
+    V = 60
+    c = _rows(rng, 4, V, 2.0)
+    t = (c + rng.standard_normal(c.shape)).astype(np.float32)
+    P = oracle.Params(window=2)
+    p = sps.softmax(c.astype(np.float64), axis=1); q = sps.softmax(t.astype(np.float64), axis=1)
+    for row in range(4):
+        cdf, R = oracle.residual_cdf(c, t, row, P)
+        ref = np.cumsum(np.maximum(q[row] - p[row], 0))
+        np.testing.assert_allclose(cdf, ref, rtol=1e-11, atol=1e-16)
+        assert abs(R - ref[-1]) < 1e-14
+        # total residual mass equals the total-variation distance
+        assert abs(R - 0.5 * np.abs(p[row] - q[row]).sum()) < 1e-13
+    ids = p.argmax(1)      # over-drafted tokens are likely rejected at u -> 1
+    v = oracle.verify(c, t, ids, np.full(4, 1 - 2.0 ** -24, np.float32), np.full(4, 0.3, np.float32), P)
+    for row in range(4):
+        if not v["accept"][row]:
+            cdf, R = oracle.residual_cdf(c, t, row, P)
+            j = v["row_id"][row]
+            T = np.float64(np.float32(0.3)) * R
+            assert cdf[j] > T and (j == 0 or cdf[j - 1] <= T)
+            m = min(abs(cdf[j] - T), abs((cdf[j - 1] if j else 0.0) - T)) / R
+            assert abs(v["res_margin"][row] - m) < 1e-12
+
+
+def test_acceptance_rate_for_gaussian_target_noise(oracle):
+    """Statistical sanity (not exact): target = draft + N(0, sigma^2) on a large flat vocabulary gives
+    E[min(1, q/p)] = 1 - TV ~ 2 Phi(-sigma/2)."""
+    rng = np.random.default_rng(18)
+    N, V, sigma = 400, 4096, 0.5
+    c = _rows(rng, N, V, 1.0)
+    t = (c + sigma * rng.standard_normal(c.shape)).astype(np.float32)
+    p = sps.softmax(c.astype(np.float64), axis=1)
+    ids = np.array([rng.choice(V, p=p[n]) for n in range(N)])
+    v = oracle.verify(c, t, ids, rng.random(N).astype(np.float32), rng.random(N).astype(np.float32),
+                      oracle.Params(window=8))
+    expect = 2 * spst.norm.cdf(-sigma / 2)
+    assert abs(v["accept"].mean() - expect) < 4 * math.sqrt(expect * (1 - expect) / N) + 0.01
+
+
+def test_threads_do_not_change_results(oracle):
+    rng = np.random.default_rng(19)
+    c = _rows(rng, 33, 257, 2.0)
+    t = (c + 0.5 * rng.standard_normal(c.shape)).astype(np.float32)
+    ids = rng.integers(0, 257, 33)
+    ua, ur = rng.random(33).astype(np.float32), rng.random(33).astype(np.float32)
+    P = oracle.Params(window=4)
+    a = oracle.quantify(c, ids, P, threads=1); b = oracle.quantify(c, ids, P, threads=5)
+    for k in a:
+        np.testing.assert_array_equal(a[k], b[k])
+    a = oracle.verify(c, t, ids, ua, ur, P, threads=1); b = oracle.verify(c, t, ids, ua, ur, P, threads=5)
+    for k in a:
+        np.testing.assert_array_equal(a[k], b[k])
+
+
+def test_empty_batch(oracle):
+    c = np.zeros((0, 16), np.float32)
+    q = oracle.quantify(c, np.zeros(0, np.int32), oracle.Params())
+    assert all(v.shape == (0,) for v in q.values())
+    v = oracle.verify(c, c, np.zeros(0, np.int32), np.zeros(0, np.float32), np.zeros(0, np.float32),
+                      oracle.Params(window=4))
+    assert v["accept_len"].shape == (0,)
