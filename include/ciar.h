@@ -1,0 +1,172 @@
+/*
+ * ciar.h -- C ABI of the MI355X (gfx950) implementation of CIAR's per-position hot path.
+ *
+ * For every drafted image-token position (a "row") the library streams the V-wide centre
+ * ("draft") logit row, and for verification also the cloud ("target") logit row, once from
+ * HBM and computes
+ *
+ *   quantify : softmax statistics, the InterFuse probability interval [p^l, p^u], the widths'
+ *              Total Ambiguity Omega, Confidence Disparity Sigma and score U = Omega * Sigma,
+ *              and the "send to the cloud" flag U > tau
+ *   verify   : the speculative accept / reject test of each drafted token against the target
+ *              distribution, the residual resample of rejected tokens, and per window of K
+ *              drafted tokens the accepted prefix length and the replacement token
+ *
+ * C99; no C++ types and no exceptions cross this boundary.
+ *
+ * Conventions for every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller; `params` is a HOST pointer
+ *     and is read before the call returns.  The library allocates nothing, frees nothing and
+ *     never synchronises: kernels are enqueued on `hip_stream` (a hipStream_t, NULL = the
+ *     default stream) and outputs are valid once the caller has synchronised that stream.
+ *   - Logits: row-major [N, row_stride] with V <= row_stride, element type `dtype`
+ *     (float32, or bfloat16 widened exactly to float32 on load).  Base pointers and
+ *     row_stride * sizeof(element) must be multiples of 16 bytes, and the buffer must be
+ *     readable up to (N-1)*row_stride + roundup(V, 16 bytes / sizeof(element)) elements.
+ *     Values must be finite or -inf (-inf = masked token: probability 0, width 0, still
+ *     counted in V); every row needs at least one finite logit.  NaN / +inf is a violated
+ *     precondition and gives unspecified numbers (never a fault).
+ *   - 0 <= draft_ids[i] < V and uniforms in [0, 1) are preconditions (ids are clamped into
+ *     range on the device so a bad id cannot fault).
+ *   - Output pointers may be NULL to skip that output, where stated.
+ *   - Return value: a ciar_status.  On any error nothing has been launched and
+ *     ciar_last_error() describes the problem.  N == 0 is valid and launches nothing.
+ *   - Supported vocabulary: 1 <= V <= 32768 (float32) or 65536 (bfloat16).
+ */
+#ifndef CIAR_H
+#define CIAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ciar_dtype { CIAR_F32 = 0, CIAR_BF16 = 1 } ciar_dtype;
+
+typedef enum ciar_status {
+    CIAR_OK = 0,
+    CIAR_EINVAL = -1,        /* NULL / out-of-range argument                      */
+    CIAR_EALIGN = -2,        /* pointer or row stride not 16-byte aligned         */
+    CIAR_EWORKSPACE = -3,    /* workspace missing or too small                    */
+    CIAR_EUNSUPPORTED = -4,  /* vocabulary or dtype outside the supported range   */
+    CIAR_EHIP = -5           /* the HIP runtime reported an error at launch       */
+} ciar_status;
+
+/*
+ * Parameters of the pass.  Fill with ciar_params_default() and override.
+ *
+ * Radius.  The paper's logit radius r is the Softplus output of a trained head (Sec. 3.2.1,
+ * Inter-Head equation); this entry point takes one scalar radius for all tokens:
+ *   r = min(kappa, radius_max),
+ *   kappa = radius_scale               if radius_scale >= 0
+ *         = sqrt(2) * erfinv(confidence) otherwise (two-sided standard-normal quantile of the
+ *           "interval confidence" gamma in (0,1): 0.8 -> 1.2816, 0.9 -> 1.6449, 0.95 -> 1.9600).
+ * radius_max is the clamp the paper applies without naming a value (App. "Proof of Interval
+ * Validity", last paragraph).
+ */
+typedef struct ciar_params {
+    uint32_t struct_size;   /* sizeof(ciar_params); checked                                        */
+    int32_t  vocab;         /* V                                                                   */
+    int32_t  dtype;         /* ciar_dtype of the logit tensors                                     */
+    int32_t  window;        /* K >= 1: drafted tokens per cloud verification (Algorithm 1)         */
+    int64_t  row_stride;    /* elements between consecutive rows                                   */
+    float    confidence;    /* gamma, used when radius_scale < 0                                   */
+    float    radius_scale;  /* kappa override, < 0 = derive from confidence                        */
+    float    radius_max;    /* clamp on the radius, default 10                                     */
+    float    tau;           /* threshold on U, default 0.30 (Algorithm 1; Sec. 4 threshold study)  */
+    float    lower_cap;     /* 0.99 (normalisation equations of the validity appendix)             */
+    float    upper_cap;     /* 1.01                                                                */
+    int32_t  normalize;     /* 1 = apply the caps (the paper), 0 = raw InterFuse                   */
+    int32_t  reserved;      /* must be 0                                                           */
+} ciar_params;
+
+/* Writes the defaults (confidence 0.9, radius_scale -1, radius_max 10, tau 0.30, caps 0.99 / 1.01,
+ * normalize 1, window 8, dtype float32, vocab 0, row_stride 0).  `p` is a host pointer. */
+void ciar_params_default(ciar_params* p);
+
+/*
+ * Bytes of device workspace ciar_verify / ciar_quantify_verify need for N rows: room for the
+ * per-row accept bit and residual sample when the caller does not ask for those outputs.
+ * Always a multiple of 256; returns 0 for N <= 0.  The workspace must be 16-byte aligned.
+ * Its contents need no initialisation and are garbage afterwards.
+ */
+size_t ciar_workspace_bytes(int64_t N, const ciar_params* params);
+
+/*
+ * Uncertainty quantifier (Sec. 3.2.1 "Device-Side Uncertainty Quantification"; Eq.
+ * uncertainty_score; App. "Proof of Interval Validity"; threshold test of Algorithm 1).
+ *
+ *   draft_logits [N, row_stride]   in   centre logits c
+ *   draft_ids    [N] int32         in   token whose interval is reported; NULL = the arg-max token
+ *   p_lo, p_mid, p_hi [N] float    out  p^l_x, softmax(c)_x, p^u_x of that token (after the caps)
+ *   omega, sigma, score [N] float  out  Omega = sum of widths, Sigma = population std of widths, U
+ *   flags        [N] uint8         out  1 = U > tau (uncertain: send to the cloud), 0 = accept locally
+ * Any output may be NULL; at least one must be given.
+ */
+int ciar_quantify(const void* draft_logits, const int32_t* draft_ids, int64_t N,
+                  const ciar_params* params,
+                  float* p_lo, float* p_mid, float* p_hi,
+                  float* omega, float* sigma, float* score, uint8_t* flags,
+                  void* hip_stream);
+
+/*
+ * Cloud-side verification of drafted tokens (Algorithm 1, "Cloud verification" and the resample /
+ * advance steps that follow it).  The paper states the step as speculative decoding without
+ * writing the test; this is the standard rule: with p = softmax(draft row), q = softmax(target row)
+ * and x the drafted token, accept iff u_accept < min(1, q_x / p_x) (evaluated in the log domain);
+ * on rejection draw from (q - p)^+ / ||(q - p)^+||_1 by inverse CDF in token order with u_resample:
+ * the smallest j whose inclusive running sum exceeds u_resample * R.
+ *
+ *   draft_logits, target_logits [N, row_stride]  in
+ *   draft_ids  [N] int32, u_accept [N] float, u_resample [N] float   in
+ *   accept          [N] uint8   out  1 = accepted                              (may be NULL)
+ *   row_resample_id [N] int32   out  residual sample of a rejected row, -1 if accepted (may be NULL)
+ *   accept_len      [W] int32   out  leading accepted rows of window w = rows [wK, min((w+1)K, N)),
+ *                                    W = ceil(N / K)                            (may be NULL)
+ *   resampled_id    [W] int32   out  row_resample_id of the window's first rejected row, -1 if the
+ *                                    whole window was accepted                  (may be NULL)
+ *   workspace                   device scratch of ciar_workspace_bytes(N, params) bytes; may be NULL
+ *                               when accept and row_resample_id are both given or no window output
+ *                               is requested.
+ * At least one output must be given.
+ */
+int ciar_verify(const void* draft_logits, const void* target_logits, const int32_t* draft_ids,
+                const float* u_accept, const float* u_resample, int64_t N,
+                const ciar_params* params,
+                uint8_t* accept, int32_t* row_resample_id,
+                int32_t* accept_len, int32_t* resampled_id,
+                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Fused quantify + verify: both rows are read from HBM exactly once and nothing V-wide is written.
+ * Arguments and semantics are the union of ciar_quantify (with draft_ids required) and ciar_verify.
+ */
+int ciar_quantify_verify(const void* draft_logits, const void* target_logits,
+                         const int32_t* draft_ids, const float* u_accept, const float* u_resample,
+                         int64_t N, const ciar_params* params,
+                         float* p_lo, float* p_mid, float* p_hi,
+                         float* omega, float* sigma, float* score, uint8_t* flags,
+                         uint8_t* accept, int32_t* row_resample_id,
+                         int32_t* accept_len, int32_t* resampled_id,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Test / debugging export of the dense curves: p_lo, p_mid, p_hi as [N, V] float32 each, densely
+ * packed (row stride V), computed with the same per-token arithmetic as ciar_quantify.  Writes
+ * 3*N*V floats; not part of the hot path.  Any of the three may be NULL.
+ */
+int ciar_dense_intervals(const void* draft_logits, int64_t N, const ciar_params* params,
+                         float* p_lo, float* p_mid, float* p_hi, void* hip_stream);
+
+/* Message for the last non-OK status returned on the calling thread; never NULL. */
+const char* ciar_last_error(void);
+
+/* "major.minor.patch" of the library. */
+const char* ciar_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CIAR_H */

@@ -1,0 +1,10 @@
+"""MI355X-native CIAR quantify + verify hot path: HIP kernels behind a C ABI, with a thin binding.
+
+``binding`` marshals torch tensors into the C ABI declared in ``include/ciar.h``;
+``workloads`` generates the seeded synthetic inputs; ``build`` compiles ``libciar.so`` for gfx950.
+"""
+from .binding import (CiarError, Params, dense_intervals, last_error, lib, quantify, quantify_verify,
+                      verify, version, workspace_bytes)
+
+__all__ = ["CiarError", "Params", "dense_intervals", "last_error", "lib", "quantify",
+           "quantify_verify", "verify", "version", "workspace_bytes"]

@@ -1,0 +1,212 @@
+"""Thin ctypes binding of ``libciar.so``: argument marshalling only.
+
+Every step of the pass runs in the HIP kernels behind the C ABI (``include/ciar.h``); this module
+turns torch tensors into device pointers, allocates output tensors and checks the status code.
+There is no CPU fallback: if the library has not been built, importing a function raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libciar.so")
+
+CIAR_F32, CIAR_BF16 = 0, 1
+STATUS = {0: "CIAR_OK", -1: "CIAR_EINVAL", -2: "CIAR_EALIGN", -3: "CIAR_EWORKSPACE",
+          -4: "CIAR_EUNSUPPORTED", -5: "CIAR_EHIP"}
+
+
+class CiarParams(ctypes.Structure):
+    """Mirror of ``struct ciar_params``."""
+    _fields_ = [("struct_size", ctypes.c_uint32), ("vocab", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("window", ctypes.c_int32), ("row_stride", ctypes.c_int64),
+                ("confidence", ctypes.c_float), ("radius_scale", ctypes.c_float),
+                ("radius_max", ctypes.c_float), ("tau", ctypes.c_float),
+                ("lower_cap", ctypes.c_float), ("upper_cap", ctypes.c_float),
+                ("normalize", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class CiarError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library.  Raises if it has not been built (``python -m paper_2603_25463_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
+        pp = ctypes.POINTER(CiarParams)
+        L.ciar_params_default.restype = None
+        L.ciar_params_default.argtypes = [pp]
+        L.ciar_workspace_bytes.restype = sz
+        L.ciar_workspace_bytes.argtypes = [i64, pp]
+        L.ciar_quantify.restype = ctypes.c_int
+        L.ciar_quantify.argtypes = [vp, vp, i64, pp] + [vp] * 7 + [vp]
+        L.ciar_verify.restype = ctypes.c_int
+        L.ciar_verify.argtypes = [vp, vp, vp, vp, vp, i64, pp] + [vp] * 4 + [vp, sz, vp]
+        L.ciar_quantify_verify.restype = ctypes.c_int
+        L.ciar_quantify_verify.argtypes = [vp, vp, vp, vp, vp, i64, pp] + [vp] * 11 + [vp, sz, vp]
+        L.ciar_dense_intervals.restype = ctypes.c_int
+        L.ciar_dense_intervals.argtypes = [vp, i64, pp, vp, vp, vp, vp]
+        L.ciar_last_error.restype = ctypes.c_char_p
+        L.ciar_last_error.argtypes = []
+        L.ciar_version.restype = ctypes.c_char_p
+        L.ciar_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def version() -> str:
+    return lib().ciar_version().decode()
+
+
+def last_error() -> str:
+    return lib().ciar_last_error().decode()
+
+
+@dataclass
+class Params:
+    """Python-side parameters; ``radius_scale < 0`` derives the radius from ``confidence``."""
+    confidence: float = 0.9
+    radius_scale: float = -1.0
+    radius_max: float = 10.0
+    tau: float = 0.30
+    lower_cap: float = 0.99
+    upper_cap: float = 1.01
+    normalize: bool = True
+    window: int = 8
+
+    def to_c(self, logits: torch.Tensor, vocab: int | None = None) -> CiarParams:
+        p = CiarParams()
+        lib().ciar_params_default(ctypes.byref(p))
+        if logits.dtype == torch.float32:
+            p.dtype = CIAR_F32
+        elif logits.dtype == torch.bfloat16:
+            p.dtype = CIAR_BF16
+        else:
+            raise TypeError(f"logits must be float32 or bfloat16, got {logits.dtype}")
+        if logits.dim() != 2 or logits.stride(1) != 1:
+            raise ValueError("logits must be a 2-D tensor with unit stride along the vocabulary")
+        p.vocab = int(logits.shape[1] if vocab is None else vocab)
+        p.row_stride = int(logits.stride(0)) if logits.shape[0] > 1 else max(int(logits.stride(0)), p.vocab)
+        p.window = int(self.window)
+        p.confidence = float(self.confidence)
+        p.radius_scale = float(self.radius_scale)
+        p.radius_max = float(self.radius_max)
+        p.tau = float(self.tau)
+        p.lower_cap = float(self.lower_cap)
+        p.upper_cap = float(self.upper_cap)
+        p.normalize = int(bool(self.normalize))
+        return p
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise CiarError(rc, last_error())
+
+
+def _need_cuda(*ts):
+    for t in ts:
+        if t is not None and not t.is_cuda:
+            raise ValueError("all tensors must live on the GPU")
+
+
+def workspace_bytes(N: int, cparams: CiarParams) -> int:
+    return int(lib().ciar_workspace_bytes(int(N), ctypes.byref(cparams)))
+
+
+def quantify(draft: torch.Tensor, ids: torch.Tensor | None, params: Params, vocab: int | None = None,
+             stream=None, out: dict | None = None) -> dict:
+    """``ciar_quantify``.  Returns dict of [N] tensors: p_lo, p_mid, p_hi, omega, sigma, score (float32)
+    and flags (uint8).  ``out`` may carry preallocated tensors under the same names."""
+    _need_cuda(draft, ids)
+    N, dev = draft.shape[0], draft.device
+    cp = params.to_c(draft, vocab)
+    o = dict(out) if out else {}
+    for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score"):
+        o.setdefault(k, torch.empty(N, dtype=torch.float32, device=dev))
+    o.setdefault("flags", torch.empty(N, dtype=torch.uint8, device=dev))
+    _check(lib().ciar_quantify(_ptr(draft), _ptr(ids), N, ctypes.byref(cp),
+                               _ptr(o["p_lo"]), _ptr(o["p_mid"]), _ptr(o["p_hi"]), _ptr(o["omega"]),
+                               _ptr(o["sigma"]), _ptr(o["score"]), _ptr(o["flags"]), _stream(stream)))
+    return o
+
+
+def _verify_outputs(N: int, K: int, dev, out: dict | None) -> dict:
+    W = (N + K - 1) // K
+    o = dict(out) if out else {}
+    o.setdefault("accept", torch.empty(N, dtype=torch.uint8, device=dev))
+    o.setdefault("row_id", torch.empty(N, dtype=torch.int32, device=dev))
+    o.setdefault("accept_len", torch.empty(W, dtype=torch.int32, device=dev))
+    o.setdefault("resampled_id", torch.empty(W, dtype=torch.int32, device=dev))
+    return o
+
+
+def verify(draft, target, ids, u_accept, u_resample, params: Params, vocab: int | None = None,
+           stream=None, out: dict | None = None, workspace: torch.Tensor | None = None) -> dict:
+    """``ciar_verify``.  Returns accept uint8 [N], row_id int32 [N], accept_len / resampled_id int32 [W]."""
+    _need_cuda(draft, target, ids, u_accept, u_resample)
+    N, dev = draft.shape[0], draft.device
+    cp = params.to_c(draft, vocab)
+    if target.dtype != draft.dtype or target.shape != draft.shape or target.stride() != draft.stride():
+        raise ValueError("target must match draft in dtype, shape and strides")
+    o = _verify_outputs(N, cp.window, dev, out)
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().ciar_verify(_ptr(draft), _ptr(target), _ptr(ids), _ptr(u_accept), _ptr(u_resample), N,
+                             ctypes.byref(cp), _ptr(o["accept"]), _ptr(o["row_id"]), _ptr(o["accept_len"]),
+                             _ptr(o["resampled_id"]), _ptr(workspace), wsb, _stream(stream)))
+    return o
+
+
+def quantify_verify(draft, target, ids, u_accept, u_resample, params: Params, vocab: int | None = None,
+                    stream=None, out: dict | None = None, workspace: torch.Tensor | None = None) -> dict:
+    """``ciar_quantify_verify``: the fused pass; union of the outputs of quantify and verify."""
+    _need_cuda(draft, target, ids, u_accept, u_resample)
+    N, dev = draft.shape[0], draft.device
+    cp = params.to_c(draft, vocab)
+    if target.dtype != draft.dtype or target.shape != draft.shape or target.stride() != draft.stride():
+        raise ValueError("target must match draft in dtype, shape and strides")
+    o = _verify_outputs(N, cp.window, dev, out)
+    for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score"):
+        o.setdefault(k, torch.empty(N, dtype=torch.float32, device=dev))
+    o.setdefault("flags", torch.empty(N, dtype=torch.uint8, device=dev))
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().ciar_quantify_verify(
+        _ptr(draft), _ptr(target), _ptr(ids), _ptr(u_accept), _ptr(u_resample), N, ctypes.byref(cp),
+        _ptr(o["p_lo"]), _ptr(o["p_mid"]), _ptr(o["p_hi"]), _ptr(o["omega"]), _ptr(o["sigma"]),
+        _ptr(o["score"]), _ptr(o["flags"]), _ptr(o["accept"]), _ptr(o["row_id"]), _ptr(o["accept_len"]),
+        _ptr(o["resampled_id"]), _ptr(workspace), wsb, _stream(stream)))
+    return o
+
+
+def dense_intervals(draft: torch.Tensor, params: Params, vocab: int | None = None, stream=None):
+    """``ciar_dense_intervals`` (test export): (p_lo, p_mid, p_hi), float32 [N, V]."""
+    _need_cuda(draft)
+    N, dev = draft.shape[0], draft.device
+    cp = params.to_c(draft, vocab)
+    lo, mid, hi = (torch.empty((N, cp.vocab), dtype=torch.float32, device=dev) for _ in range(3))
+    _check(lib().ciar_dense_intervals(_ptr(draft), N, ctypes.byref(cp), _ptr(lo), _ptr(mid), _ptr(hi),
+                                      _stream(stream)))
+    return lo, mid, hi

@@ -1,0 +1,277 @@
+// C ABI of the library (include/ciar.h): argument validation, parameter resolution, launches.
+// No allocation, no synchronisation, no state besides the thread-local error text.
+#include "../../include/ciar.h"
+#include "ciar_internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+namespace {
+
+thread_local char g_error[512] = "";
+
+int fail(ciar_status code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof g_error, fmt, ap);
+    va_end(ap);
+    return (int)code;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// z with P(|Z| <= z) = gamma for a standard normal Z, i.e. sqrt(2) * erfinv(gamma):
+// Newton's method on erf(z / sqrt 2) - gamma from a closed-form starting point.
+double two_sided_normal_quantile(double gamma)
+{
+    const double kPi = 3.14159265358979323846;
+    // Winitzki's approximation of erfinv as the start
+    const double a = 0.147, l = std::log(1.0 - gamma * gamma);
+    const double t = 2.0 / (kPi * a) + 0.5 * l;
+    double y = std::sqrt(std::sqrt(t * t - l / a) - t);          // ~ erfinv(gamma)
+    for (int it = 0; it < 8; ++it) {
+        const double f = std::erf(y) - gamma;
+        const double d = 2.0 / std::sqrt(kPi) * std::exp(-y * y);
+        y -= f / d;
+    }
+    return std::sqrt(2.0) * y;
+}
+
+struct Resolved {
+    double a, b;       // e^{+r}, e^{-r}
+    int elt;           // bytes per logit
+};
+
+// Checks everything in `p` that does not depend on the tensors.  Returns CIAR_OK or fails.
+int check_params(const ciar_params* p, Resolved* out)
+{
+    if (!p) return fail(CIAR_EINVAL, "params is NULL");
+    if (p->struct_size != sizeof(ciar_params))
+        return fail(CIAR_EINVAL, "params->struct_size is %u, expected %zu", p->struct_size, sizeof(ciar_params));
+    if (p->reserved != 0) return fail(CIAR_EINVAL, "params->reserved must be 0");
+    if (p->dtype != CIAR_F32 && p->dtype != CIAR_BF16)
+        return fail(CIAR_EUNSUPPORTED, "params->dtype %d is neither CIAR_F32 nor CIAR_BF16", p->dtype);
+    if (p->vocab < 1) return fail(CIAR_EINVAL, "params->vocab must be >= 1 (got %d)", p->vocab);
+    if (p->vocab > ciar::max_vocab(p->dtype))
+        return fail(CIAR_EUNSUPPORTED, "params->vocab %d exceeds the supported maximum %d for this dtype",
+                    p->vocab, ciar::max_vocab(p->dtype));
+    const int elt = p->dtype == CIAR_F32 ? 4 : 2;
+    if (p->row_stride < p->vocab)
+        return fail(CIAR_EINVAL, "params->row_stride %lld is smaller than vocab %d", (long long)p->row_stride,
+                    p->vocab);
+    if ((p->row_stride * elt) % 16 != 0)
+        return fail(CIAR_EALIGN, "row_stride * element size = %lld bytes is not a multiple of 16",
+                    (long long)(p->row_stride * elt));
+    if (p->window < 1) return fail(CIAR_EINVAL, "params->window must be >= 1 (got %d)", p->window);
+    if (!(p->radius_max >= 0.0f) || !(p->radius_max <= 80.0f))
+        return fail(CIAR_EINVAL, "params->radius_max must be in [0, 80]");
+    if (!std::isfinite(p->tau)) return fail(CIAR_EINVAL, "params->tau must be finite");
+    if (!(p->lower_cap > 0.0f) || !(p->lower_cap <= 1.0f) || !(p->upper_cap >= 1.0f) ||
+        !std::isfinite(p->upper_cap))
+        return fail(CIAR_EINVAL, "caps must satisfy 0 < lower_cap <= 1 <= upper_cap");
+    double kappa;
+    if (p->radius_scale >= 0.0f) {
+        kappa = (double)p->radius_scale;
+    } else {
+        if (!(p->confidence > 0.0f) || !(p->confidence < 1.0f))
+            return fail(CIAR_EINVAL, "params->confidence must be in (0, 1) when radius_scale < 0");
+        kappa = two_sided_normal_quantile((double)p->confidence);
+    }
+    if (!std::isfinite(kappa)) return fail(CIAR_EINVAL, "params->radius_scale is not finite");
+    const double r = kappa < (double)p->radius_max ? kappa : (double)p->radius_max;
+    out->a = std::exp(r);
+    out->b = std::exp(-r);
+    out->elt = elt;
+    return CIAR_OK;
+}
+
+int check_rows(const void* logits, const char* name)
+{
+    if (!logits) return fail(CIAR_EINVAL, "%s is NULL", name);
+    if (!aligned16(logits)) return fail(CIAR_EALIGN, "%s is not 16-byte aligned", name);
+    return CIAR_OK;
+}
+
+size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
+
+ciar::RowArgs base_args(const ciar_params* p, const Resolved& r, int64_t N)
+{
+    ciar::RowArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.N = N;
+    a.stride = p->row_stride;
+    a.V = p->vocab;
+    a.normalize = p->normalize ? 1 : 0;
+    a.a = r.a;
+    a.b = r.b;
+    a.tau = (double)p->tau;
+    a.cap_lo = (double)p->lower_cap;
+    a.cap_hi = (double)p->upper_cap;
+    return a;
+}
+
+int hip_fail(hipError_t e, const char* what)
+{
+    return fail(CIAR_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// Shared tail of ciar_verify and ciar_quantify_verify.
+int run_verify(ciar::Mode mode, ciar::RowArgs& a, const ciar_params* p, uint8_t* accept, int32_t* row_id,
+               int32_t* accept_len, int32_t* resampled_id, void* workspace, size_t workspace_bytes,
+               hipStream_t stream)
+{
+    const int64_t N = a.N;
+    const bool windows = accept_len || resampled_id;
+    uint8_t* acc = accept;
+    int32_t* rid = row_id;
+    if (windows && (!acc || (!rid && resampled_id))) {
+        const size_t need = ciar_workspace_bytes(N, p);
+        if (!workspace) return fail(CIAR_EWORKSPACE, "workspace is NULL but %zu bytes are needed", need);
+        if (!aligned16(workspace)) return fail(CIAR_EALIGN, "workspace is not 16-byte aligned");
+        if (workspace_bytes < need)
+            return fail(CIAR_EWORKSPACE, "workspace has %zu bytes, %zu are needed", workspace_bytes, need);
+        char* w = static_cast<char*>(workspace);
+        if (!rid) rid = reinterpret_cast<int32_t*>(w);
+        if (!acc) acc = reinterpret_cast<uint8_t*>(w + round_up((size_t)N * 4, 16));
+    }
+    a.accept = acc;
+    a.row_id = rid;
+    if (N == 0) return CIAR_OK;
+    hipError_t e = ciar::launch_rows(mode, p->dtype, a, stream);
+    if (e != hipSuccess) return hip_fail(e, "row kernel launch");
+    if (windows) {
+        e = ciar::launch_windows(acc, rid, N, p->window, accept_len, resampled_id, stream);
+        if (e != hipSuccess) return hip_fail(e, "window kernel launch");
+    }
+    return CIAR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+void ciar_params_default(ciar_params* p)
+{
+    if (!p) return;
+    std::memset(p, 0, sizeof *p);
+    p->struct_size = (uint32_t)sizeof(ciar_params);
+    p->dtype = CIAR_F32;
+    p->window = 8;
+    p->confidence = 0.9f;
+    p->radius_scale = -1.0f;
+    p->radius_max = 10.0f;
+    p->tau = 0.30f;
+    p->lower_cap = 0.99f;
+    p->upper_cap = 1.01f;
+    p->normalize = 1;
+}
+
+size_t ciar_workspace_bytes(int64_t N, const ciar_params* /*params*/)
+{
+    if (N <= 0) return 0;
+    return round_up(round_up((size_t)N * 4, 16) + (size_t)N, 256);
+}
+
+int ciar_quantify(const void* draft_logits, const int32_t* draft_ids, int64_t N, const ciar_params* params,
+                  float* p_lo, float* p_mid, float* p_hi, float* omega, float* sigma, float* score,
+                  uint8_t* flags, void* hip_stream)
+{
+    Resolved r;
+    if (int rc = check_params(params, &r)) return rc;
+    if (N < 0) return fail(CIAR_EINVAL, "N is negative");
+    if (int rc = check_rows(draft_logits, "draft_logits")) return rc;
+    if (!p_lo && !p_mid && !p_hi && !omega && !sigma && !score && !flags)
+        return fail(CIAR_EINVAL, "every output pointer is NULL");
+    if (N > 0x7fffffffLL) return fail(CIAR_EUNSUPPORTED, "N exceeds 2^31 - 1 rows per call");
+    ciar::RowArgs a = base_args(params, r, N);
+    a.draft = draft_logits;
+    a.ids = draft_ids;
+    a.p_lo = p_lo; a.p_mid = p_mid; a.p_hi = p_hi;
+    a.omega = omega; a.sigma = sigma; a.score = score; a.flags = flags;
+    if (N == 0) return CIAR_OK;
+    hipError_t e = ciar::launch_rows(ciar::Mode::Quantify, params->dtype, a, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail(e, "row kernel launch");
+    return CIAR_OK;
+}
+
+int ciar_verify(const void* draft_logits, const void* target_logits, const int32_t* draft_ids,
+                const float* u_accept, const float* u_resample, int64_t N, const ciar_params* params,
+                uint8_t* accept, int32_t* row_resample_id, int32_t* accept_len, int32_t* resampled_id,
+                void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    Resolved r;
+    if (int rc = check_params(params, &r)) return rc;
+    if (N < 0) return fail(CIAR_EINVAL, "N is negative");
+    if (int rc = check_rows(draft_logits, "draft_logits")) return rc;
+    if (int rc = check_rows(target_logits, "target_logits")) return rc;
+    if (!draft_ids) return fail(CIAR_EINVAL, "draft_ids is NULL");
+    if (!u_accept) return fail(CIAR_EINVAL, "u_accept is NULL");
+    if (!u_resample) return fail(CIAR_EINVAL, "u_resample is NULL");
+    if (!accept && !row_resample_id && !accept_len && !resampled_id)
+        return fail(CIAR_EINVAL, "every output pointer is NULL");
+    if (N > 0x7fffffffLL) return fail(CIAR_EUNSUPPORTED, "N exceeds 2^31 - 1 rows per call");
+    ciar::RowArgs a = base_args(params, r, N);
+    a.draft = draft_logits;
+    a.target = target_logits;
+    a.ids = draft_ids;
+    a.u_accept = u_accept;
+    a.u_resample = u_resample;
+    return run_verify(ciar::Mode::Verify, a, params, accept, row_resample_id, accept_len, resampled_id,
+                      workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+int ciar_quantify_verify(const void* draft_logits, const void* target_logits, const int32_t* draft_ids,
+                         const float* u_accept, const float* u_resample, int64_t N, const ciar_params* params,
+                         float* p_lo, float* p_mid, float* p_hi, float* omega, float* sigma, float* score,
+                         uint8_t* flags, uint8_t* accept, int32_t* row_resample_id, int32_t* accept_len,
+                         int32_t* resampled_id, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    Resolved r;
+    if (int rc = check_params(params, &r)) return rc;
+    if (N < 0) return fail(CIAR_EINVAL, "N is negative");
+    if (int rc = check_rows(draft_logits, "draft_logits")) return rc;
+    if (int rc = check_rows(target_logits, "target_logits")) return rc;
+    if (!draft_ids) return fail(CIAR_EINVAL, "draft_ids is NULL");
+    if (!u_accept) return fail(CIAR_EINVAL, "u_accept is NULL");
+    if (!u_resample) return fail(CIAR_EINVAL, "u_resample is NULL");
+    if (!p_lo && !p_mid && !p_hi && !omega && !sigma && !score && !flags && !accept && !row_resample_id &&
+        !accept_len && !resampled_id)
+        return fail(CIAR_EINVAL, "every output pointer is NULL");
+    if (N > 0x7fffffffLL) return fail(CIAR_EUNSUPPORTED, "N exceeds 2^31 - 1 rows per call");
+    ciar::RowArgs a = base_args(params, r, N);
+    a.draft = draft_logits;
+    a.target = target_logits;
+    a.ids = draft_ids;
+    a.u_accept = u_accept;
+    a.u_resample = u_resample;
+    a.p_lo = p_lo; a.p_mid = p_mid; a.p_hi = p_hi;
+    a.omega = omega; a.sigma = sigma; a.score = score; a.flags = flags;
+    return run_verify(ciar::Mode::Fused, a, params, accept, row_resample_id, accept_len, resampled_id,
+                      workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+int ciar_dense_intervals(const void* draft_logits, int64_t N, const ciar_params* params, float* p_lo,
+                         float* p_mid, float* p_hi, void* hip_stream)
+{
+    Resolved r;
+    if (int rc = check_params(params, &r)) return rc;
+    if (N < 0) return fail(CIAR_EINVAL, "N is negative");
+    if (int rc = check_rows(draft_logits, "draft_logits")) return rc;
+    if (!p_lo && !p_mid && !p_hi) return fail(CIAR_EINVAL, "every output pointer is NULL");
+    if (N > 0x7fffffffLL) return fail(CIAR_EUNSUPPORTED, "N exceeds 2^31 - 1 rows per call");
+    ciar::RowArgs a = base_args(params, r, N);
+    a.draft = draft_logits;
+    if (N == 0) return CIAR_OK;
+    hipError_t e = ciar::launch_dense(params->dtype, a, p_lo, p_mid, p_hi, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail(e, "dense kernel launch");
+    return CIAR_OK;
+}
+
+const char* ciar_last_error(void) { return g_error; }
+
+const char* ciar_version(void) { return "0.1.0"; }
+
+}  // extern "C"

@@ -1,0 +1,49 @@
+// Internal interface between the C ABI (ciar_api.cpp) and the gfx950 kernels (ciar_kernels.hip).
+// Not installed; the public contract is include/ciar.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ciar {
+
+// Everything a row kernel needs, passed by value.  All pointers are device pointers.
+struct RowArgs {
+    const void*    draft;       // [N, stride] centre logits
+    const void*    target;      // [N, stride] verifier logits (verify only)
+    const int32_t* ids;         // [N] drafted token (may be null for quantify: arg-max token)
+    const float*   u_accept;    // [N]
+    const float*   u_resample;  // [N]
+    float*   p_lo;  float* p_mid;  float* p_hi;     // [N] or null
+    float*   omega; float* sigma;  float* score;    // [N] or null
+    uint8_t* flags;                                  // [N] or null
+    uint8_t* accept;                                 // [N] or null
+    int32_t* row_id;                                 // [N] or null
+    int64_t  N;
+    int64_t  stride;            // elements between rows
+    int32_t  V;
+    int32_t  normalize;
+    double   a;                 // e^{+r}
+    double   b;                 // e^{-r}
+    double   tau;
+    double   cap_lo;            // 0.99
+    double   cap_hi;            // 1.01
+};
+
+enum class Mode { Quantify, Verify, Fused };
+
+// Largest vocabulary the register-resident row kernels cover for an element size.
+int max_vocab(int dtype);
+
+// Enqueue the per-row kernel.  Returns hipSuccess or the launch error.
+hipError_t launch_rows(Mode mode, int dtype, const RowArgs& args, hipStream_t stream);
+
+// accept_len / resampled_id per window of K rows from the per-row results.
+hipError_t launch_windows(const uint8_t* accept, const int32_t* row_id, int64_t N, int32_t K,
+                          int32_t* accept_len, int32_t* resampled_id, hipStream_t stream);
+
+// Dense [N, V] export of p_lo, p_mid, p_hi (any may be null).
+hipError_t launch_dense(int dtype, const RowArgs& args, float* p_lo, float* p_mid, float* p_hi,
+                        hipStream_t stream);
+
+}  // namespace ciar

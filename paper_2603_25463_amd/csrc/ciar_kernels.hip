@@ -1,0 +1,681 @@
+// gfx950 kernels of the CIAR quantify + verify pass.
+//
+// One workgroup owns one row (one drafted token position).  The centre row c and the verifier
+// row t are fetched once with 16-byte loads, interleaved over the workgroup so that every load
+// instruction of a wave covers 1 KiB of consecutive memory, and stay in registers for the whole
+// life of the workgroup: the InterFuse bounds need the partition sum S of the complete row
+// before the first bound can be formed (App. "Proof of Interval Validity": S appears in every
+// denominator), so the row has to be resident between the statistics pass and the interval pass.
+// Nothing V-wide is ever written back.
+//
+// Per row:
+//   A  max of c and of t                                   (max-trick)
+//   B  e_i = exp(c_i - max c) kept in registers, S = sum e_i;  Z = sum exp(t_i - max t)
+//   C  InterFuse for a scalar radius r, a = e^r, b = e^-r, x_i = e_i / S:
+//        p^u_i = a x_i / (1 + (a-1) x_i),   p^l_i = b x_i / (1 - (1-b) x_i)
+//      with one reciprocal of the product of the two denominators, accumulated as the lower
+//      bound p^l_i and the raw width w_i = p^u_i - p^l_i = (a-b) x_i (1-x_i) / (du_i dl_i).
+//      Five sums per row (sum p^l, sum w and the three second moments, all taken about the
+//      values of the uniform row so that nearly flat rows do not cancel) give, after the
+//      0.99 / 1.01 caps alpha_l, alpha_u are known,
+//        delta_i = alpha_u w_i + (alpha_u - alpha_l) p^l_i,
+//        Omega   = sum delta_i,   Sigma^2 = (sum (delta_i - mean)^2) / V,   U = Omega * Sigma
+//      without a second sweep over the row.                 (Eq. uncertainty_score)
+//   D  flag = U > tau; interval of the drafted token; accept test in the log domain (fp64,
+//      one lane):  ln u < min(0, ln q_x - ln p_x)
+//   E  rejected rows only (workgroup-uniform branch): res_i = max(0, q_i - p_i), inverse-CDF
+//      draw in token order from a workgroup-wide prefix sum.
+//
+// Sums over the row are accumulated per lane in fp32 and combined across lanes and waves in
+// fp64 in a fixed order, so results are deterministic and the per-row scalars carry ~1e-8
+// relative error.
+#include "ciar_internal.h"
+
+#include <limits.h>
+#include <math.h>
+
+namespace ciar {
+namespace {
+
+// log2(e) split so that the low part is positive: (-inf) * hi + ((-inf) * lo - m) stays -inf.
+constexpr float  kLog2eHi = 1.44269490242004394531f;   // largest float below log2(e)
+constexpr float  kLog2eLo = 1.384689195e-7f;           // log2(e) - kLog2eHi
+constexpr double kLog2e   = 1.4426950408889634;
+
+__device__ __forceinline__ float bits_f(uint32_t u) { return __uint_as_float(u); }
+
+// 16 bytes as loaded: a native vector type, so it can be read through an address-space pointer.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// exp(x - m) for x <= m as 2^(x log2e - m log2e); neg_m2 = -(m log2e) rounded once per row.
+__device__ __forceinline__ float exp_shifted(float x, float neg_m2)
+{
+    return __builtin_amdgcn_exp2f(fmaf(x, kLog2eHi, fmaf(x, kLog2eLo, neg_m2)));
+}
+
+template <typename T> struct Elt;
+template <> struct Elt<float> {
+    static constexpr int kPerVec = 4;
+    static constexpr uint32_t kNegInfWord = 0xff800000u;
+    __device__ static __forceinline__ void unpack(const u32x4& r, float* o)
+    {
+        o[0] = bits_f(r.x); o[1] = bits_f(r.y); o[2] = bits_f(r.z); o[3] = bits_f(r.w);
+    }
+    // Replace elements with index >= V of a vector that starts at element `base` by -inf.
+    __device__ static __forceinline__ void mask_tail(u32x4& r, int base, int V)
+    {
+        if (base + 0 >= V) r.x = kNegInfWord;
+        if (base + 1 >= V) r.y = kNegInfWord;
+        if (base + 2 >= V) r.z = kNegInfWord;
+        if (base + 3 >= V) r.w = kNegInfWord;
+    }
+};
+struct bf16_t { uint16_t bits; };
+template <> struct Elt<bf16_t> {
+    static constexpr int kPerVec = 8;
+    static constexpr uint32_t kNegInfWord = 0xff80ff80u;
+    __device__ static __forceinline__ void unpack(const u32x4& r, float* o)
+    {
+        o[0] = bits_f(r.x << 16); o[1] = bits_f(r.x & 0xffff0000u);
+        o[2] = bits_f(r.y << 16); o[3] = bits_f(r.y & 0xffff0000u);
+        o[4] = bits_f(r.z << 16); o[5] = bits_f(r.z & 0xffff0000u);
+        o[6] = bits_f(r.w << 16); o[7] = bits_f(r.w & 0xffff0000u);
+    }
+    __device__ static __forceinline__ uint32_t mask_word(uint32_t w, int base, int V)
+    {
+        if (base >= V) return kNegInfWord;
+        if (base + 1 >= V) return (w & 0x0000ffffu) | 0xff800000u;
+        return w;
+    }
+    __device__ static __forceinline__ void mask_tail(u32x4& r, int base, int V)
+    {
+        r.x = mask_word(r.x, base + 0, V); r.y = mask_word(r.y, base + 2, V);
+        r.z = mask_word(r.z, base + 4, V); r.w = mask_word(r.w, base + 6, V);
+    }
+};
+
+// ---- wave and workgroup reductions (fixed order: deterministic) ----------------------------
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ int wave_min_i(int v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ int wave_max_i(int v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o));
+    return v;
+}
+
+// All threads end up with the workgroup-wide sums of v[0..NV).  smem: NW*NV doubles.
+template <int NW, int NV>
+__device__ __forceinline__ void block_sum(double (&v)[NV], double* smem, int lane, int wave)
+{
+#pragma unroll
+    for (int i = 0; i < NV; ++i) v[i] = wave_sum(v[i]);
+    __syncthreads();
+    if (lane == 0) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) smem[wave * NV + i] = v[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        double s = 0.0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) s += smem[w * NV + i];
+        v[i] = s;
+    }
+}
+
+template <int NW>
+__device__ __forceinline__ void block_max2(float& m0, float& m1, double* smem, int lane, int wave)
+{
+    m0 = wave_max(m0);
+    m1 = wave_max(m1);
+    float* f = reinterpret_cast<float*>(smem);
+    __syncthreads();
+    if (lane == 0) { f[wave * 2] = m0; f[wave * 2 + 1] = m1; }
+    __syncthreads();
+    float r0 = f[0], r1 = f[1];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) { r0 = fmaxf(r0, f[w * 2]); r1 = fmaxf(r1, f[w * 2 + 1]); }
+    m0 = r0; m1 = r1;
+}
+
+// ---- per-token InterFuse arithmetic, shared by the row kernel and the dense export ----------
+
+// Constants of one row for a scalar radius.  Units: e_i = exp(c_i - max c), S = sum e_i.
+struct FuseRow {
+    float cu;            // (a-1)/S:  du = 1 + (a-1) x = 1 + cu e
+    float nih, nil;      // -1/S split in two floats:  1 - x = 1 + nih e + nil e  (exact to ~1e-15)
+    float b, omb;        // b and 1-b:  dl = 1 - (1-b) x = b + (1-b)(1-x), free of cancellation as x -> 1
+    float kl, kw;        // the values gl, gw take on the uniform row (e = S/V): centring constants
+};
+
+__device__ __forceinline__ FuseRow fuse_row(double S, double a, double b, int V)
+{
+    FuseRow r;
+    const double invS = 1.0 / S;
+    r.cu = (float)((a - 1.0) * invS);
+    r.nih = (float)(-invS);
+    r.nil = (float)(-invS - (double)r.nih);
+    r.b = (float)b;
+    r.omb = (float)(1.0 - b);
+    const double xu = 1.0 / (double)V, eu = S * xu;
+    const double du = 1.0 + (a - 1.0) * xu, dl = 1.0 + (b - 1.0) * xu;
+    r.kl = (float)(eu / dl);
+    r.kw = (float)(eu * (1.0 - xu) / (du * dl));
+    return r;
+}
+
+// gl = e du / (du dl) and gw = e (1-x) / (du dl):  p^l = (b/S) gl,  w = p^u - p^l = ((a-b)/S) gw.
+__device__ __forceinline__ void fuse_token(float e, const FuseRow& r, float& gl, float& gw)
+{
+    const float om = fmaf(e, r.nil, fmaf(e, r.nih, 1.0f));        // 1 - x
+    const float du = fmaf(e, r.cu, 1.0f);
+    const float dl = fmaf(om, r.omb, r.b);
+    const float g = e * __builtin_amdgcn_rcpf(du * dl);
+    gl = g * du;
+    gw = g * om;
+}
+
+// Per-row scalars of the quantifier from the five centred sums (fp64, one lane).
+struct RowScore { double alpha_l, alpha_u, omega, sigma, score; };
+
+__device__ __forceinline__ RowScore finish_score(const double (&s)[5], const FuseRow& fr, double S,
+                                                 const RowArgs& A)
+{
+    // s = { sum(gl-kl), sum(gw-kw), sum(gl-kl)^2, sum(gw-kw)^2, sum(gl-kl)(gw-kw) } over the V tokens
+    const double V = (double)A.V;
+    const double Bc = A.b / S, Wc = (A.a - A.b) / S;
+    const double Gl = s[0] + V * (double)fr.kl, Gw = s[1] + V * (double)fr.kw;
+    const double Sl = Bc * Gl, Su = Sl + Wc * Gw;
+    RowScore o;
+    o.alpha_l = 1.0; o.alpha_u = 1.0;
+    if (A.normalize) {
+        o.alpha_l = fmin(1.0, A.cap_lo / Sl);
+        o.alpha_u = fmax(1.0, A.cap_hi / Su);
+    }
+    // delta_i = alpha_u w_i + (alpha_u - alpha_l) p^l_i = cw gw_i + cl gl_i
+    const double cw = o.alpha_u * Wc, cl = (o.alpha_u - o.alpha_l) * Bc;
+    o.omega = cw * Gw + cl * Gl;
+    const double L = cw * s[1] + cl * s[0];
+    const double Q = cw * cw * s[3] + 2.0 * cw * cl * s[4] + cl * cl * s[2];
+    const double var = fmax(0.0, Q - L * L / V) / V;
+    o.sigma = sqrt(var);
+    o.score = o.omega * o.sigma;
+    return o;
+}
+
+// ---- the row kernel ---------------------------------------------------------------------------
+
+// Waves per SIMD the register allocation aims for: the rows held in registers (EPT floats for c,
+// EPT more for t in full precision, half that for packed bf16) plus ~40 working registers.
+template <typename T, int THREADS, int NVEC, bool DO_V>
+constexpr int target_waves()
+{
+    constexpr int ept = NVEC * Elt<T>::kPerVec;
+    constexpr int regs = ept + (DO_V ? ept * (int)sizeof(T) / 4 : 0) + 40;
+    constexpr int fit = 512 / regs;
+    constexpr int lo = THREADS / 256;                 // waves per SIMD one workgroup needs
+    return fit < lo ? lo : (fit > 4 ? 4 : fit);
+}
+
+// Pass C for one lane: the five centred InterFuse sums over the lane's tokens.
+// MASKED = the row does not fill the tile, so tokens with index >= V must not be counted.
+template <int THREADS, int NVEC, int EPV, bool MASKED>
+__device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const FuseRow& fr, int tid, int V,
+                                          double (&q5)[5])
+{
+    float a0[2] = {0.f, 0.f}, a1[2] = {0.f, 0.f}, a2[2] = {0.f, 0.f}, a3[2] = {0.f, 0.f}, a4[2] = {0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < NVEC; ++j) {
+        const int base = (j * THREADS + tid) * EPV;
+        if (MASKED && j * THREADS * EPV >= V) break;               // uniform: the chunk holds no token
+#pragma unroll
+        for (int k = 0; k < EPV; ++k) {
+            float gl, gw;
+            fuse_token(e[j * EPV + k], fr, gl, gw);
+            gl -= fr.kl;
+            gw -= fr.kw;
+            if (MASKED && base + k >= V) { gl = 0.f; gw = 0.f; }   // padding is not a token
+            a0[k & 1] += gl;
+            a1[k & 1] += gw;
+            a2[k & 1] = fmaf(gl, gl, a2[k & 1]);
+            a3[k & 1] = fmaf(gw, gw, a3[k & 1]);
+            a4[k & 1] = fmaf(gl, gw, a4[k & 1]);
+        }
+        __builtin_amdgcn_sched_barrier(0);                         // one vector at a time: bounded working set
+    }
+    q5[0] = (double)a0[0] + (double)a0[1];
+    q5[1] = (double)a1[0] + (double)a1[1];
+    q5[2] = (double)a2[0] + (double)a2[1];
+    q5[3] = (double)a3[0] + (double)a3[1];
+    q5[4] = (double)a4[0] + (double)a4[1];
+}
+
+template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V>
+__global__ __launch_bounds__(THREADS)
+__attribute__((amdgpu_waves_per_eu(target_waves<T, THREADS, NVEC, DO_V>())))
+void row_kernel(const RowArgs A)
+{
+    using E = Elt<T>;
+    constexpr int EPV = E::kPerVec;
+    constexpr int EPT = NVEC * EPV;
+    constexpr int NW = THREADS / 64;
+    constexpr int CHUNK = THREADS * EPV;            // tokens covered by one load instruction of the workgroup
+
+    __shared__ double smem[NW * (NVEC > 5 ? NVEC : 5) + NW];
+    __shared__ int    smem_i[NW * 2 + 2];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row = blockIdx.x;
+    const int V = A.V;
+
+    // Rows live in global memory (address space 1): say so, or the loads are emitted as flat ones.
+    using gvec = const __attribute__((address_space(1))) u32x4*;
+    gvec cvec = (gvec)(static_cast<const T*>(A.draft) + row * A.stride);
+    gvec tvec = DO_V ? (gvec)(static_cast<const T*>(A.target) + row * A.stride) : nullptr;
+
+    // ---- loads: everything is issued before the first use --------------------------------------
+    // Vector indices past the end of the row are clamped to its last vector, so every lane loads
+    // valid memory unconditionally; tokens that do not exist are set to -inf afterwards.
+    const int last_vec = (V + EPV - 1) / EPV - 1;
+    u32x4 traw[DO_V ? NVEC : 1];
+    u32x4 craw[NVEC];
+    if constexpr (DO_V) {
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) traw[j] = tvec[min(j * THREADS + tid, last_vec)];
+    }
+#pragma unroll
+    for (int j = 0; j < NVEC; ++j) craw[j] = cvec[min(j * THREADS + tid, last_vec)];
+
+    // lane 0 fetches the row's scalars and the two logits of the drafted token
+    int xid = -1;
+    float cx = 0.f, tx = 0.f, ua = 0.f, ur = 0.f;
+    if (tid == 0) {
+        if (A.ids) {
+            xid = A.ids[row];
+            xid = xid < 0 ? 0 : (xid >= V ? V - 1 : xid);
+            const T* cr = static_cast<const T*>(A.draft) + row * A.stride;
+            if constexpr (sizeof(T) == 4) cx = reinterpret_cast<const float*>(cr)[xid];
+            else cx = bits_f((uint32_t)reinterpret_cast<const uint16_t*>(cr)[xid] << 16);
+        }
+        if constexpr (DO_V) {
+            const T* tr = static_cast<const T*>(A.target) + row * A.stride;
+            if constexpr (sizeof(T) == 4) tx = reinterpret_cast<const float*>(tr)[xid];
+            else tx = bits_f((uint32_t)reinterpret_cast<const uint16_t*>(tr)[xid] << 16);
+            ua = A.u_accept[row];
+            ur = A.u_resample[row];
+        }
+    }
+    const bool partial = V != NVEC * CHUNK;                        // uniform: the row does not fill the tile
+    if (partial) {
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) {
+            const int base = (j * THREADS + tid) * EPV;
+            E::mask_tail(craw[j], base, V);
+            if constexpr (DO_V) E::mask_tail(traw[j], base, V);
+        }
+    }
+
+    // ---- A: row maxima --------------------------------------------------------------------------
+    float mt = -INFINITY;
+    if constexpr (DO_V) {
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) {
+            float tv[EPV];
+            E::unpack(traw[j], tv);
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) mt = fmaxf(mt, tv[k]);
+        }
+    }
+    float e[EPT];
+#pragma unroll
+    for (int j = 0; j < NVEC; ++j) E::unpack(craw[j], &e[j * EPV]);
+    float mc = e[0];
+#pragma unroll
+    for (int i = 1; i < EPT; ++i) mc = fmaxf(mc, e[i]);
+    block_max2<NW>(mc, mt, smem, lane, wave);
+
+    // ---- B: exponentials and partition sums -----------------------------------------------------
+    const float nmc2 = (float)(-(double)mc * kLog2e);
+    const float nmt2 = (float)(-(double)mt * kLog2e);
+    double sz[2] = {0.0, 0.0};
+    if constexpr (DO_V) {
+        float zacc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) {
+            float tv[EPV];
+            E::unpack(traw[j], tv);
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) zacc[k & 3] += exp_shifted(tv[k], nmt2);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        sz[1] = (double)((zacc[0] + zacc[1]) + (zacc[2] + zacc[3]));
+    }
+    {
+        float sacc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) {
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) {
+                e[j * EPV + k] = exp_shifted(e[j * EPV + k], nmc2);
+                sacc[k & 3] += e[j * EPV + k];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        sz[0] = (double)((sacc[0] + sacc[1]) + (sacc[2] + sacc[3]));
+    }
+    block_sum<NW, 2>(sz, smem, lane, wave);
+    const double S = sz[0], Z = sz[1];
+
+    // ---- D1 + E: accept test, and the residual draw of a rejected row -----------------------------
+    // Done before the interval pass so that the verifier row's registers are free during that pass.
+    if constexpr (DO_V) {
+        if (tid == 0) {
+            const double lp = ((double)cx - (double)mc) - log(S);
+            const double lq = ((double)tx - (double)mt) - log(Z);
+            const double ell = lq - lp;
+            const double lnu = log((double)ua);                    // log(0) = -inf: always accepted
+            const int rej = !(lnu < fmin(0.0, ell));
+            if (A.accept) A.accept[row] = (uint8_t)(!rej);
+            if (!rej && A.row_id) A.row_id[row] = -1;
+            smem_i[NW * 2] = rej;
+            smem_i[NW * 2 + 1] = __float_as_int(ur);
+        }
+        __syncthreads();
+        const int rejected = smem_i[NW * 2];
+        if (rejected && A.row_id) {                                // workgroup-uniform
+            const double u_res = (double)__int_as_float(smem_i[NW * 2 + 1]);
+            const double invS = 1.0 / S, invZ = 1.0 / Z;
+            // E1: workgroup totals of res_i = max(0, q_i - p_i) over each chunk of CHUNK tokens
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) {
+                float tv[EPV];
+                E::unpack(traw[j], tv);
+                float s = 0.f;
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) {
+                    const double q = (double)exp_shifted(tv[k], nmt2) * invZ;
+                    const double p = (double)e[j * EPV + k] * invS;
+                    s += (float)fmax(q - p, 0.0);
+                }
+                const double ws = wave_sum((double)s);
+                if (lane == 0) smem[wave * NVEC + j] = ws;
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            __syncthreads();
+            double R = 0.0;
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) {
+#pragma unroll
+                for (int w = 0; w < NW; ++w) R += smem[w * NVEC + j];
+            }
+            int cand = INT_MAX, lastpos = -1;
+            if (R > 0.0) {
+                // chunk that holds the crossing of u * R (token order = chunk order, then lane order)
+                const double thr = u_res * R;
+                int jstar = -1, jlast = 0;
+                double before = 0.0, run = 0.0;
+#pragma unroll
+                for (int j = 0; j < NVEC; ++j) {
+                    double tot = 0.0;
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) tot += smem[w * NVEC + j];
+                    if (jstar < 0 && run + tot > thr) { jstar = j; before = run; }
+                    if (tot > 0.0) jlast = j;
+                    if (jstar < 0) run += tot;
+                }
+                if (jstar < 0) { jstar = jlast; before = run; }    // unreachable for u < 1; keeps the draw valid
+                // E2: the lane's residuals inside that chunk, recomputed exactly as in E1
+                float r[EPV];
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) r[k] = 0.f;
+#pragma unroll
+                for (int j = 0; j < NVEC; ++j) {
+                    if (j == jstar) {                              // uniform
+                        float tv[EPV];
+                        E::unpack(traw[j], tv);
+#pragma unroll
+                        for (int k = 0; k < EPV; ++k) {
+                            const double q = (double)exp_shifted(tv[k], nmt2) * invZ;
+                            const double p = (double)e[j * EPV + k] * invS;
+                            r[k] = (float)fmax(q - p, 0.0);
+                        }
+                    }
+                }
+                float s = 0.f;
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) s += r[k];
+                double incl = (double)s;
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) {
+                    const double n = __shfl_up(incl, o);
+                    if (lane >= o) incl += n;
+                }
+                if (lane == 63) smem[NW * NVEC + wave] = incl;
+                __syncthreads();
+                double cum = before + (incl - (double)s);
+#pragma unroll
+                for (int w = 0; w < NW; ++w)
+                    if (w < wave) cum += smem[NW * NVEC + w];
+                // smallest token of the chunk whose inclusive running sum exceeds u * R; tokens without
+                // residual mass cannot be drawn; lastpos covers a crossing lost to rounding at the chunk end
+                const int base = (jstar * THREADS + tid) * EPV;
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) {
+                    cum += (double)r[k];
+                    if (r[k] > 0.f) {
+                        lastpos = base + k;
+                        if (cum > thr && cand == INT_MAX) cand = base + k;
+                    }
+                }
+            } else {
+                // every residual rounded to zero (q == p to working precision): the draw degenerates
+                // to the lowest-index arg-max of q; re-read the row, this path is practically never taken
+                const T* tr = static_cast<const T*>(A.target) + row * A.stride;
+                for (int i = tid; i < V; i += THREADS) {
+                    float tvv;
+                    if constexpr (sizeof(T) == 4) tvv = reinterpret_cast<const float*>(tr)[i];
+                    else tvv = bits_f((uint32_t)reinterpret_cast<const uint16_t*>(tr)[i] << 16);
+                    if (tvv == mt) { cand = i; break; }
+                }
+            }
+            cand = wave_min_i(cand);
+            lastpos = wave_max_i(lastpos);
+            if (lane == 0) { smem_i[wave * 2] = cand; smem_i[wave * 2 + 1] = lastpos; }
+            __syncthreads();
+            if (tid == 0) {
+                int c0 = smem_i[0], l0 = smem_i[1];
+#pragma unroll
+                for (int w = 1; w < NW; ++w) { c0 = min(c0, smem_i[w * 2]); l0 = max(l0, smem_i[w * 2 + 1]); }
+                int id = (c0 != INT_MAX) ? c0 : l0;
+                if (id < 0) id = 0;
+                A.row_id[row] = id;
+            }
+        }
+    }
+
+    // ---- C + D2: InterFuse sums, score, flag and the drafted token's interval ------------------------
+    if constexpr (DO_Q) {
+        const FuseRow fr = fuse_row(S, A.a, A.b, V);
+        double q5[5];
+        if (partial) fuse_sums<THREADS, NVEC, EPV, true>(e, fr, tid, V, q5);
+        else         fuse_sums<THREADS, NVEC, EPV, false>(e, fr, tid, V, q5);
+        block_sum<NW, 5>(q5, smem, lane, wave);
+        if (tid == 0) {
+            const RowScore rs = finish_score(q5, fr, S, A);
+            if (A.omega) A.omega[row] = (float)rs.omega;
+            if (A.sigma) A.sigma[row] = (float)rs.sigma;
+            if (A.score) A.score[row] = (float)rs.score;
+            if (A.flags) A.flags[row] = (uint8_t)(rs.score > A.tau);
+            if (A.p_lo || A.p_mid || A.p_hi) {
+                // the reported token: the drafted one, or the arg-max (e = 1) when no ids are given
+                const double ex = (xid >= 0) ? exp((double)cx - (double)mc) : 1.0;
+                const double x = ex / S;
+                if (A.p_mid) A.p_mid[row] = (float)x;
+                if (A.p_lo) A.p_lo[row] = (float)(rs.alpha_l * A.b * x / (1.0 + (A.b - 1.0) * x));
+                if (A.p_hi) A.p_hi[row] = (float)(rs.alpha_u * A.a * x / (1.0 + (A.a - 1.0) * x));
+            }
+        }
+    }
+}
+
+// ---- window epilogue: one thread per window of K rows -------------------------------------------------
+
+__global__ __launch_bounds__(256) void window_kernel(const uint8_t* __restrict__ accept,
+                                                     const int32_t* __restrict__ row_id, int64_t N, int32_t K,
+                                                     int32_t* __restrict__ accept_len,
+                                                     int32_t* __restrict__ resampled_id)
+{
+    const int64_t W = (N + K - 1) / K;
+    const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (w >= W) return;
+    const int64_t lo = w * K;
+    const int64_t hi = (lo + K < N) ? lo + K : N;
+    int64_t n = 0;
+    while (lo + n < hi && accept[lo + n]) ++n;
+    if (accept_len) accept_len[w] = (int32_t)n;
+    if (resampled_id) resampled_id[w] = (lo + n < hi) ? row_id[lo + n] : -1;
+}
+
+// ---- dense export (tests / debugging): same per-token arithmetic, three sweeps over global memory --------
+
+template <typename T>
+__device__ __forceinline__ float load_elt(const T* p, int i)
+{
+    if constexpr (sizeof(T) == 4) return reinterpret_cast<const float*>(p)[i];
+    else return bits_f((uint32_t)reinterpret_cast<const uint16_t*>(p)[i] << 16);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void dense_kernel(const RowArgs A, float* __restrict__ p_lo,
+                                                    float* __restrict__ p_mid, float* __restrict__ p_hi)
+{
+    constexpr int NW = 4;
+    __shared__ double smem[NW * 5];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row = blockIdx.x;
+    const int V = A.V;
+    const T* c = static_cast<const T*>(A.draft) + row * A.stride;
+
+    float m = -INFINITY, unused = -INFINITY;
+    for (int i = tid; i < V; i += 256) m = fmaxf(m, load_elt(c, i));
+    block_max2<NW>(m, unused, smem, lane, wave);
+    const float nm2 = (float)(-(double)m * kLog2e);
+
+    double s1[1] = {0.0};
+    {
+        float acc = 0.f;
+        for (int i = tid; i < V; i += 256) acc += exp_shifted(load_elt(c, i), nm2);
+        s1[0] = (double)acc;
+    }
+    block_sum<NW, 1>(s1, smem, lane, wave);
+    const double S = s1[0];
+
+    const FuseRow fr = fuse_row(S, A.a, A.b, V);
+    double q5[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    {
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f, a4 = 0.f;
+        for (int i = tid; i < V; i += 256) {
+            float gl, gw;
+            fuse_token(exp_shifted(load_elt(c, i), nm2), fr, gl, gw);
+            gl -= fr.kl; gw -= fr.kw;
+            a0 += gl; a1 += gw;
+            a2 = fmaf(gl, gl, a2); a3 = fmaf(gw, gw, a3); a4 = fmaf(gl, gw, a4);
+        }
+        q5[0] = a0; q5[1] = a1; q5[2] = a2; q5[3] = a3; q5[4] = a4;
+    }
+    block_sum<NW, 5>(q5, smem, lane, wave);
+    const RowScore rs = finish_score(q5, fr, S, A);
+
+    const float Bc = (float)(A.b / S), Wc = (float)((A.a - A.b) / S), invS = (float)(1.0 / S);
+    const float al = (float)rs.alpha_l, au = (float)rs.alpha_u;
+    for (int i = tid; i < V; i += 256) {
+        const float e = exp_shifted(load_elt(c, i), nm2);
+        float gl, gw;
+        fuse_token(e, fr, gl, gw);
+        const float pl = Bc * gl;
+        const float pu = fmaf(Wc, gw, pl);
+        const int64_t o = row * (int64_t)V + i;
+        if (p_lo) p_lo[o] = al * pl;
+        if (p_mid) p_mid[o] = e * invS;
+        if (p_hi) p_hi[o] = au * pu;
+    }
+}
+
+// ---- dispatch ---------------------------------------------------------------------------------------------
+
+template <typename T, int THREADS, int NVEC>
+hipError_t launch_cfg(Mode mode, const RowArgs& a, hipStream_t s)
+{
+    const dim3 grid((unsigned)a.N), block(THREADS);
+    switch (mode) {
+    case Mode::Quantify: hipLaunchKernelGGL((row_kernel<T, THREADS, NVEC, true, false>), grid, block, 0, s, a); break;
+    case Mode::Verify:   hipLaunchKernelGGL((row_kernel<T, THREADS, NVEC, false, true>), grid, block, 0, s, a); break;
+    case Mode::Fused:    hipLaunchKernelGGL((row_kernel<T, THREADS, NVEC, true, true>), grid, block, 0, s, a); break;
+    }
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_typed(Mode mode, const RowArgs& a, hipStream_t s)
+{
+    const int vecs = (a.V + Elt<T>::kPerVec - 1) / Elt<T>::kPerVec;   // 16-byte vectors per row
+    if (vecs <= 256 * 1)  return launch_cfg<T, 256, 1>(mode, a, s);
+    if (vecs <= 256 * 2)  return launch_cfg<T, 256, 2>(mode, a, s);
+    if (vecs <= 256 * 4)  return launch_cfg<T, 256, 4>(mode, a, s);
+    if (vecs <= 256 * 8)  return launch_cfg<T, 256, 8>(mode, a, s);
+    if (vecs <= 256 * 16) return launch_cfg<T, 256, 16>(mode, a, s);
+    if (vecs <= 1024 * 8) return launch_cfg<T, 1024, 8>(mode, a, s);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+int max_vocab(int dtype) { return dtype == 0 ? 1024 * 8 * 4 : 1024 * 8 * 8; }
+
+hipError_t launch_rows(Mode mode, int dtype, const RowArgs& args, hipStream_t stream)
+{
+    if (args.N <= 0) return hipSuccess;
+    return dtype == 0 ? launch_typed<float>(mode, args, stream) : launch_typed<bf16_t>(mode, args, stream);
+}
+
+hipError_t launch_windows(const uint8_t* accept, const int32_t* row_id, int64_t N, int32_t K,
+                          int32_t* accept_len, int32_t* resampled_id, hipStream_t stream)
+{
+    if (N <= 0) return hipSuccess;
+    const int64_t W = (N + K - 1) / K;
+    const unsigned blocks = (unsigned)((W + 255) / 256);
+    hipLaunchKernelGGL(window_kernel, dim3(blocks), dim3(256), 0, stream, accept, row_id, N, K, accept_len,
+                       resampled_id);
+    return hipGetLastError();
+}
+
+hipError_t launch_dense(int dtype, const RowArgs& args, float* p_lo, float* p_mid, float* p_hi,
+                        hipStream_t stream)
+{
+    if (args.N <= 0) return hipSuccess;
+    const dim3 grid((unsigned)args.N), block(256);
+    if (dtype == 0) hipLaunchKernelGGL(dense_kernel<float>, grid, block, 0, stream, args, p_lo, p_mid, p_hi);
+    else hipLaunchKernelGGL(dense_kernel<bf16_t>, grid, block, 0, stream, args, p_lo, p_mid, p_hi);
+    return hipGetLastError();
+}
+
+}  // namespace ciar

@@ -186,7 +186,7 @@ def make(cfg: int, device="cpu", rows: int | None = None, seed: int | None = Non
         # drafted token ~ distribution of the stored centre logits, by Gumbel-max
         u = torch.rand((_CHUNK, V), generator=gen, device=device, dtype=torch.float32)[:n]
         u = u.clamp_(min=1e-30)
-        gumbel = -torch.log(-torch.log(u).clamp_(min=1e-30))
+        gumbel = -torch.log((-torch.log(u)).clamp_(min=1e-30))
         ids[lo:hi] = torch.argmax(c_st.to(torch.float32) + gumbel, dim=1).to(torch.int32)
         u_acc[lo:hi] = _uniform24(_CHUNK, gen, device)[:n]
         u_res[lo:hi] = _uniform24(_CHUNK, gen, device)[:n]

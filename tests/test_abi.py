@@ -1,0 +1,133 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function that
+include/ciar.h declares, and rejects bad arguments with the documented status codes before any
+launch.  Pointers passed here are fake device addresses; they are validated, never dereferenced."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ciar.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2603_25463_amd import build as _build
+    from paper_2603_25463_amd import binding
+    _build.build(force=False)
+    return binding.lib()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ciar_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    names = _declared_functions()
+    for n in ("ciar_quantify", "ciar_verify", "ciar_quantify_verify", "ciar_dense_intervals",
+              "ciar_workspace_bytes", "ciar_params_default", "ciar_last_error", "ciar_version"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(L):
+    for n in _declared_functions():
+        assert hasattr(L, n), n
+
+
+def test_struct_layout_matches_the_binding(L):
+    from paper_2603_25463_amd.binding import CiarParams
+    p = CiarParams()
+    L.ciar_params_default(ctypes.byref(p))
+    assert p.struct_size == ctypes.sizeof(CiarParams) == 56
+    assert (p.dtype, p.window, p.normalize, p.reserved) == (0, 8, 1, 0)
+    assert abs(p.confidence - 0.9) < 1e-7 and p.radius_scale < 0 and p.radius_max == 10.0
+    assert abs(p.tau - 0.30) < 1e-7 and abs(p.lower_cap - 0.99) < 1e-7 and abs(p.upper_cap - 1.01) < 1e-7
+
+
+def _params(L, **kw):
+    from paper_2603_25463_amd.binding import CiarParams
+    p = CiarParams()
+    L.ciar_params_default(ctypes.byref(p))
+    p.vocab, p.row_stride = 1024, 1024
+    for k, v in kw.items():
+        setattr(p, k, v)
+    return p
+
+
+FAKE = 0x7f0000000000          # 16-byte aligned, never dereferenced on an error path
+
+
+def _quantify(L, p, draft=FAKE, N=4, out=FAKE + 4096):
+    return L.ciar_quantify(draft, None, N, ctypes.byref(p), out, None, None, None, None, None, None, None)
+
+
+def test_argument_errors_are_reported_before_any_launch(L):
+    from paper_2603_25463_amd.binding import last_error
+    EINVAL, EALIGN, EWORK, EUNSUP = -1, -2, -3, -4
+    assert _quantify(L, _params(L, struct_size=8)) == EINVAL and "struct_size" in last_error()
+    assert _quantify(L, _params(L, vocab=0)) == EINVAL
+    assert _quantify(L, _params(L, vocab=40000)) == EUNSUP and "maximum" in last_error()
+    assert _quantify(L, _params(L, vocab=70000, row_stride=70000, dtype=1)) == EUNSUP
+    assert _quantify(L, _params(L, dtype=7)) == EUNSUP
+    assert _quantify(L, _params(L, row_stride=1000)) == EINVAL            # stride < vocab
+    assert _quantify(L, _params(L, vocab=1001, row_stride=1001)) == EALIGN  # 4004 bytes per row
+    assert _quantify(L, _params(L, window=0)) == EINVAL
+    assert _quantify(L, _params(L, confidence=1.0)) == EINVAL
+    assert _quantify(L, _params(L, confidence=1.0, radius_scale=0.5), N=0) == 0   # override: gamma unused
+    assert _quantify(L, _params(L, radius_max=-1.0)) == EINVAL
+    assert _quantify(L, _params(L, tau=float("nan"))) == EINVAL
+    assert _quantify(L, _params(L, lower_cap=1.5)) == EINVAL
+    assert _quantify(L, _params(L, reserved=1)) == EINVAL
+    assert _quantify(L, _params(L), draft=None) == EINVAL and "draft_logits" in last_error()
+    assert _quantify(L, _params(L), draft=FAKE + 4) == EALIGN
+    assert _quantify(L, _params(L), N=-1) == EINVAL
+    assert _quantify(L, _params(L), out=None) == EINVAL and "output" in last_error()
+    assert L.ciar_quantify(FAKE, None, 4, None, FAKE, None, None, None, None, None, None, None) == EINVAL
+    # verify: required inputs, workspace rules
+    p = _params(L)
+    a = ctypes.byref(p)
+    assert L.ciar_verify(FAKE, None, FAKE, FAKE, FAKE, 4, a, FAKE, FAKE, None, None, None, 0, None) == EINVAL
+    assert L.ciar_verify(FAKE, FAKE, None, FAKE, FAKE, 4, a, FAKE, FAKE, None, None, None, 0, None) == EINVAL
+    assert L.ciar_verify(FAKE, FAKE, FAKE, None, FAKE, 4, a, FAKE, FAKE, None, None, None, 0, None) == EINVAL
+    assert L.ciar_verify(FAKE, FAKE, FAKE, FAKE, None, 4, a, FAKE, FAKE, None, None, None, 0, None) == EINVAL
+    assert L.ciar_verify(FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, None, None, None, None, None, 0, None) == EINVAL
+    # window outputs without per-row buffers need the workspace
+    assert L.ciar_verify(FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, None, None, FAKE, FAKE, None, 0, None) == EWORK
+    assert L.ciar_verify(FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, None, None, FAKE, FAKE, FAKE, 8, None) == EWORK
+    assert L.ciar_verify(FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, None, None, FAKE, FAKE, FAKE + 8, 4096, None) == EALIGN
+    assert L.ciar_quantify_verify(FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, *([None] * 11), None, 0, None) == EINVAL
+    assert L.ciar_dense_intervals(FAKE, 4, a, None, None, None, None) == EINVAL
+
+
+def test_empty_batch_is_ok_and_launches_nothing(L):
+    p = _params(L)
+    a = ctypes.byref(p)
+    assert _quantify(L, p, N=0) == 0
+    assert L.ciar_verify(FAKE, FAKE, FAKE, FAKE, FAKE, 0, a, FAKE, FAKE, FAKE, FAKE, None, 0, None) == 0
+    assert L.ciar_dense_intervals(FAKE, 0, a, FAKE, None, None, None) == 0
+
+
+def test_workspace_size(L):
+    p = _params(L)
+    f = L.ciar_workspace_bytes
+    assert f(0, ctypes.byref(p)) == 0 and f(-5, ctypes.byref(p)) == 0
+    for N in (1, 7, 256, 2048, 32768):
+        b = f(N, ctypes.byref(p))
+        assert b % 256 == 0 and b >= 5 * N
+
+
+def test_version_and_error_strings(L):
+    from paper_2603_25463_amd import binding
+    assert re.fullmatch(r"\d+\.\d+\.\d+", binding.version())
+    assert isinstance(binding.last_error(), str)
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    from paper_2603_25463_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "absent.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        binding.lib()

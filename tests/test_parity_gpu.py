@@ -1,0 +1,311 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on identical bytes.
+
+Every test prints what it is about to run (and flushes) before the first GPU call.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import parity
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ciar():
+    import paper_2603_25463_amd as m
+    m.lib()                      # raises if libciar.so has not been built: no fallback
+    assert torch.cuda.is_available()
+    return m
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def _oparams(oracle, p):
+    return oracle.Params(confidence=p.confidence, kappa=p.radius_scale, radius_max=p.radius_max, tau=p.tau,
+                         lower_cap=p.lower_cap, upper_cap=p.upper_cap, normalize=p.normalize, window=p.window)
+
+
+def _run_case(ciar, oracle, draft, target, ids, ua, ur, P, vocab=None, tag="", host=None):
+    """Fused, quantify-only and verify-only entry points against the oracle.  Tensors are on the GPU."""
+    say(f"[case {tag}] N={draft.shape[0]} V={vocab or draft.shape[1]} dtype={draft.dtype} "
+        f"K={P.window} conf={P.confidence} kappa={P.radius_scale} tau={P.tau} norm={P.normalize}")
+    N = draft.shape[0]
+    ws = torch.empty(ciar.workspace_bytes(N, P.to_c(draft, vocab)) or 16, dtype=torch.uint8, device=draft.device)
+    fused = ciar.quantify_verify(draft, target, ids, ua, ur, P, vocab=vocab, workspace=ws)
+    qonly = ciar.quantify(draft, ids, P, vocab=vocab)
+    vonly = ciar.verify(draft, target, ids, ua, ur, P, vocab=vocab, workspace=ws)
+    torch.cuda.synchronize()
+    # the three entry points run the same arithmetic: bit-identical outputs
+    for k in parity.FLOAT_KEYS + ("flags",):
+        assert torch.equal(fused[k], qonly[k]), k
+    for k in ("accept", "row_id", "accept_len", "resampled_id"):
+        assert torch.equal(fused[k], vonly[k]), k
+
+    OP = _oparams(oracle, P)
+    dh, th = host if host is not None else (draft.cpu(), target.cpu())
+    idh, uah, urh = ids.cpu().numpy(), ua.cpu().numpy(), ur.cpu().numpy()
+    oq = oracle.quantify(dh, idh, OP, vocab=vocab)
+    ov = oracle.verify(dh, th, idh, uah, urh, OP, vocab=vocab)
+    worst = parity.check_floats(fused, oq)
+    ex_flag = parity.check_flags(fused["flags"], oq, float(np.float32(P.tau)))
+    st = parity.check_verify(fused, ov, uah, urh, P.window,
+                             residual_cdf=lambda r: oracle.residual_cdf(dh, th, r, OP, vocab=vocab))
+    say(f"   worst err/bound {max(worst.values()):.3f}; flagged {int(oq['flags'].sum())}/{N}; "
+        f"exempt flag/accept/resample = {ex_flag}/{st['exempt_accept']}/{st['exempt_resample']}; "
+        f"rejected {st['rejected']}")
+    return oq, ov, ex_flag, st
+
+
+# ---- the five workloads, full size, every row -------------------------------------------------------
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_workload_full_size(ciar, oracle, cfg):
+    from paper_2603_25463_amd import workloads as wl
+    say(f"[workload {cfg}] generating on the GPU")
+    w = wl.make(cfg, device="cuda")
+    spec = w.spec
+    N = w.rows
+    host = (w.draft.cpu(), w.target.cpu())
+    for gi, gamma in enumerate(spec.confidences):
+        # tau = 0.30 is the paper's value (nothing is flagged on these synthetic rows: U ~ 1e-2);
+        # tau* = the oracle's median U splits the rows ~50/50 and exercises the margin rule.
+        P = ciar.Params(confidence=gamma, tau=0.30, window=spec.window)
+        if gi == 0:
+            oq, ov, exf, st = _run_case(ciar, oracle, w.draft, w.target, w.ids, w.u_accept, w.u_resample, P,
+                                        tag=f"cfg{cfg} tau=0.30", host=host)
+            assert int(oq["flags"].sum()) == 0
+            assert st["exempt_accept"] <= 2 and st["exempt_resample"] <= max(4, 0.3 * st["rejected"])
+            acc = float(ov["accept"].mean())
+            say(f"   acceptance rate {acc:.3f}")
+            if cfg == 4:
+                # identical rows always accept; only redrawn rows can reject
+                same = ~w.meta["redraw"]
+                assert ov["accept"][same].all()
+            else:
+                expect = 2 * 0.5 * math.erfc(spec.sigma / 2 / math.sqrt(2))     # 2 Phi(-sigma/2)
+                assert abs(acc - expect) < 0.06
+        else:
+            oq = oracle.quantify(host[0], w.ids.cpu().numpy(), _oparams(oracle, P))
+        tau_star = float(np.float32(np.median(oq["score"])))
+        P2 = ciar.Params(confidence=gamma, tau=tau_star, window=spec.window)
+        say(f"[workload {cfg}] gamma={gamma} tau*={tau_star:.6g}")
+        g = ciar.quantify(w.draft, w.ids, P2)
+        torch.cuda.synchronize()
+        oq2 = dict(oq)
+        oq2["flags"] = (oq["score"] > float(np.float32(tau_star))).astype(np.uint8)
+        parity.check_floats(g, oq2)
+        ex = parity.check_flags(g["flags"], oq2, float(np.float32(tau_star)))
+        frac = float(oq2["flags"].mean())
+        say(f"   flagged fraction {frac:.3f}, exempt {ex}")
+        assert 0.4 < frac < 0.6 and ex <= 3
+
+
+def test_nested_intervals_across_confidences_on_the_gpu(ciar):
+    """Raw InterFuse on the large-vocabulary workload: the drafted token's interval widens with gamma
+    and Omega grows (a property that holds at any size; checked on the GPU outputs themselves)."""
+    from paper_2603_25463_amd import workloads as wl
+    say("[nested] cfg5 first 2048 rows, normalize=0, gamma in 0.8/0.9/0.95")
+    w = wl.make(5, device="cuda", rows=2048)
+    prev = None
+    for gamma in (0.8, 0.9, 0.95):
+        g = ciar.quantify(w.draft, w.ids, ciar.Params(confidence=gamma, normalize=False, window=8))
+        torch.cuda.synchronize()
+        if prev is not None:
+            assert torch.all(g["p_lo"] <= prev["p_lo"]) and torch.all(g["p_hi"] >= prev["p_hi"])
+            assert torch.all(g["omega"] > prev["omega"])
+            assert torch.equal(g["p_mid"], prev["p_mid"])
+        prev = g
+
+
+# ---- shapes: every tile configuration, ragged vocabularies, strides, ragged last window ---------------
+
+SHAPES = [
+    # (V, stride, N, K, dtype)
+    (2, 4, 37, 4, torch.float32),
+    (5, 8, 19, 3, torch.float32),
+    (1000, 1000, 65, 8, torch.float32),
+    (1023, 1024, 33, 5, torch.float32),
+    (1024, 1024, 64, 8, torch.float32),
+    (1025, 1028, 31, 8, torch.float32),
+    (3000, 3000, 40, 7, torch.float32),
+    (4096, 4100, 40, 8, torch.float32),
+    (8191, 8192, 21, 8, torch.float32),
+    (8192, 8192, 48, 16, torch.float32),
+    (12345, 12348, 35, 8, torch.float32),
+    (16384, 16384, 70, 8, torch.float32),
+    (16385, 16388, 9, 4, torch.float32),
+    (32768, 32768, 12, 4, torch.float32),
+    (3, 8, 37, 4, torch.bfloat16),
+    (1001, 1008, 65, 8, torch.bfloat16),
+    (2048, 2048, 64, 8, torch.bfloat16),
+    (5000, 5000, 40, 6, torch.bfloat16),
+    (8192, 8192, 40, 8, torch.bfloat16),
+    (16383, 16384, 33, 8, torch.bfloat16),
+    (16384, 16384, 64, 8, torch.bfloat16),
+    (20000, 20000, 17, 8, torch.bfloat16),
+    (32768, 32776, 20, 8, torch.bfloat16),
+    (65535, 65536, 9, 4, torch.bfloat16),
+    (65536, 65536, 16, 8, torch.bfloat16),
+]
+
+
+def _random_case(V, stride, N, K, dtype, seed, sigma=0.5):
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    scale = torch.rand((N, 1), generator=g, device="cuda") * 2.5 + 0.5
+    c = torch.randn((N, stride), generator=g, device="cuda") * scale
+    peak = torch.randint(0, V, (N,), generator=g, device="cuda")
+    c[torch.arange(N, device="cuda")[::2], peak[::2]] += 8.0
+    t = c + sigma * torch.randn((N, stride), generator=g, device="cuda")
+    # poison the padding: it must never be read as a token
+    if stride > V:
+        c[:, V:] = 1e30
+        t[:, V:] = -1e30
+    c, t = c.to(dtype), t.to(dtype)
+    gum = -torch.log(-torch.log(torch.rand((N, V), generator=g, device="cuda").clamp_(1e-30, 1 - 1e-7)))
+    ids = torch.argmax(c[:, :V].float() + gum, dim=1).to(torch.int32)
+    ua = torch.randint(0, 1 << 24, (N,), generator=g, device="cuda").float() / (1 << 24)
+    ur = torch.randint(0, 1 << 24, (N,), generator=g, device="cuda").float() / (1 << 24)
+    return c, t, ids, ua, ur
+
+
+@pytest.mark.parametrize("V,stride,N,K,dtype", SHAPES)
+def test_shapes_and_ragged_tails(ciar, oracle, V, stride, N, K, dtype):
+    c, t, ids, ua, ur = _random_case(V, stride, N, K, dtype, seed=1000 + V)
+    for norm, kap in ((True, -1.0), (False, 0.7)):
+        P = ciar.Params(confidence=0.9, radius_scale=kap, normalize=norm, window=K, tau=0.01)
+        _run_case(ciar, oracle, c, t, ids, ua, ur, P, vocab=V, tag=f"V={V} stride={stride}")
+
+
+# ---- degenerate rows ----------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_degenerate_rows(ciar, oracle, dtype):
+    """Uniform, one-hot, extreme-magnitude, masked (-inf) and identical draft/target rows."""
+    V, K = 16384, 4
+    g = torch.Generator(device="cuda").manual_seed(7)
+    rows = []
+    rows.append(torch.zeros(V))                                        # uniform
+    rows.append(torch.full((V,), 3.25))                                # uniform, shifted
+    r = torch.zeros(V); r[77] = 80.0; rows.append(r)                   # one-hot
+    r = torch.zeros(V); r[V - 1] = 30.0; rows.append(r)                # one-hot at the last token
+    r = torch.randn(V) * 2 + 80.0; rows.append(r)                      # large positive logits
+    r = torch.randn(V) * 2 - 80.0; rows.append(r)                      # large negative logits
+    r = torch.randn(V) * 2; r[::3] = -float("inf"); rows.append(r)     # a third of the tokens masked
+    r = torch.full((V,), -float("inf")); r[5] = 1.0; r[9000] = 0.5; rows.append(r)   # two live tokens
+    r = torch.randn(V) * 0.01; rows.append(r)                          # nearly flat
+    r = torch.randn(V) * 10; rows.append(r)                            # very spread
+    c = torch.stack(rows).cuda()
+    N = c.shape[0]
+    t = c.clone()
+    t[4] = c[4] + 0.5 * torch.randn(V, device="cuda", generator=g)
+    t[9] = c[9] + 1.0 * torch.randn(V, device="cuda", generator=g)
+    t[2] = torch.full((V,), -30.0, device="cuda"); t[2, 100] = 5.0     # target disagrees with a one-hot draft
+    c, t = c.to(dtype), t.to(dtype)
+    ids = torch.tensor([0, 5, 77, V - 1, 3, 4, 1, 5, 6, 7], dtype=torch.int32, device="cuda")
+    ids[4] = int(torch.argmax(c[4].float())); ids[9] = int(torch.argmax(c[9].float()))
+    ua = torch.tensor([0.0, 0.999, 0.5, 0.3, 0.99, 0.2, 0.7, 0.1, 0.6, 0.999], device="cuda")
+    ur = torch.tensor([0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7, 0.8, 0.9, 1 - 2.0 ** -24], device="cuda")
+    for norm in (True, False):
+        for kap in (-1.0, 0.0, 3.0):
+            P = ciar.Params(confidence=0.9, radius_scale=kap, normalize=norm, window=K, tau=1e-3)
+            oq, ov, _, _ = _run_case(ciar, oracle, c, t, ids, ua, ur, P, tag=f"degenerate {dtype} norm={norm}")
+            assert list(ov["accept"][[0, 1, 3, 5, 6, 7, 8]]) == [1] * 7      # identical rows accept
+            assert ov["accept"][2] == 0 and ov["row_id"][2] == 100            # the only residual mass
+    # closed forms straight from the GPU (uniform row: Omega = V (p^u - p^l), U = 0; one-hot with caps)
+    gq = ciar.quantify(c, ids, ciar.Params(confidence=0.9, window=K))
+    torch.cuda.synchronize()
+    kappa = math.sqrt(2) * 1.1630871536766743      # erfinv(0.9)
+    a, b = math.exp(kappa), math.exp(-kappa)
+    assert abs(gq["omega"][0].item() - V * (a / (V - 1 + a) - b / (V - 1 + b))) < 1e-4
+    assert gq["score"][0].item() < 1e-7 and gq["flags"][0].item() == 0
+    assert abs(gq["omega"][2].item() - 0.02) < 1e-6
+    assert abs(gq["score"][2].item() - 0.02 ** 2 * math.sqrt(V - 1) / V) < 1e-9
+
+
+def test_quantify_without_ids_reports_the_argmax_token(ciar, oracle):
+    c, t, ids, ua, ur = _random_case(4096, 4096, 50, 8, torch.float32, seed=5)
+    say("[argmax] V=4096 N=50")
+    g = ciar.quantify(c, None, ciar.Params())
+    torch.cuda.synchronize()
+    o = oracle.quantify(c.cpu(), None, oracle.Params())
+    parity.check_floats(g, o)
+
+
+def test_null_outputs_and_workspace_paths(ciar, oracle):
+    """Window outputs only (per-row results go to the workspace), and single outputs."""
+    import ctypes
+    from paper_2603_25463_amd.binding import _ptr, _stream
+    c, t, ids, ua, ur = _random_case(2048, 2048, 43, 5, torch.float32, seed=11)
+    say("[null outputs] V=2048 N=43 K=5")
+    P = ciar.Params(window=5)
+    cp = P.to_c(c)
+    L = ciar.lib()
+    ref = ciar.verify(c, t, ids, ua, ur, P, workspace=None)
+    W = ref["accept_len"].numel()
+    al = torch.full((W,), -7, dtype=torch.int32, device="cuda")
+    ri = torch.full((W,), -7, dtype=torch.int32, device="cuda")
+    ws = torch.empty(ciar.workspace_bytes(43, cp), dtype=torch.uint8, device="cuda")
+    rc = L.ciar_verify(_ptr(c), _ptr(t), _ptr(ids), _ptr(ua), _ptr(ur), 43, ctypes.byref(cp),
+                       None, None, _ptr(al), _ptr(ri), _ptr(ws), ws.numel(), _stream(None))
+    assert rc == 0, ciar.last_error()
+    torch.cuda.synchronize()
+    assert torch.equal(al, ref["accept_len"]) and torch.equal(ri, ref["resampled_id"])
+    # accept_len alone: no residual draw is needed
+    al2 = torch.full((W,), -7, dtype=torch.int32, device="cuda")
+    rc = L.ciar_verify(_ptr(c), _ptr(t), _ptr(ids), _ptr(ua), _ptr(ur), 43, ctypes.byref(cp),
+                       None, None, _ptr(al2), None, _ptr(ws), ws.numel(), _stream(None))
+    assert rc == 0, ciar.last_error()
+    torch.cuda.synchronize()
+    assert torch.equal(al2, ref["accept_len"])
+    # a single quantify output
+    sc = torch.empty(43, dtype=torch.float32, device="cuda")
+    rc = L.ciar_quantify(_ptr(c), None, 43, ctypes.byref(cp), None, None, None, None, None, _ptr(sc), None,
+                         _stream(None))
+    assert rc == 0, ciar.last_error()
+    torch.cuda.synchronize()
+    assert torch.equal(sc, ciar.quantify(c, ids, P)["score"])
+
+
+def test_dense_export_matches_the_oracle_curves(ciar, oracle):
+    for V, dtype in ((1000, torch.float32), (16384, torch.bfloat16)):
+        c, *_ = _random_case(V, V, 6, 4, dtype, seed=21)
+        say(f"[dense] V={V} {dtype}")
+        for norm in (True, False):
+            P = ciar.Params(confidence=0.95, normalize=norm)
+            lo, mid, hi = ciar.dense_intervals(c, P)
+            torch.cuda.synchronize()
+            olo, omid, ohi = oracle.dense_intervals(c.cpu(), oracle.Params(confidence=0.95, normalize=norm))
+            for g, o in ((lo, olo), (mid, omid), (hi, ohi)):
+                g = g.cpu().numpy().astype(np.float64)
+                assert np.all(np.abs(g - o) <= parity.ATOL + parity.RTOL * np.abs(o))
+
+
+def test_results_are_deterministic_and_stream_ordered(ciar):
+    c, t, ids, ua, ur = _random_case(16384, 16384, 300, 8, torch.float32, seed=31)
+    say("[determinism] V=16384 N=300, two runs, second on a side stream")
+    P = ciar.Params(tau=0.01)
+    a = ciar.quantify_verify(c, t, ids, ua, ur, P)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        b = ciar.quantify_verify(c, t, ids, ua, ur, P, stream=s)
+    s.synchronize()
+    for k in a:
+        assert torch.equal(a[k], b[k]), k
+
+
+def test_bad_arguments_raise(ciar):
+    c = torch.zeros((4, 1024), device="cuda")
+    with pytest.raises(ciar.CiarError, match="CIAR_EUNSUPPORTED"):
+        ciar.quantify(torch.zeros((2, 40000), device="cuda"), None, ciar.Params())
+    with pytest.raises(ciar.CiarError, match="CIAR_EALIGN"):
+        ciar.quantify(torch.zeros((4, 1028), device="cuda")[:, 1:1025], None, ciar.Params())
+    with pytest.raises(ciar.CiarError, match="CIAR_EINVAL"):
+        ciar.quantify(c, None, ciar.Params(confidence=1.5))
+    with pytest.raises(TypeError):
+        ciar.quantify(c.half(), None, ciar.Params())
