@@ -37,20 +37,22 @@
 namespace ciar {
 namespace {
 
-// log2(e) split so that the low part is positive: (-inf) * hi + ((-inf) * lo - m) stays -inf.
+// log2(e) split so that the low part is positive: d * hi + d * lo stays -inf for d = -inf.
 constexpr float  kLog2eHi = 1.44269490242004394531f;   // largest float below log2(e)
 constexpr float  kLog2eLo = 1.384689195e-7f;           // log2(e) - kLog2eHi
-constexpr double kLog2e   = 1.4426950408889634;
 
 __device__ __forceinline__ float bits_f(uint32_t u) { return __uint_as_float(u); }
 
 // 16 bytes as loaded: a native vector type, so it can be read through an address-space pointer.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// exp(x - m) for x <= m as 2^(x log2e - m log2e); neg_m2 = -(m log2e) rounded once per row.
-__device__ __forceinline__ float exp_shifted(float x, float neg_m2)
+// exp(x - m) for x <= m.  The difference d = x - m is formed first: it is exact for logits near the
+// maximum and its rounding error shrinks with |d|, so the tokens that carry the mass get full
+// precision and the row maximum maps to exactly 1.  d * log2(e) uses the two-term constant.
+__device__ __forceinline__ float exp_shifted(float x, float m)
 {
-    return __builtin_amdgcn_exp2f(fmaf(x, kLog2eHi, fmaf(x, kLog2eLo, neg_m2)));
+    const float d = x - m;
+    return __builtin_amdgcn_exp2f(fmaf(d, kLog2eHi, d * kLog2eLo));
 }
 
 template <typename T> struct Elt;
@@ -164,10 +166,9 @@ struct FuseRow {
     float cu;            // (a-1)/S:  du = 1 + (a-1) x = 1 + cu e
     float nih, nil;      // -1/S split in two floats:  1 - x = 1 + nih e + nil e  (exact to ~1e-15)
     float b, omb;        // b and 1-b:  dl = 1 - (1-b) x = b + (1-b)(1-x), free of cancellation as x -> 1
-    float kl, kw;        // the values gl, gw take on the uniform row (e = S/V): centring constants
 };
 
-__device__ __forceinline__ FuseRow fuse_row(double S, double a, double b, int V)
+__device__ __forceinline__ FuseRow fuse_row(double S, double a, double b)
 {
     FuseRow r;
     const double invS = 1.0 / S;
@@ -176,10 +177,6 @@ __device__ __forceinline__ FuseRow fuse_row(double S, double a, double b, int V)
     r.nil = (float)(-invS - (double)r.nih);
     r.b = (float)b;
     r.omb = (float)(1.0 - b);
-    const double xu = 1.0 / (double)V, eu = S * xu;
-    const double du = 1.0 + (a - 1.0) * xu, dl = 1.0 + (b - 1.0) * xu;
-    r.kl = (float)(eu / dl);
-    r.kw = (float)(eu * (1.0 - xu) / (du * dl));
     return r;
 }
 
@@ -197,32 +194,29 @@ __device__ __forceinline__ void fuse_token(float e, const FuseRow& r, float& gl,
 // Per-row scalars of the quantifier from the five centred sums (fp64, one lane).
 struct RowScore { double alpha_l, alpha_u, omega, sigma, score; };
 
-__device__ __forceinline__ RowScore finish_score(const double (&s)[5], const FuseRow& fr, double S,
-                                                 const RowArgs& A)
+__device__ __forceinline__ RowScore finish_score(const double (&s)[5], double S, const RowArgs& A)
 {
-    // s = { sum(gl-kl), sum(gw-kw), sum(gl-kl)^2, sum(gw-kw)^2, sum(gl-kl)(gw-kw) } over the V tokens
+    // s = { sum gl, sum gw, sum gl^2, sum gw^2, sum gl gw } over the V tokens of the row
     const double V = (double)A.V;
     const double Bc = A.b / S, Wc = (A.a - A.b) / S;
-    const double Gl = s[0] + V * (double)fr.kl, Gw = s[1] + V * (double)fr.kw;
-    const double Sl = Bc * Gl, Su = Sl + Wc * Gw;
+    const double Sl = Bc * s[0], Su = Sl + Wc * s[1];
     RowScore o;
     o.alpha_l = 1.0; o.alpha_u = 1.0;
     if (A.normalize) {
         o.alpha_l = fmin(1.0, A.cap_lo / Sl);
         o.alpha_u = fmax(1.0, A.cap_hi / Su);
     }
-    // delta_i = alpha_u w_i + (alpha_u - alpha_l) p^l_i = cw gw_i + cl gl_i
+    // delta_i = alpha_u p^u_i - alpha_l p^l_i = alpha_u w_i + (alpha_u - alpha_l) p^l_i = cw gw_i + cl gl_i:
+    // both coefficients are >= 0, so Omega and the second moment are sums of non-negative terms.
     const double cw = o.alpha_u * Wc, cl = (o.alpha_u - o.alpha_l) * Bc;
-    o.omega = cw * Gw + cl * Gl;
-    const double L = cw * s[1] + cl * s[0];
+    o.omega = cw * s[1] + cl * s[0];
     const double Q = cw * cw * s[3] + 2.0 * cw * cl * s[4] + cl * cl * s[2];
-    const double var = fmax(0.0, Q - L * L / V) / V;
+    // fp64 sums: the subtraction of the squared mean costs at most ~1/CV^2 of 1e-16
+    const double var = fmax(0.0, Q - o.omega * o.omega / V) / V;
     o.sigma = sqrt(var);
     o.score = o.omega * o.sigma;
     return o;
 }
-
-// ---- the row kernel ---------------------------------------------------------------------------
 
 // Waves per SIMD the register allocation aims for: the rows held in registers (EPT floats for c,
 // EPT more for t in full precision, half that for packed bf16) plus ~40 working registers.
@@ -237,36 +231,37 @@ constexpr int target_waves()
 }
 
 // Pass C for one lane: the five centred InterFuse sums over the lane's tokens.
-// MASKED = the row does not fill the tile, so tokens with index >= V must not be counted.
+// MASKED = the row does not fill the tile: chunks past the end are skipped (padding inside the last
+// chunk has e = 0 and adds exactly nothing).
 template <int THREADS, int NVEC, int EPV, bool MASKED>
-__device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const FuseRow& fr, int tid, int V,
+__device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const FuseRow& fr, int V,
                                           double (&q5)[5])
 {
-    float a0[2] = {0.f, 0.f}, a1[2] = {0.f, 0.f}, a2[2] = {0.f, 0.f}, a3[2] = {0.f, 0.f}, a4[2] = {0.f, 0.f};
+    // The five sums run in fp64 from the first add (fp64 adds and FMAs issue at the fp32 rate on this
+    // chip).  One token can hold almost all of sum(gl), and the variance is a difference of second
+    // moments that would cancel in fp32 on nearly flat rows; in fp64 neither needs a centring trick.
+    double a0[2] = {0.0, 0.0}, a1[2] = {0.0, 0.0}, a2[2] = {0.0, 0.0}, a3[2] = {0.0, 0.0}, a4[2] = {0.0, 0.0};
 #pragma unroll
     for (int j = 0; j < NVEC; ++j) {
-        const int base = (j * THREADS + tid) * EPV;
-        if (MASKED && j * THREADS * EPV >= V) break;               // uniform: the chunk holds no token
+        if (MASKED && j * THREADS * EPV >= V) continue;            // uniform: the chunk holds no token
 #pragma unroll
         for (int k = 0; k < EPV; ++k) {
             float gl, gw;
-            fuse_token(e[j * EPV + k], fr, gl, gw);
-            gl -= fr.kl;
-            gw -= fr.kw;
-            if (MASKED && base + k >= V) { gl = 0.f; gw = 0.f; }   // padding is not a token
-            a0[k & 1] += gl;
-            a1[k & 1] += gw;
-            a2[k & 1] = fmaf(gl, gl, a2[k & 1]);
-            a3[k & 1] = fmaf(gw, gw, a3[k & 1]);
-            a4[k & 1] = fmaf(gl, gw, a4[k & 1]);
+            fuse_token(e[j * EPV + k], fr, gl, gw);                // padding has e = 0: gl = gw = 0
+            const double dl = (double)gl, dw = (double)gw;
+            a0[k & 1] += dl;
+            a1[k & 1] += dw;
+            a2[k & 1] = fma(dl, dl, a2[k & 1]);
+            a3[k & 1] = fma(dw, dw, a3[k & 1]);
+            a4[k & 1] = fma(dl, dw, a4[k & 1]);
         }
         __builtin_amdgcn_sched_barrier(0);                         // one vector at a time: bounded working set
     }
-    q5[0] = (double)a0[0] + (double)a0[1];
-    q5[1] = (double)a1[0] + (double)a1[1];
-    q5[2] = (double)a2[0] + (double)a2[1];
-    q5[3] = (double)a3[0] + (double)a3[1];
-    q5[4] = (double)a4[0] + (double)a4[1];
+    q5[0] = a0[0] + a0[1];
+    q5[1] = a1[0] + a1[1];
+    q5[2] = a2[0] + a2[1];
+    q5[3] = a3[0] + a3[1];
+    q5[4] = a4[0] + a4[1];
 }
 
 template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V>
@@ -354,8 +349,7 @@ void row_kernel(const RowArgs A)
     block_max2<NW>(mc, mt, smem, lane, wave);
 
     // ---- B: exponentials and partition sums -----------------------------------------------------
-    const float nmc2 = (float)(-(double)mc * kLog2e);
-    const float nmt2 = (float)(-(double)mt * kLog2e);
+    const double mcd = (double)mc, mtd = (double)mt;
     double sz[2] = {0.0, 0.0};
     if constexpr (DO_V) {
         float zacc[4] = {0.f, 0.f, 0.f, 0.f};
@@ -364,23 +358,26 @@ void row_kernel(const RowArgs A)
             float tv[EPV];
             E::unpack(traw[j], tv);
 #pragma unroll
-            for (int k = 0; k < EPV; ++k) zacc[k & 3] += exp_shifted(tv[k], nmt2);
+            for (int k = 0; k < EPV; ++k) zacc[k & 3] += exp_shifted(tv[k], mt);
             __builtin_amdgcn_sched_barrier(0);
         }
         sz[1] = (double)((zacc[0] + zacc[1]) + (zacc[2] + zacc[3]));
     }
     {
-        float sacc[4] = {0.f, 0.f, 0.f, 0.f};
+        // S is accumulated in fp64 from the first add: on a nearly one-hot row the bounds of the top
+        // token react to a relative error in S about five times over, and adding small terms to an
+        // fp32 partial sum that already holds 1.0 would cost 1e-7.
+        double sacc[2] = {0.0, 0.0};
 #pragma unroll
         for (int j = 0; j < NVEC; ++j) {
 #pragma unroll
             for (int k = 0; k < EPV; ++k) {
-                e[j * EPV + k] = exp_shifted(e[j * EPV + k], nmc2);
-                sacc[k & 3] += e[j * EPV + k];
+                e[j * EPV + k] = exp_shifted(e[j * EPV + k], mc);
+                sacc[k & 1] += (double)e[j * EPV + k];
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        sz[0] = (double)((sacc[0] + sacc[1]) + (sacc[2] + sacc[3]));
+        sz[0] = sacc[0] + sacc[1];
     }
     block_sum<NW, 2>(sz, smem, lane, wave);
     const double S = sz[0], Z = sz[1];
@@ -389,8 +386,8 @@ void row_kernel(const RowArgs A)
     // Done before the interval pass so that the verifier row's registers are free during that pass.
     if constexpr (DO_V) {
         if (tid == 0) {
-            const double lp = ((double)cx - (double)mc) - log(S);
-            const double lq = ((double)tx - (double)mt) - log(Z);
+            const double lp = ((double)cx - mcd) - log(S);
+            const double lq = ((double)tx - mtd) - log(Z);
             const double ell = lq - lp;
             const double lnu = log((double)ua);                    // log(0) = -inf: always accepted
             const int rej = !(lnu < fmin(0.0, ell));
@@ -412,7 +409,7 @@ void row_kernel(const RowArgs A)
                 float s = 0.f;
 #pragma unroll
                 for (int k = 0; k < EPV; ++k) {
-                    const double q = (double)exp_shifted(tv[k], nmt2) * invZ;
+                    const double q = (double)exp_shifted(tv[k], mt) * invZ;
                     const double p = (double)e[j * EPV + k] * invS;
                     s += (float)fmax(q - p, 0.0);
                 }
@@ -454,7 +451,7 @@ void row_kernel(const RowArgs A)
                         E::unpack(traw[j], tv);
 #pragma unroll
                         for (int k = 0; k < EPV; ++k) {
-                            const double q = (double)exp_shifted(tv[k], nmt2) * invZ;
+                            const double q = (double)exp_shifted(tv[k], mt) * invZ;
                             const double p = (double)e[j * EPV + k] * invS;
                             r[k] = (float)fmax(q - p, 0.0);
                         }
@@ -514,20 +511,20 @@ void row_kernel(const RowArgs A)
 
     // ---- C + D2: InterFuse sums, score, flag and the drafted token's interval ------------------------
     if constexpr (DO_Q) {
-        const FuseRow fr = fuse_row(S, A.a, A.b, V);
+        const FuseRow fr = fuse_row(S, A.a, A.b);
         double q5[5];
-        if (partial) fuse_sums<THREADS, NVEC, EPV, true>(e, fr, tid, V, q5);
-        else         fuse_sums<THREADS, NVEC, EPV, false>(e, fr, tid, V, q5);
+        if (partial) fuse_sums<THREADS, NVEC, EPV, true>(e, fr, V, q5);
+        else         fuse_sums<THREADS, NVEC, EPV, false>(e, fr, V, q5);
         block_sum<NW, 5>(q5, smem, lane, wave);
         if (tid == 0) {
-            const RowScore rs = finish_score(q5, fr, S, A);
+            const RowScore rs = finish_score(q5, S, A);
             if (A.omega) A.omega[row] = (float)rs.omega;
             if (A.sigma) A.sigma[row] = (float)rs.sigma;
             if (A.score) A.score[row] = (float)rs.score;
             if (A.flags) A.flags[row] = (uint8_t)(rs.score > A.tau);
             if (A.p_lo || A.p_mid || A.p_hi) {
                 // the reported token: the drafted one, or the arg-max (e = 1) when no ids are given
-                const double ex = (xid >= 0) ? exp((double)cx - (double)mc) : 1.0;
+                const double ex = exp((double)(xid >= 0 ? cx : mc) - mcd);
                 const double x = ex / S;
                 if (A.p_mid) A.p_mid[row] = (float)x;
                 if (A.p_lo) A.p_lo[row] = (float)(rs.alpha_l * A.b * x / (1.0 + (A.b - 1.0) * x));
@@ -578,37 +575,36 @@ __global__ __launch_bounds__(256) void dense_kernel(const RowArgs A, float* __re
     float m = -INFINITY, unused = -INFINITY;
     for (int i = tid; i < V; i += 256) m = fmaxf(m, load_elt(c, i));
     block_max2<NW>(m, unused, smem, lane, wave);
-    const float nm2 = (float)(-(double)m * kLog2e);
 
     double s1[1] = {0.0};
     {
-        float acc = 0.f;
-        for (int i = tid; i < V; i += 256) acc += exp_shifted(load_elt(c, i), nm2);
-        s1[0] = (double)acc;
+        double acc = 0.0;
+        for (int i = tid; i < V; i += 256) acc += (double)exp_shifted(load_elt(c, i), m);
+        s1[0] = acc;
     }
     block_sum<NW, 1>(s1, smem, lane, wave);
     const double S = s1[0];
 
-    const FuseRow fr = fuse_row(S, A.a, A.b, V);
+    const FuseRow fr = fuse_row(S, A.a, A.b);
     double q5[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
     {
-        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f, a4 = 0.f;
+        double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0, a4 = 0.0;
         for (int i = tid; i < V; i += 256) {
             float gl, gw;
-            fuse_token(exp_shifted(load_elt(c, i), nm2), fr, gl, gw);
-            gl -= fr.kl; gw -= fr.kw;
-            a0 += gl; a1 += gw;
-            a2 = fmaf(gl, gl, a2); a3 = fmaf(gw, gw, a3); a4 = fmaf(gl, gw, a4);
+            fuse_token(exp_shifted(load_elt(c, i), m), fr, gl, gw);
+            const double dl = (double)gl, dw = (double)gw;
+            a0 += dl; a1 += dw;
+            a2 = fma(dl, dl, a2); a3 = fma(dw, dw, a3); a4 = fma(dl, dw, a4);
         }
         q5[0] = a0; q5[1] = a1; q5[2] = a2; q5[3] = a3; q5[4] = a4;
     }
     block_sum<NW, 5>(q5, smem, lane, wave);
-    const RowScore rs = finish_score(q5, fr, S, A);
+    const RowScore rs = finish_score(q5, S, A);
 
     const float Bc = (float)(A.b / S), Wc = (float)((A.a - A.b) / S), invS = (float)(1.0 / S);
     const float al = (float)rs.alpha_l, au = (float)rs.alpha_u;
     for (int i = tid; i < V; i += 256) {
-        const float e = exp_shifted(load_elt(c, i), nm2);
+        const float e = exp_shifted(load_elt(c, i), m);
         float gl, gw;
         fuse_token(e, fr, gl, gw);
         const float pl = Bc * gl;
