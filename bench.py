@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the CIAR quantify+verify hot path on one MI355X.
+
+A *step* is one pass of the whole hot path over one batch of synthetic logits already resident
+in HBM: the fused row kernel (softmax statistics, InterFuse interval, U = Omega * Sigma, flag,
+accept test, residual resample) followed by the window epilogue.  The workload is the
+"256x256-class batch" (8 images x 16x16 = 2048 positions, V = 16384, fp32, K = 8), the
+configuration the headline metric is quoted on.  Eight distinct copies of the inputs are rotated
+so that the 256 MB last-level cache cannot serve a step's 268 MB of logits from the previous one.
+
+Prints ONE JSON line (see the keys below).  `roofline.achieved` is the row kernel's algorithmic
+bytes per launch over its mean duration, taken with events on the launch stream inside the timed
+region; `cpu_baseline` is the fp64 oracle timed on the host cores on the same batch.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+ROW_OUTPUT_BYTES = 34          # 6 floats, 2 bytes, 1 int32, + 8/K window bytes (K = 8: 1) per position
+ROW_SCALAR_INPUT_BYTES = 12    # drafted id + two uniforms
+
+
+def algorithmic_bytes_per_position(vocab: int, elt: int) -> int:
+    """What the method has to move per position: both logit rows once, the row's scalars in, the
+    per-row results out.  Nothing V-wide is written."""
+    return 2 * vocab * elt + ROW_SCALAR_INPUT_BYTES + ROW_OUTPUT_BYTES
+
+
+def measured_traffic(workload_name: str):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"row_kernel_{workload_name}_pmc.md")
+    try:
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=2, help="1..5 (default 2: the headline configuration)")
+    ap.add_argument("--copies", type=int, default=8, help="distinct input copies rotated through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain device copy of known size (reference for hardware counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (rows are independent; nothing is sharded). "
+              "Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2603_25463_amd as ciar
+    from paper_2603_25463_amd import workloads as wl
+
+    ciar.lib()                                   # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    spec = wl.SPECS[args.workload]
+    w = wl.make(args.workload, device=dev)
+    N, V, K = w.rows, spec.vocab, spec.window
+    elt = w.draft.element_size()
+    copies = max(1, args.copies)
+    drafts = [w.draft] + [w.draft.clone() for _ in range(copies - 1)]
+    targets = [w.target] + [w.target.clone() for _ in range(copies - 1)]
+    P = ciar.Params(confidence=0.9, tau=0.30, window=K)
+    W = (N + K - 1) // K
+    out = {k: torch.empty(N, dtype=torch.float32, device=dev)
+           for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score")}
+    out["flags"] = torch.empty(N, dtype=torch.uint8, device=dev)
+    out["accept"] = torch.empty(N, dtype=torch.uint8, device=dev)
+    out["row_id"] = torch.empty(N, dtype=torch.int32, device=dev)
+    wout = {"accept_len": torch.empty(W, dtype=torch.int32, device=dev),
+            "resampled_id": torch.empty(W, dtype=torch.int32, device=dev)}
+
+    import ctypes
+    from paper_2603_25463_amd.binding import _ptr, _stream, _check
+    L = ciar.lib()
+    cp = P.to_c(w.draft)
+    stream = torch.cuda.current_stream()
+    sp = _stream(stream)
+
+    def step(i: int, ev0=None, ev1=None):
+        """One pass of the hot path: row kernel, then the window epilogue (two launches, one stream)."""
+        d, t = drafts[i % copies], targets[i % copies]
+        if ev0 is not None:
+            ev0.record(stream)
+        _check(L.ciar_quantify_verify(
+            _ptr(d), _ptr(t), _ptr(w.ids), _ptr(w.u_accept), _ptr(w.u_resample), N, ctypes.byref(cp),
+            _ptr(out["p_lo"]), _ptr(out["p_mid"]), _ptr(out["p_hi"]), _ptr(out["omega"]), _ptr(out["sigma"]),
+            _ptr(out["score"]), _ptr(out["flags"]), _ptr(out["accept"]), _ptr(out["row_id"]),
+            None, None, None, 0, sp))
+        if ev1 is not None:
+            ev1.record(stream)
+        _check(L.ciar_window_epilogue(_ptr(out["accept"]), _ptr(out["row_id"]), N, ctypes.byref(cp),
+                                      _ptr(wout["accept_len"]), _ptr(wout["resampled_id"]), sp))
+
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, ev0[i], ev1[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    total_s = t1 - t0
+    ms_per_step = 1e3 * total_s / args.steps
+    kern_ms = sorted(a.elapsed_time(b) for a, b in zip(ev0, ev1))
+    kern_avg_ms = sum(kern_ms) / len(kern_ms)
+    bytes_per_launch = N * algorithmic_bytes_per_position(V, elt)
+    achieved = bytes_per_launch / (kern_avg_ms * 1e-3) / 1e9
+
+    result = {
+        "metric": "token positions/sec (quantify+verify, V=16384 fp32)" if args.workload == 2
+                  else f"token positions/sec (quantify+verify, V={V} {'fp32' if elt == 4 else 'bf16'})",
+        "value": N * args.steps / total_s,
+        "unit": "positions/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"cfg{args.workload} {spec.name}: {spec.images} images x {spec.grid}x{spec.grid} = "
+                               f"{N} positions, V={V}, {'fp32' if elt == 4 else 'bf16'} logits, window K={K}, "
+                               f"confidence 0.9, tau 0.30",
+                   "input_copies_rotated": copies, "launches_per_step": 2},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(spec.name),
+                     "kernel": "row_kernel (fused quantify+verify)", "kernel_avg_us": 1e3 * kern_avg_ms,
+                     "kernel_median_us": 1e3 * kern_ms[len(kern_ms) // 2], "kernel_min_us": 1e3 * kern_ms[0],
+                     "algorithmic_bytes_per_launch": bytes_per_launch},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        h = wl.to_host(w)
+        OP = oracle.Params(confidence=0.9, tau=0.30, window=K)
+        threads = oracle.default_threads()
+        ids, ua, ur = h.ids.numpy(), h.u_accept.numpy(), h.u_resample.numpy()
+        rows = min(N, 2048)
+        hd, ht = h.draft[:rows].contiguous(), h.target[:rows].contiguous()
+        done, c0 = 0, time.perf_counter()
+        while True:
+            oracle.quantify(hd, ids[:rows], OP, threads=threads)
+            oracle.verify(hd, ht, ids[:rows], ua[:rows], ur[:rows], OP, threads=threads)
+            done += rows
+            dt = time.perf_counter() - c0
+            if dt > 10.0:
+                break
+        result["cpu_baseline"] = {"value": done / dt, "unit": "positions/s", "cores": threads, "kind": "oracle",
+                                  "sample": f"the first {rows} positions of the same batch, quantify + verify, "
+                                            f"repeated for {dt:.1f} s ({done} positions)"}
+
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

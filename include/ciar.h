@@ -153,6 +153,19 @@ int ciar_quantify_verify(const void* draft_logits, const void* target_logits,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Window epilogue on its own (the last step of ciar_verify / ciar_quantify_verify, which run it when
+ * a window output is requested): from the per-row results of N rows,
+ *   accept_len[w]   = number of leading rows with accept != 0 in window w = rows [wK, min((w+1)K, N))
+ *   resampled_id[w] = row_resample_id of the first row with accept == 0 in the window, -1 if none
+ * (Algorithm 1: the verified prefix of a drafted window and the token that replaces the first
+ * rejected one).  accept [N] uint8 and row_resample_id [N] int32 are inputs; either output may be
+ * NULL, not both; row_resample_id may be NULL when resampled_id is.  Only params->window is read.
+ */
+int ciar_window_epilogue(const uint8_t* accept, const int32_t* row_resample_id, int64_t N,
+                         const ciar_params* params, int32_t* accept_len, int32_t* resampled_id,
+                         void* hip_stream);
+
+/*
  * Test / debugging export of the dense curves: p_lo, p_mid, p_hi as [N, V] float32 each, densely
  * packed (row stride V), computed with the same per-token arithmetic as ciar_quantify.  Writes
  * 3*N*V floats; not part of the hot path.  Any of the three may be NULL.

@@ -4,7 +4,7 @@
 ``workloads`` generates the seeded synthetic inputs; ``build`` compiles ``libciar.so`` for gfx950.
 """
 from .binding import (CiarError, Params, dense_intervals, last_error, lib, quantify, quantify_verify,
-                      verify, version, workspace_bytes)
+                      verify, version, window_epilogue, workspace_bytes)
 
 __all__ = ["CiarError", "Params", "dense_intervals", "last_error", "lib", "quantify",
-           "quantify_verify", "verify", "version", "workspace_bytes"]
+           "quantify_verify", "verify", "version", "window_epilogue", "workspace_bytes"]

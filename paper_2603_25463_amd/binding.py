@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.ciar_verify.argtypes = [vp, vp, vp, vp, vp, i64, pp] + [vp] * 4 + [vp, sz, vp]
         L.ciar_quantify_verify.restype = ctypes.c_int
         L.ciar_quantify_verify.argtypes = [vp, vp, vp, vp, vp, i64, pp] + [vp] * 11 + [vp, sz, vp]
+        L.ciar_window_epilogue.restype = ctypes.c_int
+        L.ciar_window_epilogue.argtypes = [vp, vp, i64, pp, vp, vp, vp]
         L.ciar_dense_intervals.restype = ctypes.c_int
         L.ciar_dense_intervals.argtypes = [vp, i64, pp, vp, vp, vp, vp]
         L.ciar_last_error.restype = ctypes.c_char_p
@@ -198,6 +200,23 @@ def quantify_verify(draft, target, ids, u_accept, u_resample, params: Params, vo
         _ptr(o["p_lo"]), _ptr(o["p_mid"]), _ptr(o["p_hi"]), _ptr(o["omega"]), _ptr(o["sigma"]),
         _ptr(o["score"]), _ptr(o["flags"]), _ptr(o["accept"]), _ptr(o["row_id"]), _ptr(o["accept_len"]),
         _ptr(o["resampled_id"]), _ptr(workspace), wsb, _stream(stream)))
+    return o
+
+
+def window_epilogue(accept: torch.Tensor, row_id: torch.Tensor, params: Params, stream=None,
+                    out: dict | None = None) -> dict:
+    """``ciar_window_epilogue``: accept_len / resampled_id int32 [W] from per-row accept / row_id."""
+    _need_cuda(accept, row_id)
+    N, K = accept.shape[0], int(params.window)
+    cp = CiarParams()
+    lib().ciar_params_default(ctypes.byref(cp))
+    cp.window = K
+    W = (N + K - 1) // K
+    o = dict(out) if out else {}
+    o.setdefault("accept_len", torch.empty(W, dtype=torch.int32, device=accept.device))
+    o.setdefault("resampled_id", torch.empty(W, dtype=torch.int32, device=accept.device))
+    _check(lib().ciar_window_epilogue(_ptr(accept), _ptr(row_id), N, ctypes.byref(cp), _ptr(o["accept_len"]),
+                                      _ptr(o["resampled_id"]), _stream(stream)))
     return o
 
 

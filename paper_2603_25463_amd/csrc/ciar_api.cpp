@@ -253,6 +253,27 @@ int ciar_quantify_verify(const void* draft_logits, const void* target_logits, co
                       workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
+int ciar_window_epilogue(const uint8_t* accept, const int32_t* row_resample_id, int64_t N,
+                         const ciar_params* params, int32_t* accept_len, int32_t* resampled_id,
+                         void* hip_stream)
+{
+    if (!params) return fail(CIAR_EINVAL, "params is NULL");
+    if (params->struct_size != sizeof(ciar_params))
+        return fail(CIAR_EINVAL, "params->struct_size is %u, expected %zu", params->struct_size,
+                    sizeof(ciar_params));
+    if (params->window < 1) return fail(CIAR_EINVAL, "params->window must be >= 1 (got %d)", params->window);
+    if (N < 0) return fail(CIAR_EINVAL, "N is negative");
+    if (!accept) return fail(CIAR_EINVAL, "accept is NULL");
+    if (!accept_len && !resampled_id) return fail(CIAR_EINVAL, "every output pointer is NULL");
+    if (resampled_id && !row_resample_id)
+        return fail(CIAR_EINVAL, "row_resample_id is NULL but resampled_id is requested");
+    if (N == 0) return CIAR_OK;
+    hipError_t e = ciar::launch_windows(accept, row_resample_id, N, params->window, accept_len, resampled_id,
+                                        static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail(e, "window kernel launch");
+    return CIAR_OK;
+}
+
 int ciar_dense_intervals(const void* draft_logits, int64_t N, const ciar_params* params, float* p_lo,
                          float* p_mid, float* p_hi, void* hip_stream)
 {

@@ -97,30 +97,94 @@ template <> struct Elt<bf16_t> {
 };
 
 // ---- wave and workgroup reductions (fixed order: deterministic) ----------------------------
+//
+// Wave-level reductions use DPP row shifts and row broadcasts: they run on the vector ALU at full
+// rate, whereas a shuffle (ds_bpermute) goes through the LDS crossbar and costs ~5x more per step.
+// Pattern (wave64 = 4 rows of 16 lanes): row_shr 1, 2, 4, 8 leave each row's total in its lane 15;
+// row_bcast:15 adds it into the next row (rows 1 and 3), row_bcast:31 adds lane 31 into rows 2
+// and 3; lane 63 then holds the wave total, which readlane hands to every lane.
+
+constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118;
+constexpr int kRowBcast15 = 0x142, kRowBcast31 = 0x143;
+
+// value of the lane selected by CTRL, or `fill` where the selection is out of range / masked off
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_or(int fill, int v)
+{
+    return __builtin_amdgcn_update_dpp(fill, v, CTRL, ROW_MASK, 0xf, false);
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_add(double v)
+{
+    const int lo = dpp_or<CTRL, ROW_MASK>(0, __double2loint(v));
+    const int hi = dpp_or<CTRL, ROW_MASK>(0, __double2hiint(v));
+    return v + __hiloint2double(hi, lo);           // lanes without a source add +0.0
+}
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+    v = dpp_add<kRowShr1, 0xf>(v);
+    v = dpp_add<kRowShr2, 0xf>(v);
+    v = dpp_add<kRowShr4, 0xf>(v);
+    v = dpp_add<kRowShr8, 0xf>(v);
+    v = dpp_add<kRowBcast15, 0xa>(v);
+    v = dpp_add<kRowBcast31, 0xc>(v);
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
+    return __hiloint2double(hi, lo);
+}
+
+// inclusive prefix sum over the 64 lanes (same steps, without the final broadcast)
+__device__ __forceinline__ double wave_scan(double v)
+{
+    v = dpp_add<kRowShr1, 0xf>(v);
+    v = dpp_add<kRowShr2, 0xf>(v);
+    v = dpp_add<kRowShr4, 0xf>(v);
+    v = dpp_add<kRowShr8, 0xf>(v);
+    v = dpp_add<kRowBcast15, 0xa>(v);
+    v = dpp_add<kRowBcast31, 0xc>(v);
+    return v;
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_max(float v)
+{
+    // lanes without a source get their own value back: max(v, v) = v
+    return fmaxf(v, __int_as_float(dpp_or<CTRL, ROW_MASK>(__float_as_int(v), __float_as_int(v))));
+}
 
 __device__ __forceinline__ float wave_max(float v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-    return v;
+    v = dpp_max<kRowShr1, 0xf>(v);
+    v = dpp_max<kRowShr2, 0xf>(v);
+    v = dpp_max<kRowShr4, 0xf>(v);
+    v = dpp_max<kRowShr8, 0xf>(v);
+    v = dpp_max<kRowBcast15, 0xa>(v);
+    v = dpp_max<kRowBcast31, 0xc>(v);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
-__device__ __forceinline__ double wave_sum(double v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
+
 __device__ __forceinline__ int wave_min_i(int v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o));
-    return v;
+    v = min(v, dpp_or<kRowShr1, 0xf>(v, v));
+    v = min(v, dpp_or<kRowShr2, 0xf>(v, v));
+    v = min(v, dpp_or<kRowShr4, 0xf>(v, v));
+    v = min(v, dpp_or<kRowShr8, 0xf>(v, v));
+    v = min(v, dpp_or<kRowBcast15, 0xa>(v, v));
+    v = min(v, dpp_or<kRowBcast31, 0xc>(v, v));
+    return __builtin_amdgcn_readlane(v, 63);
 }
+
 __device__ __forceinline__ int wave_max_i(int v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o));
-    return v;
+    v = max(v, dpp_or<kRowShr1, 0xf>(v, v));
+    v = max(v, dpp_or<kRowShr2, 0xf>(v, v));
+    v = max(v, dpp_or<kRowShr4, 0xf>(v, v));
+    v = max(v, dpp_or<kRowShr8, 0xf>(v, v));
+    v = max(v, dpp_or<kRowBcast15, 0xa>(v, v));
+    v = max(v, dpp_or<kRowBcast31, 0xc>(v, v));
+    return __builtin_amdgcn_readlane(v, 63);
 }
 
 // All threads end up with the workgroup-wide sums of v[0..NV).  smem: NW*NV doubles.
@@ -145,18 +209,17 @@ __device__ __forceinline__ void block_sum(double (&v)[NV], double* smem, int lan
 }
 
 template <int NW>
-__device__ __forceinline__ void block_max2(float& m0, float& m1, double* smem, int lane, int wave)
+__device__ __forceinline__ float block_max(float m, double* smem, int lane, int wave)
 {
-    m0 = wave_max(m0);
-    m1 = wave_max(m1);
+    m = wave_max(m);
     float* f = reinterpret_cast<float*>(smem);
     __syncthreads();
-    if (lane == 0) { f[wave * 2] = m0; f[wave * 2 + 1] = m1; }
+    if (lane == 0) f[wave] = m;
     __syncthreads();
-    float r0 = f[0], r1 = f[1];
+    float r = f[0];
 #pragma unroll
-    for (int w = 1; w < NW; ++w) { r0 = fmaxf(r0, f[w * 2]); r1 = fmaxf(r1, f[w * 2 + 1]); }
-    m0 = r0; m1 = r1;
+    for (int w = 1; w < NW; ++w) r = fmaxf(r, f[w]);
+    return r;
 }
 
 // ---- per-token InterFuse arithmetic, shared by the row kernel and the dense export ----------
@@ -218,19 +281,22 @@ __device__ __forceinline__ RowScore finish_score(const double (&s)[5], double S,
     return o;
 }
 
-// Waves per SIMD the register allocation aims for: the rows held in registers (EPT floats for c,
-// EPT more for t in full precision, half that for packed bf16) plus ~40 working registers.
-template <typename T, int THREADS, int NVEC, bool DO_V>
+// Waves per SIMD the register allocation aims for.  One row at a time is resident (the verifier row
+// is consumed before the centre row is fetched into the same registers): EPT floats plus ~50 working
+// registers, capped at 4 waves (more buys nothing for a kernel that streams 64 KiB per workgroup).
+template <typename T, int THREADS, int NVEC>
 constexpr int target_waves()
 {
-    constexpr int ept = NVEC * Elt<T>::kPerVec;
-    constexpr int regs = ept + (DO_V ? ept * (int)sizeof(T) / 4 : 0) + 40;
+#ifdef XP_WAVES
+    return XP_WAVES < THREADS / 256 ? THREADS / 256 : XP_WAVES;
+#endif
+    constexpr int regs = NVEC * Elt<T>::kPerVec + 56;
     constexpr int fit = 512 / regs;
     constexpr int lo = THREADS / 256;                 // waves per SIMD one workgroup needs
     return fit < lo ? lo : (fit > 4 ? 4 : fit);
 }
 
-// Pass C for one lane: the five centred InterFuse sums over the lane's tokens.
+// Pass C for one lane: the five InterFuse sums over the lane's tokens.
 // MASKED = the row does not fill the tile: chunks past the end are skipped (padding inside the last
 // chunk has e = 0 and adds exactly nothing).
 template <int THREADS, int NVEC, int EPV, bool MASKED>
@@ -264,9 +330,16 @@ __device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const Fu
     q5[4] = a4[0] + a4[1];
 }
 
+template <typename T>
+__device__ __forceinline__ float load_logit(const T* row, int i)
+{
+    if constexpr (sizeof(T) == 4) return reinterpret_cast<const float*>(row)[i];
+    else return bits_f((uint32_t)reinterpret_cast<const uint16_t*>(row)[i] << 16);
+}
+
 template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V>
 __global__ __launch_bounds__(THREADS)
-__attribute__((amdgpu_waves_per_eu(target_waves<T, THREADS, NVEC, DO_V>())))
+__attribute__((amdgpu_waves_per_eu(target_waves<T, THREADS, NVEC>())))
 void row_kernel(const RowArgs A)
 {
     using E = Elt<T>;
@@ -274,6 +347,7 @@ void row_kernel(const RowArgs A)
     constexpr int EPT = NVEC * EPV;
     constexpr int NW = THREADS / 64;
     constexpr int CHUNK = THREADS * EPV;            // tokens covered by one load instruction of the workgroup
+    constexpr int EB = NVEC > 8 ? 8 : NVEC;         // vectors of each row in flight per lane in the residual pass
 
     __shared__ double smem[NW * (NVEC > 5 ? NVEC : 5) + NW];
     __shared__ int    smem_i[NW * 2 + 2];
@@ -281,88 +355,88 @@ void row_kernel(const RowArgs A)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t row = blockIdx.x;
     const int V = A.V;
+    const bool partial = V != NVEC * CHUNK;                        // uniform: the row does not fill the tile
+    const int last_vec = (V + EPV - 1) / EPV - 1;
 
     // Rows live in global memory (address space 1): say so, or the loads are emitted as flat ones.
-    using gvec = const __attribute__((address_space(1))) u32x4*;
-    gvec cvec = (gvec)(static_cast<const T*>(A.draft) + row * A.stride);
-    gvec tvec = DO_V ? (gvec)(static_cast<const T*>(A.target) + row * A.stride) : nullptr;
-
-    // ---- loads: everything is issued before the first use --------------------------------------
     // Vector indices past the end of the row are clamped to its last vector, so every lane loads
     // valid memory unconditionally; tokens that do not exist are set to -inf afterwards.
-    const int last_vec = (V + EPV - 1) / EPV - 1;
-    u32x4 traw[DO_V ? NVEC : 1];
-    u32x4 craw[NVEC];
-    if constexpr (DO_V) {
-#pragma unroll
-        for (int j = 0; j < NVEC; ++j) traw[j] = tvec[min(j * THREADS + tid, last_vec)];
-    }
-#pragma unroll
-    for (int j = 0; j < NVEC; ++j) craw[j] = cvec[min(j * THREADS + tid, last_vec)];
+    using gbytes = const __attribute__((address_space(1))) char*;
+    using gvec = const __attribute__((address_space(1))) u32x4*;
+    const T* crow = static_cast<const T*>(A.draft) + row * A.stride;
+    const T* trow = DO_V ? static_cast<const T*>(A.target) + row * A.stride : nullptr;
+    // vector j of this lane: uniform row base + 32-bit byte offset (one VGPR per address)
+    auto load_vec_at = [&](const T* base, int j, int t) -> u32x4 {
+        const uint32_t off = (uint32_t)min(j * THREADS + t, last_vec) * 16u;
+        return *(gvec)((gbytes)base + off);
+    };
+    auto load_vec = [&](const T* base, int j) -> u32x4 { return load_vec_at(base, j, tid); };
 
-    // lane 0 fetches the row's scalars and the two logits of the drafted token
+    u32x4 raw[NVEC];                                               // landing registers: t first, then c
+
+    // ---- T: verifier row statistics (max, Z); the row is not kept ---------------------------------
     int xid = -1;
     float cx = 0.f, tx = 0.f, ua = 0.f, ur = 0.f;
-    if (tid == 0) {
+    float mt = -INFINITY;
+    double sz[2] = {0.0, 0.0};                                     // lane partials of S and Z
+    if constexpr (DO_V) {
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) raw[j] = load_vec(trow, j);
+    }
+    if (tid == 0) {                                                // the row's scalars and the drafted token's logits
         if (A.ids) {
             xid = A.ids[row];
             xid = xid < 0 ? 0 : (xid >= V ? V - 1 : xid);
-            const T* cr = static_cast<const T*>(A.draft) + row * A.stride;
-            if constexpr (sizeof(T) == 4) cx = reinterpret_cast<const float*>(cr)[xid];
-            else cx = bits_f((uint32_t)reinterpret_cast<const uint16_t*>(cr)[xid] << 16);
+            cx = load_logit(crow, xid);
         }
         if constexpr (DO_V) {
-            const T* tr = static_cast<const T*>(A.target) + row * A.stride;
-            if constexpr (sizeof(T) == 4) tx = reinterpret_cast<const float*>(tr)[xid];
-            else tx = bits_f((uint32_t)reinterpret_cast<const uint16_t*>(tr)[xid] << 16);
+            tx = load_logit(trow, xid);
             ua = A.u_accept[row];
             ur = A.u_resample[row];
         }
     }
-    const bool partial = V != NVEC * CHUNK;                        // uniform: the row does not fill the tile
-    if (partial) {
-#pragma unroll
-        for (int j = 0; j < NVEC; ++j) {
-            const int base = (j * THREADS + tid) * EPV;
-            E::mask_tail(craw[j], base, V);
-            if constexpr (DO_V) E::mask_tail(traw[j], base, V);
-        }
-    }
-
-    // ---- A: row maxima --------------------------------------------------------------------------
-    float mt = -INFINITY;
     if constexpr (DO_V) {
+        if (partial) {
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) E::mask_tail(raw[j], (j * THREADS + tid) * EPV, V);
+        }
 #pragma unroll
         for (int j = 0; j < NVEC; ++j) {
             float tv[EPV];
-            E::unpack(traw[j], tv);
+            E::unpack(raw[j], tv);
 #pragma unroll
             for (int k = 0; k < EPV; ++k) mt = fmaxf(mt, tv[k]);
         }
-    }
-    float e[EPT];
-#pragma unroll
-    for (int j = 0; j < NVEC; ++j) E::unpack(craw[j], &e[j * EPV]);
-    float mc = e[0];
-#pragma unroll
-    for (int i = 1; i < EPT; ++i) mc = fmaxf(mc, e[i]);
-    block_max2<NW>(mc, mt, smem, lane, wave);
-
-    // ---- B: exponentials and partition sums -----------------------------------------------------
-    const double mcd = (double)mc, mtd = (double)mt;
-    double sz[2] = {0.0, 0.0};
-    if constexpr (DO_V) {
+        mt = block_max<NW>(mt, smem, lane, wave);
         float zacc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int j = 0; j < NVEC; ++j) {
             float tv[EPV];
-            E::unpack(traw[j], tv);
+            E::unpack(raw[j], tv);
 #pragma unroll
             for (int k = 0; k < EPV; ++k) zacc[k & 3] += exp_shifted(tv[k], mt);
             __builtin_amdgcn_sched_barrier(0);
         }
         sz[1] = (double)((zacc[0] + zacc[1]) + (zacc[2] + zacc[3]));
+        __builtin_amdgcn_sched_barrier(0);                         // t is dead: its registers take the centre row
     }
+
+    // ---- A + B: centre row: max, e_i = exp(c_i - max), S ----------------------------------------------
+    {
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) raw[j] = load_vec(crow, j);
+        if (partial) {
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) E::mask_tail(raw[j], (j * THREADS + tid) * EPV, V);
+        }
+    }
+    float e[EPT];
+#pragma unroll
+    for (int j = 0; j < NVEC; ++j) E::unpack(raw[j], &e[j * EPV]);
+    float mc = e[0];
+#pragma unroll
+    for (int i = 1; i < EPT; ++i) mc = fmaxf(mc, e[i]);
+    mc = block_max<NW>(mc, smem, lane, wave);
     {
         // S is accumulated in fp64 from the first add: on a nearly one-hot row the bounds of the top
         // token react to a relative error in S about five times over, and adding small terms to an
@@ -375,15 +449,15 @@ void row_kernel(const RowArgs A)
                 e[j * EPV + k] = exp_shifted(e[j * EPV + k], mc);
                 sacc[k & 1] += (double)e[j * EPV + k];
             }
-            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0);                     // keep the working set to one vector at a time
         }
         sz[0] = sacc[0] + sacc[1];
     }
     block_sum<NW, 2>(sz, smem, lane, wave);
     const double S = sz[0], Z = sz[1];
+    const double mcd = (double)mc, mtd = (double)mt;
 
-    // ---- D1 + E: accept test, and the residual draw of a rejected row -----------------------------
-    // Done before the interval pass so that the verifier row's registers are free during that pass.
+    // ---- D1: accept test (one lane, fp64, log domain) ----------------------------------------------------
     if constexpr (DO_V) {
         if (tid == 0) {
             const double lp = ((double)cx - mcd) - log(S);
@@ -393,29 +467,85 @@ void row_kernel(const RowArgs A)
             const int rej = !(lnu < fmin(0.0, ell));
             if (A.accept) A.accept[row] = (uint8_t)(!rej);
             if (!rej && A.row_id) A.row_id[row] = -1;
-            smem_i[NW * 2] = rej;
+            smem_i[NW * 2] = rej;                                  // read by everyone after the next barrier
             smem_i[NW * 2 + 1] = __float_as_int(ur);
         }
+    }
+
+    // ---- C + D2: InterFuse sums, score, flag and the drafted token's interval ------------------------
+    if constexpr (DO_Q) {
+        const FuseRow fr = fuse_row(S, A.a, A.b);
+        double q5[5];
+        if (partial) fuse_sums<THREADS, NVEC, EPV, true>(e, fr, V, q5);
+        else         fuse_sums<THREADS, NVEC, EPV, false>(e, fr, V, q5);
+        block_sum<NW, 5>(q5, smem, lane, wave);
+        if (tid == 0) {
+            const RowScore rs = finish_score(q5, S, A);
+            if (A.omega) A.omega[row] = (float)rs.omega;
+            if (A.sigma) A.sigma[row] = (float)rs.sigma;
+            if (A.score) A.score[row] = (float)rs.score;
+            if (A.flags) A.flags[row] = (uint8_t)(rs.score > A.tau);
+            if (A.p_lo || A.p_mid || A.p_hi) {
+                // the reported token: the drafted one, or the arg-max (e = 1) when no ids are given
+                const double ex = exp((double)(xid >= 0 ? cx : mc) - mcd);
+                const double x = ex / S;
+                if (A.p_mid) A.p_mid[row] = (float)x;
+                if (A.p_lo) A.p_lo[row] = (float)(rs.alpha_l * A.b * x / (1.0 + (A.b - 1.0) * x));
+                if (A.p_hi) A.p_hi[row] = (float)(rs.alpha_u * A.a * x / (1.0 + (A.a - 1.0) * x));
+            }
+        }
+    }
+
+    // ---- E: residual resample of a rejected row (workgroup-uniform branch) -----------------------------
+    // res_i = max(0, q_i - p_i).  Self-contained on purpose: both rows are fetched again (they were just
+    // read, so this comes from cache) and e_i, exp(t_i - max t) are recomputed bit-identically, so that
+    // no register of the main path has to stay alive for a branch only ~1 row in 8 takes.
+    if constexpr (DO_V) {
         __syncthreads();
         const int rejected = smem_i[NW * 2];
-        if (rejected && A.row_id) {                                // workgroup-uniform
+        if (rejected && A.row_id) {
             const double u_res = (double)__int_as_float(smem_i[NW * 2 + 1]);
             const double invS = 1.0 / S, invZ = 1.0 / Z;
-            // E1: workgroup totals of res_i = max(0, q_i - p_i) over each chunk of CHUNK tokens
-#pragma unroll
-            for (int j = 0; j < NVEC; ++j) {
-                float tv[EPV];
-                E::unpack(traw[j], tv);
-                float s = 0.f;
+            // The lane index is laundered through an empty asm so that the addresses of this rare branch
+            // are formed here instead of being kept alive (and spilled) across the whole main path.
+            int tid_e = tid;
+            asm volatile("" : "+v"(tid_e));
+            // residuals of one 16-byte vector of each row
+            auto residuals = [&](u32x4 cr, u32x4 tr, int j, float (&r)[EPV]) {
+                if (partial) {
+                    E::mask_tail(cr, (j * THREADS + tid_e) * EPV, V);
+                    E::mask_tail(tr, (j * THREADS + tid_e) * EPV, V);
+                }
+                float cv[EPV], tv[EPV];
+                E::unpack(cr, cv);
+                E::unpack(tr, tv);
 #pragma unroll
                 for (int k = 0; k < EPV; ++k) {
                     const double q = (double)exp_shifted(tv[k], mt) * invZ;
-                    const double p = (double)e[j * EPV + k] * invS;
-                    s += (float)fmax(q - p, 0.0);
+                    const double p = (double)exp_shifted(cv[k], mc) * invS;
+                    r[k] = (float)fmax(q - p, 0.0);
                 }
-                const double ws = wave_sum((double)s);
-                if (lane == 0) smem[wave * NVEC + j] = ws;
-                __builtin_amdgcn_sched_barrier(0);
+            };
+            // E1: workgroup totals of the residual over each chunk of CHUNK tokens
+#pragma unroll
+            for (int b0 = 0; b0 < NVEC; b0 += EB) {
+                u32x4 cb[EB], tb[EB];
+#pragma unroll
+                for (int jj = 0; jj < EB; ++jj) {
+                    cb[jj] = load_vec_at(crow, b0 + jj, tid_e);
+                    tb[jj] = load_vec_at(trow, b0 + jj, tid_e);
+                }
+#pragma unroll
+                for (int jj = 0; jj < EB; ++jj) {
+                    float r[EPV];
+                    residuals(cb[jj], tb[jj], b0 + jj, r);
+                    float s = 0.f;
+#pragma unroll
+                    for (int k = 0; k < EPV; ++k) s += r[k];
+                    const double ws = wave_sum((double)s);
+                    if (lane == 0) smem[wave * NVEC + b0 + jj] = ws;
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
             __syncthreads();
             double R = 0.0;
@@ -442,30 +572,11 @@ void row_kernel(const RowArgs A)
                 if (jstar < 0) { jstar = jlast; before = run; }    // unreachable for u < 1; keeps the draw valid
                 // E2: the lane's residuals inside that chunk, recomputed exactly as in E1
                 float r[EPV];
-#pragma unroll
-                for (int k = 0; k < EPV; ++k) r[k] = 0.f;
-#pragma unroll
-                for (int j = 0; j < NVEC; ++j) {
-                    if (j == jstar) {                              // uniform
-                        float tv[EPV];
-                        E::unpack(traw[j], tv);
-#pragma unroll
-                        for (int k = 0; k < EPV; ++k) {
-                            const double q = (double)exp_shifted(tv[k], mt) * invZ;
-                            const double p = (double)e[j * EPV + k] * invS;
-                            r[k] = (float)fmax(q - p, 0.0);
-                        }
-                    }
-                }
+                residuals(load_vec_at(crow, jstar, tid_e), load_vec_at(trow, jstar, tid_e), jstar, r);
                 float s = 0.f;
 #pragma unroll
                 for (int k = 0; k < EPV; ++k) s += r[k];
-                double incl = (double)s;
-#pragma unroll
-                for (int o = 1; o < 64; o <<= 1) {
-                    const double n = __shfl_up(incl, o);
-                    if (lane >= o) incl += n;
-                }
+                const double incl = wave_scan((double)s);
                 if (lane == 63) smem[NW * NVEC + wave] = incl;
                 __syncthreads();
                 double cum = before + (incl - (double)s);
@@ -474,7 +585,7 @@ void row_kernel(const RowArgs A)
                     if (w < wave) cum += smem[NW * NVEC + w];
                 // smallest token of the chunk whose inclusive running sum exceeds u * R; tokens without
                 // residual mass cannot be drawn; lastpos covers a crossing lost to rounding at the chunk end
-                const int base = (jstar * THREADS + tid) * EPV;
+                const int base = (jstar * THREADS + tid_e) * EPV;
 #pragma unroll
                 for (int k = 0; k < EPV; ++k) {
                     cum += (double)r[k];
@@ -485,14 +596,9 @@ void row_kernel(const RowArgs A)
                 }
             } else {
                 // every residual rounded to zero (q == p to working precision): the draw degenerates
-                // to the lowest-index arg-max of q; re-read the row, this path is practically never taken
-                const T* tr = static_cast<const T*>(A.target) + row * A.stride;
-                for (int i = tid; i < V; i += THREADS) {
-                    float tvv;
-                    if constexpr (sizeof(T) == 4) tvv = reinterpret_cast<const float*>(tr)[i];
-                    else tvv = bits_f((uint32_t)reinterpret_cast<const uint16_t*>(tr)[i] << 16);
-                    if (tvv == mt) { cand = i; break; }
-                }
+                // to the lowest-index arg-max of q; this path is practically never taken
+                for (int i = tid; i < V; i += THREADS)
+                    if (load_logit(trow, i) == mt) { cand = i; break; }
             }
             cand = wave_min_i(cand);
             lastpos = wave_max_i(lastpos);
@@ -505,30 +611,6 @@ void row_kernel(const RowArgs A)
                 int id = (c0 != INT_MAX) ? c0 : l0;
                 if (id < 0) id = 0;
                 A.row_id[row] = id;
-            }
-        }
-    }
-
-    // ---- C + D2: InterFuse sums, score, flag and the drafted token's interval ------------------------
-    if constexpr (DO_Q) {
-        const FuseRow fr = fuse_row(S, A.a, A.b);
-        double q5[5];
-        if (partial) fuse_sums<THREADS, NVEC, EPV, true>(e, fr, V, q5);
-        else         fuse_sums<THREADS, NVEC, EPV, false>(e, fr, V, q5);
-        block_sum<NW, 5>(q5, smem, lane, wave);
-        if (tid == 0) {
-            const RowScore rs = finish_score(q5, S, A);
-            if (A.omega) A.omega[row] = (float)rs.omega;
-            if (A.sigma) A.sigma[row] = (float)rs.sigma;
-            if (A.score) A.score[row] = (float)rs.score;
-            if (A.flags) A.flags[row] = (uint8_t)(rs.score > A.tau);
-            if (A.p_lo || A.p_mid || A.p_hi) {
-                // the reported token: the drafted one, or the arg-max (e = 1) when no ids are given
-                const double ex = exp((double)(xid >= 0 ? cx : mc) - mcd);
-                const double x = ex / S;
-                if (A.p_mid) A.p_mid[row] = (float)x;
-                if (A.p_lo) A.p_lo[row] = (float)(rs.alpha_l * A.b * x / (1.0 + (A.b - 1.0) * x));
-                if (A.p_hi) A.p_hi[row] = (float)(rs.alpha_u * A.a * x / (1.0 + (A.a - 1.0) * x));
             }
         }
     }
@@ -572,9 +654,9 @@ __global__ __launch_bounds__(256) void dense_kernel(const RowArgs A, float* __re
     const int V = A.V;
     const T* c = static_cast<const T*>(A.draft) + row * A.stride;
 
-    float m = -INFINITY, unused = -INFINITY;
+    float m = -INFINITY;
     for (int i = tid; i < V; i += 256) m = fmaxf(m, load_elt(c, i));
-    block_max2<NW>(m, unused, smem, lane, wave);
+    m = block_max<NW>(m, smem, lane, wave);
 
     double s1[1] = {0.0};
     {
