@@ -96,9 +96,10 @@ def main() -> int:
     cp = P.to_c(w.draft)
     stream = torch.cuda.current_stream()
     sp = _stream(stream)
+    ws = torch.empty(ciar.workspace_bytes(N, cp), dtype=torch.uint8, device=dev)
 
     def step(i: int, ev0=None, ev1=None):
-        """One pass of the hot path: row kernel, then the window epilogue (two launches, one stream)."""
+        """One pass of the hot path: streaming kernel, finishing kernel, window epilogue (one stream)."""
         d, t = drafts[i % copies], targets[i % copies]
         if ev0 is not None:
             ev0.record(stream)
@@ -106,7 +107,7 @@ def main() -> int:
             _ptr(d), _ptr(t), _ptr(w.ids), _ptr(w.u_accept), _ptr(w.u_resample), N, ctypes.byref(cp),
             _ptr(out["p_lo"]), _ptr(out["p_mid"]), _ptr(out["p_hi"]), _ptr(out["omega"]), _ptr(out["sigma"]),
             _ptr(out["score"]), _ptr(out["flags"]), _ptr(out["accept"]), _ptr(out["row_id"]),
-            None, None, None, 0, sp))
+            None, None, _ptr(ws), ws.numel(), sp))
         if ev1 is not None:
             ev1.record(stream)
         _check(L.ciar_window_epilogue(_ptr(out["accept"]), _ptr(out["row_id"]), N, ctypes.byref(cp),

@@ -19,6 +19,11 @@
  *     and is read before the call returns.  The library allocates nothing, frees nothing and
  *     never synchronises: kernels are enqueued on `hip_stream` (a hipStream_t, NULL = the
  *     default stream) and outputs are valid once the caller has synchronised that stream.
+ *   - `workspace` is device scratch of at least ciar_workspace_bytes(N, params) bytes, 16-byte
+ *     aligned, owned by the caller.  It carries the per-row statistics from the streaming kernel
+ *     to the finishing kernel (and per-row results the caller did not ask for).  Its contents need
+ *     no initialisation and are garbage afterwards; calls that overlap in time on one device
+ *     must not share a workspace.
  *   - Logits: row-major [N, row_stride] with V <= row_stride, element type `dtype`
  *     (float32, or bfloat16 widened exactly to float32 on load).  Base pointers and
  *     row_stride * sizeof(element) must be multiples of 16 bytes, and the buffer must be
@@ -87,10 +92,8 @@ typedef struct ciar_params {
 void ciar_params_default(ciar_params* p);
 
 /*
- * Bytes of device workspace ciar_verify / ciar_quantify_verify need for N rows: room for the
- * per-row accept bit and residual sample when the caller does not ask for those outputs.
- * Always a multiple of 256; returns 0 for N <= 0.  The workspace must be 16-byte aligned.
- * Its contents need no initialisation and are garbage afterwards.
+ * Bytes of device workspace ciar_quantify / ciar_verify / ciar_quantify_verify need for N rows
+ * (77 bytes per row, rounded up).  Always a multiple of 256; returns 0 for N <= 0.
  */
 size_t ciar_workspace_bytes(int64_t N, const ciar_params* params);
 
@@ -109,7 +112,7 @@ int ciar_quantify(const void* draft_logits, const int32_t* draft_ids, int64_t N,
                   const ciar_params* params,
                   float* p_lo, float* p_mid, float* p_hi,
                   float* omega, float* sigma, float* score, uint8_t* flags,
-                  void* hip_stream);
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Cloud-side verification of drafted tokens (Algorithm 1, "Cloud verification" and the resample /
@@ -127,9 +130,6 @@ int ciar_quantify(const void* draft_logits, const int32_t* draft_ids, int64_t N,
  *                                    W = ceil(N / K)                            (may be NULL)
  *   resampled_id    [W] int32   out  row_resample_id of the window's first rejected row, -1 if the
  *                                    whole window was accepted                  (may be NULL)
- *   workspace                   device scratch of ciar_workspace_bytes(N, params) bytes; may be NULL
- *                               when accept and row_resample_id are both given or no window output
- *                               is requested.
  * At least one output must be given.
  */
 int ciar_verify(const void* draft_logits, const void* target_logits, const int32_t* draft_ids,

@@ -54,7 +54,7 @@ def lib() -> ctypes.CDLL:
         L.ciar_workspace_bytes.restype = sz
         L.ciar_workspace_bytes.argtypes = [i64, pp]
         L.ciar_quantify.restype = ctypes.c_int
-        L.ciar_quantify.argtypes = [vp, vp, i64, pp] + [vp] * 7 + [vp]
+        L.ciar_quantify.argtypes = [vp, vp, i64, pp] + [vp] * 7 + [vp, sz, vp]
         L.ciar_verify.restype = ctypes.c_int
         L.ciar_verify.argtypes = [vp, vp, vp, vp, vp, i64, pp] + [vp] * 4 + [vp, sz, vp]
         L.ciar_quantify_verify.restype = ctypes.c_int
@@ -139,20 +139,29 @@ def workspace_bytes(N: int, cparams: CiarParams) -> int:
     return int(lib().ciar_workspace_bytes(int(N), ctypes.byref(cparams)))
 
 
+def _workspace(N: int, cp: CiarParams, dev, workspace):
+    """The caller's workspace, or a fresh one of the size the library asks for."""
+    if workspace is None:
+        workspace = torch.empty(max(workspace_bytes(N, cp), 16), dtype=torch.uint8, device=dev)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
 def quantify(draft: torch.Tensor, ids: torch.Tensor | None, params: Params, vocab: int | None = None,
-             stream=None, out: dict | None = None) -> dict:
+             stream=None, out: dict | None = None, workspace: torch.Tensor | None = None) -> dict:
     """``ciar_quantify``.  Returns dict of [N] tensors: p_lo, p_mid, p_hi, omega, sigma, score (float32)
     and flags (uint8).  ``out`` may carry preallocated tensors under the same names."""
     _need_cuda(draft, ids)
     N, dev = draft.shape[0], draft.device
     cp = params.to_c(draft, vocab)
+    workspace, wsb = _workspace(N, cp, dev, workspace)
     o = dict(out) if out else {}
     for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score"):
         o.setdefault(k, torch.empty(N, dtype=torch.float32, device=dev))
     o.setdefault("flags", torch.empty(N, dtype=torch.uint8, device=dev))
     _check(lib().ciar_quantify(_ptr(draft), _ptr(ids), N, ctypes.byref(cp),
                                _ptr(o["p_lo"]), _ptr(o["p_mid"]), _ptr(o["p_hi"]), _ptr(o["omega"]),
-                               _ptr(o["sigma"]), _ptr(o["score"]), _ptr(o["flags"]), _stream(stream)))
+                               _ptr(o["sigma"]), _ptr(o["score"]), _ptr(o["flags"]), _ptr(workspace), wsb,
+                               _stream(stream)))
     return o
 
 
@@ -175,7 +184,7 @@ def verify(draft, target, ids, u_accept, u_resample, params: Params, vocab: int 
     if target.dtype != draft.dtype or target.shape != draft.shape or target.stride() != draft.stride():
         raise ValueError("target must match draft in dtype, shape and strides")
     o = _verify_outputs(N, cp.window, dev, out)
-    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    workspace, wsb = _workspace(N, cp, dev, workspace)
     _check(lib().ciar_verify(_ptr(draft), _ptr(target), _ptr(ids), _ptr(u_accept), _ptr(u_resample), N,
                              ctypes.byref(cp), _ptr(o["accept"]), _ptr(o["row_id"]), _ptr(o["accept_len"]),
                              _ptr(o["resampled_id"]), _ptr(workspace), wsb, _stream(stream)))
@@ -194,7 +203,7 @@ def quantify_verify(draft, target, ids, u_accept, u_resample, params: Params, vo
     for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score"):
         o.setdefault(k, torch.empty(N, dtype=torch.float32, device=dev))
     o.setdefault("flags", torch.empty(N, dtype=torch.uint8, device=dev))
-    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    workspace, wsb = _workspace(N, cp, dev, workspace)
     _check(lib().ciar_quantify_verify(
         _ptr(draft), _ptr(target), _ptr(ids), _ptr(u_accept), _ptr(u_resample), N, ctypes.byref(cp),
         _ptr(o["p_lo"]), _ptr(o["p_mid"]), _ptr(o["p_hi"]), _ptr(o["omega"]), _ptr(o["sigma"]),

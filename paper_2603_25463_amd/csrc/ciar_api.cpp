@@ -110,6 +110,15 @@ ciar::RowArgs base_args(const ciar_params* p, const Resolved& r, int64_t N)
     a.tau = (double)p->tau;
     a.cap_lo = (double)p->lower_cap;
     a.cap_hi = (double)p->upper_cap;
+    // S_l <= b / (1 - (1-b) x_max) <= cap_lo  and  S_u >= a / (1 + (a-1) x_max) >= cap_hi  both hold when
+    // x_max <= min((1 - b/cap_lo) / (1-b), (a/cap_hi - 1) / (a-1)); a hair below, to be safe against rounding.
+    double xm = 0.0;
+    if (r.a > 1.0) {
+        const double x1 = (1.0 - r.b / a.cap_lo) / (1.0 - r.b), x2 = (r.a / a.cap_hi - 1.0) / (r.a - 1.0);
+        xm = 0.999 * (x1 < x2 ? x1 : x2);
+        if (!(xm > 0.0)) xm = 0.0;
+    }
+    a.capless_xmax = xm;
     return a;
 }
 
@@ -118,30 +127,42 @@ int hip_fail(hipError_t e, const char* what)
     return fail(CIAR_EHIP, "%s: %s", what, hipGetErrorString(e));
 }
 
+// Workspace layout: [N] RowStats | [N] int32 row ids | [N] uint8 accept bits.
+size_t stats_bytes(int64_t N) { return round_up((size_t)N * sizeof(ciar::RowStats), 16); }
+size_t ids_bytes(int64_t N) { return round_up((size_t)N * 4, 16); }
+
+int check_workspace(int64_t N, const ciar_params* p, void* workspace, size_t workspace_bytes)
+{
+    if (N == 0) return CIAR_OK;
+    const size_t need = ciar_workspace_bytes(N, p);
+    if (!workspace) return fail(CIAR_EWORKSPACE, "workspace is NULL but %zu bytes are needed", need);
+    if (!aligned16(workspace)) return fail(CIAR_EALIGN, "workspace is not 16-byte aligned");
+    if (workspace_bytes < need)
+        return fail(CIAR_EWORKSPACE, "workspace has %zu bytes, %zu are needed", workspace_bytes, need);
+    return CIAR_OK;
+}
+
 // Shared tail of ciar_verify and ciar_quantify_verify.
 int run_verify(ciar::Mode mode, ciar::RowArgs& a, const ciar_params* p, uint8_t* accept, int32_t* row_id,
                int32_t* accept_len, int32_t* resampled_id, void* workspace, size_t workspace_bytes,
                hipStream_t stream)
 {
     const int64_t N = a.N;
+    if (int rc = check_workspace(N, p, workspace, workspace_bytes)) return rc;
+    if (N == 0) return CIAR_OK;
     const bool windows = accept_len || resampled_id;
+    char* w = static_cast<char*>(workspace);
+    a.stats = reinterpret_cast<ciar::RowStats*>(w);
     uint8_t* acc = accept;
     int32_t* rid = row_id;
-    if (windows && (!acc || (!rid && resampled_id))) {
-        const size_t need = ciar_workspace_bytes(N, p);
-        if (!workspace) return fail(CIAR_EWORKSPACE, "workspace is NULL but %zu bytes are needed", need);
-        if (!aligned16(workspace)) return fail(CIAR_EALIGN, "workspace is not 16-byte aligned");
-        if (workspace_bytes < need)
-            return fail(CIAR_EWORKSPACE, "workspace has %zu bytes, %zu are needed", workspace_bytes, need);
-        char* w = static_cast<char*>(workspace);
-        if (!rid) rid = reinterpret_cast<int32_t*>(w);
-        if (!acc) acc = reinterpret_cast<uint8_t*>(w + round_up((size_t)N * 4, 16));
-    }
+    if (windows && !acc) acc = reinterpret_cast<uint8_t*>(w + stats_bytes(N) + ids_bytes(N));
+    if (resampled_id && !rid) rid = reinterpret_cast<int32_t*>(w + stats_bytes(N));
     a.accept = acc;
     a.row_id = rid;
-    if (N == 0) return CIAR_OK;
-    hipError_t e = ciar::launch_rows(mode, p->dtype, a, stream);
-    if (e != hipSuccess) return hip_fail(e, "row kernel launch");
+    hipError_t e = ciar::launch_stream(mode, p->dtype, a, stream);
+    if (e != hipSuccess) return hip_fail(e, "streaming kernel launch");
+    e = ciar::launch_finish(mode, p->dtype, a, stream);
+    if (e != hipSuccess) return hip_fail(e, "finishing kernel launch");
     if (windows) {
         e = ciar::launch_windows(acc, rid, N, p->window, accept_len, resampled_id, stream);
         if (e != hipSuccess) return hip_fail(e, "window kernel launch");
@@ -172,12 +193,12 @@ void ciar_params_default(ciar_params* p)
 size_t ciar_workspace_bytes(int64_t N, const ciar_params* /*params*/)
 {
     if (N <= 0) return 0;
-    return round_up(round_up((size_t)N * 4, 16) + (size_t)N, 256);
+    return round_up(stats_bytes(N) + ids_bytes(N) + (size_t)N, 256);
 }
 
 int ciar_quantify(const void* draft_logits, const int32_t* draft_ids, int64_t N, const ciar_params* params,
                   float* p_lo, float* p_mid, float* p_hi, float* omega, float* sigma, float* score,
-                  uint8_t* flags, void* hip_stream)
+                  uint8_t* flags, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     Resolved r;
     if (int rc = check_params(params, &r)) return rc;
@@ -191,9 +212,14 @@ int ciar_quantify(const void* draft_logits, const int32_t* draft_ids, int64_t N,
     a.ids = draft_ids;
     a.p_lo = p_lo; a.p_mid = p_mid; a.p_hi = p_hi;
     a.omega = omega; a.sigma = sigma; a.score = score; a.flags = flags;
+    if (int rc = check_workspace(N, params, workspace, workspace_bytes)) return rc;
     if (N == 0) return CIAR_OK;
-    hipError_t e = ciar::launch_rows(ciar::Mode::Quantify, params->dtype, a, static_cast<hipStream_t>(hip_stream));
-    if (e != hipSuccess) return hip_fail(e, "row kernel launch");
+    a.stats = static_cast<ciar::RowStats*>(workspace);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = ciar::launch_stream(ciar::Mode::Quantify, params->dtype, a, stream);
+    if (e != hipSuccess) return hip_fail(e, "streaming kernel launch");
+    e = ciar::launch_finish(ciar::Mode::Quantify, params->dtype, a, stream);
+    if (e != hipSuccess) return hip_fail(e, "finishing kernel launch");
     return CIAR_OK;
 }
 

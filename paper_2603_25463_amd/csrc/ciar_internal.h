@@ -7,7 +7,20 @@
 
 namespace ciar {
 
-// Everything a row kernel needs, passed by value.  All pointers are device pointers.
+// What the streaming kernel leaves per row for the finishing kernel (device workspace).
+// Units: e_i = 2^(c_i log2e - n), S = sum e_i; likewise Z with nt for the verifier row.
+struct RowStats {
+    double S;        // partition sum of the centre row in units of 2^-n
+    double Z;        // partition sum of the verifier row in units of 2^-nt
+    double q[5];     // sum gl, sum gw, sum gl^2, sum gw^2, sum gl gw  (InterFuse sums, units of e)
+    float  n;        // integer-valued reference of the centre row
+    float  nt;       // integer-valued reference of the verifier row
+    float  mc;       // largest centre logit (the arg-max token's logit)
+    float  capless;  // 1 = the caps are inactive for this row and only q[1], q[3] were accumulated
+};
+static_assert(sizeof(RowStats) == 72, "RowStats layout");
+
+// Everything the kernels need, passed by value.  All pointers are device pointers.
 struct RowArgs {
     const void*    draft;       // [N, stride] centre logits
     const void*    target;      // [N, stride] verifier logits (verify only)
@@ -19,6 +32,7 @@ struct RowArgs {
     uint8_t* flags;                                  // [N] or null
     uint8_t* accept;                                 // [N] or null
     int32_t* row_id;                                 // [N] or null
+    RowStats* stats;                                 // [N] workspace
     int64_t  N;
     int64_t  stride;            // elements between rows
     int32_t  V;
@@ -28,15 +42,19 @@ struct RowArgs {
     double   tau;
     double   cap_lo;            // 0.99
     double   cap_hi;            // 1.01
+    double   capless_xmax;      // rows whose largest probability is below this have inactive caps
 };
 
 enum class Mode { Quantify, Verify, Fused };
 
-// Largest vocabulary the register-resident row kernels cover for an element size.
+// Largest vocabulary the register-resident streaming kernels cover for an element size.
 int max_vocab(int dtype);
 
-// Enqueue the per-row kernel.  Returns hipSuccess or the launch error.
-hipError_t launch_rows(Mode mode, int dtype, const RowArgs& args, hipStream_t stream);
+// Streaming pass over the rows: statistics and InterFuse sums into args.stats.
+hipError_t launch_stream(Mode mode, int dtype, const RowArgs& args, hipStream_t stream);
+
+// Per-row finishing: score, flag, reported interval, accept test, residual draw of rejected rows.
+hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, hipStream_t stream);
 
 // accept_len / resampled_id per window of K rows from the per-row results.
 hipError_t launch_windows(const uint8_t* accept, const int32_t* row_id, int64_t N, int32_t K,

@@ -1,34 +1,51 @@
 // gfx950 kernels of the CIAR quantify + verify pass.
 //
-// One workgroup owns one row (one drafted token position).  The centre row c and the verifier
-// row t are fetched once with 16-byte loads, interleaved over the workgroup so that every load
-// instruction of a wave covers 1 KiB of consecutive memory, and stay in registers for the whole
-// life of the workgroup: the InterFuse bounds need the partition sum S of the complete row
-// before the first bound can be formed (App. "Proof of Interval Validity": S appears in every
-// denominator), so the row has to be resident between the statistics pass and the interval pass.
-// Nothing V-wide is ever written back.
+// The pass is split in two kernels so that the kernel that touches the V-wide rows is pure
+// streaming arithmetic:
 //
-// Per row:
-//   A  max of c and of t                                   (max-trick)
-//   B  e_i = exp(c_i - max c) kept in registers, S = sum e_i;  Z = sum exp(t_i - max t)
+//   stream_kernel   reads every logit row exactly once from HBM and leaves ten numbers per row
+//                   (RowStats).  A workgroup of 256 lanes (1024 for the largest vocabularies) owns
+//                   one row at a time and walks over rows blockIdx.x, blockIdx.x + gridDim.x, ...
+//                   The grid holds a few workgroups per compute unit; while a workgroup computes on
+//                   one row, the 16-byte loads of its next row are already in flight into a second
+//                   set of registers, so the memory system stays busy.  Loads are interleaved over the
+//                   workgroup so that every load instruction of a wave covers 1 KiB of consecutive
+//                   memory.  Nothing V-wide is ever written back.
+//   finish_kernel   one workgroup per row: lane 0 turns RowStats into the row's outputs in fp64 (caps,
+//                   Omega, Sigma, U, flag, interval of the reported token, accept test); only for a
+//                   rejected row does the whole workgroup run the residual draw, re-reading the two
+//                   rows (~1 row in 8, served by the caches).
+//
+// The centre row has to be resident between its statistics pass and its interval pass: the InterFuse
+// bounds need the partition sum S of the complete row before the first bound can be formed (App.
+// "Proof of Interval Validity": S appears in every denominator).  It lives in registers as
+// e_i = 2^(c_i log2e - n_w).  The verifier row is only needed for max / Z and is consumed on arrival.
+//
+// stream_kernel, per row:
+//   T  verifier row: per-wave maximum, Z_w = sum 2^(t_i log2e - nt_w)          (max-trick)
+//   B  centre row:   per-wave maximum, e_i = 2^(c_i log2e - n_w) kept in registers, S_w = sum e_i
+//      The reference n_w is an integer (the next integer above max * log2e of the *wave*), so the
+//      waves need no barrier before exponentiating and their results combine exactly:
+//      S = sum_w S_w 2^(n_w - n), n = max_w n_w, a power-of-two rescale.
+//   -- barrier: the waves exchange (n_w, S_w, nt_w, Z_w) --
 //   C  InterFuse for a scalar radius r, a = e^r, b = e^-r, x_i = e_i / S:
 //        p^u_i = a x_i / (1 + (a-1) x_i),   p^l_i = b x_i / (1 - (1-b) x_i)
 //      with one reciprocal of the product of the two denominators, accumulated as the lower
-//      bound p^l_i and the raw width w_i = p^u_i - p^l_i = (a-b) x_i (1-x_i) / (du_i dl_i).
-//      Five sums per row (sum p^l, sum w and the three second moments, all taken about the
-//      values of the uniform row so that nearly flat rows do not cancel) give, after the
-//      0.99 / 1.01 caps alpha_l, alpha_u are known,
-//        delta_i = alpha_u w_i + (alpha_u - alpha_l) p^l_i,
-//        Omega   = sum delta_i,   Sigma^2 = (sum (delta_i - mean)^2) / V,   U = Omega * Sigma
-//      without a second sweep over the row.                 (Eq. uncertainty_score)
-//   D  flag = U > tau; interval of the drafted token; accept test in the log domain (fp64,
-//      one lane):  ln u < min(0, ln q_x - ln p_x)
-//   E  rejected rows only (workgroup-uniform branch): res_i = max(0, q_i - p_i), inverse-CDF
-//      draw in token order from a workgroup-wide prefix sum.
+//      bound p^l_i and the raw width w_i = p^u_i - p^l_i = (a-b) x_i (1-x_i) / (du_i dl_i):
+//      five fp64 sums per row (sum p^l, sum w and the three second moments).
+//   -- barrier: the waves exchange their five sums; lane 0 writes RowStats --
 //
-// Sums over the row are accumulated per lane in fp32 and combined across lanes and waves in
-// fp64 in a fixed order, so results are deterministic and the per-row scalars carry ~1e-8
-// relative error.
+// finish_kernel, per row (Eq. uncertainty_score; Algorithm 1's threshold and verification steps):
+//   delta_i = alpha_u w_i + (alpha_u - alpha_l) p^l_i once the 0.99 / 1.01 caps alpha_l, alpha_u are
+//   known, so Omega = sum delta_i, Sigma^2 = (sum delta_i^2) / V - (Omega / V)^2, U = Omega * Sigma
+//   follow from the five sums without a second sweep over the row; flag = U > tau;
+//   accept iff ln u < min(0, ln q_x - ln p_x) (log domain, fp64);
+//   rejected rows: res_i = max(0, q_i - p_i), inverse-CDF draw in token order from a workgroup-wide
+//   prefix sum.
+//
+// Sums over a row are accumulated per lane (S and the five interval sums in fp64, which this chip
+// issues at the fp32 rate) and combined across lanes with DPP and across waves through LDS in a fixed
+// order, so results are deterministic and the per-row scalars carry ~1e-8 relative error.
 #include "ciar_internal.h"
 
 #include <limits.h>
@@ -37,23 +54,31 @@
 namespace ciar {
 namespace {
 
-// log2(e) split so that the low part is positive: d * hi + d * lo stays -inf for d = -inf.
+// log2(e) split so that the low part is positive: x * hi + x * lo stays -inf for x = -inf.
 constexpr float  kLog2eHi = 1.44269490242004394531f;   // largest float below log2(e)
 constexpr float  kLog2eLo = 1.384689195e-7f;           // log2(e) - kLog2eHi
+constexpr double kLn2 = 0.69314718055994530942;
 
 __device__ __forceinline__ float bits_f(uint32_t u) { return __uint_as_float(u); }
 
 // 16 bytes as loaded: a native vector type, so it can be read through an address-space pointer.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+using gbytes = const __attribute__((address_space(1))) char*;
+using gvec = const __attribute__((address_space(1))) u32x4*;
 
-// exp(x - m) for x <= m.  The difference d = x - m is formed first: it is exact for logits near the
-// maximum and its rounding error shrinks with |d|, so the tokens that carry the mass get full
-// precision and the row maximum maps to exactly 1.  d * log2(e) uses the two-term constant.
-__device__ __forceinline__ float exp_shifted(float x, float m)
+// 2^(x log2(e) - n) for an integer-valued reference n.  x * hi - n is exact inside the FMA and is
+// rounded at the magnitude of the (small) result; the low part of log2(e) is added by a second FMA.
+__device__ __forceinline__ float exp2_ref(float x, float n)
 {
-    const float d = x - m;
-    return __builtin_amdgcn_exp2f(fmaf(d, kLog2eHi, d * kLog2eLo));
+    return __builtin_amdgcn_exp2f(fmaf(x, kLog2eLo, fmaf(x, kLog2eHi, -n)));
 }
+
+// Integer reference for a set of logits whose maximum is m: the next integer above m * log2(e), so
+// every 2^(x log2e - n) is <= 1 (up to rounding).  -inf (nothing but masked tokens) maps to -inf.
+__device__ __forceinline__ float ref_of(float m) { return ceilf(m * 1.44269504f); }
+
+// 2^k as a double for an integer-valued float difference k <= 0 (clamped: below 2^-1000 it is 0 anyway)
+__device__ __forceinline__ double pow2_of(float k) { return ldexp(1.0, (int)fmaxf(k, -1000.f)); }
 
 template <typename T> struct Elt;
 template <> struct Elt<float> {
@@ -96,13 +121,21 @@ template <> struct Elt<bf16_t> {
     }
 };
 
-// ---- wave and workgroup reductions (fixed order: deterministic) ----------------------------
+template <typename T>
+__device__ __forceinline__ float load_logit(const T* row, int i)
+{
+    if constexpr (sizeof(T) == 4) return reinterpret_cast<const float*>(row)[i];
+    else return bits_f((uint32_t)reinterpret_cast<const uint16_t*>(row)[i] << 16);
+}
+
+// ---- wave reductions (fixed order: deterministic) ----------------------------------------------
 //
-// Wave-level reductions use DPP row shifts and row broadcasts: they run on the vector ALU at full
-// rate, whereas a shuffle (ds_bpermute) goes through the LDS crossbar and costs ~5x more per step.
-// Pattern (wave64 = 4 rows of 16 lanes): row_shr 1, 2, 4, 8 leave each row's total in its lane 15;
-// row_bcast:15 adds it into the next row (rows 1 and 3), row_bcast:31 adds lane 31 into rows 2
-// and 3; lane 63 then holds the wave total, which readlane hands to every lane.
+// DPP row shifts and row broadcasts: they run on the vector ALU at full rate, whereas a shuffle
+// (ds_bpermute) goes through the LDS crossbar and costs ~5x more per step.
+// Pattern (wave64 = 4 rows of 16 lanes): row_shr 1, 2, 4, 8 leave each row's inclusive prefix in its
+// lanes; row_bcast:15 adds a row's total into the next row (rows 1 and 3), row_bcast:31 adds lane 31
+// into rows 2 and 3; every lane then holds its inclusive prefix over the wave and lane 63 the total,
+// which readlane hands to every lane.
 
 constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118;
 constexpr int kRowBcast15 = 0x142, kRowBcast31 = 0x143;
@@ -122,20 +155,7 @@ __device__ __forceinline__ double dpp_add(double v)
     return v + __hiloint2double(hi, lo);           // lanes without a source add +0.0
 }
 
-__device__ __forceinline__ double wave_sum(double v)
-{
-    v = dpp_add<kRowShr1, 0xf>(v);
-    v = dpp_add<kRowShr2, 0xf>(v);
-    v = dpp_add<kRowShr4, 0xf>(v);
-    v = dpp_add<kRowShr8, 0xf>(v);
-    v = dpp_add<kRowBcast15, 0xa>(v);
-    v = dpp_add<kRowBcast31, 0xc>(v);
-    const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
-    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
-    return __hiloint2double(hi, lo);
-}
-
-// inclusive prefix sum over the 64 lanes (same steps, without the final broadcast)
+// inclusive prefix sum over the 64 lanes
 __device__ __forceinline__ double wave_scan(double v)
 {
     v = dpp_add<kRowShr1, 0xf>(v);
@@ -145,6 +165,14 @@ __device__ __forceinline__ double wave_scan(double v)
     v = dpp_add<kRowBcast15, 0xa>(v);
     v = dpp_add<kRowBcast31, 0xc>(v);
     return v;
+}
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+    v = wave_scan(v);
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
+    return __hiloint2double(hi, lo);
 }
 
 template <int CTRL, int ROW_MASK>
@@ -187,44 +215,9 @@ __device__ __forceinline__ int wave_max_i(int v)
     return __builtin_amdgcn_readlane(v, 63);
 }
 
-// All threads end up with the workgroup-wide sums of v[0..NV).  smem: NW*NV doubles.
-template <int NW, int NV>
-__device__ __forceinline__ void block_sum(double (&v)[NV], double* smem, int lane, int wave)
-{
-#pragma unroll
-    for (int i = 0; i < NV; ++i) v[i] = wave_sum(v[i]);
-    __syncthreads();
-    if (lane == 0) {
-#pragma unroll
-        for (int i = 0; i < NV; ++i) smem[wave * NV + i] = v[i];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        double s = 0.0;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) s += smem[w * NV + i];
-        v[i] = s;
-    }
-}
+// ---- per-token InterFuse arithmetic, shared by the streaming kernel and the dense export ------------
 
-template <int NW>
-__device__ __forceinline__ float block_max(float m, double* smem, int lane, int wave)
-{
-    m = wave_max(m);
-    float* f = reinterpret_cast<float*>(smem);
-    __syncthreads();
-    if (lane == 0) f[wave] = m;
-    __syncthreads();
-    float r = f[0];
-#pragma unroll
-    for (int w = 1; w < NW; ++w) r = fmaxf(r, f[w]);
-    return r;
-}
-
-// ---- per-token InterFuse arithmetic, shared by the row kernel and the dense export ----------
-
-// Constants of one row for a scalar radius.  Units: e_i = exp(c_i - max c), S = sum e_i.
+// Constants of one row for a scalar radius.  Units: e_i as held by the lane, S = sum e_i in the same units.
 struct FuseRow {
     float cu;            // (a-1)/S:  du = 1 + (a-1) x = 1 + cu e
     float nih, nil;      // -1/S split in two floats:  1 - x = 1 + nih e + nil e  (exact to ~1e-15)
@@ -254,18 +247,19 @@ __device__ __forceinline__ void fuse_token(float e, const FuseRow& r, float& gl,
     gw = g * om;
 }
 
-// Per-row scalars of the quantifier from the five centred sums (fp64, one lane).
+// Per-row scalars of the quantifier from the five sums (fp64, one lane).
 struct RowScore { double alpha_l, alpha_u, omega, sigma, score; };
 
-__device__ __forceinline__ RowScore finish_score(const double (&s)[5], double S, const RowArgs& A)
+__device__ __forceinline__ RowScore finish_score(const double* s, double S, bool capless, const RowArgs& A)
 {
-    // s = { sum gl, sum gw, sum gl^2, sum gw^2, sum gl gw } over the V tokens of the row
+    // s = { sum gl, sum gw, sum gl^2, sum gw^2, sum gl gw } over the V tokens of the row;
+    // capless = the caps are known to be inactive and only sum gw, sum gw^2 were accumulated
     const double V = (double)A.V;
     const double Bc = A.b / S, Wc = (A.a - A.b) / S;
     const double Sl = Bc * s[0], Su = Sl + Wc * s[1];
     RowScore o;
     o.alpha_l = 1.0; o.alpha_u = 1.0;
-    if (A.normalize) {
+    if (A.normalize && !capless) {
         o.alpha_l = fmin(1.0, A.cap_lo / Sl);
         o.alpha_u = fmax(1.0, A.cap_hi / Su);
     }
@@ -281,29 +275,37 @@ __device__ __forceinline__ RowScore finish_score(const double (&s)[5], double S,
     return o;
 }
 
-// Waves per SIMD the register allocation aims for.  One row at a time is resident (the verifier row
-// is consumed before the centre row is fetched into the same registers): EPT floats plus ~50 working
-// registers, capped at 4 waves (more buys nothing for a kernel that streams 64 KiB per workgroup).
-template <typename T, int THREADS, int NVEC>
+// ---- the streaming kernel ---------------------------------------------------------------------------------
+
+// Waves per SIMD the register allocation aims for: the rows held in registers plus ~40 working
+// registers, capped at 4 waves (more buys nothing for a kernel that streams 64 KiB per row).
+// With prefetch a lane holds the current centre row as floats, and the next centre row and one
+// verifier row as loaded.
+template <typename T, int THREADS, int NVEC, bool DO_V>
 constexpr int target_waves()
 {
 #ifdef XP_WAVES
     return XP_WAVES < THREADS / 256 ? THREADS / 256 : XP_WAVES;
 #endif
-    constexpr int regs = NVEC * Elt<T>::kPerVec + 56;
-    constexpr int fit = 512 / regs;
+    constexpr bool prefetch = THREADS == 256;
+    constexpr int raw = NVEC * 4;                                  // one row as loaded
+    constexpr int ept = NVEC * Elt<T>::kPerVec;                    // one row as floats
+    constexpr int rows = ept + (prefetch ? raw : 0) + (DO_V && prefetch ? raw : 0);
+    constexpr int fit = 512 / (rows + 40);
     constexpr int lo = THREADS / 256;                 // waves per SIMD one workgroup needs
     return fit < lo ? lo : (fit > 4 ? 4 : fit);
 }
 
-// Pass C for one lane: the five InterFuse sums over the lane's tokens.
+// Pass C for one lane: the InterFuse sums over the lane's tokens.
 // MASKED = the row does not fill the tile: chunks past the end are skipped (padding inside the last
 // chunk has e = 0 and adds exactly nothing).
-template <int THREADS, int NVEC, int EPV, bool MASKED>
+// WIDTH_ONLY = the caps are known to be inactive for this row (alpha_l = alpha_u = 1), so
+// delta_i = w_i and only sum gw and sum gw^2 are needed.
+template <int THREADS, int NVEC, int EPV, bool MASKED, bool WIDTH_ONLY>
 __device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const FuseRow& fr, int V,
                                           double (&q5)[5])
 {
-    // The five sums run in fp64 from the first add (fp64 adds and FMAs issue at the fp32 rate on this
+    // The sums run in fp64 from the first add (fp64 adds and FMAs issue at the fp32 rate on this
     // chip).  One token can hold almost all of sum(gl), and the variance is a difference of second
     // moments that would cancel in fp32 on nearly flat rows; in fp64 neither needs a centring trick.
     double a0[2] = {0.0, 0.0}, a1[2] = {0.0, 0.0}, a2[2] = {0.0, 0.0}, a3[2] = {0.0, 0.0}, a4[2] = {0.0, 0.0};
@@ -314,12 +316,15 @@ __device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const Fu
         for (int k = 0; k < EPV; ++k) {
             float gl, gw;
             fuse_token(e[j * EPV + k], fr, gl, gw);                // padding has e = 0: gl = gw = 0
-            const double dl = (double)gl, dw = (double)gw;
-            a0[k & 1] += dl;
+            const double dw = (double)gw;
             a1[k & 1] += dw;
-            a2[k & 1] = fma(dl, dl, a2[k & 1]);
             a3[k & 1] = fma(dw, dw, a3[k & 1]);
-            a4[k & 1] = fma(dl, dw, a4[k & 1]);
+            if constexpr (!WIDTH_ONLY) {
+                const double dl = (double)gl;
+                a0[k & 1] += dl;
+                a2[k & 1] = fma(dl, dl, a2[k & 1]);
+                a4[k & 1] = fma(dl, dw, a4[k & 1]);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);                         // one vector at a time: bounded working set
     }
@@ -330,288 +335,412 @@ __device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const Fu
     q5[4] = a4[0] + a4[1];
 }
 
-template <typename T>
-__device__ __forceinline__ float load_logit(const T* row, int i)
-{
-    if constexpr (sizeof(T) == 4) return reinterpret_cast<const float*>(row)[i];
-    else return bits_f((uint32_t)reinterpret_cast<const uint16_t*>(row)[i] << 16);
-}
-
 template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V>
 __global__ __launch_bounds__(THREADS)
-__attribute__((amdgpu_waves_per_eu(target_waves<T, THREADS, NVEC>())))
-void row_kernel(const RowArgs A)
+__attribute__((amdgpu_waves_per_eu(target_waves<T, THREADS, NVEC, DO_V>())))
+void stream_kernel(const RowArgs A)
 {
     using E = Elt<T>;
     constexpr int EPV = E::kPerVec;
     constexpr int EPT = NVEC * EPV;
     constexpr int NW = THREADS / 64;
     constexpr int CHUNK = THREADS * EPV;            // tokens covered by one load instruction of the workgroup
-    constexpr int EB = NVEC > 8 ? 8 : NVEC;         // vectors of each row in flight per lane in the residual pass
+    // With 256 lanes there is register room to fetch the next row while this one is computed on.
+    constexpr bool PREFETCH = THREADS == 256;
 
-    __shared__ double smem[NW * (NVEC > 5 ? NVEC : 5) + NW];
-    __shared__ int    smem_i[NW * 2 + 2];
+    // exchange slots, double-buffered by row parity so that one barrier per exchange is enough
+    __shared__ float  sm_ref[2][NW * 3];            // per wave: max centre logit, n_w, nt_w
+    __shared__ double sm_sum[2][NW * 2];            // per wave: S_w, Z_w
+    __shared__ double sm_q5[NW * 5];                // per wave: the five interval sums, already in row units
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int V = A.V;
+    const bool partial = V != NVEC * CHUNK;                        // uniform: the row does not fill the tile
+    const int last_vec = (V + EPV - 1) / EPV - 1;
+    const int nrows = (int)A.N;
+    const int step = (int)gridDim.x;
+
+    // Rows live in global memory (address space 1).  Vector j of this lane: scalar row base + 32-bit
+    // byte offset.  Vector indices past the end of the row are clamped to its last vector, so every
+    // lane loads valid memory unconditionally; tokens that do not exist are set to -inf afterwards.
+    // The base goes through readfirstlane and the lane index through an empty asm on every use: both
+    // are opaque to the optimiser, which otherwise turns the sixteen addresses of a row into sixteen
+    // 64-bit induction variables per row buffer, spills them, and serialises the prefetch on the reloads.
+    auto load_vec = [&](const void* rows, int r, int j) -> u32x4 {
+        const uint64_t b = (uint64_t)(static_cast<const T*>(rows) + (int64_t)r * A.stride);
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+        const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+        int t = tid;
+        asm volatile("" : "+v"(t));
+        const uint32_t off = (uint32_t)min(j * THREADS + t, last_vec) * 16u;
+        return *(gvec)((gbytes)(((uint64_t)hi << 32) | lo) + off);
+    };
+
+    // the row index is uniform over the workgroup: keep it in a scalar register
+    int row = __builtin_amdgcn_readfirstlane((int)blockIdx.x);     // the launcher keeps gridDim.x <= N
+    u32x4 tbuf[NVEC];                                              // verifier row as loaded (without prefetch: both rows in turn)
+    u32x4 cbuf[PREFETCH ? NVEC : 1];                               // centre row as loaded
+    if constexpr (DO_V) {
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) tbuf[j] = load_vec(A.target, row, j);
+    }
+    if constexpr (PREFETCH) {
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) cbuf[j] = load_vec(A.draft, row, j);
+    }
+
+    for (int it = 0;; ++it) {
+        const int next = __builtin_amdgcn_readfirstlane(row + step);
+        const bool has_next = next < nrows;                        // uniform
+        const int par = it & 1;
+
+        // ---- T: verifier row statistics, per wave; the row is not kept -----------------------------
+        float ntw = -INFINITY;
+        double Zw = 0.0;
+        if constexpr (DO_V) {
+            if (partial) {
+#pragma unroll
+                for (int j = 0; j < NVEC; ++j) E::mask_tail(tbuf[j], (j * THREADS + tid) * EPV, V);
+            }
+            float mt = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) {
+                float tv[EPV];
+                E::unpack(tbuf[j], tv);
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) mt = fmaxf(mt, tv[k]);
+            }
+            ntw = ref_of(wave_max(mt));
+            const float nref = ntw == -INFINITY ? 0.f : ntw;       // an all-masked wave: every term is 2^-inf = 0
+            float zacc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) {
+                float tv[EPV];
+                E::unpack(tbuf[j], tv);
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) zacc[k & 3] += exp2_ref(tv[k], nref);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            Zw = wave_sum((double)((zacc[0] + zacc[1]) + (zacc[2] + zacc[3])));
+            __builtin_amdgcn_sched_barrier(0);                     // t is dead from here on
+            if constexpr (PREFETCH) {
+                // (the else branch kills the old contents: otherwise they would stay live to the loop's end)
+                if (has_next) {
+#pragma unroll
+                    for (int j = 0; j < NVEC; ++j) tbuf[j] = load_vec(A.target, next, j);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < NVEC; ++j) tbuf[j] = u32x4{0u, 0u, 0u, 0u};
+                }
+            }
+        }
+
+        // ---- A + B: centre row: per-wave max, e_i = 2^(c_i log2e - n_w), S_w -------------------------
+        float e[EPT];
+        u32x4 cnext[PREFETCH ? NVEC : 1];
+        if constexpr (PREFETCH) {
+            if (partial) {
+#pragma unroll
+                for (int j = 0; j < NVEC; ++j) E::mask_tail(cbuf[j], (j * THREADS + tid) * EPV, V);
+            }
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) E::unpack(cbuf[j], &e[j * EPV]);
+            // the next centre row goes in flight now, into registers of its own, and lands while this
+            // row is computed on
+            __builtin_amdgcn_sched_barrier(0);
+            if (has_next) {
+#pragma unroll
+                for (int j = 0; j < NVEC; ++j) cnext[j] = load_vec(A.draft, next, j);
+            } else {
+#pragma unroll
+                for (int j = 0; j < NVEC; ++j) cnext[j] = u32x4{0u, 0u, 0u, 0u};
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        } else {
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) tbuf[j] = load_vec(A.draft, row, j);
+            if (partial) {
+#pragma unroll
+                for (int j = 0; j < NVEC; ++j) E::mask_tail(tbuf[j], (j * THREADS + tid) * EPV, V);
+            }
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) E::unpack(tbuf[j], &e[j * EPV]);
+        }
+        float mcl = e[0];
+#pragma unroll
+        for (int i = 1; i < EPT; ++i) mcl = fmaxf(mcl, e[i]);
+        const float mcw = wave_max(mcl);
+        const float nw = ref_of(mcw);
+        double Sw;
+        {
+            // S is accumulated in fp64 from the first add: on a nearly one-hot row the bounds of the top
+            // token react to a relative error in S about five times over, and adding small terms to an
+            // fp32 partial sum that already holds ~1 would cost 1e-7.
+            const float nref = nw == -INFINITY ? 0.f : nw;
+            double sacc[2] = {0.0, 0.0};
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) {
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) {
+                    e[j * EPV + k] = exp2_ref(e[j * EPV + k], nref);
+                    sacc[k & 1] += (double)e[j * EPV + k];
+                }
+                __builtin_amdgcn_sched_barrier(0);                 // keep the working set to one vector at a time
+            }
+            Sw = wave_sum(sacc[0] + sacc[1]);
+        }
+
+        // ---- the waves exchange their statistics: the only barrier before the interval pass ------------
+        if (lane == 0) {
+            sm_ref[par][wave * 3] = mcw; sm_ref[par][wave * 3 + 1] = nw; sm_ref[par][wave * 3 + 2] = ntw;
+            sm_sum[par][wave * 2] = Sw;  sm_sum[par][wave * 2 + 1] = Zw;
+        }
+        __syncthreads();
+        float mc = sm_ref[par][0], n = sm_ref[par][1], nt = sm_ref[par][2];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) {
+            mc = fmaxf(mc, sm_ref[par][w * 3]);
+            n = fmaxf(n, sm_ref[par][w * 3 + 1]);
+            nt = fmaxf(nt, sm_ref[par][w * 3 + 2]);
+        }
+        double S = 0.0, Z = 0.0;                                   // in units of 2^-n and 2^-nt
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float rn = sm_ref[par][w * 3 + 1], rt = sm_ref[par][w * 3 + 2];
+            if (rn != -INFINITY) S += sm_sum[par][w * 2] * pow2_of(rn - n);
+            if (DO_V && rt != -INFINITY) Z += sm_sum[par][w * 2 + 1] * pow2_of(rt - nt);
+        }
+        const double fw = nw == -INFINITY ? 0.0 : pow2_of(nw - n);     // this wave's e_i are 1/fw too large
+
+        // ---- C: InterFuse sums in this wave's units, rescaled to row units by lane 0 of the wave ---------
+        // Caps: S_l <= b / (1 - (1-b) x_max) and S_u >= a / (1 + (a-1) x_max) for the largest probability
+        // x_max of the row, so below the host-computed bound on x_max both caps are inactive and the
+        // cheaper width-only pass is exact.  Uniform over the workgroup.
+        const bool capless = !A.normalize || (double)exp2_ref(mc, n) <= A.capless_xmax * S;
+        if constexpr (DO_Q) {
+            // x_i = e_i fw / S: hand fuse_row the partition sum expressed in this wave's units
+            const FuseRow fr = fuse_row(fw > 0.0 ? S / fw : 1.0, A.a, A.b);
+            double q5[5];
+            if (capless) {
+                if (partial) fuse_sums<THREADS, NVEC, EPV, true, true>(e, fr, V, q5);
+                else         fuse_sums<THREADS, NVEC, EPV, false, true>(e, fr, V, q5);
+            } else {
+                if (partial) fuse_sums<THREADS, NVEC, EPV, true, false>(e, fr, V, q5);
+                else         fuse_sums<THREADS, NVEC, EPV, false, false>(e, fr, V, q5);
+            }
+#pragma unroll
+            for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
+            if (lane == 0) {
+                const double f2 = fw * fw;
+                sm_q5[wave * 5 + 0] = q5[0] * fw; sm_q5[wave * 5 + 1] = q5[1] * fw;
+                sm_q5[wave * 5 + 2] = q5[2] * f2; sm_q5[wave * 5 + 3] = q5[3] * f2; sm_q5[wave * 5 + 4] = q5[4] * f2;
+            }
+        }
+        if constexpr (PREFETCH) {
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) cbuf[j] = cnext[j];
+        }
+
+        // ---- lane 0 leaves the row's ten numbers for the finishing kernel --------------------------------
+        if constexpr (DO_Q) __syncthreads();
+        if (tid == 0) {
+            RowStats* st = A.stats + row;
+            st->S = S; st->Z = Z; st->n = n; st->nt = nt; st->mc = mc; st->capless = capless ? 1.f : 0.f;
+#pragma unroll
+            for (int i = 0; i < 5; ++i) {
+                double t = 0.0;
+                if constexpr (DO_Q) {
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) t += sm_q5[w * 5 + i];
+                }
+                st->q[i] = t;
+            }
+        }
+
+        if (!has_next) break;
+        row = next;
+        if constexpr (!PREFETCH && DO_V) {
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) tbuf[j] = load_vec(A.target, row, j);
+        }
+    }
+}
+
+// ---- the finishing kernel: one workgroup per row --------------------------------------------------------------
+
+// THREADS = 64 when no verification is asked for (lane 0 does all the work), 256 otherwise.
+template <typename T, int THREADS>
+__global__ __launch_bounds__(THREADS) void finish_kernel(const RowArgs A, const int do_q, const int do_v)
+{
+    using E = Elt<T>;
+    constexpr int EPV = E::kPerVec;
+    constexpr int NW = THREADS / 64;
+    constexpr int CHUNK = THREADS * EPV;
+    constexpr int MAXCH = 64;                       // chunks of CHUNK tokens a row can have (V <= 65536)
+    constexpr int UB = 16;                          // vectors of each row in flight per lane
+
+    __shared__ double sm_e[NW * MAXCH + NW];
+    __shared__ int    sm_i[NW * 2 + 1];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t row = blockIdx.x;
     const int V = A.V;
-    const bool partial = V != NVEC * CHUNK;                        // uniform: the row does not fill the tile
-    const int last_vec = (V + EPV - 1) / EPV - 1;
-
-    // Rows live in global memory (address space 1): say so, or the loads are emitted as flat ones.
-    // Vector indices past the end of the row are clamped to its last vector, so every lane loads
-    // valid memory unconditionally; tokens that do not exist are set to -inf afterwards.
-    using gbytes = const __attribute__((address_space(1))) char*;
-    using gvec = const __attribute__((address_space(1))) u32x4*;
     const T* crow = static_cast<const T*>(A.draft) + row * A.stride;
-    const T* trow = DO_V ? static_cast<const T*>(A.target) + row * A.stride : nullptr;
-    // vector j of this lane: uniform row base + 32-bit byte offset (one VGPR per address)
-    auto load_vec_at = [&](const T* base, int j, int t) -> u32x4 {
-        const uint32_t off = (uint32_t)min(j * THREADS + t, last_vec) * 16u;
-        return *(gvec)((gbytes)base + off);
-    };
-    auto load_vec = [&](const T* base, int j) -> u32x4 { return load_vec_at(base, j, tid); };
+    const T* trow = do_v ? static_cast<const T*>(A.target) + row * A.stride : nullptr;
+    const RowStats st = A.stats[row];
+    const double S = st.S, Z = st.Z;
+    const float n = st.n, nt = st.nt;
 
-    u32x4 raw[NVEC];                                               // landing registers: t first, then c
-
-    // ---- T: verifier row statistics (max, Z); the row is not kept ---------------------------------
-    int xid = -1;
-    float cx = 0.f, tx = 0.f, ua = 0.f, ur = 0.f;
-    float mt = -INFINITY;
-    double sz[2] = {0.0, 0.0};                                     // lane partials of S and Z
-    if constexpr (DO_V) {
-#pragma unroll
-        for (int j = 0; j < NVEC; ++j) raw[j] = load_vec(trow, j);
-    }
-    if (tid == 0) {                                                // the row's scalars and the drafted token's logits
+    if (tid == 0) {
+        int xid = -1;
+        float cx = st.mc;                                          // no ids: the arg-max token is reported
         if (A.ids) {
             xid = A.ids[row];
             xid = xid < 0 ? 0 : (xid >= V ? V - 1 : xid);
             cx = load_logit(crow, xid);
         }
-        if constexpr (DO_V) {
-            tx = load_logit(trow, xid);
-            ua = A.u_accept[row];
-            ur = A.u_resample[row];
-        }
-    }
-    if constexpr (DO_V) {
-        if (partial) {
-#pragma unroll
-            for (int j = 0; j < NVEC; ++j) E::mask_tail(raw[j], (j * THREADS + tid) * EPV, V);
-        }
-#pragma unroll
-        for (int j = 0; j < NVEC; ++j) {
-            float tv[EPV];
-            E::unpack(raw[j], tv);
-#pragma unroll
-            for (int k = 0; k < EPV; ++k) mt = fmaxf(mt, tv[k]);
-        }
-        mt = block_max<NW>(mt, smem, lane, wave);
-        float zacc[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int j = 0; j < NVEC; ++j) {
-            float tv[EPV];
-            E::unpack(raw[j], tv);
-#pragma unroll
-            for (int k = 0; k < EPV; ++k) zacc[k & 3] += exp_shifted(tv[k], mt);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        sz[1] = (double)((zacc[0] + zacc[1]) + (zacc[2] + zacc[3]));
-        __builtin_amdgcn_sched_barrier(0);                         // t is dead: its registers take the centre row
-    }
-
-    // ---- A + B: centre row: max, e_i = exp(c_i - max), S ----------------------------------------------
-    {
-#pragma unroll
-        for (int j = 0; j < NVEC; ++j) raw[j] = load_vec(crow, j);
-        if (partial) {
-#pragma unroll
-            for (int j = 0; j < NVEC; ++j) E::mask_tail(raw[j], (j * THREADS + tid) * EPV, V);
-        }
-    }
-    float e[EPT];
-#pragma unroll
-    for (int j = 0; j < NVEC; ++j) E::unpack(raw[j], &e[j * EPV]);
-    float mc = e[0];
-#pragma unroll
-    for (int i = 1; i < EPT; ++i) mc = fmaxf(mc, e[i]);
-    mc = block_max<NW>(mc, smem, lane, wave);
-    {
-        // S is accumulated in fp64 from the first add: on a nearly one-hot row the bounds of the top
-        // token react to a relative error in S about five times over, and adding small terms to an
-        // fp32 partial sum that already holds 1.0 would cost 1e-7.
-        double sacc[2] = {0.0, 0.0};
-#pragma unroll
-        for (int j = 0; j < NVEC; ++j) {
-#pragma unroll
-            for (int k = 0; k < EPV; ++k) {
-                e[j * EPV + k] = exp_shifted(e[j * EPV + k], mc);
-                sacc[k & 1] += (double)e[j * EPV + k];
-            }
-            __builtin_amdgcn_sched_barrier(0);                     // keep the working set to one vector at a time
-        }
-        sz[0] = sacc[0] + sacc[1];
-    }
-    block_sum<NW, 2>(sz, smem, lane, wave);
-    const double S = sz[0], Z = sz[1];
-    const double mcd = (double)mc, mtd = (double)mt;
-
-    // ---- D1: accept test (one lane, fp64, log domain) ----------------------------------------------------
-    if constexpr (DO_V) {
-        if (tid == 0) {
-            const double lp = ((double)cx - mcd) - log(S);
-            const double lq = ((double)tx - mtd) - log(Z);
-            const double ell = lq - lp;
-            const double lnu = log((double)ua);                    // log(0) = -inf: always accepted
-            const int rej = !(lnu < fmin(0.0, ell));
-            if (A.accept) A.accept[row] = (uint8_t)(!rej);
-            if (!rej && A.row_id) A.row_id[row] = -1;
-            smem_i[NW * 2] = rej;                                  // read by everyone after the next barrier
-            smem_i[NW * 2 + 1] = __float_as_int(ur);
-        }
-    }
-
-    // ---- C + D2: InterFuse sums, score, flag and the drafted token's interval ------------------------
-    if constexpr (DO_Q) {
-        const FuseRow fr = fuse_row(S, A.a, A.b);
-        double q5[5];
-        if (partial) fuse_sums<THREADS, NVEC, EPV, true>(e, fr, V, q5);
-        else         fuse_sums<THREADS, NVEC, EPV, false>(e, fr, V, q5);
-        block_sum<NW, 5>(q5, smem, lane, wave);
-        if (tid == 0) {
-            const RowScore rs = finish_score(q5, S, A);
+        if (do_q) {
+            const RowScore rs = finish_score(st.q, S, st.capless != 0.f, A);
             if (A.omega) A.omega[row] = (float)rs.omega;
             if (A.sigma) A.sigma[row] = (float)rs.sigma;
             if (A.score) A.score[row] = (float)rs.score;
             if (A.flags) A.flags[row] = (uint8_t)(rs.score > A.tau);
             if (A.p_lo || A.p_mid || A.p_hi) {
-                // the reported token: the drafted one, or the arg-max (e = 1) when no ids are given
-                const double ex = exp((double)(xid >= 0 ? cx : mc) - mcd);
-                const double x = ex / S;
+                const double x = exp((double)cx - (double)n * kLn2) / S;
                 if (A.p_mid) A.p_mid[row] = (float)x;
                 if (A.p_lo) A.p_lo[row] = (float)(rs.alpha_l * A.b * x / (1.0 + (A.b - 1.0) * x));
                 if (A.p_hi) A.p_hi[row] = (float)(rs.alpha_u * A.a * x / (1.0 + (A.a - 1.0) * x));
             }
         }
+        int rej = 0;
+        if (do_v) {
+            // ln p_x = cx - n ln2 - ln S, ln q_x = tx - nt ln2 - ln Z;  accept iff ln u < min(0, ln q_x - ln p_x)
+            const float tx = load_logit(trow, xid);
+            const double lp = ((double)cx - (double)n * kLn2) - log(S);
+            const double lq = ((double)tx - (double)nt * kLn2) - log(Z);
+            const double lnu = log((double)A.u_accept[row]);       // log(0) = -inf: always accepted
+            rej = !(lnu < fmin(0.0, lq - lp));
+            if (A.accept) A.accept[row] = (uint8_t)(!rej);
+            if (!rej && A.row_id) A.row_id[row] = -1;
+        }
+        sm_i[NW * 2] = rej;
     }
-
-    // ---- E: residual resample of a rejected row (workgroup-uniform branch) -----------------------------
-    // res_i = max(0, q_i - p_i).  Self-contained on purpose: both rows are fetched again (they were just
-    // read, so this comes from cache) and e_i, exp(t_i - max t) are recomputed bit-identically, so that
-    // no register of the main path has to stay alive for a branch only ~1 row in 8 takes.
-    if constexpr (DO_V) {
+    if constexpr (THREADS == 64) {
+        return;                                                    // quantify only
+    } else {
         __syncthreads();
-        const int rejected = smem_i[NW * 2];
-        if (rejected && A.row_id) {
-            const double u_res = (double)__int_as_float(smem_i[NW * 2 + 1]);
-            const double invS = 1.0 / S, invZ = 1.0 / Z;
-            // The lane index is laundered through an empty asm so that the addresses of this rare branch
-            // are formed here instead of being kept alive (and spilled) across the whole main path.
-            int tid_e = tid;
-            asm volatile("" : "+v"(tid_e));
-            // residuals of one 16-byte vector of each row
-            auto residuals = [&](u32x4 cr, u32x4 tr, int j, float (&r)[EPV]) {
-                if (partial) {
-                    E::mask_tail(cr, (j * THREADS + tid_e) * EPV, V);
-                    E::mask_tail(tr, (j * THREADS + tid_e) * EPV, V);
-                }
-                float cv[EPV], tv[EPV];
-                E::unpack(cr, cv);
-                E::unpack(tr, tv);
+        if (!sm_i[NW * 2] || !A.row_id) return;                    // workgroup-uniform
+
+        // ---- residual resample of a rejected row: res_i = max(0, q_i - p_i) ----------------------------
+        const double u_res = (double)A.u_resample[row];
+        const double invS = 1.0 / S, invZ = 1.0 / Z;
+        const int last_vec = (V + EPV - 1) / EPV - 1;
+        const int nch = (V + CHUNK - 1) / CHUNK;                   // <= MAXCH by the supported vocabulary range
+        auto load_vec = [&](const T* base, int j) -> u32x4 {
+            const uint32_t off = (uint32_t)min(j * THREADS + tid, last_vec) * 16u;
+            return *(gvec)((gbytes)base + off);
+        };
+        // residuals of one 16-byte vector of each row; tokens past the end of the row are masked to -inf
+        auto residuals = [&](u32x4 cr, u32x4 tr, int j, float (&r)[EPV]) {
+            E::mask_tail(cr, (j * THREADS + tid) * EPV, V);
+            E::mask_tail(tr, (j * THREADS + tid) * EPV, V);
+            float cv[EPV], tv[EPV];
+            E::unpack(cr, cv);
+            E::unpack(tr, tv);
 #pragma unroll
-                for (int k = 0; k < EPV; ++k) {
-                    const double q = (double)exp_shifted(tv[k], mt) * invZ;
-                    const double p = (double)exp_shifted(cv[k], mc) * invS;
-                    r[k] = (float)fmax(q - p, 0.0);
-                }
-            };
-            // E1: workgroup totals of the residual over each chunk of CHUNK tokens
+            for (int k = 0; k < EPV; ++k) {
+                const double q = (double)exp2_ref(tv[k], nt) * invZ;
+                const double p = (double)exp2_ref(cv[k], n) * invS;
+                r[k] = (float)fmax(q - p, 0.0);
+            }
+        };
+        // E1: workgroup totals of the residual over each chunk of CHUNK tokens
+        for (int j0 = 0; j0 < nch; j0 += UB) {
+            u32x4 cb[UB], tb[UB];
 #pragma unroll
-            for (int b0 = 0; b0 < NVEC; b0 += EB) {
-                u32x4 cb[EB], tb[EB];
+            for (int u = 0; u < UB; ++u) { cb[u] = load_vec(crow, j0 + u); tb[u] = load_vec(trow, j0 + u); }
 #pragma unroll
-                for (int jj = 0; jj < EB; ++jj) {
-                    cb[jj] = load_vec_at(crow, b0 + jj, tid_e);
-                    tb[jj] = load_vec_at(trow, b0 + jj, tid_e);
-                }
-#pragma unroll
-                for (int jj = 0; jj < EB; ++jj) {
+            for (int u = 0; u < UB; ++u) {
+                if (j0 + u < nch) {                                // uniform
                     float r[EPV];
-                    residuals(cb[jj], tb[jj], b0 + jj, r);
+                    residuals(cb[u], tb[u], j0 + u, r);
                     float s = 0.f;
 #pragma unroll
                     for (int k = 0; k < EPV; ++k) s += r[k];
                     const double ws = wave_sum((double)s);
-                    if (lane == 0) smem[wave * NVEC + b0 + jj] = ws;
-                    __builtin_amdgcn_sched_barrier(0);
+                    if (lane == 0) sm_e[wave * MAXCH + j0 + u] = ws;
                 }
             }
+        }
+        __syncthreads();
+        double R = 0.0;
+        for (int j = 0; j < nch; ++j) {
+#pragma unroll
+            for (int w = 0; w < NW; ++w) R += sm_e[w * MAXCH + j];
+        }
+        int cand = INT_MAX, lastpos = -1;
+        if (R > 0.0) {
+            // chunk that holds the crossing of u * R (token order = chunk order, then lane order)
+            const double thr = u_res * R;
+            int jstar = -1, jlast = 0;
+            double before = 0.0, run = 0.0;
+            for (int j = 0; j < nch; ++j) {
+                double tot = 0.0;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) tot += sm_e[w * MAXCH + j];
+                if (jstar < 0 && run + tot > thr) { jstar = j; before = run; }
+                if (tot > 0.0) jlast = j;
+                if (jstar < 0) run += tot;
+            }
+            if (jstar < 0) { jstar = jlast; before = run; }        // unreachable for u < 1; keeps the draw valid
+            // E2: the lane's residuals inside that chunk, recomputed exactly as in E1
+            float r[EPV];
+            residuals(load_vec(crow, jstar), load_vec(trow, jstar), jstar, r);
+            float s = 0.f;
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) s += r[k];
+            const double incl = wave_scan((double)s);
+            if (lane == 63) sm_e[NW * MAXCH + wave] = incl;
             __syncthreads();
-            double R = 0.0;
+            double cum = before + (incl - (double)s);
 #pragma unroll
-            for (int j = 0; j < NVEC; ++j) {
+            for (int w = 0; w < NW; ++w)
+                if (w < wave) cum += sm_e[NW * MAXCH + w];
+            // smallest token of the chunk whose inclusive running sum exceeds u * R; tokens without
+            // residual mass cannot be drawn; lastpos covers a crossing lost to rounding at the chunk end
+            const int base = (jstar * THREADS + tid) * EPV;
 #pragma unroll
-                for (int w = 0; w < NW; ++w) R += smem[w * NVEC + j];
-            }
-            int cand = INT_MAX, lastpos = -1;
-            if (R > 0.0) {
-                // chunk that holds the crossing of u * R (token order = chunk order, then lane order)
-                const double thr = u_res * R;
-                int jstar = -1, jlast = 0;
-                double before = 0.0, run = 0.0;
-#pragma unroll
-                for (int j = 0; j < NVEC; ++j) {
-                    double tot = 0.0;
-#pragma unroll
-                    for (int w = 0; w < NW; ++w) tot += smem[w * NVEC + j];
-                    if (jstar < 0 && run + tot > thr) { jstar = j; before = run; }
-                    if (tot > 0.0) jlast = j;
-                    if (jstar < 0) run += tot;
+            for (int k = 0; k < EPV; ++k) {
+                cum += (double)r[k];
+                if (r[k] > 0.f) {
+                    lastpos = base + k;
+                    if (cum > thr && cand == INT_MAX) cand = base + k;
                 }
-                if (jstar < 0) { jstar = jlast; before = run; }    // unreachable for u < 1; keeps the draw valid
-                // E2: the lane's residuals inside that chunk, recomputed exactly as in E1
-                float r[EPV];
-                residuals(load_vec_at(crow, jstar, tid_e), load_vec_at(trow, jstar, tid_e), jstar, r);
-                float s = 0.f;
-#pragma unroll
-                for (int k = 0; k < EPV; ++k) s += r[k];
-                const double incl = wave_scan((double)s);
-                if (lane == 63) smem[NW * NVEC + wave] = incl;
-                __syncthreads();
-                double cum = before + (incl - (double)s);
-#pragma unroll
-                for (int w = 0; w < NW; ++w)
-                    if (w < wave) cum += smem[NW * NVEC + w];
-                // smallest token of the chunk whose inclusive running sum exceeds u * R; tokens without
-                // residual mass cannot be drawn; lastpos covers a crossing lost to rounding at the chunk end
-                const int base = (jstar * THREADS + tid_e) * EPV;
-#pragma unroll
-                for (int k = 0; k < EPV; ++k) {
-                    cum += (double)r[k];
-                    if (r[k] > 0.f) {
-                        lastpos = base + k;
-                        if (cum > thr && cand == INT_MAX) cand = base + k;
-                    }
-                }
-            } else {
-                // every residual rounded to zero (q == p to working precision): the draw degenerates
-                // to the lowest-index arg-max of q; this path is practically never taken
-                for (int i = tid; i < V; i += THREADS)
-                    if (load_logit(trow, i) == mt) { cand = i; break; }
             }
-            cand = wave_min_i(cand);
-            lastpos = wave_max_i(lastpos);
-            if (lane == 0) { smem_i[wave * 2] = cand; smem_i[wave * 2 + 1] = lastpos; }
+        } else {
+            // every residual rounded to zero (q == p to working precision): the draw degenerates to the
+            // lowest-index arg-max of q; this path is practically never taken
+            float mt = -INFINITY;
+            for (int i = tid; i < V; i += THREADS) mt = fmaxf(mt, load_logit(trow, i));
+            mt = wave_max(mt);
+            if (lane == 0) sm_e[NW * MAXCH + wave] = (double)mt;
             __syncthreads();
-            if (tid == 0) {
-                int c0 = smem_i[0], l0 = smem_i[1];
 #pragma unroll
-                for (int w = 1; w < NW; ++w) { c0 = min(c0, smem_i[w * 2]); l0 = max(l0, smem_i[w * 2 + 1]); }
-                int id = (c0 != INT_MAX) ? c0 : l0;
-                if (id < 0) id = 0;
-                A.row_id[row] = id;
-            }
+            for (int w = 0; w < NW; ++w) mt = fmaxf(mt, (float)sm_e[NW * MAXCH + w]);
+            for (int i = tid; i < V; i += THREADS)
+                if (load_logit(trow, i) == mt) { cand = i; break; }
+        }
+        cand = wave_min_i(cand);
+        lastpos = wave_max_i(lastpos);
+        if (lane == 0) { sm_i[wave * 2] = cand; sm_i[wave * 2 + 1] = lastpos; }
+        __syncthreads();
+        if (tid == 0) {
+            int c0 = sm_i[0], l0 = sm_i[1];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) { c0 = min(c0, sm_i[w * 2]); l0 = max(l0, sm_i[w * 2 + 1]); }
+            int id = (c0 != INT_MAX) ? c0 : l0;
+            if (id < 0) id = 0;
+            A.row_id[row] = id;
         }
     }
 }
@@ -634,59 +763,60 @@ __global__ __launch_bounds__(256) void window_kernel(const uint8_t* __restrict__
     if (resampled_id) resampled_id[w] = (lo + n < hi) ? row_id[lo + n] : -1;
 }
 
-// ---- dense export (tests / debugging): same per-token arithmetic, three sweeps over global memory --------
-
-template <typename T>
-__device__ __forceinline__ float load_elt(const T* p, int i)
-{
-    if constexpr (sizeof(T) == 4) return reinterpret_cast<const float*>(p)[i];
-    else return bits_f((uint32_t)reinterpret_cast<const uint16_t*>(p)[i] << 16);
-}
+// ---- dense export (tests / debugging): same per-token arithmetic, sweeps over global memory ---------------
 
 template <typename T>
 __global__ __launch_bounds__(256) void dense_kernel(const RowArgs A, float* __restrict__ p_lo,
                                                     float* __restrict__ p_mid, float* __restrict__ p_hi)
 {
     constexpr int NW = 4;
-    __shared__ double smem[NW * 5];
+    __shared__ double smem[NW];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t row = blockIdx.x;
     const int V = A.V;
     const T* c = static_cast<const T*>(A.draft) + row * A.stride;
 
-    float m = -INFINITY;
-    for (int i = tid; i < V; i += 256) m = fmaxf(m, load_elt(c, i));
-    m = block_max<NW>(m, smem, lane, wave);
+    auto block_sum = [&](double v) -> double {
+        v = wave_sum(v);
+        __syncthreads();
+        if (lane == 0) smem[wave] = v;
+        __syncthreads();
+        return (smem[0] + smem[1]) + (smem[2] + smem[3]);
+    };
 
-    double s1[1] = {0.0};
-    {
-        double acc = 0.0;
-        for (int i = tid; i < V; i += 256) acc += (double)exp_shifted(load_elt(c, i), m);
-        s1[0] = acc;
-    }
-    block_sum<NW, 1>(s1, smem, lane, wave);
-    const double S = s1[0];
+    float m = -INFINITY;
+    for (int i = tid; i < V; i += 256) m = fmaxf(m, load_logit(c, i));
+    m = wave_max(m);
+    __syncthreads();
+    if (lane == 0) smem[wave] = (double)m;
+    __syncthreads();
+    m = fmaxf(fmaxf((float)smem[0], (float)smem[1]), fmaxf((float)smem[2], (float)smem[3]));
+    const float n = ref_of(m);
+
+    double acc = 0.0;
+    for (int i = tid; i < V; i += 256) acc += (double)exp2_ref(load_logit(c, i), n);
+    const double S = block_sum(acc);
 
     const FuseRow fr = fuse_row(S, A.a, A.b);
-    double q5[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    double q5[5];
     {
         double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0, a4 = 0.0;
         for (int i = tid; i < V; i += 256) {
             float gl, gw;
-            fuse_token(exp_shifted(load_elt(c, i), m), fr, gl, gw);
+            fuse_token(exp2_ref(load_logit(c, i), n), fr, gl, gw);
             const double dl = (double)gl, dw = (double)gw;
             a0 += dl; a1 += dw;
             a2 = fma(dl, dl, a2); a3 = fma(dw, dw, a3); a4 = fma(dl, dw, a4);
         }
-        q5[0] = a0; q5[1] = a1; q5[2] = a2; q5[3] = a3; q5[4] = a4;
+        q5[0] = block_sum(a0); q5[1] = block_sum(a1); q5[2] = block_sum(a2);
+        q5[3] = block_sum(a3); q5[4] = block_sum(a4);
     }
-    block_sum<NW, 5>(q5, smem, lane, wave);
-    const RowScore rs = finish_score(q5, S, A);
+    const RowScore rs = finish_score(q5, S, false, A);
 
     const float Bc = (float)(A.b / S), Wc = (float)((A.a - A.b) / S), invS = (float)(1.0 / S);
     const float al = (float)rs.alpha_l, au = (float)rs.alpha_u;
     for (int i = tid; i < V; i += 256) {
-        const float e = exp_shifted(load_elt(c, i), m);
+        const float e = exp2_ref(load_logit(c, i), n);
         float gl, gw;
         fuse_token(e, fr, gl, gw);
         const float pl = Bc * gl;
@@ -700,39 +830,85 @@ __global__ __launch_bounds__(256) void dense_kernel(const RowArgs A, float* __re
 
 // ---- dispatch ---------------------------------------------------------------------------------------------
 
-template <typename T, int THREADS, int NVEC>
-hipError_t launch_cfg(Mode mode, const RowArgs& a, hipStream_t s)
+// Compute units of the current device (asked once per device, then cached).
+int compute_units()
 {
-    const dim3 grid((unsigned)a.N), block(THREADS);
-    switch (mode) {
-    case Mode::Quantify: hipLaunchKernelGGL((row_kernel<T, THREADS, NVEC, true, false>), grid, block, 0, s, a); break;
-    case Mode::Verify:   hipLaunchKernelGGL((row_kernel<T, THREADS, NVEC, false, true>), grid, block, 0, s, a); break;
-    case Mode::Fused:    hipLaunchKernelGGL((row_kernel<T, THREADS, NVEC, true, true>), grid, block, 0, s, a); break;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+    static int cache[64] = {0};
+    if (cache[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+            cus = 256;
+        cache[dev] = cus;
     }
+    return cache[dev];
+}
+
+template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V>
+hipError_t launch_stream_kernel(const RowArgs& a, hipStream_t s)
+{
+    // One wave of resident workgroups, each walking over rows with stride gridDim.x.  The register
+    // budget the kernel was compiled for fixes how many fit: target_waves() waves per SIMD, and a
+    // workgroup puts THREADS / 256 waves on each of the four SIMDs of a compute unit.
+    constexpr int per_cu = target_waves<T, THREADS, NVEC, DO_V>() / (THREADS / 256);
+    const int64_t resident = (int64_t)per_cu * compute_units();
+    const unsigned grid = (unsigned)(a.N < resident ? a.N : resident);
+    hipLaunchKernelGGL((stream_kernel<T, THREADS, NVEC, DO_Q, DO_V>), dim3(grid), dim3(THREADS), 0, s, a);
     return hipGetLastError();
 }
 
+template <typename T, int THREADS, int NVEC>
+hipError_t launch_stream_cfg(Mode mode, const RowArgs& a, hipStream_t s)
+{
+    switch (mode) {
+    case Mode::Quantify: return launch_stream_kernel<T, THREADS, NVEC, true, false>(a, s);
+    case Mode::Verify:   return launch_stream_kernel<T, THREADS, NVEC, false, true>(a, s);
+    case Mode::Fused:    return launch_stream_kernel<T, THREADS, NVEC, true, true>(a, s);
+    }
+    return hipErrorInvalidValue;
+}
+
 template <typename T>
-hipError_t launch_typed(Mode mode, const RowArgs& a, hipStream_t s)
+hipError_t launch_stream_typed(Mode mode, const RowArgs& a, hipStream_t s)
 {
     const int vecs = (a.V + Elt<T>::kPerVec - 1) / Elt<T>::kPerVec;   // 16-byte vectors per row
-    if (vecs <= 256 * 1)  return launch_cfg<T, 256, 1>(mode, a, s);
-    if (vecs <= 256 * 2)  return launch_cfg<T, 256, 2>(mode, a, s);
-    if (vecs <= 256 * 4)  return launch_cfg<T, 256, 4>(mode, a, s);
-    if (vecs <= 256 * 8)  return launch_cfg<T, 256, 8>(mode, a, s);
-    if (vecs <= 256 * 16) return launch_cfg<T, 256, 16>(mode, a, s);
-    if (vecs <= 1024 * 8) return launch_cfg<T, 1024, 8>(mode, a, s);
+    if (vecs <= 256 * 1)  return launch_stream_cfg<T, 256, 1>(mode, a, s);
+    if (vecs <= 256 * 2)  return launch_stream_cfg<T, 256, 2>(mode, a, s);
+    if (vecs <= 256 * 4)  return launch_stream_cfg<T, 256, 4>(mode, a, s);
+    if (vecs <= 256 * 8)  return launch_stream_cfg<T, 256, 8>(mode, a, s);
+    if (vecs <= 256 * 16) return launch_stream_cfg<T, 256, 16>(mode, a, s);
+    if (vecs <= 1024 * 8) return launch_stream_cfg<T, 1024, 8>(mode, a, s);
     return hipErrorInvalidValue;
+}
+
+template <typename T>
+hipError_t launch_finish_typed(Mode mode, const RowArgs& a, hipStream_t s)
+{
+    const dim3 grid((unsigned)a.N);
+    if (mode == Mode::Quantify)
+        hipLaunchKernelGGL((finish_kernel<T, 64>), grid, dim3(64), 0, s, a, 1, 0);
+    else
+        hipLaunchKernelGGL((finish_kernel<T, 256>), grid, dim3(256), 0, s, a, mode == Mode::Fused ? 1 : 0, 1);
+    return hipGetLastError();
 }
 
 }  // namespace
 
 int max_vocab(int dtype) { return dtype == 0 ? 1024 * 8 * 4 : 1024 * 8 * 8; }
 
-hipError_t launch_rows(Mode mode, int dtype, const RowArgs& args, hipStream_t stream)
+hipError_t launch_stream(Mode mode, int dtype, const RowArgs& args, hipStream_t stream)
 {
     if (args.N <= 0) return hipSuccess;
-    return dtype == 0 ? launch_typed<float>(mode, args, stream) : launch_typed<bf16_t>(mode, args, stream);
+    return dtype == 0 ? launch_stream_typed<float>(mode, args, stream)
+                      : launch_stream_typed<bf16_t>(mode, args, stream);
+}
+
+hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, hipStream_t stream)
+{
+    if (args.N <= 0) return hipSuccess;
+    return dtype == 0 ? launch_finish_typed<float>(mode, args, stream)
+                      : launch_finish_typed<bf16_t>(mode, args, stream);
 }
 
 hipError_t launch_windows(const uint8_t* accept, const int32_t* row_id, int64_t N, int32_t K,

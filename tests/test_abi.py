@@ -60,8 +60,9 @@ def _params(L, **kw):
 FAKE = 0x7f0000000000          # 16-byte aligned, never dereferenced on an error path
 
 
-def _quantify(L, p, draft=FAKE, N=4, out=FAKE + 4096):
-    return L.ciar_quantify(draft, None, N, ctypes.byref(p), out, None, None, None, None, None, None, None)
+def _quantify(L, p, draft=FAKE, N=4, out=FAKE + 4096, ws=FAKE + 8192, wsb=1 << 20):
+    return L.ciar_quantify(draft, None, N, ctypes.byref(p), out, None, None, None, None, None, None,
+                           ws, wsb, None)
 
 
 def test_argument_errors_are_reported_before_any_launch(L):
@@ -85,7 +86,11 @@ def test_argument_errors_are_reported_before_any_launch(L):
     assert _quantify(L, _params(L), draft=FAKE + 4) == EALIGN
     assert _quantify(L, _params(L), N=-1) == EINVAL
     assert _quantify(L, _params(L), out=None) == EINVAL and "output" in last_error()
-    assert L.ciar_quantify(FAKE, None, 4, None, FAKE, None, None, None, None, None, None, None) == EINVAL
+    assert L.ciar_quantify(FAKE, None, 4, None, FAKE, None, None, None, None, None, None, FAKE, 4096, None) == EINVAL
+    # the workspace carries the per-row statistics between the two kernels: always required
+    assert _quantify(L, _params(L), ws=None, wsb=0) == EWORK and "workspace" in last_error()
+    assert _quantify(L, _params(L), wsb=64) == EWORK
+    assert _quantify(L, _params(L), ws=FAKE + 8) == EALIGN
     # verify: required inputs, workspace rules
     p = _params(L)
     a = ctypes.byref(p)
@@ -94,7 +99,7 @@ def test_argument_errors_are_reported_before_any_launch(L):
     assert L.ciar_verify(FAKE, FAKE, FAKE, None, FAKE, 4, a, FAKE, FAKE, None, None, None, 0, None) == EINVAL
     assert L.ciar_verify(FAKE, FAKE, FAKE, FAKE, None, 4, a, FAKE, FAKE, None, None, None, 0, None) == EINVAL
     assert L.ciar_verify(FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, None, None, None, None, None, 0, None) == EINVAL
-    # window outputs without per-row buffers need the workspace
+    assert L.ciar_verify(FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, FAKE, FAKE, None, None, None, 0, None) == EWORK
     assert L.ciar_verify(FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, None, None, FAKE, FAKE, None, 0, None) == EWORK
     assert L.ciar_verify(FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, None, None, FAKE, FAKE, FAKE, 8, None) == EWORK
     assert L.ciar_verify(FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, None, None, FAKE, FAKE, FAKE + 8, 4096, None) == EALIGN
@@ -116,7 +121,7 @@ def test_workspace_size(L):
     assert f(0, ctypes.byref(p)) == 0 and f(-5, ctypes.byref(p)) == 0
     for N in (1, 7, 256, 2048, 32768):
         b = f(N, ctypes.byref(p))
-        assert b % 256 == 0 and b >= 5 * N
+        assert b % 256 == 0 and b >= 77 * N
 
 
 def test_version_and_error_strings(L):

@@ -37,7 +37,7 @@ def _run_case(ciar, oracle, draft, target, ids, ua, ur, P, vocab=None, tag="", h
     N = draft.shape[0]
     ws = torch.empty(ciar.workspace_bytes(N, P.to_c(draft, vocab)) or 16, dtype=torch.uint8, device=draft.device)
     fused = ciar.quantify_verify(draft, target, ids, ua, ur, P, vocab=vocab, workspace=ws)
-    qonly = ciar.quantify(draft, ids, P, vocab=vocab)
+    qonly = ciar.quantify(draft, ids, P, vocab=vocab, workspace=ws)
     vonly = ciar.verify(draft, target, ids, ua, ur, P, vocab=vocab, workspace=ws)
     torch.cuda.synchronize()
     # the three entry points run the same arithmetic: bit-identical outputs
@@ -265,7 +265,7 @@ def test_null_outputs_and_workspace_paths(ciar, oracle):
     # a single quantify output
     sc = torch.empty(43, dtype=torch.float32, device="cuda")
     rc = L.ciar_quantify(_ptr(c), None, 43, ctypes.byref(cp), None, None, None, None, None, _ptr(sc), None,
-                         _stream(None))
+                         _ptr(ws), ws.numel(), _stream(None))
     assert rc == 0, ciar.last_error()
     torch.cuda.synchronize()
     assert torch.equal(sc, ciar.quantify(c, ids, P)["score"])
