@@ -153,6 +153,31 @@ int ciar_quantify_verify(const void* draft_logits, const void* target_logits,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The two stages of the calls above, on their own, for callers that want to time them or to put
+ * other work between them.  ciar_quantify, ciar_verify and ciar_quantify_verify are exactly
+ * ciar_stream_rows followed by ciar_finish_rows (same kernels, same launch configuration).
+ *
+ * ciar_stream_rows   the streaming kernel: reads every logit row once from HBM and leaves the
+ *                    per-row statistics (max-trick references, partition sums, the InterFuse sums)
+ *                    in `workspace`.  target_logits = NULL: quantify only (with_intervals must be 1);
+ *                    with_intervals = 0: verify only; otherwise both.
+ * ciar_finish_rows   the finishing kernel (+ the window epilogue when a window output is given):
+ *                    arguments as ciar_quantify_verify; it must be given the workspace a
+ *                    ciar_stream_rows call on the same rows and parameters has filled, the same
+ *                    target_logits (or NULL), and quantify outputs iff with_intervals was 1.
+ */
+int ciar_stream_rows(const void* draft_logits, const void* target_logits, int with_intervals, int64_t N,
+                     const ciar_params* params, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+int ciar_finish_rows(const void* draft_logits, const void* target_logits, const int32_t* draft_ids,
+                     const float* u_accept, const float* u_resample, int64_t N, const ciar_params* params,
+                     float* p_lo, float* p_mid, float* p_hi,
+                     float* omega, float* sigma, float* score, uint8_t* flags,
+                     uint8_t* accept, int32_t* row_resample_id,
+                     int32_t* accept_len, int32_t* resampled_id,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Window epilogue on its own (the last step of ciar_verify / ciar_quantify_verify, which run it when
  * a window output is requested): from the per-row results of N rows,
  *   accept_len[w]   = number of leading rows with accept != 0 in window w = rows [wK, min((w+1)K, N))

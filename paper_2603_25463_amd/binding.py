@@ -59,6 +59,10 @@ def lib() -> ctypes.CDLL:
         L.ciar_verify.argtypes = [vp, vp, vp, vp, vp, i64, pp] + [vp] * 4 + [vp, sz, vp]
         L.ciar_quantify_verify.restype = ctypes.c_int
         L.ciar_quantify_verify.argtypes = [vp, vp, vp, vp, vp, i64, pp] + [vp] * 11 + [vp, sz, vp]
+        L.ciar_stream_rows.restype = ctypes.c_int
+        L.ciar_stream_rows.argtypes = [vp, vp, ctypes.c_int, i64, pp, vp, sz, vp]
+        L.ciar_finish_rows.restype = ctypes.c_int
+        L.ciar_finish_rows.argtypes = [vp, vp, vp, vp, vp, i64, pp] + [vp] * 11 + [vp, sz, vp]
         L.ciar_window_epilogue.restype = ctypes.c_int
         L.ciar_window_epilogue.argtypes = [vp, vp, i64, pp, vp, vp, vp]
         L.ciar_dense_intervals.restype = ctypes.c_int
@@ -209,6 +213,39 @@ def quantify_verify(draft, target, ids, u_accept, u_resample, params: Params, vo
         _ptr(o["p_lo"]), _ptr(o["p_mid"]), _ptr(o["p_hi"]), _ptr(o["omega"]), _ptr(o["sigma"]),
         _ptr(o["score"]), _ptr(o["flags"]), _ptr(o["accept"]), _ptr(o["row_id"]), _ptr(o["accept_len"]),
         _ptr(o["resampled_id"]), _ptr(workspace), wsb, _stream(stream)))
+    return o
+
+
+def stream_rows(draft, target, with_intervals: bool, params: Params, workspace: torch.Tensor,
+                vocab: int | None = None, stream=None) -> None:
+    """``ciar_stream_rows``: the streaming kernel alone; leaves the per-row statistics in ``workspace``."""
+    _need_cuda(draft, target, workspace)
+    cp = params.to_c(draft, vocab)
+    _check(lib().ciar_stream_rows(_ptr(draft), _ptr(target), int(bool(with_intervals)), draft.shape[0],
+                                  ctypes.byref(cp), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                  _stream(stream)))
+
+
+def finish_rows(draft, target, ids, u_accept, u_resample, params: Params, workspace: torch.Tensor,
+                with_intervals: bool = True, vocab: int | None = None, stream=None, out: dict | None = None) -> dict:
+    """``ciar_finish_rows``: the finishing kernel and the window epilogue on a workspace filled by
+    ``stream_rows`` (same rows, same parameters, same ``with_intervals``)."""
+    _need_cuda(draft, target, ids, u_accept, u_resample, workspace)
+    N, dev = draft.shape[0], draft.device
+    cp = params.to_c(draft, vocab)
+    o = dict(out) if out else {}
+    if target is not None:
+        o = _verify_outputs(N, cp.window, dev, o)
+    if with_intervals:
+        for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score"):
+            o.setdefault(k, torch.empty(N, dtype=torch.float32, device=dev))
+        o.setdefault("flags", torch.empty(N, dtype=torch.uint8, device=dev))
+    g = lambda k: _ptr(o.get(k))
+    _check(lib().ciar_finish_rows(
+        _ptr(draft), _ptr(target), _ptr(ids), _ptr(u_accept), _ptr(u_resample), N, ctypes.byref(cp),
+        g("p_lo"), g("p_mid"), g("p_hi"), g("omega"), g("sigma"), g("score"), g("flags"), g("accept"),
+        g("row_id"), g("accept_len"), g("resampled_id"), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)))
     return o
 
 

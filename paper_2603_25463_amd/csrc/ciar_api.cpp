@@ -142,32 +142,94 @@ int check_workspace(int64_t N, const ciar_params* p, void* workspace, size_t wor
     return CIAR_OK;
 }
 
-// Shared tail of ciar_verify and ciar_quantify_verify.
-int run_verify(ciar::Mode mode, ciar::RowArgs& a, const ciar_params* p, uint8_t* accept, int32_t* row_id,
-               int32_t* accept_len, int32_t* resampled_id, void* workspace, size_t workspace_bytes,
-               hipStream_t stream)
+// Everything the three public passes share: validation, workspace carving, the two stages.
+struct Call {
+    const void* draft; const void* target; const int32_t* ids; const float* u_accept; const float* u_resample;
+    int64_t N; const ciar_params* params;
+    float* p_lo; float* p_mid; float* p_hi; float* omega; float* sigma; float* score; uint8_t* flags;
+    uint8_t* accept; int32_t* row_id; int32_t* accept_len; int32_t* resampled_id;
+    void* workspace; size_t workspace_bytes; hipStream_t stream;
+};
+
+bool wants_intervals(const Call& c)
 {
-    const int64_t N = a.N;
-    if (int rc = check_workspace(N, p, workspace, workspace_bytes)) return rc;
-    if (N == 0) return CIAR_OK;
-    const bool windows = accept_len || resampled_id;
-    char* w = static_cast<char*>(workspace);
-    a.stats = reinterpret_cast<ciar::RowStats*>(w);
-    uint8_t* acc = accept;
-    int32_t* rid = row_id;
-    if (windows && !acc) acc = reinterpret_cast<uint8_t*>(w + stats_bytes(N) + ids_bytes(N));
-    if (resampled_id && !rid) rid = reinterpret_cast<int32_t*>(w + stats_bytes(N));
-    a.accept = acc;
-    a.row_id = rid;
-    hipError_t e = ciar::launch_stream(mode, p->dtype, a, stream);
+    return c.p_lo || c.p_mid || c.p_hi || c.omega || c.sigma || c.score || c.flags;
+}
+bool wants_verify(const Call& c) { return c.accept || c.row_id || c.accept_len || c.resampled_id; }
+
+// Validates what every stage needs and fills `a` (without the per-row output pointers).
+int prepare(const Call& c, ciar::Mode mode, ciar::RowArgs* a)
+{
+    Resolved r;
+    if (int rc = check_params(c.params, &r)) return rc;
+    if (c.N < 0) return fail(CIAR_EINVAL, "N is negative");
+    if (c.N > 0x7fffffffLL) return fail(CIAR_EUNSUPPORTED, "N exceeds 2^31 - 1 rows per call");
+    if (int rc = check_rows(c.draft, "draft_logits")) return rc;
+    if (mode != ciar::Mode::Quantify)
+        if (int rc = check_rows(c.target, "target_logits")) return rc;
+    *a = base_args(c.params, r, c.N);
+    a->draft = c.draft;
+    a->target = c.target;
+    return CIAR_OK;
+}
+
+int run_stream(const Call& c, ciar::Mode mode)
+{
+    ciar::RowArgs a;
+    if (int rc = prepare(c, mode, &a)) return rc;
+    if (int rc = check_workspace(c.N, c.params, c.workspace, c.workspace_bytes)) return rc;
+    if (c.N == 0) return CIAR_OK;
+    a.stats = static_cast<ciar::RowStats*>(c.workspace);
+    const hipError_t e = ciar::launch_stream(mode, c.params->dtype, a, c.stream);
     if (e != hipSuccess) return hip_fail(e, "streaming kernel launch");
-    e = ciar::launch_finish(mode, p->dtype, a, stream);
+    return CIAR_OK;
+}
+
+int run_finish(const Call& c, ciar::Mode mode)
+{
+    ciar::RowArgs a;
+    if (int rc = prepare(c, mode, &a)) return rc;
+    if (mode != ciar::Mode::Quantify) {
+        if (!c.ids) return fail(CIAR_EINVAL, "draft_ids is NULL");
+        if (!c.u_accept) return fail(CIAR_EINVAL, "u_accept is NULL");
+        if (!c.u_resample) return fail(CIAR_EINVAL, "u_resample is NULL");
+    }
+    if (!wants_intervals(c) && !wants_verify(c)) return fail(CIAR_EINVAL, "every output pointer is NULL");
+    if (int rc = check_workspace(c.N, c.params, c.workspace, c.workspace_bytes)) return rc;
+    if (c.N == 0) return CIAR_OK;
+    const int64_t N = c.N;
+    char* w = static_cast<char*>(c.workspace);
+    a.stats = reinterpret_cast<ciar::RowStats*>(w);
+    a.ids = c.ids; a.u_accept = c.u_accept; a.u_resample = c.u_resample;
+    a.p_lo = c.p_lo; a.p_mid = c.p_mid; a.p_hi = c.p_hi;
+    a.omega = c.omega; a.sigma = c.sigma; a.score = c.score; a.flags = c.flags;
+    const bool windows = c.accept_len || c.resampled_id;
+    a.accept = c.accept;
+    a.row_id = c.row_id;
+    if (windows && !a.accept) a.accept = reinterpret_cast<uint8_t*>(w + stats_bytes(N) + ids_bytes(N));
+    if (c.resampled_id && !a.row_id) a.row_id = reinterpret_cast<int32_t*>(w + stats_bytes(N));
+    hipError_t e = ciar::launch_finish(mode, c.params->dtype, a, c.stream);
     if (e != hipSuccess) return hip_fail(e, "finishing kernel launch");
     if (windows) {
-        e = ciar::launch_windows(acc, rid, N, p->window, accept_len, resampled_id, stream);
+        e = ciar::launch_windows(a.accept, a.row_id, N, c.params->window, c.accept_len, c.resampled_id, c.stream);
         if (e != hipSuccess) return hip_fail(e, "window kernel launch");
     }
     return CIAR_OK;
+}
+
+int run_both(const Call& c, ciar::Mode mode)
+{
+    // validate the finishing stage's arguments before anything is launched
+    ciar::RowArgs a;
+    if (int rc = prepare(c, mode, &a)) return rc;
+    if (mode != ciar::Mode::Quantify) {
+        if (!c.ids) return fail(CIAR_EINVAL, "draft_ids is NULL");
+        if (!c.u_accept) return fail(CIAR_EINVAL, "u_accept is NULL");
+        if (!c.u_resample) return fail(CIAR_EINVAL, "u_resample is NULL");
+    }
+    if (!wants_intervals(c) && !wants_verify(c)) return fail(CIAR_EINVAL, "every output pointer is NULL");
+    if (int rc = run_stream(c, mode)) return rc;
+    return run_finish(c, mode);
 }
 
 }  // namespace
@@ -200,27 +262,10 @@ int ciar_quantify(const void* draft_logits, const int32_t* draft_ids, int64_t N,
                   float* p_lo, float* p_mid, float* p_hi, float* omega, float* sigma, float* score,
                   uint8_t* flags, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    Resolved r;
-    if (int rc = check_params(params, &r)) return rc;
-    if (N < 0) return fail(CIAR_EINVAL, "N is negative");
-    if (int rc = check_rows(draft_logits, "draft_logits")) return rc;
-    if (!p_lo && !p_mid && !p_hi && !omega && !sigma && !score && !flags)
-        return fail(CIAR_EINVAL, "every output pointer is NULL");
-    if (N > 0x7fffffffLL) return fail(CIAR_EUNSUPPORTED, "N exceeds 2^31 - 1 rows per call");
-    ciar::RowArgs a = base_args(params, r, N);
-    a.draft = draft_logits;
-    a.ids = draft_ids;
-    a.p_lo = p_lo; a.p_mid = p_mid; a.p_hi = p_hi;
-    a.omega = omega; a.sigma = sigma; a.score = score; a.flags = flags;
-    if (int rc = check_workspace(N, params, workspace, workspace_bytes)) return rc;
-    if (N == 0) return CIAR_OK;
-    a.stats = static_cast<ciar::RowStats*>(workspace);
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    hipError_t e = ciar::launch_stream(ciar::Mode::Quantify, params->dtype, a, stream);
-    if (e != hipSuccess) return hip_fail(e, "streaming kernel launch");
-    e = ciar::launch_finish(ciar::Mode::Quantify, params->dtype, a, stream);
-    if (e != hipSuccess) return hip_fail(e, "finishing kernel launch");
-    return CIAR_OK;
+    const Call c{draft_logits, nullptr, draft_ids, nullptr, nullptr, N, params, p_lo, p_mid, p_hi, omega, sigma,
+                 score, flags, nullptr, nullptr, nullptr, nullptr, workspace, workspace_bytes,
+                 static_cast<hipStream_t>(hip_stream)};
+    return run_both(c, ciar::Mode::Quantify);
 }
 
 int ciar_verify(const void* draft_logits, const void* target_logits, const int32_t* draft_ids,
@@ -228,25 +273,10 @@ int ciar_verify(const void* draft_logits, const void* target_logits, const int32
                 uint8_t* accept, int32_t* row_resample_id, int32_t* accept_len, int32_t* resampled_id,
                 void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    Resolved r;
-    if (int rc = check_params(params, &r)) return rc;
-    if (N < 0) return fail(CIAR_EINVAL, "N is negative");
-    if (int rc = check_rows(draft_logits, "draft_logits")) return rc;
-    if (int rc = check_rows(target_logits, "target_logits")) return rc;
-    if (!draft_ids) return fail(CIAR_EINVAL, "draft_ids is NULL");
-    if (!u_accept) return fail(CIAR_EINVAL, "u_accept is NULL");
-    if (!u_resample) return fail(CIAR_EINVAL, "u_resample is NULL");
-    if (!accept && !row_resample_id && !accept_len && !resampled_id)
-        return fail(CIAR_EINVAL, "every output pointer is NULL");
-    if (N > 0x7fffffffLL) return fail(CIAR_EUNSUPPORTED, "N exceeds 2^31 - 1 rows per call");
-    ciar::RowArgs a = base_args(params, r, N);
-    a.draft = draft_logits;
-    a.target = target_logits;
-    a.ids = draft_ids;
-    a.u_accept = u_accept;
-    a.u_resample = u_resample;
-    return run_verify(ciar::Mode::Verify, a, params, accept, row_resample_id, accept_len, resampled_id,
-                      workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+    const Call c{draft_logits, target_logits, draft_ids, u_accept, u_resample, N, params, nullptr, nullptr, nullptr,
+                 nullptr, nullptr, nullptr, nullptr, accept, row_resample_id, accept_len, resampled_id, workspace,
+                 workspace_bytes, static_cast<hipStream_t>(hip_stream)};
+    return run_both(c, ciar::Mode::Verify);
 }
 
 int ciar_quantify_verify(const void* draft_logits, const void* target_logits, const int32_t* draft_ids,
@@ -255,28 +285,39 @@ int ciar_quantify_verify(const void* draft_logits, const void* target_logits, co
                          uint8_t* flags, uint8_t* accept, int32_t* row_resample_id, int32_t* accept_len,
                          int32_t* resampled_id, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    Resolved r;
-    if (int rc = check_params(params, &r)) return rc;
-    if (N < 0) return fail(CIAR_EINVAL, "N is negative");
-    if (int rc = check_rows(draft_logits, "draft_logits")) return rc;
-    if (int rc = check_rows(target_logits, "target_logits")) return rc;
-    if (!draft_ids) return fail(CIAR_EINVAL, "draft_ids is NULL");
-    if (!u_accept) return fail(CIAR_EINVAL, "u_accept is NULL");
-    if (!u_resample) return fail(CIAR_EINVAL, "u_resample is NULL");
-    if (!p_lo && !p_mid && !p_hi && !omega && !sigma && !score && !flags && !accept && !row_resample_id &&
-        !accept_len && !resampled_id)
-        return fail(CIAR_EINVAL, "every output pointer is NULL");
-    if (N > 0x7fffffffLL) return fail(CIAR_EUNSUPPORTED, "N exceeds 2^31 - 1 rows per call");
-    ciar::RowArgs a = base_args(params, r, N);
-    a.draft = draft_logits;
-    a.target = target_logits;
-    a.ids = draft_ids;
-    a.u_accept = u_accept;
-    a.u_resample = u_resample;
-    a.p_lo = p_lo; a.p_mid = p_mid; a.p_hi = p_hi;
-    a.omega = omega; a.sigma = sigma; a.score = score; a.flags = flags;
-    return run_verify(ciar::Mode::Fused, a, params, accept, row_resample_id, accept_len, resampled_id,
-                      workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+    const Call c{draft_logits, target_logits, draft_ids, u_accept, u_resample, N, params, p_lo, p_mid, p_hi, omega,
+                 sigma, score, flags, accept, row_resample_id, accept_len, resampled_id, workspace, workspace_bytes,
+                 static_cast<hipStream_t>(hip_stream)};
+    return run_both(c, ciar::Mode::Fused);
+}
+
+int ciar_stream_rows(const void* draft_logits, const void* target_logits, int with_intervals, int64_t N,
+                     const ciar_params* params, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!target_logits && !with_intervals)
+        return fail(CIAR_EINVAL, "neither target_logits nor with_intervals: nothing to compute");
+    const ciar::Mode mode = !target_logits ? ciar::Mode::Quantify
+                                           : (with_intervals ? ciar::Mode::Fused : ciar::Mode::Verify);
+    Call c{};
+    c.draft = draft_logits; c.target = target_logits; c.N = N; c.params = params;
+    c.workspace = workspace; c.workspace_bytes = workspace_bytes; c.stream = static_cast<hipStream_t>(hip_stream);
+    return run_stream(c, mode);
+}
+
+int ciar_finish_rows(const void* draft_logits, const void* target_logits, const int32_t* draft_ids,
+                     const float* u_accept, const float* u_resample, int64_t N, const ciar_params* params,
+                     float* p_lo, float* p_mid, float* p_hi, float* omega, float* sigma, float* score,
+                     uint8_t* flags, uint8_t* accept, int32_t* row_resample_id, int32_t* accept_len,
+                     int32_t* resampled_id, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    const Call c{draft_logits, target_logits, draft_ids, u_accept, u_resample, N, params, p_lo, p_mid, p_hi, omega,
+                 sigma, score, flags, accept, row_resample_id, accept_len, resampled_id, workspace, workspace_bytes,
+                 static_cast<hipStream_t>(hip_stream)};
+    if (target_logits && !wants_verify(c)) return fail(CIAR_EINVAL, "target_logits given but no verify output");
+    if (!target_logits && wants_verify(c)) return fail(CIAR_EINVAL, "verify outputs need target_logits");
+    const ciar::Mode mode = !target_logits ? ciar::Mode::Quantify
+                                           : (wants_intervals(c) ? ciar::Mode::Fused : ciar::Mode::Verify);
+    return run_finish(c, mode);
 }
 
 int ciar_window_epilogue(const uint8_t* accept, const int32_t* row_resample_id, int64_t N,

@@ -28,6 +28,7 @@ def _declared_functions():
 def test_header_declares_the_expected_entry_points():
     names = _declared_functions()
     for n in ("ciar_quantify", "ciar_verify", "ciar_quantify_verify", "ciar_dense_intervals",
+              "ciar_stream_rows", "ciar_finish_rows", "ciar_window_epilogue",
               "ciar_workspace_bytes", "ciar_params_default", "ciar_last_error", "ciar_version"):
         assert n in names
 
@@ -105,6 +106,17 @@ def test_argument_errors_are_reported_before_any_launch(L):
     assert L.ciar_verify(FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, None, None, FAKE, FAKE, FAKE + 8, 4096, None) == EALIGN
     assert L.ciar_quantify_verify(FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, *([None] * 11), None, 0, None) == EINVAL
     assert L.ciar_dense_intervals(FAKE, 4, a, None, None, None, None) == EINVAL
+    # the stages on their own
+    assert L.ciar_stream_rows(FAKE, None, 0, 4, a, FAKE, 4096, None) == EINVAL      # nothing to compute
+    assert L.ciar_stream_rows(FAKE, FAKE, 1, 4, a, None, 0, None) == EWORK
+    assert L.ciar_stream_rows(None, FAKE, 1, 4, a, FAKE, 4096, None) == EINVAL
+    assert L.ciar_finish_rows(FAKE, None, FAKE, FAKE, FAKE, 4, a, *([None] * 7), FAKE, FAKE, None, None,
+                              FAKE, 4096, None) == EINVAL                            # verify outputs, no target
+    assert L.ciar_finish_rows(FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, FAKE, *([None] * 10), FAKE, 4096,
+                              None) == EINVAL                                        # target, no verify output
+    assert L.ciar_window_epilogue(None, FAKE, 4, a, FAKE, FAKE, None) == EINVAL
+    assert L.ciar_window_epilogue(FAKE, None, 4, a, FAKE, FAKE, None) == EINVAL
+    assert L.ciar_window_epilogue(FAKE, FAKE, 4, a, None, None, None) == EINVAL
 
 
 def test_empty_batch_is_ok_and_launches_nothing(L):
