@@ -93,7 +93,7 @@ void ciar_params_default(ciar_params* p);
 
 /*
  * Bytes of device workspace ciar_quantify / ciar_verify / ciar_quantify_verify need for N rows
- * (77 bytes per row, rounded up).  Always a multiple of 256; returns 0 for N <= 0.
+ * (81 bytes per row, rounded up).  Always a multiple of 256; returns 0 for N <= 0.
  */
 size_t ciar_workspace_bytes(int64_t N, const ciar_params* params);
 

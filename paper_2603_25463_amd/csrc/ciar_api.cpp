@@ -127,9 +127,18 @@ int hip_fail(hipError_t e, const char* what)
     return fail(CIAR_EHIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-// Workspace layout: [N] RowStats | [N] int32 row ids | [N] uint8 accept bits.
+// Workspace layout: [N] RowStats | [N] int32 row ids | [N] int32 rejected rows | 16 B counter | [N] uint8 accept bits.
 size_t stats_bytes(int64_t N) { return round_up((size_t)N * sizeof(ciar::RowStats), 16); }
 size_t ids_bytes(int64_t N) { return round_up((size_t)N * 4, 16); }
+
+void carve(char* w, int64_t N, ciar::RowArgs* a, int32_t** row_ids, uint8_t** accept)
+{
+    a->stats = reinterpret_cast<ciar::RowStats*>(w);
+    *row_ids = reinterpret_cast<int32_t*>(w + stats_bytes(N));
+    a->reject_list = reinterpret_cast<int32_t*>(w + stats_bytes(N) + ids_bytes(N));
+    a->reject_count = reinterpret_cast<int32_t*>(w + stats_bytes(N) + 2 * ids_bytes(N));
+    *accept = reinterpret_cast<uint8_t*>(w + stats_bytes(N) + 2 * ids_bytes(N) + 16);
+}
 
 int check_workspace(int64_t N, const ciar_params* p, void* workspace, size_t workspace_bytes)
 {
@@ -179,7 +188,8 @@ int run_stream(const Call& c, ciar::Mode mode)
     if (int rc = prepare(c, mode, &a)) return rc;
     if (int rc = check_workspace(c.N, c.params, c.workspace, c.workspace_bytes)) return rc;
     if (c.N == 0) return CIAR_OK;
-    a.stats = static_cast<ciar::RowStats*>(c.workspace);
+    int32_t* ws_ids; uint8_t* ws_accept;
+    carve(static_cast<char*>(c.workspace), c.N, &a, &ws_ids, &ws_accept);
     const hipError_t e = ciar::launch_stream(mode, c.params->dtype, a, c.stream);
     if (e != hipSuccess) return hip_fail(e, "streaming kernel launch");
     return CIAR_OK;
@@ -198,22 +208,19 @@ int run_finish(const Call& c, ciar::Mode mode)
     if (int rc = check_workspace(c.N, c.params, c.workspace, c.workspace_bytes)) return rc;
     if (c.N == 0) return CIAR_OK;
     const int64_t N = c.N;
-    char* w = static_cast<char*>(c.workspace);
-    a.stats = reinterpret_cast<ciar::RowStats*>(w);
+    int32_t* ws_ids; uint8_t* ws_accept;
+    carve(static_cast<char*>(c.workspace), N, &a, &ws_ids, &ws_accept);
     a.ids = c.ids; a.u_accept = c.u_accept; a.u_resample = c.u_resample;
     a.p_lo = c.p_lo; a.p_mid = c.p_mid; a.p_hi = c.p_hi;
     a.omega = c.omega; a.sigma = c.sigma; a.score = c.score; a.flags = c.flags;
     const bool windows = c.accept_len || c.resampled_id;
     a.accept = c.accept;
     a.row_id = c.row_id;
-    if (windows && !a.accept) a.accept = reinterpret_cast<uint8_t*>(w + stats_bytes(N) + ids_bytes(N));
-    if (c.resampled_id && !a.row_id) a.row_id = reinterpret_cast<int32_t*>(w + stats_bytes(N));
-    hipError_t e = ciar::launch_finish(mode, c.params->dtype, a, c.stream);
+    if (windows && !a.accept) a.accept = ws_accept;
+    if (c.resampled_id && !a.row_id) a.row_id = ws_ids;
+    const hipError_t e = ciar::launch_finish(mode, c.params->dtype, a, c.params->window, c.accept_len,
+                                             c.resampled_id, c.stream);
     if (e != hipSuccess) return hip_fail(e, "finishing kernel launch");
-    if (windows) {
-        e = ciar::launch_windows(a.accept, a.row_id, N, c.params->window, c.accept_len, c.resampled_id, c.stream);
-        if (e != hipSuccess) return hip_fail(e, "window kernel launch");
-    }
     return CIAR_OK;
 }
 
@@ -255,7 +262,7 @@ void ciar_params_default(ciar_params* p)
 size_t ciar_workspace_bytes(int64_t N, const ciar_params* /*params*/)
 {
     if (N <= 0) return 0;
-    return round_up(stats_bytes(N) + ids_bytes(N) + (size_t)N, 256);
+    return round_up(stats_bytes(N) + 2 * ids_bytes(N) + 16 + (size_t)N, 256);
 }
 
 int ciar_quantify(const void* draft_logits, const int32_t* draft_ids, int64_t N, const ciar_params* params,

@@ -33,6 +33,8 @@ struct RowArgs {
     uint8_t* accept;                                 // [N] or null
     int32_t* row_id;                                 // [N] or null
     RowStats* stats;                                 // [N] workspace
+    int32_t* reject_list;                            // [N] workspace: rows whose drafted token was rejected
+    int32_t* reject_count;                           // workspace: length of that list
     int64_t  N;
     int64_t  stride;            // elements between rows
     int32_t  V;
@@ -53,8 +55,10 @@ int max_vocab(int dtype);
 // Streaming pass over the rows: statistics and InterFuse sums into args.stats.
 hipError_t launch_stream(Mode mode, int dtype, const RowArgs& args, hipStream_t stream);
 
-// Per-row finishing: score, flag, reported interval, accept test, residual draw of rejected rows.
-hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, hipStream_t stream);
+// Per-row finishing: score, flag, reported interval, accept test, residual draw of rejected rows, and the
+// window outputs (either may be null) for windows of K rows.
+hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, int32_t K, int32_t* accept_len,
+                         int32_t* resampled_id, hipStream_t stream);
 
 // accept_len / resampled_id per window of K rows from the per-row results.
 hipError_t launch_windows(const uint8_t* accept, const int32_t* row_id, int64_t N, int32_t K,

@@ -1,7 +1,6 @@
 // gfx950 kernels of the CIAR quantify + verify pass.
 //
-// The pass is split in two kernels so that the kernel that touches the V-wide rows is pure
-// streaming arithmetic:
+// The pass is split so that the kernel that touches the V-wide rows is pure streaming arithmetic:
 //
 //   stream_kernel   reads every logit row exactly once from HBM and leaves ten numbers per row
 //                   (RowStats).  A workgroup of 256 lanes (1024 for the largest vocabularies) owns
@@ -11,10 +10,11 @@
 //                   set of registers, so the memory system stays busy.  Loads are interleaved over the
 //                   workgroup so that every load instruction of a wave covers 1 KiB of consecutive
 //                   memory.  Nothing V-wide is ever written back.
-//   finish_kernel   one workgroup per row: lane 0 turns RowStats into the row's outputs in fp64 (caps,
-//                   Omega, Sigma, U, flag, interval of the reported token, accept test); only for a
-//                   rejected row does the whole workgroup run the residual draw, re-reading the two
-//                   rows (~1 row in 8, served by the caches).
+//   rowfinish_kernel  one thread per row turns RowStats into the row's outputs in fp64 (caps, Omega,
+//                   Sigma, U, flag, interval of the reported token, accept test) and appends rejected
+//                   rows to a list.
+//   resample_kernel 1024-lane workgroups walk over that list (~1 row in 8) and run the residual draw,
+//                   re-reading the two rows (mostly served by the caches).
 //
 // The centre row has to be resident between its statistics pass and its interval pass: the InterFuse
 // bounds need the partition sum S of the complete row before the first bound can be formed (App.
@@ -35,7 +35,7 @@
 //      five fp64 sums per row (sum p^l, sum w and the three second moments).
 //   -- barrier: the waves exchange their five sums; lane 0 writes RowStats --
 //
-// finish_kernel, per row (Eq. uncertainty_score; Algorithm 1's threshold and verification steps):
+// rowfinish_kernel / resample_kernel, per row (Eq. uncertainty_score; Algorithm 1's threshold and verification steps):
 //   delta_i = alpha_u w_i + (alpha_u - alpha_l) p^l_i once the 0.99 / 1.01 caps alpha_l, alpha_u are
 //   known, so Omega = sum delta_i, Sigma^2 = (sum delta_i^2) / V - (Omega / V)^2, U = Omega * Sigma
 //   follow from the five sums without a second sweep over the row; flag = U > tau;
@@ -376,6 +376,9 @@ void stream_kernel(const RowArgs A)
         return *(gvec)((gbytes)(((uint64_t)hi << 32) | lo) + off);
     };
 
+    // the list of rejected rows that the finishing kernels build starts empty
+    if (DO_V && blockIdx.x == 0 && tid == 0) *A.reject_count = 0;
+
     // the row index is uniform over the workgroup: keep it in a scalar register
     int row = __builtin_amdgcn_readfirstlane((int)blockIdx.x);     // the launcher keeps gridDim.x <= N
     u32x4 tbuf[NVEC];                                              // verifier row as loaded (without prefetch: both rows in turn)
@@ -566,32 +569,47 @@ void stream_kernel(const RowArgs A)
     }
 }
 
-// ---- the finishing kernel: one workgroup per row --------------------------------------------------------------
+// ---- the finishing kernels ----------------------------------------------------------------------------------------
 
-// THREADS = 64 when no verification is asked for (lane 0 does all the work), 256 otherwise.
-template <typename T, int THREADS>
-__global__ __launch_bounds__(THREADS) void finish_kernel(const RowArgs A, const int do_q, const int do_v)
+// Window w = rows [wK, min((w+1)K, N)): accepted prefix length and the draw of the first rejected row
+// (Algorithm 1: the verified part of a drafted window and the token that replaces the first rejection).
+__device__ __forceinline__ void window_of(const uint8_t* accept, const int32_t* row_id, int64_t N, int32_t K,
+                                          int64_t w, int32_t* accept_len, int32_t* resampled_id)
 {
-    using E = Elt<T>;
-    constexpr int EPV = E::kPerVec;
-    constexpr int NW = THREADS / 64;
-    constexpr int CHUNK = THREADS * EPV;
-    constexpr int MAXCH = 64;                       // chunks of CHUNK tokens a row can have (V <= 65536)
-    constexpr int UB = 16;                          // vectors of each row in flight per lane
+    const int64_t lo = w * K;
+    const int64_t hi = (lo + K < N) ? lo + K : N;
+    int64_t n = 0;
+    while (lo + n < hi && accept[lo + n]) ++n;
+    if (accept_len) accept_len[w] = (int32_t)n;
+    if (resampled_id)
+        resampled_id[w] = (lo + n < hi) ? row_id[lo + n] : -1;
+}
 
-    __shared__ double sm_e[NW * MAXCH + NW];
-    __shared__ int    sm_i[NW * 2 + 1];
+// One thread per row: RowStats -> the row's outputs, in fp64 (Eq. uncertainty_score; Algorithm 1's threshold
+// and verification steps).  Rejected rows are appended to a list for the residual draw.
+// A workgroup covers `rows_per_block` consecutive rows.  When the window outputs are asked for, that is a
+// multiple of the window length K, so every window lies inside one workgroup: its leader thread counts the
+// accepted prefix from the accept bits the workgroup shares through LDS, and writes -1 for a window
+// without a rejection (the draw of a window with one is written by the residual-draw kernel).
+template <typename T>
+__global__ __launch_bounds__(256) void rowfinish_kernel(const RowArgs A, const int do_q, const int do_v,
+                                                        const int rows_per_block, const int K,
+                                                        int32_t* __restrict__ accept_len,
+                                                        int32_t* __restrict__ resampled_id)
+{
+    __shared__ uint8_t sm_acc[256];
+    const int tid = threadIdx.x;
+    const int64_t row = (int64_t)blockIdx.x * rows_per_block + tid;
+    const bool live = tid < rows_per_block && row < A.N;
+    const bool windows = accept_len || resampled_id;               // uniform over the grid
+    int rej = 0;
+    if (live) {
+        const int V = A.V;
+        const T* crow = static_cast<const T*>(A.draft) + row * A.stride;
+        const RowStats st = A.stats[row];
+        const double S = st.S;
+        const float n = st.n;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t row = blockIdx.x;
-    const int V = A.V;
-    const T* crow = static_cast<const T*>(A.draft) + row * A.stride;
-    const T* trow = do_v ? static_cast<const T*>(A.target) + row * A.stride : nullptr;
-    const RowStats st = A.stats[row];
-    const double S = st.S, Z = st.Z;
-    const float n = st.n, nt = st.nt;
-
-    if (tid == 0) {
         int xid = -1;
         float cx = st.mc;                                          // no ids: the arg-max token is reported
         if (A.ids) {
@@ -612,30 +630,77 @@ __global__ __launch_bounds__(THREADS) void finish_kernel(const RowArgs A, const 
                 if (A.p_hi) A.p_hi[row] = (float)(rs.alpha_u * A.a * x / (1.0 + (A.a - 1.0) * x));
             }
         }
-        int rej = 0;
         if (do_v) {
             // ln p_x = cx - n ln2 - ln S, ln q_x = tx - nt ln2 - ln Z;  accept iff ln u < min(0, ln q_x - ln p_x)
+            const T* trow = static_cast<const T*>(A.target) + row * A.stride;
             const float tx = load_logit(trow, xid);
             const double lp = ((double)cx - (double)n * kLn2) - log(S);
-            const double lq = ((double)tx - (double)nt * kLn2) - log(Z);
+            const double lq = ((double)tx - (double)st.nt * kLn2) - log(st.Z);
             const double lnu = log((double)A.u_accept[row]);       // log(0) = -inf: always accepted
             rej = !(lnu < fmin(0.0, lq - lp));
             if (A.accept) A.accept[row] = (uint8_t)(!rej);
-            if (!rej && A.row_id) A.row_id[row] = -1;
+            if (A.row_id && !rej) A.row_id[row] = -1;
         }
-        sm_i[NW * 2] = rej;
     }
-    if constexpr (THREADS == 64) {
-        return;                                                    // quantify only
-    } else {
+    bool first = false;                                            // first rejection of its window
+    if (windows) {
+        sm_acc[tid] = (uint8_t)(!rej);
         __syncthreads();
-        if (!sm_i[NW * 2] || !A.row_id) return;                    // workgroup-uniform
+        const int lead = tid - tid % K;                            // block starts are multiples of K
+        if (live && tid == lead) {
+            const int64_t left = A.N - row;
+            const int len = (int)(left < K ? left : K);
+            int m = 0;
+            while (m < len && sm_acc[tid + m]) ++m;
+            const int64_t w = row / K;
+            if (accept_len) accept_len[w] = m;
+            if (resampled_id && m == len) resampled_id[w] = -1;
+        }
+        if (rej) {
+            first = true;
+            for (int i = lead; i < tid; ++i) first = first && sm_acc[i] != 0;
+        }
+    }
+    if (rej && A.row_id) {
+        // list entry: the row, bit-complemented when the row's draw is also its window's
+        const int slot = atomicAdd(A.reject_count, 1);
+        if (slot < A.N) A.reject_list[slot] = first ? ~(int32_t)row : (int32_t)row;   // (one entry per row at most)
+    }
+}
 
-        // ---- residual resample of a rejected row: res_i = max(0, q_i - p_i) ----------------------------
+// Residual draw of the rejected rows: res_i = max(0, q_i - p_i), inverse CDF in token order.  Workgroups of
+// 1024 lanes walk over the list of rejected rows; both rows are fetched again (they were read moments ago:
+// mostly from cache), at most 8 vectors of each row per lane, all in flight at once.
+template <typename T>
+__global__ __launch_bounds__(1024) void resample_kernel(const RowArgs A, const int K, int32_t* __restrict__ resampled_id)
+{
+    using E = Elt<T>;
+    constexpr int EPV = E::kPerVec;
+    constexpr int THREADS = 1024, NW = 16;
+    constexpr int CHUNK = THREADS * EPV;
+    constexpr int MAXCH = 8;                        // chunks of CHUNK tokens a row can have (supported vocabularies)
+    constexpr int UB = 4;                           // chunks of each row in flight per lane
+
+    __shared__ double sm_e[NW * MAXCH + NW];
+    __shared__ int    sm_i[NW * 2];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int V = A.V;
+    const int last_vec = (V + EPV - 1) / EPV - 1;
+    const int nch = (V + CHUNK - 1) / CHUNK;        // <= MAXCH
+    int count = *A.reject_count;
+    if (count > A.N) count = (int)A.N;
+
+    for (int item = blockIdx.x; item < count; item += gridDim.x) {
+        const int32_t entry = A.reject_list[item];
+        const int64_t row = entry < 0 ? ~entry : entry;
+        const T* crow = static_cast<const T*>(A.draft) + row * A.stride;
+        const T* trow = static_cast<const T*>(A.target) + row * A.stride;
+        const RowStats st = A.stats[row];
+        const double invS = 1.0 / st.S, invZ = 1.0 / st.Z;
+        const float n = st.n, nt = st.nt;
         const double u_res = (double)A.u_resample[row];
-        const double invS = 1.0 / S, invZ = 1.0 / Z;
-        const int last_vec = (V + EPV - 1) / EPV - 1;
-        const int nch = (V + CHUNK - 1) / CHUNK;                   // <= MAXCH by the supported vocabulary range
+
         auto load_vec = [&](const T* base, int j) -> u32x4 {
             const uint32_t off = (uint32_t)min(j * THREADS + tid, last_vec) * 16u;
             return *(gvec)((gbytes)base + off);
@@ -654,7 +719,7 @@ __global__ __launch_bounds__(THREADS) void finish_kernel(const RowArgs A, const 
                 r[k] = (float)fmax(q - p, 0.0);
             }
         };
-        // E1: workgroup totals of the residual over each chunk of CHUNK tokens
+        // E1: workgroup totals of the residual over each chunk of CHUNK tokens, UB chunks of each row in flight
         for (int j0 = 0; j0 < nch; j0 += UB) {
             u32x4 cb[UB], tb[UB];
 #pragma unroll
@@ -693,7 +758,7 @@ __global__ __launch_bounds__(THREADS) void finish_kernel(const RowArgs A, const 
                 if (jstar < 0) run += tot;
             }
             if (jstar < 0) { jstar = jlast; before = run; }        // unreachable for u < 1; keeps the draw valid
-            // E2: the lane's residuals inside that chunk, recomputed exactly as in E1
+            // E2: the lane's residuals inside that chunk, fetched again (cache) and recomputed exactly as in E1
             float r[EPV];
             residuals(load_vec(crow, jstar), load_vec(trow, jstar), jstar, r);
             float s = 0.f;
@@ -703,9 +768,7 @@ __global__ __launch_bounds__(THREADS) void finish_kernel(const RowArgs A, const 
             if (lane == 63) sm_e[NW * MAXCH + wave] = incl;
             __syncthreads();
             double cum = before + (incl - (double)s);
-#pragma unroll
-            for (int w = 0; w < NW; ++w)
-                if (w < wave) cum += sm_e[NW * MAXCH + w];
+            for (int w = 0; w < wave; ++w) cum += sm_e[NW * MAXCH + w];
             // smallest token of the chunk whose inclusive running sum exceeds u * R; tokens without
             // residual mass cannot be drawn; lastpos covers a crossing lost to rounding at the chunk end
             const int base = (jstar * THREADS + tid) * EPV;
@@ -741,7 +804,9 @@ __global__ __launch_bounds__(THREADS) void finish_kernel(const RowArgs A, const 
             int id = (c0 != INT_MAX) ? c0 : l0;
             if (id < 0) id = 0;
             A.row_id[row] = id;
+            if (entry < 0 && resampled_id) resampled_id[row / K] = id;             // the window's draw is its first rejected row's
         }
+        __syncthreads();                                           // the LDS slots are reused by the next row
     }
 }
 
@@ -755,12 +820,7 @@ __global__ __launch_bounds__(256) void window_kernel(const uint8_t* __restrict__
     const int64_t W = (N + K - 1) / K;
     const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (w >= W) return;
-    const int64_t lo = w * K;
-    const int64_t hi = (lo + K < N) ? lo + K : N;
-    int64_t n = 0;
-    while (lo + n < hi && accept[lo + n]) ++n;
-    if (accept_len) accept_len[w] = (int32_t)n;
-    if (resampled_id) resampled_id[w] = (lo + n < hi) ? row_id[lo + n] : -1;
+    window_of(accept, row_id, N, K, w, accept_len, resampled_id);
 }
 
 // ---- dense export (tests / debugging): same per-token arithmetic, sweeps over global memory ---------------
@@ -830,6 +890,11 @@ __global__ __launch_bounds__(256) void dense_kernel(const RowArgs A, float* __re
 
 // ---- dispatch ---------------------------------------------------------------------------------------------
 
+}  // namespace
+hipError_t launch_windows(const uint8_t* accept, const int32_t* row_id, int64_t N, int32_t K,
+                          int32_t* accept_len, int32_t* resampled_id, hipStream_t stream);
+namespace {
+
 // Compute units of the current device (asked once per device, then cached).
 int compute_units()
 {
@@ -883,14 +948,31 @@ hipError_t launch_stream_typed(Mode mode, const RowArgs& a, hipStream_t s)
 }
 
 template <typename T>
-hipError_t launch_finish_typed(Mode mode, const RowArgs& a, hipStream_t s)
+hipError_t launch_finish_typed(Mode mode, const RowArgs& a, int32_t K, int32_t* accept_len, int32_t* resampled_id,
+                               hipStream_t s)
 {
-    const dim3 grid((unsigned)a.N);
-    if (mode == Mode::Quantify)
-        hipLaunchKernelGGL((finish_kernel<T, 64>), grid, dim3(64), 0, s, a, 1, 0);
-    else
-        hipLaunchKernelGGL((finish_kernel<T, 256>), grid, dim3(256), 0, s, a, mode == Mode::Fused ? 1 : 0, 1);
-    return hipGetLastError();
+    // Windows of up to 256 rows are finished inside the two kernels; longer ones by the window kernel.
+    const bool want_windows = mode != Mode::Quantify && (accept_len || resampled_id);
+    const bool inline_windows = want_windows && K <= 256 && (a.row_id || !resampled_id);
+    const int rows_per_block = inline_windows ? (256 / K) * K : 256;
+    const unsigned blocks = (unsigned)((a.N + rows_per_block - 1) / rows_per_block);
+    hipLaunchKernelGGL(rowfinish_kernel<T>, dim3(blocks), dim3(256), 0, s, a, mode != Mode::Verify ? 1 : 0,
+                       mode != Mode::Quantify ? 1 : 0, rows_per_block, K, inline_windows ? accept_len : nullptr,
+                       inline_windows ? resampled_id : nullptr);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || mode == Mode::Quantify) return e;
+    if (a.row_id) {
+        // one 1024-lane workgroup per compute unit walks over the rejected rows
+        const int64_t cus = compute_units();
+        const unsigned grid = (unsigned)(a.N < cus ? a.N : cus);
+        hipLaunchKernelGGL(resample_kernel<T>, dim3(grid), dim3(1024), 0, s, a, K,
+                           inline_windows ? resampled_id : nullptr);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (want_windows && !inline_windows)
+        return launch_windows(a.accept, a.row_id, a.N, K, accept_len, resampled_id, s);
+    return hipSuccess;
 }
 
 }  // namespace
@@ -904,11 +986,12 @@ hipError_t launch_stream(Mode mode, int dtype, const RowArgs& args, hipStream_t 
                       : launch_stream_typed<bf16_t>(mode, args, stream);
 }
 
-hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, hipStream_t stream)
+hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, int32_t K, int32_t* accept_len,
+                         int32_t* resampled_id, hipStream_t stream)
 {
     if (args.N <= 0) return hipSuccess;
-    return dtype == 0 ? launch_finish_typed<float>(mode, args, stream)
-                      : launch_finish_typed<bf16_t>(mode, args, stream);
+    return dtype == 0 ? launch_finish_typed<float>(mode, args, K, accept_len, resampled_id, stream)
+                      : launch_finish_typed<bf16_t>(mode, args, K, accept_len, resampled_id, stream);
 }
 
 hipError_t launch_windows(const uint8_t* accept, const int32_t* row_id, int64_t N, int32_t K,

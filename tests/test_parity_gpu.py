@@ -187,6 +187,15 @@ def test_shapes_and_ragged_tails(ciar, oracle, V, stride, N, K, dtype):
         _run_case(ciar, oracle, c, t, ids, ua, ur, P, vocab=V, tag=f"V={V} stride={stride}")
 
 
+@pytest.mark.parametrize("K", [1, 3, 8, 100, 128, 255, 256, 257, 300, 1000])
+def test_window_lengths(ciar, oracle, K):
+    """Windows that divide, straddle and exceed the finishing kernel's 256-row workgroups; N = 700 leaves a
+    ragged last window for most K."""
+    c, t, ids, ua, ur = _random_case(1024, 1024, 700, K, torch.float32, seed=500 + K, sigma=0.25)
+    P = ciar.Params(confidence=0.9, window=K, tau=0.01)
+    _run_case(ciar, oracle, c, t, ids, ua, ur, P, vocab=1024, tag=f"window K={K}")
+
+
 # ---- degenerate rows ----------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
