@@ -178,6 +178,18 @@ int ciar_finish_rows(const void* draft_logits, const void* target_logits, const 
                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Measurement aid, not a step of the method: a plain streaming read of the rows the hot path reads
+ * (the "read both rows and sum" ceiling a memory-bound pass is held against).  Every logit of
+ * draft_logits [N, row_stride] and, unless NULL, target_logits is loaded once with 16-byte loads and
+ * added up as floats; padding between rows is not counted.
+ *   row_sum [N] fp32  out  sum of the row's V draft logits (plus its V target logits)
+ * params supplies vocab, dtype and row_stride (validated as for the other calls).  Same pointer,
+ * alignment, stream and error rules as ciar_quantify; no workspace.
+ */
+int ciar_read_rows(const void* draft_logits, const void* target_logits, int64_t N, const ciar_params* params,
+                   float* row_sum, void* hip_stream);
+
+/*
  * Window epilogue on its own (the last step of ciar_verify / ciar_quantify_verify, which run it when
  * a window output is requested): from the per-row results of N rows,
  *   accept_len[w]   = number of leading rows with accept != 0 in window w = rows [wK, min((w+1)K, N))

@@ -4,7 +4,7 @@
 ``workloads`` generates the seeded synthetic inputs; ``build`` compiles ``libciar.so`` for gfx950.
 """
 from .binding import (CiarError, Params, dense_intervals, finish_rows, last_error, lib, quantify,
-                      quantify_verify, stream_rows, verify, version, window_epilogue, workspace_bytes)
+                      quantify_verify, read_rows, stream_rows, verify, version, window_epilogue, workspace_bytes)
 
 __all__ = ["CiarError", "Params", "dense_intervals", "finish_rows", "last_error", "lib", "quantify",
-           "quantify_verify", "stream_rows", "verify", "version", "window_epilogue", "workspace_bytes"]
+           "quantify_verify", "read_rows", "stream_rows", "verify", "version", "window_epilogue", "workspace_bytes"]

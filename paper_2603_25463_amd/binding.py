@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
         L.ciar_window_epilogue.argtypes = [vp, vp, i64, pp, vp, vp, vp]
         L.ciar_dense_intervals.restype = ctypes.c_int
         L.ciar_dense_intervals.argtypes = [vp, i64, pp, vp, vp, vp, vp]
+        L.ciar_read_rows.restype = ctypes.c_int
+        L.ciar_read_rows.argtypes = [vp, vp, i64, pp, vp, vp]
         L.ciar_last_error.restype = ctypes.c_char_p
         L.ciar_last_error.argtypes = []
         L.ciar_version.restype = ctypes.c_char_p
@@ -275,3 +277,15 @@ def dense_intervals(draft: torch.Tensor, params: Params, vocab: int | None = Non
     _check(lib().ciar_dense_intervals(_ptr(draft), N, ctypes.byref(cp), _ptr(lo), _ptr(mid), _ptr(hi),
                                       _stream(stream)))
     return lo, mid, hi
+
+
+def read_rows(draft: torch.Tensor, target: torch.Tensor | None, params: Params, vocab: int | None = None,
+              out: torch.Tensor | None = None, stream=None):
+    """``ciar_read_rows`` (measurement aid): the sum of every row's logits, float32 [N]."""
+    _need_cuda(draft)
+    N, dev = draft.shape[0], draft.device
+    cp = params.to_c(draft, vocab)
+    if out is None:
+        out = torch.empty(N, dtype=torch.float32, device=dev)
+    _check(lib().ciar_read_rows(_ptr(draft), _ptr(target), N, ctypes.byref(cp), _ptr(out), _stream(stream)))
+    return out

@@ -365,6 +365,26 @@ int ciar_dense_intervals(const void* draft_logits, int64_t N, const ciar_params*
     return CIAR_OK;
 }
 
+int ciar_read_rows(const void* draft_logits, const void* target_logits, int64_t N, const ciar_params* params,
+                   float* row_sum, void* hip_stream)
+{
+    Resolved r;
+    if (int rc = check_params(params, &r)) return rc;
+    if (N < 0) return fail(CIAR_EINVAL, "N is negative");
+    if (N > 0x7fffffffLL) return fail(CIAR_EUNSUPPORTED, "N exceeds 2^31 - 1 rows per call");
+    if (int rc = check_rows(draft_logits, "draft_logits")) return rc;
+    if (target_logits)
+        if (int rc = check_rows(target_logits, "target_logits")) return rc;
+    if (!row_sum) return fail(CIAR_EINVAL, "row_sum is NULL");
+    if (N == 0) return CIAR_OK;
+    ciar::RowArgs a = base_args(params, r, N);
+    a.draft = draft_logits;
+    a.target = target_logits;
+    const hipError_t e = ciar::launch_read(params->dtype, a, row_sum, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail(e, "read kernel launch");
+    return CIAR_OK;
+}
+
 const char* ciar_last_error(void) { return g_error; }
 
 const char* ciar_version(void) { return "0.1.0"; }

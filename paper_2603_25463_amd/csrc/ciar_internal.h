@@ -68,4 +68,7 @@ hipError_t launch_windows(const uint8_t* accept, const int32_t* row_id, int64_t 
 hipError_t launch_dense(int dtype, const RowArgs& args, float* p_lo, float* p_mid, float* p_hi,
                         hipStream_t stream);
 
+// Plain streaming read of the rows (args.target may be null): the sum of each row's logits.
+hipError_t launch_read(int dtype, const RowArgs& args, float* row_sum, hipStream_t stream);
+
 }  // namespace ciar

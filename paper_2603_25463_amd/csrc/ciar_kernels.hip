@@ -3,13 +3,13 @@
 // The pass is split so that the kernel that touches the V-wide rows is pure streaming arithmetic:
 //
 //   stream_kernel   reads every logit row exactly once from HBM and leaves ten numbers per row
-//                   (RowStats).  A workgroup of 256 lanes (1024 for the largest vocabularies) owns
-//                   one row at a time and walks over rows blockIdx.x, blockIdx.x + gridDim.x, ...
-//                   The grid holds a few workgroups per compute unit; while a workgroup computes on
-//                   one row, the 16-byte loads of its next row are already in flight into a second
-//                   set of registers, so the memory system stays busy.  Loads are interleaved over the
-//                   workgroup so that every load instruction of a wave covers 1 KiB of consecutive
-//                   memory.  Nothing V-wide is ever written back.
+//                   (RowStats).  A workgroup of 256 lanes (512 or 1024 for large vocabularies or few
+//                   rows) owns one row at a time and walks over rows blockIdx.x, blockIdx.x +
+//                   gridDim.x, ...  The grid is exactly the workgroups that are resident at once (four
+//                   waves per SIMD): while one workgroup waits for its row, the others compute, which
+//                   keeps the memory system busy without a second set of row registers.  Loads are
+//                   interleaved over the workgroup so that every load instruction of a wave covers
+//                   1 KiB of consecutive memory.  Nothing V-wide is ever written back.
 //   rowfinish_kernel  one thread per row turns RowStats into the row's outputs in fp64 (caps, Omega,
 //                   Sigma, U, flag, interval of the reported token, accept test) and appends rejected
 //                   rows to a list.
@@ -21,19 +21,22 @@
 // "Proof of Interval Validity": S appears in every denominator).  It lives in registers as
 // e_i = 2^(c_i log2e - n_w).  The verifier row is only needed for max / Z and is consumed on arrival.
 //
-// stream_kernel, per row:
-//   T  verifier row: per-wave maximum, Z_w = sum 2^(t_i log2e - nt_w)          (max-trick)
+// stream_kernel, per row (centre row first: it carries most of the arithmetic, so that little is left
+// to do when the last bytes of a launch arrive):
 //   B  centre row:   per-wave maximum, e_i = 2^(c_i log2e - n_w) kept in registers, S_w = sum e_i
 //      The reference n_w is an integer (the next integer above max * log2e of the *wave*), so the
 //      waves need no barrier before exponentiating and their results combine exactly:
 //      S = sum_w S_w 2^(n_w - n), n = max_w n_w, a power-of-two rescale.
-//   -- barrier: the waves exchange (n_w, S_w, nt_w, Z_w) --
+//   -- barrier: the waves exchange (max, n_w, S_w) --
 //   C  InterFuse for a scalar radius r, a = e^r, b = e^-r, x_i = e_i / S:
 //        p^u_i = a x_i / (1 + (a-1) x_i),   p^l_i = b x_i / (1 - (1-b) x_i)
 //      with one reciprocal of the product of the two denominators, accumulated as the lower
 //      bound p^l_i and the raw width w_i = p^u_i - p^l_i = (a-b) x_i (1-x_i) / (du_i dl_i):
-//      five fp64 sums per row (sum p^l, sum w and the three second moments).
-//   -- barrier: the waves exchange their five sums; lane 0 writes RowStats --
+//      five fp64 sums per row (sum p^l, sum w and the three second moments); two of them when the
+//      row's largest probability shows that the caps cannot be active.
+//   T  verifier row, loaded into the registers the centre row came in: per-wave maximum,
+//      Z_w = sum 2^(t_i log2e - nt_w)                                               (max-trick)
+//   -- barrier: the waves exchange their interval sums and (nt_w, Z_w); thread 0 writes RowStats --
 //
 // rowfinish_kernel / resample_kernel, per row (Eq. uncertainty_score; Algorithm 1's threshold and verification steps):
 //   delta_i = alpha_u w_i + (alpha_u - alpha_l) p^l_i once the 0.99 / 1.01 caps alpha_l, alpha_u are
@@ -277,22 +280,16 @@ __device__ __forceinline__ RowScore finish_score(const double* s, double S, bool
 
 // ---- the streaming kernel ---------------------------------------------------------------------------------
 
-// Waves per SIMD the register allocation aims for: the rows held in registers plus ~40 working
-// registers, capped at 4 waves (more buys nothing for a kernel that streams 64 KiB per row).
-// With prefetch a lane holds the current centre row as floats, and the next centre row and one
-// verifier row as loaded.
-template <typename T, int THREADS, int NVEC, bool DO_V>
+// Waves per SIMD the register allocation aims for: the centre row held as floats plus ~40 working
+// registers, capped at 4 waves.  Memory latency is hidden by the other resident workgroups of the compute
+// unit rather than by fetching ahead into a second set of registers: measured on this chip, three or
+// four resident workgroups beat two with a register prefetch of the next row at every vocabulary size.
+template <typename T, int THREADS, int NVEC>
 constexpr int target_waves()
 {
-#ifdef XP_WAVES
-    return XP_WAVES < THREADS / 256 ? THREADS / 256 : XP_WAVES;
-#endif
-    constexpr bool prefetch = THREADS == 256;
-    constexpr int raw = NVEC * 4;                                  // one row as loaded
     constexpr int ept = NVEC * Elt<T>::kPerVec;                    // one row as floats
-    constexpr int rows = ept + (prefetch ? raw : 0) + (DO_V && prefetch ? raw : 0);
-    constexpr int fit = 512 / (rows + 40);
-    constexpr int lo = THREADS / 256;                 // waves per SIMD one workgroup needs
+    constexpr int fit = 512 / (ept + 40);
+    constexpr int lo = THREADS / 256;                              // waves per SIMD one workgroup needs
     return fit < lo ? lo : (fit > 4 ? 4 : fit);
 }
 
@@ -337,7 +334,7 @@ __device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const Fu
 
 template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V>
 __global__ __launch_bounds__(THREADS)
-__attribute__((amdgpu_waves_per_eu(target_waves<T, THREADS, NVEC, DO_V>())))
+__attribute__((amdgpu_waves_per_eu(target_waves<T, THREADS, NVEC>())))
 void stream_kernel(const RowArgs A)
 {
     using E = Elt<T>;
@@ -345,12 +342,14 @@ void stream_kernel(const RowArgs A)
     constexpr int EPT = NVEC * EPV;
     constexpr int NW = THREADS / 64;
     constexpr int CHUNK = THREADS * EPV;            // tokens covered by one load instruction of the workgroup
-    // With 256 lanes there is register room to fetch the next row while this one is computed on.
-    constexpr bool PREFETCH = THREADS == 256;
 
-    // exchange slots, double-buffered by row parity so that one barrier per exchange is enough
-    __shared__ float  sm_ref[2][NW * 3];            // per wave: max centre logit, n_w, nt_w
-    __shared__ double sm_sum[2][NW * 2];            // per wave: S_w, Z_w
+    // Exchange slots.  Two barriers per row order every write against every read: the centre-row
+    // slots are written before the first and read between the two, the others are written between the
+    // two and read by thread 0 after the second, before it reaches the next row's first barrier.
+    __shared__ float  sm_ref[NW * 2];               // per wave: max centre logit, n_w
+    __shared__ double sm_S[NW];                     // per wave: S_w
+    __shared__ float  sm_nt[NW];                    // per wave: nt_w
+    __shared__ double sm_Z[NW];                     // per wave: Z_w
     __shared__ double sm_q5[NW * 5];                // per wave: the five interval sums, already in row units
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -361,114 +360,83 @@ void stream_kernel(const RowArgs A)
     const int step = (int)gridDim.x;
 
     // Rows live in global memory (address space 1).  Vector j of this lane: scalar row base + 32-bit
-    // byte offset.  Vector indices past the end of the row are clamped to its last vector, so every
-    // lane loads valid memory unconditionally; tokens that do not exist are set to -inf afterwards.
-    // The base goes through readfirstlane and the lane index through an empty asm on every use: both
-    // are opaque to the optimiser, which otherwise turns the sixteen addresses of a row into sixteen
-    // 64-bit induction variables per row buffer, spills them, and serialises the prefetch on the reloads.
-    auto load_vec = [&](const void* rows, int r, int j) -> u32x4 {
+    // byte offset.  A row that fills the tile needs one lane offset for all of its vectors (the
+    // distance between vectors is a constant on top of the scalar base).  Otherwise vector indices
+    // past the end of the row are clamped to its last vector, so every lane loads valid memory
+    // unconditionally; tokens that do not exist are set to -inf afterwards.
+    // The base goes through readfirstlane and the lane index through an empty asm: both are opaque
+    // to the optimiser, which otherwise turns the sixteen addresses of a row into sixteen 64-bit
+    // induction variables, spills them, and serialises the loads on the reloads.
+    auto load_row = [&](u32x4 (&buf)[NVEC], const void* rows, int r) {
         const uint64_t b = (uint64_t)(static_cast<const T*>(rows) + (int64_t)r * A.stride);
         const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
         const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+        const gbytes base = (gbytes)(((uint64_t)hi << 32) | lo);
         int t = tid;
         asm volatile("" : "+v"(t));
-        const uint32_t off = (uint32_t)min(j * THREADS + t, last_vec) * 16u;
-        return *(gvec)((gbytes)(((uint64_t)hi << 32) | lo) + off);
+        if (partial) {
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) {
+                const uint32_t off = (uint32_t)min(j * THREADS + t, last_vec) * 16u;
+                buf[j] = *(gvec)(base + off);
+            }
+        } else {
+            const uint32_t off = (uint32_t)t * 16u;
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) buf[j] = *(gvec)(base + (uint64_t)j * (THREADS * 16u) + off);
+        }
+    };
+    // Verifier row statistics of one wave from the row as loaded: nt_w and Z_w = sum 2^(t_i log2e - nt_w).
+    auto verifier_stats = [&](u32x4 (&tb)[NVEC], float& ntw, double& Zw) {
+        if (partial) {
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) E::mask_tail(tb[j], (j * THREADS + tid) * EPV, V);
+        }
+        float mt = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) {
+            float tv[EPV];
+            E::unpack(tb[j], tv);
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) mt = fmaxf(mt, tv[k]);
+        }
+        ntw = ref_of(wave_max(mt));
+        const float nref = ntw == -INFINITY ? 0.f : ntw;           // an all-masked wave: every term is 2^-inf = 0
+        float zacc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) {
+            float tv[EPV];
+            E::unpack(tb[j], tv);
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) zacc[k & 3] += exp2_ref(tv[k], nref);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        Zw = wave_sum((double)((zacc[0] + zacc[1]) + (zacc[2] + zacc[3])));
     };
 
     // the list of rejected rows that the finishing kernels build starts empty
     if (DO_V && blockIdx.x == 0 && tid == 0) *A.reject_count = 0;
 
-    // the row index is uniform over the workgroup: keep it in a scalar register
+    // The row index is uniform over the workgroup: keep it in a scalar register.
+    // A row's centre logits are loaded and worked on first, its verifier logits second: the centre row
+    // carries most of the arithmetic (both of its passes), the verifier row only a short one, so
+    // little work is left when the last bytes of the launch arrive.
     int row = __builtin_amdgcn_readfirstlane((int)blockIdx.x);     // the launcher keeps gridDim.x <= N
-    u32x4 tbuf[NVEC];                                              // verifier row as loaded (without prefetch: both rows in turn)
-    u32x4 cbuf[PREFETCH ? NVEC : 1];                               // centre row as loaded
-    if constexpr (DO_V) {
-#pragma unroll
-        for (int j = 0; j < NVEC; ++j) tbuf[j] = load_vec(A.target, row, j);
-    }
-    if constexpr (PREFETCH) {
-#pragma unroll
-        for (int j = 0; j < NVEC; ++j) cbuf[j] = load_vec(A.draft, row, j);
-    }
+    u32x4 buf[NVEC];                                               // a row as loaded: centre and verifier row in turn
+    load_row(buf, A.draft, row);
 
-    for (int it = 0;; ++it) {
+    for (;;) {
         const int next = __builtin_amdgcn_readfirstlane(row + step);
         const bool has_next = next < nrows;                        // uniform
-        const int par = it & 1;
 
-        // ---- T: verifier row statistics, per wave; the row is not kept -----------------------------
-        float ntw = -INFINITY;
-        double Zw = 0.0;
-        if constexpr (DO_V) {
-            if (partial) {
-#pragma unroll
-                for (int j = 0; j < NVEC; ++j) E::mask_tail(tbuf[j], (j * THREADS + tid) * EPV, V);
-            }
-            float mt = -INFINITY;
-#pragma unroll
-            for (int j = 0; j < NVEC; ++j) {
-                float tv[EPV];
-                E::unpack(tbuf[j], tv);
-#pragma unroll
-                for (int k = 0; k < EPV; ++k) mt = fmaxf(mt, tv[k]);
-            }
-            ntw = ref_of(wave_max(mt));
-            const float nref = ntw == -INFINITY ? 0.f : ntw;       // an all-masked wave: every term is 2^-inf = 0
-            float zacc[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int j = 0; j < NVEC; ++j) {
-                float tv[EPV];
-                E::unpack(tbuf[j], tv);
-#pragma unroll
-                for (int k = 0; k < EPV; ++k) zacc[k & 3] += exp2_ref(tv[k], nref);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            Zw = wave_sum((double)((zacc[0] + zacc[1]) + (zacc[2] + zacc[3])));
-            __builtin_amdgcn_sched_barrier(0);                     // t is dead from here on
-            if constexpr (PREFETCH) {
-                // (the else branch kills the old contents: otherwise they would stay live to the loop's end)
-                if (has_next) {
-#pragma unroll
-                    for (int j = 0; j < NVEC; ++j) tbuf[j] = load_vec(A.target, next, j);
-                } else {
-#pragma unroll
-                    for (int j = 0; j < NVEC; ++j) tbuf[j] = u32x4{0u, 0u, 0u, 0u};
-                }
-            }
-        }
-
-        // ---- A + B: centre row: per-wave max, e_i = 2^(c_i log2e - n_w), S_w -------------------------
+        // ---- B: centre row: per-wave max, e_i = 2^(c_i log2e - n_w), S_w -------------------------------
         float e[EPT];
-        u32x4 cnext[PREFETCH ? NVEC : 1];
-        if constexpr (PREFETCH) {
-            if (partial) {
+        if (partial) {
 #pragma unroll
-                for (int j = 0; j < NVEC; ++j) E::mask_tail(cbuf[j], (j * THREADS + tid) * EPV, V);
-            }
-#pragma unroll
-            for (int j = 0; j < NVEC; ++j) E::unpack(cbuf[j], &e[j * EPV]);
-            // the next centre row goes in flight now, into registers of its own, and lands while this
-            // row is computed on
-            __builtin_amdgcn_sched_barrier(0);
-            if (has_next) {
-#pragma unroll
-                for (int j = 0; j < NVEC; ++j) cnext[j] = load_vec(A.draft, next, j);
-            } else {
-#pragma unroll
-                for (int j = 0; j < NVEC; ++j) cnext[j] = u32x4{0u, 0u, 0u, 0u};
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        } else {
-#pragma unroll
-            for (int j = 0; j < NVEC; ++j) tbuf[j] = load_vec(A.draft, row, j);
-            if (partial) {
-#pragma unroll
-                for (int j = 0; j < NVEC; ++j) E::mask_tail(tbuf[j], (j * THREADS + tid) * EPV, V);
-            }
-#pragma unroll
-            for (int j = 0; j < NVEC; ++j) E::unpack(tbuf[j], &e[j * EPV]);
+            for (int j = 0; j < NVEC; ++j) E::mask_tail(buf[j], (j * THREADS + tid) * EPV, V);
         }
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) E::unpack(buf[j], &e[j * EPV]);
         float mcl = e[0];
 #pragma unroll
         for (int i = 1; i < EPT; ++i) mcl = fmaxf(mcl, e[i]);
@@ -493,25 +461,23 @@ void stream_kernel(const RowArgs A)
             Sw = wave_sum(sacc[0] + sacc[1]);
         }
 
-        // ---- the waves exchange their statistics: the only barrier before the interval pass ------------
+        // ---- the waves exchange the centre row's statistics ----------------------------------------------
         if (lane == 0) {
-            sm_ref[par][wave * 3] = mcw; sm_ref[par][wave * 3 + 1] = nw; sm_ref[par][wave * 3 + 2] = ntw;
-            sm_sum[par][wave * 2] = Sw;  sm_sum[par][wave * 2 + 1] = Zw;
+            sm_ref[wave * 2] = mcw; sm_ref[wave * 2 + 1] = nw;
+            sm_S[wave] = Sw;
         }
         __syncthreads();
-        float mc = sm_ref[par][0], n = sm_ref[par][1], nt = sm_ref[par][2];
+        float mc = sm_ref[0], n = sm_ref[1];
 #pragma unroll
         for (int w = 1; w < NW; ++w) {
-            mc = fmaxf(mc, sm_ref[par][w * 3]);
-            n = fmaxf(n, sm_ref[par][w * 3 + 1]);
-            nt = fmaxf(nt, sm_ref[par][w * 3 + 2]);
+            mc = fmaxf(mc, sm_ref[w * 2]);
+            n = fmaxf(n, sm_ref[w * 2 + 1]);
         }
-        double S = 0.0, Z = 0.0;                                   // in units of 2^-n and 2^-nt
+        double S = 0.0;                                            // in units of 2^-n
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
-            const float rn = sm_ref[par][w * 3 + 1], rt = sm_ref[par][w * 3 + 2];
-            if (rn != -INFINITY) S += sm_sum[par][w * 2] * pow2_of(rn - n);
-            if (DO_V && rt != -INFINITY) Z += sm_sum[par][w * 2 + 1] * pow2_of(rt - nt);
+            const float rn = sm_ref[w * 2 + 1];
+            if (rn != -INFINITY) S += sm_S[w] * pow2_of(rn - n);
         }
         const double fw = nw == -INFINITY ? 0.0 : pow2_of(nw - n);     // this wave's e_i are 1/fw too large
 
@@ -527,26 +493,51 @@ void stream_kernel(const RowArgs A)
             if (capless) {
                 if (partial) fuse_sums<THREADS, NVEC, EPV, true, true>(e, fr, V, q5);
                 else         fuse_sums<THREADS, NVEC, EPV, false, true>(e, fr, V, q5);
+                q5[1] = wave_sum(q5[1]);
+                q5[3] = wave_sum(q5[3]);
             } else {
                 if (partial) fuse_sums<THREADS, NVEC, EPV, true, false>(e, fr, V, q5);
                 else         fuse_sums<THREADS, NVEC, EPV, false, false>(e, fr, V, q5);
-            }
 #pragma unroll
-            for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
+                for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
+            }
             if (lane == 0) {
                 const double f2 = fw * fw;
                 sm_q5[wave * 5 + 0] = q5[0] * fw; sm_q5[wave * 5 + 1] = q5[1] * fw;
                 sm_q5[wave * 5 + 2] = q5[2] * f2; sm_q5[wave * 5 + 3] = q5[3] * f2; sm_q5[wave * 5 + 4] = q5[4] * f2;
             }
         }
-        if constexpr (PREFETCH) {
-#pragma unroll
-            for (int j = 0; j < NVEC; ++j) cbuf[j] = cnext[j];
-        }
 
-        // ---- lane 0 leaves the row's ten numbers for the finishing kernel --------------------------------
-        if constexpr (DO_Q) __syncthreads();
+        // ---- T: verifier row statistics, per wave; the row is not kept -------------------------------------
+        if constexpr (DO_V) {
+            float ntw;
+            double Zw;
+            // The verifier row is fetched only now, into the registers the centre row came in.  Fetching
+            // it earlier, next to the interval pass, was measured slower: the other resident workgroups
+            // already keep the memory system busy, and more loads in flight per wave only lengthen queues.
+            __builtin_amdgcn_sched_barrier(0);
+            load_row(buf, A.target, row);
+            verifier_stats(buf, ntw, Zw);
+            if (lane == 0) { sm_nt[wave] = ntw; sm_Z[wave] = Zw; }
+        }
+        // the next centre row goes in flight before the barrier and thread 0's bookkeeping
+        __builtin_amdgcn_sched_barrier(0);
+        if (has_next) load_row(buf, A.draft, next);
+
+        // ---- thread 0 leaves the row's ten numbers for the finishing kernels -------------------------------
+        __syncthreads();
         if (tid == 0) {
+            float nt = -INFINITY;
+            double Z = 0.0;                                        // in units of 2^-nt
+            if constexpr (DO_V) {
+#pragma unroll
+                for (int w = 0; w < NW; ++w) nt = fmaxf(nt, sm_nt[w]);
+#pragma unroll
+                for (int w = 0; w < NW; ++w) {
+                    const float rt = sm_nt[w];
+                    if (rt != -INFINITY) Z += sm_Z[w] * pow2_of(rt - nt);
+                }
+            }
             RowStats* st = A.stats + row;
             st->S = S; st->Z = Z; st->n = n; st->nt = nt; st->mc = mc; st->capless = capless ? 1.f : 0.f;
 #pragma unroll
@@ -562,10 +553,6 @@ void stream_kernel(const RowArgs A)
 
         if (!has_next) break;
         row = next;
-        if constexpr (!PREFETCH && DO_V) {
-#pragma unroll
-            for (int j = 0; j < NVEC; ++j) tbuf[j] = load_vec(A.target, row, j);
-        }
     }
 }
 
@@ -888,6 +875,75 @@ __global__ __launch_bounds__(256) void dense_kernel(const RowArgs A, float* __re
     }
 }
 
+// ---- plain streaming read: the bandwidth ceiling the streaming kernel is held against ---------------------
+
+// One workgroup per row: every 16-byte vector of the row pair is loaded once, with up to 2 x 8 loads per
+// lane in flight, and summed as floats.  No exponentials, no exchange beyond one reduction per row.
+template <typename T>
+__global__ __launch_bounds__(256) void read_kernel(const RowArgs A, float* __restrict__ row_sum)
+{
+    using E = Elt<T>;
+    constexpr int EPV = E::kPerVec, UB = 8;
+    __shared__ float sm[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row = blockIdx.x;
+    const int V = A.V;
+    const int nvec = (V + EPV - 1) / EPV;
+    const gvec c = (gvec)(gbytes)(static_cast<const T*>(A.draft) + row * A.stride);
+    const gvec t = (gvec)(gbytes)(static_cast<const T*>(A.target ? A.target : A.draft) + row * A.stride);
+    const bool two = A.target != nullptr;                          // uniform
+    // Vectors past the end of the row are clamped to its last one and zeroed as loaded; so is the
+    // padding inside the row's last vector.  Branch-free: a word survives iff its token exists.
+    auto clean = [&](u32x4& r, int v) {
+        const int first = v * EPV;
+        if constexpr (EPV == 4) {
+            r.x = first + 0 < V ? r.x : 0u;
+            r.y = first + 1 < V ? r.y : 0u;
+            r.z = first + 2 < V ? r.z : 0u;
+            r.w = first + 3 < V ? r.w : 0u;
+        } else {
+            r.x &= (first + 0 < V ? 0x0000ffffu : 0u) | (first + 1 < V ? 0xffff0000u : 0u);
+            r.y &= (first + 2 < V ? 0x0000ffffu : 0u) | (first + 3 < V ? 0xffff0000u : 0u);
+            r.z &= (first + 4 < V ? 0x0000ffffu : 0u) | (first + 5 < V ? 0xffff0000u : 0u);
+            r.w &= (first + 6 < V ? 0x0000ffffu : 0u) | (first + 7 < V ? 0xffff0000u : 0u);
+        }
+    };
+    float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll 1
+    for (int base = 0; base < nvec; base += UB * 256) {
+        u32x4 cb[UB], tb[UB];
+#pragma unroll
+        for (int j = 0; j < UB; ++j) cb[j] = c[min(base + j * 256 + tid, nvec - 1)];
+        if (two) {
+#pragma unroll
+            for (int j = 0; j < UB; ++j) tb[j] = t[min(base + j * 256 + tid, nvec - 1)];
+        }
+        const bool ragged = base + UB * 256 >= nvec;               // uniform: this sweep reaches the row's end
+#pragma unroll
+        for (int j = 0; j < UB; ++j) {
+            if (ragged) {
+                clean(cb[j], base + j * 256 + tid);
+                if (two) clean(tb[j], base + j * 256 + tid);
+            }
+            float cv[EPV], tv[EPV];
+            E::unpack(cb[j], cv);
+#pragma unroll
+            for (int k = 0; k < EPV; k += 2) { acc0 += cv[k]; acc1 += cv[k + 1]; }
+            if (two) {
+                E::unpack(tb[j], tv);
+#pragma unroll
+                for (int k = 0; k < EPV; k += 2) { acc0 += tv[k]; acc1 += tv[k + 1]; }
+            }
+            __builtin_amdgcn_sched_barrier(0);                     // unpack one vector at a time
+        }
+    }
+    float acc = acc0 + acc1;
+    acc = (float)wave_sum((double)acc);
+    if (lane == 0) sm[wave] = acc;
+    __syncthreads();
+    if (tid == 0) row_sum[row] = (sm[0] + sm[1]) + (sm[2] + sm[3]);
+}
+
 // ---- dispatch ---------------------------------------------------------------------------------------------
 
 }  // namespace
@@ -916,7 +972,7 @@ hipError_t launch_stream_kernel(const RowArgs& a, hipStream_t s)
     // One wave of resident workgroups, each walking over rows with stride gridDim.x.  The register
     // budget the kernel was compiled for fixes how many fit: target_waves() waves per SIMD, and a
     // workgroup puts THREADS / 256 waves on each of the four SIMDs of a compute unit.
-    constexpr int per_cu = target_waves<T, THREADS, NVEC, DO_V>() / (THREADS / 256);
+    constexpr int per_cu = target_waves<T, THREADS, NVEC>() / (THREADS / 256);
     const int64_t resident = (int64_t)per_cu * compute_units();
     const unsigned grid = (unsigned)(a.N < resident ? a.N : resident);
     hipLaunchKernelGGL((stream_kernel<T, THREADS, NVEC, DO_Q, DO_V>), dim3(grid), dim3(THREADS), 0, s, a);
@@ -942,7 +998,12 @@ hipError_t launch_stream_typed(Mode mode, const RowArgs& a, hipStream_t s)
     if (vecs <= 256 * 2)  return launch_stream_cfg<T, 256, 2>(mode, a, s);
     if (vecs <= 256 * 4)  return launch_stream_cfg<T, 256, 4>(mode, a, s);
     if (vecs <= 256 * 8)  return launch_stream_cfg<T, 256, 8>(mode, a, s);
-    if (vecs <= 256 * 16) return launch_stream_cfg<T, 256, 16>(mode, a, s);
+    if (vecs <= 256 * 16) {
+        // Few rows per workgroup: eight waves on a row keep the last rows of the launch short and the
+        // grid even; with many rows the four-wave tile has less exchange overhead (measured).
+        if (a.N < 12 * (int64_t)compute_units()) return launch_stream_cfg<T, 512, 8>(mode, a, s);
+        return launch_stream_cfg<T, 256, 16>(mode, a, s);
+    }
     if (vecs <= 1024 * 8) return launch_stream_cfg<T, 1024, 8>(mode, a, s);
     return hipErrorInvalidValue;
 }
@@ -1012,6 +1073,15 @@ hipError_t launch_dense(int dtype, const RowArgs& args, float* p_lo, float* p_mi
     const dim3 grid((unsigned)args.N), block(256);
     if (dtype == 0) hipLaunchKernelGGL(dense_kernel<float>, grid, block, 0, stream, args, p_lo, p_mid, p_hi);
     else hipLaunchKernelGGL(dense_kernel<bf16_t>, grid, block, 0, stream, args, p_lo, p_mid, p_hi);
+    return hipGetLastError();
+}
+
+hipError_t launch_read(int dtype, const RowArgs& args, float* row_sum, hipStream_t stream)
+{
+    if (args.N <= 0) return hipSuccess;
+    const dim3 grid((unsigned)args.N), block(256);
+    if (dtype == 0) hipLaunchKernelGGL(read_kernel<float>, grid, block, 0, stream, args, row_sum);
+    else hipLaunchKernelGGL(read_kernel<bf16_t>, grid, block, 0, stream, args, row_sum);
     return hipGetLastError();
 }
 

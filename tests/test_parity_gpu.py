@@ -300,6 +300,23 @@ def test_dense_export_matches_the_oracle_curves(ciar, oracle):
                 assert np.all(np.abs(g - o) <= parity.ATOL + parity.RTOL * np.abs(o))
 
 
+@pytest.mark.parametrize("V,stride,N,dtype", [(1000, 1000, 9, torch.float32), (16384, 16384, 33, torch.float32),
+                                              (16385, 16388, 5, torch.float32), (5000, 5008, 7, torch.bfloat16),
+                                              (65536, 65536, 3, torch.bfloat16)])
+def test_read_rows_sums_every_logit_once(ciar, V, stride, N, dtype):
+    """The bandwidth-ceiling kernel is not part of the method; its row sums are checked against a plain
+    fp64 sum of the same bits so that the benchmark's ceiling provably reads every logit."""
+    c, t, *_ = _random_case(V, stride, N, 4, dtype, seed=77 + V)
+    say(f"[read_rows] V={V} stride={stride} N={N} {dtype}")
+    both = ciar.read_rows(c, t, ciar.Params(), vocab=V)
+    one = ciar.read_rows(c, None, ciar.Params(), vocab=V)
+    torch.cuda.synchronize()
+    cs, ts = c[:, :V].double().sum(1), t[:, :V].double().sum(1)
+    scale = c[:, :V].double().abs().sum(1) + t[:, :V].double().abs().sum(1)
+    assert torch.all((both.double() - (cs + ts)).abs() <= 1e-5 * scale)
+    assert torch.all((one.double() - cs).abs() <= 1e-5 * scale)
+
+
 def test_results_are_deterministic_and_stream_ordered(ciar):
     c, t, ids, ua, ur = _random_case(16384, 16384, 300, 8, torch.float32, seed=31)
     say("[determinism] V=16384 N=300, two runs, second on a side stream")
