@@ -240,9 +240,12 @@ __device__ __forceinline__ FuseRow fuse_row(double S, double a, double b)
 }
 
 // gl = e du / (du dl) and gw = e (1-x) / (du dl):  p^l = (b/S) gl,  w = p^u - p^l = ((a-b)/S) gw.
+// SPLIT = form 1 - x with the two-float 1/S.  It matters only when some x is close to 1 (the relative
+// error of 1 - x is 6e-8 x / (1 - x) without it); rows whose largest probability is at most 1/2 skip it.
+template <bool SPLIT = true>
 __device__ __forceinline__ void fuse_token(float e, const FuseRow& r, float& gl, float& gw)
 {
-    const float om = fmaf(e, r.nil, fmaf(e, r.nih, 1.0f));        // 1 - x
+    const float om = SPLIT ? fmaf(e, r.nil, fmaf(e, r.nih, 1.0f)) : fmaf(e, r.nih, 1.0f);   // 1 - x
     const float du = fmaf(e, r.cu, 1.0f);
     const float dl = fmaf(om, r.omb, r.b);
     const float g = e * __builtin_amdgcn_rcpf(du * dl);
@@ -294,11 +297,12 @@ constexpr int target_waves()
 }
 
 // Pass C for one lane: the InterFuse sums over the lane's tokens.
-// MASKED = the row does not fill the tile: chunks past the end are skipped (padding inside the last
-// chunk has e = 0 and adds exactly nothing).
+// Chunks past the end of a row that does not fill the tile are skipped (padding inside the last chunk
+// has e = 0 and adds exactly nothing).
 // WIDTH_ONLY = the caps are known to be inactive for this row (alpha_l = alpha_u = 1), so
 // delta_i = w_i and only sum gw and sum gw^2 are needed.
-template <int THREADS, int NVEC, int EPV, bool MASKED, bool WIDTH_ONLY>
+// SPLIT = see fuse_token.
+template <int THREADS, int NVEC, int EPV, bool WIDTH_ONLY, bool SPLIT>
 __device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const FuseRow& fr, int V,
                                           double (&q5)[5])
 {
@@ -308,11 +312,11 @@ __device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const Fu
     double a0[2] = {0.0, 0.0}, a1[2] = {0.0, 0.0}, a2[2] = {0.0, 0.0}, a3[2] = {0.0, 0.0}, a4[2] = {0.0, 0.0};
 #pragma unroll
     for (int j = 0; j < NVEC; ++j) {
-        if (MASKED && j * THREADS * EPV >= V) continue;            // uniform: the chunk holds no token
+        if (j * THREADS * EPV >= V) continue;                      // uniform: the chunk holds no token
 #pragma unroll
         for (int k = 0; k < EPV; ++k) {
             float gl, gw;
-            fuse_token(e[j * EPV + k], fr, gl, gw);                // padding has e = 0: gl = gw = 0
+            fuse_token<SPLIT>(e[j * EPV + k], fr, gl, gw);         // padding has e = 0: gl = gw = 0
             const double dw = (double)gw;
             a1[k & 1] += dw;
             a3[k & 1] = fma(dw, dw, a3[k & 1]);
@@ -445,8 +449,9 @@ void stream_kernel(const RowArgs A)
         double Sw;
         {
             // S is accumulated in fp64 from the first add: on a nearly one-hot row the bounds of the top
-            // token react to a relative error in S about five times over, and adding small terms to an
-            // fp32 partial sum that already holds ~1 would cost 1e-7.
+            // token react to a relative error in S about five times over, and on a two-token row Sigma is
+            // a difference of two nearly equal widths; even one fp32 add of two comparable terms (6e-8)
+            // shows there (measured against the fp64 definition).
             const float nref = nw == -INFINITY ? 0.f : nw;
             double sacc[2] = {0.0, 0.0};
 #pragma unroll
@@ -485,19 +490,20 @@ void stream_kernel(const RowArgs A)
         // Caps: S_l <= b / (1 - (1-b) x_max) and S_u >= a / (1 + (a-1) x_max) for the largest probability
         // x_max of the row, so below the host-computed bound on x_max both caps are inactive and the
         // cheaper width-only pass is exact.  Uniform over the workgroup.
-        const bool capless = !A.normalize || (double)exp2_ref(mc, n) <= A.capless_xmax * S;
+        const double emax = (double)exp2_ref(mc, n);               // the row's largest e_i, in row units
+        const bool capless = !A.normalize || emax <= A.capless_xmax * S;
+        const bool split = emax > 0.5 * S;                         // some x_i above 1/2: 1 - x needs the two-float 1/S
         if constexpr (DO_Q) {
             // x_i = e_i fw / S: hand fuse_row the partition sum expressed in this wave's units
             const FuseRow fr = fuse_row(fw > 0.0 ? S / fw : 1.0, A.a, A.b);
             double q5[5];
             if (capless) {
-                if (partial) fuse_sums<THREADS, NVEC, EPV, true, true>(e, fr, V, q5);
-                else         fuse_sums<THREADS, NVEC, EPV, false, true>(e, fr, V, q5);
+                if (split) fuse_sums<THREADS, NVEC, EPV, true, true>(e, fr, V, q5);
+                else       fuse_sums<THREADS, NVEC, EPV, true, false>(e, fr, V, q5);
                 q5[1] = wave_sum(q5[1]);
                 q5[3] = wave_sum(q5[3]);
             } else {
-                if (partial) fuse_sums<THREADS, NVEC, EPV, true, false>(e, fr, V, q5);
-                else         fuse_sums<THREADS, NVEC, EPV, false, false>(e, fr, V, q5);
+                fuse_sums<THREADS, NVEC, EPV, false, true>(e, fr, V, q5);
 #pragma unroll
                 for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
             }
