@@ -64,9 +64,9 @@ def _load():
         lib.ciar_oracle_kappa.restype = ctypes.c_double
         lib.ciar_oracle_kappa.argtypes = [ctypes.c_double]
         lib.ciar_oracle_quantify.restype = i32
-        lib.ciar_oracle_quantify.argtypes = [vp, vp, i64, pp] + [vp] * 7 + [i32]
+        lib.ciar_oracle_quantify.argtypes = [vp, vp, vp, i64, pp] + [vp] * 7 + [i32]
         lib.ciar_oracle_dense_intervals.restype = i32
-        lib.ciar_oracle_dense_intervals.argtypes = [vp, i64, pp, vp, vp, vp]
+        lib.ciar_oracle_dense_intervals.argtypes = [vp, vp, i64, pp, vp, vp, vp]
         lib.ciar_oracle_residual_cdf.restype = ctypes.c_double
         lib.ciar_oracle_residual_cdf.argtypes = [vp, vp, i64, pp, vp]
         lib.ciar_oracle_verify.restype = i32
@@ -109,17 +109,29 @@ def default_threads() -> int:
     return max(1, min(len(os.sched_getaffinity(0)), int(os.environ.get("OMP_NUM_THREADS", "1024"))))
 
 
-def quantify(draft, ids, params: Params, vocab: int | None = None, threads: int | None = None):
-    """Returns dict of fp64 arrays p_lo, p_mid, p_hi, omega, sigma, score and uint8 flags, each [N]."""
+def _radius(radius, c: np.ndarray):
+    """The raw radius tensor (None: scalar mode): same dtype, shape and stride as the logits."""
+    if radius is None:
+        return None
+    r = _logits(radius)
+    assert r.shape == c.shape and r.dtype == c.dtype
+    return r
+
+
+def quantify(draft, ids, params: Params, vocab: int | None = None, threads: int | None = None, radius=None):
+    """Returns dict of fp64 arrays p_lo, p_mid, p_hi, omega, sigma, score and uint8 flags, each [N].
+    ``radius``: raw radius tensor like ``draft`` (r_i = min(kappa * Softplus(raw_i), radius_max)), or None
+    for the scalar radius r = min(kappa, radius_max)."""
     c = _logits(draft)
     N = c.shape[0]
     cp = _cparams(params, c, vocab)
+    rad = _radius(radius, c)
     ids32 = None if ids is None else np.ascontiguousarray(np.asarray(ids), dtype=np.int32)
     if ids32 is not None:
         assert ids32.shape == (N,) and (N == 0 or (ids32.min() >= 0 and ids32.max() < cp.vocab))
     out = {k: np.empty(N, dtype=np.float64) for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score")}
     out["flags"] = np.empty(N, dtype=np.uint8)
-    rc = _load().ciar_oracle_quantify(_ptr(c), _ptr(ids32), N, ctypes.byref(cp),
+    rc = _load().ciar_oracle_quantify(_ptr(c), _ptr(rad), _ptr(ids32), N, ctypes.byref(cp),
                                       _ptr(out["p_lo"]), _ptr(out["p_mid"]), _ptr(out["p_hi"]),
                                       _ptr(out["omega"]), _ptr(out["sigma"]), _ptr(out["score"]),
                                       _ptr(out["flags"]), threads or default_threads())
@@ -127,13 +139,15 @@ def quantify(draft, ids, params: Params, vocab: int | None = None, threads: int 
     return out
 
 
-def dense_intervals(draft, params: Params, vocab: int | None = None):
-    """Returns (p_lo, p_mid, p_hi), fp64 [N, V]."""
+def dense_intervals(draft, params: Params, vocab: int | None = None, radius=None):
+    """Returns (p_lo, p_mid, p_hi), fp64 [N, V].  ``radius`` as for :func:`quantify`."""
     c = _logits(draft)
     cp = _cparams(params, c, vocab)
+    rad = _radius(radius, c)
     N, V = c.shape[0], cp.vocab
     lo, mid, hi = (np.empty((N, V), dtype=np.float64) for _ in range(3))
-    rc = _load().ciar_oracle_dense_intervals(_ptr(c), N, ctypes.byref(cp), _ptr(lo), _ptr(mid), _ptr(hi))
+    rc = _load().ciar_oracle_dense_intervals(_ptr(c), _ptr(rad), N, ctypes.byref(cp), _ptr(lo), _ptr(mid),
+                                             _ptr(hi))
     assert rc == 0
     return lo, mid, hi
 

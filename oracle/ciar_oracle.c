@@ -29,10 +29,13 @@
  * claims and propositions, brute-force enumeration of the acceptance law for V <= 8).
  *
  * Parameters not fixed by the paper (stated as readings where this repo documents them):
- *   - kappa: the logit half-width r.  The paper's radius comes from a trained head; here a
- *     scalar radius is either given directly or derived from an "interval confidence" gamma
- *     as the two-sided standard-normal quantile kappa = sqrt(2) * erfinv(gamma).
+ *   - kappa: the scale of the logit half-width.  It is either given directly or derived from an
+ *     "interval confidence" gamma as the two-sided standard-normal quantile
+ *     kappa = sqrt(2) * erfinv(gamma).
  *   - radius_max: the clamp on the radius (the paper clamps but gives no value).
+ *   - the radius itself: r_i = min(kappa * rho_i, radius_max).  Scalar mode (no radius tensor): rho_i = 1.
+ *     Tensor mode: rho_i = Softplus(raw_i) for the raw output raw of the radius half of the Interval Head
+ *     (Sec. 3.2.3, the equation that defines c_t and r_t); kappa = 1 is the paper's head as written.
  */
 #include <math.h>
 #include <stdint.h>
@@ -84,10 +87,19 @@ double ciar_oracle_kappa(double gamma)
     return 0.5 * (lo + hi);
 }
 
-static double scalar_radius(const ciar_oracle_params* P)
+/* Softplus(x) = ln(1 + e^x), evaluated on the side that cannot overflow. */
+static double softplus(double x)
 {
-    double kappa = P->kappa >= 0.0 ? P->kappa : ciar_oracle_kappa(P->confidence);
-    return kappa < P->radius_max ? kappa : P->radius_max;
+    return x > 0.0 ? x + log1p(exp(-x)) : log1p(exp(x));
+}
+
+/* r_i = min(kappa * rho_i, radius_max); rho_i = 1 without a radius tensor, else Softplus(raw_i). */
+static double token_radius(const ciar_oracle_params* P, const void* radius, int64_t index)
+{
+    const double kappa = P->kappa >= 0.0 ? P->kappa : ciar_oracle_kappa(P->confidence);
+    const double rho = radius ? softplus(load_logit(radius, P->dtype, index)) : 1.0;
+    const double r = kappa * rho;
+    return r < P->radius_max ? r : P->radius_max;
 }
 
 /* ---- one row of the quantifier -------------------------------------------------------- */
@@ -114,14 +126,15 @@ static double row_exponentials(const void* logits, const ciar_oracle_params* P, 
 }
 
 /* InterFuse bounds for the whole row, normalised if requested.
- * In: e[i], S.  Out: pl[i], pu[i] (the final, possibly scaled, bounds). */
+ * In: e[i], S, the raw radius tensor (NULL: scalar mode) and the row.  Out: pl[i], pu[i] (the final,
+ * possibly scaled, bounds). */
 static void row_interfuse(const double* e, double S, const ciar_oracle_params* P,
-                          double* pl, double* pu)
+                          const void* radius, int64_t row, double* pl, double* pu)
 {
     const int V = P->vocab;
-    const double r = scalar_radius(P);
     double Sl = 0.0, Su = 0.0;
     for (int i = 0; i < V; ++i) {
+        const double r = token_radius(P, radius, row * P->row_stride + i);
         double down = e[i] * exp(-r);   /* exp(c_i - r_i) up to the common shift */
         double up   = e[i] * exp(r);    /* exp(c_i + r_i) up to the common shift */
         pl[i] = down / (S - e[i] + down);
@@ -145,11 +158,12 @@ static int lowest_argmax(const double* x, int V)
 
 /*
  * Quantifier for rows [0, N).  Outputs are fp64; any output pointer may be NULL.
+ *   radius == NULL: scalar radius; else the raw radius tensor, same dtype and row stride as draft.
  *   ids == NULL: the reported token is the lowest-index argmax of the centre logits.
  *   flags[i] = 1 means "uncertain, send to the cloud" = (U > tau); U == tau is not flagged.
  * Returns 0, or -1 on allocation failure.
  */
-int ciar_oracle_quantify(const void* draft, const int32_t* ids, int64_t N,
+int ciar_oracle_quantify(const void* draft, const void* radius, const int32_t* ids, int64_t N,
                          const ciar_oracle_params* P,
                          double* p_lo, double* p_mid, double* p_hi,
                          double* omega, double* sigma, double* score, uint8_t* flags,
@@ -173,7 +187,7 @@ int ciar_oracle_quantify(const void* draft, const int32_t* ids, int64_t N,
             for (int64_t row = 0; row < N; ++row) {
                 double m;
                 double S = row_exponentials(draft, P, row, e, &m);
-                row_interfuse(e, S, P, pl, pu);
+                row_interfuse(e, S, P, radius, row, pl, pu);
 
                 /* widths, L1 norm, population standard deviation (two passes) */
                 double Om = 0.0;
@@ -203,8 +217,8 @@ int ciar_oracle_quantify(const void* draft, const int32_t* ids, int64_t N,
 }
 
 /* Dense export of the three per-token curves, [N, V] each, for tests. */
-int ciar_oracle_dense_intervals(const void* draft, int64_t N, const ciar_oracle_params* P,
-                                double* p_lo, double* p_mid, double* p_hi)
+int ciar_oracle_dense_intervals(const void* draft, const void* radius, int64_t N,
+                                const ciar_oracle_params* P, double* p_lo, double* p_mid, double* p_hi)
 {
     const int V = P->vocab;
     double* e = (double*)malloc(sizeof(double) * (size_t)V);
@@ -212,7 +226,7 @@ int ciar_oracle_dense_intervals(const void* draft, int64_t N, const ciar_oracle_
     for (int64_t row = 0; row < N; ++row) {
         double m;
         double S = row_exponentials(draft, P, row, e, &m);
-        row_interfuse(e, S, P, p_lo + row * (int64_t)V, p_hi + row * (int64_t)V);
+        row_interfuse(e, S, P, radius, row, p_lo + row * (int64_t)V, p_hi + row * (int64_t)V);
         for (int i = 0; i < V; ++i) p_mid[row * (int64_t)V + i] = e[i] / S;
     }
     free(e);

@@ -502,3 +502,127 @@ def test_empty_batch(oracle):
     v = oracle.verify(c, c, np.zeros(0, np.int32), np.zeros(0, np.float32), np.zeros(0, np.float32),
                       oracle.Params(window=4))
     assert v["accept_len"].shape == (0,)
+
+
+# ---- tensor radius: r_i = min(kappa * Softplus(raw_i), radius_max)  (Sec. 3.2.3, Interval Head) ----------
+
+def _raw_radius(rng, n, V, mu=0.0, sd=1.5):
+    return (mu + sd * rng.standard_normal((n, V))).astype(np.float32)
+
+
+def test_tensor_radius_two_token_vocabulary_is_the_logistic_sigmoid(oracle):
+    """V = 2 with one radius per token: p^u_i = sigma(c_i - c_j + r_i), p^l_i = sigma(c_i - c_j - r_i), with
+    r_i = kappa * ln(1 + e^raw_i) from numpy's log1p / exp (pins the Softplus and which token's radius is used)."""
+    rng = np.random.default_rng(41)
+    c = _rows(rng, 60, 2, 3.0)
+    raw = _raw_radius(rng, 60, 2, sd=3.0)
+    kap = 0.8
+    r = kap * np.log1p(np.exp(raw.astype(np.float64)))
+    lo, mid, hi = oracle.dense_intervals(c, oracle.Params(kappa=kap, radius_max=1e9, normalize=False), radius=raw)
+    d = c[:, 0].astype(np.float64) - c[:, 1].astype(np.float64)
+    np.testing.assert_allclose(mid[:, 0], sps.expit(d), rtol=1e-13)
+    np.testing.assert_allclose(hi[:, 0], sps.expit(d + r[:, 0]), rtol=1e-12)
+    np.testing.assert_allclose(lo[:, 0], sps.expit(d - r[:, 0]), rtol=1e-12)
+    np.testing.assert_allclose(hi[:, 1], sps.expit(-d + r[:, 1]), rtol=1e-12)
+    np.testing.assert_allclose(lo[:, 1], sps.expit(-d - r[:, 1]), rtol=1e-12)
+    # the two tokens' radii differ, so using the other token's radius must be told apart
+    assert np.max(np.abs(hi[:, 0] - sps.expit(d + r[:, 1]))) > 1e-3
+
+
+def test_tensor_radius_equals_softmax_of_the_row_with_one_logit_shifted_by_its_own_radius(oracle):
+    """Brute force over tokens with a library softmax; radii and rows differ from row to row (a wrong row
+    stride or a transposed radius tensor fails)."""
+    rng = np.random.default_rng(42)
+    V, kap = 9, 1.0
+    stride = 12
+    c = np.full((4, stride), 1e30, dtype=np.float32)
+    raw = np.full((4, stride), -1e30, dtype=np.float32)
+    c[:, :V] = _rows(rng, 4, V, 2.5)
+    raw[:, :V] = _raw_radius(rng, 4, V)
+    lo, mid, hi = oracle.dense_intervals(c, oracle.Params(kappa=kap, normalize=False), vocab=V, radius=raw)
+    for n in range(4):
+        cn = c[n, :V].astype(np.float64)
+        for i in range(V):
+            r = kap * sps.log1p(math.exp(float(raw[n, i])))
+            up = cn.copy(); up[i] += r
+            dn = cn.copy(); dn[i] -= r
+            assert abs(hi[n, i] - sps.softmax(up)[i]) < 1e-14
+            assert abs(lo[n, i] - sps.softmax(dn)[i]) < 1e-14
+
+
+def test_constant_raw_radius_reduces_to_the_scalar_mode(oracle):
+    """raw = const: every token has r = kappa * Softplus(const), which is the scalar mode with that radius
+    (already pinned above).  Softplus(0) = ln 2."""
+    rng = np.random.default_rng(43)
+    c = _rows(rng, 6, 257, 2.0)
+    ids = rng.integers(0, 257, 6).astype(np.int32)
+    for const, kap in ((0.0, 1.7), (1.25, 1.0), (-2.0, 3.0)):
+        raw = np.full_like(c, const)
+        r = kap * (math.log(2.0) if const == 0.0 else math.log1p(math.exp(const)))
+        for norm in (False, True):
+            t = oracle.quantify(c, ids, oracle.Params(kappa=kap, normalize=norm, tau=0.01), radius=raw)
+            s = oracle.quantify(c, ids, oracle.Params(kappa=r, normalize=norm, tau=0.01))
+            for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score"):
+                np.testing.assert_allclose(t[k], s[k], rtol=1e-12, atol=1e-18)
+            np.testing.assert_array_equal(t["flags"], s["flags"])
+
+
+def test_tensor_radius_limits_and_clamp(oracle):
+    """raw -> -inf: r -> 0 and the interval collapses onto the softmax; raw large: Softplus(raw) = raw without
+    overflow, and the clamp turns every radius into radius_max (= scalar mode at radius_max)."""
+    rng = np.random.default_rng(44)
+    c = _rows(rng, 3, 40, 2.0)
+    lo, mid, hi = oracle.dense_intervals(c, oracle.Params(kappa=1.0, normalize=False),
+                                         radius=np.full_like(c, -800.0))
+    np.testing.assert_allclose(lo, mid, rtol=1e-13)
+    np.testing.assert_allclose(hi, mid, rtol=1e-13)
+    np.testing.assert_allclose(mid, sps.softmax(c.astype(np.float64), axis=1), rtol=1e-13)
+    big = oracle.dense_intervals(c, oracle.Params(kappa=1.0, radius_max=2.5, normalize=False),
+                                 radius=np.full_like(c, 900.0))
+    ref = oracle.dense_intervals(c, oracle.Params(kappa=2.5, normalize=False))
+    for x, y in zip(big, ref):
+        assert np.all(np.isfinite(x))
+        np.testing.assert_array_equal(x, y)
+    # unclamped large raw: Softplus(30) = 30 + ln(1 + e^-30)
+    one = oracle.dense_intervals(c[:1, :2], oracle.Params(kappa=1.0, radius_max=1e9, normalize=False),
+                                 radius=np.full((1, 2), 30.0, dtype=np.float32))
+    d = float(c[0, 0]) - float(c[0, 1])
+    assert abs(one[2][0, 0] - sps.expit(d + 30.0 + math.log1p(math.exp(-30.0)))) < 1e-15
+
+
+def test_tensor_radius_scores_against_numpy_and_invariants(oracle):
+    """Omega, Sigma, U from numpy on the dense curves; validity p^l <= p <= p^u, S_l <= 1 <= S_u (raw) and the
+    0.99 / 1.01 caps (normalised); widths grow with kappa (raw InterFuse)."""
+    rng = np.random.default_rng(45)
+    c = _rows(rng, 8, 300, 2.0)
+    raw = _raw_radius(rng, 8, 300)
+    for norm in (False, True):
+        P = oracle.Params(kappa=1.0, normalize=norm)
+        lo, mid, hi = oracle.dense_intervals(c, P, radius=raw)
+        d = hi - lo
+        q = oracle.quantify(c, None, P, radius=raw)
+        np.testing.assert_allclose(q["omega"], d.sum(1), rtol=1e-12)
+        np.testing.assert_allclose(q["sigma"], d.std(axis=1, ddof=0), rtol=1e-10)
+        np.testing.assert_allclose(q["score"], d.sum(1) * d.std(axis=1), rtol=1e-10)
+        am = c.argmax(1)
+        np.testing.assert_allclose(q["p_lo"], lo[np.arange(8), am], rtol=1e-13)
+        np.testing.assert_allclose(q["p_hi"], hi[np.arange(8), am], rtol=1e-13)
+        if norm:
+            assert np.all(lo.sum(1) <= 0.99 + 1e-12) and np.all(hi.sum(1) >= 1.01 - 1e-12)
+        else:
+            assert np.all(lo <= mid * (1 + 1e-15)) and np.all(mid <= hi * (1 + 1e-15))
+            assert np.all(lo.sum(1) <= 1.0) and np.all(hi.sum(1) >= 1.0)
+    a = oracle.dense_intervals(c, oracle.Params(kappa=0.5, normalize=False), radius=raw)
+    b = oracle.dense_intervals(c, oracle.Params(kappa=1.0, normalize=False), radius=raw)
+    assert np.all(b[0] <= a[0]) and np.all(a[2] <= b[2])
+
+
+def test_tensor_radius_bf16_is_widened_exactly(oracle):
+    import torch
+    rng = np.random.default_rng(46)
+    c = torch.from_numpy(_rows(rng, 4, 64, 2.0)).to(torch.bfloat16)
+    raw = torch.from_numpy(_raw_radius(rng, 4, 64)).to(torch.bfloat16)
+    a = oracle.quantify(c, None, oracle.Params(kappa=1.0), radius=raw)
+    b = oracle.quantify(c.float(), None, oracle.Params(kappa=1.0), radius=raw.float())
+    for k in a:
+        np.testing.assert_array_equal(a[k], b[k])
