@@ -34,10 +34,11 @@ ROW_OUTPUT_BYTES = 34          # 6 floats, 2 bytes, 1 int32, + 8/K window bytes 
 ROW_SCALAR_INPUT_BYTES = 12    # drafted id + two uniforms
 
 
-def algorithmic_bytes_per_position(vocab: int, elt: int) -> int:
-    """What the method has to move per position: both logit rows once, the row's scalars in, the
-    per-row results out.  Nothing V-wide is written."""
-    return 2 * vocab * elt + ROW_SCALAR_INPUT_BYTES + ROW_OUTPUT_BYTES
+def algorithmic_bytes_per_position(vocab: int, elt: int, rows: int = 2) -> int:
+    """What the method has to move per position: the logit rows once (centre and verifier; the raw
+    radius row as well in tensor-radius mode), the row's scalars in, the per-row results out.
+    Nothing V-wide is written."""
+    return rows * vocab * elt + ROW_SCALAR_INPUT_BYTES + ROW_OUTPUT_BYTES
 
 
 def measured_traffic(workload_name: str):
@@ -58,6 +59,8 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=2, help="1..5 (default 2: the headline configuration)")
     ap.add_argument("--copies", type=int, default=8, help="distinct input copies rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--radius-tensor", action="store_true",
+                    help="tensor-radius mode: a raw radius row per position is streamed as well (not the headline)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of known size (reference for hardware counters)")
     args = ap.parse_args()
@@ -82,7 +85,12 @@ def main() -> int:
     copies = max(1, args.copies)
     drafts = [w.draft] + [w.draft.clone() for _ in range(copies - 1)]
     targets = [w.target] + [w.target.clone() for _ in range(copies - 1)]
-    P = ciar.Params(confidence=0.9, tau=0.30, window=K)
+    # tensor-radius mode: the Interval Head as written (kappa = 1), raw radius ~ N(mu_row, 1)
+    P = ciar.Params(confidence=0.9, tau=0.30, window=K, radius_scale=1.0 if args.radius_tensor else -1.0)
+    rads = None
+    if args.radius_tensor:
+        r0 = wl.make_radius(w, device=dev)
+        rads = [r0] + [r0.clone() for _ in range(copies - 1)]
     W = (N + K - 1) // K
     out = {k: torch.empty(N, dtype=torch.float32, device=dev)
            for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score")}
@@ -103,13 +111,14 @@ def main() -> int:
     def step(i: int, ev0=None, ev1=None):
         """One pass of the hot path: streaming kernel, then the two finishing kernels (one stream)."""
         d, t = drafts[i % copies], targets[i % copies]
+        rad = rads[i % copies] if rads else None
         if ev0 is not None:
             ev0.record(stream)
-        _check(L.ciar_stream_rows(_ptr(d), _ptr(t), 1, N, ctypes.byref(cp), _ptr(ws), ws.numel(), sp))
+        _check(L.ciar_stream_rows(_ptr(d), _ptr(rad), _ptr(t), 1, N, ctypes.byref(cp), _ptr(ws), ws.numel(), sp))
         if ev1 is not None:
             ev1.record(stream)
         _check(L.ciar_finish_rows(
-            _ptr(d), _ptr(t), _ptr(w.ids), _ptr(w.u_accept), _ptr(w.u_resample), N, ctypes.byref(cp),
+            _ptr(d), _ptr(rad), _ptr(t), _ptr(w.ids), _ptr(w.u_accept), _ptr(w.u_resample), N, ctypes.byref(cp),
             _ptr(out["p_lo"]), _ptr(out["p_mid"]), _ptr(out["p_hi"]), _ptr(out["omega"]), _ptr(out["sigma"]),
             _ptr(out["score"]), _ptr(out["flags"]), _ptr(out["accept"]), _ptr(out["row_id"]),
             _ptr(wout["accept_len"]), _ptr(wout["resampled_id"]), _ptr(ws), ws.numel(), sp))
@@ -152,12 +161,13 @@ def main() -> int:
     ms_per_step = 1e3 * total_s / args.steps
     kern_ms = sorted(a.elapsed_time(b) for a, b in zip(ev0, ev1))
     kern_avg_ms = sum(kern_ms) / len(kern_ms)
-    bytes_per_launch = N * algorithmic_bytes_per_position(V, elt)
+    bytes_per_launch = N * algorithmic_bytes_per_position(V, elt, 3 if rads else 2)
     achieved = bytes_per_launch / (kern_avg_ms * 1e-3) / 1e9
 
     result = {
-        "metric": "token positions/sec (quantify+verify, V=16384 fp32)" if args.workload == 2
-                  else f"token positions/sec (quantify+verify, V={V} {'fp32' if elt == 4 else 'bf16'})",
+        "metric": "token positions/sec (quantify+verify, V=16384 fp32)" if args.workload == 2 and not rads
+                  else f"token positions/sec (quantify+verify, V={V} {'fp32' if elt == 4 else 'bf16'}"
+                       f"{', tensor radius' if rads else ''})",
         "value": N * args.steps / total_s,
         "unit": "positions/s",
         "n_gpus": 1,
@@ -171,11 +181,11 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"cfg{args.workload} {spec.name}: {spec.images} images x {spec.grid}x{spec.grid} = "
                                f"{N} positions, V={V}, {'fp32' if elt == 4 else 'bf16'} logits, window K={K}, "
-                               f"confidence 0.9, tau 0.30",
+                               + ("radius tensor N(mu_row, 1), kappa 1, tau 0.30" if rads else "confidence 0.9, tau 0.30"),
                    "input_copies_rotated": copies, "launches_per_step": 3 if K <= 256 else 4},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(spec.name),
-                     "kernel": "stream_kernel (both logit rows of every position, read once)", "kernel_avg_us": 1e3 * kern_avg_ms,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if rads else measured_traffic(spec.name),
+                     "kernel": "stream_kernel (every logit row of every position, read once)", "kernel_avg_us": 1e3 * kern_avg_ms,
                      "kernel_median_us": 1e3 * kern_ms[len(kern_ms) // 2], "kernel_min_us": 1e3 * kern_ms[0],
                      "algorithmic_bytes_per_launch": bytes_per_launch,
                      "plain_read_ceiling": {"kernel": "read_kernel (ciar_read_rows: load both rows, add)",
@@ -186,14 +196,15 @@ def main() -> int:
     if not args.no_cpu_baseline:
         import oracle
         h = wl.to_host(w)
-        OP = oracle.Params(confidence=0.9, tau=0.30, window=K)
+        OP = oracle.Params(confidence=0.9, tau=0.30, window=K, kappa=1.0 if rads else -1.0)
+        hr = rads[0][:min(N, 2048)].cpu().contiguous() if rads else None
         threads = oracle.default_threads()
         ids, ua, ur = h.ids.numpy(), h.u_accept.numpy(), h.u_resample.numpy()
         rows = min(N, 2048)
         hd, ht = h.draft[:rows].contiguous(), h.target[:rows].contiguous()
         done, c0 = 0, time.perf_counter()
         while True:
-            oracle.quantify(hd, ids[:rows], OP, threads=threads)
+            oracle.quantify(hd, ids[:rows], OP, threads=threads, radius=hr)
             oracle.verify(hd, ht, ids[:rows], ua[:rows], ur[:rows], OP, threads=threads)
             done += rows
             dt = time.perf_counter() - c0

@@ -62,10 +62,14 @@ typedef enum ciar_status {
 /*
  * Parameters of the pass.  Fill with ciar_params_default() and override.
  *
- * Radius.  The paper's logit radius r is the Softplus output of a trained head (Sec. 3.2.1,
- * Inter-Head equation); this entry point takes one scalar radius for all tokens:
- *   r = min(kappa, radius_max),
- *   kappa = radius_scale               if radius_scale >= 0
+ * Radius.  The paper's logit radius is the Softplus output of a trained head (Sec. 3.2.1,
+ * Inter-Head equation: r_t = Softplus(Linear_radius(h_t))).  Token i of a row has the radius
+ *   r_i = min(kappa * rho_i, radius_max),
+ *   rho_i = 1                          scalar mode: the call's `radius` argument is NULL
+ *         = Softplus(radius[row, i])   tensor mode: `radius` is the raw output of the radius half of
+ *                                      the Interval Head, laid out like draft_logits (same dtype,
+ *                                      same row_stride, same alignment rules; any finite value)
+ *   kappa = radius_scale               if radius_scale >= 0 (1 = the head as the paper writes it)
  *         = sqrt(2) * erfinv(confidence) otherwise (two-sided standard-normal quantile of the
  *           "interval confidence" gamma in (0,1): 0.8 -> 1.2816, 0.9 -> 1.6449, 0.95 -> 1.9600).
  * radius_max is the clamp the paper applies without naming a value (App. "Proof of Interval
@@ -102,13 +106,14 @@ size_t ciar_workspace_bytes(int64_t N, const ciar_params* params);
  * uncertainty_score; App. "Proof of Interval Validity"; threshold test of Algorithm 1).
  *
  *   draft_logits [N, row_stride]   in   centre logits c
+ *   radius       [N, row_stride]   in   raw radius tensor (tensor mode), or NULL (scalar mode)
  *   draft_ids    [N] int32         in   token whose interval is reported; NULL = the arg-max token
  *   p_lo, p_mid, p_hi [N] float    out  p^l_x, softmax(c)_x, p^u_x of that token (after the caps)
  *   omega, sigma, score [N] float  out  Omega = sum of widths, Sigma = population std of widths, U
  *   flags        [N] uint8         out  1 = U > tau (uncertain: send to the cloud), 0 = accept locally
  * Any output may be NULL; at least one must be given.
  */
-int ciar_quantify(const void* draft_logits, const int32_t* draft_ids, int64_t N,
+int ciar_quantify(const void* draft_logits, const void* radius, const int32_t* draft_ids, int64_t N,
                   const ciar_params* params,
                   float* p_lo, float* p_mid, float* p_hi,
                   float* omega, float* sigma, float* score, uint8_t* flags,
@@ -142,8 +147,9 @@ int ciar_verify(const void* draft_logits, const void* target_logits, const int32
 /*
  * Fused quantify + verify: both rows are read from HBM exactly once and nothing V-wide is written.
  * Arguments and semantics are the union of ciar_quantify (with draft_ids required) and ciar_verify.
+ * In tensor mode the radius rows are read once as well (three V-wide rows per position).
  */
-int ciar_quantify_verify(const void* draft_logits, const void* target_logits,
+int ciar_quantify_verify(const void* draft_logits, const void* radius, const void* target_logits,
                          const int32_t* draft_ids, const float* u_accept, const float* u_resample,
                          int64_t N, const ciar_params* params,
                          float* p_lo, float* p_mid, float* p_hi,
@@ -160,16 +166,18 @@ int ciar_quantify_verify(const void* draft_logits, const void* target_logits,
  * ciar_stream_rows   the streaming kernel: reads every logit row once from HBM and leaves the
  *                    per-row statistics (max-trick references, partition sums, the InterFuse sums)
  *                    in `workspace`.  target_logits = NULL: quantify only (with_intervals must be 1);
- *                    with_intervals = 0: verify only; otherwise both.
+ *                    with_intervals = 0: verify only (radius must be NULL); otherwise both.
  * ciar_finish_rows   the finishing kernel (+ the window epilogue when a window output is given):
  *                    arguments as ciar_quantify_verify; it must be given the workspace a
  *                    ciar_stream_rows call on the same rows and parameters has filled, the same
- *                    target_logits (or NULL), and quantify outputs iff with_intervals was 1.
+ *                    radius and target_logits (or NULL), and quantify outputs iff with_intervals was 1.
  */
-int ciar_stream_rows(const void* draft_logits, const void* target_logits, int with_intervals, int64_t N,
+int ciar_stream_rows(const void* draft_logits, const void* radius, const void* target_logits, int with_intervals,
+                     int64_t N,
                      const ciar_params* params, void* workspace, size_t workspace_bytes, void* hip_stream);
 
-int ciar_finish_rows(const void* draft_logits, const void* target_logits, const int32_t* draft_ids,
+int ciar_finish_rows(const void* draft_logits, const void* radius, const void* target_logits,
+                     const int32_t* draft_ids,
                      const float* u_accept, const float* u_resample, int64_t N, const ciar_params* params,
                      float* p_lo, float* p_mid, float* p_hi,
                      float* omega, float* sigma, float* score, uint8_t* flags,
@@ -205,9 +213,9 @@ int ciar_window_epilogue(const uint8_t* accept, const int32_t* row_resample_id, 
 /*
  * Test / debugging export of the dense curves: p_lo, p_mid, p_hi as [N, V] float32 each, densely
  * packed (row stride V), computed with the same per-token arithmetic as ciar_quantify.  Writes
- * 3*N*V floats; not part of the hot path.  Any of the three may be NULL.
+ * 3*N*V floats; not part of the hot path.  Any of the three may be NULL.  radius as for ciar_quantify.
  */
-int ciar_dense_intervals(const void* draft_logits, int64_t N, const ciar_params* params,
+int ciar_dense_intervals(const void* draft_logits, const void* radius, int64_t N, const ciar_params* params,
                          float* p_lo, float* p_mid, float* p_hi, void* hip_stream);
 
 /* Message for the last non-OK status returned on the calling thread; never NULL. */

@@ -93,10 +93,15 @@ static double softplus(double x)
     return x > 0.0 ? x + log1p(exp(-x)) : log1p(exp(x));
 }
 
-/* r_i = min(kappa * rho_i, radius_max); rho_i = 1 without a radius tensor, else Softplus(raw_i). */
-static double token_radius(const ciar_oracle_params* P, const void* radius, int64_t index)
+/* The radius scale: given, or the quantile of the interval confidence. */
+static double radius_scale(const ciar_oracle_params* P)
 {
-    const double kappa = P->kappa >= 0.0 ? P->kappa : ciar_oracle_kappa(P->confidence);
+    return P->kappa >= 0.0 ? P->kappa : ciar_oracle_kappa(P->confidence);
+}
+
+/* r_i = min(kappa * rho_i, radius_max); rho_i = 1 without a radius tensor, else Softplus(raw_i). */
+static double token_radius(const ciar_oracle_params* P, double kappa, const void* radius, int64_t index)
+{
     const double rho = radius ? softplus(load_logit(radius, P->dtype, index)) : 1.0;
     const double r = kappa * rho;
     return r < P->radius_max ? r : P->radius_max;
@@ -132,9 +137,10 @@ static void row_interfuse(const double* e, double S, const ciar_oracle_params* P
                           const void* radius, int64_t row, double* pl, double* pu)
 {
     const int V = P->vocab;
+    const double kappa = radius_scale(P);
     double Sl = 0.0, Su = 0.0;
     for (int i = 0; i < V; ++i) {
-        const double r = token_radius(P, radius, row * P->row_stride + i);
+        const double r = token_radius(P, kappa, radius, row * P->row_stride + i);
         double down = e[i] * exp(-r);   /* exp(c_i - r_i) up to the common shift */
         double up   = e[i] * exp(r);    /* exp(c_i + r_i) up to the common shift */
         pl[i] = down / (S - e[i] + down);

@@ -54,19 +54,19 @@ def lib() -> ctypes.CDLL:
         L.ciar_workspace_bytes.restype = sz
         L.ciar_workspace_bytes.argtypes = [i64, pp]
         L.ciar_quantify.restype = ctypes.c_int
-        L.ciar_quantify.argtypes = [vp, vp, i64, pp] + [vp] * 7 + [vp, sz, vp]
+        L.ciar_quantify.argtypes = [vp, vp, vp, i64, pp] + [vp] * 7 + [vp, sz, vp]
         L.ciar_verify.restype = ctypes.c_int
         L.ciar_verify.argtypes = [vp, vp, vp, vp, vp, i64, pp] + [vp] * 4 + [vp, sz, vp]
         L.ciar_quantify_verify.restype = ctypes.c_int
-        L.ciar_quantify_verify.argtypes = [vp, vp, vp, vp, vp, i64, pp] + [vp] * 11 + [vp, sz, vp]
+        L.ciar_quantify_verify.argtypes = [vp, vp, vp, vp, vp, vp, i64, pp] + [vp] * 11 + [vp, sz, vp]
         L.ciar_stream_rows.restype = ctypes.c_int
-        L.ciar_stream_rows.argtypes = [vp, vp, ctypes.c_int, i64, pp, vp, sz, vp]
+        L.ciar_stream_rows.argtypes = [vp, vp, vp, ctypes.c_int, i64, pp, vp, sz, vp]
         L.ciar_finish_rows.restype = ctypes.c_int
-        L.ciar_finish_rows.argtypes = [vp, vp, vp, vp, vp, i64, pp] + [vp] * 11 + [vp, sz, vp]
+        L.ciar_finish_rows.argtypes = [vp, vp, vp, vp, vp, vp, i64, pp] + [vp] * 11 + [vp, sz, vp]
         L.ciar_window_epilogue.restype = ctypes.c_int
         L.ciar_window_epilogue.argtypes = [vp, vp, i64, pp, vp, vp, vp]
         L.ciar_dense_intervals.restype = ctypes.c_int
-        L.ciar_dense_intervals.argtypes = [vp, i64, pp, vp, vp, vp, vp]
+        L.ciar_dense_intervals.argtypes = [vp, vp, i64, pp, vp, vp, vp, vp]
         L.ciar_read_rows.restype = ctypes.c_int
         L.ciar_read_rows.argtypes = [vp, vp, i64, pp, vp, vp]
         L.ciar_last_error.restype = ctypes.c_char_p
@@ -141,6 +141,12 @@ def _need_cuda(*ts):
             raise ValueError("all tensors must live on the GPU")
 
 
+def _like_draft(t, draft, name: str):
+    """``target`` / ``radius`` tensors share the layout of the draft logits."""
+    if t is not None and (t.dtype != draft.dtype or t.shape != draft.shape or t.stride() != draft.stride()):
+        raise ValueError(f"{name} must match draft in dtype, shape and strides")
+
+
 def workspace_bytes(N: int, cparams: CiarParams) -> int:
     return int(lib().ciar_workspace_bytes(int(N), ctypes.byref(cparams)))
 
@@ -153,10 +159,13 @@ def _workspace(N: int, cp: CiarParams, dev, workspace):
 
 
 def quantify(draft: torch.Tensor, ids: torch.Tensor | None, params: Params, vocab: int | None = None,
-             stream=None, out: dict | None = None, workspace: torch.Tensor | None = None) -> dict:
+             stream=None, out: dict | None = None, workspace: torch.Tensor | None = None,
+             radius: torch.Tensor | None = None) -> dict:
     """``ciar_quantify``.  Returns dict of [N] tensors: p_lo, p_mid, p_hi, omega, sigma, score (float32)
-    and flags (uint8).  ``out`` may carry preallocated tensors under the same names."""
-    _need_cuda(draft, ids)
+    and flags (uint8).  ``out`` may carry preallocated tensors under the same names.  ``radius``: the raw
+    radius tensor (tensor mode), laid out like ``draft``."""
+    _need_cuda(draft, ids, radius)
+    _like_draft(radius, draft, "radius")
     N, dev = draft.shape[0], draft.device
     cp = params.to_c(draft, vocab)
     workspace, wsb = _workspace(N, cp, dev, workspace)
@@ -164,7 +173,7 @@ def quantify(draft: torch.Tensor, ids: torch.Tensor | None, params: Params, voca
     for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score"):
         o.setdefault(k, torch.empty(N, dtype=torch.float32, device=dev))
     o.setdefault("flags", torch.empty(N, dtype=torch.uint8, device=dev))
-    _check(lib().ciar_quantify(_ptr(draft), _ptr(ids), N, ctypes.byref(cp),
+    _check(lib().ciar_quantify(_ptr(draft), _ptr(radius), _ptr(ids), N, ctypes.byref(cp),
                                _ptr(o["p_lo"]), _ptr(o["p_mid"]), _ptr(o["p_hi"]), _ptr(o["omega"]),
                                _ptr(o["sigma"]), _ptr(o["score"]), _ptr(o["flags"]), _ptr(workspace), wsb,
                                _stream(stream)))
@@ -187,8 +196,7 @@ def verify(draft, target, ids, u_accept, u_resample, params: Params, vocab: int 
     _need_cuda(draft, target, ids, u_accept, u_resample)
     N, dev = draft.shape[0], draft.device
     cp = params.to_c(draft, vocab)
-    if target.dtype != draft.dtype or target.shape != draft.shape or target.stride() != draft.stride():
-        raise ValueError("target must match draft in dtype, shape and strides")
+    _like_draft(target, draft, "target")
     o = _verify_outputs(N, cp.window, dev, out)
     workspace, wsb = _workspace(N, cp, dev, workspace)
     _check(lib().ciar_verify(_ptr(draft), _ptr(target), _ptr(ids), _ptr(u_accept), _ptr(u_resample), N,
@@ -198,20 +206,21 @@ def verify(draft, target, ids, u_accept, u_resample, params: Params, vocab: int 
 
 
 def quantify_verify(draft, target, ids, u_accept, u_resample, params: Params, vocab: int | None = None,
-                    stream=None, out: dict | None = None, workspace: torch.Tensor | None = None) -> dict:
+                    stream=None, out: dict | None = None, workspace: torch.Tensor | None = None,
+                    radius: torch.Tensor | None = None) -> dict:
     """``ciar_quantify_verify``: the fused pass; union of the outputs of quantify and verify."""
-    _need_cuda(draft, target, ids, u_accept, u_resample)
+    _need_cuda(draft, target, ids, u_accept, u_resample, radius)
     N, dev = draft.shape[0], draft.device
     cp = params.to_c(draft, vocab)
-    if target.dtype != draft.dtype or target.shape != draft.shape or target.stride() != draft.stride():
-        raise ValueError("target must match draft in dtype, shape and strides")
+    _like_draft(target, draft, "target")
+    _like_draft(radius, draft, "radius")
     o = _verify_outputs(N, cp.window, dev, out)
     for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score"):
         o.setdefault(k, torch.empty(N, dtype=torch.float32, device=dev))
     o.setdefault("flags", torch.empty(N, dtype=torch.uint8, device=dev))
     workspace, wsb = _workspace(N, cp, dev, workspace)
     _check(lib().ciar_quantify_verify(
-        _ptr(draft), _ptr(target), _ptr(ids), _ptr(u_accept), _ptr(u_resample), N, ctypes.byref(cp),
+        _ptr(draft), _ptr(radius), _ptr(target), _ptr(ids), _ptr(u_accept), _ptr(u_resample), N, ctypes.byref(cp),
         _ptr(o["p_lo"]), _ptr(o["p_mid"]), _ptr(o["p_hi"]), _ptr(o["omega"]), _ptr(o["sigma"]),
         _ptr(o["score"]), _ptr(o["flags"]), _ptr(o["accept"]), _ptr(o["row_id"]), _ptr(o["accept_len"]),
         _ptr(o["resampled_id"]), _ptr(workspace), wsb, _stream(stream)))
@@ -219,17 +228,19 @@ def quantify_verify(draft, target, ids, u_accept, u_resample, params: Params, vo
 
 
 def stream_rows(draft, target, with_intervals: bool, params: Params, workspace: torch.Tensor,
-                vocab: int | None = None, stream=None) -> None:
+                vocab: int | None = None, stream=None, radius: torch.Tensor | None = None) -> None:
     """``ciar_stream_rows``: the streaming kernel alone; leaves the per-row statistics in ``workspace``."""
-    _need_cuda(draft, target, workspace)
+    _need_cuda(draft, target, workspace, radius)
+    _like_draft(radius, draft, "radius")
     cp = params.to_c(draft, vocab)
-    _check(lib().ciar_stream_rows(_ptr(draft), _ptr(target), int(bool(with_intervals)), draft.shape[0],
+    _check(lib().ciar_stream_rows(_ptr(draft), _ptr(radius), _ptr(target), int(bool(with_intervals)), draft.shape[0],
                                   ctypes.byref(cp), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                   _stream(stream)))
 
 
 def finish_rows(draft, target, ids, u_accept, u_resample, params: Params, workspace: torch.Tensor,
-                with_intervals: bool = True, vocab: int | None = None, stream=None, out: dict | None = None) -> dict:
+                with_intervals: bool = True, vocab: int | None = None, stream=None, out: dict | None = None,
+                radius: torch.Tensor | None = None) -> dict:
     """``ciar_finish_rows``: the finishing kernel and the window epilogue on a workspace filled by
     ``stream_rows`` (same rows, same parameters, same ``with_intervals``)."""
     _need_cuda(draft, target, ids, u_accept, u_resample, workspace)
@@ -244,7 +255,7 @@ def finish_rows(draft, target, ids, u_accept, u_resample, params: Params, worksp
         o.setdefault("flags", torch.empty(N, dtype=torch.uint8, device=dev))
     g = lambda k: _ptr(o.get(k))
     _check(lib().ciar_finish_rows(
-        _ptr(draft), _ptr(target), _ptr(ids), _ptr(u_accept), _ptr(u_resample), N, ctypes.byref(cp),
+        _ptr(draft), _ptr(radius), _ptr(target), _ptr(ids), _ptr(u_accept), _ptr(u_resample), N, ctypes.byref(cp),
         g("p_lo"), g("p_mid"), g("p_hi"), g("omega"), g("sigma"), g("score"), g("flags"), g("accept"),
         g("row_id"), g("accept_len"), g("resampled_id"), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)))
@@ -268,13 +279,15 @@ def window_epilogue(accept: torch.Tensor, row_id: torch.Tensor, params: Params, 
     return o
 
 
-def dense_intervals(draft: torch.Tensor, params: Params, vocab: int | None = None, stream=None):
+def dense_intervals(draft: torch.Tensor, params: Params, vocab: int | None = None, stream=None,
+                    radius: torch.Tensor | None = None):
     """``ciar_dense_intervals`` (test export): (p_lo, p_mid, p_hi), float32 [N, V]."""
-    _need_cuda(draft)
+    _need_cuda(draft, radius)
+    _like_draft(radius, draft, "radius")
     N, dev = draft.shape[0], draft.device
     cp = params.to_c(draft, vocab)
     lo, mid, hi = (torch.empty((N, cp.vocab), dtype=torch.float32, device=dev) for _ in range(3))
-    _check(lib().ciar_dense_intervals(_ptr(draft), N, ctypes.byref(cp), _ptr(lo), _ptr(mid), _ptr(hi),
+    _check(lib().ciar_dense_intervals(_ptr(draft), _ptr(radius), N, ctypes.byref(cp), _ptr(lo), _ptr(mid), _ptr(hi),
                                       _stream(stream)))
     return lo, mid, hi
 

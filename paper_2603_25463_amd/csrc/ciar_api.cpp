@@ -41,7 +41,8 @@ double two_sided_normal_quantile(double gamma)
 }
 
 struct Resolved {
-    double a, b;       // e^{+r}, e^{-r}
+    double a, b;       // e^{+r}, e^{-r} of the scalar radius r = min(kappa, radius_max)
+    double kappa;      // radius scale
     int elt;           // bytes per logit
 };
 
@@ -84,6 +85,7 @@ int check_params(const ciar_params* p, Resolved* out)
     const double r = kappa < (double)p->radius_max ? kappa : (double)p->radius_max;
     out->a = std::exp(r);
     out->b = std::exp(-r);
+    out->kappa = kappa;
     out->elt = elt;
     return CIAR_OK;
 }
@@ -107,6 +109,8 @@ ciar::RowArgs base_args(const ciar_params* p, const Resolved& r, int64_t N)
     a.normalize = p->normalize ? 1 : 0;
     a.a = r.a;
     a.b = r.b;
+    a.kappa = r.kappa;
+    a.rmax = (double)p->radius_max;
     a.tau = (double)p->tau;
     a.cap_lo = (double)p->lower_cap;
     a.cap_hi = (double)p->upper_cap;
@@ -153,7 +157,7 @@ int check_workspace(int64_t N, const ciar_params* p, void* workspace, size_t wor
 
 // Everything the three public passes share: validation, workspace carving, the two stages.
 struct Call {
-    const void* draft; const void* target; const int32_t* ids; const float* u_accept; const float* u_resample;
+    const void* draft; const void* radius; const void* target; const int32_t* ids; const float* u_accept; const float* u_resample;
     int64_t N; const ciar_params* params;
     float* p_lo; float* p_mid; float* p_hi; float* omega; float* sigma; float* score; uint8_t* flags;
     uint8_t* accept; int32_t* row_id; int32_t* accept_len; int32_t* resampled_id;
@@ -176,8 +180,13 @@ int prepare(const Call& c, ciar::Mode mode, ciar::RowArgs* a)
     if (int rc = check_rows(c.draft, "draft_logits")) return rc;
     if (mode != ciar::Mode::Quantify)
         if (int rc = check_rows(c.target, "target_logits")) return rc;
+    if (c.radius) {
+        if (mode == ciar::Mode::Verify) return fail(CIAR_EINVAL, "radius given but no interval output is computed");
+        if (int rc = check_rows(c.radius, "radius")) return rc;
+    }
     *a = base_args(c.params, r, c.N);
     a->draft = c.draft;
+    a->radius = c.radius;
     a->target = c.target;
     return CIAR_OK;
 }
@@ -212,6 +221,13 @@ int run_finish(const Call& c, ciar::Mode mode)
     carve(static_cast<char*>(c.workspace), N, &a, &ws_ids, &ws_accept);
     a.ids = c.ids; a.u_accept = c.u_accept; a.u_resample = c.u_resample;
     a.p_lo = c.p_lo; a.p_mid = c.p_mid; a.p_hi = c.p_hi;
+    if (a.radius && !a.ids && (a.p_lo || a.p_hi)) {
+        // tensor mode reports the arg-max token's interval with that token's own radius: find the
+        // index first (quantify-only calls: the list of rejected rows is not in use)
+        const hipError_t e = ciar::launch_argmax(c.params->dtype, a, a.reject_list, c.stream);
+        if (e != hipSuccess) return hip_fail(e, "arg-max kernel launch");
+        a.ids = a.reject_list;
+    }
     a.omega = c.omega; a.sigma = c.sigma; a.score = c.score; a.flags = c.flags;
     const bool windows = c.accept_len || c.resampled_id;
     a.accept = c.accept;
@@ -265,11 +281,11 @@ size_t ciar_workspace_bytes(int64_t N, const ciar_params* /*params*/)
     return round_up(stats_bytes(N) + 2 * ids_bytes(N) + 16 + (size_t)N, 256);
 }
 
-int ciar_quantify(const void* draft_logits, const int32_t* draft_ids, int64_t N, const ciar_params* params,
-                  float* p_lo, float* p_mid, float* p_hi, float* omega, float* sigma, float* score,
-                  uint8_t* flags, void* workspace, size_t workspace_bytes, void* hip_stream)
+int ciar_quantify(const void* draft_logits, const void* radius, const int32_t* draft_ids, int64_t N,
+                  const ciar_params* params, float* p_lo, float* p_mid, float* p_hi, float* omega, float* sigma,
+                  float* score, uint8_t* flags, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    const Call c{draft_logits, nullptr, draft_ids, nullptr, nullptr, N, params, p_lo, p_mid, p_hi, omega, sigma,
+    const Call c{draft_logits, radius, nullptr, draft_ids, nullptr, nullptr, N, params, p_lo, p_mid, p_hi, omega, sigma,
                  score, flags, nullptr, nullptr, nullptr, nullptr, workspace, workspace_bytes,
                  static_cast<hipStream_t>(hip_stream)};
     return run_both(c, ciar::Mode::Quantify);
@@ -280,44 +296,45 @@ int ciar_verify(const void* draft_logits, const void* target_logits, const int32
                 uint8_t* accept, int32_t* row_resample_id, int32_t* accept_len, int32_t* resampled_id,
                 void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    const Call c{draft_logits, target_logits, draft_ids, u_accept, u_resample, N, params, nullptr, nullptr, nullptr,
-                 nullptr, nullptr, nullptr, nullptr, accept, row_resample_id, accept_len, resampled_id, workspace,
-                 workspace_bytes, static_cast<hipStream_t>(hip_stream)};
+    const Call c{draft_logits, nullptr, target_logits, draft_ids, u_accept, u_resample, N, params, nullptr, nullptr,
+                 nullptr, nullptr, nullptr, nullptr, nullptr, accept, row_resample_id, accept_len, resampled_id,
+                 workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream)};
     return run_both(c, ciar::Mode::Verify);
 }
 
-int ciar_quantify_verify(const void* draft_logits, const void* target_logits, const int32_t* draft_ids,
-                         const float* u_accept, const float* u_resample, int64_t N, const ciar_params* params,
-                         float* p_lo, float* p_mid, float* p_hi, float* omega, float* sigma, float* score,
-                         uint8_t* flags, uint8_t* accept, int32_t* row_resample_id, int32_t* accept_len,
-                         int32_t* resampled_id, void* workspace, size_t workspace_bytes, void* hip_stream)
+int ciar_quantify_verify(const void* draft_logits, const void* radius, const void* target_logits,
+                         const int32_t* draft_ids, const float* u_accept, const float* u_resample, int64_t N,
+                         const ciar_params* params, float* p_lo, float* p_mid, float* p_hi, float* omega,
+                         float* sigma, float* score, uint8_t* flags, uint8_t* accept, int32_t* row_resample_id,
+                         int32_t* accept_len, int32_t* resampled_id, void* workspace, size_t workspace_bytes,
+                         void* hip_stream)
 {
-    const Call c{draft_logits, target_logits, draft_ids, u_accept, u_resample, N, params, p_lo, p_mid, p_hi, omega,
+    const Call c{draft_logits, radius, target_logits, draft_ids, u_accept, u_resample, N, params, p_lo, p_mid, p_hi, omega,
                  sigma, score, flags, accept, row_resample_id, accept_len, resampled_id, workspace, workspace_bytes,
                  static_cast<hipStream_t>(hip_stream)};
     return run_both(c, ciar::Mode::Fused);
 }
 
-int ciar_stream_rows(const void* draft_logits, const void* target_logits, int with_intervals, int64_t N,
-                     const ciar_params* params, void* workspace, size_t workspace_bytes, void* hip_stream)
+int ciar_stream_rows(const void* draft_logits, const void* radius, const void* target_logits, int with_intervals,
+                     int64_t N, const ciar_params* params, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     if (!target_logits && !with_intervals)
         return fail(CIAR_EINVAL, "neither target_logits nor with_intervals: nothing to compute");
     const ciar::Mode mode = !target_logits ? ciar::Mode::Quantify
                                            : (with_intervals ? ciar::Mode::Fused : ciar::Mode::Verify);
     Call c{};
-    c.draft = draft_logits; c.target = target_logits; c.N = N; c.params = params;
+    c.draft = draft_logits; c.radius = radius; c.target = target_logits; c.N = N; c.params = params;
     c.workspace = workspace; c.workspace_bytes = workspace_bytes; c.stream = static_cast<hipStream_t>(hip_stream);
     return run_stream(c, mode);
 }
 
-int ciar_finish_rows(const void* draft_logits, const void* target_logits, const int32_t* draft_ids,
-                     const float* u_accept, const float* u_resample, int64_t N, const ciar_params* params,
-                     float* p_lo, float* p_mid, float* p_hi, float* omega, float* sigma, float* score,
-                     uint8_t* flags, uint8_t* accept, int32_t* row_resample_id, int32_t* accept_len,
+int ciar_finish_rows(const void* draft_logits, const void* radius, const void* target_logits,
+                     const int32_t* draft_ids, const float* u_accept, const float* u_resample, int64_t N,
+                     const ciar_params* params, float* p_lo, float* p_mid, float* p_hi, float* omega, float* sigma,
+                     float* score, uint8_t* flags, uint8_t* accept, int32_t* row_resample_id, int32_t* accept_len,
                      int32_t* resampled_id, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    const Call c{draft_logits, target_logits, draft_ids, u_accept, u_resample, N, params, p_lo, p_mid, p_hi, omega,
+    const Call c{draft_logits, radius, target_logits, draft_ids, u_accept, u_resample, N, params, p_lo, p_mid, p_hi, omega,
                  sigma, score, flags, accept, row_resample_id, accept_len, resampled_id, workspace, workspace_bytes,
                  static_cast<hipStream_t>(hip_stream)};
     if (target_logits && !wants_verify(c)) return fail(CIAR_EINVAL, "target_logits given but no verify output");
@@ -348,8 +365,8 @@ int ciar_window_epilogue(const uint8_t* accept, const int32_t* row_resample_id, 
     return CIAR_OK;
 }
 
-int ciar_dense_intervals(const void* draft_logits, int64_t N, const ciar_params* params, float* p_lo,
-                         float* p_mid, float* p_hi, void* hip_stream)
+int ciar_dense_intervals(const void* draft_logits, const void* radius, int64_t N, const ciar_params* params,
+                         float* p_lo, float* p_mid, float* p_hi, void* hip_stream)
 {
     Resolved r;
     if (int rc = check_params(params, &r)) return rc;
@@ -357,8 +374,11 @@ int ciar_dense_intervals(const void* draft_logits, int64_t N, const ciar_params*
     if (int rc = check_rows(draft_logits, "draft_logits")) return rc;
     if (!p_lo && !p_mid && !p_hi) return fail(CIAR_EINVAL, "every output pointer is NULL");
     if (N > 0x7fffffffLL) return fail(CIAR_EUNSUPPORTED, "N exceeds 2^31 - 1 rows per call");
+    if (radius)
+        if (int rc = check_rows(radius, "radius")) return rc;
     ciar::RowArgs a = base_args(params, r, N);
     a.draft = draft_logits;
+    a.radius = radius;
     if (N == 0) return CIAR_OK;
     hipError_t e = ciar::launch_dense(params->dtype, a, p_lo, p_mid, p_hi, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return hip_fail(e, "dense kernel launch");

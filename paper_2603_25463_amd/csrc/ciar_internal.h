@@ -24,6 +24,7 @@ static_assert(sizeof(RowStats) == 72, "RowStats layout");
 struct RowArgs {
     const void*    draft;       // [N, stride] centre logits
     const void*    target;      // [N, stride] verifier logits (verify only)
+    const void*    radius;      // [N, stride] raw radius tensor, or null: scalar radius
     const int32_t* ids;         // [N] drafted token (may be null for quantify: arg-max token)
     const float*   u_accept;    // [N]
     const float*   u_resample;  // [N]
@@ -39,8 +40,10 @@ struct RowArgs {
     int64_t  stride;            // elements between rows
     int32_t  V;
     int32_t  normalize;
-    double   a;                 // e^{+r}
+    double   a;                 // e^{+r}   (scalar radius r = min(kappa, rmax))
     double   b;                 // e^{-r}
+    double   kappa;             // radius scale: tensor mode r_i = min(kappa Softplus(raw_i), rmax)
+    double   rmax;              // radius clamp
     double   tau;
     double   cap_lo;            // 0.99
     double   cap_hi;            // 1.01
@@ -63,6 +66,9 @@ hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, int32_t K, i
 // accept_len / resampled_id per window of K rows from the per-row results.
 hipError_t launch_windows(const uint8_t* accept, const int32_t* row_id, int64_t N, int32_t K,
                           int32_t* accept_len, int32_t* resampled_id, hipStream_t stream);
+
+// out[row] = lowest index of the row's largest centre logit.
+hipError_t launch_argmax(int dtype, const RowArgs& args, int32_t* out, hipStream_t stream);
 
 // Dense [N, V] export of p_lo, p_mid, p_hi (any may be null).
 hipError_t launch_dense(int dtype, const RowArgs& args, float* p_lo, float* p_mid, float* p_hi,

@@ -99,6 +99,14 @@ template <> struct Elt<float> {
         if (base + 2 >= V) r.z = kNegInfWord;
         if (base + 3 >= V) r.w = kNegInfWord;
     }
+    // ... by zero.
+    __device__ static __forceinline__ void zero_tail(u32x4& r, int base, int V)
+    {
+        if (base + 0 >= V) r.x = 0u;
+        if (base + 1 >= V) r.y = 0u;
+        if (base + 2 >= V) r.z = 0u;
+        if (base + 3 >= V) r.w = 0u;
+    }
 };
 struct bf16_t { uint16_t bits; };
 template <> struct Elt<bf16_t> {
@@ -121,6 +129,15 @@ template <> struct Elt<bf16_t> {
     {
         r.x = mask_word(r.x, base + 0, V); r.y = mask_word(r.y, base + 2, V);
         r.z = mask_word(r.z, base + 4, V); r.w = mask_word(r.w, base + 6, V);
+    }
+    __device__ static __forceinline__ uint32_t zero_word(uint32_t w, int base, int V)
+    {
+        return w & ((base < V ? 0x0000ffffu : 0u) | (base + 1 < V ? 0xffff0000u : 0u));
+    }
+    __device__ static __forceinline__ void zero_tail(u32x4& r, int base, int V)
+    {
+        r.x = zero_word(r.x, base + 0, V); r.y = zero_word(r.y, base + 2, V);
+        r.z = zero_word(r.z, base + 4, V); r.w = zero_word(r.w, base + 6, V);
     }
 };
 
@@ -253,15 +270,54 @@ __device__ __forceinline__ void fuse_token(float e, const FuseRow& r, float& gl,
     gw = g * om;
 }
 
+// Tensor-radius mode (Sec. 3.2.3, the Interval Head: r = Softplus(raw)): a = e^r, b = e^-r for
+// r = min(kappa Softplus(raw), rmax).  Softplus(raw) = max(raw, 0) + ln(1 + t), t = e^-|raw|;
+// ln(1 + t) = ln(u) t / (u - 1) with u = fl(1 + t): u - 1 is exact, so the rounding of 1 + t cancels in
+// the ratio and small radii (raw << 0) keep their relative accuracy.
+__device__ __forceinline__ void radius_ab(float raw, float kappa, float rmax, float& a, float& b)
+{
+    const float t = __builtin_amdgcn_exp2f(-fabsf(raw) * 1.44269504f);
+    const float u = 1.0f + t;
+    const float d = u - 1.0f;
+    const float lg = d == 0.f ? t : (__builtin_amdgcn_logf(u) * 0.693147181f) * (t * __builtin_amdgcn_rcpf(d));
+    const float r = fminf(kappa * (fmaxf(raw, 0.f) + lg), rmax);
+    a = __builtin_amdgcn_exp2f(r * 1.44269504f);
+    b = __builtin_amdgcn_rcpf(a);
+}
+
+// The same radius in fp64 (one token per row: the reported token's interval).
+__device__ __forceinline__ double radius_of(double raw, double kappa, double rmax)
+{
+    const double sp = raw > 0.0 ? raw + log1p(exp(-raw)) : log1p(exp(raw));
+    return fmin(kappa * sp, rmax);
+}
+
+// Tensor-radius token: pl = p^l_i S and w = (p^u_i - p^l_i) S in the units of e.
+__device__ __forceinline__ void fuse_token_rad(float e, float raw, const FuseRow& r, float kappa, float rmax,
+                                               float& pl, float& w)
+{
+    float a, b;
+    radius_ab(raw, kappa, rmax, a, b);
+    const float om = fmaf(e, r.nil, fmaf(e, r.nih, 1.0f));        // 1 - x
+    const float x = -e * r.nih;
+    const float du = fmaf(a - 1.0f, x, 1.0f);
+    const float dl = fmaf(om, 1.0f - b, b);
+    const float g = e * __builtin_amdgcn_rcpf(du * dl);
+    pl = b * (g * du);
+    w = (a - b) * (g * om);
+}
+
 // Per-row scalars of the quantifier from the five sums (fp64, one lane).
 struct RowScore { double alpha_l, alpha_u, omega, sigma, score; };
 
 __device__ __forceinline__ RowScore finish_score(const double* s, double S, bool capless, const RowArgs& A)
 {
-    // s = { sum gl, sum gw, sum gl^2, sum gw^2, sum gl gw } over the V tokens of the row;
+    // s = { sum gl, sum gw, sum gl^2, sum gw^2, sum gl gw } over the V tokens of the row, with
+    // p^l_i = Bc gl_i and p^u_i - p^l_i = Wc gw_i (tensor-radius mode: the per-token factors are already
+    // inside gl and gw);
     // capless = the caps are known to be inactive and only sum gw, sum gw^2 were accumulated
     const double V = (double)A.V;
-    const double Bc = A.b / S, Wc = (A.a - A.b) / S;
+    const double Bc = (A.radius ? 1.0 : A.b) / S, Wc = (A.radius ? 1.0 : A.a - A.b) / S;
     const double Sl = Bc * s[0], Su = Sl + Wc * s[1];
     RowScore o;
     o.alpha_l = 1.0; o.alpha_u = 1.0;
@@ -287,11 +343,12 @@ __device__ __forceinline__ RowScore finish_score(const double* s, double S, bool
 // registers, capped at 4 waves.  Memory latency is hidden by the other resident workgroups of the compute
 // unit rather than by fetching ahead into a second set of registers: measured on this chip, three or
 // four resident workgroups beat two with a register prefetch of the next row at every vocabulary size.
-template <typename T, int THREADS, int NVEC>
+// (Tensor-radius mode: the raw radius row sits in registers next to the centre row during the interval pass.)
+template <typename T, int THREADS, int NVEC, bool RAD>
 constexpr int target_waves()
 {
     constexpr int ept = NVEC * Elt<T>::kPerVec;                    // one row as floats
-    constexpr int fit = 512 / (ept + 40);
+    constexpr int fit = 512 / (ept + (RAD ? NVEC * 4 + 8 : 0) + 40);
     constexpr int lo = THREADS / 256;                              // waves per SIMD one workgroup needs
     return fit < lo ? lo : (fit > 4 ? 4 : fit);
 }
@@ -336,9 +393,42 @@ __device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const Fu
     q5[4] = a4[0] + a4[1];
 }
 
-template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V>
+// Pass C in tensor-radius mode: every token has its own a_i, b_i from the raw radius row `rad` (as loaded,
+// padding already zeroed); the sums are of p^l_i S and (p^u_i - p^l_i) S themselves.
+template <typename T, int THREADS, int NVEC>
+__device__ __forceinline__ void fuse_sums_rad(const float (&e)[NVEC * Elt<T>::kPerVec], const u32x4 (&rad)[NVEC],
+                                              const FuseRow& fr, float kappa, float rmax, int V, double (&q5)[5])
+{
+    constexpr int EPV = Elt<T>::kPerVec;
+    double a0[2] = {0.0, 0.0}, a1[2] = {0.0, 0.0}, a2[2] = {0.0, 0.0}, a3[2] = {0.0, 0.0}, a4[2] = {0.0, 0.0};
+#pragma unroll
+    for (int j = 0; j < NVEC; ++j) {
+        if (j * THREADS * EPV >= V) continue;                      // uniform: the chunk holds no token
+        float raw[EPV];
+        Elt<T>::unpack(rad[j], raw);
+#pragma unroll
+        for (int k = 0; k < EPV; ++k) {
+            float pl, w;
+            fuse_token_rad(e[j * EPV + k], raw[k], fr, kappa, rmax, pl, w);   // padding has e = 0: pl = w = 0
+            const double dl = (double)pl, dw = (double)w;
+            a0[k & 1] += dl;
+            a1[k & 1] += dw;
+            a2[k & 1] = fma(dl, dl, a2[k & 1]);
+            a3[k & 1] = fma(dw, dw, a3[k & 1]);
+            a4[k & 1] = fma(dl, dw, a4[k & 1]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    q5[0] = a0[0] + a0[1];
+    q5[1] = a1[0] + a1[1];
+    q5[2] = a2[0] + a2[1];
+    q5[3] = a3[0] + a3[1];
+    q5[4] = a4[0] + a4[1];
+}
+
+template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V, bool RAD>
 __global__ __launch_bounds__(THREADS)
-__attribute__((amdgpu_waves_per_eu(target_waves<T, THREADS, NVEC>())))
+__attribute__((amdgpu_waves_per_eu(target_waves<T, THREADS, NVEC, RAD>())))
 void stream_kernel(const RowArgs A)
 {
     using E = Elt<T>;
@@ -491,13 +581,24 @@ void stream_kernel(const RowArgs A)
         // x_max of the row, so below the host-computed bound on x_max both caps are inactive and the
         // cheaper width-only pass is exact.  Uniform over the workgroup.
         const double emax = (double)exp2_ref(mc, n);               // the row's largest e_i, in row units
-        const bool capless = !A.normalize || emax <= A.capless_xmax * S;
+        const bool capless = !A.normalize || (!RAD && emax <= A.capless_xmax * S);
         const bool split = emax > 0.5 * S;                         // some x_i above 1/2: 1 - x needs the two-float 1/S
         if constexpr (DO_Q) {
             // x_i = e_i fw / S: hand fuse_row the partition sum expressed in this wave's units
             const FuseRow fr = fuse_row(fw > 0.0 ? S / fw : 1.0, A.a, A.b);
             double q5[5];
-            if (capless) {
+            if constexpr (RAD) {
+                // the raw radius row comes into the registers the centre row came in
+                __builtin_amdgcn_sched_barrier(0);
+                load_row(buf, A.radius, row);
+                if (partial) {
+#pragma unroll
+                    for (int j = 0; j < NVEC; ++j) E::zero_tail(buf[j], (j * THREADS + tid) * EPV, V);
+                }
+                fuse_sums_rad<T, THREADS, NVEC>(e, buf, fr, (float)A.kappa, (float)A.rmax, V, q5);
+#pragma unroll
+                for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
+            } else if (capless) {
                 if (split) fuse_sums<THREADS, NVEC, EPV, true, true>(e, fr, V, q5);
                 else       fuse_sums<THREADS, NVEC, EPV, true, false>(e, fr, V, q5);
                 q5[1] = wave_sum(q5[1]);
@@ -618,9 +719,16 @@ __global__ __launch_bounds__(256) void rowfinish_kernel(const RowArgs A, const i
             if (A.flags) A.flags[row] = (uint8_t)(rs.score > A.tau);
             if (A.p_lo || A.p_mid || A.p_hi) {
                 const double x = exp((double)cx - (double)n * kLn2) / S;
+                double a = A.a, b = A.b;
+                if (A.radius) {
+                    // the reported token's own radius (the launcher supplies ids in this mode)
+                    const T* rrow = static_cast<const T*>(A.radius) + row * A.stride;
+                    const double r = radius_of((double)load_logit(rrow, xid < 0 ? 0 : xid), A.kappa, A.rmax);
+                    a = exp(r); b = exp(-r);
+                }
                 if (A.p_mid) A.p_mid[row] = (float)x;
-                if (A.p_lo) A.p_lo[row] = (float)(rs.alpha_l * A.b * x / (1.0 + (A.b - 1.0) * x));
-                if (A.p_hi) A.p_hi[row] = (float)(rs.alpha_u * A.a * x / (1.0 + (A.a - 1.0) * x));
+                if (A.p_lo) A.p_lo[row] = (float)(rs.alpha_l * b * x / (1.0 + (b - 1.0) * x));
+                if (A.p_hi) A.p_hi[row] = (float)(rs.alpha_u * a * x / (1.0 + (a - 1.0) * x));
             }
         }
         if (do_v) {
@@ -803,6 +911,37 @@ __global__ __launch_bounds__(1024) void resample_kernel(const RowArgs A, const i
     }
 }
 
+// ---- arg-max token of every row (tensor-radius calls without drafted ids) ----------------------------------
+
+// One workgroup per row: the lowest index that holds the row's largest centre logit.  Only the
+// tensor-radius mode needs the index itself (to pick that token's radius); the scalar mode reports the
+// arg-max token from the row maximum alone.
+template <typename T>
+__global__ __launch_bounds__(256) void argmax_kernel(const RowArgs A, int32_t* __restrict__ out)
+{
+    __shared__ float sm_m[4];
+    __shared__ int sm_i[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row = blockIdx.x;
+    const T* c = static_cast<const T*>(A.draft) + row * A.stride;
+    float m = -INFINITY;
+    int idx = INT_MAX;
+    for (int i = tid; i < A.V; i += 256) {
+        const float v = load_logit(c, i);
+        if (v > m || idx == INT_MAX) { m = v; idx = i; }           // ascending i: the first of equal values stays
+    }
+    const float wm = wave_max(m);
+    const int wi = wave_min_i(m == wm ? idx : INT_MAX);
+    if (lane == 0) { sm_m[wave] = wm; sm_i[wave] = wi; }
+    __syncthreads();
+    if (tid == 0) {
+        const float rm = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));
+        int best = INT_MAX;
+        for (int w = 0; w < 4; ++w) if (sm_m[w] == rm && sm_i[w] < best) best = sm_i[w];
+        out[row] = best == INT_MAX ? 0 : best;
+    }
+}
+
 // ---- window epilogue: one thread per window of K rows -------------------------------------------------
 
 __global__ __launch_bounds__(256) void window_kernel(const uint8_t* __restrict__ accept,
@@ -851,12 +990,20 @@ __global__ __launch_bounds__(256) void dense_kernel(const RowArgs A, float* __re
     const double S = block_sum(acc);
 
     const FuseRow fr = fuse_row(S, A.a, A.b);
+    const T* rad = A.radius ? static_cast<const T*>(A.radius) + row * A.stride : nullptr;
+    const float kap = (float)A.kappa, rmax = (float)A.rmax;
+    // gl, gw of one token: p^l = Bc gl, p^u - p^l = Wc gw (tensor-radius mode: Bc = Wc = 1 / S)
+    auto token = [&](int i, float& e, float& gl, float& gw) {
+        e = exp2_ref(load_logit(c, i), n);
+        if (rad) fuse_token_rad(e, load_logit(rad, i), fr, kap, rmax, gl, gw);
+        else fuse_token(e, fr, gl, gw);
+    };
     double q5[5];
     {
         double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0, a4 = 0.0;
         for (int i = tid; i < V; i += 256) {
-            float gl, gw;
-            fuse_token(exp2_ref(load_logit(c, i), n), fr, gl, gw);
+            float e, gl, gw;
+            token(i, e, gl, gw);
             const double dl = (double)gl, dw = (double)gw;
             a0 += dl; a1 += dw;
             a2 = fma(dl, dl, a2); a3 = fma(dw, dw, a3); a4 = fma(dl, dw, a4);
@@ -866,12 +1013,11 @@ __global__ __launch_bounds__(256) void dense_kernel(const RowArgs A, float* __re
     }
     const RowScore rs = finish_score(q5, S, false, A);
 
-    const float Bc = (float)(A.b / S), Wc = (float)((A.a - A.b) / S), invS = (float)(1.0 / S);
+    const float Bc = (float)((rad ? 1.0 : A.b) / S), Wc = (float)((rad ? 1.0 : A.a - A.b) / S), invS = (float)(1.0 / S);
     const float al = (float)rs.alpha_l, au = (float)rs.alpha_u;
     for (int i = tid; i < V; i += 256) {
-        const float e = exp2_ref(load_logit(c, i), n);
-        float gl, gw;
-        fuse_token(e, fr, gl, gw);
+        float e, gl, gw;
+        token(i, e, gl, gw);
         const float pl = Bc * gl;
         const float pu = fmaf(Wc, gw, pl);
         const int64_t o = row * (int64_t)V + i;
@@ -972,26 +1118,29 @@ int compute_units()
     return cache[dev];
 }
 
-template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V>
+template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V, bool RAD>
 hipError_t launch_stream_kernel(const RowArgs& a, hipStream_t s)
 {
     // One wave of resident workgroups, each walking over rows with stride gridDim.x.  The register
     // budget the kernel was compiled for fixes how many fit: target_waves() waves per SIMD, and a
     // workgroup puts THREADS / 256 waves on each of the four SIMDs of a compute unit.
-    constexpr int per_cu = target_waves<T, THREADS, NVEC>() / (THREADS / 256);
+    constexpr int per_cu = target_waves<T, THREADS, NVEC, RAD>() / (THREADS / 256);
     const int64_t resident = (int64_t)per_cu * compute_units();
     const unsigned grid = (unsigned)(a.N < resident ? a.N : resident);
-    hipLaunchKernelGGL((stream_kernel<T, THREADS, NVEC, DO_Q, DO_V>), dim3(grid), dim3(THREADS), 0, s, a);
+    hipLaunchKernelGGL((stream_kernel<T, THREADS, NVEC, DO_Q, DO_V, RAD>), dim3(grid), dim3(THREADS), 0, s, a);
     return hipGetLastError();
 }
 
 template <typename T, int THREADS, int NVEC>
 hipError_t launch_stream_cfg(Mode mode, const RowArgs& a, hipStream_t s)
 {
+    const bool rad = a.radius != nullptr;
     switch (mode) {
-    case Mode::Quantify: return launch_stream_kernel<T, THREADS, NVEC, true, false>(a, s);
-    case Mode::Verify:   return launch_stream_kernel<T, THREADS, NVEC, false, true>(a, s);
-    case Mode::Fused:    return launch_stream_kernel<T, THREADS, NVEC, true, true>(a, s);
+    case Mode::Quantify: return rad ? launch_stream_kernel<T, THREADS, NVEC, true, false, true>(a, s)
+                                    : launch_stream_kernel<T, THREADS, NVEC, true, false, false>(a, s);
+    case Mode::Verify:   return launch_stream_kernel<T, THREADS, NVEC, false, true, false>(a, s);
+    case Mode::Fused:    return rad ? launch_stream_kernel<T, THREADS, NVEC, true, true, true>(a, s)
+                                    : launch_stream_kernel<T, THREADS, NVEC, true, true, false>(a, s);
     }
     return hipErrorInvalidValue;
 }
@@ -1079,6 +1228,15 @@ hipError_t launch_dense(int dtype, const RowArgs& args, float* p_lo, float* p_mi
     const dim3 grid((unsigned)args.N), block(256);
     if (dtype == 0) hipLaunchKernelGGL(dense_kernel<float>, grid, block, 0, stream, args, p_lo, p_mid, p_hi);
     else hipLaunchKernelGGL(dense_kernel<bf16_t>, grid, block, 0, stream, args, p_lo, p_mid, p_hi);
+    return hipGetLastError();
+}
+
+hipError_t launch_argmax(int dtype, const RowArgs& args, int32_t* out, hipStream_t stream)
+{
+    if (args.N <= 0) return hipSuccess;
+    const dim3 grid((unsigned)args.N), block(256);
+    if (dtype == 0) hipLaunchKernelGGL(argmax_kernel<float>, grid, block, 0, stream, args, out);
+    else hipLaunchKernelGGL(argmax_kernel<bf16_t>, grid, block, 0, stream, args, out);
     return hipGetLastError();
 }
 

@@ -196,6 +196,26 @@ def make(cfg: int, device="cpu", rows: int | None = None, seed: int | None = Non
                     {"seed": seed, "redraw": redraw[:N].copy()})
 
 
+def make_radius(w: Workload, device=None, seed: int | None = None) -> torch.Tensor:
+    """Raw radius tensor for the tensor-radius mode: what the radius half of an Interval Head would emit
+    before its Softplus.  No trained head is available, so the stand-in is raw ~ N(mu_row, 1) with one
+    mean per row, mu_row ~ U(-1, 1) (Softplus then gives radii of about 0.3 ... 2.5), in the dtype and
+    shape of the workload's logits.  Seeded per 256-row block like the logits."""
+    device = w.draft.device if device is None else torch.device(device)
+    seed = (int(w.meta["seed"]) ^ 0x5AD105) if seed is None else seed
+    N, V = w.draft.shape
+    mu = np.random.default_rng(seed).uniform(-1.0, 1.0, size=w.spec.rows).astype(np.float32)
+    out = torch.empty((N, V), dtype=w.draft.dtype, device=device)
+    for lo in range(0, N, _CHUNK):
+        hi = min(lo + _CHUNK, N)
+        gen = torch.Generator(device=device)
+        gen.manual_seed((seed * 1000003 + lo // _CHUNK) & 0x7FFFFFFFFFFFFFFF)
+        raw = torch.randn((_CHUNK, V), generator=gen, device=device, dtype=torch.float32)[:hi - lo]
+        raw += torch.from_numpy(mu[lo:hi]).to(device)[:, None]
+        out[lo:hi] = raw.to(w.draft.dtype)
+    return out
+
+
 def take_rows(w: Workload, index) -> Workload:
     """Row subset (e.g. whole sampled windows) on the same device."""
     idx_np = np.asarray(index, dtype=np.int64)

@@ -62,7 +62,7 @@ FAKE = 0x7f0000000000          # 16-byte aligned, never dereferenced on an error
 
 
 def _quantify(L, p, draft=FAKE, N=4, out=FAKE + 4096, ws=FAKE + 8192, wsb=1 << 20):
-    return L.ciar_quantify(draft, None, N, ctypes.byref(p), out, None, None, None, None, None, None,
+    return L.ciar_quantify(draft, None, None, N, ctypes.byref(p), out, None, None, None, None, None, None,
                            ws, wsb, None)
 
 
@@ -87,7 +87,7 @@ def test_argument_errors_are_reported_before_any_launch(L):
     assert _quantify(L, _params(L), draft=FAKE + 4) == EALIGN
     assert _quantify(L, _params(L), N=-1) == EINVAL
     assert _quantify(L, _params(L), out=None) == EINVAL and "output" in last_error()
-    assert L.ciar_quantify(FAKE, None, 4, None, FAKE, None, None, None, None, None, None, FAKE, 4096, None) == EINVAL
+    assert L.ciar_quantify(FAKE, None, None, 4, None, FAKE, None, None, None, None, None, None, FAKE, 4096, None) == EINVAL
     # the workspace carries the per-row statistics between the two kernels: always required
     assert _quantify(L, _params(L), ws=None, wsb=0) == EWORK and "workspace" in last_error()
     assert _quantify(L, _params(L), wsb=64) == EWORK
@@ -104,15 +104,18 @@ def test_argument_errors_are_reported_before_any_launch(L):
     assert L.ciar_verify(FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, None, None, FAKE, FAKE, None, 0, None) == EWORK
     assert L.ciar_verify(FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, None, None, FAKE, FAKE, FAKE, 8, None) == EWORK
     assert L.ciar_verify(FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, None, None, FAKE, FAKE, FAKE + 8, 4096, None) == EALIGN
-    assert L.ciar_quantify_verify(FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, *([None] * 11), None, 0, None) == EINVAL
-    assert L.ciar_dense_intervals(FAKE, 4, a, None, None, None, None) == EINVAL
+    assert L.ciar_quantify_verify(FAKE, None, FAKE, FAKE, FAKE, FAKE, 4, a, *([None] * 11), None, 0, None) == EINVAL
+    assert L.ciar_dense_intervals(FAKE, None, 4, a, None, None, None, None) == EINVAL
+    assert L.ciar_dense_intervals(FAKE, FAKE + 8, 4, a, FAKE, None, None, None) == EALIGN     # radius alignment
     # the stages on their own
-    assert L.ciar_stream_rows(FAKE, None, 0, 4, a, FAKE, 4096, None) == EINVAL      # nothing to compute
-    assert L.ciar_stream_rows(FAKE, FAKE, 1, 4, a, None, 0, None) == EWORK
-    assert L.ciar_stream_rows(None, FAKE, 1, 4, a, FAKE, 4096, None) == EINVAL
-    assert L.ciar_finish_rows(FAKE, None, FAKE, FAKE, FAKE, 4, a, *([None] * 7), FAKE, FAKE, None, None,
+    assert L.ciar_stream_rows(FAKE, None, None, 0, 4, a, FAKE, 4096, None) == EINVAL      # nothing to compute
+    assert L.ciar_stream_rows(FAKE, None, FAKE, 1, 4, a, None, 0, None) == EWORK
+    assert L.ciar_stream_rows(None, None, FAKE, 1, 4, a, FAKE, 4096, None) == EINVAL
+    assert L.ciar_stream_rows(FAKE, FAKE, FAKE, 0, 4, a, FAKE, 4096, None) == EINVAL      # radius without intervals
+    assert L.ciar_stream_rows(FAKE, FAKE + 4, FAKE, 1, 4, a, FAKE, 4096, None) == EALIGN  # radius alignment
+    assert L.ciar_finish_rows(FAKE, None, None, FAKE, FAKE, FAKE, 4, a, *([None] * 7), FAKE, FAKE, None, None,
                               FAKE, 4096, None) == EINVAL                            # verify outputs, no target
-    assert L.ciar_finish_rows(FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, FAKE, *([None] * 10), FAKE, 4096,
+    assert L.ciar_finish_rows(FAKE, None, FAKE, FAKE, FAKE, FAKE, 4, a, FAKE, *([None] * 10), FAKE, 4096,
                               None) == EINVAL                                        # target, no verify output
     assert L.ciar_read_rows(FAKE, FAKE, 4, a, None, None) == EINVAL
     assert L.ciar_read_rows(None, FAKE, 4, a, FAKE, None) == EINVAL
@@ -128,7 +131,7 @@ def test_empty_batch_is_ok_and_launches_nothing(L):
     a = ctypes.byref(p)
     assert _quantify(L, p, N=0) == 0
     assert L.ciar_verify(FAKE, FAKE, FAKE, FAKE, FAKE, 0, a, FAKE, FAKE, FAKE, FAKE, None, 0, None) == 0
-    assert L.ciar_dense_intervals(FAKE, 0, a, FAKE, None, None, None) == 0
+    assert L.ciar_dense_intervals(FAKE, None, 0, a, FAKE, None, None, None) == 0
 
 
 def test_workspace_size(L):

@@ -30,19 +30,21 @@ def _oparams(oracle, p):
                          lower_cap=p.lower_cap, upper_cap=p.upper_cap, normalize=p.normalize, window=p.window)
 
 
-def _run_case(ciar, oracle, draft, target, ids, ua, ur, P, vocab=None, tag="", host=None):
-    """Fused, quantify-only and verify-only entry points against the oracle.  Tensors are on the GPU."""
+def _run_case(ciar, oracle, draft, target, ids, ua, ur, P, vocab=None, tag="", host=None, radius=None):
+    """Fused, quantify-only and verify-only entry points against the oracle.  Tensors are on the GPU.
+    ``radius``: raw radius tensor (tensor-radius mode) or None (scalar radius)."""
     say(f"[case {tag}] N={draft.shape[0]} V={vocab or draft.shape[1]} dtype={draft.dtype} "
-        f"K={P.window} conf={P.confidence} kappa={P.radius_scale} tau={P.tau} norm={P.normalize}")
+        f"K={P.window} conf={P.confidence} kappa={P.radius_scale} tau={P.tau} norm={P.normalize} "
+        f"radius={'tensor' if radius is not None else 'scalar'}")
     N = draft.shape[0]
     ws = torch.empty(ciar.workspace_bytes(N, P.to_c(draft, vocab)) or 16, dtype=torch.uint8, device=draft.device)
-    fused = ciar.quantify_verify(draft, target, ids, ua, ur, P, vocab=vocab, workspace=ws)
-    qonly = ciar.quantify(draft, ids, P, vocab=vocab, workspace=ws)
+    fused = ciar.quantify_verify(draft, target, ids, ua, ur, P, vocab=vocab, workspace=ws, radius=radius)
+    qonly = ciar.quantify(draft, ids, P, vocab=vocab, workspace=ws, radius=radius)
     vonly = ciar.verify(draft, target, ids, ua, ur, P, vocab=vocab, workspace=ws)
     # the launch configuration the benchmark times: the two stages called one after the other
     ws2 = torch.empty_like(ws)
-    ciar.stream_rows(draft, target, True, P, ws2, vocab=vocab)
-    staged = ciar.finish_rows(draft, target, ids, ua, ur, P, ws2, with_intervals=True, vocab=vocab)
+    ciar.stream_rows(draft, target, True, P, ws2, vocab=vocab, radius=radius)
+    staged = ciar.finish_rows(draft, target, ids, ua, ur, P, ws2, with_intervals=True, vocab=vocab, radius=radius)
     torch.cuda.synchronize()
     # the entry points run the same arithmetic: bit-identical outputs
     for k in parity.FLOAT_KEYS + ("flags",):
@@ -55,7 +57,7 @@ def _run_case(ciar, oracle, draft, target, ids, ua, ur, P, vocab=None, tag="", h
     OP = _oparams(oracle, P)
     dh, th = host if host is not None else (draft.cpu(), target.cpu())
     idh, uah, urh = ids.cpu().numpy(), ua.cpu().numpy(), ur.cpu().numpy()
-    oq = oracle.quantify(dh, idh, OP, vocab=vocab)
+    oq = oracle.quantify(dh, idh, OP, vocab=vocab, radius=None if radius is None else radius.cpu())
     ov = oracle.verify(dh, th, idh, uah, urh, OP, vocab=vocab)
     worst = parity.check_floats(fused, oq)
     ex_flag = parity.check_flags(fused["flags"], oq, float(np.float32(P.tau)))
@@ -187,6 +189,104 @@ def test_shapes_and_ragged_tails(ciar, oracle, V, stride, N, K, dtype):
         _run_case(ciar, oracle, c, t, ids, ua, ur, P, vocab=V, tag=f"V={V} stride={stride}")
 
 
+# ---- tensor-radius mode: r_i = min(kappa Softplus(raw_i), r_max)  (Sec. 3.2.3, Interval Head) ----------------
+
+def _raw_radius(N, stride, V, dtype, seed, mu_lo=-1.0, mu_hi=1.0, sd=1.0):
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    mu = torch.rand((N, 1), generator=g, device="cuda") * (mu_hi - mu_lo) + mu_lo
+    raw = torch.randn((N, stride), generator=g, device="cuda") * sd + mu
+    if stride > V:
+        raw[:, V:] = float("nan")          # poison the padding: it must never reach a result
+    return raw.to(dtype)
+
+
+RADIUS_SHAPES = [
+    (2, 4, 37, 4, torch.float32), (5, 8, 19, 3, torch.float32), (1023, 1024, 33, 5, torch.float32),
+    (3000, 3000, 40, 7, torch.float32), (8192, 8192, 48, 16, torch.float32), (12345, 12348, 35, 8, torch.float32),
+    (16384, 16384, 70, 8, torch.float32), (32768, 32768, 12, 4, torch.float32),
+    (3, 8, 37, 4, torch.bfloat16), (1001, 1008, 65, 8, torch.bfloat16), (5000, 5000, 40, 6, torch.bfloat16),
+    (16384, 16384, 64, 8, torch.bfloat16), (20000, 20000, 17, 8, torch.bfloat16), (65535, 65536, 9, 4, torch.bfloat16),
+]
+
+
+@pytest.mark.parametrize("V,stride,N,K,dtype", RADIUS_SHAPES)
+def test_tensor_radius_shapes(ciar, oracle, V, stride, N, K, dtype):
+    c, t, ids, ua, ur = _random_case(V, stride, N, K, dtype, seed=2000 + V)
+    raw = _raw_radius(N, stride, V, dtype, seed=3000 + V)
+    for norm, kap in ((True, 1.0), (False, 0.6)):
+        P = ciar.Params(radius_scale=kap, normalize=norm, window=K, tau=0.01)
+        _run_case(ciar, oracle, c, t, ids, ua, ur, P, vocab=V, tag=f"tensor radius V={V} stride={stride}",
+                  radius=raw)
+
+
+def test_tensor_radius_extremes_and_clamp(ciar, oracle):
+    """Raw radii from -60 (radius ~ 1e-26) to +60 (clamped), a small clamp, rows of constant raw radius (which
+    must reproduce the scalar mode bit for bit in the flags and to tolerance in the floats)."""
+    V, N, K = 4096, 24, 4
+    c, t, ids, ua, ur = _random_case(V, V, N, K, torch.float32, seed=61)
+    raw = _raw_radius(N, V, V, torch.float32, seed=62, mu_lo=-3.0, mu_hi=3.0, sd=8.0)
+    raw[0] = -60.0
+    raw[1] = 60.0
+    raw[2, ::2] = -30.0
+    for rmax in (10.0, 1.5):
+        P = ciar.Params(radius_scale=1.0, radius_max=rmax, window=K, tau=0.01)
+        _run_case(ciar, oracle, c, t, ids, ua, ur, P, tag=f"tensor radius extremes rmax={rmax}", radius=raw)
+    const = torch.full_like(c, 0.75)
+    kap = 1.3
+    r = kap * math.log1p(math.exp(0.75))
+    say("[tensor radius] constant raw radius against the scalar mode")
+    a = ciar.quantify(c, ids, ciar.Params(radius_scale=kap, tau=0.01), radius=const)
+    b = ciar.quantify(c, ids, ciar.Params(radius_scale=r, tau=0.01))
+    torch.cuda.synchronize()
+    for k in parity.FLOAT_KEYS:
+        assert torch.allclose(a[k], b[k], rtol=2e-5, atol=1e-7), k
+
+
+def test_tensor_radius_argmax_token_and_dense(ciar, oracle):
+    """Without drafted ids the reported token is the lowest-index arg-max and its own radius applies; the dense
+    curves match the oracle's."""
+    for V, dtype in ((1000, torch.float32), (16384, torch.bfloat16)):
+        c, *_ = _random_case(V, V, 9, 4, dtype, seed=71)
+        c[3, 5] = c[3].max() + 1
+        c[3, 400] = c[3, 5]                                           # a tie: the lower index wins
+        raw = _raw_radius(9, V, V, dtype, seed=72)
+        say(f"[tensor radius] arg-max report and dense export V={V} {dtype}")
+        P = ciar.Params(radius_scale=1.0)
+        g = ciar.quantify(c, None, P, radius=raw)
+        lo, mid, hi = ciar.dense_intervals(c, P, radius=raw)
+        torch.cuda.synchronize()
+        OP = oracle.Params(kappa=1.0)
+        o = oracle.quantify(c.cpu(), None, OP, radius=raw.cpu())
+        parity.check_floats(g, o)
+        olo, omid, ohi = oracle.dense_intervals(c.cpu(), OP, radius=raw.cpu())
+        for gg, oo in ((lo, olo), (mid, omid), (hi, ohi)):
+            gg = gg.cpu().numpy().astype(np.float64)
+            assert np.all(np.abs(gg - oo) <= parity.ATOL + parity.RTOL * np.abs(oo))
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3])
+def test_tensor_radius_workloads(ciar, oracle, cfg):
+    """Workloads 1-3 at full size with the synthetic radius head (raw ~ N(mu_row, 1), kappa = 1), at tau = 0.30
+    and at the oracle's median U."""
+    from paper_2603_25463_amd import workloads as wl
+    say(f"[tensor radius workload {cfg}] generating on the GPU")
+    w = wl.make(cfg, device="cuda")
+    raw = wl.make_radius(w)
+    P = ciar.Params(radius_scale=1.0, tau=0.30, window=w.spec.window)
+    oq, ov, exf, st = _run_case(ciar, oracle, w.draft, w.target, w.ids, w.u_accept, w.u_resample, P,
+                                tag=f"cfg{cfg} tensor radius", radius=raw)
+    tau_star = float(np.float32(np.median(oq["score"])))
+    g = ciar.quantify(w.draft, w.ids, ciar.Params(radius_scale=1.0, tau=tau_star, window=w.spec.window), radius=raw)
+    torch.cuda.synchronize()
+    oq2 = dict(oq)
+    oq2["flags"] = (oq["score"] > float(np.float32(tau_star))).astype(np.uint8)
+    parity.check_floats(g, oq2)
+    ex = parity.check_flags(g["flags"], oq2, float(np.float32(tau_star)))
+    frac = float(oq2["flags"].mean())
+    say(f"   tau*={tau_star:.6g} flagged fraction {frac:.3f}, exempt {ex}")
+    assert 0.4 < frac < 0.6 and ex <= 3
+
+
 @pytest.mark.parametrize("K", [1, 3, 8, 100, 128, 255, 256, 257, 300, 1000])
 def test_window_lengths(ciar, oracle, K):
     """Windows that divide, straddle and exceed the finishing kernel's 256-row workgroups; N = 700 leaves a
@@ -279,7 +379,7 @@ def test_null_outputs_and_workspace_paths(ciar, oracle):
     assert torch.equal(al2, ref["accept_len"])
     # a single quantify output
     sc = torch.empty(43, dtype=torch.float32, device="cuda")
-    rc = L.ciar_quantify(_ptr(c), None, 43, ctypes.byref(cp), None, None, None, None, None, _ptr(sc), None,
+    rc = L.ciar_quantify(_ptr(c), None, None, 43, ctypes.byref(cp), None, None, None, None, None, _ptr(sc), None,
                          _ptr(ws), ws.numel(), _stream(None))
     assert rc == 0, ciar.last_error()
     torch.cuda.synchronize()
