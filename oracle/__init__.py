@@ -67,6 +67,9 @@ def _load():
         lib.ciar_oracle_quantify.argtypes = [vp, vp, vp, i64, pp] + [vp] * 7 + [i32]
         lib.ciar_oracle_dense_intervals.restype = i32
         lib.ciar_oracle_dense_intervals.argtypes = [vp, vp, i64, pp, vp, vp, vp]
+        lib.ciar_oracle_quantify_multihead.restype = i32
+        lib.ciar_oracle_quantify_multihead.argtypes = [vp, vp, ctypes.c_int32, i64, vp, i64, pp, ctypes.c_int32] + \
+            [vp] * 8 + [i32]
         lib.ciar_oracle_residual_cdf.restype = ctypes.c_double
         lib.ciar_oracle_residual_cdf.argtypes = [vp, vp, i64, pp, vp]
         lib.ciar_oracle_verify.restype = i32
@@ -135,6 +138,49 @@ def quantify(draft, ids, params: Params, vocab: int | None = None, threads: int 
                                       _ptr(out["p_lo"]), _ptr(out["p_mid"]), _ptr(out["p_hi"]),
                                       _ptr(out["omega"]), _ptr(out["sigma"]), _ptr(out["score"]),
                                       _ptr(out["flags"]), threads or default_threads())
+    assert rc == 0
+    return out
+
+
+VOTING, ENSEMBLE = 0, 1
+
+
+def _heads(a) -> np.ndarray:
+    """[H, N, stride] logits of H heads as one C-contiguous array (float32, or uint16 bfloat16 bits)."""
+    if not isinstance(a, np.ndarray):
+        import torch
+        assert isinstance(a, torch.Tensor) and a.device.type == "cpu" and a.dim() == 3
+        if a.dtype == torch.bfloat16:
+            a = a.contiguous().view(torch.int16).numpy().view(np.uint16)
+        else:
+            a = a.contiguous().numpy()
+    assert a.dtype in (np.float32, np.uint16) and a.ndim == 3 and a.flags.c_contiguous
+    return a
+
+
+def quantify_multihead(draft_heads, ids, params: Params, strategy: int, vocab: int | None = None,
+                       threads: int | None = None, radius_heads=None):
+    """Quantifier over H heads ([H, N, stride]).  VOTING: per-head fp64 arrays [H, N], head_flags [H, N] and the
+    voted flags [N].  ENSEMBLE: arrays [N] from the token-wise average of the heads' curves."""
+    c = _heads(draft_heads)
+    H, N = c.shape[0], c.shape[1]
+    cp = _cparams(params, c[0], vocab)
+    rad = None
+    if radius_heads is not None:
+        rad = _heads(radius_heads)
+        assert rad.shape == c.shape and rad.dtype == c.dtype
+    ids32 = None if ids is None else np.ascontiguousarray(np.asarray(ids), dtype=np.int32)
+    if ids32 is not None:
+        assert ids32.shape == (N,) and (N == 0 or (ids32.min() >= 0 and ids32.max() < cp.vocab))
+    shape = (H, N) if strategy == VOTING else (N,)
+    out = {k: np.empty(shape, dtype=np.float64) for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score")}
+    out["flags"] = np.empty(N, dtype=np.uint8)
+    if strategy == VOTING:
+        out["head_flags"] = np.empty((H, N), dtype=np.uint8)
+    rc = _load().ciar_oracle_quantify_multihead(
+        _ptr(c), _ptr(rad), H, c.shape[1] * c.shape[2], _ptr(ids32), N, ctypes.byref(cp), int(strategy),
+        _ptr(out["p_lo"]), _ptr(out["p_mid"]), _ptr(out["p_hi"]), _ptr(out["omega"]), _ptr(out["sigma"]),
+        _ptr(out["score"]), _ptr(out["flags"]), _ptr(out.get("head_flags")), threads or default_threads())
     assert rc == 0
     return out
 

@@ -13,6 +13,9 @@
  *     Disparity Sigma (population std), score U = Omega*Sigma (Eq. "uncertainty_score"; App. "Analysis of the
  *                                                            Uncertainty Quantification", first three equations)
  *   - the threshold rule  "accept locally iff U <= tau"     (Algorithm 1, the test on U_t)
+ *   - aggregation of several Interval Heads                 (Sec. 4, ablation on the Inter-Head: "Voting" = the
+ *                                                            majority of the heads' decisions, "Ensemble" = the
+ *                                                            heads' probability distributions averaged)
  *   - cloud verification of a window of K drafted tokens and resampling (Algorithm 1, the "Cloud verification"
  *     step and the following resample / advance steps).  The paper names this step as speculative decoding
  *     (Introduction) without writing the test down; this file uses the standard speculative-sampling rule:
@@ -237,6 +240,116 @@ int ciar_oracle_dense_intervals(const void* draft, const void* radius, int64_t N
     }
     free(e);
     return 0;
+}
+
+/* ---- several heads ------------------------------------------------------------------- */
+
+static const void* head_base(const void* base, int32_t dtype, int64_t head, int64_t head_stride)
+{
+    if (!base) return NULL;
+    return (const char*)base + (size_t)head * (size_t)head_stride * (dtype == 0 ? 4u : 2u);
+}
+
+/*
+ * Quantifier over H heads.  draft (and radius, unless NULL) hold H tensors [N, row_stride], head h starting
+ * head_stride elements after head h-1.  The paper names the two strategies without formulas (Sec. 4, ablation
+ * on the Inter-Head); the readings used here:
+ *
+ *   strategy 0, Voting:   every head runs the quantifier on its own; the voted flag is the strict majority of
+ *                         the heads' flags (2 * votes > H).  p_lo ... score are per head, [H, N];
+ *                         head_flags [H, N]; flags [N] is the vote.
+ *   strategy 1, Ensemble: the heads' curves are averaged token by token -- pl_i = mean_h pl_{h,i},
+ *                         p_i = mean_h p_{h,i}, pu_i = mean_h pu_{h,i}, every head after its own 0.99 / 1.01
+ *                         scaling -- and widths, Omega, Sigma, U and the flag follow from the averaged
+ *                         curves.  All outputs are [N]; head_flags is not written.  ids == NULL reports the
+ *                         lowest-index arg-max of the averaged p.
+ * Returns 0, or -1 on allocation failure / unknown strategy.
+ */
+int ciar_oracle_quantify_multihead(const void* draft, const void* radius, int32_t heads, int64_t head_stride,
+                                   const int32_t* ids, int64_t N, const ciar_oracle_params* P, int32_t strategy,
+                                   double* p_lo, double* p_mid, double* p_hi,
+                                   double* omega, double* sigma, double* score,
+                                   uint8_t* flags, uint8_t* head_flags, int threads)
+{
+    const int V = P->vocab;
+    const int H = heads;
+    if (H < 1) return -1;
+    if (strategy == 0) {
+        uint8_t* hf = (uint8_t*)malloc((size_t)H * (size_t)(N > 0 ? N : 1));
+        if (!hf) return -1;
+        for (int h = 0; h < H; ++h) {
+            const int64_t o = (int64_t)h * N;
+            int rc = ciar_oracle_quantify(head_base(draft, P->dtype, h, head_stride),
+                                          head_base(radius, P->dtype, h, head_stride), ids, N, P,
+                                          p_lo ? p_lo + o : NULL, p_mid ? p_mid + o : NULL, p_hi ? p_hi + o : NULL,
+                                          omega ? omega + o : NULL, sigma ? sigma + o : NULL,
+                                          score ? score + o : NULL, hf + o, threads);
+            if (rc) { free(hf); return rc; }
+        }
+        for (int64_t row = 0; row < N; ++row) {
+            int votes = 0;
+            for (int h = 0; h < H; ++h) votes += hf[(int64_t)h * N + row];
+            if (flags) flags[row] = (uint8_t)(2 * votes > H);
+        }
+        if (head_flags) memcpy(head_flags, hf, (size_t)H * (size_t)N);
+        free(hf);
+        return 0;
+    }
+    if (strategy != 1) return -1;
+
+    int failed = 0;
+    if (threads < 1) threads = 1;
+#pragma omp parallel num_threads(threads)
+    {
+        double* e   = (double*)malloc(sizeof(double) * (size_t)V);
+        double* pl  = (double*)malloc(sizeof(double) * (size_t)V);
+        double* pu  = (double*)malloc(sizeof(double) * (size_t)V);
+        double* apl = (double*)malloc(sizeof(double) * (size_t)V);
+        double* apm = (double*)malloc(sizeof(double) * (size_t)V);
+        double* apu = (double*)malloc(sizeof(double) * (size_t)V);
+        if (!e || !pl || !pu || !apl || !apm || !apu) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+#pragma omp for schedule(static)
+            for (int64_t row = 0; row < N; ++row) {
+                for (int i = 0; i < V; ++i) apl[i] = apm[i] = apu[i] = 0.0;
+                for (int h = 0; h < H; ++h) {
+                    const void* c = head_base(draft, P->dtype, h, head_stride);
+                    const void* r = head_base(radius, P->dtype, h, head_stride);
+                    double m;
+                    double S = row_exponentials(c, P, row, e, &m);
+                    row_interfuse(e, S, P, r, row, pl, pu);
+                    for (int i = 0; i < V; ++i) { apl[i] += pl[i]; apm[i] += e[i] / S; apu[i] += pu[i]; }
+                }
+                for (int i = 0; i < V; ++i) { apl[i] /= (double)H; apm[i] /= (double)H; apu[i] /= (double)H; }
+
+                double Om = 0.0;
+                for (int i = 0; i < V; ++i) Om += apu[i] - apl[i];
+                double mean = Om / (double)V;
+                double ss = 0.0;
+                for (int i = 0; i < V; ++i) {
+                    double d = (apu[i] - apl[i]) - mean;
+                    ss += d * d;
+                }
+                double Sg = sqrt(ss / (double)V);
+                double U = Om * Sg;
+
+                int x = ids ? ids[row] : lowest_argmax(apm, V);
+                if (p_lo)  p_lo[row]  = apl[x];
+                if (p_mid) p_mid[row] = apm[x];
+                if (p_hi)  p_hi[row]  = apu[x];
+                if (omega) omega[row] = Om;
+                if (sigma) sigma[row] = Sg;
+                if (score) score[row] = U;
+                if (flags) flags[row] = (uint8_t)(U > P->tau);
+            }
+        }
+        free(e); free(pl); free(pu); free(apl); free(apm); free(apu);
+    }
+    return failed ? -1 : 0;
 }
 
 /* ---- verification -------------------------------------------------------------------- */

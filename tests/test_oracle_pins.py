@@ -626,3 +626,99 @@ def test_tensor_radius_bf16_is_widened_exactly(oracle):
     b = oracle.quantify(c.float(), None, oracle.Params(kappa=1.0), radius=raw.float())
     for k in a:
         np.testing.assert_array_equal(a[k], b[k])
+
+
+# ---- several heads: Voting and Ensemble (Sec. 4, ablation on the Inter-Head) ------------------------------
+
+def _heads(rng, H, n, V, scale=2.0):
+    base = _rows(rng, n, V, scale)
+    return np.stack([base + 0.5 * _rows(rng, n, V, 1.0) for _ in range(H)]).astype(np.float32)
+
+
+def test_ensemble_is_numpy_mean_of_the_heads_dense_curves(oracle):
+    """Ensemble: token-wise mean of the per-head curves (each from the already pinned single-head path, computed
+    here with numpy), then Omega = sum, Sigma = numpy std (ddof 0), U, flag.  Heads differ and one head has a
+    radius tensor of its own."""
+    rng = np.random.default_rng(51)
+    H, n, V = 3, 6, 211
+    c = _heads(rng, H, n, V)
+    raw = np.stack([_raw_radius(rng, n, V) for _ in range(H)])
+    ids = rng.integers(0, V, n).astype(np.int32)
+    for radius, P in ((None, oracle.Params(confidence=0.9, tau=0.02)), (raw, oracle.Params(kappa=1.0, tau=0.02))):
+        curves = [oracle.dense_intervals(c[h], P, radius=None if radius is None else radius[h]) for h in range(H)]
+        lo = np.mean([x[0] for x in curves], axis=0)
+        mid = np.mean([x[1] for x in curves], axis=0)
+        hi = np.mean([x[2] for x in curves], axis=0)
+        d = hi - lo
+        q = oracle.quantify_multihead(c, ids, P, oracle.ENSEMBLE, radius_heads=radius)
+        np.testing.assert_allclose(q["omega"], d.sum(1), rtol=1e-12)
+        np.testing.assert_allclose(q["sigma"], d.std(axis=1), rtol=1e-10)
+        np.testing.assert_allclose(q["score"], d.sum(1) * d.std(axis=1), rtol=1e-10)
+        np.testing.assert_array_equal(q["flags"], (q["score"] > P.tau).astype(np.uint8))
+        r = np.arange(n)
+        np.testing.assert_allclose(q["p_lo"], lo[r, ids], rtol=1e-13)
+        np.testing.assert_allclose(q["p_mid"], mid[r, ids], rtol=1e-13)
+        np.testing.assert_allclose(q["p_hi"], hi[r, ids], rtol=1e-13)
+        # averaging keeps the caps: sum of lower bounds <= 0.99, of upper bounds >= 1.01; centres sum to one
+        assert np.all(lo.sum(1) <= 0.99 + 1e-12) and np.all(hi.sum(1) >= 1.01 - 1e-12)
+        np.testing.assert_allclose(mid.sum(1), 1.0, rtol=1e-12)
+        # no ids: the arg-max of the averaged centre distribution
+        qa = oracle.quantify_multihead(c, None, P, oracle.ENSEMBLE, radius_heads=radius)
+        np.testing.assert_allclose(qa["p_mid"], mid.max(1), rtol=1e-13)
+    # the ensemble of different heads is not the score of any single head, nor the mean of the heads' scores
+    P = oracle.Params(confidence=0.9)
+    q = oracle.quantify_multihead(c, ids, P, oracle.ENSEMBLE)
+    singles = np.stack([oracle.quantify(c[h], ids, P)["score"] for h in range(H)])
+    assert np.all(np.abs(q["score"] - singles.mean(0)) > 1e-9)
+
+
+def test_ensemble_of_one_or_identical_heads_is_the_single_head(oracle):
+    rng = np.random.default_rng(52)
+    c = _rows(rng, 5, 97, 2.0)
+    ids = rng.integers(0, 97, 5).astype(np.int32)
+    P = oracle.Params(confidence=0.9, tau=0.01)
+    s = oracle.quantify(c, ids, P)
+    for H in (1, 4):
+        q = oracle.quantify_multihead(np.stack([c] * H), ids, P, oracle.ENSEMBLE)
+        for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score"):
+            np.testing.assert_allclose(q[k], s[k], rtol=1e-12, atol=1e-18)
+        np.testing.assert_array_equal(q["flags"], s["flags"])
+
+
+def test_voting_is_the_strict_majority_of_the_heads_flags(oracle):
+    """Voting: every head's outputs equal the single-head quantifier on that head; the vote is 2 * votes > H
+    (a tie of an even number of heads does not flag); the order of the heads does not matter."""
+    rng = np.random.default_rng(53)
+    n, V = 64, 129
+    for H in (1, 2, 3, 5):
+        c = _heads(rng, H, n, V, scale=1.5)
+        ids = rng.integers(0, V, n).astype(np.int32)
+        med = float(np.median(oracle.quantify(c[0], ids, oracle.Params(confidence=0.9))["score"]))
+        P = oracle.Params(confidence=0.9, tau=med)
+        q = oracle.quantify_multihead(c, ids, P, oracle.VOTING)
+        votes = np.zeros(n, dtype=int)
+        for h in range(H):
+            s = oracle.quantify(c[h], ids, P)
+            for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score"):
+                np.testing.assert_array_equal(q[k][h], s[k])
+            np.testing.assert_array_equal(q["head_flags"][h], s["flags"])
+            votes += s["flags"]
+        np.testing.assert_array_equal(q["flags"], (2 * votes > H).astype(np.uint8))
+        if H > 1:
+            assert 0 < q["flags"].sum() < n                      # both outcomes occur
+            p = oracle.quantify_multihead(c[::-1].copy(), ids, P, oracle.VOTING)
+            np.testing.assert_array_equal(p["flags"], q["flags"])
+        if H == 2:
+            assert np.any(votes == 1) and not np.any(q["flags"][votes == 1])
+
+
+def test_multihead_head_stride_and_bf16(oracle):
+    import torch
+    rng = np.random.default_rng(54)
+    c = torch.from_numpy(_heads(rng, 2, 4, 64)).to(torch.bfloat16)
+    ids = np.array([1, 5, 9, 63], dtype=np.int32)
+    P = oracle.Params(confidence=0.9)
+    a = oracle.quantify_multihead(c, ids, P, oracle.ENSEMBLE)
+    b = oracle.quantify_multihead(c.float(), ids, P, oracle.ENSEMBLE)
+    for k in a:
+        np.testing.assert_array_equal(a[k], b[k])
