@@ -186,6 +186,41 @@ int ciar_finish_rows(const void* draft_logits, const void* radius, const void* t
                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Several Interval Heads (Sec. 4, ablation on the Inter-Head: heads trained under different seeds,
+ * aggregated by "Voting" or "Ensemble"; the paper names the two strategies without formulas, the
+ * readings are stated here).
+ *
+ *   draft_heads  [heads, N, row_stride]  in   centre logits of head h at draft_heads + h * head_stride
+ *                                             elements; head_stride * sizeof(element) a multiple of 16
+ *   radius_heads same layout, or NULL    in   raw radius tensors (tensor mode), one per head
+ *   draft_ids    [N] int32, or NULL      in   reported token (NULL: the arg-max token, see below)
+ *   strategy = CIAR_VOTING    every head runs ciar_quantify on its own; flags [N] is the strict majority of
+ *                             the heads' flags (2 * votes > heads).  p_lo ... score are per head,
+ *                             [heads, N]; head_flags [heads, N] uint8 (may be NULL) are the heads' own
+ *                             flags; a NULL draft_ids reports each head's own arg-max token.
+ *   strategy = CIAR_ENSEMBLE  the heads' curves are averaged token by token (p^l_i = mean_h p^l_{h,i}, the
+ *                             same for the centre probabilities and p^u, every head after its own
+ *                             0.99 / 1.01 scaling), and Omega, Sigma, U, the flag and the reported
+ *                             token's interval come from the averaged curves.  All outputs are [N];
+ *                             head_flags is not written; a NULL draft_ids reports the arg-max token of
+ *                             the averaged centre distribution.
+ * Any output may be NULL; at least one must be given.  1 <= heads <= 8.  workspace: at least
+ * ciar_multihead_workspace_bytes(N, heads, params) bytes, rules as above.  Every head's rows are
+ * streamed once (Voting) or twice (Ensemble: the second sweep forms the token-wise averages once
+ * every head's partition sum and caps are known).
+ */
+enum { CIAR_VOTING = 0, CIAR_ENSEMBLE = 1 };
+
+size_t ciar_multihead_workspace_bytes(int64_t N, int32_t heads, const ciar_params* params);
+
+int ciar_quantify_multihead(const void* draft_heads, const void* radius_heads, int32_t heads, int64_t head_stride,
+                            const int32_t* draft_ids, int64_t N, const ciar_params* params, int32_t strategy,
+                            float* p_lo, float* p_mid, float* p_hi,
+                            float* omega, float* sigma, float* score,
+                            uint8_t* flags, uint8_t* head_flags,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Measurement aid, not a step of the method: a plain streaming read of the rows the hot path reads
  * (the "read both rows and sum" ceiling a memory-bound pass is held against).  Every logit of
  * draft_logits [N, row_stride] and, unless NULL, target_logits is loaded once with 16-byte loads and

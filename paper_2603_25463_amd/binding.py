@@ -67,6 +67,11 @@ def lib() -> ctypes.CDLL:
         L.ciar_window_epilogue.argtypes = [vp, vp, i64, pp, vp, vp, vp]
         L.ciar_dense_intervals.restype = ctypes.c_int
         L.ciar_dense_intervals.argtypes = [vp, vp, i64, pp, vp, vp, vp, vp]
+        L.ciar_multihead_workspace_bytes.restype = sz
+        L.ciar_multihead_workspace_bytes.argtypes = [i64, ctypes.c_int32, pp]
+        L.ciar_quantify_multihead.restype = ctypes.c_int
+        L.ciar_quantify_multihead.argtypes = [vp, vp, ctypes.c_int32, i64, vp, i64, pp, ctypes.c_int32] + \
+            [vp] * 8 + [vp, sz, vp]
         L.ciar_read_rows.restype = ctypes.c_int
         L.ciar_read_rows.argtypes = [vp, vp, i64, pp, vp, vp]
         L.ciar_last_error.restype = ctypes.c_char_p
@@ -302,3 +307,37 @@ def read_rows(draft: torch.Tensor, target: torch.Tensor | None, params: Params, 
         out = torch.empty(N, dtype=torch.float32, device=dev)
     _check(lib().ciar_read_rows(_ptr(draft), _ptr(target), N, ctypes.byref(cp), _ptr(out), _stream(stream)))
     return out
+
+
+VOTING, ENSEMBLE = 0, 1
+
+
+def quantify_multihead(draft_heads: torch.Tensor, ids: torch.Tensor | None, params: Params, strategy: int,
+                       vocab: int | None = None, stream=None, radius_heads: torch.Tensor | None = None,
+                       workspace: torch.Tensor | None = None) -> dict:
+    """``ciar_quantify_multihead``.  ``draft_heads`` (and ``radius_heads``): [H, N, stride].  VOTING: per-head
+    float outputs [H, N], ``head_flags`` [H, N] and the voted ``flags`` [N]; ENSEMBLE: all outputs [N]."""
+    _need_cuda(draft_heads, ids, radius_heads)
+    if draft_heads.dim() != 3 or draft_heads.stride(2) != 1:
+        raise ValueError("draft_heads must be [H, N, stride] with unit stride along the vocabulary")
+    if radius_heads is not None and (radius_heads.dtype != draft_heads.dtype or radius_heads.shape != draft_heads.shape
+                                     or radius_heads.stride() != draft_heads.stride()):
+        raise ValueError("radius_heads must match draft_heads in dtype, shape and strides")
+    H, N, dev = draft_heads.shape[0], draft_heads.shape[1], draft_heads.device
+    cp = params.to_c(draft_heads[0], vocab)
+    head_stride = int(draft_heads.stride(0)) if H > 1 else N * int(cp.row_stride)
+    shape = (H, N) if strategy == VOTING else (N,)
+    o = {k: torch.empty(shape, dtype=torch.float32, device=dev)
+         for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score")}
+    o["flags"] = torch.empty(N, dtype=torch.uint8, device=dev)
+    if strategy == VOTING:
+        o["head_flags"] = torch.empty((H, N), dtype=torch.uint8, device=dev)
+    if workspace is None:
+        nbytes = int(lib().ciar_multihead_workspace_bytes(N, H, ctypes.byref(cp)))
+        workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=dev)
+    _check(lib().ciar_quantify_multihead(
+        _ptr(draft_heads), _ptr(radius_heads), H, head_stride, _ptr(ids), N, ctypes.byref(cp), int(strategy),
+        _ptr(o["p_lo"]), _ptr(o["p_mid"]), _ptr(o["p_hi"]), _ptr(o["omega"]), _ptr(o["sigma"]), _ptr(o["score"]),
+        _ptr(o["flags"]), _ptr(o.get("head_flags")), _ptr(workspace), workspace.numel() * workspace.element_size(),
+        _stream(stream)))
+    return o

@@ -385,6 +385,96 @@ int ciar_dense_intervals(const void* draft_logits, const void* radius, int64_t N
     return CIAR_OK;
 }
 
+size_t ciar_multihead_workspace_bytes(int64_t N, int32_t heads, const ciar_params* /*params*/)
+{
+    if (N <= 0 || heads < 1) return 0;
+    return round_up((size_t)heads * (stats_bytes(N) + ids_bytes(N) + round_up((size_t)N, 16)), 256);
+}
+
+int ciar_quantify_multihead(const void* draft_heads, const void* radius_heads, int32_t heads, int64_t head_stride,
+                            const int32_t* draft_ids, int64_t N, const ciar_params* params, int32_t strategy,
+                            float* p_lo, float* p_mid, float* p_hi, float* omega, float* sigma, float* score,
+                            uint8_t* flags, uint8_t* head_flags, void* workspace, size_t workspace_bytes,
+                            void* hip_stream)
+{
+    Resolved r;
+    if (int rc = check_params(params, &r)) return rc;
+    if (N < 0) return fail(CIAR_EINVAL, "N is negative");
+    if (N > 0x7fffffffLL) return fail(CIAR_EUNSUPPORTED, "N exceeds 2^31 - 1 rows per call");
+    if (heads < 1 || heads > ciar::max_heads())
+        return fail(CIAR_EUNSUPPORTED, "heads must be in [1, %d] (got %d)", ciar::max_heads(), heads);
+    if (strategy != CIAR_VOTING && strategy != CIAR_ENSEMBLE)
+        return fail(CIAR_EINVAL, "strategy %d is neither CIAR_VOTING nor CIAR_ENSEMBLE", strategy);
+    if (int rc = check_rows(draft_heads, "draft_heads")) return rc;
+    if (radius_heads)
+        if (int rc = check_rows(radius_heads, "radius_heads")) return rc;
+    if (heads > 1) {
+        if (head_stride < (N > 0 ? (N - 1) * params->row_stride + params->vocab : 0))
+            return fail(CIAR_EINVAL, "head_stride %lld is smaller than one head's tensor", (long long)head_stride);
+        if ((head_stride * r.elt) % 16 != 0)
+            return fail(CIAR_EALIGN, "head_stride * element size is not a multiple of 16 bytes");
+    }
+    const bool any_float = p_lo || p_mid || p_hi || omega || sigma || score;
+    if (!any_float && !flags && !(strategy == CIAR_VOTING && head_flags))
+        return fail(CIAR_EINVAL, "every output pointer is NULL");
+    if (N == 0) return CIAR_OK;
+    const size_t need = ciar_multihead_workspace_bytes(N, heads, params);
+    if (!workspace) return fail(CIAR_EWORKSPACE, "workspace is NULL but %zu bytes are needed", need);
+    if (!aligned16(workspace)) return fail(CIAR_EALIGN, "workspace is not 16-byte aligned");
+    if (workspace_bytes < need)
+        return fail(CIAR_EWORKSPACE, "workspace has %zu bytes, %zu are needed", workspace_bytes, need);
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    char* w = static_cast<char*>(workspace);
+    ciar::RowStats* stats = reinterpret_cast<ciar::RowStats*>(w);
+    int32_t* ws_ids = reinterpret_cast<int32_t*>(w + (size_t)heads * stats_bytes(N));
+    uint8_t* ws_flags = reinterpret_cast<uint8_t*>(w + (size_t)heads * (stats_bytes(N) + ids_bytes(N)));
+    const size_t head_bytes = (size_t)head_stride * (size_t)r.elt;
+
+    // one streaming pass per head: every head's RowStats
+    for (int h = 0; h < heads; ++h) {
+        ciar::RowArgs a = base_args(params, r, N);
+        a.draft = static_cast<const char*>(draft_heads) + (size_t)h * head_bytes;
+        a.radius = radius_heads ? static_cast<const char*>(radius_heads) + (size_t)h * head_bytes : nullptr;
+        a.stats = stats + (size_t)h * (size_t)N;
+        a.reject_list = ws_ids + (size_t)h * (ids_bytes(N) / 4);
+        a.reject_count = a.reject_list;                      // not used by a quantify-only pass
+        hipError_t e = ciar::launch_stream(ciar::Mode::Quantify, params->dtype, a, stream);
+        if (e != hipSuccess) return hip_fail(e, "streaming kernel launch");
+        if (strategy == CIAR_VOTING) {
+            const size_t o = (size_t)h * (size_t)N;
+            a.ids = draft_ids;
+            a.p_lo = p_lo ? p_lo + o : nullptr; a.p_mid = p_mid ? p_mid + o : nullptr; a.p_hi = p_hi ? p_hi + o : nullptr;
+            a.omega = omega ? omega + o : nullptr; a.sigma = sigma ? sigma + o : nullptr;
+            a.score = score ? score + o : nullptr;
+            a.flags = (head_flags ? head_flags : ws_flags) + o;
+            if (a.radius && !a.ids && (a.p_lo || a.p_hi)) {
+                e = ciar::launch_argmax(params->dtype, a, a.reject_list, stream);
+                if (e != hipSuccess) return hip_fail(e, "arg-max kernel launch");
+                a.ids = a.reject_list;
+            }
+            e = ciar::launch_finish(ciar::Mode::Quantify, params->dtype, a, params->window, nullptr, nullptr, stream);
+            if (e != hipSuccess) return hip_fail(e, "finishing kernel launch");
+        }
+    }
+    if (strategy == CIAR_VOTING) {
+        if (flags) {
+            const hipError_t e = ciar::launch_vote(head_flags ? head_flags : ws_flags, heads, N, flags, stream);
+            if (e != hipSuccess) return hip_fail(e, "vote kernel launch");
+        }
+        return CIAR_OK;
+    }
+    ciar::RowArgs a = base_args(params, r, N);
+    a.draft = draft_heads;
+    a.radius = radius_heads;
+    a.stats = stats;
+    a.ids = draft_ids;
+    a.p_lo = p_lo; a.p_mid = p_mid; a.p_hi = p_hi; a.omega = omega; a.sigma = sigma; a.score = score; a.flags = flags;
+    const hipError_t e = ciar::launch_ensemble(params->dtype, a, heads, head_stride, stream);
+    if (e != hipSuccess) return hip_fail(e, "ensemble kernel launch");
+    return CIAR_OK;
+}
+
 int ciar_read_rows(const void* draft_logits, const void* target_logits, int64_t N, const ciar_params* params,
                    float* row_sum, void* hip_stream)
 {

@@ -67,6 +67,14 @@ hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, int32_t K, i
 hipError_t launch_windows(const uint8_t* accept, const int32_t* row_id, int64_t N, int32_t K,
                           int32_t* accept_len, int32_t* resampled_id, hipStream_t stream);
 
+// Several heads.  Head h of args.draft / args.radius starts h * head_stride elements after head 0;
+// args.stats holds [heads][N] RowStats left by one streaming pass per head.
+int max_heads();
+// Ensemble: token-wise mean of the heads' curves -> the [N] outputs in args.
+hipError_t launch_ensemble(int dtype, const RowArgs& args, int heads, int64_t head_stride, hipStream_t stream);
+// Voting: flags[row] = strict majority of head_flags[h * N + row].
+hipError_t launch_vote(const uint8_t* head_flags, int heads, int64_t N, uint8_t* flags, hipStream_t stream);
+
 // out[row] = lowest index of the row's largest centre logit.
 hipError_t launch_argmax(int dtype, const RowArgs& args, int32_t* out, hipStream_t stream);
 

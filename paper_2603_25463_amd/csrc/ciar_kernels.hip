@@ -393,6 +393,37 @@ __device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const Fu
     q5[4] = a4[0] + a4[1];
 }
 
+// Pass C for a handful of tokens (V <= kTinyVocab), in fp64 from the fp32 e_i.  With so few tokens the widths
+// are O(1) and Sigma can be an exact zero (two tokens: delta_1 = delta_2 identically, because x_1 + x_2 = 1
+// holds for the computed x as well); fp32 token arithmetic leaves ~1e-7 there, fp64 keeps the symmetry.
+// Same units as fuse_sums / fuse_sums_rad: gl, gw per token with p^l = Bc gl, p^u - p^l = Wc gw.
+constexpr int kTinyVocab = 64;
+
+template <typename T, int EPV, bool RAD>
+__device__ __forceinline__ void fuse_sums_tiny(const float (&e)[EPV], const u32x4& rad, double S_units, double a,
+                                               double b, double kappa, double rmax, double (&q5)[5])
+{
+    float raw[EPV];
+    Elt<T>::unpack(rad, raw);
+    const double invS = 1.0 / S_units;
+#pragma unroll
+    for (int i = 0; i < 5; ++i) q5[i] = 0.0;
+#pragma unroll
+    for (int k = 0; k < EPV; ++k) {
+        const double ed = (double)e[k], x = ed * invS;
+        double ak = a, bk = b;
+        if constexpr (RAD) {
+            const double r = radius_of((double)raw[k], kappa, rmax);
+            ak = exp(r); bk = exp(-r);
+        }
+        const double om = 1.0 - x, du = 1.0 + (ak - 1.0) * x, dl = 1.0 - (1.0 - bk) * x;
+        double gl = ed / dl, gw = ed * om / (du * dl);
+        if constexpr (RAD) { gl *= bk; gw *= ak - bk; }
+        q5[0] += gl; q5[1] += gw;
+        q5[2] = fma(gl, gl, q5[2]); q5[3] = fma(gw, gw, q5[3]); q5[4] = fma(gl, gw, q5[4]);
+    }
+}
+
 // Pass C in tensor-radius mode: every token has its own a_i, b_i from the raw radius row `rad` (as loaded,
 // padding already zeroed); the sums are of p^l_i S and (p^u_i - p^l_i) S themselves.
 template <typename T, int THREADS, int NVEC>
@@ -587,7 +618,20 @@ void stream_kernel(const RowArgs A)
             // x_i = e_i fw / S: hand fuse_row the partition sum expressed in this wave's units
             const FuseRow fr = fuse_row(fw > 0.0 ? S / fw : 1.0, A.a, A.b);
             double q5[5];
-            if constexpr (RAD) {
+            bool tiny = false;
+            if constexpr (NVEC == 1) tiny = V <= kTinyVocab;       // uniform
+            if (tiny) {
+                if constexpr (NVEC == 1) {
+                    if constexpr (RAD) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        load_row(buf, A.radius, row);
+                        E::zero_tail(buf[0], tid * EPV, V);
+                    }
+                    fuse_sums_tiny<T, EPV, RAD>(e, buf[0], fw > 0.0 ? S / fw : 1.0, A.a, A.b, A.kappa, A.rmax, q5);
+#pragma unroll
+                    for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
+                }
+            } else if constexpr (RAD) {
                 // the raw radius row comes into the registers the centre row came in
                 __builtin_amdgcn_sched_barrier(0);
                 load_row(buf, A.radius, row);
@@ -942,6 +986,172 @@ __global__ __launch_bounds__(256) void argmax_kernel(const RowArgs A, int32_t* _
     }
 }
 
+// ---- several heads (Sec. 4, ablation on the Inter-Head): Ensemble and Voting ------------------------------
+
+constexpr int kMaxHeads = 8;
+
+// Ensemble: the heads' curves are averaged token by token, so the widths of all heads of a token have to
+// meet: a second sweep over the H rows of a position, after the streaming kernel has left every head's
+// RowStats (partition sum, reference, interval sums -> that head's caps).  One workgroup per position;
+// per token and head the same arithmetic as the streaming kernel's interval pass.
+//   D_i = sum_h delta_{h,i},  Omega = sum_i D_i / H,  Sigma^2 = sum_i D_i^2 / (H^2 V) - (Omega / V)^2.
+template <typename T>
+__global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const int H, const int64_t head_stride)
+{
+    using E = Elt<T>;
+    constexpr int EPV = E::kPerVec;
+    __shared__ FuseRow sm_fr[kMaxHeads];
+    __shared__ float sm_n[kMaxHeads], sm_invS[kMaxHeads];
+    __shared__ double sm_cw[kMaxHeads], sm_cl[kMaxHeads], sm_S[kMaxHeads], sm_al[kMaxHeads], sm_au[kMaxHeads];
+    __shared__ double sm_red[2][4];
+    __shared__ float sm_pm[4];
+    __shared__ int sm_pi[4];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row = blockIdx.x;
+    const int V = A.V;
+    const bool rad = A.radius != nullptr;
+    const bool need_argmax = A.ids == nullptr && (A.p_lo || A.p_mid || A.p_hi);
+    const bool tiny = V <= 64;
+
+    if (tid < H) {
+        const RowStats st = A.stats[(int64_t)tid * A.N + row];
+        const RowScore rs = finish_score(st.q, st.S, st.capless != 0.f, A);
+        const double Bc = (rad ? 1.0 : A.b) / st.S, Wc = (rad ? 1.0 : A.a - A.b) / st.S;
+        sm_fr[tid] = fuse_row(st.S, A.a, A.b);
+        sm_n[tid] = st.n;
+        sm_cw[tid] = rs.alpha_u * Wc;
+        sm_cl[tid] = (rs.alpha_u - rs.alpha_l) * Bc;
+        sm_invS[tid] = (float)(1.0 / st.S);
+        sm_S[tid] = st.S; sm_al[tid] = rs.alpha_l; sm_au[tid] = rs.alpha_u;
+    }
+    __syncthreads();
+
+    const float kap = (float)A.kappa, rmax = (float)A.rmax;
+    const int nvec = (V + EPV - 1) / EPV;
+    double s1 = 0.0, s2 = 0.0;
+    float best = -INFINITY;
+    int best_i = INT_MAX;
+    for (int v = tid; v < nvec; v += 256) {
+        double D[EPV];                                             // fp64 across heads: a two-token row's Sigma is a
+        float pm[EPV];                                             // difference of two nearly equal averaged widths
+#pragma unroll
+        for (int k = 0; k < EPV; ++k) { D[k] = 0.0; pm[k] = 0.f; }
+        for (int h = 0; h < H; ++h) {
+            const gvec c = (gvec)(gbytes)(static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride);
+            float cv[EPV], rv[EPV];
+            const u32x4 cw4 = c[v];
+            E::unpack(cw4, cv);
+            if (rad) {
+                const gvec r = (gvec)(gbytes)(static_cast<const T*>(A.radius) + (int64_t)h * head_stride + row * A.stride);
+                const u32x4 rw4 = r[v];
+                E::unpack(rw4, rv);
+            }
+            const FuseRow fr = sm_fr[h];
+            const float n = sm_n[h], invS = sm_invS[h];
+            const double cw = sm_cw[h], cl = sm_cl[h];
+            if (tiny) {
+                // A handful of tokens: widths are O(1) and Sigma can be an exact zero (two tokens), which
+                // fp32 token arithmetic cannot resolve to 1e-7; the few tokens are done in fp64.
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) {
+                    if (v * EPV + k < V) {
+                        const double x = exp((double)cv[k] - (double)n * kLn2) / sm_S[h];
+                        double a = A.a, b = A.b;
+                        if (rad) {
+                            const double r = radius_of((double)rv[k], A.kappa, A.rmax);
+                            a = exp(r); b = exp(-r);
+                        }
+                        D[k] += sm_au[h] * a * x / (1.0 + (a - 1.0) * x) - sm_al[h] * b * x / (1.0 + (b - 1.0) * x);
+                        pm[k] += (float)x;
+                    }
+                }
+                continue;
+            }
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) {
+                if (v * EPV + k < V) {
+                    const float e = exp2_ref(cv[k], n);
+                    float gl, gw;
+                    if (rad) fuse_token_rad(e, rv[k], fr, kap, rmax, gl, gw);
+                    else fuse_token(e, fr, gl, gw);
+                    D[k] = fma(cw, (double)gw, fma(cl, (double)gl, D[k]));
+                    pm[k] = fmaf(e, invS, pm[k]);
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < EPV; ++k) {
+            const double d = D[k];                                 // tokens past V contribute exactly 0
+            s1 += d;
+            s2 = fma(d, d, s2);
+            if (need_argmax && v * EPV + k < V && pm[k] > best) { best = pm[k]; best_i = v * EPV + k; }
+        }
+    }
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    if (lane == 0) { sm_red[0][wave] = s1; sm_red[1][wave] = s2; }
+    if (need_argmax) {
+        // each lane walked its tokens in ascending order, so it holds its lowest index of its maximum
+        const float wm = wave_max(best);
+        const int wi = wave_min_i(best == wm ? best_i : INT_MAX);
+        if (lane == 0) { sm_pm[wave] = wm; sm_pi[wave] = wi; }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        const double t1 = (sm_red[0][0] + sm_red[0][1]) + (sm_red[0][2] + sm_red[0][3]);
+        const double t2 = (sm_red[1][0] + sm_red[1][1]) + (sm_red[1][2] + sm_red[1][3]);
+        const double Hd = (double)H, Vd = (double)V;
+        const double omega = t1 / Hd;
+        const double var = fmax(0.0, t2 / (Hd * Hd) - omega * omega / Vd) / Vd;
+        const double sigma = sqrt(var), score = omega * sigma;
+        if (A.omega) A.omega[row] = (float)omega;
+        if (A.sigma) A.sigma[row] = (float)sigma;
+        if (A.score) A.score[row] = (float)score;
+        if (A.flags) A.flags[row] = (uint8_t)(score > A.tau);
+        if (A.p_lo || A.p_mid || A.p_hi) {
+            int xid;
+            if (A.ids) {
+                xid = A.ids[row];
+                xid = xid < 0 ? 0 : (xid >= V ? V - 1 : xid);
+            } else {
+                const float rm = fmaxf(fmaxf(sm_pm[0], sm_pm[1]), fmaxf(sm_pm[2], sm_pm[3]));
+                xid = INT_MAX;
+                for (int w = 0; w < 4; ++w) if (sm_pm[w] == rm && sm_pi[w] < xid) xid = sm_pi[w];
+                if (xid == INT_MAX) xid = 0;
+            }
+            double lo = 0.0, mid = 0.0, hi = 0.0;
+            for (int h = 0; h < H; ++h) {
+                const T* crow = static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride;
+                const double x = exp((double)load_logit(crow, xid) - (double)sm_n[h] * kLn2) / sm_S[h];
+                double a = A.a, b = A.b;
+                if (rad) {
+                    const T* rrow = static_cast<const T*>(A.radius) + (int64_t)h * head_stride + row * A.stride;
+                    const double r = radius_of((double)load_logit(rrow, xid), A.kappa, A.rmax);
+                    a = exp(r); b = exp(-r);
+                }
+                mid += x;
+                lo += sm_al[h] * b * x / (1.0 + (b - 1.0) * x);
+                hi += sm_au[h] * a * x / (1.0 + (a - 1.0) * x);
+            }
+            if (A.p_lo) A.p_lo[row] = (float)(lo / Hd);
+            if (A.p_mid) A.p_mid[row] = (float)(mid / Hd);
+            if (A.p_hi) A.p_hi[row] = (float)(hi / Hd);
+        }
+    }
+}
+
+// Voting: flags[row] = strict majority of head_flags[h][row].
+__global__ __launch_bounds__(256) void vote_kernel(const uint8_t* __restrict__ head_flags, int H, int64_t N,
+                                                   uint8_t* __restrict__ flags)
+{
+    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (row >= N) return;
+    int votes = 0;
+    for (int h = 0; h < H; ++h) votes += head_flags[(int64_t)h * N + row] != 0;
+    flags[row] = (uint8_t)(2 * votes > H);
+}
+
 // ---- window epilogue: one thread per window of K rows -------------------------------------------------
 
 __global__ __launch_bounds__(256) void window_kernel(const uint8_t* __restrict__ accept,
@@ -1228,6 +1438,24 @@ hipError_t launch_dense(int dtype, const RowArgs& args, float* p_lo, float* p_mi
     const dim3 grid((unsigned)args.N), block(256);
     if (dtype == 0) hipLaunchKernelGGL(dense_kernel<float>, grid, block, 0, stream, args, p_lo, p_mid, p_hi);
     else hipLaunchKernelGGL(dense_kernel<bf16_t>, grid, block, 0, stream, args, p_lo, p_mid, p_hi);
+    return hipGetLastError();
+}
+
+int max_heads() { return kMaxHeads; }
+
+hipError_t launch_ensemble(int dtype, const RowArgs& args, int heads, int64_t head_stride, hipStream_t stream)
+{
+    if (args.N <= 0) return hipSuccess;
+    const dim3 grid((unsigned)args.N), block(256);
+    if (dtype == 0) hipLaunchKernelGGL(ensemble_kernel<float>, grid, block, 0, stream, args, heads, head_stride);
+    else hipLaunchKernelGGL(ensemble_kernel<bf16_t>, grid, block, 0, stream, args, heads, head_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_vote(const uint8_t* head_flags, int heads, int64_t N, uint8_t* flags, hipStream_t stream)
+{
+    if (N <= 0) return hipSuccess;
+    hipLaunchKernelGGL(vote_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, stream, head_flags, heads, N, flags);
     return hipGetLastError();
 }
 

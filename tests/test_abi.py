@@ -28,7 +28,7 @@ def _declared_functions():
 def test_header_declares_the_expected_entry_points():
     names = _declared_functions()
     for n in ("ciar_quantify", "ciar_verify", "ciar_quantify_verify", "ciar_dense_intervals",
-              "ciar_stream_rows", "ciar_finish_rows", "ciar_window_epilogue", "ciar_read_rows",
+              "ciar_stream_rows", "ciar_finish_rows", "ciar_window_epilogue", "ciar_read_rows", "ciar_quantify_multihead", "ciar_multihead_workspace_bytes",
               "ciar_workspace_bytes", "ciar_params_default", "ciar_last_error", "ciar_version"):
         assert n in names
 
@@ -117,6 +117,19 @@ def test_argument_errors_are_reported_before_any_launch(L):
                               FAKE, 4096, None) == EINVAL                            # verify outputs, no target
     assert L.ciar_finish_rows(FAKE, None, FAKE, FAKE, FAKE, FAKE, 4, a, FAKE, *([None] * 10), FAKE, 4096,
                               None) == EINVAL                                        # target, no verify output
+    # several heads
+    def mh(heads=2, hs=4096, strategy=1, out=FAKE, ws=FAKE, wsb=1 << 20, draft=FAKE, radius=None, hf=None):
+        return L.ciar_quantify_multihead(draft, radius, heads, hs, None, 4, a, strategy, out, None, None, None,
+                                         None, None, None, hf, ws, wsb, None)
+    assert mh(heads=0) == EUNSUP and mh(heads=9) == EUNSUP
+    assert mh(strategy=2) == EINVAL
+    assert mh(hs=100) == EINVAL                      # heads overlap
+    assert mh(hs=4097) == EALIGN
+    assert mh(draft=None) == EINVAL and mh(radius=FAKE + 4) == EALIGN
+    assert mh(out=None) == EINVAL
+    assert mh(ws=None, wsb=0) == EWORK and mh(wsb=64) == EWORK
+    assert L.ciar_multihead_workspace_bytes(0, 2, a) == 0 and L.ciar_multihead_workspace_bytes(4, 0, a) == 0
+    assert L.ciar_multihead_workspace_bytes(2048, 3, a) >= 3 * 77 * 2048
     assert L.ciar_read_rows(FAKE, FAKE, 4, a, None, None) == EINVAL
     assert L.ciar_read_rows(None, FAKE, 4, a, FAKE, None) == EINVAL
     assert L.ciar_read_rows(FAKE, FAKE + 4, 4, a, FAKE, None) == EALIGN

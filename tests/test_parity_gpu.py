@@ -287,6 +287,69 @@ def test_tensor_radius_workloads(ciar, oracle, cfg):
     assert 0.4 < frac < 0.6 and ex <= 3
 
 
+# ---- several heads: Voting and Ensemble (Sec. 4, ablation on the Inter-Head) ---------------------------------
+
+def _head_stack(H, V, stride, N, dtype, seed):
+    """H heads that agree on the gist of every row and differ in detail: one shared row plus per-head noise."""
+    c, *_ = _random_case(V, stride, N, 4, torch.float32, seed=seed)
+    g = torch.Generator(device="cuda").manual_seed(seed + 1)
+    heads = torch.stack([c + 0.4 * torch.randn((N, stride), generator=g, device="cuda") for _ in range(H)])
+    if stride > V:
+        heads[:, :, V:] = 1e30
+    return heads.to(dtype).contiguous()
+
+
+MULTIHEAD_CASES = [
+    (2, 2, 4, 21, torch.float32), (3, 1000, 1000, 33, torch.float32), (3, 16384, 16384, 40, torch.float32),
+    (5, 4099, 4100, 17, torch.float32), (2, 16385, 16388, 9, torch.float32), (8, 777, 780, 12, torch.float32),
+    (3, 1001, 1008, 30, torch.bfloat16), (2, 65536, 65536, 6, torch.bfloat16), (1, 512, 512, 20, torch.float32),
+]
+
+
+@pytest.mark.parametrize("H,V,stride,N,dtype", MULTIHEAD_CASES)
+@pytest.mark.parametrize("tensor_radius", [False, True])
+def test_multihead_ensemble_and_voting(ciar, oracle, H, V, stride, N, dtype, tensor_radius):
+    heads = _head_stack(H, V, stride, N, dtype, seed=4000 + V + H)
+    raw = None
+    if tensor_radius:
+        raw = torch.stack([_raw_radius(N, stride, V, dtype, seed=5000 + V + h) for h in range(H)]).contiguous()
+    g = torch.Generator(device="cuda").manual_seed(9)
+    ids = torch.randint(0, V, (N,), generator=g, device="cuda").to(torch.int32)
+    say(f"[multihead] H={H} V={V} stride={stride} N={N} {dtype} radius={'tensor' if tensor_radius else 'scalar'}")
+    kw = dict(radius_scale=1.0) if tensor_radius else dict(confidence=0.9)
+    okw = dict(kappa=1.0) if tensor_radius else dict(confidence=0.9)
+    hh, rh = heads.cpu(), None if raw is None else raw.cpu()
+    # a threshold in the middle of the scores so that flags and votes go both ways
+    o0 = oracle.quantify_multihead(hh, ids.cpu().numpy(), oracle.Params(**okw), oracle.ENSEMBLE, vocab=V,
+                                   radius_heads=rh)
+    tau = float(np.float32(np.median(o0["score"])))
+    P, OP = ciar.Params(tau=tau, **kw), oracle.Params(tau=tau, **okw)
+    for with_ids in (True, False):
+        i_gpu = ids if with_ids else None
+        i_cpu = ids.cpu().numpy() if with_ids else None
+        ge = ciar.quantify_multihead(heads, i_gpu, P, ciar.ENSEMBLE, vocab=V, radius_heads=raw)
+        gv = ciar.quantify_multihead(heads, i_gpu, P, ciar.VOTING, vocab=V, radius_heads=raw)
+        torch.cuda.synchronize()
+        oe = oracle.quantify_multihead(hh, i_cpu, OP, oracle.ENSEMBLE, vocab=V, radius_heads=rh)
+        ov = oracle.quantify_multihead(hh, i_cpu, OP, oracle.VOTING, vocab=V, radius_heads=rh)
+        parity.check_floats(ge, oe)
+        parity.check_flags(ge["flags"], oe, float(np.float32(tau)))
+        # voting: every head against the oracle's head, the vote recomputed from the GPU's own head flags, and
+        # the vote against the oracle's wherever no head sits inside the threshold margin
+        near = np.zeros(N, dtype=bool)
+        for h in range(H):
+            gh = {k: gv[k][h] for k in parity.FLOAT_KEYS}
+            oh = {k: ov[k][h] for k in parity.FLOAT_KEYS}
+            oh["flags"] = ov["head_flags"][h]
+            parity.check_floats(gh, oh)
+            parity.check_flags(gv["head_flags"][h], oh, float(np.float32(tau)))
+            near |= np.abs(ov["score"][h] - float(np.float32(tau))) < parity.MARGIN
+        votes = gv["head_flags"].sum(0, dtype=torch.int32)
+        assert torch.equal(gv["flags"], (2 * votes > H).to(torch.uint8))
+        same = gv["flags"].cpu().numpy() == ov["flags"]
+        assert np.all(same | near)
+
+
 @pytest.mark.parametrize("K", [1, 3, 8, 100, 128, 255, 256, 257, 300, 1000])
 def test_window_lengths(ciar, oracle, K):
     """Windows that divide, straddle and exceed the finishing kernel's 256-row workgroups; N = 700 leaves a
