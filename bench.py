@@ -51,6 +51,91 @@ def measured_traffic(workload_name: str):
         return None
 
 
+def bench_multihead(args, torch, ciar, wl, dev) -> int:
+    """Several Interval Heads: one step = one ciar_quantify_multihead call over H heads of the workload's rows
+    (head h = the workload's centre logits + 0.3 N(0,1), seeded: heads trained under different seeds agree on
+    the gist of a row and differ in detail).  Algorithmic bytes: every head's row once."""
+    import ctypes
+    from paper_2603_25463_amd.binding import _ptr, _stream, _check
+    spec = wl.SPECS[args.workload]
+    w = wl.make(args.workload, device=dev)
+    N, V, H = w.rows, spec.vocab, args.heads
+    elt = w.draft.element_size()
+    copies = max(1, min(args.copies, 4))
+    g = torch.Generator(device=dev).manual_seed(0xC1A2 + args.workload)
+    base = torch.empty((H, N, V), dtype=w.draft.dtype, device=dev)
+    for h in range(H):
+        for lo in range(0, N, 256):
+            hi = min(lo + 256, N)
+            noise = torch.randn((hi - lo, V), generator=g, device=dev, dtype=torch.float32)
+            base[h, lo:hi] = (w.draft[lo:hi].float() + 0.3 * noise).to(w.draft.dtype)
+    stacks = [base] + [base.clone() for _ in range(copies - 1)]
+    strategy = ciar.ENSEMBLE if args.strategy == "ensemble" else ciar.VOTING
+    P = ciar.Params(confidence=0.9, tau=0.30, window=spec.window)
+    cp = P.to_c(base[0])
+    L = ciar.lib()
+    shape = (N,) if strategy == ciar.ENSEMBLE else (H, N)
+    out = [torch.empty(shape, dtype=torch.float32, device=dev) for _ in range(6)]
+    flags = torch.empty(N, dtype=torch.uint8, device=dev)
+    hflags = torch.empty((H, N), dtype=torch.uint8, device=dev)
+    ws = torch.empty(int(L.ciar_multihead_workspace_bytes(N, H, ctypes.byref(cp))), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+    sp = _stream(stream)
+
+    def step(i):
+        st = stacks[i % copies]
+        _check(L.ciar_quantify_multihead(_ptr(st), None, H, int(st.stride(0)), _ptr(w.ids), N, ctypes.byref(cp),
+                                         strategy, *[_ptr(o) for o in out], _ptr(flags),
+                                         _ptr(hflags) if strategy == ciar.VOTING else None, _ptr(ws), ws.numel(), sp))
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+    ms = 1e3 * total_s / args.steps
+    bytes_per_call = H * N * V * elt + N * 34
+    achieved = bytes_per_call / (ms * 1e-3) / 1e9
+    passes = 2 if strategy == ciar.ENSEMBLE else 1
+    result = {
+        "metric": f"token positions/sec (multi-head quantify, {args.strategy}, H={H}, V={V} "
+                  f"{'fp32' if elt == 4 else 'bf16'})",
+        "value": N * args.steps / total_s, "unit": "positions/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"cfg{args.workload} {spec.name}: {N} positions x {H} heads, V={V}, "
+                               f"{'fp32' if elt == 4 else 'bf16'} logits, {args.strategy}, confidence 0.9, tau 0.30",
+                   "input_copies_rotated": copies},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": f"whole call: {H} streaming passes"
+                               + (" + the averaging sweep (every head's rows are read twice)" if passes == 2
+                                  else f" + {H} finishing kernels + the vote"),
+                     "kernel_avg_us": 1e3 * ms, "algorithmic_bytes_per_launch": bytes_per_call},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = min(N, 512)
+        hh = base[:, :rows].cpu().contiguous()
+        ids = w.ids[:rows].cpu().numpy()
+        OP = oracle.Params(confidence=0.9, tau=0.30)
+        threads = oracle.default_threads()
+        done, c0 = 0, time.perf_counter()
+        while True:
+            oracle.quantify_multihead(hh, ids, OP, oracle.ENSEMBLE if passes == 2 else oracle.VOTING, threads=threads)
+            done += rows
+            dt = time.perf_counter() - c0
+            if dt > 10.0:
+                break
+        result["cpu_baseline"] = {"value": done / dt, "unit": "positions/s", "cores": threads, "kind": "oracle",
+                                  "sample": f"the first {rows} positions x {H} heads, repeated for {dt:.1f} s"}
+    print(json.dumps(result))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -61,6 +146,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--radius-tensor", action="store_true",
                     help="tensor-radius mode: a raw radius row per position is streamed as well (not the headline)")
+    ap.add_argument("--heads", type=int, default=0,
+                    help="H > 0: time ciar_quantify_multihead over H synthetic heads instead (not the headline)")
+    ap.add_argument("--strategy", choices=("ensemble", "voting"), default="ensemble")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of known size (reference for hardware counters)")
     args = ap.parse_args()
@@ -77,6 +165,9 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.heads > 0:
+        return bench_multihead(args, torch, ciar, wl, dev)
 
     spec = wl.SPECS[args.workload]
     w = wl.make(args.workload, device=dev)

@@ -1032,60 +1032,95 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
     double s1 = 0.0, s2 = 0.0;
     float best = -INFINITY;
     int best_i = INT_MAX;
-    for (int v = tid; v < nvec; v += 256) {
-        double D[EPV];                                             // fp64 across heads: a two-token row's Sigma is a
-        float pm[EPV];                                             // difference of two nearly equal averaged widths
+    if (tiny) {
+        // A handful of tokens (one vector per lane at most): widths are O(1) and Sigma can be an exact zero
+        // (two tokens), which fp32 token arithmetic cannot resolve to 1e-7; the few tokens are done in fp64.
+        if (tid < nvec) {
+            double D[EPV];
+            float pm[EPV];
 #pragma unroll
-        for (int k = 0; k < EPV; ++k) { D[k] = 0.0; pm[k] = 0.f; }
-        for (int h = 0; h < H; ++h) {
-            const gvec c = (gvec)(gbytes)(static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride);
-            float cv[EPV], rv[EPV];
-            const u32x4 cw4 = c[v];
-            E::unpack(cw4, cv);
-            if (rad) {
-                const gvec r = (gvec)(gbytes)(static_cast<const T*>(A.radius) + (int64_t)h * head_stride + row * A.stride);
-                const u32x4 rw4 = r[v];
+            for (int k = 0; k < EPV; ++k) { D[k] = 0.0; pm[k] = 0.f; }
+            for (int h = 0; h < H; ++h) {
+                const gvec c = (gvec)(gbytes)(static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride);
+                const gvec r = (gvec)(gbytes)(static_cast<const T*>(rad ? A.radius : A.draft) +
+                                              (int64_t)h * head_stride + row * A.stride);
+                const u32x4 cw4 = c[tid], rw4 = r[tid];
+                float cv[EPV], rv[EPV];
+                E::unpack(cw4, cv);
                 E::unpack(rw4, rv);
-            }
-            const FuseRow fr = sm_fr[h];
-            const float n = sm_n[h], invS = sm_invS[h];
-            const double cw = sm_cw[h], cl = sm_cl[h];
-            if (tiny) {
-                // A handful of tokens: widths are O(1) and Sigma can be an exact zero (two tokens), which
-                // fp32 token arithmetic cannot resolve to 1e-7; the few tokens are done in fp64.
-#pragma unroll
                 for (int k = 0; k < EPV; ++k) {
-                    if (v * EPV + k < V) {
-                        const double x = exp((double)cv[k] - (double)n * kLn2) / sm_S[h];
+                    if (tid * EPV + k < V) {
+                        const double x = exp((double)cv[k] - (double)sm_n[h] * kLn2) / sm_S[h];
                         double a = A.a, b = A.b;
                         if (rad) {
-                            const double r = radius_of((double)rv[k], A.kappa, A.rmax);
-                            a = exp(r); b = exp(-r);
+                            const double rr = radius_of((double)rv[k], A.kappa, A.rmax);
+                            a = exp(rr); b = exp(-rr);
                         }
                         D[k] += sm_au[h] * a * x / (1.0 + (a - 1.0) * x) - sm_al[h] * b * x / (1.0 + (b - 1.0) * x);
                         pm[k] += (float)x;
                     }
                 }
-                continue;
             }
-#pragma unroll
             for (int k = 0; k < EPV; ++k) {
-                if (v * EPV + k < V) {
-                    const float e = exp2_ref(cv[k], n);
-                    float gl, gw;
-                    if (rad) fuse_token_rad(e, rv[k], fr, kap, rmax, gl, gw);
-                    else fuse_token(e, fr, gl, gw);
-                    D[k] = fma(cw, (double)gw, fma(cl, (double)gl, D[k]));
-                    pm[k] = fmaf(e, invS, pm[k]);
+                const int tok = tid * EPV + k;
+                s1 += D[k];
+                s2 = fma(D[k], D[k], s2);
+                if (need_argmax && tok < V && pm[k] > best) { best = pm[k]; best_i = tok; }
+            }
+        }
+    }
+    constexpr int UB = 16 / EPV;                                   // vectors of a head in flight per lane
+    for (int v0 = tid; !tiny && v0 < nvec; v0 += 256 * UB) {
+        double D[UB][EPV];                                         // fp64 across heads
+        float pm[UB][EPV];
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) { D[u][k] = 0.0; pm[u][k] = 0.f; }
+        }
+        for (int h = 0; h < H; ++h) {
+            const gvec c = (gvec)(gbytes)(static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride);
+            const gvec r = (gvec)(gbytes)(static_cast<const T*>(rad ? A.radius : A.draft) + (int64_t)h * head_stride +
+                                          row * A.stride);
+            u32x4 cw4[UB], rw4[UB];
+#pragma unroll
+            for (int u = 0; u < UB; ++u) cw4[u] = c[min(v0 + u * 256, nvec - 1)];
+            if (rad) {
+#pragma unroll
+                for (int u = 0; u < UB; ++u) rw4[u] = r[min(v0 + u * 256, nvec - 1)];
+            }
+            const FuseRow fr = sm_fr[h];
+            const float n = sm_n[h], invS = sm_invS[h];
+            const double cw = sm_cw[h], cl = sm_cl[h];
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const int tok0 = (v0 + u * 256) * EPV;             // >= V for vectors past the row's end
+                float cv[EPV], rv[EPV];
+                E::unpack(cw4[u], cv);
+                if (rad) E::unpack(rw4[u], rv);
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) {
+                    if (tok0 + k < V) {
+                        const float e = exp2_ref(cv[k], n);
+                        float gl, gw;
+                        if (rad) fuse_token_rad(e, rv[k], fr, kap, rmax, gl, gw);
+                        else fuse_token(e, fr, gl, gw);
+                        D[u][k] = fma(cw, (double)gw, fma(cl, (double)gl, D[u][k]));
+                        pm[u][k] = fmaf(e, invS, pm[u][k]);
+                    }
                 }
             }
         }
 #pragma unroll
-        for (int k = 0; k < EPV; ++k) {
-            const double d = D[k];                                 // tokens past V contribute exactly 0
-            s1 += d;
-            s2 = fma(d, d, s2);
-            if (need_argmax && v * EPV + k < V && pm[k] > best) { best = pm[k]; best_i = v * EPV + k; }
+        for (int u = 0; u < UB; ++u) {
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) {
+                const int tok = (v0 + u * 256) * EPV + k;
+                const double d = D[u][k];                          // tokens past V contribute exactly 0
+                s1 += d;
+                s2 = fma(d, d, s2);
+                if (need_argmax && tok < V && pm[u][k] > best) { best = pm[u][k]; best_i = tok; }
+            }
         }
     }
     s1 = wave_sum(s1);
