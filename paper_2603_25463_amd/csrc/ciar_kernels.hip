@@ -813,17 +813,20 @@ __global__ __launch_bounds__(256) void rowfinish_kernel(const RowArgs A, const i
     }
 }
 
-// Residual draw of the rejected rows: res_i = max(0, q_i - p_i), inverse CDF in token order.  Workgroups of
-// 1024 lanes walk over the list of rejected rows; both rows are fetched again (they were read moments ago:
-// mostly from cache), at most 8 vectors of each row per lane, all in flight at once.
-template <typename T>
-__global__ __launch_bounds__(1024) void resample_kernel(const RowArgs A, const int K, int32_t* __restrict__ resampled_id)
+// Residual draw of the rejected rows: res_i = max(0, q_i - p_i), inverse CDF in token order.  Workgroups walk
+// over the list of rejected rows; both rows are fetched again (they were read moments ago: mostly from
+// cache), four vectors of each row per lane in flight at once.  A row's draw is a chain of dependent
+// steps (list entry, statistics, loads, totals, crossing chunk, scan), so what matters is how many rows
+// a compute unit has in flight: 256-lane workgroups, several per compute unit, unless the launch is so
+// small that most compute units would see no rejected row at all (then 1024 lanes work on each row).
+template <typename T, int THREADS>
+__global__ __launch_bounds__(THREADS) void resample_kernel(const RowArgs A, const int K, int32_t* __restrict__ resampled_id)
 {
     using E = Elt<T>;
     constexpr int EPV = E::kPerVec;
-    constexpr int THREADS = 1024, NW = 16;
+    constexpr int NW = THREADS / 64;
     constexpr int CHUNK = THREADS * EPV;
-    constexpr int MAXCH = 8;                        // chunks of CHUNK tokens a row can have (supported vocabularies)
+    constexpr int MAXCH = 8192 / THREADS;           // chunks of CHUNK tokens a row can have (supported vocabularies)
     constexpr int UB = 4;                           // chunks of each row in flight per lane
 
     __shared__ double sm_e[NW * MAXCH + NW];
@@ -1423,11 +1426,17 @@ hipError_t launch_finish_typed(Mode mode, const RowArgs& a, int32_t K, int32_t* 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || mode == Mode::Quantify) return e;
     if (a.row_id) {
-        // one 1024-lane workgroup per compute unit walks over the rejected rows
         const int64_t cus = compute_units();
-        const unsigned grid = (unsigned)(a.N < cus ? a.N : cus);
-        hipLaunchKernelGGL(resample_kernel<T>, dim3(grid), dim3(1024), 0, s, a, K,
-                           inline_windows ? resampled_id : nullptr);
+        if (a.N >= 4 * cus) {
+            // four 256-lane workgroups per compute unit walk over the rejected rows
+            hipLaunchKernelGGL((resample_kernel<T, 256>), dim3((unsigned)(4 * cus)), dim3(256), 0, s, a, K,
+                               inline_windows ? resampled_id : nullptr);
+        } else {
+            // very few rows (less than one rejected row per compute unit): 1024 lanes on each row
+            const unsigned grid = (unsigned)(a.N < cus ? a.N : cus);
+            hipLaunchKernelGGL((resample_kernel<T, 1024>), dim3(grid), dim3(1024), 0, s, a, K,
+                               inline_windows ? resampled_id : nullptr);
+        }
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
