@@ -70,6 +70,8 @@ def _load():
         lib.ciar_oracle_quantify_multihead.restype = i32
         lib.ciar_oracle_quantify_multihead.argtypes = [vp, vp, ctypes.c_int32, i64, vp, i64, pp, ctypes.c_int32] + \
             [vp] * 8 + [i32]
+        lib.ciar_oracle_interdro_loss.restype = i32
+        lib.ciar_oracle_interdro_loss.argtypes = [vp, vp, vp, i64, pp] + [ctypes.c_double] * 4 + [vp, vp, vp, i32]
         lib.ciar_oracle_residual_cdf.restype = ctypes.c_double
         lib.ciar_oracle_residual_cdf.argtypes = [vp, vp, i64, pp, vp]
         lib.ciar_oracle_verify.restype = i32
@@ -139,6 +141,32 @@ def quantify(draft, ids, params: Params, vocab: int | None = None, threads: int 
                                       _ptr(out["omega"]), _ptr(out["sigma"]), _ptr(out["score"]),
                                       _ptr(out["flags"]), threads or default_threads())
     assert rc == 0
+    return out
+
+
+DRO_TERMS = ("l1_mid", "l1_up", "l1_lo", "ce_mid", "ce_up", "ce_lo", "kl")
+DRO_LOSSES = ("center", "upper", "lower", "dro", "total")
+
+
+def interdro_loss(center, radius, cloud, params: Params, lambda_v: float, lambda_p: float, lambda_beta: float,
+                  alpha: float, vocab: int | None = None, threads: int | None = None):
+    """Forward value of the Inter-DRO loss.  Returns dict: the seven per-row terms (fp64 [N] each, names in
+    DRO_TERMS), ``weights`` [N] and the five scalars of DRO_LOSSES."""
+    c, t = _logits(center), _logits(cloud)
+    assert c.shape == t.shape and c.dtype == t.dtype
+    rad = _radius(radius, c)
+    N = c.shape[0]
+    cp = _cparams(params, c, vocab)
+    rows = np.empty((7, N), dtype=np.float64)
+    w = np.empty(N, dtype=np.float64)
+    losses = np.empty(5, dtype=np.float64)
+    rc = _load().ciar_oracle_interdro_loss(_ptr(c), _ptr(rad), _ptr(t), N, ctypes.byref(cp), float(lambda_v),
+                                           float(lambda_p), float(lambda_beta), float(alpha), _ptr(rows), _ptr(w),
+                                           _ptr(losses), threads or default_threads())
+    assert rc == 0
+    out = {k: rows[i] for i, k in enumerate(DRO_TERMS)}
+    out["weights"] = w
+    out.update({k: float(losses[i]) for i, k in enumerate(DRO_LOSSES)})
     return out
 
 

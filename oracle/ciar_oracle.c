@@ -16,6 +16,8 @@
  *   - aggregation of several Interval Heads                 (Sec. 4, ablation on the Inter-Head: "Voting" = the
  *                                                            majority of the heads' decisions, "Ensemble" = the
  *                                                            heads' probability distributions averaged)
+ *   - the forward value of the Inter-DRO training loss      (Sec. 3.2.3 "Interval-enhanced Distributionally Robust
+ *                                                            Training": anchor, DRO and alignment equations)
  *   - cloud verification of a window of K drafted tokens and resampling (Algorithm 1, the "Cloud verification"
  *     step and the following resample / advance steps).  The paper names this step as speculative decoding
  *     (Introduction) without writing the test down; this file uses the standard speculative-sampling rule:
@@ -349,6 +351,108 @@ int ciar_oracle_quantify_multihead(const void* draft, const void* radius, int32_
         }
         free(e); free(pl); free(pu); free(apl); free(apm); free(apu);
     }
+    return failed ? -1 : 0;
+}
+
+/* ---- Inter-DRO loss, forward ----------------------------------------------------------- */
+
+/* ln softmax(o)_i for a row of V logits o (fp64): lsm[i] = o_i - max o - ln sum_j exp(o_j - max o). */
+static void log_softmax(const double* o, int V, double* lsm)
+{
+    double m = -INFINITY;
+    for (int i = 0; i < V; ++i) if (o[i] > m) m = o[i];
+    double s = 0.0;
+    for (int i = 0; i < V; ++i) s += exp(o[i] - m);
+    const double lz = m + log(s);
+    for (int i = 0; i < V; ++i) lsm[i] = o[i] - lz;
+}
+
+/*
+ * Forward value of the Inter-DRO loss (Sec. 3.2.3, the four loss equations) for a batch of N rows.
+ *   p_mid = softmax(c), p_up = softmax(c + r), p_lo = softmax(c - r), p_cloud = softmax(cloud), r_i as in the
+ *   quantifier (min(kappa * rho_i, radius_max), rho_i = Softplus(raw_i) with a radius tensor, else 1);
+ *   L1(p) = ||p - p_cloud||_1,  CE(p) = - sum_i p_cloud,i ln p_i,  KL = sum_i p_cloud,i (ln p_cloud,i - ln p_mid,i)
+ *   (tokens with p_cloud,i = 0 contribute nothing to CE and KL);
+ *   w_n = exp(alpha CE_n(p_lo)) / sum_k exp(alpha CE_k(p_lo)),  DRO = sum_n w_n CE_n(p_lo).
+ * Per-row terms rows[t * N + n], t = 0..6: L1(p_mid), L1(p_up), L1(p_lo), CE(p_mid), CE(p_up), CE(p_lo), KL.
+ * losses[0..4] = centre, upper, lower, DRO, total, with the batch reduction the paper leaves open taken as the
+ * mean over the N rows for the anchor and alignment terms (the DRO term is the weighted sum as printed):
+ *   centre = mean(lambda_v L1(p_mid) + lambda_p CE(p_mid) + lambda_beta KL)
+ *   upper  = mean(lambda_v L1(p_up) + lambda_p CE(p_up)),   lower = mean(lambda_v L1(p_lo) + lambda_p CE(p_lo))
+ *   total  = centre + upper + lower + DRO.
+ * Any of rows, weights, losses may be NULL.  Returns 0, or -1 on allocation failure.
+ */
+int ciar_oracle_interdro_loss(const void* center, const void* radius, const void* cloud, int64_t N,
+                              const ciar_oracle_params* P, double lambda_v, double lambda_p, double lambda_beta,
+                              double alpha, double* rows, double* weights, double* losses, int threads)
+{
+    const int V = P->vocab;
+    int failed = 0;
+    if (threads < 1) threads = 1;
+    double* terms = (double*)malloc(sizeof(double) * 7 * (size_t)(N > 0 ? N : 1));
+    if (!terms) return -1;
+#pragma omp parallel num_threads(threads)
+    {
+        double* o   = (double*)malloc(sizeof(double) * (size_t)V);
+        double* lpc = (double*)malloc(sizeof(double) * (size_t)V);
+        double* lp  = (double*)malloc(sizeof(double) * (size_t)V);
+        double* r   = (double*)malloc(sizeof(double) * (size_t)V);
+        if (!o || !lpc || !lp || !r) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+            const double kappa = radius_scale(P);
+#pragma omp for schedule(static)
+            for (int64_t n = 0; n < N; ++n) {
+                const int64_t off = n * P->row_stride;
+                for (int i = 0; i < V; ++i) {
+                    o[i] = load_logit(cloud, P->dtype, off + i);
+                    r[i] = token_radius(P, kappa, radius, off + i);
+                }
+                log_softmax(o, V, lpc);
+                for (int v = 0; v < 3; ++v) {                      /* mid, up, lo */
+                    const double sgn = v == 0 ? 0.0 : (v == 1 ? 1.0 : -1.0);
+                    for (int i = 0; i < V; ++i) o[i] = load_logit(center, P->dtype, off + i) + sgn * r[i];
+                    log_softmax(o, V, lp);
+                    double l1 = 0.0, ce = 0.0, kl = 0.0;
+                    for (int i = 0; i < V; ++i) {
+                        const double pc = exp(lpc[i]), p = exp(lp[i]);
+                        l1 += fabs(p - pc);
+                        if (pc > 0.0) { ce -= pc * lp[i]; kl += pc * (lpc[i] - lp[i]); }
+                    }
+                    terms[(int64_t)v * N + n] = l1;
+                    terms[(int64_t)(3 + v) * N + n] = ce;
+                    if (v == 0) terms[6 * N + n] = kl;
+                }
+            }
+        }
+        free(o); free(lpc); free(lp); free(r);
+    }
+    if (!failed) {
+        if (rows) memcpy(rows, terms, sizeof(double) * 7 * (size_t)N);
+        const double* ce_lo = terms + 5 * N;
+        double mx = -INFINITY;
+        for (int64_t n = 0; n < N; ++n) if (alpha * ce_lo[n] > mx) mx = alpha * ce_lo[n];
+        double den = 0.0;
+        for (int64_t n = 0; n < N; ++n) den += exp(alpha * ce_lo[n] - mx);
+        double dro = 0.0, centre = 0.0, upper = 0.0, lower = 0.0;
+        for (int64_t n = 0; n < N; ++n) {
+            const double w = exp(alpha * ce_lo[n] - mx) / den;
+            if (weights) weights[n] = w;
+            dro += w * ce_lo[n];
+            centre += lambda_v * terms[n] + lambda_p * terms[3 * N + n] + lambda_beta * terms[6 * N + n];
+            upper  += lambda_v * terms[N + n] + lambda_p * terms[4 * N + n];
+            lower  += lambda_v * terms[2 * N + n] + lambda_p * terms[5 * N + n];
+        }
+        if (N > 0) { centre /= (double)N; upper /= (double)N; lower /= (double)N; }
+        if (losses) {
+            losses[0] = centre; losses[1] = upper; losses[2] = lower; losses[3] = dro;
+            losses[4] = centre + upper + lower + dro;
+        }
+    }
+    free(terms);
     return failed ? -1 : 0;
 }
 

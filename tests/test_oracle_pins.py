@@ -722,3 +722,109 @@ def test_multihead_head_stride_and_bf16(oracle):
     b = oracle.quantify_multihead(c.float(), ids, P, oracle.ENSEMBLE)
     for k in a:
         np.testing.assert_array_equal(a[k], b[k])
+
+
+# ---- Inter-DRO loss, forward (Sec. 3.2.3: anchor, DRO and alignment equations) -----------------------------
+
+def _dro_inputs(rng, n, V, scale=2.0, noise=0.6):
+    c = _rows(rng, n, V, scale)
+    t = (c + noise * rng.standard_normal((n, V))).astype(np.float32)
+    raw = _raw_radius(rng, n, V)
+    return c, raw, t
+
+
+def test_interdro_terms_against_scipy(oracle):
+    """Per-row terms from library routines: p = scipy softmax of c, c + r, c - r; L1 by numpy; CE = H(p_cloud) +
+    KL(p_cloud || p) with scipy.stats.entropy; KL by scipy.special.rel_entr.  r = kappa * log1p(exp(raw)) by numpy."""
+    rng = np.random.default_rng(61)
+    n, V, kap = 7, 193, 1.0
+    c, raw, t = _dro_inputs(rng, n, V)
+    q = oracle.interdro_loss(c, raw, t, oracle.Params(kappa=kap), 0.7, 1.3, 0.4, 2.0)
+    c64, t64 = c.astype(np.float64), t.astype(np.float64)
+    r = kap * np.log1p(np.exp(raw.astype(np.float64)))
+    pc = sps.softmax(t64, axis=1)
+    ps = {"mid": sps.softmax(c64, axis=1), "up": sps.softmax(c64 + r, axis=1), "lo": sps.softmax(c64 - r, axis=1)}
+    for k, p in ps.items():
+        np.testing.assert_allclose(q[f"l1_{k}"], np.abs(p - pc).sum(1), rtol=1e-12)
+        ce = np.array([spst.entropy(pc[i]) + spst.entropy(pc[i], p[i]) for i in range(n)])
+        np.testing.assert_allclose(q[f"ce_{k}"], ce, rtol=1e-12)
+    np.testing.assert_allclose(q["kl"], sps.rel_entr(pc, ps["mid"]).sum(1), rtol=1e-11, atol=1e-15)
+    # the three distributions differ: shifting by +r is not shifting by -r
+    assert np.all(np.abs(q["ce_up"] - q["ce_lo"]) > 1e-6)
+    # Gibbs and Pinsker
+    H = np.array([spst.entropy(pc[i]) for i in range(n)])
+    assert np.all(q["ce_mid"] >= H - 1e-12) and np.all(q["kl"] >= -1e-15)
+    assert np.all(q["l1_mid"] ** 2 <= 2 * q["kl"] + 1e-12)
+
+
+def test_interdro_batch_weights_and_total(oracle):
+    """w = scipy softmax of alpha * CE(p_lo) over the batch; DRO = sum w CE; anchor / alignment terms are batch
+    means with the lambdas; total is their sum.  alpha = 0 gives uniform weights, a large alpha the worst row."""
+    rng = np.random.default_rng(62)
+    n, V = 33, 101
+    c, raw, t = _dro_inputs(rng, n, V)
+    lv, lp, lb, alpha = 0.5, 2.0, 0.25, 3.0
+    q = oracle.interdro_loss(c, raw, t, oracle.Params(kappa=1.0), lv, lp, lb, alpha)
+    w = sps.softmax(alpha * q["ce_lo"])
+    np.testing.assert_allclose(q["weights"], w, rtol=1e-12)
+    np.testing.assert_allclose(q["dro"], float(np.dot(w, q["ce_lo"])), rtol=1e-12)
+    centre = np.mean(lv * q["l1_mid"] + lp * q["ce_mid"] + lb * q["kl"])
+    upper = np.mean(lv * q["l1_up"] + lp * q["ce_up"])
+    lower = np.mean(lv * q["l1_lo"] + lp * q["ce_lo"])
+    np.testing.assert_allclose([q["center"], q["upper"], q["lower"]], [centre, upper, lower], rtol=1e-12)
+    np.testing.assert_allclose(q["total"], centre + upper + lower + q["dro"], rtol=1e-12)
+    q0 = oracle.interdro_loss(c, raw, t, oracle.Params(kappa=1.0), lv, lp, lb, 0.0)
+    np.testing.assert_allclose(q0["weights"], 1.0 / n, rtol=1e-12)
+    np.testing.assert_allclose(q0["dro"], q["ce_lo"].mean(), rtol=1e-12)
+    qi = oracle.interdro_loss(c, raw, t, oracle.Params(kappa=1.0), lv, lp, lb, 1e4)
+    np.testing.assert_allclose(qi["dro"], q["ce_lo"].max(), rtol=1e-9)
+    assert q0["dro"] < q["dro"] < qi["dro"]                      # harder rows weigh more as alpha grows
+
+
+def test_interdro_special_cases(oracle):
+    """cloud == centre and zero radius: every distance vanishes and CE is the entropy.  A scalar radius shifts
+    every logit alike, so p_up = p_lo = p_mid.  V = 2: CE(p_mid) = softplus form of the two-class cross-entropy."""
+    rng = np.random.default_rng(63)
+    c = _rows(rng, 5, 64, 2.0)
+    q = oracle.interdro_loss(c, np.full_like(c, -900.0), c, oracle.Params(kappa=1.0), 1.0, 1.0, 1.0, 1.0)
+    H = np.array([spst.entropy(sps.softmax(c[i].astype(np.float64))) for i in range(5)])
+    for k in ("l1_mid", "l1_up", "l1_lo", "kl"):
+        np.testing.assert_allclose(q[k], 0.0, atol=1e-14)
+    for k in ("ce_mid", "ce_up", "ce_lo"):
+        np.testing.assert_allclose(q[k], H, rtol=1e-12)
+    t = (c + rng.standard_normal(c.shape)).astype(np.float32)
+    s = oracle.interdro_loss(c, None, t, oracle.Params(kappa=1.7), 1.0, 1.0, 1.0, 1.0)
+    np.testing.assert_allclose(s["ce_up"], s["ce_mid"], rtol=1e-12)
+    np.testing.assert_allclose(s["l1_lo"], s["l1_mid"], rtol=1e-12, atol=1e-16)
+    c2 = _rows(rng, 9, 2, 2.0)
+    t2 = _rows(rng, 9, 2, 2.0)
+    b = oracle.interdro_loss(c2, None, t2, oracle.Params(kappa=0.0), 1.0, 1.0, 1.0, 0.0)
+    d = c2[:, 0].astype(np.float64) - c2[:, 1]
+    dt = t2[:, 0].astype(np.float64) - t2[:, 1]
+    pc0 = sps.expit(dt)
+    ce = pc0 * np.log1p(np.exp(-d)) + (1 - pc0) * np.log1p(np.exp(d))
+    np.testing.assert_allclose(b["ce_mid"], ce, rtol=1e-12)
+    np.testing.assert_allclose(b["l1_mid"], 2 * np.abs(sps.expit(d) - pc0), rtol=1e-12, atol=1e-16)
+
+
+def test_interdro_masked_cloud_tokens_stride_and_bf16(oracle):
+    import torch
+    rng = np.random.default_rng(64)
+    V, stride = 50, 56
+    c = np.full((4, stride), 1e30, dtype=np.float32)
+    t = np.full((4, stride), 1e30, dtype=np.float32)
+    raw = np.full((4, stride), np.nan, dtype=np.float32)
+    c[:, :V], raw[:, :V], t[:, :V] = _dro_inputs(rng, 4, V)
+    t[:, 3] = -np.inf                                             # a token the cloud model rules out
+    q = oracle.interdro_loss(c, raw, t, oracle.Params(kappa=1.0), 1.0, 1.0, 1.0, 1.0, vocab=V)
+    assert all(np.all(np.isfinite(q[k])) for k in oracle.DRO_TERMS) and np.isfinite(q["total"])
+    pc = sps.softmax(t[:, :V].astype(np.float64), axis=1)
+    assert np.all(pc[:, 3] == 0.0)
+    p = sps.softmax(c[:, :V].astype(np.float64), axis=1)
+    keep = np.arange(V) != 3
+    np.testing.assert_allclose(q["kl"], (pc[:, keep] * (np.log(pc[:, keep]) - np.log(p[:, keep]))).sum(1), rtol=1e-11)
+    cb, rb, tb = (torch.from_numpy(x[:, :V].copy()).to(torch.bfloat16) for x in (c, np.nan_to_num(raw), t))
+    a = oracle.interdro_loss(cb, rb, tb, oracle.Params(kappa=1.0), 1.0, 1.0, 1.0, 1.0)
+    b = oracle.interdro_loss(cb.float(), rb.float(), tb.float(), oracle.Params(kappa=1.0), 1.0, 1.0, 1.0, 1.0)
+    for k in oracle.DRO_TERMS:
+        np.testing.assert_array_equal(a[k], b[k])
