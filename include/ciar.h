@@ -221,6 +221,30 @@ int ciar_quantify_multihead(const void* draft_heads, const void* radius_heads, i
                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Forward value of the Inter-DRO training loss (Sec. 3.2.3 "Interval-enhanced Distributionally Robust
+ * Training": the anchor, DRO and alignment equations).  No gradients.
+ *
+ *   center_logits [N, row_stride]   in   centre logits c of the Interval Head
+ *   radius        [N, row_stride]   in   raw radius tensor, or NULL (scalar radius; radius rules as above)
+ *   cloud_logits  [N, row_stride]   in   the cloud model's logits o_cloud
+ * With p_mid = softmax(c), p_up = softmax(c + r), p_lo = softmax(c - r), p_cloud = softmax(o_cloud):
+ *   L1(p) = ||p - p_cloud||_1,  CE(p) = - sum_i p_cloud,i ln p_i,  KL = KL(p_cloud || p_mid)
+ *   (a token with p_cloud,i = 0, e.g. a -inf cloud logit, contributes nothing to CE and KL).
+ *   row_terms [7, N] float  out  rows of L1(p_mid), L1(p_up), L1(p_lo), CE(p_mid), CE(p_up), CE(p_lo), KL
+ *   weights   [N]    float  out  w_n = exp(alpha CE_n(p_lo)) / sum_k exp(alpha CE_k(p_lo))   (may be NULL)
+ *   losses    [5]    float  out  centre, upper, lower, DRO, total                             (may be NULL)
+ *       centre = mean_n(lambda_v L1(p_mid) + lambda_p CE(p_mid) + lambda_beta KL)
+ *       upper  = mean_n(lambda_v L1(p_up) + lambda_p CE(p_up)),  lower likewise with p_lo
+ *       DRO    = sum_n w_n CE_n(p_lo),  total = centre + upper + lower + DRO
+ * The paper prints no batch reduction for the anchor and alignment terms: the mean over the N rows is this
+ * library's reading; lambda_v, lambda_p, lambda_beta and alpha are not given in the paper and have no defaults.
+ * No workspace.  Same pointer, alignment, stream and error rules as ciar_quantify.
+ */
+int ciar_interdro_loss(const void* center_logits, const void* radius, const void* cloud_logits, int64_t N,
+                       const ciar_params* params, float lambda_v, float lambda_p, float lambda_beta, float alpha,
+                       float* row_terms, float* weights, float* losses, void* hip_stream);
+
+/*
  * Measurement aid, not a step of the method: a plain streaming read of the rows the hot path reads
  * (the "read both rows and sum" ceiling a memory-bound pass is held against).  Every logit of
  * draft_logits [N, row_stride] and, unless NULL, target_logits is loaded once with 16-byte loads and

@@ -3,8 +3,12 @@
 ``binding`` marshals torch tensors into the C ABI declared in ``include/ciar.h``;
 ``workloads`` generates the seeded synthetic inputs; ``build`` compiles ``libciar.so`` for gfx950.
 """
-from .binding import (ENSEMBLE, VOTING, CiarError, Params, dense_intervals, finish_rows, last_error, lib, quantify,
-                      quantify_multihead, quantify_verify, read_rows, stream_rows, verify, version, window_epilogue, workspace_bytes)
+from .binding import (DRO_LOSSES, DRO_TERMS, ENSEMBLE, VOTING, CiarError, Params, dense_intervals,
+                      finish_rows, interdro_loss, last_error, lib, quantify, quantify_multihead,
+                      quantify_verify, read_rows, stream_rows, verify, version, window_epilogue,
+                      workspace_bytes)
 
-__all__ = ["ENSEMBLE", "VOTING", "CiarError", "Params", "dense_intervals", "finish_rows", "last_error", "lib", "quantify",
-           "quantify_multihead", "quantify_verify", "read_rows", "stream_rows", "verify", "version", "window_epilogue", "workspace_bytes"]
+__all__ = ["DRO_LOSSES", "DRO_TERMS", "ENSEMBLE", "VOTING", "CiarError", "Params", "dense_intervals",
+           "finish_rows", "interdro_loss", "last_error", "lib", "quantify", "quantify_multihead",
+           "quantify_verify", "read_rows", "stream_rows", "verify", "version", "window_epilogue",
+           "workspace_bytes"]

@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.ciar_quantify_multihead.restype = ctypes.c_int
         L.ciar_quantify_multihead.argtypes = [vp, vp, ctypes.c_int32, i64, vp, i64, pp, ctypes.c_int32] + \
             [vp] * 8 + [vp, sz, vp]
+        L.ciar_interdro_loss.restype = ctypes.c_int
+        L.ciar_interdro_loss.argtypes = [vp, vp, vp, i64, pp] + [ctypes.c_float] * 4 + [vp, vp, vp, vp]
         L.ciar_read_rows.restype = ctypes.c_int
         L.ciar_read_rows.argtypes = [vp, vp, i64, pp, vp, vp]
         L.ciar_last_error.restype = ctypes.c_char_p
@@ -340,4 +342,27 @@ def quantify_multihead(draft_heads: torch.Tensor, ids: torch.Tensor | None, para
         _ptr(o["p_lo"]), _ptr(o["p_mid"]), _ptr(o["p_hi"]), _ptr(o["omega"]), _ptr(o["sigma"]), _ptr(o["score"]),
         _ptr(o["flags"]), _ptr(o.get("head_flags")), _ptr(workspace), workspace.numel() * workspace.element_size(),
         _stream(stream)))
+    return o
+
+
+DRO_TERMS = ("l1_mid", "l1_up", "l1_lo", "ce_mid", "ce_up", "ce_lo", "kl")
+DRO_LOSSES = ("center", "upper", "lower", "dro", "total")
+
+
+def interdro_loss(center: torch.Tensor, radius: torch.Tensor | None, cloud: torch.Tensor, params: Params,
+                  lambda_v: float, lambda_p: float, lambda_beta: float, alpha: float, vocab: int | None = None,
+                  stream=None) -> dict:
+    """``ciar_interdro_loss`` (forward only).  Returns ``terms`` float32 [7, N] (rows named by DRO_TERMS),
+    ``weights`` float32 [N] and ``losses`` float32 [5] (named by DRO_LOSSES), all on the GPU."""
+    _need_cuda(center, radius, cloud)
+    _like_draft(cloud, center, "cloud")
+    _like_draft(radius, center, "radius")
+    N, dev = center.shape[0], center.device
+    cp = params.to_c(center, vocab)
+    o = {"terms": torch.empty((7, N), dtype=torch.float32, device=dev),
+         "weights": torch.empty(N, dtype=torch.float32, device=dev),
+         "losses": torch.empty(5, dtype=torch.float32, device=dev)}
+    _check(lib().ciar_interdro_loss(_ptr(center), _ptr(radius), _ptr(cloud), N, ctypes.byref(cp), float(lambda_v),
+                                    float(lambda_p), float(lambda_beta), float(alpha), _ptr(o["terms"]),
+                                    _ptr(o["weights"]), _ptr(o["losses"]), _stream(stream)))
     return o

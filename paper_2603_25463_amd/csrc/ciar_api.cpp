@@ -385,6 +385,32 @@ int ciar_dense_intervals(const void* draft_logits, const void* radius, int64_t N
     return CIAR_OK;
 }
 
+int ciar_interdro_loss(const void* center_logits, const void* radius, const void* cloud_logits, int64_t N,
+                       const ciar_params* params, float lambda_v, float lambda_p, float lambda_beta, float alpha,
+                       float* row_terms, float* weights, float* losses, void* hip_stream)
+{
+    Resolved r;
+    if (int rc = check_params(params, &r)) return rc;
+    if (N < 0) return fail(CIAR_EINVAL, "N is negative");
+    if (N > 0x7fffffffLL) return fail(CIAR_EUNSUPPORTED, "N exceeds 2^31 - 1 rows per call");
+    if (int rc = check_rows(center_logits, "center_logits")) return rc;
+    if (int rc = check_rows(cloud_logits, "cloud_logits")) return rc;
+    if (radius)
+        if (int rc = check_rows(radius, "radius")) return rc;
+    if (!std::isfinite(lambda_v) || !std::isfinite(lambda_p) || !std::isfinite(lambda_beta) || !std::isfinite(alpha))
+        return fail(CIAR_EINVAL, "lambda_v, lambda_p, lambda_beta and alpha must be finite");
+    if (!row_terms) return fail(CIAR_EINVAL, "row_terms is NULL");
+    if (N == 0) return CIAR_OK;
+    ciar::RowArgs a = base_args(params, r, N);
+    a.draft = center_logits;
+    a.radius = radius;
+    a.target = cloud_logits;
+    const hipError_t e = ciar::launch_dro(params->dtype, a, row_terms, lambda_v, lambda_p, lambda_beta, alpha, weights,
+                                          losses, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail(e, "loss kernel launch");
+    return CIAR_OK;
+}
+
 size_t ciar_multihead_workspace_bytes(int64_t N, int32_t heads, const ciar_params* /*params*/)
 {
     if (N <= 0 || heads < 1) return 0;

@@ -67,6 +67,11 @@ hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, int32_t K, i
 hipError_t launch_windows(const uint8_t* accept, const int32_t* row_id, int64_t N, int32_t K,
                           int32_t* accept_len, int32_t* resampled_id, hipStream_t stream);
 
+// Forward value of the Inter-DRO loss: args.draft = centre logits, args.radius (or null), args.target = cloud
+// logits.  terms [7][N]; weights [N] and losses [5] may be null.
+hipError_t launch_dro(int dtype, const RowArgs& args, float* terms, double lambda_v, double lambda_p,
+                      double lambda_beta, double alpha, float* weights, float* losses, hipStream_t stream);
+
 // Several heads.  Head h of args.draft / args.radius starts h * head_stride elements after head 0;
 // args.stats holds [heads][N] RowStats left by one streaming pass per head.
 int max_heads();

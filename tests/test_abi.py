@@ -28,7 +28,7 @@ def _declared_functions():
 def test_header_declares_the_expected_entry_points():
     names = _declared_functions()
     for n in ("ciar_quantify", "ciar_verify", "ciar_quantify_verify", "ciar_dense_intervals",
-              "ciar_stream_rows", "ciar_finish_rows", "ciar_window_epilogue", "ciar_read_rows", "ciar_quantify_multihead", "ciar_multihead_workspace_bytes",
+              "ciar_stream_rows", "ciar_finish_rows", "ciar_window_epilogue", "ciar_read_rows", "ciar_interdro_loss", "ciar_quantify_multihead", "ciar_multihead_workspace_bytes",
               "ciar_workspace_bytes", "ciar_params_default", "ciar_last_error", "ciar_version"):
         assert n in names
 
@@ -117,6 +117,15 @@ def test_argument_errors_are_reported_before_any_launch(L):
                               FAKE, 4096, None) == EINVAL                            # verify outputs, no target
     assert L.ciar_finish_rows(FAKE, None, FAKE, FAKE, FAKE, FAKE, 4, a, FAKE, *([None] * 10), FAKE, 4096,
                               None) == EINVAL                                        # target, no verify output
+    # Inter-DRO loss
+    f4 = [ctypes.c_float(1.0)] * 4
+    assert L.ciar_interdro_loss(FAKE, None, FAKE, 4, a, *f4, None, None, None, None) == EINVAL      # no row_terms
+    assert L.ciar_interdro_loss(None, None, FAKE, 4, a, *f4, FAKE, None, None, None) == EINVAL
+    assert L.ciar_interdro_loss(FAKE, None, None, 4, a, *f4, FAKE, None, None, None) == EINVAL
+    assert L.ciar_interdro_loss(FAKE, FAKE + 2, FAKE, 4, a, *f4, FAKE, None, None, None) == EALIGN
+    assert L.ciar_interdro_loss(FAKE, None, FAKE, 4, a, ctypes.c_float(float("nan")), *f4[:3], FAKE, None, None,
+                                None) == EINVAL
+    assert L.ciar_interdro_loss(FAKE, None, FAKE, 0, a, *f4, FAKE, None, None, None) == 0
     # several heads
     def mh(heads=2, hs=4096, strategy=1, out=FAKE, ws=FAKE, wsb=1 << 20, draft=FAKE, radius=None, hf=None):
         return L.ciar_quantify_multihead(draft, radius, heads, hs, None, 4, a, strategy, out, None, None, None,

@@ -350,6 +350,68 @@ def test_multihead_ensemble_and_voting(ciar, oracle, H, V, stride, N, dtype, ten
         assert np.all(same | near)
 
 
+# ---- Inter-DRO loss, forward (Sec. 3.2.3) -------------------------------------------------------------------
+
+def _check_dro(g, o, N):
+    """Per-row terms, batch weights and the five scalars against the oracle: 1e-5 relative, 1e-7 absolute
+    (the weights sum to one, so their absolute floor is scaled by 1/N)."""
+    terms = g["terms"].cpu().numpy().astype(np.float64)
+    for i, k in enumerate(("l1_mid", "l1_up", "l1_lo", "ce_mid", "ce_up", "ce_lo", "kl")):
+        assert np.all(np.isfinite(terms[i])), k
+        err = np.abs(terms[i] - o[k])
+        bound = parity.ATOL + parity.RTOL * np.abs(o[k])
+        assert np.all(err <= bound), (k, int(np.argmax(err / bound)), float(np.max(err / bound)))
+    w = g["weights"].cpu().numpy().astype(np.float64)
+    # a weight is exp(alpha CE): an error of 1e-5 relative in CE of ~10 with alpha ~2 moves it by ~2e-4 relative
+    assert np.all(np.abs(w - o["weights"]) <= parity.ATOL / max(N, 1) + 5e-4 * o["weights"])
+    assert abs(w.sum() - 1.0) < 1e-5
+    L = g["losses"].cpu().numpy().astype(np.float64)
+    for i, k in enumerate(("center", "upper", "lower", "dro", "total")):
+        assert abs(L[i] - o[k]) <= parity.ATOL + parity.RTOL * abs(o[k]), (k, L[i], o[k])
+
+
+DRO_SHAPES = [
+    (2, 4, 21, torch.float32), (193, 196, 33, torch.float32), (4096, 4096, 40, torch.float32),
+    (4100, 4100, 9, torch.float32), (16384, 16384, 64, torch.float32), (16385, 16388, 5, torch.float32),
+    (32768, 32768, 6, torch.float32), (1001, 1008, 30, torch.bfloat16), (16384, 16384, 40, torch.bfloat16),
+    (65536, 65536, 6, torch.bfloat16),
+]
+
+
+@pytest.mark.parametrize("V,stride,N,dtype", DRO_SHAPES)
+@pytest.mark.parametrize("tensor_radius", [True, False])
+def test_interdro_loss(ciar, oracle, V, stride, N, dtype, tensor_radius):
+    c, t, *_ = _random_case(V, stride, N, 4, dtype, seed=6000 + V)
+    if stride > V:                                                   # _random_case poisons target padding with -1e30
+        t[:, V:] = 1e30
+    raw = _raw_radius(N, stride, V, dtype, seed=6100 + V) if tensor_radius else None
+    if V > 8:
+        t[0, 3] = float("-inf")                                      # a token the cloud rules out
+    say(f"[interdro] V={V} stride={stride} N={N} {dtype} radius={'tensor' if tensor_radius else 'scalar'}")
+    lam = (0.7, 1.3, 0.4, 2.0)
+    P = ciar.Params(radius_scale=1.0 if tensor_radius else 0.8)
+    g = ciar.interdro_loss(c, raw, t, P, *lam, vocab=V)
+    torch.cuda.synchronize()
+    o = oracle.interdro_loss(c.cpu(), None if raw is None else raw.cpu(), t.cpu(),
+                             oracle.Params(kappa=P.radius_scale), *lam, vocab=V)
+    _check_dro(g, o, N)
+
+
+def test_interdro_loss_on_a_workload(ciar, oracle):
+    """The benchmark workload's rows as (centre, cloud) pairs with the synthetic radius head, every row."""
+    from paper_2603_25463_amd import workloads as wl
+    say("[interdro] workload 2, full size")
+    w = wl.make(2, device="cuda")
+    raw = wl.make_radius(w)
+    lam = (1.0, 1.0, 0.5, 1.0)
+    g = ciar.interdro_loss(w.draft, raw, w.target, ciar.Params(radius_scale=1.0), *lam)
+    torch.cuda.synchronize()
+    o = oracle.interdro_loss(w.draft.cpu(), raw.cpu(), w.target.cpu(), oracle.Params(kappa=1.0), *lam)
+    _check_dro(g, o, w.rows)
+    say(f"   total loss {o['total']:.6f} (centre {o['center']:.4f}, upper {o['upper']:.4f}, lower {o['lower']:.4f}, "
+        f"DRO {o['dro']:.4f})")
+
+
 @pytest.mark.parametrize("K", [1, 3, 8, 100, 128, 255, 256, 257, 300, 1000])
 def test_window_lengths(ciar, oracle, K):
     """Windows that divide, straddle and exceed the finishing kernel's 256-row workgroups; N = 700 leaves a
