@@ -136,6 +136,77 @@ def bench_multihead(args, torch, ciar, wl, dev) -> int:
     return 0
 
 
+def bench_interdro(args, torch, ciar, wl, dev) -> int:
+    """Forward value of the Inter-DRO loss: one step = one ciar_interdro_loss call on the workload's
+    (centre, cloud) row pairs with the synthetic radius head.  Algorithmic bytes: three rows per position."""
+    import ctypes
+    from paper_2603_25463_amd.binding import _ptr, _stream, _check
+    spec = wl.SPECS[args.workload]
+    w = wl.make(args.workload, device=dev)
+    N, V = w.rows, spec.vocab
+    elt = w.draft.element_size()
+    copies = max(1, args.copies)
+    r0 = wl.make_radius(w, device=dev)
+    cs = [w.draft] + [w.draft.clone() for _ in range(copies - 1)]
+    ts = [w.target] + [w.target.clone() for _ in range(copies - 1)]
+    rs = [r0] + [r0.clone() for _ in range(copies - 1)]
+    P = ciar.Params(radius_scale=1.0)
+    cp = P.to_c(w.draft)
+    L = ciar.lib()
+    terms = torch.empty((7, N), dtype=torch.float32, device=dev)
+    weights = torch.empty(N, dtype=torch.float32, device=dev)
+    losses = torch.empty(5, dtype=torch.float32, device=dev)
+    sp = _stream(torch.cuda.current_stream())
+    lam = (1.0, 1.0, 0.5, 1.0)
+
+    def step(i):
+        k = i % copies
+        _check(L.ciar_interdro_loss(_ptr(cs[k]), _ptr(rs[k]), _ptr(ts[k]), N, ctypes.byref(cp), *lam, _ptr(terms),
+                                    _ptr(weights), _ptr(losses), sp))
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+    ms = 1e3 * total_s / args.steps
+    bytes_per_call = N * (3 * V * elt + 32)
+    achieved = bytes_per_call / (ms * 1e-3) / 1e9
+    result = {
+        "metric": f"token positions/sec (Inter-DRO loss forward, V={V} {'fp32' if elt == 4 else 'bf16'})",
+        "value": N * args.steps / total_s, "unit": "positions/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"cfg{args.workload} {spec.name}: {N} positions, V={V}, "
+                               f"{'fp32' if elt == 4 else 'bf16'} centre / raw radius / cloud logits, kappa 1, "
+                               f"lambda_v 1, lambda_p 1, lambda_beta 0.5, alpha 1",
+                   "input_copies_rotated": copies},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "whole call: dro_row_kernel + dro_batch_kernel", "kernel_avg_us": 1e3 * ms,
+                     "algorithmic_bytes_per_launch": bytes_per_call},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = min(N, 512)
+        hc, hr, ht = (x[:rows].cpu().contiguous() for x in (w.draft, r0, w.target))
+        threads = oracle.default_threads()
+        done, c0 = 0, time.perf_counter()
+        while True:
+            oracle.interdro_loss(hc, hr, ht, oracle.Params(kappa=1.0), *lam, threads=threads)
+            done += rows
+            dt = time.perf_counter() - c0
+            if dt > 10.0:
+                break
+        result["cpu_baseline"] = {"value": done / dt, "unit": "positions/s", "cores": threads, "kind": "oracle",
+                                  "sample": f"the first {rows} positions, repeated for {dt:.1f} s"}
+    print(json.dumps(result))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -149,6 +220,8 @@ def main() -> int:
     ap.add_argument("--heads", type=int, default=0,
                     help="H > 0: time ciar_quantify_multihead over H synthetic heads instead (not the headline)")
     ap.add_argument("--strategy", choices=("ensemble", "voting"), default="ensemble")
+    ap.add_argument("--interdro", action="store_true",
+                    help="time ciar_interdro_loss (forward value of the training loss) instead (not the headline)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of known size (reference for hardware counters)")
     args = ap.parse_args()
@@ -168,6 +241,8 @@ def main() -> int:
 
     if args.heads > 0:
         return bench_multihead(args, torch, ciar, wl, dev)
+    if args.interdro:
+        return bench_interdro(args, torch, ciar, wl, dev)
 
     spec = wl.SPECS[args.workload]
     w = wl.make(args.workload, device=dev)

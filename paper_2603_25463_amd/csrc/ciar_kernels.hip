@@ -1242,13 +1242,31 @@ __global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* _
         E::mask_tail(tw[j], base, V);
         if (rad) E::zero_tail(rw[j], base, V);
     }
+    // The radii are formed once (Softplus costs about as much as the rest of a pass) and kept as floats where
+    // the registers allow: up to 32 tokens per lane.  Beyond that they are recomputed in every pass.
+    constexpr bool CACHE_R = NVEC * EPV <= 32;
+    float rc[CACHE_R ? NVEC * EPV : 1];
+    if constexpr (CACHE_R) {
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) {
+            float rv[EPV];
+            if (rad) E::unpack(rw[j], rv);
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) rc[j * EPV + k] = rad ? radius_r(rv[k], kap, rmax) : r0;
+        }
+    }
     // element k of vector j: centre logit, radius, cloud logit
     auto element = [&](int j, int k, float& c, float& r, float& t) {
         float cv[EPV], tv[EPV], rv[EPV];
         E::unpack(cw[j], cv);
         E::unpack(tw[j], tv);
-        c = cv[k]; t = tv[k]; r = r0;
-        if (rad) { E::unpack(rw[j], rv); r = radius_r(rv[k], kap, rmax); }
+        c = cv[k]; t = tv[k];
+        if constexpr (CACHE_R) {
+            r = rc[j * EPV + k];
+        } else {
+            r = r0;
+            if (rad) { E::unpack(rw[j], rv); r = radius_r(rv[k], kap, rmax); }
+        }
     };
     // The three passes recompute the radius and the sums c +- r from the rows as loaded.  Passing the row
     // registers through an empty asm before each pass keeps the optimiser from carrying every per-token
@@ -1257,7 +1275,7 @@ __global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* _
 #pragma unroll
         for (int j = 0; j < NVEC; ++j) {
             asm volatile("" : "+v"(cw[j]), "+v"(tw[j]));
-            if (rad) asm volatile("" : "+v"(rw[j]));
+            if (!CACHE_R && rad) asm volatile("" : "+v"(rw[j]));
         }
     };
     auto block_max4 = [&](float (&m)[4]) {
