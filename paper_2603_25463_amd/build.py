@@ -3,12 +3,13 @@ from __future__ import annotations
 
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libciar.so")
-SOURCES = ["ciar_kernels.hip", "ciar_api.cpp"]
-HEADERS = ["ciar_internal.h", os.path.join("..", "..", "include", "ciar.h")]
+SOURCES = ["ciar_stream.hip", "ciar_finish.hip", "ciar_heads.hip", "ciar_loss.hip", "ciar_aux.hip", "ciar_api.cpp"]
+HEADERS = ["ciar_internal.h", "ciar_device.h", os.path.join("..", "..", "include", "ciar.h")]
 
 # Packed-FP32 instructions are switched off for every device compile of this library.
 HIPCC_FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
@@ -29,15 +30,17 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if not force and not stale():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    objs = []
-    for src in SOURCES:
+    def compile_one(src: str) -> str:
         obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
         cmd = [hipcc, *HIPCC_FLAGS, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd))
         subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL if not verbose else None,
                        stderr=subprocess.PIPE if not verbose else None)
-        objs.append(obj)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1, 8)) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
     cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs]
     if verbose:
         print(" ".join(cmd))

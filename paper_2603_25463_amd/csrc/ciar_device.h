@@ -1,0 +1,324 @@
+// Device-side helpers shared by the gfx950 kernels of the library: element types, exact-by-construction
+// exponentials, wave reductions, the per-token InterFuse arithmetic and the per-row finishing formulas.
+// Internal; included by the .hip files only.
+#pragma once
+
+#include "ciar_internal.h"
+
+#include <limits.h>
+#include <math.h>
+
+namespace ciar {
+namespace {
+
+
+// log2(e) split so that the low part is positive: x * hi + x * lo stays -inf for x = -inf.
+constexpr float  kLog2eHi = 1.44269490242004394531f;   // largest float below log2(e)
+constexpr float  kLog2eLo = 1.384689195e-7f;           // log2(e) - kLog2eHi
+constexpr double kLn2 = 0.69314718055994530942;
+
+__device__ __forceinline__ float bits_f(uint32_t u) { return __uint_as_float(u); }
+
+// 16 bytes as loaded: a native vector type, so it can be read through an address-space pointer.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+using gbytes = const __attribute__((address_space(1))) char*;
+using gvec = const __attribute__((address_space(1))) u32x4*;
+
+// 2^(x log2(e) - n) for an integer-valued reference n.  x * hi - n is exact inside the FMA and is
+// rounded at the magnitude of the (small) result; the low part of log2(e) is added by a second FMA.
+__device__ __forceinline__ float exp2_ref(float x, float n)
+{
+    return __builtin_amdgcn_exp2f(fmaf(x, kLog2eLo, fmaf(x, kLog2eHi, -n)));
+}
+
+// Integer reference for a set of logits whose maximum is m: the next integer above m * log2(e), so
+// every 2^(x log2e - n) is <= 1 (up to rounding).  -inf (nothing but masked tokens) maps to -inf.
+__device__ __forceinline__ float ref_of(float m) { return ceilf(m * 1.44269504f); }
+
+// 2^k as a double for an integer-valued float difference k <= 0 (clamped: below 2^-1000 it is 0 anyway)
+__device__ __forceinline__ double pow2_of(float k) { return ldexp(1.0, (int)fmaxf(k, -1000.f)); }
+
+template <typename T> struct Elt;
+template <> struct Elt<float> {
+    static constexpr int kPerVec = 4;
+    static constexpr uint32_t kNegInfWord = 0xff800000u;
+    __device__ static __forceinline__ void unpack(const u32x4& r, float* o)
+    {
+        o[0] = bits_f(r.x); o[1] = bits_f(r.y); o[2] = bits_f(r.z); o[3] = bits_f(r.w);
+    }
+    // Replace elements with index >= V of a vector that starts at element `base` by -inf.
+    __device__ static __forceinline__ void mask_tail(u32x4& r, int base, int V)
+    {
+        if (base + 0 >= V) r.x = kNegInfWord;
+        if (base + 1 >= V) r.y = kNegInfWord;
+        if (base + 2 >= V) r.z = kNegInfWord;
+        if (base + 3 >= V) r.w = kNegInfWord;
+    }
+    // ... by zero.
+    __device__ static __forceinline__ void zero_tail(u32x4& r, int base, int V)
+    {
+        if (base + 0 >= V) r.x = 0u;
+        if (base + 1 >= V) r.y = 0u;
+        if (base + 2 >= V) r.z = 0u;
+        if (base + 3 >= V) r.w = 0u;
+    }
+};
+struct bf16_t { uint16_t bits; };
+template <> struct Elt<bf16_t> {
+    static constexpr int kPerVec = 8;
+    static constexpr uint32_t kNegInfWord = 0xff80ff80u;
+    __device__ static __forceinline__ void unpack(const u32x4& r, float* o)
+    {
+        o[0] = bits_f(r.x << 16); o[1] = bits_f(r.x & 0xffff0000u);
+        o[2] = bits_f(r.y << 16); o[3] = bits_f(r.y & 0xffff0000u);
+        o[4] = bits_f(r.z << 16); o[5] = bits_f(r.z & 0xffff0000u);
+        o[6] = bits_f(r.w << 16); o[7] = bits_f(r.w & 0xffff0000u);
+    }
+    __device__ static __forceinline__ uint32_t mask_word(uint32_t w, int base, int V)
+    {
+        if (base >= V) return kNegInfWord;
+        if (base + 1 >= V) return (w & 0x0000ffffu) | 0xff800000u;
+        return w;
+    }
+    __device__ static __forceinline__ void mask_tail(u32x4& r, int base, int V)
+    {
+        r.x = mask_word(r.x, base + 0, V); r.y = mask_word(r.y, base + 2, V);
+        r.z = mask_word(r.z, base + 4, V); r.w = mask_word(r.w, base + 6, V);
+    }
+    __device__ static __forceinline__ uint32_t zero_word(uint32_t w, int base, int V)
+    {
+        return w & ((base < V ? 0x0000ffffu : 0u) | (base + 1 < V ? 0xffff0000u : 0u));
+    }
+    __device__ static __forceinline__ void zero_tail(u32x4& r, int base, int V)
+    {
+        r.x = zero_word(r.x, base + 0, V); r.y = zero_word(r.y, base + 2, V);
+        r.z = zero_word(r.z, base + 4, V); r.w = zero_word(r.w, base + 6, V);
+    }
+};
+
+template <typename T>
+__device__ __forceinline__ float load_logit(const T* row, int i)
+{
+    if constexpr (sizeof(T) == 4) return reinterpret_cast<const float*>(row)[i];
+    else return bits_f((uint32_t)reinterpret_cast<const uint16_t*>(row)[i] << 16);
+}
+
+// ---- wave reductions (fixed order: deterministic) ----------------------------------------------
+//
+// DPP row shifts and row broadcasts: they run on the vector ALU at full rate, whereas a shuffle
+// (ds_bpermute) goes through the LDS crossbar and costs ~5x more per step.
+// Pattern (wave64 = 4 rows of 16 lanes): row_shr 1, 2, 4, 8 leave each row's inclusive prefix in its
+// lanes; row_bcast:15 adds a row's total into the next row (rows 1 and 3), row_bcast:31 adds lane 31
+// into rows 2 and 3; every lane then holds its inclusive prefix over the wave and lane 63 the total,
+// which readlane hands to every lane.
+
+constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118;
+constexpr int kRowBcast15 = 0x142, kRowBcast31 = 0x143;
+
+// value of the lane selected by CTRL, or `fill` where the selection is out of range / masked off
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_or(int fill, int v)
+{
+    return __builtin_amdgcn_update_dpp(fill, v, CTRL, ROW_MASK, 0xf, false);
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_add(double v)
+{
+    const int lo = dpp_or<CTRL, ROW_MASK>(0, __double2loint(v));
+    const int hi = dpp_or<CTRL, ROW_MASK>(0, __double2hiint(v));
+    return v + __hiloint2double(hi, lo);           // lanes without a source add +0.0
+}
+
+// inclusive prefix sum over the 64 lanes
+__device__ __forceinline__ double wave_scan(double v)
+{
+    v = dpp_add<kRowShr1, 0xf>(v);
+    v = dpp_add<kRowShr2, 0xf>(v);
+    v = dpp_add<kRowShr4, 0xf>(v);
+    v = dpp_add<kRowShr8, 0xf>(v);
+    v = dpp_add<kRowBcast15, 0xa>(v);
+    v = dpp_add<kRowBcast31, 0xc>(v);
+    return v;
+}
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+    v = wave_scan(v);
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
+    return __hiloint2double(hi, lo);
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_max(float v)
+{
+    // lanes without a source get their own value back: max(v, v) = v
+    return fmaxf(v, __int_as_float(dpp_or<CTRL, ROW_MASK>(__float_as_int(v), __float_as_int(v))));
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+    v = dpp_max<kRowShr1, 0xf>(v);
+    v = dpp_max<kRowShr2, 0xf>(v);
+    v = dpp_max<kRowShr4, 0xf>(v);
+    v = dpp_max<kRowShr8, 0xf>(v);
+    v = dpp_max<kRowBcast15, 0xa>(v);
+    v = dpp_max<kRowBcast31, 0xc>(v);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+__device__ __forceinline__ int wave_min_i(int v)
+{
+    v = min(v, dpp_or<kRowShr1, 0xf>(v, v));
+    v = min(v, dpp_or<kRowShr2, 0xf>(v, v));
+    v = min(v, dpp_or<kRowShr4, 0xf>(v, v));
+    v = min(v, dpp_or<kRowShr8, 0xf>(v, v));
+    v = min(v, dpp_or<kRowBcast15, 0xa>(v, v));
+    v = min(v, dpp_or<kRowBcast31, 0xc>(v, v));
+    return __builtin_amdgcn_readlane(v, 63);
+}
+
+__device__ __forceinline__ int wave_max_i(int v)
+{
+    v = max(v, dpp_or<kRowShr1, 0xf>(v, v));
+    v = max(v, dpp_or<kRowShr2, 0xf>(v, v));
+    v = max(v, dpp_or<kRowShr4, 0xf>(v, v));
+    v = max(v, dpp_or<kRowShr8, 0xf>(v, v));
+    v = max(v, dpp_or<kRowBcast15, 0xa>(v, v));
+    v = max(v, dpp_or<kRowBcast31, 0xc>(v, v));
+    return __builtin_amdgcn_readlane(v, 63);
+}
+
+// ---- per-token InterFuse arithmetic, shared by the streaming kernel and the dense export ------------
+
+// Constants of one row for a scalar radius.  Units: e_i as held by the lane, S = sum e_i in the same units.
+struct FuseRow {
+    float cu;            // (a-1)/S:  du = 1 + (a-1) x = 1 + cu e
+    float nih, nil;      // -1/S split in two floats:  1 - x = 1 + nih e + nil e  (exact to ~1e-15)
+    float b, omb;        // b and 1-b:  dl = 1 - (1-b) x = b + (1-b)(1-x), free of cancellation as x -> 1
+};
+
+__device__ __forceinline__ FuseRow fuse_row(double S, double a, double b)
+{
+    FuseRow r;
+    const double invS = 1.0 / S;
+    r.cu = (float)((a - 1.0) * invS);
+    r.nih = (float)(-invS);
+    r.nil = (float)(-invS - (double)r.nih);
+    r.b = (float)b;
+    r.omb = (float)(1.0 - b);
+    return r;
+}
+
+// gl = e du / (du dl) and gw = e (1-x) / (du dl):  p^l = (b/S) gl,  w = p^u - p^l = ((a-b)/S) gw.
+// SPLIT = form 1 - x with the two-float 1/S.  It matters only when some x is close to 1 (the relative
+// error of 1 - x is 6e-8 x / (1 - x) without it); rows whose largest probability is at most 1/2 skip it.
+template <bool SPLIT = true>
+__device__ __forceinline__ void fuse_token(float e, const FuseRow& r, float& gl, float& gw)
+{
+    const float om = SPLIT ? fmaf(e, r.nil, fmaf(e, r.nih, 1.0f)) : fmaf(e, r.nih, 1.0f);   // 1 - x
+    const float du = fmaf(e, r.cu, 1.0f);
+    const float dl = fmaf(om, r.omb, r.b);
+    const float g = e * __builtin_amdgcn_rcpf(du * dl);
+    gl = g * du;
+    gw = g * om;
+}
+
+// Tensor-radius mode (Sec. 3.2.3, the Interval Head: r = Softplus(raw)): a = e^r, b = e^-r for
+// r = min(kappa Softplus(raw), rmax).  Softplus(raw) = max(raw, 0) + ln(1 + t), t = e^-|raw|;
+// ln(1 + t) = ln(u) t / (u - 1) with u = fl(1 + t): u - 1 is exact, so the rounding of 1 + t cancels in
+// the ratio and small radii (raw << 0) keep their relative accuracy.
+__device__ __forceinline__ void radius_ab(float raw, float kappa, float rmax, float& a, float& b)
+{
+    const float t = __builtin_amdgcn_exp2f(-fabsf(raw) * 1.44269504f);
+    const float u = 1.0f + t;
+    const float d = u - 1.0f;
+    const float lg = d == 0.f ? t : (__builtin_amdgcn_logf(u) * 0.693147181f) * (t * __builtin_amdgcn_rcpf(d));
+    const float r = fminf(kappa * (fmaxf(raw, 0.f) + lg), rmax);
+    a = __builtin_amdgcn_exp2f(r * 1.44269504f);
+    b = __builtin_amdgcn_rcpf(a);
+}
+
+// The same radius in fp64 (one token per row: the reported token's interval).
+__device__ __forceinline__ double radius_of(double raw, double kappa, double rmax)
+{
+    const double sp = raw > 0.0 ? raw + log1p(exp(-raw)) : log1p(exp(raw));
+    return fmin(kappa * sp, rmax);
+}
+
+// Tensor-radius token: pl = p^l_i S and w = (p^u_i - p^l_i) S in the units of e.
+__device__ __forceinline__ void fuse_token_rad(float e, float raw, const FuseRow& r, float kappa, float rmax,
+                                               float& pl, float& w)
+{
+    float a, b;
+    radius_ab(raw, kappa, rmax, a, b);
+    const float om = fmaf(e, r.nil, fmaf(e, r.nih, 1.0f));        // 1 - x
+    const float x = -e * r.nih;
+    const float du = fmaf(a - 1.0f, x, 1.0f);
+    const float dl = fmaf(om, 1.0f - b, b);
+    const float g = e * __builtin_amdgcn_rcpf(du * dl);
+    pl = b * (g * du);
+    w = (a - b) * (g * om);
+}
+
+// Per-row scalars of the quantifier from the five sums (fp64, one lane).
+struct RowScore { double alpha_l, alpha_u, omega, sigma, score; };
+
+__device__ __forceinline__ RowScore finish_score(const double* s, double S, bool capless, const RowArgs& A)
+{
+    // s = { sum gl, sum gw, sum gl^2, sum gw^2, sum gl gw } over the V tokens of the row, with
+    // p^l_i = Bc gl_i and p^u_i - p^l_i = Wc gw_i (tensor-radius mode: the per-token factors are already
+    // inside gl and gw);
+    // capless = the caps are known to be inactive and only sum gw, sum gw^2 were accumulated
+    const double V = (double)A.V;
+    const double Bc = (A.radius ? 1.0 : A.b) / S, Wc = (A.radius ? 1.0 : A.a - A.b) / S;
+    const double Sl = Bc * s[0], Su = Sl + Wc * s[1];
+    RowScore o;
+    o.alpha_l = 1.0; o.alpha_u = 1.0;
+    if (A.normalize && !capless) {
+        o.alpha_l = fmin(1.0, A.cap_lo / Sl);
+        o.alpha_u = fmax(1.0, A.cap_hi / Su);
+    }
+    // delta_i = alpha_u p^u_i - alpha_l p^l_i = alpha_u w_i + (alpha_u - alpha_l) p^l_i = cw gw_i + cl gl_i:
+    // both coefficients are >= 0, so Omega and the second moment are sums of non-negative terms.
+    const double cw = o.alpha_u * Wc, cl = (o.alpha_u - o.alpha_l) * Bc;
+    o.omega = cw * s[1] + cl * s[0];
+    const double Q = cw * cw * s[3] + 2.0 * cw * cl * s[4] + cl * cl * s[2];
+    // fp64 sums: the subtraction of the squared mean costs at most ~1/CV^2 of 1e-16
+    const double var = fmax(0.0, Q - o.omega * o.omega / V) / V;
+    o.sigma = sqrt(var);
+    o.score = o.omega * o.sigma;
+    return o;
+}
+
+// r = min(kappa Softplus(raw), rmax) in fp32 (see radius_ab for the ln(1 + t) form).
+__device__ __forceinline__ float radius_r(float raw, float kappa, float rmax)
+{
+    const float t = __builtin_amdgcn_exp2f(-fabsf(raw) * 1.44269504f);
+    const float u = 1.0f + t;
+    const float d = u - 1.0f;
+    const float lg = d == 0.f ? t : (__builtin_amdgcn_logf(u) * 0.693147181f) * (t * __builtin_amdgcn_rcpf(d));
+    return fminf(kappa * (fmaxf(raw, 0.f) + lg), rmax);
+}
+
+// Vocabularies of at most this many tokens take fp64 token arithmetic (see fuse_sums_tiny, dro_row_tiny_kernel).
+constexpr int kTinyVocab = 64;
+
+// Compute units of the current device (asked once per device, then cached).
+inline int compute_units()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+    static int cache[64] = {0};
+    if (cache[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+            cus = 256;
+        cache[dev] = cus;
+    }
+    return cache[dev];
+}
+
+}  // namespace
+}  // namespace ciar

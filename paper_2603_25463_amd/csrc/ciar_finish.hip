@@ -1,0 +1,373 @@
+// gfx950 kernels of the finishing pass: per-row scalars (score, flag, reported interval, accept test), the
+// residual draw of rejected rows, the window outputs, and the arg-max index for tensor-radius calls
+// without drafted ids.  (Eq. uncertainty_score; Algorithm 1's threshold and verification steps.)
+#include "ciar_device.h"
+
+namespace ciar {
+namespace {
+
+// ---- the finishing kernels ----------------------------------------------------------------------------------------
+
+// Window w = rows [wK, min((w+1)K, N)): accepted prefix length and the draw of the first rejected row
+// (Algorithm 1: the verified part of a drafted window and the token that replaces the first rejection).
+__device__ __forceinline__ void window_of(const uint8_t* accept, const int32_t* row_id, int64_t N, int32_t K,
+                                          int64_t w, int32_t* accept_len, int32_t* resampled_id)
+{
+    const int64_t lo = w * K;
+    const int64_t hi = (lo + K < N) ? lo + K : N;
+    int64_t n = 0;
+    while (lo + n < hi && accept[lo + n]) ++n;
+    if (accept_len) accept_len[w] = (int32_t)n;
+    if (resampled_id)
+        resampled_id[w] = (lo + n < hi) ? row_id[lo + n] : -1;
+}
+
+// One thread per row: RowStats -> the row's outputs, in fp64 (Eq. uncertainty_score; Algorithm 1's threshold
+// and verification steps).  Rejected rows are appended to a list for the residual draw.
+// A workgroup covers `rows_per_block` consecutive rows.  When the window outputs are asked for, that is a
+// multiple of the window length K, so every window lies inside one workgroup: its leader thread counts the
+// accepted prefix from the accept bits the workgroup shares through LDS, and writes -1 for a window
+// without a rejection (the draw of a window with one is written by the residual-draw kernel).
+template <typename T>
+__global__ __launch_bounds__(256) void rowfinish_kernel(const RowArgs A, const int do_q, const int do_v,
+                                                        const int rows_per_block, const int K,
+                                                        int32_t* __restrict__ accept_len,
+                                                        int32_t* __restrict__ resampled_id)
+{
+    __shared__ uint8_t sm_acc[256];
+    const int tid = threadIdx.x;
+    const int64_t row = (int64_t)blockIdx.x * rows_per_block + tid;
+    const bool live = tid < rows_per_block && row < A.N;
+    const bool windows = accept_len || resampled_id;               // uniform over the grid
+    int rej = 0;
+    if (live) {
+        const int V = A.V;
+        const T* crow = static_cast<const T*>(A.draft) + row * A.stride;
+        const RowStats st = A.stats[row];
+        const double S = st.S;
+        const float n = st.n;
+
+        int xid = -1;
+        float cx = st.mc;                                          // no ids: the arg-max token is reported
+        if (A.ids) {
+            xid = A.ids[row];
+            xid = xid < 0 ? 0 : (xid >= V ? V - 1 : xid);
+            cx = load_logit(crow, xid);
+        }
+        if (do_q) {
+            const RowScore rs = finish_score(st.q, S, st.capless != 0.f, A);
+            if (A.omega) A.omega[row] = (float)rs.omega;
+            if (A.sigma) A.sigma[row] = (float)rs.sigma;
+            if (A.score) A.score[row] = (float)rs.score;
+            if (A.flags) A.flags[row] = (uint8_t)(rs.score > A.tau);
+            if (A.p_lo || A.p_mid || A.p_hi) {
+                const double x = exp((double)cx - (double)n * kLn2) / S;
+                double a = A.a, b = A.b;
+                if (A.radius) {
+                    // the reported token's own radius (the launcher supplies ids in this mode)
+                    const T* rrow = static_cast<const T*>(A.radius) + row * A.stride;
+                    const double r = radius_of((double)load_logit(rrow, xid < 0 ? 0 : xid), A.kappa, A.rmax);
+                    a = exp(r); b = exp(-r);
+                }
+                if (A.p_mid) A.p_mid[row] = (float)x;
+                if (A.p_lo) A.p_lo[row] = (float)(rs.alpha_l * b * x / (1.0 + (b - 1.0) * x));
+                if (A.p_hi) A.p_hi[row] = (float)(rs.alpha_u * a * x / (1.0 + (a - 1.0) * x));
+            }
+        }
+        if (do_v) {
+            // ln p_x = cx - n ln2 - ln S, ln q_x = tx - nt ln2 - ln Z;  accept iff ln u < min(0, ln q_x - ln p_x)
+            const T* trow = static_cast<const T*>(A.target) + row * A.stride;
+            const float tx = load_logit(trow, xid);
+            const double lp = ((double)cx - (double)n * kLn2) - log(S);
+            const double lq = ((double)tx - (double)st.nt * kLn2) - log(st.Z);
+            const double lnu = log((double)A.u_accept[row]);       // log(0) = -inf: always accepted
+            rej = !(lnu < fmin(0.0, lq - lp));
+            if (A.accept) A.accept[row] = (uint8_t)(!rej);
+            if (A.row_id && !rej) A.row_id[row] = -1;
+        }
+    }
+    bool first = false;                                            // first rejection of its window
+    if (windows) {
+        sm_acc[tid] = (uint8_t)(!rej);
+        __syncthreads();
+        const int lead = tid - tid % K;                            // block starts are multiples of K
+        if (live && tid == lead) {
+            const int64_t left = A.N - row;
+            const int len = (int)(left < K ? left : K);
+            int m = 0;
+            while (m < len && sm_acc[tid + m]) ++m;
+            const int64_t w = row / K;
+            if (accept_len) accept_len[w] = m;
+            if (resampled_id && m == len) resampled_id[w] = -1;
+        }
+        if (rej) {
+            first = true;
+            for (int i = lead; i < tid; ++i) first = first && sm_acc[i] != 0;
+        }
+    }
+    if (rej && A.row_id) {
+        // list entry: the row, bit-complemented when the row's draw is also its window's
+        const int slot = atomicAdd(A.reject_count, 1);
+        if (slot < A.N) A.reject_list[slot] = first ? ~(int32_t)row : (int32_t)row;   // (one entry per row at most)
+    }
+}
+
+// Residual draw of the rejected rows: res_i = max(0, q_i - p_i), inverse CDF in token order.  Workgroups walk
+// over the list of rejected rows; both rows are fetched again (they were read moments ago: mostly from
+// cache), four vectors of each row per lane in flight at once.  A row's draw is a chain of dependent
+// steps (list entry, statistics, loads, totals, crossing chunk, scan), so what matters is how many rows
+// a compute unit has in flight: 256-lane workgroups, several per compute unit, unless the launch is so
+// small that most compute units would see no rejected row at all (then 1024 lanes work on each row).
+template <typename T, int THREADS>
+__global__ __launch_bounds__(THREADS) void resample_kernel(const RowArgs A, const int K, int32_t* __restrict__ resampled_id)
+{
+    using E = Elt<T>;
+    constexpr int EPV = E::kPerVec;
+    constexpr int NW = THREADS / 64;
+    constexpr int CHUNK = THREADS * EPV;
+    constexpr int MAXCH = 8192 / THREADS;           // chunks of CHUNK tokens a row can have (supported vocabularies)
+    constexpr int UB = 4;                           // chunks of each row in flight per lane
+
+    __shared__ double sm_e[NW * MAXCH + NW];
+    __shared__ int    sm_i[NW * 2];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int V = A.V;
+    const int last_vec = (V + EPV - 1) / EPV - 1;
+    const int nch = (V + CHUNK - 1) / CHUNK;        // <= MAXCH
+    int count = *A.reject_count;
+    if (count > A.N) count = (int)A.N;
+
+    for (int item = blockIdx.x; item < count; item += gridDim.x) {
+        const int32_t entry = A.reject_list[item];
+        const int64_t row = entry < 0 ? ~entry : entry;
+        const T* crow = static_cast<const T*>(A.draft) + row * A.stride;
+        const T* trow = static_cast<const T*>(A.target) + row * A.stride;
+        const RowStats st = A.stats[row];
+        const double invS = 1.0 / st.S, invZ = 1.0 / st.Z;
+        const float n = st.n, nt = st.nt;
+        const double u_res = (double)A.u_resample[row];
+
+        auto load_vec = [&](const T* base, int j) -> u32x4 {
+            const uint32_t off = (uint32_t)min(j * THREADS + tid, last_vec) * 16u;
+            return *(gvec)((gbytes)base + off);
+        };
+        // residuals of one 16-byte vector of each row; tokens past the end of the row are masked to -inf
+        auto residuals = [&](u32x4 cr, u32x4 tr, int j, float (&r)[EPV]) {
+            E::mask_tail(cr, (j * THREADS + tid) * EPV, V);
+            E::mask_tail(tr, (j * THREADS + tid) * EPV, V);
+            float cv[EPV], tv[EPV];
+            E::unpack(cr, cv);
+            E::unpack(tr, tv);
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) {
+                const double q = (double)exp2_ref(tv[k], nt) * invZ;
+                const double p = (double)exp2_ref(cv[k], n) * invS;
+                r[k] = (float)fmax(q - p, 0.0);
+            }
+        };
+        // E1: workgroup totals of the residual over each chunk of CHUNK tokens, UB chunks of each row in flight
+        for (int j0 = 0; j0 < nch; j0 += UB) {
+            u32x4 cb[UB], tb[UB];
+#pragma unroll
+            for (int u = 0; u < UB; ++u) { cb[u] = load_vec(crow, j0 + u); tb[u] = load_vec(trow, j0 + u); }
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                if (j0 + u < nch) {                                // uniform
+                    float r[EPV];
+                    residuals(cb[u], tb[u], j0 + u, r);
+                    float s = 0.f;
+#pragma unroll
+                    for (int k = 0; k < EPV; ++k) s += r[k];
+                    const double ws = wave_sum((double)s);
+                    if (lane == 0) sm_e[wave * MAXCH + j0 + u] = ws;
+                }
+            }
+        }
+        __syncthreads();
+        double R = 0.0;
+        for (int j = 0; j < nch; ++j) {
+#pragma unroll
+            for (int w = 0; w < NW; ++w) R += sm_e[w * MAXCH + j];
+        }
+        int cand = INT_MAX, lastpos = -1;
+        if (R > 0.0) {
+            // chunk that holds the crossing of u * R (token order = chunk order, then lane order)
+            const double thr = u_res * R;
+            int jstar = -1, jlast = 0;
+            double before = 0.0, run = 0.0;
+            for (int j = 0; j < nch; ++j) {
+                double tot = 0.0;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) tot += sm_e[w * MAXCH + j];
+                if (jstar < 0 && run + tot > thr) { jstar = j; before = run; }
+                if (tot > 0.0) jlast = j;
+                if (jstar < 0) run += tot;
+            }
+            if (jstar < 0) { jstar = jlast; before = run; }        // unreachable for u < 1; keeps the draw valid
+            // E2: the lane's residuals inside that chunk, fetched again (cache) and recomputed exactly as in E1
+            float r[EPV];
+            residuals(load_vec(crow, jstar), load_vec(trow, jstar), jstar, r);
+            float s = 0.f;
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) s += r[k];
+            const double incl = wave_scan((double)s);
+            if (lane == 63) sm_e[NW * MAXCH + wave] = incl;
+            __syncthreads();
+            double cum = before + (incl - (double)s);
+            for (int w = 0; w < wave; ++w) cum += sm_e[NW * MAXCH + w];
+            // smallest token of the chunk whose inclusive running sum exceeds u * R; tokens without
+            // residual mass cannot be drawn; lastpos covers a crossing lost to rounding at the chunk end
+            const int base = (jstar * THREADS + tid) * EPV;
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) {
+                cum += (double)r[k];
+                if (r[k] > 0.f) {
+                    lastpos = base + k;
+                    if (cum > thr && cand == INT_MAX) cand = base + k;
+                }
+            }
+        } else {
+            // every residual rounded to zero (q == p to working precision): the draw degenerates to the
+            // lowest-index arg-max of q; this path is practically never taken
+            float mt = -INFINITY;
+            for (int i = tid; i < V; i += THREADS) mt = fmaxf(mt, load_logit(trow, i));
+            mt = wave_max(mt);
+            if (lane == 0) sm_e[NW * MAXCH + wave] = (double)mt;
+            __syncthreads();
+#pragma unroll
+            for (int w = 0; w < NW; ++w) mt = fmaxf(mt, (float)sm_e[NW * MAXCH + w]);
+            for (int i = tid; i < V; i += THREADS)
+                if (load_logit(trow, i) == mt) { cand = i; break; }
+        }
+        cand = wave_min_i(cand);
+        lastpos = wave_max_i(lastpos);
+        if (lane == 0) { sm_i[wave * 2] = cand; sm_i[wave * 2 + 1] = lastpos; }
+        __syncthreads();
+        if (tid == 0) {
+            int c0 = sm_i[0], l0 = sm_i[1];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) { c0 = min(c0, sm_i[w * 2]); l0 = max(l0, sm_i[w * 2 + 1]); }
+            int id = (c0 != INT_MAX) ? c0 : l0;
+            if (id < 0) id = 0;
+            A.row_id[row] = id;
+            if (entry < 0 && resampled_id) resampled_id[row / K] = id;             // the window's draw is its first rejected row's
+        }
+        __syncthreads();                                           // the LDS slots are reused by the next row
+    }
+}
+
+// ---- arg-max token of every row (tensor-radius calls without drafted ids) ----------------------------------
+
+// One workgroup per row: the lowest index that holds the row's largest centre logit.  Only the
+// tensor-radius mode needs the index itself (to pick that token's radius); the scalar mode reports the
+// arg-max token from the row maximum alone.
+template <typename T>
+__global__ __launch_bounds__(256) void argmax_kernel(const RowArgs A, int32_t* __restrict__ out)
+{
+    __shared__ float sm_m[4];
+    __shared__ int sm_i[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row = blockIdx.x;
+    const T* c = static_cast<const T*>(A.draft) + row * A.stride;
+    float m = -INFINITY;
+    int idx = INT_MAX;
+    for (int i = tid; i < A.V; i += 256) {
+        const float v = load_logit(c, i);
+        if (v > m || idx == INT_MAX) { m = v; idx = i; }           // ascending i: the first of equal values stays
+    }
+    const float wm = wave_max(m);
+    const int wi = wave_min_i(m == wm ? idx : INT_MAX);
+    if (lane == 0) { sm_m[wave] = wm; sm_i[wave] = wi; }
+    __syncthreads();
+    if (tid == 0) {
+        const float rm = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));
+        int best = INT_MAX;
+        for (int w = 0; w < 4; ++w) if (sm_m[w] == rm && sm_i[w] < best) best = sm_i[w];
+        out[row] = best == INT_MAX ? 0 : best;
+    }
+}
+
+// ---- window epilogue: one thread per window of K rows -------------------------------------------------
+
+__global__ __launch_bounds__(256) void window_kernel(const uint8_t* __restrict__ accept,
+                                                     const int32_t* __restrict__ row_id, int64_t N, int32_t K,
+                                                     int32_t* __restrict__ accept_len,
+                                                     int32_t* __restrict__ resampled_id)
+{
+    const int64_t W = (N + K - 1) / K;
+    const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (w >= W) return;
+    window_of(accept, row_id, N, K, w, accept_len, resampled_id);
+}
+
+}  // namespace
+hipError_t launch_windows(const uint8_t* accept, const int32_t* row_id, int64_t N, int32_t K,
+                          int32_t* accept_len, int32_t* resampled_id, hipStream_t stream);
+namespace {
+
+template <typename T>
+hipError_t launch_finish_typed(Mode mode, const RowArgs& a, int32_t K, int32_t* accept_len, int32_t* resampled_id,
+                               hipStream_t s)
+{
+    // Windows of up to 256 rows are finished inside the two kernels; longer ones by the window kernel.
+    const bool want_windows = mode != Mode::Quantify && (accept_len || resampled_id);
+    const bool inline_windows = want_windows && K <= 256 && (a.row_id || !resampled_id);
+    const int rows_per_block = inline_windows ? (256 / K) * K : 256;
+    const unsigned blocks = (unsigned)((a.N + rows_per_block - 1) / rows_per_block);
+    hipLaunchKernelGGL(rowfinish_kernel<T>, dim3(blocks), dim3(256), 0, s, a, mode != Mode::Verify ? 1 : 0,
+                       mode != Mode::Quantify ? 1 : 0, rows_per_block, K, inline_windows ? accept_len : nullptr,
+                       inline_windows ? resampled_id : nullptr);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || mode == Mode::Quantify) return e;
+    if (a.row_id) {
+        const int64_t cus = compute_units();
+        if (a.N >= 4 * cus) {
+            // four 256-lane workgroups per compute unit walk over the rejected rows
+            hipLaunchKernelGGL((resample_kernel<T, 256>), dim3((unsigned)(4 * cus)), dim3(256), 0, s, a, K,
+                               inline_windows ? resampled_id : nullptr);
+        } else {
+            // very few rows (less than one rejected row per compute unit): 1024 lanes on each row
+            const unsigned grid = (unsigned)(a.N < cus ? a.N : cus);
+            hipLaunchKernelGGL((resample_kernel<T, 1024>), dim3(grid), dim3(1024), 0, s, a, K,
+                               inline_windows ? resampled_id : nullptr);
+        }
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (want_windows && !inline_windows)
+        return launch_windows(a.accept, a.row_id, a.N, K, accept_len, resampled_id, s);
+    return hipSuccess;
+}
+
+}  // namespace
+
+hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, int32_t K, int32_t* accept_len,
+                         int32_t* resampled_id, hipStream_t stream)
+{
+    if (args.N <= 0) return hipSuccess;
+    return dtype == 0 ? launch_finish_typed<float>(mode, args, K, accept_len, resampled_id, stream)
+                      : launch_finish_typed<bf16_t>(mode, args, K, accept_len, resampled_id, stream);
+}
+
+hipError_t launch_windows(const uint8_t* accept, const int32_t* row_id, int64_t N, int32_t K,
+                          int32_t* accept_len, int32_t* resampled_id, hipStream_t stream)
+{
+    if (N <= 0) return hipSuccess;
+    const int64_t W = (N + K - 1) / K;
+    const unsigned blocks = (unsigned)((W + 255) / 256);
+    hipLaunchKernelGGL(window_kernel, dim3(blocks), dim3(256), 0, stream, accept, row_id, N, K, accept_len,
+                       resampled_id);
+    return hipGetLastError();
+}
+
+hipError_t launch_argmax(int dtype, const RowArgs& args, int32_t* out, hipStream_t stream)
+{
+    if (args.N <= 0) return hipSuccess;
+    const dim3 grid((unsigned)args.N), block(256);
+    if (dtype == 0) hipLaunchKernelGGL(argmax_kernel<float>, grid, block, 0, stream, args, out);
+    else hipLaunchKernelGGL(argmax_kernel<bf16_t>, grid, block, 0, stream, args, out);
+    return hipGetLastError();
+}
+
+}  // namespace ciar

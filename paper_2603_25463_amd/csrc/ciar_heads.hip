@@ -1,0 +1,229 @@
+// gfx950 kernels for several Interval Heads (Sec. 4, ablation on the Inter-Head): the Ensemble sweep that
+// averages the heads' widths token by token, and the Voting majority.
+#include "ciar_device.h"
+
+namespace ciar {
+namespace {
+
+// ---- several heads (Sec. 4, ablation on the Inter-Head): Ensemble and Voting ------------------------------
+
+constexpr int kMaxHeads = 8;
+
+// Ensemble: the heads' curves are averaged token by token, so the widths of all heads of a token have to
+// meet: a second sweep over the H rows of a position, after the streaming kernel has left every head's
+// RowStats (partition sum, reference, interval sums -> that head's caps).  One workgroup per position;
+// per token and head the same arithmetic as the streaming kernel's interval pass.
+//   D_i = sum_h delta_{h,i},  Omega = sum_i D_i / H,  Sigma^2 = sum_i D_i^2 / (H^2 V) - (Omega / V)^2.
+template <typename T>
+__global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const int H, const int64_t head_stride)
+{
+    using E = Elt<T>;
+    constexpr int EPV = E::kPerVec;
+    __shared__ FuseRow sm_fr[kMaxHeads];
+    __shared__ float sm_n[kMaxHeads], sm_invS[kMaxHeads];
+    __shared__ double sm_cw[kMaxHeads], sm_cl[kMaxHeads], sm_S[kMaxHeads], sm_al[kMaxHeads], sm_au[kMaxHeads];
+    __shared__ double sm_red[2][4];
+    __shared__ float sm_pm[4];
+    __shared__ int sm_pi[4];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row = blockIdx.x;
+    const int V = A.V;
+    const bool rad = A.radius != nullptr;
+    const bool need_argmax = A.ids == nullptr && (A.p_lo || A.p_mid || A.p_hi);
+    const bool tiny = V <= 64;
+
+    if (tid < H) {
+        const RowStats st = A.stats[(int64_t)tid * A.N + row];
+        const RowScore rs = finish_score(st.q, st.S, st.capless != 0.f, A);
+        const double Bc = (rad ? 1.0 : A.b) / st.S, Wc = (rad ? 1.0 : A.a - A.b) / st.S;
+        sm_fr[tid] = fuse_row(st.S, A.a, A.b);
+        sm_n[tid] = st.n;
+        sm_cw[tid] = rs.alpha_u * Wc;
+        sm_cl[tid] = (rs.alpha_u - rs.alpha_l) * Bc;
+        sm_invS[tid] = (float)(1.0 / st.S);
+        sm_S[tid] = st.S; sm_al[tid] = rs.alpha_l; sm_au[tid] = rs.alpha_u;
+    }
+    __syncthreads();
+
+    const float kap = (float)A.kappa, rmax = (float)A.rmax;
+    const int nvec = (V + EPV - 1) / EPV;
+    double s1 = 0.0, s2 = 0.0;
+    float best = -INFINITY;
+    int best_i = INT_MAX;
+    if (tiny) {
+        // A handful of tokens (one vector per lane at most): widths are O(1) and Sigma can be an exact zero
+        // (two tokens), which fp32 token arithmetic cannot resolve to 1e-7; the few tokens are done in fp64.
+        if (tid < nvec) {
+            double D[EPV];
+            float pm[EPV];
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) { D[k] = 0.0; pm[k] = 0.f; }
+            for (int h = 0; h < H; ++h) {
+                const gvec c = (gvec)(gbytes)(static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride);
+                const gvec r = (gvec)(gbytes)(static_cast<const T*>(rad ? A.radius : A.draft) +
+                                              (int64_t)h * head_stride + row * A.stride);
+                const u32x4 cw4 = c[tid], rw4 = r[tid];
+                float cv[EPV], rv[EPV];
+                E::unpack(cw4, cv);
+                E::unpack(rw4, rv);
+                for (int k = 0; k < EPV; ++k) {
+                    if (tid * EPV + k < V) {
+                        const double x = exp((double)cv[k] - (double)sm_n[h] * kLn2) / sm_S[h];
+                        double a = A.a, b = A.b;
+                        if (rad) {
+                            const double rr = radius_of((double)rv[k], A.kappa, A.rmax);
+                            a = exp(rr); b = exp(-rr);
+                        }
+                        D[k] += sm_au[h] * a * x / (1.0 + (a - 1.0) * x) - sm_al[h] * b * x / (1.0 + (b - 1.0) * x);
+                        pm[k] += (float)x;
+                    }
+                }
+            }
+            for (int k = 0; k < EPV; ++k) {
+                const int tok = tid * EPV + k;
+                s1 += D[k];
+                s2 = fma(D[k], D[k], s2);
+                if (need_argmax && tok < V && pm[k] > best) { best = pm[k]; best_i = tok; }
+            }
+        }
+    }
+    constexpr int UB = 16 / EPV;                                   // vectors of a head in flight per lane
+    for (int v0 = tid; !tiny && v0 < nvec; v0 += 256 * UB) {
+        double D[UB][EPV];                                         // fp64 across heads
+        float pm[UB][EPV];
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) { D[u][k] = 0.0; pm[u][k] = 0.f; }
+        }
+        for (int h = 0; h < H; ++h) {
+            const gvec c = (gvec)(gbytes)(static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride);
+            const gvec r = (gvec)(gbytes)(static_cast<const T*>(rad ? A.radius : A.draft) + (int64_t)h * head_stride +
+                                          row * A.stride);
+            u32x4 cw4[UB], rw4[UB];
+#pragma unroll
+            for (int u = 0; u < UB; ++u) cw4[u] = c[min(v0 + u * 256, nvec - 1)];
+            if (rad) {
+#pragma unroll
+                for (int u = 0; u < UB; ++u) rw4[u] = r[min(v0 + u * 256, nvec - 1)];
+            }
+            const FuseRow fr = sm_fr[h];
+            const float n = sm_n[h], invS = sm_invS[h];
+            const double cw = sm_cw[h], cl = sm_cl[h];
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const int tok0 = (v0 + u * 256) * EPV;             // >= V for vectors past the row's end
+                float cv[EPV], rv[EPV];
+                E::unpack(cw4[u], cv);
+                if (rad) E::unpack(rw4[u], rv);
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) {
+                    if (tok0 + k < V) {
+                        const float e = exp2_ref(cv[k], n);
+                        float gl, gw;
+                        if (rad) fuse_token_rad(e, rv[k], fr, kap, rmax, gl, gw);
+                        else fuse_token(e, fr, gl, gw);
+                        D[u][k] = fma(cw, (double)gw, fma(cl, (double)gl, D[u][k]));
+                        pm[u][k] = fmaf(e, invS, pm[u][k]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) {
+                const int tok = (v0 + u * 256) * EPV + k;
+                const double d = D[u][k];                          // tokens past V contribute exactly 0
+                s1 += d;
+                s2 = fma(d, d, s2);
+                if (need_argmax && tok < V && pm[u][k] > best) { best = pm[u][k]; best_i = tok; }
+            }
+        }
+    }
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    if (lane == 0) { sm_red[0][wave] = s1; sm_red[1][wave] = s2; }
+    if (need_argmax) {
+        // each lane walked its tokens in ascending order, so it holds its lowest index of its maximum
+        const float wm = wave_max(best);
+        const int wi = wave_min_i(best == wm ? best_i : INT_MAX);
+        if (lane == 0) { sm_pm[wave] = wm; sm_pi[wave] = wi; }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        const double t1 = (sm_red[0][0] + sm_red[0][1]) + (sm_red[0][2] + sm_red[0][3]);
+        const double t2 = (sm_red[1][0] + sm_red[1][1]) + (sm_red[1][2] + sm_red[1][3]);
+        const double Hd = (double)H, Vd = (double)V;
+        const double omega = t1 / Hd;
+        const double var = fmax(0.0, t2 / (Hd * Hd) - omega * omega / Vd) / Vd;
+        const double sigma = sqrt(var), score = omega * sigma;
+        if (A.omega) A.omega[row] = (float)omega;
+        if (A.sigma) A.sigma[row] = (float)sigma;
+        if (A.score) A.score[row] = (float)score;
+        if (A.flags) A.flags[row] = (uint8_t)(score > A.tau);
+        if (A.p_lo || A.p_mid || A.p_hi) {
+            int xid;
+            if (A.ids) {
+                xid = A.ids[row];
+                xid = xid < 0 ? 0 : (xid >= V ? V - 1 : xid);
+            } else {
+                const float rm = fmaxf(fmaxf(sm_pm[0], sm_pm[1]), fmaxf(sm_pm[2], sm_pm[3]));
+                xid = INT_MAX;
+                for (int w = 0; w < 4; ++w) if (sm_pm[w] == rm && sm_pi[w] < xid) xid = sm_pi[w];
+                if (xid == INT_MAX) xid = 0;
+            }
+            double lo = 0.0, mid = 0.0, hi = 0.0;
+            for (int h = 0; h < H; ++h) {
+                const T* crow = static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride;
+                const double x = exp((double)load_logit(crow, xid) - (double)sm_n[h] * kLn2) / sm_S[h];
+                double a = A.a, b = A.b;
+                if (rad) {
+                    const T* rrow = static_cast<const T*>(A.radius) + (int64_t)h * head_stride + row * A.stride;
+                    const double r = radius_of((double)load_logit(rrow, xid), A.kappa, A.rmax);
+                    a = exp(r); b = exp(-r);
+                }
+                mid += x;
+                lo += sm_al[h] * b * x / (1.0 + (b - 1.0) * x);
+                hi += sm_au[h] * a * x / (1.0 + (a - 1.0) * x);
+            }
+            if (A.p_lo) A.p_lo[row] = (float)(lo / Hd);
+            if (A.p_mid) A.p_mid[row] = (float)(mid / Hd);
+            if (A.p_hi) A.p_hi[row] = (float)(hi / Hd);
+        }
+    }
+}
+
+// Voting: flags[row] = strict majority of head_flags[h][row].
+__global__ __launch_bounds__(256) void vote_kernel(const uint8_t* __restrict__ head_flags, int H, int64_t N,
+                                                   uint8_t* __restrict__ flags)
+{
+    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (row >= N) return;
+    int votes = 0;
+    for (int h = 0; h < H; ++h) votes += head_flags[(int64_t)h * N + row] != 0;
+    flags[row] = (uint8_t)(2 * votes > H);
+}
+
+}  // namespace
+
+int max_heads() { return kMaxHeads; }
+
+hipError_t launch_ensemble(int dtype, const RowArgs& args, int heads, int64_t head_stride, hipStream_t stream)
+{
+    if (args.N <= 0) return hipSuccess;
+    const dim3 grid((unsigned)args.N), block(256);
+    if (dtype == 0) hipLaunchKernelGGL(ensemble_kernel<float>, grid, block, 0, stream, args, heads, head_stride);
+    else hipLaunchKernelGGL(ensemble_kernel<bf16_t>, grid, block, 0, stream, args, heads, head_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_vote(const uint8_t* head_flags, int heads, int64_t N, uint8_t* flags, hipStream_t stream)
+{
+    if (N <= 0) return hipSuccess;
+    hipLaunchKernelGGL(vote_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, stream, head_flags, heads, N, flags);
+    return hipGetLastError();
+}
+
+}  // namespace ciar

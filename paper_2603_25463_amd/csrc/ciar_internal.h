@@ -1,4 +1,4 @@
-// Internal interface between the C ABI (ciar_api.cpp) and the gfx950 kernels (ciar_kernels.hip).
+// Internal interface between the C ABI (ciar_api.cpp) and the gfx950 kernels (ciar_*.hip).
 // Not installed; the public contract is include/ciar.h.
 #pragma once
 

@@ -1,0 +1,485 @@
+// gfx950 streaming kernel of the CIAR quantify + verify pass (this file), with an overview of the pass.
+//
+// The pass is split so that the kernel that touches the V-wide rows is pure streaming arithmetic
+// (rowfinish_kernel and resample_kernel live in ciar_finish.hip):
+//
+//   stream_kernel   reads every logit row exactly once from HBM and leaves ten numbers per row
+//                   (RowStats).  A workgroup of 256 lanes (512 or 1024 for large vocabularies or few
+//                   rows) owns one row at a time and walks over rows blockIdx.x, blockIdx.x +
+//                   gridDim.x, ...  The grid is exactly the workgroups that are resident at once (four
+//                   waves per SIMD): while one workgroup waits for its row, the others compute, which
+//                   keeps the memory system busy without a second set of row registers.  Loads are
+//                   interleaved over the workgroup so that every load instruction of a wave covers
+//                   1 KiB of consecutive memory.  Nothing V-wide is ever written back.
+//   rowfinish_kernel  one thread per row turns RowStats into the row's outputs in fp64 (caps, Omega,
+//                   Sigma, U, flag, interval of the reported token, accept test) and appends rejected
+//                   rows to a list.
+//   resample_kernel 1024-lane workgroups walk over that list (~1 row in 8) and run the residual draw,
+//                   re-reading the two rows (mostly served by the caches).
+//
+// The centre row has to be resident between its statistics pass and its interval pass: the InterFuse
+// bounds need the partition sum S of the complete row before the first bound can be formed (App.
+// "Proof of Interval Validity": S appears in every denominator).  It lives in registers as
+// e_i = 2^(c_i log2e - n_w).  The verifier row is only needed for max / Z and is consumed on arrival.
+//
+// stream_kernel, per row (centre row first: it carries most of the arithmetic, so that little is left
+// to do when the last bytes of a launch arrive):
+//   B  centre row:   per-wave maximum, e_i = 2^(c_i log2e - n_w) kept in registers, S_w = sum e_i
+//      The reference n_w is an integer (the next integer above max * log2e of the *wave*), so the
+//      waves need no barrier before exponentiating and their results combine exactly:
+//      S = sum_w S_w 2^(n_w - n), n = max_w n_w, a power-of-two rescale.
+//   -- barrier: the waves exchange (max, n_w, S_w) --
+//   C  InterFuse for a scalar radius r, a = e^r, b = e^-r, x_i = e_i / S:
+//        p^u_i = a x_i / (1 + (a-1) x_i),   p^l_i = b x_i / (1 - (1-b) x_i)
+//      with one reciprocal of the product of the two denominators, accumulated as the lower
+//      bound p^l_i and the raw width w_i = p^u_i - p^l_i = (a-b) x_i (1-x_i) / (du_i dl_i):
+//      five fp64 sums per row (sum p^l, sum w and the three second moments); two of them when the
+//      row's largest probability shows that the caps cannot be active.
+//   T  verifier row, loaded into the registers the centre row came in: per-wave maximum,
+//      Z_w = sum 2^(t_i log2e - nt_w)                                               (max-trick)
+//   -- barrier: the waves exchange their interval sums and (nt_w, Z_w); thread 0 writes RowStats --
+//
+// rowfinish_kernel / resample_kernel, per row (Eq. uncertainty_score; Algorithm 1's threshold and verification steps):
+//   delta_i = alpha_u w_i + (alpha_u - alpha_l) p^l_i once the 0.99 / 1.01 caps alpha_l, alpha_u are
+//   known, so Omega = sum delta_i, Sigma^2 = (sum delta_i^2) / V - (Omega / V)^2, U = Omega * Sigma
+//   follow from the five sums without a second sweep over the row; flag = U > tau;
+//   accept iff ln u < min(0, ln q_x - ln p_x) (log domain, fp64);
+//   rejected rows: res_i = max(0, q_i - p_i), inverse-CDF draw in token order from a workgroup-wide
+//   prefix sum.
+//
+// Sums over a row are accumulated per lane (S and the five interval sums in fp64, which this chip
+// issues at the fp32 rate) and combined across lanes with DPP and across waves through LDS in a fixed
+// order, so results are deterministic and the per-row scalars carry ~1e-8 relative error.
+#include "ciar_device.h"
+
+namespace ciar {
+namespace {
+
+// ---- the streaming kernel ---------------------------------------------------------------------------------
+
+// Waves per SIMD the register allocation aims for: the centre row held as floats plus ~40 working
+// registers, capped at 4 waves.  Memory latency is hidden by the other resident workgroups of the compute
+// unit rather than by fetching ahead into a second set of registers: measured on this chip, three or
+// four resident workgroups beat two with a register prefetch of the next row at every vocabulary size.
+// (Tensor-radius mode: the raw radius row sits in registers next to the centre row during the interval pass.)
+template <typename T, int THREADS, int NVEC, bool RAD>
+constexpr int target_waves()
+{
+    constexpr int ept = NVEC * Elt<T>::kPerVec;                    // one row as floats
+    constexpr int fit = 512 / (ept + (RAD ? NVEC * 4 + 8 : 0) + 40);
+    constexpr int lo = THREADS / 256;                              // waves per SIMD one workgroup needs
+    return fit < lo ? lo : (fit > 4 ? 4 : fit);
+}
+
+// Pass C for one lane: the InterFuse sums over the lane's tokens.
+// Chunks past the end of a row that does not fill the tile are skipped (padding inside the last chunk
+// has e = 0 and adds exactly nothing).
+// WIDTH_ONLY = the caps are known to be inactive for this row (alpha_l = alpha_u = 1), so
+// delta_i = w_i and only sum gw and sum gw^2 are needed.
+// SPLIT = see fuse_token.
+template <int THREADS, int NVEC, int EPV, bool WIDTH_ONLY, bool SPLIT>
+__device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const FuseRow& fr, int V,
+                                          double (&q5)[5])
+{
+    // The sums run in fp64 from the first add (fp64 adds and FMAs issue at the fp32 rate on this
+    // chip).  One token can hold almost all of sum(gl), and the variance is a difference of second
+    // moments that would cancel in fp32 on nearly flat rows; in fp64 neither needs a centring trick.
+    double a0[2] = {0.0, 0.0}, a1[2] = {0.0, 0.0}, a2[2] = {0.0, 0.0}, a3[2] = {0.0, 0.0}, a4[2] = {0.0, 0.0};
+#pragma unroll
+    for (int j = 0; j < NVEC; ++j) {
+        if (j * THREADS * EPV >= V) continue;                      // uniform: the chunk holds no token
+#pragma unroll
+        for (int k = 0; k < EPV; ++k) {
+            float gl, gw;
+            fuse_token<SPLIT>(e[j * EPV + k], fr, gl, gw);         // padding has e = 0: gl = gw = 0
+            const double dw = (double)gw;
+            a1[k & 1] += dw;
+            a3[k & 1] = fma(dw, dw, a3[k & 1]);
+            if constexpr (!WIDTH_ONLY) {
+                const double dl = (double)gl;
+                a0[k & 1] += dl;
+                a2[k & 1] = fma(dl, dl, a2[k & 1]);
+                a4[k & 1] = fma(dl, dw, a4[k & 1]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);                         // one vector at a time: bounded working set
+    }
+    q5[0] = a0[0] + a0[1];
+    q5[1] = a1[0] + a1[1];
+    q5[2] = a2[0] + a2[1];
+    q5[3] = a3[0] + a3[1];
+    q5[4] = a4[0] + a4[1];
+}
+
+// Pass C for a handful of tokens (V <= kTinyVocab), in fp64 from the fp32 e_i.  With so few tokens the widths
+// are O(1) and Sigma can be an exact zero (two tokens: delta_1 = delta_2 identically, because x_1 + x_2 = 1
+// holds for the computed x as well); fp32 token arithmetic leaves ~1e-7 there, fp64 keeps the symmetry.
+// Same units as fuse_sums / fuse_sums_rad: gl, gw per token with p^l = Bc gl, p^u - p^l = Wc gw.
+
+template <typename T, int EPV, bool RAD>
+__device__ __forceinline__ void fuse_sums_tiny(const float (&e)[EPV], const u32x4& rad, double S_units, double a,
+                                               double b, double kappa, double rmax, double (&q5)[5])
+{
+    float raw[EPV];
+    Elt<T>::unpack(rad, raw);
+    const double invS = 1.0 / S_units;
+#pragma unroll
+    for (int i = 0; i < 5; ++i) q5[i] = 0.0;
+#pragma unroll
+    for (int k = 0; k < EPV; ++k) {
+        const double ed = (double)e[k], x = ed * invS;
+        double ak = a, bk = b;
+        if constexpr (RAD) {
+            const double r = radius_of((double)raw[k], kappa, rmax);
+            ak = exp(r); bk = exp(-r);
+        }
+        const double om = 1.0 - x, du = 1.0 + (ak - 1.0) * x, dl = 1.0 - (1.0 - bk) * x;
+        double gl = ed / dl, gw = ed * om / (du * dl);
+        if constexpr (RAD) { gl *= bk; gw *= ak - bk; }
+        q5[0] += gl; q5[1] += gw;
+        q5[2] = fma(gl, gl, q5[2]); q5[3] = fma(gw, gw, q5[3]); q5[4] = fma(gl, gw, q5[4]);
+    }
+}
+
+// Pass C in tensor-radius mode: every token has its own a_i, b_i from the raw radius row `rad` (as loaded,
+// padding already zeroed); the sums are of p^l_i S and (p^u_i - p^l_i) S themselves.
+template <typename T, int THREADS, int NVEC>
+__device__ __forceinline__ void fuse_sums_rad(const float (&e)[NVEC * Elt<T>::kPerVec], const u32x4 (&rad)[NVEC],
+                                              const FuseRow& fr, float kappa, float rmax, int V, double (&q5)[5])
+{
+    constexpr int EPV = Elt<T>::kPerVec;
+    double a0[2] = {0.0, 0.0}, a1[2] = {0.0, 0.0}, a2[2] = {0.0, 0.0}, a3[2] = {0.0, 0.0}, a4[2] = {0.0, 0.0};
+#pragma unroll
+    for (int j = 0; j < NVEC; ++j) {
+        if (j * THREADS * EPV >= V) continue;                      // uniform: the chunk holds no token
+        float raw[EPV];
+        Elt<T>::unpack(rad[j], raw);
+#pragma unroll
+        for (int k = 0; k < EPV; ++k) {
+            float pl, w;
+            fuse_token_rad(e[j * EPV + k], raw[k], fr, kappa, rmax, pl, w);   // padding has e = 0: pl = w = 0
+            const double dl = (double)pl, dw = (double)w;
+            a0[k & 1] += dl;
+            a1[k & 1] += dw;
+            a2[k & 1] = fma(dl, dl, a2[k & 1]);
+            a3[k & 1] = fma(dw, dw, a3[k & 1]);
+            a4[k & 1] = fma(dl, dw, a4[k & 1]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    q5[0] = a0[0] + a0[1];
+    q5[1] = a1[0] + a1[1];
+    q5[2] = a2[0] + a2[1];
+    q5[3] = a3[0] + a3[1];
+    q5[4] = a4[0] + a4[1];
+}
+
+template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V, bool RAD>
+__global__ __launch_bounds__(THREADS)
+__attribute__((amdgpu_waves_per_eu(target_waves<T, THREADS, NVEC, RAD>())))
+void stream_kernel(const RowArgs A)
+{
+    using E = Elt<T>;
+    constexpr int EPV = E::kPerVec;
+    constexpr int EPT = NVEC * EPV;
+    constexpr int NW = THREADS / 64;
+    constexpr int CHUNK = THREADS * EPV;            // tokens covered by one load instruction of the workgroup
+
+    // Exchange slots.  Two barriers per row order every write against every read: the centre-row
+    // slots are written before the first and read between the two, the others are written between the
+    // two and read by thread 0 after the second, before it reaches the next row's first barrier.
+    __shared__ float  sm_ref[NW * 2];               // per wave: max centre logit, n_w
+    __shared__ double sm_S[NW];                     // per wave: S_w
+    __shared__ float  sm_nt[NW];                    // per wave: nt_w
+    __shared__ double sm_Z[NW];                     // per wave: Z_w
+    __shared__ double sm_q5[NW * 5];                // per wave: the five interval sums, already in row units
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int V = A.V;
+    const bool partial = V != NVEC * CHUNK;                        // uniform: the row does not fill the tile
+    const int last_vec = (V + EPV - 1) / EPV - 1;
+    const int nrows = (int)A.N;
+    const int step = (int)gridDim.x;
+
+    // Rows live in global memory (address space 1).  Vector j of this lane: scalar row base + 32-bit
+    // byte offset.  A row that fills the tile needs one lane offset for all of its vectors (the
+    // distance between vectors is a constant on top of the scalar base).  Otherwise vector indices
+    // past the end of the row are clamped to its last vector, so every lane loads valid memory
+    // unconditionally; tokens that do not exist are set to -inf afterwards.
+    // The base goes through readfirstlane and the lane index through an empty asm: both are opaque
+    // to the optimiser, which otherwise turns the sixteen addresses of a row into sixteen 64-bit
+    // induction variables, spills them, and serialises the loads on the reloads.
+    auto load_row = [&](u32x4 (&buf)[NVEC], const void* rows, int r) {
+        const uint64_t b = (uint64_t)(static_cast<const T*>(rows) + (int64_t)r * A.stride);
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+        const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+        const gbytes base = (gbytes)(((uint64_t)hi << 32) | lo);
+        int t = tid;
+        asm volatile("" : "+v"(t));
+        if (partial) {
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) {
+                const uint32_t off = (uint32_t)min(j * THREADS + t, last_vec) * 16u;
+                buf[j] = *(gvec)(base + off);
+            }
+        } else {
+            const uint32_t off = (uint32_t)t * 16u;
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) buf[j] = *(gvec)(base + (uint64_t)j * (THREADS * 16u) + off);
+        }
+    };
+    // Verifier row statistics of one wave from the row as loaded: nt_w and Z_w = sum 2^(t_i log2e - nt_w).
+    auto verifier_stats = [&](u32x4 (&tb)[NVEC], float& ntw, double& Zw) {
+        if (partial) {
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) E::mask_tail(tb[j], (j * THREADS + tid) * EPV, V);
+        }
+        float mt = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) {
+            float tv[EPV];
+            E::unpack(tb[j], tv);
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) mt = fmaxf(mt, tv[k]);
+        }
+        ntw = ref_of(wave_max(mt));
+        const float nref = ntw == -INFINITY ? 0.f : ntw;           // an all-masked wave: every term is 2^-inf = 0
+        float zacc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) {
+            float tv[EPV];
+            E::unpack(tb[j], tv);
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) zacc[k & 3] += exp2_ref(tv[k], nref);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        Zw = wave_sum((double)((zacc[0] + zacc[1]) + (zacc[2] + zacc[3])));
+    };
+
+    // the list of rejected rows that the finishing kernels build starts empty
+    if (DO_V && blockIdx.x == 0 && tid == 0) *A.reject_count = 0;
+
+    // The row index is uniform over the workgroup: keep it in a scalar register.
+    // A row's centre logits are loaded and worked on first, its verifier logits second: the centre row
+    // carries most of the arithmetic (both of its passes), the verifier row only a short one, so
+    // little work is left when the last bytes of the launch arrive.
+    int row = __builtin_amdgcn_readfirstlane((int)blockIdx.x);     // the launcher keeps gridDim.x <= N
+    u32x4 buf[NVEC];                                               // a row as loaded: centre and verifier row in turn
+    load_row(buf, A.draft, row);
+
+    for (;;) {
+        const int next = __builtin_amdgcn_readfirstlane(row + step);
+        const bool has_next = next < nrows;                        // uniform
+
+        // ---- B: centre row: per-wave max, e_i = 2^(c_i log2e - n_w), S_w -------------------------------
+        float e[EPT];
+        if (partial) {
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) E::mask_tail(buf[j], (j * THREADS + tid) * EPV, V);
+        }
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) E::unpack(buf[j], &e[j * EPV]);
+        float mcl = e[0];
+#pragma unroll
+        for (int i = 1; i < EPT; ++i) mcl = fmaxf(mcl, e[i]);
+        const float mcw = wave_max(mcl);
+        const float nw = ref_of(mcw);
+        double Sw;
+        {
+            // S is accumulated in fp64 from the first add: on a nearly one-hot row the bounds of the top
+            // token react to a relative error in S about five times over, and on a two-token row Sigma is
+            // a difference of two nearly equal widths; even one fp32 add of two comparable terms (6e-8)
+            // shows there (measured against the fp64 definition).
+            const float nref = nw == -INFINITY ? 0.f : nw;
+            double sacc[2] = {0.0, 0.0};
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) {
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) {
+                    e[j * EPV + k] = exp2_ref(e[j * EPV + k], nref);
+                    sacc[k & 1] += (double)e[j * EPV + k];
+                }
+                __builtin_amdgcn_sched_barrier(0);                 // keep the working set to one vector at a time
+            }
+            Sw = wave_sum(sacc[0] + sacc[1]);
+        }
+
+        // ---- the waves exchange the centre row's statistics ----------------------------------------------
+        if (lane == 0) {
+            sm_ref[wave * 2] = mcw; sm_ref[wave * 2 + 1] = nw;
+            sm_S[wave] = Sw;
+        }
+        __syncthreads();
+        float mc = sm_ref[0], n = sm_ref[1];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) {
+            mc = fmaxf(mc, sm_ref[w * 2]);
+            n = fmaxf(n, sm_ref[w * 2 + 1]);
+        }
+        double S = 0.0;                                            // in units of 2^-n
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float rn = sm_ref[w * 2 + 1];
+            if (rn != -INFINITY) S += sm_S[w] * pow2_of(rn - n);
+        }
+        const double fw = nw == -INFINITY ? 0.0 : pow2_of(nw - n);     // this wave's e_i are 1/fw too large
+
+        // ---- C: InterFuse sums in this wave's units, rescaled to row units by lane 0 of the wave ---------
+        // Caps: S_l <= b / (1 - (1-b) x_max) and S_u >= a / (1 + (a-1) x_max) for the largest probability
+        // x_max of the row, so below the host-computed bound on x_max both caps are inactive and the
+        // cheaper width-only pass is exact.  Uniform over the workgroup.
+        const double emax = (double)exp2_ref(mc, n);               // the row's largest e_i, in row units
+        const bool capless = !A.normalize || (!RAD && emax <= A.capless_xmax * S);
+        const bool split = emax > 0.5 * S;                         // some x_i above 1/2: 1 - x needs the two-float 1/S
+        if constexpr (DO_Q) {
+            // x_i = e_i fw / S: hand fuse_row the partition sum expressed in this wave's units
+            const FuseRow fr = fuse_row(fw > 0.0 ? S / fw : 1.0, A.a, A.b);
+            double q5[5];
+            bool tiny = false;
+            if constexpr (NVEC == 1) tiny = V <= kTinyVocab;       // uniform
+            if (tiny) {
+                if constexpr (NVEC == 1) {
+                    if constexpr (RAD) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        load_row(buf, A.radius, row);
+                        E::zero_tail(buf[0], tid * EPV, V);
+                    }
+                    fuse_sums_tiny<T, EPV, RAD>(e, buf[0], fw > 0.0 ? S / fw : 1.0, A.a, A.b, A.kappa, A.rmax, q5);
+#pragma unroll
+                    for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
+                }
+            } else if constexpr (RAD) {
+                // the raw radius row comes into the registers the centre row came in
+                __builtin_amdgcn_sched_barrier(0);
+                load_row(buf, A.radius, row);
+                if (partial) {
+#pragma unroll
+                    for (int j = 0; j < NVEC; ++j) E::zero_tail(buf[j], (j * THREADS + tid) * EPV, V);
+                }
+                fuse_sums_rad<T, THREADS, NVEC>(e, buf, fr, (float)A.kappa, (float)A.rmax, V, q5);
+#pragma unroll
+                for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
+            } else if (capless) {
+                if (split) fuse_sums<THREADS, NVEC, EPV, true, true>(e, fr, V, q5);
+                else       fuse_sums<THREADS, NVEC, EPV, true, false>(e, fr, V, q5);
+                q5[1] = wave_sum(q5[1]);
+                q5[3] = wave_sum(q5[3]);
+            } else {
+                fuse_sums<THREADS, NVEC, EPV, false, true>(e, fr, V, q5);
+#pragma unroll
+                for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
+            }
+            if (lane == 0) {
+                const double f2 = fw * fw;
+                sm_q5[wave * 5 + 0] = q5[0] * fw; sm_q5[wave * 5 + 1] = q5[1] * fw;
+                sm_q5[wave * 5 + 2] = q5[2] * f2; sm_q5[wave * 5 + 3] = q5[3] * f2; sm_q5[wave * 5 + 4] = q5[4] * f2;
+            }
+        }
+
+        // ---- T: verifier row statistics, per wave; the row is not kept -------------------------------------
+        if constexpr (DO_V) {
+            float ntw;
+            double Zw;
+            // The verifier row is fetched only now, into the registers the centre row came in.  Fetching
+            // it earlier, next to the interval pass, was measured slower: the other resident workgroups
+            // already keep the memory system busy, and more loads in flight per wave only lengthen queues.
+            __builtin_amdgcn_sched_barrier(0);
+            load_row(buf, A.target, row);
+            verifier_stats(buf, ntw, Zw);
+            if (lane == 0) { sm_nt[wave] = ntw; sm_Z[wave] = Zw; }
+        }
+        // the next centre row goes in flight before the barrier and thread 0's bookkeeping
+        __builtin_amdgcn_sched_barrier(0);
+        if (has_next) load_row(buf, A.draft, next);
+
+        // ---- thread 0 leaves the row's ten numbers for the finishing kernels -------------------------------
+        __syncthreads();
+        if (tid == 0) {
+            float nt = -INFINITY;
+            double Z = 0.0;                                        // in units of 2^-nt
+            if constexpr (DO_V) {
+#pragma unroll
+                for (int w = 0; w < NW; ++w) nt = fmaxf(nt, sm_nt[w]);
+#pragma unroll
+                for (int w = 0; w < NW; ++w) {
+                    const float rt = sm_nt[w];
+                    if (rt != -INFINITY) Z += sm_Z[w] * pow2_of(rt - nt);
+                }
+            }
+            RowStats* st = A.stats + row;
+            st->S = S; st->Z = Z; st->n = n; st->nt = nt; st->mc = mc; st->capless = capless ? 1.f : 0.f;
+#pragma unroll
+            for (int i = 0; i < 5; ++i) {
+                double t = 0.0;
+                if constexpr (DO_Q) {
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) t += sm_q5[w * 5 + i];
+                }
+                st->q[i] = t;
+            }
+        }
+
+        if (!has_next) break;
+        row = next;
+    }
+}
+
+// ---- dispatch ---------------------------------------------------------------------------------------------
+
+template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V, bool RAD>
+hipError_t launch_stream_kernel(const RowArgs& a, hipStream_t s)
+{
+    // One wave of resident workgroups, each walking over rows with stride gridDim.x.  The register
+    // budget the kernel was compiled for fixes how many fit: target_waves() waves per SIMD, and a
+    // workgroup puts THREADS / 256 waves on each of the four SIMDs of a compute unit.
+    constexpr int per_cu = target_waves<T, THREADS, NVEC, RAD>() / (THREADS / 256);
+    const int64_t resident = (int64_t)per_cu * compute_units();
+    const unsigned grid = (unsigned)(a.N < resident ? a.N : resident);
+    hipLaunchKernelGGL((stream_kernel<T, THREADS, NVEC, DO_Q, DO_V, RAD>), dim3(grid), dim3(THREADS), 0, s, a);
+    return hipGetLastError();
+}
+
+template <typename T, int THREADS, int NVEC>
+hipError_t launch_stream_cfg(Mode mode, const RowArgs& a, hipStream_t s)
+{
+    const bool rad = a.radius != nullptr;
+    switch (mode) {
+    case Mode::Quantify: return rad ? launch_stream_kernel<T, THREADS, NVEC, true, false, true>(a, s)
+                                    : launch_stream_kernel<T, THREADS, NVEC, true, false, false>(a, s);
+    case Mode::Verify:   return launch_stream_kernel<T, THREADS, NVEC, false, true, false>(a, s);
+    case Mode::Fused:    return rad ? launch_stream_kernel<T, THREADS, NVEC, true, true, true>(a, s)
+                                    : launch_stream_kernel<T, THREADS, NVEC, true, true, false>(a, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+template <typename T>
+hipError_t launch_stream_typed(Mode mode, const RowArgs& a, hipStream_t s)
+{
+    const int vecs = (a.V + Elt<T>::kPerVec - 1) / Elt<T>::kPerVec;   // 16-byte vectors per row
+    if (vecs <= 256 * 1)  return launch_stream_cfg<T, 256, 1>(mode, a, s);
+    if (vecs <= 256 * 2)  return launch_stream_cfg<T, 256, 2>(mode, a, s);
+    if (vecs <= 256 * 4)  return launch_stream_cfg<T, 256, 4>(mode, a, s);
+    if (vecs <= 256 * 8)  return launch_stream_cfg<T, 256, 8>(mode, a, s);
+    if (vecs <= 256 * 16) {
+        // Few rows per workgroup: eight waves on a row keep the last rows of the launch short and the
+        // grid even; with many rows the four-wave tile has less exchange overhead (measured).
+        if (a.N < 12 * (int64_t)compute_units()) return launch_stream_cfg<T, 512, 8>(mode, a, s);
+        return launch_stream_cfg<T, 256, 16>(mode, a, s);
+    }
+    if (vecs <= 1024 * 8) return launch_stream_cfg<T, 1024, 8>(mode, a, s);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+int max_vocab(int dtype) { return dtype == 0 ? 1024 * 8 * 4 : 1024 * 8 * 8; }
+
+hipError_t launch_stream(Mode mode, int dtype, const RowArgs& args, hipStream_t stream)
+{
+    if (args.N <= 0) return hipSuccess;
+    return dtype == 0 ? launch_stream_typed<float>(mode, args, stream)
+                      : launch_stream_typed<bf16_t>(mode, args, stream);
+}
+
+}  // namespace ciar
