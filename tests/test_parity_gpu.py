@@ -556,6 +556,47 @@ def test_results_are_deterministic_and_stream_ordered(ciar):
         assert torch.equal(a[k], b[k]), k
 
 
+@pytest.mark.parametrize("N", [1, 2, 7, 255, 256, 257, 511, 513, 1025])
+def test_row_counts_around_the_block_sizes(ciar, oracle, N):
+    """Row counts below, at and just above the finishing kernels' 256-row workgroups and the streaming
+    kernel's resident grid, with a window length that does not divide them."""
+    c, t, ids, ua, ur = _random_case(1024, 1024, N, 5, torch.float32, seed=700 + N, sigma=0.4)
+    _run_case(ciar, oracle, c, t, ids, ua, ur, ciar.Params(confidence=0.9, window=5, tau=0.01), vocab=1024,
+              tag=f"row count N={N}")
+
+
+def test_calls_replay_from_a_captured_graph(ciar):
+    """The library allocates nothing, records no memset and never synchronises, so a call can be captured into
+    a HIP graph.  Replays (with eager work and synchronisation between them, and the inputs changed between
+    replays) must reproduce the eager results bit for bit."""
+    c, t, ids, ua, ur = _random_case(16384, 16384, 300, 8, torch.float32, seed=41)
+    c2, t2, *_ = _random_case(16384, 16384, 300, 8, torch.float32, seed=42)
+    say("[graph] V=16384 N=300: capture ciar_quantify_verify, replay 4 times on alternating inputs")
+    P = ciar.Params(tau=0.01)
+    ref1 = ciar.quantify_verify(c, t, ids, ua, ur, P)
+    ref2 = ciar.quantify_verify(c2, t2, ids, ua, ur, P)
+    torch.cuda.synchronize()
+    cin, tin = c.clone(), t.clone()
+    ws = torch.empty(ciar.workspace_bytes(300, P.to_c(c)), dtype=torch.uint8, device="cuda")
+    out = {k: torch.empty_like(v) for k, v in ref1.items()}
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        ciar.quantify_verify(cin, tin, ids, ua, ur, P, out=out, workspace=ws, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for i in range(4):
+        src_c, src_t, ref = (c, t, ref1) if i % 2 == 0 else (c2, t2, ref2)
+        cin.copy_(src_c)
+        tin.copy_(src_t)
+        for k in out:
+            out[k].fill_(0)                      # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for k in ref:
+            assert torch.equal(out[k], ref[k]), (i, k)
+
+
 def test_bad_arguments_raise(ciar):
     c = torch.zeros((4, 1024), device="cuda")
     with pytest.raises(ciar.CiarError, match="CIAR_EUNSUPPORTED"):
