@@ -115,10 +115,10 @@ __global__ __launch_bounds__(256) void read_kernel(const RowArgs A, float* __res
     for (int base = 0; base < nvec; base += UB * 256) {
         u32x4 cb[UB], tb[UB];
 #pragma unroll
-        for (int j = 0; j < UB; ++j) cb[j] = c[min(base + j * 256 + tid, nvec - 1)];
+        for (int j = 0; j < UB; ++j) cb[j] = __builtin_nontemporal_load(&c[min(base + j * 256 + tid, nvec - 1)]);
         if (two) {
 #pragma unroll
-            for (int j = 0; j < UB; ++j) tb[j] = t[min(base + j * 256 + tid, nvec - 1)];
+            for (int j = 0; j < UB; ++j) tb[j] = __builtin_nontemporal_load(&t[min(base + j * 256 + tid, nvec - 1)]);
         }
         const bool ragged = base + UB * 256 >= nvec;               // uniform: this sweep reaches the row's end
 #pragma unroll

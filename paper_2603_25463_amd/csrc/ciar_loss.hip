@@ -37,9 +37,9 @@ __global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* _
 #pragma unroll
     for (int j = 0; j < NVEC; ++j) {
         const uint32_t off = (uint32_t)min(j * THREADS + tid, last_vec) * 16u;
-        cw[j] = *(gvec)(cb + off);
-        tw[j] = *(gvec)(tb + off);
-        if (rad) rw[j] = *(gvec)(rb + off);
+        cw[j] = __builtin_nontemporal_load((gvec)(cb + off));     // every row is used once: stream past the caches
+        tw[j] = __builtin_nontemporal_load((gvec)(tb + off));
+        if (rad) rw[j] = __builtin_nontemporal_load((gvec)(rb + off));
     }
 #pragma unroll
     for (int j = 0; j < NVEC; ++j) {

