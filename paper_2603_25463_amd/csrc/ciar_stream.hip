@@ -184,6 +184,10 @@ void stream_kernel(const RowArgs A)
     constexpr int EPT = NVEC * EPV;
     constexpr int NW = THREADS / 64;
     constexpr int CHUNK = THREADS * EPV;            // tokens covered by one load instruction of the workgroup
+    // The verifier row is requested before the interval pass where a second row fits in the registers at
+    // four waves per SIMD next to the centre row's floats (fp32 tiles of up to 8 vectors per lane; measured
+    // 51 -> 48.6 us on the benchmark); elsewhere it would spill, and it is requested after the pass.
+    constexpr bool EARLY_T = DO_V && !RAD && (EPT + NVEC * 4 + 56) * 4 <= 512;
 
     // Exchange slots.  Two barriers per row order every write against every read: the centre-row
     // slots are written before the first and read between the two, the others are written between the
@@ -333,6 +337,13 @@ void stream_kernel(const RowArgs A)
         const double emax = (double)exp2_ref(mc, n);               // the row's largest e_i, in row units
         const bool capless = !A.normalize || (!RAD && emax <= A.capless_xmax * S);
         const bool split = emax > 0.5 * S;                         // some x_i above 1/2: 1 - x needs the two-float 1/S
+        if constexpr (EARLY_T) {
+            // the verifier row goes in flight now, into the registers the centre row came in, and lands
+            // during the interval pass
+            __builtin_amdgcn_sched_barrier(0);
+            load_row(buf, A.target, row);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         if constexpr (DO_Q) {
             // x_i = e_i fw / S: hand fuse_row the partition sum expressed in this wave's units
             const FuseRow fr = fuse_row(fw > 0.0 ? S / fw : 1.0, A.a, A.b);
@@ -382,11 +393,11 @@ void stream_kernel(const RowArgs A)
         if constexpr (DO_V) {
             float ntw;
             double Zw;
-            // The verifier row is fetched only now, into the registers the centre row came in.  Fetching
-            // it earlier, next to the interval pass, was measured slower: the other resident workgroups
-            // already keep the memory system busy, and more loads in flight per wave only lengthen queues.
-            __builtin_amdgcn_sched_barrier(0);
-            load_row(buf, A.target, row);
+            if constexpr (!EARLY_T) {
+                // no registers to spare next to the interval pass: the verifier row is fetched only now
+                __builtin_amdgcn_sched_barrier(0);
+                load_row(buf, A.target, row);
+            }
             verifier_stats(buf, ntw, Zw);
             if (lane == 0) { sm_nt[wave] = ntw; sm_Z[wave] = Zw; }
         }
