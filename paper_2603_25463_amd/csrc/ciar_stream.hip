@@ -475,10 +475,15 @@ hipError_t launch_stream_typed(Mode mode, const RowArgs& a, hipStream_t s)
     if (vecs <= 256 * 4)  return launch_stream_cfg<T, 256, 4>(mode, a, s);
     if (vecs <= 256 * 8)  return launch_stream_cfg<T, 256, 8>(mode, a, s);
     if (vecs <= 256 * 16) {
-        // Few rows per workgroup: eight waves on a row keep the last rows of the launch short and the
-        // grid even; with many rows the four-wave tile has less exchange overhead (measured).
-        if (a.N < 12 * (int64_t)compute_units()) return launch_stream_cfg<T, 512, 8>(mode, a, s);
-        return launch_stream_cfg<T, 256, 16>(mode, a, s);
+        // Few rows: eight waves on a row keep the last rows of the launch short and the grid even; with many
+        // rows the four-wave tile has less exchange overhead (measured).  For bf16 the four-wave tile would
+        // hold 128 floats per lane and spill: eight waves always.
+        if constexpr (sizeof(T) == 2) {
+            return launch_stream_cfg<T, 512, 8>(mode, a, s);
+        } else {
+            if (a.N < 12 * (int64_t)compute_units()) return launch_stream_cfg<T, 512, 8>(mode, a, s);
+            return launch_stream_cfg<T, 256, 16>(mode, a, s);
+        }
     }
     if (vecs <= 1024 * 8) return launch_stream_cfg<T, 1024, 8>(mode, a, s);
     return hipErrorInvalidValue;
