@@ -10,12 +10,13 @@
 //                   waves per SIMD): while one workgroup waits for its row, the others compute, which
 //                   keeps the memory system busy without a second set of row registers.  Loads are
 //                   interleaved over the workgroup so that every load instruction of a wave covers
-//                   1 KiB of consecutive memory.  Nothing V-wide is ever written back.
+//                   1 KiB of consecutive memory, and non-temporal (every logit is used once).
+//                   Nothing V-wide is ever written back.
 //   rowfinish_kernel  one thread per row turns RowStats into the row's outputs in fp64 (caps, Omega,
 //                   Sigma, U, flag, interval of the reported token, accept test) and appends rejected
 //                   rows to a list.
-//   resample_kernel 1024-lane workgroups walk over that list (~1 row in 8) and run the residual draw,
-//                   re-reading the two rows (mostly served by the caches).
+//   resample_kernel workgroups walk over that list (~1 row in 8) and run the residual draw, re-reading
+//                   the two rows.
 //
 // The centre row has to be resident between its statistics pass and its interval pass: the InterFuse
 // bounds need the partition sum S of the complete row before the first bound can be formed (App.
@@ -35,8 +36,8 @@
 //      bound p^l_i and the raw width w_i = p^u_i - p^l_i = (a-b) x_i (1-x_i) / (du_i dl_i):
 //      five fp64 sums per row (sum p^l, sum w and the three second moments); two of them when the
 //      row's largest probability shows that the caps cannot be active.
-//   T  verifier row, loaded into the registers the centre row came in: per-wave maximum,
-//      Z_w = sum 2^(t_i log2e - nt_w)                                               (max-trick)
+//   T  verifier row, loaded into the registers the centre row came in (requested before C where the
+//      registers allow, else after it): per-wave maximum, Z_w = sum 2^(t_i log2e - nt_w)   (max-trick)
 //   -- barrier: the waves exchange their interval sums and (nt_w, Z_w); thread 0 writes RowStats --
 //
 // rowfinish_kernel / resample_kernel, per row (Eq. uncertainty_score; Algorithm 1's threshold and verification steps):
@@ -67,7 +68,7 @@ constexpr int target_waves()
 {
     constexpr int ept = NVEC * Elt<T>::kPerVec;                    // one row as floats
     constexpr int fit = 512 / (ept + (RAD ? NVEC * 4 + 8 : 0) + 40);
-    constexpr int lo = THREADS / 256;                              // waves per SIMD one workgroup needs
+    constexpr int lo = (THREADS + 255) / 256;                      // waves per SIMD one workgroup needs
     return fit < lo ? lo : (fit > 4 ? 4 : fit);
 }
 
@@ -444,8 +445,9 @@ hipError_t launch_stream_kernel(const RowArgs& a, hipStream_t s)
 {
     // One wave of resident workgroups, each walking over rows with stride gridDim.x.  The register
     // budget the kernel was compiled for fixes how many fit: target_waves() waves per SIMD, and a
-    // workgroup puts THREADS / 256 waves on each of the four SIMDs of a compute unit.
-    constexpr int per_cu = target_waves<T, THREADS, NVEC, RAD>() / (THREADS / 256);
+    // workgroup puts THREADS / 256 waves on each of the four SIMDs of a compute unit (a 128-lane one: one
+    // wave on two of them).
+    constexpr int per_cu = target_waves<T, THREADS, NVEC, RAD>() * 256 / THREADS;
     const int64_t resident = (int64_t)per_cu * compute_units();
     const unsigned grid = (unsigned)(a.N < resident ? a.N : resident);
     hipLaunchKernelGGL((stream_kernel<T, THREADS, NVEC, DO_Q, DO_V, RAD>), dim3(grid), dim3(THREADS), 0, s, a);
