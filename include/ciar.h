@@ -21,7 +21,8 @@
  *     default stream) and outputs are valid once the caller has synchronised that stream.
  *   - `workspace` is device scratch of at least ciar_workspace_bytes(N, params) bytes, 16-byte
  *     aligned, owned by the caller.  It carries the per-row statistics from the streaming kernel
- *     to the finishing kernel (and per-row results the caller did not ask for).  Its contents need
+ *     to the finishing kernels, the list of rejected rows, and per-row results the caller did not
+ *     ask for.  Its contents need
  *     no initialisation and are garbage afterwards; calls that overlap in time on one device
  *     must not share a workspace.
  *   - Logits: row-major [N, row_stride] with V <= row_stride, element type `dtype`
@@ -167,7 +168,8 @@ int ciar_quantify_verify(const void* draft_logits, const void* radius, const voi
  *                    per-row statistics (max-trick references, partition sums, the InterFuse sums)
  *                    in `workspace`.  target_logits = NULL: quantify only (with_intervals must be 1);
  *                    with_intervals = 0: verify only (radius must be NULL); otherwise both.
- * ciar_finish_rows   the finishing kernel (+ the window epilogue when a window output is given):
+ * ciar_finish_rows   the finishing kernels (per-row scalars, then the residual draw of the rejected rows;
+ *                    both also write the window outputs when one is given):
  *                    arguments as ciar_quantify_verify; it must be given the workspace a
  *                    ciar_stream_rows call on the same rows and parameters has filled, the same
  *                    radius and target_logits (or NULL), and quantify outputs iff with_intervals was 1.
