@@ -189,6 +189,9 @@ void stream_kernel(const RowArgs A)
     // four waves per SIMD next to the centre row's floats (fp32 tiles of up to 8 vectors per lane; measured
     // 51 -> 48.6 us on the benchmark); elsewhere it would spill, and it is requested after the pass.
     constexpr bool EARLY_T = DO_V && !RAD && (EPT + NVEC * 4 + 56) * 4 <= 512;
+    // Quantify-only launches have no verifier row; under the same condition the next centre row is requested
+    // before the interval pass instead.
+    constexpr bool EARLY_NEXT = !DO_V && !RAD && (EPT + NVEC * 4 + 56) * 4 <= 512;
 
     // Exchange slots.  Two barriers per row order every write against every read: the centre-row
     // slots are written before the first and read between the two, the others are written between the
@@ -338,6 +341,11 @@ void stream_kernel(const RowArgs A)
         const double emax = (double)exp2_ref(mc, n);               // the row's largest e_i, in row units
         const bool capless = !A.normalize || (!RAD && emax <= A.capless_xmax * S);
         const bool split = emax > 0.5 * S;                         // some x_i above 1/2: 1 - x needs the two-float 1/S
+        if constexpr (EARLY_NEXT) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (has_next) load_row(buf, A.draft, next);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         if constexpr (EARLY_T) {
             // the verifier row goes in flight now, into the registers the centre row came in, and lands
             // during the interval pass
@@ -403,8 +411,10 @@ void stream_kernel(const RowArgs A)
             if (lane == 0) { sm_nt[wave] = ntw; sm_Z[wave] = Zw; }
         }
         // the next centre row goes in flight before the barrier and thread 0's bookkeeping
-        __builtin_amdgcn_sched_barrier(0);
-        if (has_next) load_row(buf, A.draft, next);
+        if constexpr (!EARLY_NEXT) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (has_next) load_row(buf, A.draft, next);
+        }
 
         // ---- thread 0 leaves the row's ten numbers for the finishing kernels -------------------------------
         __syncthreads();
