@@ -225,6 +225,23 @@ __device__ __forceinline__ void fuse_token(float e, const FuseRow& r, float& gl,
     gw = g * om;
 }
 
+// The complement of the width next to gl and gw:  ec = 1 - (p^u - p^l) = (1 - 2 (1-b) x (1-x)) / (du dl)
+// (from a b = 1).  The numerator lies in [1/2, 1], so ec keeps its relative accuracy where the width itself
+// rounds to 1: with a large radius every p^u_i is close to 1, the widths differ from each other by less
+// than an fp32 ulp, and only the sums of ec resolve their standard deviation.
+__device__ __forceinline__ void fuse_token_wide(float e, const FuseRow& r, float& gl, float& gw, float& ec)
+{
+    const float om = fmaf(e, r.nil, fmaf(e, r.nih, 1.0f));        // 1 - x
+    const float x = -e * r.nih;
+    const float du = fmaf(e, r.cu, 1.0f);
+    const float dl = fmaf(om, r.omb, r.b);
+    const float rc = __builtin_amdgcn_rcpf(du * dl);
+    const float g = e * rc;
+    gl = g * du;
+    gw = g * om;
+    ec = fmaf(-2.0f * r.omb, x * om, 1.0f) * rc;
+}
+
 // Tensor-radius mode (Sec. 3.2.3, the Interval Head: r = Softplus(raw)): a = e^r, b = e^-r for
 // r = min(kappa Softplus(raw), rmax).  Softplus(raw) = max(raw, 0) + ln(1 + t), t = e^-|raw|;
 // ln(1 + t) = ln(u) t / (u - 1) with u = fl(1 + t): u - 1 is exact, so the rounding of 1 + t cancels in
@@ -262,16 +279,48 @@ __device__ __forceinline__ void fuse_token_rad(float e, float raw, const FuseRow
     w = (a - b) * (g * om);
 }
 
+// The same with the complement of the width, ec = 1 - (p^u_i - p^l_i) (see fuse_token_wide).
+__device__ __forceinline__ void fuse_token_rad_wide(float e, float raw, const FuseRow& r, float kappa, float rmax,
+                                                    float& pl, float& w, float& ec)
+{
+    float a, b;
+    radius_ab(raw, kappa, rmax, a, b);
+    const float om = fmaf(e, r.nil, fmaf(e, r.nih, 1.0f));        // 1 - x
+    const float x = -e * r.nih;
+    const float du = fmaf(a - 1.0f, x, 1.0f);
+    const float dl = fmaf(om, 1.0f - b, b);
+    const float rc = __builtin_amdgcn_rcpf(du * dl);
+    const float g = e * rc;
+    pl = b * (g * du);
+    w = (a - b) * (g * om);
+    ec = fmaf(-2.0f * (1.0f - b), x * om, 1.0f) * rc;
+}
+
 // Per-row scalars of the quantifier from the five sums (fp64, one lane).
 struct RowScore { double alpha_l, alpha_u, omega, sigma, score; };
 
-__device__ __forceinline__ RowScore finish_score(const double* s, double S, bool capless, const RowArgs& A)
+// How a row's interval sums are to be read (RowStats::mode).
+constexpr float kSumsFull = 0.f;         // all five sums
+constexpr float kSumsWidthOnly = 1.f;    // the caps are known to be inactive; only sum gw, sum gw^2 were accumulated
+constexpr float kSumsComplement = 2.f;   // caps inactive, every width above 1/2: q[1] = sum ec, q[3] = sum ec^2
+
+__device__ __forceinline__ RowScore finish_score(const double* s, double S, float mode, const RowArgs& A)
 {
     // s = { sum gl, sum gw, sum gl^2, sum gw^2, sum gl gw } over the V tokens of the row, with
     // p^l_i = Bc gl_i and p^u_i - p^l_i = Wc gw_i (tensor-radius mode: the per-token factors are already
-    // inside gl and gw);
-    // capless = the caps are known to be inactive and only sum gw, sum gw^2 were accumulated
+    // inside gl and gw)
     const double V = (double)A.V;
+    if (mode == kSumsComplement) {
+        // delta_i = 1 - ec_i:  Omega = V - sum ec,  Var(delta) = Var(ec), the latter taken among the small
+        // ec_i themselves instead of among numbers that all round to 1
+        RowScore o;
+        o.alpha_l = 1.0; o.alpha_u = 1.0;
+        o.omega = V - s[1];
+        o.sigma = sqrt(fmax(0.0, s[3] - s[1] * s[1] / V) / V);
+        o.score = o.omega * o.sigma;
+        return o;
+    }
+    const bool capless = mode == kSumsWidthOnly;
     const double Bc = (A.radius ? 1.0 : A.b) / S, Wc = (A.radius ? 1.0 : A.a - A.b) / S;
     const double Sl = Bc * s[0], Su = Sl + Wc * s[1];
     RowScore o;

@@ -55,13 +55,18 @@ __global__ __launch_bounds__(256) void rowfinish_kernel(const RowArgs A, const i
             cx = load_logit(crow, xid);
         }
         if (do_q) {
-            const RowScore rs = finish_score(st.q, S, st.capless != 0.f, A);
+            const RowScore rs = finish_score(st.q, S, st.mode, A);
             if (A.omega) A.omega[row] = (float)rs.omega;
             if (A.sigma) A.sigma[row] = (float)rs.sigma;
             if (A.score) A.score[row] = (float)rs.score;
             if (A.flags) A.flags[row] = (uint8_t)(rs.score > A.tau);
             if (A.p_lo || A.p_mid || A.p_hi) {
-                const double x = exp((double)cx - (double)n * kLn2) / S;
+                // e_x exactly as the streaming kernel summed it into S (the arg-max token, the only one whose
+                // probability can approach 1, sits in a wave whose reference is n), so that S - e_x is the
+                // sum of the other tokens to fp64 rounding and 1 - x keeps its relative accuracy as x -> 1:
+                // the lower bound's denominator b + (1-b)(1-x) is that small number when b is small too.
+                const double ex = (double)exp2_ref(cx, n == -INFINITY ? 0.f : n);
+                const double x = ex / S, omx = fmax(0.0, S - ex) / S;
                 double a = A.a, b = A.b;
                 if (A.radius) {
                     // the reported token's own radius (the launcher supplies ids in this mode)
@@ -70,7 +75,7 @@ __global__ __launch_bounds__(256) void rowfinish_kernel(const RowArgs A, const i
                     a = exp(r); b = exp(-r);
                 }
                 if (A.p_mid) A.p_mid[row] = (float)x;
-                if (A.p_lo) A.p_lo[row] = (float)(rs.alpha_l * b * x / (1.0 + (b - 1.0) * x));
+                if (A.p_lo) A.p_lo[row] = (float)(rs.alpha_l * b * x / (b + (1.0 - b) * omx));
                 if (A.p_hi) A.p_hi[row] = (float)(rs.alpha_u * a * x / (1.0 + (a - 1.0) * x));
             }
         }

@@ -14,7 +14,10 @@ constexpr int kMaxHeads = 8;
 // RowStats (partition sum, reference, interval sums -> that head's caps).  One workgroup per position;
 // per token and head the same arithmetic as the streaming kernel's interval pass.
 //   D_i = sum_h delta_{h,i},  Omega = sum_i D_i / H,  Sigma^2 = sum_i D_i^2 / (H^2 V) - (Omega / V)^2.
-template <typename T>
+// WIDE (calls with a wide radius, see wide_radius): also C_i = sum_h (1 - width_{h,i}); where every mean width is
+// above 1/2 and no head has an active cap, D_i = H - C_i, and Omega and Sigma are taken from the sums of C_i,
+// which resolve a spread that the widths, all rounding to 1, no longer show.
+template <typename T, bool WIDE>
 __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const int H, const int64_t head_stride)
 {
     using E = Elt<T>;
@@ -22,7 +25,7 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
     __shared__ FuseRow sm_fr[kMaxHeads];
     __shared__ float sm_n[kMaxHeads], sm_invS[kMaxHeads];
     __shared__ double sm_cw[kMaxHeads], sm_cl[kMaxHeads], sm_S[kMaxHeads], sm_al[kMaxHeads], sm_au[kMaxHeads];
-    __shared__ double sm_red[2][4];
+    __shared__ double sm_red[5][4];
     __shared__ float sm_pm[4];
     __shared__ int sm_pi[4];
 
@@ -35,7 +38,7 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
 
     if (tid < H) {
         const RowStats st = A.stats[(int64_t)tid * A.N + row];
-        const RowScore rs = finish_score(st.q, st.S, st.capless != 0.f, A);
+        const RowScore rs = finish_score(st.q, st.S, st.mode, A);
         const double Bc = (rad ? 1.0 : A.b) / st.S, Wc = (rad ? 1.0 : A.a - A.b) / st.S;
         sm_fr[tid] = fuse_row(st.S, A.a, A.b);
         sm_n[tid] = st.n;
@@ -49,16 +52,17 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
     const float kap = (float)A.kappa, rmax = (float)A.rmax;
     const int nvec = (V + EPV - 1) / EPV;
     double s1 = 0.0, s2 = 0.0;
+    double c1 = 0.0, c2 = 0.0, cbig = 0.0;                         // WIDE: sum C_i, sum C_i^2, max C_i
     float best = -INFINITY;
     int best_i = INT_MAX;
     if (tiny) {
         // A handful of tokens (one vector per lane at most): widths are O(1) and Sigma can be an exact zero
         // (two tokens), which fp32 token arithmetic cannot resolve to 1e-7; the few tokens are done in fp64.
         if (tid < nvec) {
-            double D[EPV];
+            double D[EPV], C[EPV];
             float pm[EPV];
 #pragma unroll
-            for (int k = 0; k < EPV; ++k) { D[k] = 0.0; pm[k] = 0.f; }
+            for (int k = 0; k < EPV; ++k) { D[k] = 0.0; C[k] = 0.0; pm[k] = 0.f; }
             for (int h = 0; h < H; ++h) {
                 const gvec c = (gvec)(gbytes)(static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride);
                 const gvec r = (gvec)(gbytes)(static_cast<const T*>(rad ? A.radius : A.draft) +
@@ -69,13 +73,17 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
                 E::unpack(rw4, rv);
                 for (int k = 0; k < EPV; ++k) {
                     if (tid * EPV + k < V) {
-                        const double x = exp((double)cv[k] - (double)sm_n[h] * kLn2) / sm_S[h];
+                        // e as the streaming kernel summed it into S: 1 - x stays accurate as x -> 1
+                        const double ed = (double)exp2_ref(cv[k], sm_n[h]);
+                        const double x = ed / sm_S[h], omx = fmax(0.0, sm_S[h] - ed) / sm_S[h];
                         double a = A.a, b = A.b;
                         if (rad) {
                             const double rr = radius_of((double)rv[k], A.kappa, A.rmax);
                             a = exp(rr); b = exp(-rr);
                         }
-                        D[k] += sm_au[h] * a * x / (1.0 + (a - 1.0) * x) - sm_al[h] * b * x / (1.0 + (b - 1.0) * x);
+                        const double du = 1.0 + (a - 1.0) * x, dl = b + (1.0 - b) * omx;
+                        D[k] += sm_au[h] * a * x / du - sm_al[h] * b * x / dl;
+                        if constexpr (WIDE) C[k] += (1.0 - 2.0 * (1.0 - b) * x * omx) / (du * dl);
                         pm[k] += (float)x;
                     }
                 }
@@ -84,6 +92,9 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
                 const int tok = tid * EPV + k;
                 s1 += D[k];
                 s2 = fma(D[k], D[k], s2);
+                if constexpr (WIDE) {
+                    if (tok < V) { c1 += C[k]; c2 = fma(C[k], C[k], c2); cbig = fmax(cbig, C[k]); }
+                }
                 if (need_argmax && tok < V && pm[k] > best) { best = pm[k]; best_i = tok; }
             }
         }
@@ -91,11 +102,15 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
     constexpr int UB = 16 / EPV;                                   // vectors of a head in flight per lane
     for (int v0 = tid; !tiny && v0 < nvec; v0 += 256 * UB) {
         double D[UB][EPV];                                         // fp64 across heads
+        double C[WIDE ? UB : 1][EPV];
         float pm[UB][EPV];
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
 #pragma unroll
-            for (int k = 0; k < EPV; ++k) { D[u][k] = 0.0; pm[u][k] = 0.f; }
+            for (int k = 0; k < EPV; ++k) {
+                D[u][k] = 0.0; pm[u][k] = 0.f;
+                if constexpr (WIDE) C[u][k] = 0.0;
+            }
         }
         for (int h = 0; h < H; ++h) {
             const gvec c = (gvec)(gbytes)(static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride);
@@ -122,8 +137,15 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
                     if (tok0 + k < V) {
                         const float e = exp2_ref(cv[k], n);
                         float gl, gw;
-                        if (rad) fuse_token_rad(e, rv[k], fr, kap, rmax, gl, gw);
-                        else fuse_token(e, fr, gl, gw);
+                        if constexpr (WIDE) {
+                            float ec;
+                            if (rad) fuse_token_rad_wide(e, rv[k], fr, kap, rmax, gl, gw, ec);
+                            else fuse_token_wide(e, fr, gl, gw, ec);
+                            C[u][k] += (double)ec;
+                        } else {
+                            if (rad) fuse_token_rad(e, rv[k], fr, kap, rmax, gl, gw);
+                            else fuse_token(e, fr, gl, gw);
+                        }
                         D[u][k] = fma(cw, (double)gw, fma(cl, (double)gl, D[u][k]));
                         pm[u][k] = fmaf(e, invS, pm[u][k]);
                     }
@@ -138,6 +160,10 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
                 const double d = D[u][k];                          // tokens past V contribute exactly 0
                 s1 += d;
                 s2 = fma(d, d, s2);
+                if constexpr (WIDE) {
+                    const double c = C[u][k];
+                    c1 += c; c2 = fma(c, c, c2); cbig = fmax(cbig, c);
+                }
                 if (need_argmax && tok < V && pm[u][k] > best) { best = pm[u][k]; best_i = tok; }
             }
         }
@@ -145,6 +171,12 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
     s1 = wave_sum(s1);
     s2 = wave_sum(s2);
     if (lane == 0) { sm_red[0][wave] = s1; sm_red[1][wave] = s2; }
+    if constexpr (WIDE) {
+        c1 = wave_sum(c1);
+        c2 = wave_sum(c2);
+        cbig = (double)wave_max((float)cbig);
+        if (lane == 0) { sm_red[2][wave] = c1; sm_red[3][wave] = c2; sm_red[4][wave] = cbig; }
+    }
     if (need_argmax) {
         // each lane walked its tokens in ascending order, so it holds its lowest index of its maximum
         const float wm = wave_max(best);
@@ -156,8 +188,19 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
         const double t1 = (sm_red[0][0] + sm_red[0][1]) + (sm_red[0][2] + sm_red[0][3]);
         const double t2 = (sm_red[1][0] + sm_red[1][1]) + (sm_red[1][2] + sm_red[1][3]);
         const double Hd = (double)H, Vd = (double)V;
-        const double omega = t1 / Hd;
-        const double var = fmax(0.0, t2 / (Hd * Hd) - omega * omega / Vd) / Vd;
+        double omega = t1 / Hd;
+        double var = fmax(0.0, t2 / (Hd * Hd) - omega * omega / Vd) / Vd;
+        if constexpr (WIDE) {
+            const double u1 = (sm_red[2][0] + sm_red[2][1]) + (sm_red[2][2] + sm_red[2][3]);
+            const double u2 = (sm_red[3][0] + sm_red[3][1]) + (sm_red[3][2] + sm_red[3][3]);
+            const double ub = fmax(fmax(sm_red[4][0], sm_red[4][1]), fmax(sm_red[4][2], sm_red[4][3]));
+            bool plain = ub < 0.5 * Hd;                            // every mean width above 1/2
+            for (int h = 0; h < H; ++h) plain = plain && sm_al[h] == 1.0 && sm_au[h] == 1.0;
+            if (plain) {
+                omega = Vd - u1 / Hd;
+                var = fmax(0.0, u2 - u1 * u1 / Vd) / (Hd * Hd * Vd);
+            }
+        }
         const double sigma = sqrt(var), score = omega * sigma;
         if (A.omega) A.omega[row] = (float)omega;
         if (A.sigma) A.sigma[row] = (float)sigma;
@@ -177,7 +220,8 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
             double lo = 0.0, mid = 0.0, hi = 0.0;
             for (int h = 0; h < H; ++h) {
                 const T* crow = static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride;
-                const double x = exp((double)load_logit(crow, xid) - (double)sm_n[h] * kLn2) / sm_S[h];
+                const double ex = (double)exp2_ref(load_logit(crow, xid), sm_n[h]);
+                const double x = ex / sm_S[h], omx = fmax(0.0, sm_S[h] - ex) / sm_S[h];
                 double a = A.a, b = A.b;
                 if (rad) {
                     const T* rrow = static_cast<const T*>(A.radius) + (int64_t)h * head_stride + row * A.stride;
@@ -185,7 +229,7 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
                     a = exp(r); b = exp(-r);
                 }
                 mid += x;
-                lo += sm_al[h] * b * x / (1.0 + (b - 1.0) * x);
+                lo += sm_al[h] * b * x / (b + (1.0 - b) * omx);
                 hi += sm_au[h] * a * x / (1.0 + (a - 1.0) * x);
             }
             if (A.p_lo) A.p_lo[row] = (float)(lo / Hd);
@@ -214,8 +258,13 @@ hipError_t launch_ensemble(int dtype, const RowArgs& args, int heads, int64_t he
 {
     if (args.N <= 0) return hipSuccess;
     const dim3 grid((unsigned)args.N), block(256);
-    if (dtype == 0) hipLaunchKernelGGL(ensemble_kernel<float>, grid, block, 0, stream, args, heads, head_stride);
-    else hipLaunchKernelGGL(ensemble_kernel<bf16_t>, grid, block, 0, stream, args, heads, head_stride);
+    if (wide_radius(args)) {
+        if (dtype == 0) hipLaunchKernelGGL((ensemble_kernel<float, true>), grid, block, 0, stream, args, heads, head_stride);
+        else hipLaunchKernelGGL((ensemble_kernel<bf16_t, true>), grid, block, 0, stream, args, heads, head_stride);
+    } else {
+        if (dtype == 0) hipLaunchKernelGGL((ensemble_kernel<float, false>), grid, block, 0, stream, args, heads, head_stride);
+        else hipLaunchKernelGGL((ensemble_kernel<bf16_t, false>), grid, block, 0, stream, args, heads, head_stride);
+    }
     return hipGetLastError();
 }
 

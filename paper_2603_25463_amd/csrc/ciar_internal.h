@@ -16,7 +16,8 @@ struct RowStats {
     float  n;        // integer-valued reference of the centre row
     float  nt;       // integer-valued reference of the verifier row
     float  mc;       // largest centre logit (the arg-max token's logit)
-    float  capless;  // 1 = the caps are inactive for this row and only q[1], q[3] were accumulated
+    float  mode;     // 0 = all five sums; 1 = caps inactive, only q[1], q[3] were accumulated;
+                     // 2 = caps inactive and every width above 1/2: q[1], q[3] hold the sums of 1 - width
 };
 static_assert(sizeof(RowStats) == 72, "RowStats layout");
 
@@ -51,6 +52,14 @@ struct RowArgs {
 };
 
 enum class Mode { Quantify, Verify, Fused };
+
+// Radii from which the kernels also accumulate the complements of the widths (e^6 x_i >> 1 for most tokens of
+// a row makes the widths crowd against 1, where fp32 widths no longer resolve their own spread).
+constexpr double kWideRadius = 6.0;
+inline bool wide_radius(const RowArgs& a)
+{
+    return a.radius ? (a.kappa > 0.0 && a.rmax >= kWideRadius) : (a.a >= 403.4287934927351 /* e^6 */);
+}
 
 // Largest vocabulary the register-resident streaming kernels cover for an element size.
 int max_vocab(int dtype);

@@ -112,20 +112,51 @@ __device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const Fu
     q5[4] = a4[0] + a4[1];
 }
 
+// Pass C for calls with a wide radius (see wide_radius): the five sums and, over the tokens that exist, the
+// complements ec_i = 1 - width_i: q[5] = sum ec, q[6] = sum ec^2, q[7] = the lane's largest ec.
+template <int THREADS, int NVEC, int EPV>
+__device__ __forceinline__ void fuse_sums_wide(const float (&e)[NVEC * EPV], const FuseRow& fr, int V, int tid,
+                                               double (&q)[8])
+{
+    double acc[7] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+    float big = 0.f;
+#pragma unroll
+    for (int j = 0; j < NVEC; ++j) {
+        if (j * THREADS * EPV >= V) continue;                      // uniform: the chunk holds no token
+#pragma unroll
+        for (int k = 0; k < EPV; ++k) {
+            float gl, gw, ec;
+            fuse_token_wide(e[j * EPV + k], fr, gl, gw, ec);
+            if ((j * THREADS + tid) * EPV + k >= V) ec = 0.f;      // padding (gl = gw = 0 there already)
+            const double dl = (double)gl, dw = (double)gw, dc = (double)ec;
+            acc[0] += dl; acc[1] += dw;
+            acc[2] = fma(dl, dl, acc[2]); acc[3] = fma(dw, dw, acc[3]); acc[4] = fma(dl, dw, acc[4]);
+            acc[5] += dc; acc[6] = fma(dc, dc, acc[6]);
+            big = fmaxf(big, ec);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int i = 0; i < 7; ++i) q[i] = acc[i];
+    q[7] = (double)big;
+}
+
 // Pass C for a handful of tokens (V <= kTinyVocab), in fp64 from the fp32 e_i.  With so few tokens the widths
 // are O(1) and Sigma can be an exact zero (two tokens: delta_1 = delta_2 identically, because x_1 + x_2 = 1
 // holds for the computed x as well); fp32 token arithmetic leaves ~1e-7 there, fp64 keeps the symmetry.
 // Same units as fuse_sums / fuse_sums_rad: gl, gw per token with p^l = Bc gl, p^u - p^l = Wc gw.
 
-template <typename T, int EPV, bool RAD>
+// WIDE: also the complement sums of fuse_sums_wide; first_tok = index of the lane's first token.
+template <typename T, int EPV, bool RAD, bool WIDE>
 __device__ __forceinline__ void fuse_sums_tiny(const float (&e)[EPV], const u32x4& rad, double S_units, double a,
-                                               double b, double kappa, double rmax, double (&q5)[5])
+                                               double b, double kappa, double rmax, int first_tok, int V,
+                                               double (&q5)[WIDE ? 8 : 5])
 {
     float raw[EPV];
     Elt<T>::unpack(rad, raw);
     const double invS = 1.0 / S_units;
 #pragma unroll
-    for (int i = 0; i < 5; ++i) q5[i] = 0.0;
+    for (int i = 0; i < (WIDE ? 8 : 5); ++i) q5[i] = 0.0;
 #pragma unroll
     for (int k = 0; k < EPV; ++k) {
         const double ed = (double)e[k], x = ed * invS;
@@ -134,22 +165,32 @@ __device__ __forceinline__ void fuse_sums_tiny(const float (&e)[EPV], const u32x
             const double r = radius_of((double)raw[k], kappa, rmax);
             ak = exp(r); bk = exp(-r);
         }
-        const double om = 1.0 - x, du = 1.0 + (ak - 1.0) * x, dl = 1.0 - (1.0 - bk) * x;
+        const double om = 1.0 - x, du = 1.0 + (ak - 1.0) * x, dl = bk + (1.0 - bk) * om;   // dl = 1 - (1-b) x
         double gl = ed / dl, gw = ed * om / (du * dl);
         if constexpr (RAD) { gl *= bk; gw *= ak - bk; }
         q5[0] += gl; q5[1] += gw;
         q5[2] = fma(gl, gl, q5[2]); q5[3] = fma(gw, gw, q5[3]); q5[4] = fma(gl, gw, q5[4]);
+        if constexpr (WIDE) {
+            if (first_tok + k < V) {
+                const double ec = (1.0 - 2.0 * (1.0 - bk) * x * om) / (du * dl);
+                q5[5] += ec; q5[6] = fma(ec, ec, q5[6]); q5[7] = fmax(q5[7], ec);
+            }
+        }
     }
 }
 
 // Pass C in tensor-radius mode: every token has its own a_i, b_i from the raw radius row `rad` (as loaded,
 // padding already zeroed); the sums are of p^l_i S and (p^u_i - p^l_i) S themselves.
-template <typename T, int THREADS, int NVEC>
+// WIDE: also the complement sums of fuse_sums_wide.
+template <typename T, int THREADS, int NVEC, bool WIDE>
 __device__ __forceinline__ void fuse_sums_rad(const float (&e)[NVEC * Elt<T>::kPerVec], const u32x4 (&rad)[NVEC],
-                                              const FuseRow& fr, float kappa, float rmax, int V, double (&q5)[5])
+                                              const FuseRow& fr, float kappa, float rmax, int V, int tid,
+                                              double (&q5)[WIDE ? 8 : 5])
 {
     constexpr int EPV = Elt<T>::kPerVec;
     double a0[2] = {0.0, 0.0}, a1[2] = {0.0, 0.0}, a2[2] = {0.0, 0.0}, a3[2] = {0.0, 0.0}, a4[2] = {0.0, 0.0};
+    double c1 = 0.0, c2 = 0.0;
+    float big = 0.f;
 #pragma unroll
     for (int j = 0; j < NVEC; ++j) {
         if (j * THREADS * EPV >= V) continue;                      // uniform: the chunk holds no token
@@ -158,7 +199,16 @@ __device__ __forceinline__ void fuse_sums_rad(const float (&e)[NVEC * Elt<T>::kP
 #pragma unroll
         for (int k = 0; k < EPV; ++k) {
             float pl, w;
-            fuse_token_rad(e[j * EPV + k], raw[k], fr, kappa, rmax, pl, w);   // padding has e = 0: pl = w = 0
+            if constexpr (WIDE) {
+                float ec;
+                fuse_token_rad_wide(e[j * EPV + k], raw[k], fr, kappa, rmax, pl, w, ec);
+                if ((j * THREADS + tid) * EPV + k >= V) ec = 0.f;  // padding
+                const double dc = (double)ec;
+                c1 += dc; c2 = fma(dc, dc, c2);
+                big = fmaxf(big, ec);
+            } else {
+                fuse_token_rad(e[j * EPV + k], raw[k], fr, kappa, rmax, pl, w);   // padding has e = 0: pl = w = 0
+            }
             const double dl = (double)pl, dw = (double)w;
             a0[k & 1] += dl;
             a1[k & 1] += dw;
@@ -173,9 +223,10 @@ __device__ __forceinline__ void fuse_sums_rad(const float (&e)[NVEC * Elt<T>::kP
     q5[2] = a2[0] + a2[1];
     q5[3] = a3[0] + a3[1];
     q5[4] = a4[0] + a4[1];
+    if constexpr (WIDE) { q5[5] = c1; q5[6] = c2; q5[7] = (double)big; }
 }
 
-template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V, bool RAD>
+template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V, bool RAD, bool WIDE>
 __global__ __launch_bounds__(THREADS)
 __attribute__((amdgpu_waves_per_eu(target_waves<T, THREADS, NVEC, RAD>())))
 void stream_kernel(const RowArgs A)
@@ -188,10 +239,11 @@ void stream_kernel(const RowArgs A)
     // The verifier row is requested before the interval pass where a second row fits in the registers at
     // four waves per SIMD next to the centre row's floats (fp32 tiles of up to 8 vectors per lane; measured
     // 51 -> 48.6 us on the benchmark); elsewhere it would spill, and it is requested after the pass.
-    constexpr bool EARLY_T = DO_V && !RAD && (EPT + NVEC * 4 + 56) * 4 <= 512;
+    constexpr bool EARLY_T = DO_V && !RAD && !WIDE && (EPT + NVEC * 4 + 56) * 4 <= 512;
     // Quantify-only launches have no verifier row; under the same condition the next centre row is requested
     // before the interval pass instead.
-    constexpr bool EARLY_NEXT = !DO_V && !RAD && (EPT + NVEC * 4 + 56) * 4 <= 512;
+    constexpr bool EARLY_NEXT = !DO_V && !RAD && !WIDE && (EPT + NVEC * 4 + 56) * 4 <= 512;
+    constexpr int NQ = WIDE ? 8 : 5;                // interval sums a wave hands over
 
     // Exchange slots.  Two barriers per row order every write against every read: the centre-row
     // slots are written before the first and read between the two, the others are written between the
@@ -200,7 +252,7 @@ void stream_kernel(const RowArgs A)
     __shared__ double sm_S[NW];                     // per wave: S_w
     __shared__ float  sm_nt[NW];                    // per wave: nt_w
     __shared__ double sm_Z[NW];                     // per wave: Z_w
-    __shared__ double sm_q5[NW * 5];                // per wave: the five interval sums, already in row units
+    __shared__ double sm_q5[NW * NQ];               // per wave: the interval sums, already in row units
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int V = A.V;
@@ -356,7 +408,7 @@ void stream_kernel(const RowArgs A)
         if constexpr (DO_Q) {
             // x_i = e_i fw / S: hand fuse_row the partition sum expressed in this wave's units
             const FuseRow fr = fuse_row(fw > 0.0 ? S / fw : 1.0, A.a, A.b);
-            double q5[5];
+            double q5[NQ];
             bool tiny = false;
             if constexpr (NVEC == 1) tiny = V <= kTinyVocab;       // uniform
             if (tiny) {
@@ -366,7 +418,8 @@ void stream_kernel(const RowArgs A)
                         load_row(buf, A.radius, row);
                         E::zero_tail(buf[0], tid * EPV, V);
                     }
-                    fuse_sums_tiny<T, EPV, RAD>(e, buf[0], fw > 0.0 ? S / fw : 1.0, A.a, A.b, A.kappa, A.rmax, q5);
+                    fuse_sums_tiny<T, EPV, RAD, WIDE>(e, buf[0], fw > 0.0 ? S / fw : 1.0, A.a, A.b, A.kappa, A.rmax,
+                                                      tid * EPV, V, q5);
 #pragma unroll
                     for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
                 }
@@ -378,7 +431,11 @@ void stream_kernel(const RowArgs A)
 #pragma unroll
                     for (int j = 0; j < NVEC; ++j) E::zero_tail(buf[j], (j * THREADS + tid) * EPV, V);
                 }
-                fuse_sums_rad<T, THREADS, NVEC>(e, buf, fr, (float)A.kappa, (float)A.rmax, V, q5);
+                fuse_sums_rad<T, THREADS, NVEC, WIDE>(e, buf, fr, (float)A.kappa, (float)A.rmax, V, tid, q5);
+#pragma unroll
+                for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
+            } else if constexpr (WIDE) {
+                fuse_sums_wide<THREADS, NVEC, EPV>(e, fr, V, tid, q5);
 #pragma unroll
                 for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
             } else if (capless) {
@@ -391,10 +448,19 @@ void stream_kernel(const RowArgs A)
 #pragma unroll
                 for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
             }
+            if constexpr (WIDE) {
+                q5[5] = wave_sum(q5[5]);
+                q5[6] = wave_sum(q5[6]);
+                q5[7] = (double)wave_max((float)q5[7]);
+            }
             if (lane == 0) {
                 const double f2 = fw * fw;
-                sm_q5[wave * 5 + 0] = q5[0] * fw; sm_q5[wave * 5 + 1] = q5[1] * fw;
-                sm_q5[wave * 5 + 2] = q5[2] * f2; sm_q5[wave * 5 + 3] = q5[3] * f2; sm_q5[wave * 5 + 4] = q5[4] * f2;
+                sm_q5[wave * NQ + 0] = q5[0] * fw; sm_q5[wave * NQ + 1] = q5[1] * fw;
+                sm_q5[wave * NQ + 2] = q5[2] * f2; sm_q5[wave * NQ + 3] = q5[3] * f2; sm_q5[wave * NQ + 4] = q5[4] * f2;
+                if constexpr (WIDE) {
+                    // the complements are plain numbers: no units to rescale
+                    sm_q5[wave * NQ + 5] = q5[5]; sm_q5[wave * NQ + 6] = q5[6]; sm_q5[wave * NQ + 7] = q5[7];
+                }
             }
         }
 
@@ -431,16 +497,27 @@ void stream_kernel(const RowArgs A)
                 }
             }
             RowStats* st = A.stats + row;
-            st->S = S; st->Z = Z; st->n = n; st->nt = nt; st->mc = mc; st->capless = capless ? 1.f : 0.f;
+            st->S = S; st->Z = Z; st->n = n; st->nt = nt; st->mc = mc;
+            double t[NQ];
 #pragma unroll
-            for (int i = 0; i < 5; ++i) {
-                double t = 0.0;
+            for (int i = 0; i < NQ; ++i) {
+                t[i] = 0.0;
                 if constexpr (DO_Q) {
 #pragma unroll
-                    for (int w = 0; w < NW; ++w) t += sm_q5[w * 5 + i];
+                    for (int w = 0; w < NW; ++w) t[i] = i == 7 ? fmax(t[i], sm_q5[w * NQ + i]) : t[i] + sm_q5[w * NQ + i];
                 }
-                st->q[i] = t;
             }
+            float mode = (capless && !WIDE) ? kSumsWidthOnly : kSumsFull;
+            if constexpr (WIDE && DO_Q) {
+                // every width above 1/2 and both caps inactive: the finishing kernels read the complement sums
+                if (t[7] < 0.5) {
+                    const RowScore rs = finish_score(t, S, kSumsFull, A);
+                    if (rs.alpha_l == 1.0 && rs.alpha_u == 1.0) { t[1] = t[5]; t[3] = t[6]; mode = kSumsComplement; }
+                }
+            }
+            st->mode = mode;
+#pragma unroll
+            for (int i = 0; i < 5; ++i) st->q[i] = t[i];
         }
 
         if (!has_next) break;
@@ -450,7 +527,7 @@ void stream_kernel(const RowArgs A)
 
 // ---- dispatch ---------------------------------------------------------------------------------------------
 
-template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V, bool RAD>
+template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V, bool RAD, bool WIDE = false>
 hipError_t launch_stream_kernel(const RowArgs& a, hipStream_t s)
 {
     // One wave of resident workgroups, each walking over rows with stride gridDim.x.  The register
@@ -460,7 +537,7 @@ hipError_t launch_stream_kernel(const RowArgs& a, hipStream_t s)
     constexpr int per_cu = target_waves<T, THREADS, NVEC, RAD>() * 256 / THREADS;
     const int64_t resident = (int64_t)per_cu * compute_units();
     const unsigned grid = (unsigned)(a.N < resident ? a.N : resident);
-    hipLaunchKernelGGL((stream_kernel<T, THREADS, NVEC, DO_Q, DO_V, RAD>), dim3(grid), dim3(THREADS), 0, s, a);
+    hipLaunchKernelGGL((stream_kernel<T, THREADS, NVEC, DO_Q, DO_V, RAD, WIDE>), dim3(grid), dim3(THREADS), 0, s, a);
     return hipGetLastError();
 }
 
@@ -468,6 +545,14 @@ template <typename T, int THREADS, int NVEC>
 hipError_t launch_stream_cfg(Mode mode, const RowArgs& a, hipStream_t s)
 {
     const bool rad = a.radius != nullptr;
+    if (mode != Mode::Verify && wide_radius(a)) {
+        // radii at which the widths crowd against 1: the variants that also accumulate their complements
+        if (mode == Mode::Quantify)
+            return rad ? launch_stream_kernel<T, THREADS, NVEC, true, false, true, true>(a, s)
+                       : launch_stream_kernel<T, THREADS, NVEC, true, false, false, true>(a, s);
+        return rad ? launch_stream_kernel<T, THREADS, NVEC, true, true, true, true>(a, s)
+                   : launch_stream_kernel<T, THREADS, NVEC, true, true, false, true>(a, s);
+    }
     switch (mode) {
     case Mode::Quantify: return rad ? launch_stream_kernel<T, THREADS, NVEC, true, false, true>(a, s)
                                     : launch_stream_kernel<T, THREADS, NVEC, true, false, false>(a, s);
