@@ -25,7 +25,7 @@
  *     p = softmax(centre logits), q = softmax(target logits).
  *
  * Every sum runs sequentially in index order, in double precision.  There is no blocking,
- * no fusion and no reordering.  Only tests/, __graft_entry__.smoke() and the cpu_baseline
+ * no fusion and no reordering (one sum is taken twice, with and without its largest term: see row_rest).  Only tests/, __graft_entry__.smoke() and the cpu_baseline
  * leg of bench.py may call this file; the product path never does.  It shares no code with
  * the HIP kernels.
  *
@@ -114,31 +114,50 @@ static double token_radius(const ciar_oracle_params* P, double kappa, const void
 
 /* ---- one row of the quantifier -------------------------------------------------------- */
 
-/* Fills e[i] = exp(c_i - max c) and returns S = sum_i e[i]; *m_out = max c. */
-static double row_exponentials(const void* logits, const ciar_oracle_params* P, int64_t row,
-                               double* e, double* m_out)
+/* What row_interfuse needs besides S: sum_{j != i} e[j].  For every token but the largest this is S - e[i]
+ * (e[i] <= S / 2: nothing cancels).  For the largest token S - e[i] would cancel -- when it holds nearly all of
+ * the mass, S has already dropped what lies below half an ulp of it -- so its sum over the others is formed
+ * directly. */
+typedef struct {
+    int    imax;        /* lowest index of the largest e[i] */
+    double rest_imax;   /* sum_{j != imax} e[j], summed in index order without e[imax] */
+} row_rest;
+
+/* Fills e[i] = exp(c_i - max c) and returns S = sum_i e[i]; *m_out = max c; *rest (may be NULL) as above. */
+static double row_exponentials_ext(const void* logits, const ciar_oracle_params* P, int64_t row,
+                                   double* e, double* m_out, row_rest* rest)
 {
     const int64_t off = row * P->row_stride;
     const int V = P->vocab;
     double m = -INFINITY;
+    int imax = 0;
     for (int i = 0; i < V; ++i) {
         double c = load_logit(logits, P->dtype, off + i);
-        if (c > m) m = c;
+        if (c > m) { m = c; imax = i; }
     }
-    double S = 0.0;
+    double S = 0.0, others = 0.0;
     for (int i = 0; i < V; ++i) {
         double c = load_logit(logits, P->dtype, off + i);
         e[i] = exp(c - m);
         S += e[i];
+        if (i != imax) others += e[i];
     }
     *m_out = m;
+    if (rest) { rest->imax = imax; rest->rest_imax = others; }
     return S;
 }
 
+static double row_exponentials(const void* logits, const ciar_oracle_params* P, int64_t row,
+                               double* e, double* m_out)
+{
+    return row_exponentials_ext(logits, P, row, e, m_out, NULL);
+}
+
 /* InterFuse bounds for the whole row, normalised if requested.
- * In: e[i], S, the raw radius tensor (NULL: scalar mode) and the row.  Out: pl[i], pu[i] (the final,
- * possibly scaled, bounds). */
-static void row_interfuse(const double* e, double S, const ciar_oracle_params* P,
+ * In: e[i], S and the sum over the others of the largest token (see row_rest), the raw radius tensor (NULL:
+ * scalar mode) and the row.  Out: pl[i], pu[i] (the final, possibly scaled, bounds).
+ * The defining equations have sum_{j != i} exp(o_j) in the denominator. */
+static void row_interfuse(const double* e, double S, const row_rest* rest, const ciar_oracle_params* P,
                           const void* radius, int64_t row, double* pl, double* pu)
 {
     const int V = P->vocab;
@@ -148,8 +167,9 @@ static void row_interfuse(const double* e, double S, const ciar_oracle_params* P
         const double r = token_radius(P, kappa, radius, row * P->row_stride + i);
         double down = e[i] * exp(-r);   /* exp(c_i - r_i) up to the common shift */
         double up   = e[i] * exp(r);    /* exp(c_i + r_i) up to the common shift */
-        pl[i] = down / (S - e[i] + down);
-        pu[i] = up / (S - e[i] + up);
+        const double others = i == rest->imax ? rest->rest_imax : S - e[i];   /* sum over the other tokens */
+        pl[i] = down / (others + down);
+        pu[i] = up / (others + up);
         Sl += pl[i];
         Su += pu[i];
     }
@@ -197,8 +217,9 @@ int ciar_oracle_quantify(const void* draft, const void* radius, const int32_t* i
 #pragma omp for schedule(static)
             for (int64_t row = 0; row < N; ++row) {
                 double m;
-                double S = row_exponentials(draft, P, row, e, &m);
-                row_interfuse(e, S, P, radius, row, pl, pu);
+                row_rest rest;
+                double S = row_exponentials_ext(draft, P, row, e, &m, &rest);
+                row_interfuse(e, S, &rest, P, radius, row, pl, pu);
 
                 /* widths, L1 norm, population standard deviation (two passes) */
                 double Om = 0.0;
@@ -236,8 +257,9 @@ int ciar_oracle_dense_intervals(const void* draft, const void* radius, int64_t N
     if (!e) return -1;
     for (int64_t row = 0; row < N; ++row) {
         double m;
-        double S = row_exponentials(draft, P, row, e, &m);
-        row_interfuse(e, S, P, radius, row, p_lo + row * (int64_t)V, p_hi + row * (int64_t)V);
+        row_rest rest;
+        double S = row_exponentials_ext(draft, P, row, e, &m, &rest);
+        row_interfuse(e, S, &rest, P, radius, row, p_lo + row * (int64_t)V, p_hi + row * (int64_t)V);
         for (int i = 0; i < V; ++i) p_mid[row * (int64_t)V + i] = e[i] / S;
     }
     free(e);
@@ -322,8 +344,9 @@ int ciar_oracle_quantify_multihead(const void* draft, const void* radius, int32_
                     const void* c = head_base(draft, P->dtype, h, head_stride);
                     const void* r = head_base(radius, P->dtype, h, head_stride);
                     double m;
-                    double S = row_exponentials(c, P, row, e, &m);
-                    row_interfuse(e, S, P, r, row, pl, pu);
+                    row_rest rest;
+                    double S = row_exponentials_ext(c, P, row, e, &m, &rest);
+                    row_interfuse(e, S, &rest, P, r, row, pl, pu);
                     for (int i = 0; i < V; ++i) { apl[i] += pl[i]; apm[i] += e[i] / S; apu[i] += pu[i]; }
                 }
                 for (int i = 0; i < V; ++i) { apl[i] /= (double)H; apm[i] /= (double)H; apu[i] /= (double)H; }

@@ -176,6 +176,42 @@ def test_one_hot_row_closed_form(oracle):
     np.testing.assert_allclose(q["p_hi"], 1.01, rtol=1e-12)   # the caps may lift p^u above 1
 
 
+def test_dominant_token_bounds_against_50_digit_arithmetic(oracle):
+    """A token that holds all but 1e-13 of the mass, thousands of others each below an ulp of 1, and a radius
+    with e^-r ~ 1e-7: the dominant token's lower bound is 1 / (1 + rest / e^-r) with rest = the sum over the
+    OTHER tokens, as the defining equations of the validity appendix have it.  Evaluated here with Python's
+    decimal module at 50 digits straight from those equations; a partition sum that has already absorbed the
+    dominant term cannot give rest back by subtraction (off by tens of percent in double)."""
+    from decimal import Decimal, getcontext
+    getcontext().prec = 50
+    rng = np.random.default_rng(44)
+    V = 6000
+    c = (rng.standard_normal((1, V)) * 1.5).astype(np.float32)
+    c[0, 1234] = 42.25
+    r = 15.5
+    P = oracle.Params(kappa=r, radius_max=16.0, normalize=False)
+    lo, mid, hi = oracle.dense_intervals(c, P)
+    cs = [Decimal(float(v)) for v in c[0]]
+    m = max(cs)
+    es = [(v - m).exp() for v in cs]
+    a, b = Decimal(r).exp(), (-Decimal(r)).exp()
+    for i in (1234, 0, 17):
+        rest = sum(e for k, e in enumerate(es) if k != i)
+        pl = es[i] * b / (rest + es[i] * b)
+        pu = es[i] * a / (rest + es[i] * a)
+        # compare the distances from 1 (dominant token) or the values themselves (the others)
+        if i == 1234:
+            assert abs(Decimal(1) - Decimal(float(lo[0, i])) - (1 - pl)) < Decimal(1e-9) * (1 - pl) + Decimal(2e-16)
+            assert float(1 - pl) > 1e-8                              # the test has something to resolve
+        else:
+            assert abs(Decimal(float(lo[0, i])) - pl) < Decimal(1e-12) * pl
+        assert abs(Decimal(float(hi[0, i])) - pu) < Decimal(1e-12) * pu + Decimal(2e-16)
+    q = oracle.quantify(c, np.array([1234]), P)
+    S = sum(es)
+    width = sum(es[i] * a / (S - es[i] + es[i] * a) - es[i] * b / (S - es[i] + es[i] * b) for i in range(V))
+    assert abs(Decimal(float(q["omega"][0])) - width) < Decimal(1e-9) * width
+
+
 # ---- the score -----------------------------------------------------------------------------
 
 def test_omega_sigma_score_against_numpy_on_the_dense_curves(oracle):
