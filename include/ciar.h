@@ -74,10 +74,11 @@ typedef enum ciar_status {
  *         = sqrt(2) * erfinv(confidence) otherwise (two-sided standard-normal quantile of the
  *           "interval confidence" gamma in (0,1): 0.8 -> 1.2816, 0.9 -> 1.6449, 0.95 -> 1.9600).
  * radius_max is the clamp the paper applies without naming a value (App. "Proof of Interval
- * Validity", last paragraph).  Accepted range [0, 20] (CIAR_EINVAL outside it): at radius 20 the bounds of a
- * token are its probability scaled by e^20 = 4.9e8 either way in the odds; beyond that the lower bound of the top
- * token of a nearly one-hot row is a quotient of two numbers below 1e-9 (e^-r and 1 - x_max) that the fp64
- * partition sum no longer resolves to the library's 1e-5 relative accuracy.
+ * Validity", last paragraph).  Accepted range [0, 16] (CIAR_EINVAL outside it): at radius 16 the bounds of a
+ * token are its probability with the odds scaled by e^16 = 8.9e6 either way.  Beyond that the bounds of the top
+ * token of a nearly one-hot row are quotients of e^-r and 1 - x_max: its width is (1 - x_max) / e^-r with
+ * 1 - x_max known to 4e-15 from fp32 exponentials, which stops meeting the library's 1e-7 absolute accuracy
+ * at e^-r = 4e-8.
  */
 typedef struct ciar_params {
     uint32_t struct_size;   /* sizeof(ciar_params); checked                                        */
@@ -87,7 +88,7 @@ typedef struct ciar_params {
     int64_t  row_stride;    /* elements between consecutive rows                                   */
     float    confidence;    /* gamma, used when radius_scale < 0                                   */
     float    radius_scale;  /* kappa override, < 0 = derive from confidence                        */
-    float    radius_max;    /* clamp on the radius, in [0, 20], default 10                         */
+    float    radius_max;    /* clamp on the radius, in [0, 16], default 10                         */
     float    tau;           /* threshold on U, default 0.30 (Algorithm 1; Sec. 4 threshold study)  */
     float    lower_cap;     /* 0.99 (normalisation equations of the validity appendix)             */
     float    upper_cap;     /* 1.01                                                                */
@@ -101,7 +102,7 @@ void ciar_params_default(ciar_params* p);
 
 /*
  * Bytes of device workspace ciar_quantify / ciar_verify / ciar_quantify_verify need for N rows
- * (81 bytes per row, rounded up).  Always a multiple of 256; returns 0 for N <= 0.
+ * (97 bytes per row, rounded up).  Always a multiple of 256; returns 0 for N <= 0.
  */
 size_t ciar_workspace_bytes(int64_t N, const ciar_params* params);
 

@@ -67,8 +67,8 @@ int check_params(const ciar_params* p, Resolved* out)
         return fail(CIAR_EALIGN, "row_stride * element size = %lld bytes is not a multiple of 16",
                     (long long)(p->row_stride * elt));
     if (p->window < 1) return fail(CIAR_EINVAL, "params->window must be >= 1 (got %d)", p->window);
-    if (!(p->radius_max >= 0.0f) || !(p->radius_max <= 20.0f))
-        return fail(CIAR_EINVAL, "params->radius_max must be in [0, 20] (got %g)", (double)p->radius_max);
+    if (!(p->radius_max >= 0.0f) || !(p->radius_max <= 16.0f))
+        return fail(CIAR_EINVAL, "params->radius_max must be in [0, 16] (got %g)", (double)p->radius_max);
     if (!std::isfinite(p->tau)) return fail(CIAR_EINVAL, "params->tau must be finite");
     if (!(p->lower_cap > 0.0f) || !(p->lower_cap <= 1.0f) || !(p->upper_cap >= 1.0f) ||
         !std::isfinite(p->upper_cap))

@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void dense_kernel(const RowArgs A, float* __re
         q5[0] = block_sum(a0); q5[1] = block_sum(a1); q5[2] = block_sum(a2);
         q5[3] = block_sum(a3); q5[4] = block_sum(a4);
     }
-    const RowScore rs = finish_score(q5, S, kSumsFull, A);
+    const RowScore rs = finish_score(q5, S, kSumsFull, A, 0.0, 0.0);
 
     const float Bc = (float)((rad ? 1.0 : A.b) / S), Wc = (float)((rad ? 1.0 : A.a - A.b) / S), invS = (float)(1.0 / S);
     const float al = (float)rs.alpha_l, au = (float)rs.alpha_u;

@@ -211,16 +211,24 @@ __device__ __forceinline__ FuseRow fuse_row(double S, double a, double b)
     return r;
 }
 
-// gl = e du / (du dl) and gw = e (1-x) / (du dl):  p^l = (b/S) gl,  w = p^u - p^l = ((a-b)/S) gw.
+// One token of the scalar-radius interval pass:  g = e / (du dl), so that gl = g du and gw = g om (om = 1 - x)
+// with p^l = (b/S) gl and w = p^u - p^l = ((a-b)/S) gw.
 // SPLIT = form 1 - x with the two-float 1/S.  It matters only when some x is close to 1 (the relative
 // error of 1 - x is 6e-8 x / (1 - x) without it); rows whose largest probability is at most 1/2 skip it.
 template <bool SPLIT = true>
+__device__ __forceinline__ void fuse_parts(float e, const FuseRow& r, float& g, float& du, float& om)
+{
+    om = SPLIT ? fmaf(e, r.nil, fmaf(e, r.nih, 1.0f)) : fmaf(e, r.nih, 1.0f);   // 1 - x
+    du = fmaf(e, r.cu, 1.0f);
+    const float dl = fmaf(om, r.omb, r.b);
+    g = e * __builtin_amdgcn_rcpf(du * dl);
+}
+
+template <bool SPLIT = true>
 __device__ __forceinline__ void fuse_token(float e, const FuseRow& r, float& gl, float& gw)
 {
-    const float om = SPLIT ? fmaf(e, r.nil, fmaf(e, r.nih, 1.0f)) : fmaf(e, r.nih, 1.0f);   // 1 - x
-    const float du = fmaf(e, r.cu, 1.0f);
-    const float dl = fmaf(om, r.omb, r.b);
-    const float g = e * __builtin_amdgcn_rcpf(du * dl);
+    float g, du, om;
+    fuse_parts<SPLIT>(e, r, g, du, om);
     gl = g * du;
     gw = g * om;
 }
@@ -304,25 +312,36 @@ constexpr float kSumsFull = 0.f;         // all five sums
 constexpr float kSumsWidthOnly = 1.f;    // the caps are known to be inactive; only sum gw, sum gw^2 were accumulated
 constexpr float kSumsComplement = 2.f;   // caps inactive, every width above 1/2: q[1] = sum ec, q[3] = sum ec^2
 
-__device__ __forceinline__ RowScore finish_score(const double* s, double S, float mode, const RowArgs& A)
+// The sums arrive shifted: s = { sum (gl - kl), sum (gw - kw), sum (gl - kl)^2, sum (gw - kw)^2,
+// sum (gl - kl)(gw - kw) } over the V tokens of the row, where (kl, kw) are the values of one of the row's own
+// tokens.  Sums and sums of squares taken about such a point lose at most a factor V of fp64's 1e-16 when the
+// squared mean is subtracted, however small the spread is against the mean (a row of equal logits has spread 0
+// and mean > 0: about the origin the difference of the two moments is rounding noise of relative size 1e-8
+// after the square root, which Omega ~ V then multiplies).  Pass kl = kw = 0 for plain sums.
+__device__ __forceinline__ RowScore finish_score(const double* s, double S, float mode, const RowArgs& A,
+                                                 double kl, double kw)
 {
-    // s = { sum gl, sum gw, sum gl^2, sum gw^2, sum gl gw } over the V tokens of the row, with
     // p^l_i = Bc gl_i and p^u_i - p^l_i = Wc gw_i (tensor-radius mode: the per-token factors are already
     // inside gl and gw)
     const double V = (double)A.V;
     if (mode == kSumsComplement) {
-        // delta_i = 1 - ec_i:  Omega = V - sum ec,  Var(delta) = Var(ec), the latter taken among the small
-        // ec_i themselves instead of among numbers that all round to 1
+        // s[1], s[3]: sums of (ec_i - kw) and its square, ec_i = 1 - delta_i:  Omega = V - sum ec,
+        // Var(delta) = Var(ec), the latter taken among the small ec_i themselves instead of among numbers that
+        // all round to 1
         RowScore o;
         o.alpha_l = 1.0; o.alpha_u = 1.0;
-        o.omega = V - s[1];
+        o.omega = V - (s[1] + V * kw);
         o.sigma = sqrt(fmax(0.0, s[3] - s[1] * s[1] / V) / V);
         o.score = o.omega * o.sigma;
         return o;
     }
     const bool capless = mode == kSumsWidthOnly;
     const double Bc = (A.radius ? 1.0 : A.b) / S, Wc = (A.radius ? 1.0 : A.a - A.b) / S;
-    const double Sl = Bc * s[0], Su = Sl + Wc * s[1];
+    const double sum_gl = s[0] + V * kl, sum_gw = s[1] + V * kw;
+    // S_l <= 1 <= S_u holds for every radius (p^l_i <= x_i <= p^u_i token by token); the computed sums carry ~1e-7
+    // of fp32 token arithmetic and may land on the wrong side of 1 for a one-hot row, which a cap of exactly 1
+    // would turn into a spurious scaling
+    const double Sl = fmin(1.0, Bc * sum_gl), Su = fmax(1.0, Bc * sum_gl + Wc * sum_gw);
     RowScore o;
     o.alpha_l = 1.0; o.alpha_u = 1.0;
     if (A.normalize && !capless) {
@@ -330,13 +349,13 @@ __device__ __forceinline__ RowScore finish_score(const double* s, double S, floa
         o.alpha_u = fmax(1.0, A.cap_hi / Su);
     }
     // delta_i = alpha_u p^u_i - alpha_l p^l_i = alpha_u w_i + (alpha_u - alpha_l) p^l_i = cw gw_i + cl gl_i:
-    // both coefficients are >= 0, so Omega and the second moment are sums of non-negative terms.
+    // both coefficients are >= 0, so Omega is a sum of non-negative terms; the spread is that of
+    // delta_i - (cw kw + cl kl) = cw (gw_i - kw) + cl (gl_i - kl).
     const double cw = o.alpha_u * Wc, cl = (o.alpha_u - o.alpha_l) * Bc;
-    o.omega = cw * s[1] + cl * s[0];
-    const double Q = cw * cw * s[3] + 2.0 * cw * cl * s[4] + cl * cl * s[2];
-    // fp64 sums: the subtraction of the squared mean costs at most ~1/CV^2 of 1e-16
-    const double var = fmax(0.0, Q - o.omega * o.omega / V) / V;
-    o.sigma = sqrt(var);
+    o.omega = cw * sum_gw + (capless ? 0.0 : cl * sum_gl);
+    const double T1 = cw * s[1] + cl * s[0];
+    const double T2 = cw * cw * s[3] + 2.0 * cw * cl * s[4] + cl * cl * s[2];
+    o.sigma = sqrt(fmax(0.0, T2 - T1 * T1 / V) / V);
     o.score = o.omega * o.sigma;
     return o;
 }

@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256) void rowfinish_kernel(const RowArgs A, const i
             cx = load_logit(crow, xid);
         }
         if (do_q) {
-            const RowScore rs = finish_score(st.q, S, st.mode, A);
+            const RowScore rs = finish_score(st.q, S, st.mode, A, st.kl, st.kw);
             if (A.omega) A.omega[row] = (float)rs.omega;
             if (A.sigma) A.sigma[row] = (float)rs.sigma;
             if (A.score) A.score[row] = (float)rs.score;

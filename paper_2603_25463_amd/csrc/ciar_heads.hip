@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
 
     if (tid < H) {
         const RowStats st = A.stats[(int64_t)tid * A.N + row];
-        const RowScore rs = finish_score(st.q, st.S, st.mode, A);
+        const RowScore rs = finish_score(st.q, st.S, st.mode, A, st.kl, st.kw);
         const double Bc = (rad ? 1.0 : A.b) / st.S, Wc = (rad ? 1.0 : A.a - A.b) / st.S;
         sm_fr[tid] = fuse_row(st.S, A.a, A.b);
         sm_n[tid] = st.n;
@@ -51,8 +51,50 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
 
     const float kap = (float)A.kappa, rmax = (float)A.rmax;
     const int nvec = (V + EPV - 1) / EPV;
-    double s1 = 0.0, s2 = 0.0;
-    double c1 = 0.0, c2 = 0.0, cbig = 0.0;                         // WIDE: sum C_i, sum C_i^2, max C_i
+    // One head's share of a token: its width after the head's caps (added to d) and, WIDE, its complement (to c).
+    auto head_token = [&](int h, float cval, float rval, const FuseRow& fr, double& d, double& c) {
+        const float e = exp2_ref(cval, sm_n[h]);
+        float gl, gw;
+        if constexpr (WIDE) {
+            float ec;
+            if (rad) fuse_token_rad_wide(e, rval, fr, kap, rmax, gl, gw, ec);
+            else fuse_token_wide(e, fr, gl, gw, ec);
+            c += (double)ec;
+        } else {
+            if (rad) fuse_token_rad(e, rval, fr, kap, rmax, gl, gw);
+            else fuse_token(e, fr, gl, gw);
+        }
+        d = fma(sm_cw[h], (double)gw, fma(sm_cl[h], (double)gl, d));
+        return e;
+    };
+    // The same in fp64 from the fp32 e (rows of a handful of tokens).
+    auto head_token_tiny = [&](int h, float cval, float rval, double& d, double& c) {
+        // e as the streaming kernel summed it into S: 1 - x stays accurate as x -> 1
+        const double ed = (double)exp2_ref(cval, sm_n[h]);
+        const double x = ed / sm_S[h], omx = fmax(0.0, sm_S[h] - ed) / sm_S[h];
+        double a = A.a, b = A.b;
+        if (rad) {
+            const double rr = radius_of((double)rval, A.kappa, A.rmax);
+            a = exp(rr); b = exp(-rr);
+        }
+        const double du = 1.0 + (a - 1.0) * x, dl = b + (1.0 - b) * omx;
+        d += sm_au[h] * a * x / du - sm_al[h] * b * x / dl;
+        if constexpr (WIDE) c += (1.0 - 2.0 * (1.0 - b) * x * omx) / (du * dl);
+        return x;
+    };
+    // The sums over the tokens are taken about D and C of the row's first token (every lane forms the same two
+    // numbers): the spread of a row whose widths all agree is then 0 instead of the rounding noise that the
+    // difference of two large moments leaves.
+    double KD = 0.0, KC = 0.0;
+    for (int h = 0; h < H; ++h) {
+        const T* crow = static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride;
+        const T* rrow = static_cast<const T*>(rad ? A.radius : A.draft) + (int64_t)h * head_stride + row * A.stride;
+        const float c0 = load_logit(crow, 0), r0 = load_logit(rrow, 0);
+        if (tiny) head_token_tiny(h, c0, r0, KD, KC);
+        else head_token(h, c0, r0, sm_fr[h], KD, KC);
+    }
+    double s1 = 0.0, s2 = 0.0;                                     // sum (D_i - KD), sum (D_i - KD)^2
+    double c1 = 0.0, c2 = 0.0, cbig = 0.0;                         // WIDE: sum (C_i - KC), its square, max C_i
     float best = -INFINITY;
     int best_i = INT_MAX;
     if (tiny) {
@@ -72,28 +114,19 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
                 E::unpack(cw4, cv);
                 E::unpack(rw4, rv);
                 for (int k = 0; k < EPV; ++k) {
-                    if (tid * EPV + k < V) {
-                        // e as the streaming kernel summed it into S: 1 - x stays accurate as x -> 1
-                        const double ed = (double)exp2_ref(cv[k], sm_n[h]);
-                        const double x = ed / sm_S[h], omx = fmax(0.0, sm_S[h] - ed) / sm_S[h];
-                        double a = A.a, b = A.b;
-                        if (rad) {
-                            const double rr = radius_of((double)rv[k], A.kappa, A.rmax);
-                            a = exp(rr); b = exp(-rr);
-                        }
-                        const double du = 1.0 + (a - 1.0) * x, dl = b + (1.0 - b) * omx;
-                        D[k] += sm_au[h] * a * x / du - sm_al[h] * b * x / dl;
-                        if constexpr (WIDE) C[k] += (1.0 - 2.0 * (1.0 - b) * x * omx) / (du * dl);
-                        pm[k] += (float)x;
-                    }
+                    if (tid * EPV + k < V) pm[k] += (float)head_token_tiny(h, cv[k], rv[k], D[k], C[k]);
                 }
             }
             for (int k = 0; k < EPV; ++k) {
                 const int tok = tid * EPV + k;
-                s1 += D[k];
-                s2 = fma(D[k], D[k], s2);
-                if constexpr (WIDE) {
-                    if (tok < V) { c1 += C[k]; c2 = fma(C[k], C[k], c2); cbig = fmax(cbig, C[k]); }
+                if (tok < V) {
+                    const double d = D[k] - KD;
+                    s1 += d;
+                    s2 = fma(d, d, s2);
+                    if constexpr (WIDE) {
+                        const double c = C[k] - KC;
+                        c1 += c; c2 = fma(c, c, c2); cbig = fmax(cbig, C[k]);
+                    }
                 }
                 if (need_argmax && tok < V && pm[k] > best) { best = pm[k]; best_i = tok; }
             }
@@ -124,8 +157,7 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
                 for (int u = 0; u < UB; ++u) rw4[u] = r[min(v0 + u * 256, nvec - 1)];
             }
             const FuseRow fr = sm_fr[h];
-            const float n = sm_n[h], invS = sm_invS[h];
-            const double cw = sm_cw[h], cl = sm_cl[h];
+            const float invS = sm_invS[h];
 #pragma unroll
             for (int u = 0; u < UB; ++u) {
                 const int tok0 = (v0 + u * 256) * EPV;             // >= V for vectors past the row's end
@@ -135,18 +167,7 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
 #pragma unroll
                 for (int k = 0; k < EPV; ++k) {
                     if (tok0 + k < V) {
-                        const float e = exp2_ref(cv[k], n);
-                        float gl, gw;
-                        if constexpr (WIDE) {
-                            float ec;
-                            if (rad) fuse_token_rad_wide(e, rv[k], fr, kap, rmax, gl, gw, ec);
-                            else fuse_token_wide(e, fr, gl, gw, ec);
-                            C[u][k] += (double)ec;
-                        } else {
-                            if (rad) fuse_token_rad(e, rv[k], fr, kap, rmax, gl, gw);
-                            else fuse_token(e, fr, gl, gw);
-                        }
-                        D[u][k] = fma(cw, (double)gw, fma(cl, (double)gl, D[u][k]));
+                        const float e = head_token(h, cv[k], rad ? rv[k] : 0.f, fr, D[u][k], C[WIDE ? u : 0][k]);
                         pm[u][k] = fmaf(e, invS, pm[u][k]);
                     }
                 }
@@ -157,12 +178,14 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
 #pragma unroll
             for (int k = 0; k < EPV; ++k) {
                 const int tok = (v0 + u * 256) * EPV + k;
-                const double d = D[u][k];                          // tokens past V contribute exactly 0
-                s1 += d;
-                s2 = fma(d, d, s2);
-                if constexpr (WIDE) {
-                    const double c = C[u][k];
-                    c1 += c; c2 = fma(c, c, c2); cbig = fmax(cbig, c);
+                if (tok < V) {
+                    const double d = D[u][k] - KD;
+                    s1 += d;
+                    s2 = fma(d, d, s2);
+                    if constexpr (WIDE) {
+                        const double c = C[u][k] - KC;
+                        c1 += c; c2 = fma(c, c, c2); cbig = fmax(cbig, C[u][k]);
+                    }
                 }
                 if (need_argmax && tok < V && pm[u][k] > best) { best = pm[u][k]; best_i = tok; }
             }
@@ -188,8 +211,9 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
         const double t1 = (sm_red[0][0] + sm_red[0][1]) + (sm_red[0][2] + sm_red[0][3]);
         const double t2 = (sm_red[1][0] + sm_red[1][1]) + (sm_red[1][2] + sm_red[1][3]);
         const double Hd = (double)H, Vd = (double)V;
-        double omega = t1 / Hd;
-        double var = fmax(0.0, t2 / (Hd * Hd) - omega * omega / Vd) / Vd;
+        // t1 = sum (D_i - KD), t2 = sum (D_i - KD)^2
+        double omega = (t1 + Vd * KD) / Hd;
+        double var = fmax(0.0, t2 - t1 * t1 / Vd) / (Hd * Hd * Vd);
         if constexpr (WIDE) {
             const double u1 = (sm_red[2][0] + sm_red[2][1]) + (sm_red[2][2] + sm_red[2][3]);
             const double u2 = (sm_red[3][0] + sm_red[3][1]) + (sm_red[3][2] + sm_red[3][3]);
@@ -197,7 +221,7 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
             bool plain = ub < 0.5 * Hd;                            // every mean width above 1/2
             for (int h = 0; h < H; ++h) plain = plain && sm_al[h] == 1.0 && sm_au[h] == 1.0;
             if (plain) {
-                omega = Vd - u1 / Hd;
+                omega = Vd - (u1 + Vd * KC) / Hd;
                 var = fmax(0.0, u2 - u1 * u1 / Vd) / (Hd * Hd * Vd);
             }
         }

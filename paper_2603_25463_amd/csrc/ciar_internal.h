@@ -12,14 +12,16 @@ namespace ciar {
 struct RowStats {
     double S;        // partition sum of the centre row in units of 2^-n
     double Z;        // partition sum of the verifier row in units of 2^-nt
-    double q[5];     // sum gl, sum gw, sum gl^2, sum gw^2, sum gl gw  (InterFuse sums, units of e)
+    double q[5];     // InterFuse sums about the shift (kl, kw), units of e: sum (gl - kl), sum (gw - kw),
+                     // sum (gl - kl)^2, sum (gw - kw)^2, sum (gl - kl)(gw - kw)
+    double kl, kw;   // the shift: gl and gw of the row's first token
     float  n;        // integer-valued reference of the centre row
     float  nt;       // integer-valued reference of the verifier row
     float  mc;       // largest centre logit (the arg-max token's logit)
     float  mode;     // 0 = all five sums; 1 = caps inactive, only q[1], q[3] were accumulated;
                      // 2 = caps inactive and every width above 1/2: q[1], q[3] hold the sums of 1 - width
 };
-static_assert(sizeof(RowStats) == 72, "RowStats layout");
+static_assert(sizeof(RowStats) == 88, "RowStats layout");
 
 // Everything the kernels need, passed by value.  All pointers are device pointers.
 struct RowArgs {

@@ -72,32 +72,51 @@ constexpr int target_waves()
     return fit < lo ? lo : (fit > 4 ? 4 : fit);
 }
 
-// Pass C for one lane: the InterFuse sums over the lane's tokens.
-// Chunks past the end of a row that does not fill the tile are skipped (padding inside the last chunk
-// has e = 0 and adds exactly nothing).
+// The interval sums of a row are taken about the values (kl, kw, kc) of the row's first token: sum (gl - kl),
+// sum (gw - kw) and their second moments.  Subtracting the squared mean from a second moment taken about one of
+// the data loses at most a factor V of fp64's 1e-16, however small the spread is against the mean; about the
+// origin a row of equal logits (spread 0, mean > 0) leaves rounding noise of relative size 1e-8 in Sigma, which
+// Omega ~ V multiplies.  Every wave forms the shift itself from that token's e rescaled to its own units, a power
+// of two, so the shifts agree bit for bit once they are back in row units and the waves' sums simply add.
+struct Shift { float kl, kw, kc; };
+
+// Pass C for one lane: the shifted InterFuse sums over the lane's tokens.  gl - kl and gw - kw come out of the
+// FMA that would otherwise have been the multiplication g du, g om: the shift costs no instruction.
+// Chunks past the end of a row that does not fill the tile are skipped.
 // WIDTH_ONLY = the caps are known to be inactive for this row (alpha_l = alpha_u = 1), so
-// delta_i = w_i and only sum gw and sum gw^2 are needed.
-// SPLIT = see fuse_token.
-template <int THREADS, int NVEC, int EPV, bool WIDTH_ONLY, bool SPLIT>
-__device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const FuseRow& fr, int V,
-                                          double (&q5)[5])
+// delta_i = w_i and only the sums of gw are needed.
+// SPLIT = see fuse_parts.
+// MASK = the row does not fill the tile: slots past its end contribute nothing (they hold e = 0, which would
+// otherwise enter as 0 - k).
+template <int THREADS, int NVEC, int EPV, bool WIDTH_ONLY, bool SPLIT, bool MASK>
+__device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const FuseRow& fr_in, const Shift& sh, int V,
+                                          int tid, double (&q5)[5])
 {
-    // The sums run in fp64 from the first add (fp64 adds and FMAs issue at the fp32 rate on this
-    // chip).  One token can hold almost all of sum(gl), and the variance is a difference of second
-    // moments that would cancel in fp32 on nearly flat rows; in fp64 neither needs a centring trick.
+    // The caller branches between several instances of this pass.  The row constants go through an empty asm
+    // so that each instance has its own: otherwise the optimiser hoists the sub-expressions the instances share
+    // (1 + cu e for every token of the lane) above the branch and spills them.
+    FuseRow fr = fr_in;
+    asm volatile("" : "+v"(fr.cu), "+v"(fr.nih));
+    // The sums run in fp64 from the first add (fp64 adds and FMAs issue at the fp32 rate on this chip): one
+    // token can hold almost all of a sum.
     double a0[2] = {0.0, 0.0}, a1[2] = {0.0, 0.0}, a2[2] = {0.0, 0.0}, a3[2] = {0.0, 0.0}, a4[2] = {0.0, 0.0};
 #pragma unroll
     for (int j = 0; j < NVEC; ++j) {
         if (j * THREADS * EPV >= V) continue;                      // uniform: the chunk holds no token
 #pragma unroll
         for (int k = 0; k < EPV; ++k) {
-            float gl, gw;
-            fuse_token<SPLIT>(e[j * EPV + k], fr, gl, gw);         // padding has e = 0: gl = gw = 0
-            const double dw = (double)gw;
+            float g, du, om;
+            fuse_parts<SPLIT>(e[j * EPV + k], fr, g, du, om);
+            const bool live = !MASK || (j * THREADS + tid) * EPV + k < V;
+            float sw = fmaf(g, om, -sh.kw);
+            if (!live) sw = 0.f;
+            const double dw = (double)sw;
             a1[k & 1] += dw;
             a3[k & 1] = fma(dw, dw, a3[k & 1]);
             if constexpr (!WIDTH_ONLY) {
-                const double dl = (double)gl;
+                float sl = fmaf(g, du, -sh.kl);
+                if (!live) sl = 0.f;
+                const double dl = (double)sl;
                 a0[k & 1] += dl;
                 a2[k & 1] = fma(dl, dl, a2[k & 1]);
                 a4[k & 1] = fma(dl, dw, a4[k & 1]);
@@ -112,11 +131,12 @@ __device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const Fu
     q5[4] = a4[0] + a4[1];
 }
 
-// Pass C for calls with a wide radius (see wide_radius): the five sums and, over the tokens that exist, the
-// complements ec_i = 1 - width_i: q[5] = sum ec, q[6] = sum ec^2, q[7] = the lane's largest ec.
+// Pass C for calls with a wide radius (see wide_radius): the five shifted sums and the complements
+// ec_i = 1 - width_i over the tokens that exist: q[5] = sum (ec - kc), q[6] = sum (ec - kc)^2, q[7] = the
+// lane's largest ec.
 template <int THREADS, int NVEC, int EPV>
-__device__ __forceinline__ void fuse_sums_wide(const float (&e)[NVEC * EPV], const FuseRow& fr, int V, int tid,
-                                               double (&q)[8])
+__device__ __forceinline__ void fuse_sums_wide(const float (&e)[NVEC * EPV], const FuseRow& fr, const Shift& sh,
+                                               int V, int tid, double (&q)[8])
 {
     double acc[7] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
     float big = 0.f;
@@ -127,12 +147,13 @@ __device__ __forceinline__ void fuse_sums_wide(const float (&e)[NVEC * EPV], con
         for (int k = 0; k < EPV; ++k) {
             float gl, gw, ec;
             fuse_token_wide(e[j * EPV + k], fr, gl, gw, ec);
-            if ((j * THREADS + tid) * EPV + k >= V) ec = 0.f;      // padding (gl = gw = 0 there already)
-            const double dl = (double)gl, dw = (double)gw, dc = (double)ec;
-            acc[0] += dl; acc[1] += dw;
-            acc[2] = fma(dl, dl, acc[2]); acc[3] = fma(dw, dw, acc[3]); acc[4] = fma(dl, dw, acc[4]);
-            acc[5] += dc; acc[6] = fma(dc, dc, acc[6]);
-            big = fmaxf(big, ec);
+            if ((j * THREADS + tid) * EPV + k < V) {
+                const double dl = (double)(gl - sh.kl), dw = (double)(gw - sh.kw), dc = (double)(ec - sh.kc);
+                acc[0] += dl; acc[1] += dw;
+                acc[2] = fma(dl, dl, acc[2]); acc[3] = fma(dw, dw, acc[3]); acc[4] = fma(dl, dw, acc[4]);
+                acc[5] += dc; acc[6] = fma(dc, dc, acc[6]);
+                big = fmaxf(big, ec);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -144,48 +165,59 @@ __device__ __forceinline__ void fuse_sums_wide(const float (&e)[NVEC * EPV], con
 // Pass C for a handful of tokens (V <= kTinyVocab), in fp64 from the fp32 e_i.  With so few tokens the widths
 // are O(1) and Sigma can be an exact zero (two tokens: delta_1 = delta_2 identically, because x_1 + x_2 = 1
 // holds for the computed x as well); fp32 token arithmetic leaves ~1e-7 there, fp64 keeps the symmetry.
-// Same units as fuse_sums / fuse_sums_rad: gl, gw per token with p^l = Bc gl, p^u - p^l = Wc gw.
-
+// Same units as fuse_sums / fuse_sums_rad: gl, gw per token with p^l = Bc gl, p^u - p^l = Wc gw; the shift
+// (the values of the row's first token, which lane 0 of wave 0 holds) is returned in kq.
 // WIDE: also the complement sums of fuse_sums_wide; first_tok = index of the lane's first token.
 template <typename T, int EPV, bool RAD, bool WIDE>
 __device__ __forceinline__ void fuse_sums_tiny(const float (&e)[EPV], const u32x4& rad, double S_units, double a,
                                                double b, double kappa, double rmax, int first_tok, int V,
-                                               double (&q5)[WIDE ? 8 : 5])
+                                               double (&q5)[WIDE ? 8 : 5], double (&kq)[3])
 {
     float raw[EPV];
     Elt<T>::unpack(rad, raw);
     const double invS = 1.0 / S_units;
+    auto token = [&](float ef, float rawf, double& gl, double& gw, double& ec) {
+        const double ed = (double)ef, x = ed * invS;
+        double ak = a, bk = b;
+        if constexpr (RAD) {
+            const double r = radius_of((double)rawf, kappa, rmax);
+            ak = exp(r); bk = exp(-r);
+        }
+        const double om = 1.0 - x, du = 1.0 + (ak - 1.0) * x, dl = bk + (1.0 - bk) * om;   // dl = 1 - (1-b) x
+        gl = ed / dl; gw = ed * om / (du * dl);
+        if constexpr (RAD) { gl *= bk; gw *= ak - bk; }
+        ec = (1.0 - 2.0 * (1.0 - bk) * x * om) / (du * dl);
+    };
+    // the same reference in every lane: lane 0's first token
+    const float e_ref = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(e[0])));
+    const float raw_ref = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(raw[0])));
+    token(e_ref, raw_ref, kq[0], kq[1], kq[2]);
 #pragma unroll
     for (int i = 0; i < (WIDE ? 8 : 5); ++i) q5[i] = 0.0;
 #pragma unroll
     for (int k = 0; k < EPV; ++k) {
-        const double ed = (double)e[k], x = ed * invS;
-        double ak = a, bk = b;
-        if constexpr (RAD) {
-            const double r = radius_of((double)raw[k], kappa, rmax);
-            ak = exp(r); bk = exp(-r);
-        }
-        const double om = 1.0 - x, du = 1.0 + (ak - 1.0) * x, dl = bk + (1.0 - bk) * om;   // dl = 1 - (1-b) x
-        double gl = ed / dl, gw = ed * om / (du * dl);
-        if constexpr (RAD) { gl *= bk; gw *= ak - bk; }
-        q5[0] += gl; q5[1] += gw;
-        q5[2] = fma(gl, gl, q5[2]); q5[3] = fma(gw, gw, q5[3]); q5[4] = fma(gl, gw, q5[4]);
-        if constexpr (WIDE) {
-            if (first_tok + k < V) {
-                const double ec = (1.0 - 2.0 * (1.0 - bk) * x * om) / (du * dl);
-                q5[5] += ec; q5[6] = fma(ec, ec, q5[6]); q5[7] = fmax(q5[7], ec);
+        if (first_tok + k < V) {
+            double gl, gw, ec;
+            token(e[k], raw[k], gl, gw, ec);
+            gl -= kq[0]; gw -= kq[1];
+            q5[0] += gl; q5[1] += gw;
+            q5[2] = fma(gl, gl, q5[2]); q5[3] = fma(gw, gw, q5[3]); q5[4] = fma(gl, gw, q5[4]);
+            if constexpr (WIDE) {
+                q5[7] = fmax(q5[7], ec);
+                ec -= kq[2];
+                q5[5] += ec; q5[6] = fma(ec, ec, q5[6]);
             }
         }
     }
 }
 
 // Pass C in tensor-radius mode: every token has its own a_i, b_i from the raw radius row `rad` (as loaded,
-// padding already zeroed); the sums are of p^l_i S and (p^u_i - p^l_i) S themselves.
+// padding already zeroed); the sums are of p^l_i S and (p^u_i - p^l_i) S themselves, about the shift sh.
 // WIDE: also the complement sums of fuse_sums_wide.
 template <typename T, int THREADS, int NVEC, bool WIDE>
 __device__ __forceinline__ void fuse_sums_rad(const float (&e)[NVEC * Elt<T>::kPerVec], const u32x4 (&rad)[NVEC],
-                                              const FuseRow& fr, float kappa, float rmax, int V, int tid,
-                                              double (&q5)[WIDE ? 8 : 5])
+                                              const FuseRow& fr, float kappa, float rmax, const Shift& sh, int V,
+                                              int tid, double (&q5)[WIDE ? 8 : 5])
 {
     constexpr int EPV = Elt<T>::kPerVec;
     double a0[2] = {0.0, 0.0}, a1[2] = {0.0, 0.0}, a2[2] = {0.0, 0.0}, a3[2] = {0.0, 0.0}, a4[2] = {0.0, 0.0};
@@ -199,17 +231,19 @@ __device__ __forceinline__ void fuse_sums_rad(const float (&e)[NVEC * Elt<T>::kP
 #pragma unroll
         for (int k = 0; k < EPV; ++k) {
             float pl, w;
+            const bool live = (j * THREADS + tid) * EPV + k < V;
             if constexpr (WIDE) {
                 float ec;
                 fuse_token_rad_wide(e[j * EPV + k], raw[k], fr, kappa, rmax, pl, w, ec);
-                if ((j * THREADS + tid) * EPV + k >= V) ec = 0.f;  // padding
-                const double dc = (double)ec;
-                c1 += dc; c2 = fma(dc, dc, c2);
-                big = fmaxf(big, ec);
+                if (live) {
+                    const double dc = (double)(ec - sh.kc);
+                    c1 += dc; c2 = fma(dc, dc, c2);
+                    big = fmaxf(big, ec);
+                }
             } else {
-                fuse_token_rad(e[j * EPV + k], raw[k], fr, kappa, rmax, pl, w);   // padding has e = 0: pl = w = 0
+                fuse_token_rad(e[j * EPV + k], raw[k], fr, kappa, rmax, pl, w);
             }
-            const double dl = (double)pl, dw = (double)w;
+            const double dl = live ? (double)(pl - sh.kl) : 0.0, dw = live ? (double)(w - sh.kw) : 0.0;
             a0[k & 1] += dl;
             a1[k & 1] += dw;
             a2[k & 1] = fma(dl, dl, a2[k & 1]);
@@ -253,6 +287,8 @@ void stream_kernel(const RowArgs A)
     __shared__ float  sm_nt[NW];                    // per wave: nt_w
     __shared__ double sm_Z[NW];                     // per wave: Z_w
     __shared__ double sm_q5[NW * NQ];               // per wave: the interval sums, already in row units
+    __shared__ double sm_k[3];                      // the shift the sums are taken about (row units), from wave 0
+    __shared__ float  sm_e0;                        // e of the row's first token, in the units of wave 0
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int V = A.V;
@@ -332,6 +368,8 @@ void stream_kernel(const RowArgs A)
     for (;;) {
         const int next = __builtin_amdgcn_readfirstlane(row + step);
         const bool has_next = next < nrows;                        // uniform
+        float raw0 = 0.f;                                          // raw radius of the row's first token
+        if constexpr (RAD && DO_Q) raw0 = load_logit(static_cast<const T*>(A.radius) + (int64_t)row * A.stride, 0);
 
         // ---- B: centre row: per-wave max, e_i = 2^(c_i log2e - n_w), S_w -------------------------------
         float e[EPT];
@@ -370,6 +408,7 @@ void stream_kernel(const RowArgs A)
         if (lane == 0) {
             sm_ref[wave * 2] = mcw; sm_ref[wave * 2 + 1] = nw;
             sm_S[wave] = Sw;
+            if (DO_Q && wave == 0) sm_e0 = e[0];
         }
         __syncthreads();
         float mc = sm_ref[0], n = sm_ref[1];
@@ -409,6 +448,26 @@ void stream_kernel(const RowArgs A)
             // x_i = e_i fw / S: hand fuse_row the partition sum expressed in this wave's units
             const FuseRow fr = fuse_row(fw > 0.0 ? S / fw : 1.0, A.a, A.b);
             double q5[NQ];
+            // The shift: the values of the row's first token.  e0 is 2^up times larger in this wave's units than
+            // in wave 0's; a wave more than 2^64 away from wave 0 takes its sums about 0 and its lane 0 moves them
+            // to the common shift afterwards.
+            const float up = sm_ref[1] - nw;
+            const bool near = fabsf(up) <= 64.f;                   // uniform over the wave; false for inf and nan
+            auto shift_of = [&](float e0, const FuseRow& r) {
+                Shift k;
+                k.kc = 0.f;
+                if constexpr (RAD) {
+                    if constexpr (WIDE) fuse_token_rad_wide(e0, raw0, r, (float)A.kappa, (float)A.rmax, k.kl, k.kw, k.kc);
+                    else fuse_token_rad(e0, raw0, r, (float)A.kappa, (float)A.rmax, k.kl, k.kw);
+                } else {
+                    if constexpr (WIDE) fuse_token_wide(e0, r, k.kl, k.kw, k.kc);
+                    else fuse_token<true>(e0, r, k.kl, k.kw);
+                }
+                return k;
+            };
+            Shift sh = {0.f, 0.f, 0.f};
+            if (near) sh = shift_of(ldexpf(sm_e0, (int)up), fr);
+            double kq[3] = {(double)sh.kl, (double)sh.kw, (double)sh.kc};   // fp64 copy (the tiny path sets its own)
             bool tiny = false;
             if constexpr (NVEC == 1) tiny = V <= kTinyVocab;       // uniform
             if (tiny) {
@@ -418,8 +477,9 @@ void stream_kernel(const RowArgs A)
                         load_row(buf, A.radius, row);
                         E::zero_tail(buf[0], tid * EPV, V);
                     }
+                    // all tokens sit in wave 0, whose lane 0 holds the first one
                     fuse_sums_tiny<T, EPV, RAD, WIDE>(e, buf[0], fw > 0.0 ? S / fw : 1.0, A.a, A.b, A.kappa, A.rmax,
-                                                      tid * EPV, V, q5);
+                                                      tid * EPV, V, q5, kq);
 #pragma unroll
                     for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
                 }
@@ -431,20 +491,22 @@ void stream_kernel(const RowArgs A)
 #pragma unroll
                     for (int j = 0; j < NVEC; ++j) E::zero_tail(buf[j], (j * THREADS + tid) * EPV, V);
                 }
-                fuse_sums_rad<T, THREADS, NVEC, WIDE>(e, buf, fr, (float)A.kappa, (float)A.rmax, V, tid, q5);
+                fuse_sums_rad<T, THREADS, NVEC, WIDE>(e, buf, fr, (float)A.kappa, (float)A.rmax, sh, V, tid, q5);
 #pragma unroll
                 for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
             } else if constexpr (WIDE) {
-                fuse_sums_wide<THREADS, NVEC, EPV>(e, fr, V, tid, q5);
+                fuse_sums_wide<THREADS, NVEC, EPV>(e, fr, sh, V, tid, q5);
 #pragma unroll
                 for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
             } else if (capless) {
-                if (split) fuse_sums<THREADS, NVEC, EPV, true, true>(e, fr, V, q5);
-                else       fuse_sums<THREADS, NVEC, EPV, true, false>(e, fr, V, q5);
+                if (partial)    fuse_sums<THREADS, NVEC, EPV, true, true, true>(e, fr, sh, V, tid, q5);
+                else if (split) fuse_sums<THREADS, NVEC, EPV, true, true, false>(e, fr, sh, V, tid, q5);
+                else            fuse_sums<THREADS, NVEC, EPV, true, false, false>(e, fr, sh, V, tid, q5);
                 q5[1] = wave_sum(q5[1]);
                 q5[3] = wave_sum(q5[3]);
             } else {
-                fuse_sums<THREADS, NVEC, EPV, false, true>(e, fr, V, q5);
+                if (partial) fuse_sums<THREADS, NVEC, EPV, false, true, true>(e, fr, sh, V, tid, q5);
+                else         fuse_sums<THREADS, NVEC, EPV, false, true, false>(e, fr, sh, V, tid, q5);
 #pragma unroll
                 for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
             }
@@ -454,13 +516,33 @@ void stream_kernel(const RowArgs A)
                 q5[7] = (double)wave_max((float)q5[7]);
             }
             if (lane == 0) {
+                // to row units (the complements are plain numbers: nothing to rescale)
                 const double f2 = fw * fw;
-                sm_q5[wave * NQ + 0] = q5[0] * fw; sm_q5[wave * NQ + 1] = q5[1] * fw;
-                sm_q5[wave * NQ + 2] = q5[2] * f2; sm_q5[wave * NQ + 3] = q5[3] * f2; sm_q5[wave * NQ + 4] = q5[4] * f2;
-                if constexpr (WIDE) {
-                    // the complements are plain numbers: no units to rescale
-                    sm_q5[wave * NQ + 5] = q5[5]; sm_q5[wave * NQ + 6] = q5[6]; sm_q5[wave * NQ + 7] = q5[7];
+                q5[0] *= fw; q5[1] *= fw; q5[2] *= f2; q5[3] *= f2; q5[4] *= f2;
+                if (!near && !tiny) {
+                    // Rare: this wave's sums are about 0.  Form the common shift in wave 0's units, as wave 0 does,
+                    // and move the sums to it:  with c = 0 - K and n tokens,
+                    //   sum (d - K) = s1 + n c,  sum (d - K)^2 = s2 + 2 c s1 + n c^2,  likewise the cross moment.
+                    const double fw0 = pow2_of(sm_ref[1] - n);
+                    const Shift k0 = shift_of(sm_e0, fuse_row(S / fw0, A.a, A.b));
+                    const double cl = -(double)k0.kl * fw0, cw = -(double)k0.kw * fw0, cc = -(double)k0.kc;
+                    int cnt = 0;                                   // tokens of the row in this wave
+#pragma unroll
+                    for (int j = 0; j < NVEC; ++j) cnt += min(max(V - (j * THREADS + wave * 64) * EPV, 0), 64 * EPV);
+                    const double nn = (double)cnt;
+                    q5[4] += cl * q5[1] + cw * (q5[0] + nn * cl);
+                    q5[2] += cl * (2.0 * q5[0] + nn * cl);
+                    q5[3] += cw * (2.0 * q5[1] + nn * cw);
+                    q5[0] += nn * cl;
+                    q5[1] += nn * cw;
+                    if constexpr (WIDE) {
+                        q5[6] += cc * (2.0 * q5[5] + nn * cc);
+                        q5[5] += nn * cc;
+                    }
                 }
+#pragma unroll
+                for (int i = 0; i < NQ; ++i) sm_q5[wave * NQ + i] = q5[i];
+                if (wave == 0) { sm_k[0] = kq[0] * fw; sm_k[1] = kq[1] * fw; sm_k[2] = kq[2]; }
             }
         }
 
@@ -498,11 +580,15 @@ void stream_kernel(const RowArgs A)
             }
             RowStats* st = A.stats + row;
             st->S = S; st->Z = Z; st->n = n; st->nt = nt; st->mc = mc;
+            // the waves' sums are about one common shift (wave 0 left it in row units): they simply add
             double t[NQ];
 #pragma unroll
-            for (int i = 0; i < NQ; ++i) {
-                t[i] = 0.0;
-                if constexpr (DO_Q) {
+            for (int i = 0; i < NQ; ++i) t[i] = 0.0;
+            double K[3] = {0.0, 0.0, 0.0};
+            if constexpr (DO_Q) {
+                K[0] = sm_k[0]; K[1] = sm_k[1]; K[2] = sm_k[2];
+#pragma unroll
+                for (int i = 0; i < NQ; ++i) {
 #pragma unroll
                     for (int w = 0; w < NW; ++w) t[i] = i == 7 ? fmax(t[i], sm_q5[w * NQ + i]) : t[i] + sm_q5[w * NQ + i];
                 }
@@ -511,10 +597,14 @@ void stream_kernel(const RowArgs A)
             if constexpr (WIDE && DO_Q) {
                 // every width above 1/2 and both caps inactive: the finishing kernels read the complement sums
                 if (t[7] < 0.5) {
-                    const RowScore rs = finish_score(t, S, kSumsFull, A);
-                    if (rs.alpha_l == 1.0 && rs.alpha_u == 1.0) { t[1] = t[5]; t[3] = t[6]; mode = kSumsComplement; }
+                    const RowScore rs = finish_score(t, S, kSumsFull, A, K[0], K[1]);
+                    if (rs.alpha_l == 1.0 && rs.alpha_u == 1.0) {
+                        t[1] = t[5]; t[3] = t[6]; K[1] = K[2];
+                        mode = kSumsComplement;
+                    }
                 }
             }
+            st->kl = K[0]; st->kw = K[1];
             st->mode = mode;
 #pragma unroll
             for (int i = 0; i < 5; ++i) st->q[i] = t[i];
