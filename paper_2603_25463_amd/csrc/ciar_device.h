@@ -168,6 +168,28 @@ __device__ __forceinline__ float wave_max(float v)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_max(double v)
+{
+    // lanes without a source get their own value back
+    const int lo = dpp_or<CTRL, ROW_MASK>(__double2loint(v), __double2loint(v));
+    const int hi = dpp_or<CTRL, ROW_MASK>(__double2hiint(v), __double2hiint(v));
+    return fmax(v, __hiloint2double(hi, lo));
+}
+
+__device__ __forceinline__ double wave_max(double v)
+{
+    v = dpp_max<kRowShr1, 0xf>(v);
+    v = dpp_max<kRowShr2, 0xf>(v);
+    v = dpp_max<kRowShr4, 0xf>(v);
+    v = dpp_max<kRowShr8, 0xf>(v);
+    v = dpp_max<kRowBcast15, 0xa>(v);
+    v = dpp_max<kRowBcast31, 0xc>(v);
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
+    return __hiloint2double(hi, lo);
+}
+
 __device__ __forceinline__ int wave_min_i(int v)
 {
     v = min(v, dpp_or<kRowShr1, 0xf>(v, v));

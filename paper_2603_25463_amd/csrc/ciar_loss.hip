@@ -7,20 +7,37 @@ namespace {
 
 // ---- Inter-DRO loss, forward (Sec. 3.2.3: anchor, DRO and alignment equations) -----------------------------
 
+// e^((c + r) - (c* + r*)) for the token (c*, r*) that carries the row maximum of c + r, formed as
+// (c - c*) + (r - r*): each difference is exact for tokens near the maximum and rounded relative to itself
+// elsewhere, so c + r is never rounded to fp32.  That rounding, 6e-8 |c + r|, is a relative error of the same
+// size in the token's probability, and for logits of magnitude ~30 it shows as ~1e-6 absolute in a cross-entropy
+// (the difference of max + ln S and the p_cloud-weighted mean logit) and in an L1 distance.  The largest token
+// contributes exactly 1 to S.  sign = +1 for c + r, -1 for c - r.
+__device__ __forceinline__ float exp_rel(float c, float r, float cs, float rs, float sign)
+{
+    const float d = fmaf(sign, r - rs, c - cs);
+    return __builtin_amdgcn_exp2f(fmaf(d, kLog2eLo, d * kLog2eHi));
+}
+
+// e^(x - m) for a row of plain logits.
+__device__ __forceinline__ float exp_rel(float x, float m)
+{
+    const float d = x - m;
+    return __builtin_amdgcn_exp2f(fmaf(d, kLog2eLo, d * kLog2eHi));
+}
 
 // Per-row terms of the loss.  One 1024-lane workgroup per row holds the centre, raw-radius and cloud rows as
 // loaded (12 registers per vector) and makes three passes over them: the four maxima (of c, c + r, c - r and
 // the cloud logits), the four partition sums together with sum p_cloud o for the cross-entropies, and the
-// three L1 distances, which need all four normalisers.  With e = 2^(o log2e - n), n = ceil(max log2e):
-//   CE(p_cloud, softmax(o)) = (n ln2 + ln S_o) - (sum_i et_i o_i) / Z,
-//   KL(p_cloud || p_mid)    = (sum_i et_i t_i) / Z - (nt ln2 + ln Z) + CE(p_cloud, p_mid).
+// three L1 distances, which need all four normalisers.  With e = exp(o - max o):
+//   CE(p_cloud, softmax(o)) = (max o + ln S_o) - (sum_i et_i o_i) / Z,
+//   KL(p_cloud || p_mid)    = (sum_i et_i t_i) / Z - (max t + ln Z) + CE(p_cloud, p_mid).
 // terms[k * N + row], k = 0..6: L1(mid), L1(up), L1(lo), CE(mid), CE(up), CE(lo), KL.
 template <typename T, int NVEC>
 __global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* __restrict__ terms)
 {
     using E = Elt<T>;
     constexpr int EPV = E::kPerVec, THREADS = 1024, NW = 16;
-    __shared__ float sm_f[NW * 4];
     __shared__ double sm_d[NW * 7];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t row = blockIdx.x;
@@ -84,38 +101,58 @@ __global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* _
             if (!CACHE_R && rad) asm volatile("" : "+v"(rw[j]));
         }
     };
-    auto block_max4 = [&](float (&m)[4]) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) m[i] = wave_max(m[i]);
-        if (lane == 0) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) sm_f[wave * 4 + i] = m[i];
-        }
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float v = sm_f[i];
-#pragma unroll 1
-            for (int w = 1; w < NW; ++w) v = fmaxf(v, sm_f[w * 4 + i]);
-            m[i] = v;
-        }
-    };
-
-    // pass 1: maxima -> integer references
-    float mx[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    // pass 1: the four maxima; for c + r and c - r also the (c, r) of the token that carries the maximum
+    float mc = -INFINITY, mt = -INFINITY;
+    float su = -INFINITY, cu = 0.f, ru = 0.f;                      // max of c + r and its token
+    float sl = -INFINITY, cl = 0.f, rl = 0.f;                      // max of c - r and its token
 #pragma unroll
     for (int j = 0; j < NVEC; ++j) {
 #pragma unroll
         for (int k = 0; k < EPV; ++k) {
             float c, r, t;
             element(j, k, c, r, t);
-            mx[0] = fmaxf(mx[0], c); mx[1] = fmaxf(mx[1], c + r); mx[2] = fmaxf(mx[2], c - r); mx[3] = fmaxf(mx[3], t);
+            mc = fmaxf(mc, c); mt = fmaxf(mt, t);
+            const float s1 = c + r, s2 = c - r;
+            if (s1 > su) { su = s1; cu = c; ru = r; }
+            if (s2 > sl) { sl = s2; cl = c; rl = r; }
         }
     }
-    block_max4(mx);
-    float nref[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { nref[i] = ref_of(mx[i]); if (nref[i] == -INFINITY) nref[i] = 0.f; }
+    {
+        // wave: the lowest lane that holds the wave's maximum hands over its token
+        auto wave_argmax = [&](float& sv, float& cv, float& rv) {
+            const float w = wave_max(sv);
+            const unsigned long long b = __ballot(sv == w);
+            const int src = b ? __ffsll((long long)b) - 1 : 0;
+            cv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cv), src));
+            rv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(rv), src));
+            sv = w;
+        };
+        mc = wave_max(mc); mt = wave_max(mt);
+        wave_argmax(su, cu, ru);
+        wave_argmax(sl, cl, rl);
+        float* slot = reinterpret_cast<float*>(sm_d);              // 8 floats per wave (sm_d holds 7 doubles per wave)
+        if (lane == 0) {
+            float* q = slot + wave * 8;
+            q[0] = mc; q[1] = mt; q[2] = su; q[3] = cu; q[4] = ru; q[5] = sl; q[6] = cl; q[7] = rl;
+        }
+        __syncthreads();
+#pragma unroll 1
+        for (int w = 0; w < NW; ++w) {
+            const float* q = slot + w * 8;
+            mc = fmaxf(mc, q[0]); mt = fmaxf(mt, q[1]);
+            if (q[2] > su) { su = q[2]; cu = q[3]; ru = q[4]; }
+            if (q[5] > sl) { sl = q[5]; cl = q[6]; rl = q[7]; }
+        }
+        __syncthreads();                                           // sm_d is reused below
+    }
+    // a row without a live token: any finite reference will do (every exponential is 0)
+    if (mc == -INFINITY) mc = 0.f;
+    if (mt == -INFINITY) mt = 0.f;
+    // the references are the same in every lane: keep them in scalar registers
+    auto uniform = [](float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); };
+    mc = uniform(mc); mt = uniform(mt);
+    cu = uniform(cu); ru = uniform(ru); cl = uniform(cl); rl = uniform(rl);
+    const double mu = (double)cu + (double)ru, ml = (double)cl - (double)rl;   // the two maxima, exact
 
     // pass 2: partition sums and the p_cloud-weighted sums of c, r and the cloud logits
     fresh();
@@ -126,18 +163,18 @@ __global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* _
         for (int k = 0; k < EPV; ++k) {
             float c, r, t;
             element(j, k, c, r, t);
-            const float et = exp2_ref(t, nref[3]);
-            acc[0] += (double)exp2_ref(c, nref[0]);
-            acc[1] += (double)exp2_ref(c + r, nref[1]);
-            acc[2] += (double)exp2_ref(c - r, nref[2]);
+            const float et = exp_rel(t, mt);
+            acc[0] += (double)exp_rel(c, mc);
+            acc[1] += (double)exp_rel(c, r, cu, ru, 1.f);
+            acc[2] += (double)exp_rel(c, r, cl, rl, -1.f);
             acc[3] += (double)et;
             if (et > 0.f) {                                        // a token the cloud rules out weighs nothing
                 acc[4] = fma((double)et, (double)c, acc[4]);
                 acc[5] = fma((double)et, (double)r, acc[5]);
                 acc[6] = fma((double)et, (double)t, acc[6]);
             }
+            if (k & 1) __builtin_amdgcn_sched_barrier(0);          // two tokens at a time: bounded working set
         }
-        __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
     for (int i = 0; i < 7; ++i) acc[i] = wave_sum(acc[i]);
@@ -167,12 +204,12 @@ __global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* _
         for (int k = 0; k < EPV; ++k) {
             float c, r, t;
             element(j, k, c, r, t);
-            const float pc = exp2_ref(t, nref[3]) * iz;
-            l1[0] += (double)fabsf(exp2_ref(c, nref[0]) * is0 - pc);
-            l1[1] += (double)fabsf(exp2_ref(c + r, nref[1]) * is1 - pc);
-            l1[2] += (double)fabsf(exp2_ref(c - r, nref[2]) * is2 - pc);
+            const float pc = exp_rel(t, mt) * iz;
+            l1[0] += (double)fabsf(exp_rel(c, mc) * is0 - pc);
+            l1[1] += (double)fabsf(exp_rel(c, r, cu, ru, 1.f) * is1 - pc);
+            l1[2] += (double)fabsf(exp_rel(c, r, cl, rl, -1.f) * is2 - pc);
+            if (k & 1) __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
     for (int i = 0; i < 3; ++i) l1[i] = wave_sum(l1[i]);
@@ -187,10 +224,10 @@ __global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* _
         for (int w = 0; w < NW; ++w) { L[0] += sm_d[w * 7]; L[1] += sm_d[w * 7 + 1]; L[2] += sm_d[w * 7 + 2]; }
         const double Z = tot[3];
         const double pc_c = tot[4] / Z, pc_r = tot[5] / Z, pc_t = tot[6] / Z;
-        const double ce_mid = ((double)nref[0] * kLn2 + log(tot[0])) - pc_c;
-        const double ce_up = ((double)nref[1] * kLn2 + log(tot[1])) - (pc_c + pc_r);
-        const double ce_lo = ((double)nref[2] * kLn2 + log(tot[2])) - (pc_c - pc_r);
-        const double kl = pc_t - ((double)nref[3] * kLn2 + log(Z)) + ce_mid;
+        const double ce_mid = ((double)mc + log(tot[0])) - pc_c;
+        const double ce_up = (mu + log(tot[1])) - (pc_c + pc_r);
+        const double ce_lo = (ml + log(tot[2])) - (pc_c - pc_r);
+        const double kl = pc_t - ((double)mt + log(Z)) + ce_mid;
         const int64_t N = A.N;
         terms[0 * N + row] = (float)L[0]; terms[1 * N + row] = (float)L[1]; terms[2 * N + row] = (float)L[2];
         terms[3 * N + row] = (float)ce_mid; terms[4 * N + row] = (float)ce_up; terms[5 * N + row] = (float)ce_lo;

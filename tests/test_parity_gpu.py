@@ -755,6 +755,99 @@ def test_random_parameters(ciar, oracle, seed):
     _run_case(ciar, oracle, c, t, ids, ua, ur, ciar.Params(tau=tau, **kw), vocab=V, tag=f"random {seed}", radius=raw)
 
 
+def _random_shape(rng):
+    dtype = (torch.float32, torch.bfloat16)[int(rng.integers(0, 2))]
+    epv = 4 if dtype == torch.float32 else 8
+    vmax = 32768 if dtype == torch.float32 else 65536
+    V = int(min(vmax, max(2, round(2.0 ** rng.uniform(1.0, 16.0)))))
+    stride = -(-V // epv) * epv + epv * int(rng.integers(0, 3))
+    if stride > vmax:
+        stride = -(-V // epv) * epv
+    return dtype, V, stride
+
+
+@pytest.mark.parametrize("seed", list(range(int(os.environ.get("CIAR_RANDOM_CASES", "16")))))
+def test_random_parameters_multihead(ciar, oracle, seed):
+    """Ensemble and Voting with the number of heads, the shapes and the quantifier's parameters drawn at random."""
+    rng = np.random.default_rng(19000 + seed)
+    dtype, V, stride = _random_shape(rng)
+    H = int(rng.integers(1, 9))
+    N = int(rng.integers(1, 14))
+    gen = torch.Generator(device="cuda").manual_seed(19100 + seed)
+    base = _archetype_rows(N, V, stride, torch.float32, rng, gen)
+    noise = float(10.0 ** rng.uniform(-2.0, 0.3))
+    heads = torch.stack([base + noise * torch.randn((N, stride), generator=gen, device="cuda") for _ in range(H)])
+    heads = torch.where(torch.isfinite(base).unsqueeze(0).expand_as(heads), heads, base.unsqueeze(0).expand_as(heads))
+    if stride > V:
+        heads[:, :, V:] = 1e30
+    heads = heads.to(dtype).contiguous()
+    ids = torch.randint(0, V, (N,), generator=gen, device="cuda").to(torch.int32)
+    raw = None
+    if rng.integers(0, 2):
+        raw = torch.stack([_raw_radius(N, stride, V, dtype, seed=19200 + 10 * seed + h,
+                                       mu_lo=float(rng.uniform(-10.0, 0.0)), mu_hi=float(rng.uniform(0.0, 10.0)),
+                                       sd=float(10.0 ** rng.uniform(-1.0, 0.7))) for h in range(H)]).contiguous()
+    kw = dict(radius_scale=float(10.0 ** rng.uniform(-3.0, 1.3)), radius_max=float(rng.uniform(0.3, 16.0)),
+              normalize=bool(rng.integers(0, 4)),
+              lower_cap=float(rng.choice([0.99, 0.9, 0.5, 1.0])), upper_cap=float(rng.choice([1.01, 1.1, 2.0, 1.0])))
+    say(f"[random multihead {seed}] H={H} V={V} stride={stride} N={N} {dtype} {kw} "
+        f"radius={'tensor' if raw is not None else 'scalar'}")
+    hh, rh = heads.cpu(), None if raw is None else raw.cpu()
+    P0 = ciar.Params(**kw)
+    o0 = oracle.quantify_multihead(hh, ids.cpu().numpy(), _oparams(oracle, P0), oracle.ENSEMBLE, vocab=V,
+                                   radius_heads=rh)
+    sc = np.sort(np.asarray(o0["score"], dtype=np.float64))
+    lo, hi = sc[(N - 1) // 2], sc[min(N - 1, (N - 1) // 2 + 1)]
+    tau = float(np.float32(0.5 * (lo + hi) if hi - lo > 1e-3 * hi else 0.5 * lo))
+    P = ciar.Params(tau=tau, **kw)
+    OP = _oparams(oracle, P)
+    ge = ciar.quantify_multihead(heads, ids, P, ciar.ENSEMBLE, vocab=V, radius_heads=raw)
+    gv = ciar.quantify_multihead(heads, ids, P, ciar.VOTING, vocab=V, radius_heads=raw)
+    torch.cuda.synchronize()
+    oe = oracle.quantify_multihead(hh, ids.cpu().numpy(), OP, oracle.ENSEMBLE, vocab=V, radius_heads=rh)
+    ov = oracle.quantify_multihead(hh, ids.cpu().numpy(), OP, oracle.VOTING, vocab=V, radius_heads=rh)
+    parity.check_floats(ge, oe)
+    parity.check_flags(ge["flags"], oe, float(np.float32(tau)))
+    for h in range(H):
+        gh = {k: gv[k][h] for k in parity.FLOAT_KEYS}
+        oh = {k: ov[k][h] for k in parity.FLOAT_KEYS}
+        oh["flags"] = ov["head_flags"][h]
+        parity.check_floats(gh, oh)
+        parity.check_flags(gv["head_flags"][h], oh, float(np.float32(tau)))
+    votes = gv["head_flags"].sum(0, dtype=torch.int32)
+    assert torch.equal(gv["flags"], (2 * votes > H).to(torch.uint8))
+
+
+@pytest.mark.parametrize("seed", list(range(int(os.environ.get("CIAR_RANDOM_CASES", "16")))))
+def test_random_parameters_interdro(ciar, oracle, seed):
+    """The Inter-DRO loss with shapes, radius mode, scale, clamp, weights and temperature drawn at random."""
+    rng = np.random.default_rng(29000 + seed)
+    dtype, V, stride = _random_shape(rng)
+    N = int(rng.integers(1, 40))
+    gen = torch.Generator(device="cuda").manual_seed(29100 + seed)
+    c = torch.randn((N, stride), generator=gen, device="cuda") * float(10.0 ** rng.uniform(-1.5, 0.8))
+    t = c + float(10.0 ** rng.uniform(-2.0, 0.5)) * torch.randn((N, stride), generator=gen, device="cuda")
+    if rng.integers(0, 2) and V > 4:
+        t[int(rng.integers(0, N)), int(rng.integers(0, V))] = float("-inf")   # a token the cloud rules out
+    if stride > V:
+        c[:, V:] = 1e30
+        t[:, V:] = 1e30
+    c, t = c.to(dtype), t.to(dtype)
+    raw = None
+    if rng.integers(0, 2):
+        raw = _raw_radius(N, stride, V, dtype, seed=29200 + seed, mu_lo=float(rng.uniform(-6.0, 0.0)),
+                          mu_hi=float(rng.uniform(0.0, 3.0)), sd=float(10.0 ** rng.uniform(-1.0, 0.3)))
+    kw = dict(radius_scale=float(10.0 ** rng.uniform(-2.0, 0.7)), radius_max=float(rng.uniform(0.3, 8.0)))
+    lam = tuple(float(10.0 ** rng.uniform(-1.0, 0.7)) for _ in range(3)) + (float(10.0 ** rng.uniform(-1.0, 0.5)),)
+    say(f"[random interdro {seed}] V={V} stride={stride} N={N} {dtype} {kw} lam={lam} "
+        f"radius={'tensor' if raw is not None else 'scalar'}")
+    P = ciar.Params(**kw)
+    g = ciar.interdro_loss(c, raw, t, P, *lam, vocab=V)
+    torch.cuda.synchronize()
+    o = oracle.interdro_loss(c.cpu(), None if raw is None else raw.cpu(), t.cpu(), _oparams(oracle, P), *lam, vocab=V)
+    _check_dro(g, o, N)
+
+
 def test_bad_arguments_raise(ciar):
     c = torch.zeros((4, 1024), device="cuda")
     with pytest.raises(ciar.CiarError, match="CIAR_EUNSUPPORTED"):
