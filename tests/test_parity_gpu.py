@@ -752,7 +752,25 @@ def test_random_parameters(ciar, oracle, seed):
     sc = np.sort(np.asarray(o0["score"], dtype=np.float64))
     lo, hi = sc[(N - 1) // 2], sc[min(N - 1, (N - 1) // 2 + 1)]
     tau = float(np.float32(0.5 * (lo + hi) if hi - lo > 1e-3 * hi else 0.5 * lo))
-    _run_case(ciar, oracle, c, t, ids, ua, ur, ciar.Params(tau=tau, **kw), vocab=V, tag=f"random {seed}", radius=raw)
+    P = ciar.Params(tau=tau, **kw)
+    _run_case(ciar, oracle, c, t, ids, ua, ur, P, vocab=V, tag=f"random {seed}", radius=raw)
+    # the same rows without drafted ids (the arg-max token is reported; rows with a tie for the maximum are left
+    # out: which of the tied tokens is lowest is covered elsewhere, here their radii may differ) and as dense curves
+    OP = _oparams(oracle, P)
+    rh = None if raw is None else raw.cpu()
+    g = ciar.quantify(c, None, P, vocab=V, radius=raw)
+    lo, mid, hi = ciar.dense_intervals(c, P, vocab=V, radius=raw)
+    torch.cuda.synchronize()
+    o = oracle.quantify(c.cpu(), None, OP, vocab=V, radius=rh)
+    cf = c[:, :V].float()
+    untied = ((cf == cf.max(dim=1, keepdim=True).values).sum(dim=1) == 1).cpu().numpy()
+    parity.check_floats({k: g[k][torch.from_numpy(untied).cuda()] for k in parity.FLOAT_KEYS},
+                        {k: np.asarray(o[k])[untied] for k in parity.FLOAT_KEYS})
+    olo, omid, ohi = oracle.dense_intervals(c.cpu(), OP, vocab=V, radius=rh)
+    for gd, od, name in ((lo, olo, "p_lo"), (mid, omid, "p_mid"), (hi, ohi, "p_hi")):
+        gd = gd.cpu().numpy().astype(np.float64)
+        bad = np.abs(gd - od) > parity.ATOL + parity.RTOL * np.abs(od)
+        assert not bad.any(), (name, np.argwhere(bad)[0], gd[bad][0], od[bad][0])
 
 
 def _random_shape(rng):
