@@ -218,7 +218,7 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
             const double u1 = (sm_red[2][0] + sm_red[2][1]) + (sm_red[2][2] + sm_red[2][3]);
             const double u2 = (sm_red[3][0] + sm_red[3][1]) + (sm_red[3][2] + sm_red[3][3]);
             const double ub = fmax(fmax(sm_red[4][0], sm_red[4][1]), fmax(sm_red[4][2], sm_red[4][3]));
-            bool plain = ub < 0.5 * Hd;                            // every mean width above 1/2
+            bool plain = ub < kComplementBelow * Hd;               // every mean width above 1/2
             for (int h = 0; h < H; ++h) plain = plain && sm_al[h] == 1.0 && sm_au[h] == 1.0;
             if (plain) {
                 omega = Vd - (u1 + Vd * KC) / Hd;

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <math.h>
 #include <stdint.h>
 
 namespace ciar {
@@ -55,12 +56,17 @@ struct RowArgs {
 
 enum class Mode { Quantify, Verify, Fused };
 
-// Radii from which the kernels also accumulate the complements of the widths (e^6 x_i >> 1 for most tokens of
-// a row makes the widths crowd against 1, where fp32 widths no longer resolve their own spread).
-constexpr double kWideRadius = 6.0;
+// Calls whose radius can push every width of a row close to 1 run kernel instances that also accumulate the
+// complements of the widths: there the widths crowd against 1, and fp32 widths no longer resolve their own
+// spread.  A row's complement sums are used when every 1 - width_i is below 1/2 (the complement is then the
+// smaller and the more accurately known of the two).  For that (a - 1) x_i > 1 must hold for the smallest
+// probability x_i <= 1 / V, so a = e^r > V is necessary; the instances are chosen from a >= 3 V, because with a
+// in between every complement of such a row lies between 1/4 and 1/2, where the two forms are equally accurate.
+constexpr double kComplementBelow = 0.5;      // the complement sums are used when every 1 - width is below this
 inline bool wide_radius(const RowArgs& a)
 {
-    return a.radius ? (a.kappa > 0.0 && a.rmax >= kWideRadius) : (a.a >= 403.4287934927351 /* e^6 */);
+    const double amax = a.radius ? (a.kappa > 0.0 ? exp(a.rmax) : 1.0) : a.a;
+    return amax >= 3.0 * (double)a.V;
 }
 
 // Largest vocabulary the register-resident streaming kernels cover for an element size.

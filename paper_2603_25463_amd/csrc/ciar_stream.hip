@@ -596,7 +596,7 @@ void stream_kernel(const RowArgs A)
             float mode = (capless && !WIDE) ? kSumsWidthOnly : kSumsFull;
             if constexpr (WIDE && DO_Q) {
                 // every width above 1/2 and both caps inactive: the finishing kernels read the complement sums
-                if (t[7] < 0.5) {
+                if (t[7] < kComplementBelow) {
                     const RowScore rs = finish_score(t, S, kSumsFull, A, K[0], K[1]);
                     if (rs.alpha_l == 1.0 && rs.alpha_u == 1.0) {
                         t[1] = t[5]; t[3] = t[6]; K[1] = K[2];
