@@ -280,14 +280,14 @@ def main() -> int:
         rad = rads[i % copies] if rads else None
         if ev0 is not None:
             ev0.record(stream)
-        _check(L.ciar_stream_rows(_ptr(d), _ptr(rad), _ptr(t), 1, N, ctypes.byref(cp), _ptr(ws), ws.numel(), sp))
+        call = (_ptr(d), _ptr(rad), _ptr(t), _ptr(w.ids), _ptr(w.u_accept), _ptr(w.u_resample), N, ctypes.byref(cp),
+                _ptr(out["p_lo"]), _ptr(out["p_mid"]), _ptr(out["p_hi"]), _ptr(out["omega"]), _ptr(out["sigma"]),
+                _ptr(out["score"]), _ptr(out["flags"]), _ptr(out["accept"]), _ptr(out["row_id"]),
+                _ptr(wout["accept_len"]), _ptr(wout["resampled_id"]), _ptr(ws), ws.numel(), sp)
+        _check(L.ciar_stream_rows(*call))
         if ev1 is not None:
             ev1.record(stream)
-        _check(L.ciar_finish_rows(
-            _ptr(d), _ptr(rad), _ptr(t), _ptr(w.ids), _ptr(w.u_accept), _ptr(w.u_resample), N, ctypes.byref(cp),
-            _ptr(out["p_lo"]), _ptr(out["p_mid"]), _ptr(out["p_hi"]), _ptr(out["omega"]), _ptr(out["sigma"]),
-            _ptr(out["score"]), _ptr(out["flags"]), _ptr(out["accept"]), _ptr(out["row_id"]),
-            _ptr(wout["accept_len"]), _ptr(wout["resampled_id"]), _ptr(ws), ws.numel(), sp))
+        _check(L.ciar_finish_rows(*call))
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)

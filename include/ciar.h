@@ -166,21 +166,27 @@ int ciar_quantify_verify(const void* draft_logits, const void* radius, const voi
 /*
  * The two stages of the calls above, on their own, for callers that want to time them or to put
  * other work between them.  ciar_quantify, ciar_verify and ciar_quantify_verify are exactly
- * ciar_stream_rows followed by ciar_finish_rows (same kernels, same launch configuration).
+ * ciar_stream_rows followed by ciar_finish_rows (same kernels, same launch configuration).  Both take the
+ * argument list of ciar_quantify_verify and must be given the same arguments: target_logits = NULL with
+ * no verify output is a quantify-only call, no quantify output a verify-only call (radius must be NULL).
  *
- * ciar_stream_rows   the streaming kernel: reads every logit row once from HBM and leaves the
- *                    per-row statistics (max-trick references, partition sums, the InterFuse sums)
- *                    in `workspace`.  target_logits = NULL: quantify only (with_intervals must be 1);
- *                    with_intervals = 0: verify only (radius must be NULL); otherwise both.
- * ciar_finish_rows   the finishing kernels (per-row scalars, then the residual draw of the rejected rows;
- *                    both also write the window outputs when one is given):
- *                    arguments as ciar_quantify_verify; it must be given the workspace a
- *                    ciar_stream_rows call on the same rows and parameters has filled, the same
- *                    radius and target_logits (or NULL), and quantify outputs iff with_intervals was 1.
+ * ciar_stream_rows   the streaming kernel: reads every logit row once from HBM and leaves the per-row
+ *                    statistics (max-trick references, partition sums, the InterFuse sums) in `workspace`.
+ *                    A quantify-only call in which every workgroup of the launch handles at most 128 rows
+ *                    (N up to 128 times the number of resident workgroups: 131072 rows and more on this chip)
+ *                    also finishes its rows here: p_lo ... flags are complete when the kernel ends.
+ * ciar_finish_rows   what remains: the per-row outputs where the streaming kernel has not produced them, the
+ *                    residual draw of the rejected rows, and the window outputs.  A quantify-only call whose
+ *                    rows the streaming kernel has finished launches nothing here.
  */
-int ciar_stream_rows(const void* draft_logits, const void* radius, const void* target_logits, int with_intervals,
-                     int64_t N,
-                     const ciar_params* params, void* workspace, size_t workspace_bytes, void* hip_stream);
+int ciar_stream_rows(const void* draft_logits, const void* radius, const void* target_logits,
+                     const int32_t* draft_ids,
+                     const float* u_accept, const float* u_resample, int64_t N, const ciar_params* params,
+                     float* p_lo, float* p_mid, float* p_hi,
+                     float* omega, float* sigma, float* score, uint8_t* flags,
+                     uint8_t* accept, int32_t* row_resample_id,
+                     int32_t* accept_len, int32_t* resampled_id,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 int ciar_finish_rows(const void* draft_logits, const void* radius, const void* target_logits,
                      const int32_t* draft_ids,

@@ -60,7 +60,7 @@ def lib() -> ctypes.CDLL:
         L.ciar_quantify_verify.restype = ctypes.c_int
         L.ciar_quantify_verify.argtypes = [vp, vp, vp, vp, vp, vp, i64, pp] + [vp] * 11 + [vp, sz, vp]
         L.ciar_stream_rows.restype = ctypes.c_int
-        L.ciar_stream_rows.argtypes = [vp, vp, vp, ctypes.c_int, i64, pp, vp, sz, vp]
+        L.ciar_stream_rows.argtypes = [vp, vp, vp, vp, vp, vp, i64, pp] + [vp] * 11 + [vp, sz, vp]
         L.ciar_finish_rows.restype = ctypes.c_int
         L.ciar_finish_rows.argtypes = [vp, vp, vp, vp, vp, vp, i64, pp] + [vp] * 11 + [vp, sz, vp]
         L.ciar_window_epilogue.restype = ctypes.c_int
@@ -234,23 +234,10 @@ def quantify_verify(draft, target, ids, u_accept, u_resample, params: Params, vo
     return o
 
 
-def stream_rows(draft, target, with_intervals: bool, params: Params, workspace: torch.Tensor,
-                vocab: int | None = None, stream=None, radius: torch.Tensor | None = None) -> None:
-    """``ciar_stream_rows``: the streaming kernel alone; leaves the per-row statistics in ``workspace``."""
-    _need_cuda(draft, target, workspace, radius)
+def _staged(entry, draft, target, ids, u_accept, u_resample, params: Params, workspace: torch.Tensor,
+            with_intervals: bool, vocab, stream, out, radius) -> dict:
+    _need_cuda(draft, target, ids, u_accept, u_resample, workspace, radius)
     _like_draft(radius, draft, "radius")
-    cp = params.to_c(draft, vocab)
-    _check(lib().ciar_stream_rows(_ptr(draft), _ptr(radius), _ptr(target), int(bool(with_intervals)), draft.shape[0],
-                                  ctypes.byref(cp), _ptr(workspace), workspace.numel() * workspace.element_size(),
-                                  _stream(stream)))
-
-
-def finish_rows(draft, target, ids, u_accept, u_resample, params: Params, workspace: torch.Tensor,
-                with_intervals: bool = True, vocab: int | None = None, stream=None, out: dict | None = None,
-                radius: torch.Tensor | None = None) -> dict:
-    """``ciar_finish_rows``: the finishing kernel and the window epilogue on a workspace filled by
-    ``stream_rows`` (same rows, same parameters, same ``with_intervals``)."""
-    _need_cuda(draft, target, ids, u_accept, u_resample, workspace)
     N, dev = draft.shape[0], draft.device
     cp = params.to_c(draft, vocab)
     o = dict(out) if out else {}
@@ -261,12 +248,31 @@ def finish_rows(draft, target, ids, u_accept, u_resample, params: Params, worksp
             o.setdefault(k, torch.empty(N, dtype=torch.float32, device=dev))
         o.setdefault("flags", torch.empty(N, dtype=torch.uint8, device=dev))
     g = lambda k: _ptr(o.get(k))
-    _check(lib().ciar_finish_rows(
+    _check(entry(
         _ptr(draft), _ptr(radius), _ptr(target), _ptr(ids), _ptr(u_accept), _ptr(u_resample), N, ctypes.byref(cp),
         g("p_lo"), g("p_mid"), g("p_hi"), g("omega"), g("sigma"), g("score"), g("flags"), g("accept"),
         g("row_id"), g("accept_len"), g("resampled_id"), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)))
     return o
+
+
+def stream_rows(draft, target, ids, u_accept, u_resample, params: Params, workspace: torch.Tensor,
+                with_intervals: bool = True, vocab: int | None = None, stream=None, out: dict | None = None,
+                radius: torch.Tensor | None = None) -> dict:
+    """``ciar_stream_rows``: stage 1, the streaming kernel (which also finishes its rows where the launch shape
+    allows).  Returns the output tensors (allocated here unless passed in ``out``); hand the same dict and the same
+    arguments to ``finish_rows``."""
+    return _staged(lib().ciar_stream_rows, draft, target, ids, u_accept, u_resample, params, workspace,
+                   with_intervals, vocab, stream, out, radius)
+
+
+def finish_rows(draft, target, ids, u_accept, u_resample, params: Params, workspace: torch.Tensor,
+                with_intervals: bool = True, vocab: int | None = None, stream=None, out: dict | None = None,
+                radius: torch.Tensor | None = None) -> dict:
+    """``ciar_finish_rows``: stage 2 on a workspace filled by ``stream_rows`` (same arguments, same ``out``):
+    whatever per-row finishing is left, the residual draws and the window outputs."""
+    return _staged(lib().ciar_finish_rows, draft, target, ids, u_accept, u_resample, params, workspace,
+                   with_intervals, vocab, stream, out, radius)
 
 
 def window_epilogue(accept: torch.Tensor, row_id: torch.Tensor, params: Params, stream=None,

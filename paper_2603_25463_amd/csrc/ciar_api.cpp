@@ -191,23 +191,10 @@ int prepare(const Call& c, ciar::Mode mode, ciar::RowArgs* a)
     return CIAR_OK;
 }
 
-int run_stream(const Call& c, ciar::Mode mode)
+// Validates a call's arguments, carves the workspace and fills every pointer the two stages use.
+int fill(const Call& c, ciar::Mode mode, ciar::RowArgs* a)
 {
-    ciar::RowArgs a;
-    if (int rc = prepare(c, mode, &a)) return rc;
-    if (int rc = check_workspace(c.N, c.params, c.workspace, c.workspace_bytes)) return rc;
-    if (c.N == 0) return CIAR_OK;
-    int32_t* ws_ids; uint8_t* ws_accept;
-    carve(static_cast<char*>(c.workspace), c.N, &a, &ws_ids, &ws_accept);
-    const hipError_t e = ciar::launch_stream(mode, c.params->dtype, a, c.stream);
-    if (e != hipSuccess) return hip_fail(e, "streaming kernel launch");
-    return CIAR_OK;
-}
-
-int run_finish(const Call& c, ciar::Mode mode)
-{
-    ciar::RowArgs a;
-    if (int rc = prepare(c, mode, &a)) return rc;
+    if (int rc = prepare(c, mode, a)) return rc;
     if (mode != ciar::Mode::Quantify) {
         if (!c.ids) return fail(CIAR_EINVAL, "draft_ids is NULL");
         if (!c.u_accept) return fail(CIAR_EINVAL, "u_accept is NULL");
@@ -216,41 +203,56 @@ int run_finish(const Call& c, ciar::Mode mode)
     if (!wants_intervals(c) && !wants_verify(c)) return fail(CIAR_EINVAL, "every output pointer is NULL");
     if (int rc = check_workspace(c.N, c.params, c.workspace, c.workspace_bytes)) return rc;
     if (c.N == 0) return CIAR_OK;
-    const int64_t N = c.N;
     int32_t* ws_ids; uint8_t* ws_accept;
-    carve(static_cast<char*>(c.workspace), N, &a, &ws_ids, &ws_accept);
-    a.ids = c.ids; a.u_accept = c.u_accept; a.u_resample = c.u_resample;
-    a.p_lo = c.p_lo; a.p_mid = c.p_mid; a.p_hi = c.p_hi;
-    if (a.radius && !a.ids && (a.p_lo || a.p_hi)) {
-        // tensor mode reports the arg-max token's interval with that token's own radius: find the
-        // index first (quantify-only calls: the list of rejected rows is not in use)
+    carve(static_cast<char*>(c.workspace), c.N, a, &ws_ids, &ws_accept);
+    a->ids = c.ids; a->u_accept = c.u_accept; a->u_resample = c.u_resample;
+    a->p_lo = c.p_lo; a->p_mid = c.p_mid; a->p_hi = c.p_hi;
+    a->omega = c.omega; a->sigma = c.sigma; a->score = c.score; a->flags = c.flags;
+    a->accept = c.accept;
+    a->row_id = c.row_id;
+    // the window outputs are assembled from the per-row accept bits and draws
+    if ((c.accept_len || c.resampled_id) && !a->accept) a->accept = ws_accept;
+    if (c.resampled_id && !a->row_id) a->row_id = ws_ids;
+    return CIAR_OK;
+}
+
+// Tensor mode reports the arg-max token's interval with that token's own radius: without drafted ids the index
+// comes from a kernel of its own, into the list of rejected rows (not in use in a quantify-only call).
+bool needs_argmax(const ciar::RowArgs& a) { return a.radius && !a.ids && (a.p_lo || a.p_hi); }
+
+// Stage 1: the streaming kernel; a quantify-only launch also finishes its rows where its shape allows.
+int run_stream(const Call& c, ciar::Mode mode)
+{
+    ciar::RowArgs a;
+    if (int rc = fill(c, mode, &a)) return rc;
+    if (c.N == 0) return CIAR_OK;
+    if (needs_argmax(a)) {
         const hipError_t e = ciar::launch_argmax(c.params->dtype, a, a.reject_list, c.stream);
         if (e != hipSuccess) return hip_fail(e, "arg-max kernel launch");
         a.ids = a.reject_list;
     }
-    a.omega = c.omega; a.sigma = c.sigma; a.score = c.score; a.flags = c.flags;
-    const bool windows = c.accept_len || c.resampled_id;
-    a.accept = c.accept;
-    a.row_id = c.row_id;
-    if (windows && !a.accept) a.accept = ws_accept;
-    if (c.resampled_id && !a.row_id) a.row_id = ws_ids;
-    const hipError_t e = ciar::launch_finish(mode, c.params->dtype, a, c.params->window, c.accept_len,
-                                             c.resampled_id, c.stream);
+    const hipError_t e = ciar::launch_stream(mode, c.params->dtype, a, true, c.stream);
+    if (e != hipSuccess) return hip_fail(e, "streaming kernel launch");
+    return CIAR_OK;
+}
+
+// Stage 2: whatever the streaming kernel has left (the per-row finishing for launch shapes it does not cover),
+// the residual draws and the window outputs.
+int run_finish(const Call& c, ciar::Mode mode)
+{
+    ciar::RowArgs a;
+    if (int rc = fill(c, mode, &a)) return rc;
+    if (c.N == 0) return CIAR_OK;
+    if (needs_argmax(a)) a.ids = a.reject_list;                    // found by stage 1
+    const ciar::StreamPlan plan = ciar::plan_stream(mode, c.params->dtype, a);
+    const hipError_t e = ciar::launch_finish(mode, c.params->dtype, a, plan.can_finish, c.params->window,
+                                             c.accept_len, c.resampled_id, c.stream);
     if (e != hipSuccess) return hip_fail(e, "finishing kernel launch");
     return CIAR_OK;
 }
 
 int run_both(const Call& c, ciar::Mode mode)
 {
-    // validate the finishing stage's arguments before anything is launched
-    ciar::RowArgs a;
-    if (int rc = prepare(c, mode, &a)) return rc;
-    if (mode != ciar::Mode::Quantify) {
-        if (!c.ids) return fail(CIAR_EINVAL, "draft_ids is NULL");
-        if (!c.u_accept) return fail(CIAR_EINVAL, "u_accept is NULL");
-        if (!c.u_resample) return fail(CIAR_EINVAL, "u_resample is NULL");
-    }
-    if (!wants_intervals(c) && !wants_verify(c)) return fail(CIAR_EINVAL, "every output pointer is NULL");
     if (int rc = run_stream(c, mode)) return rc;
     return run_finish(c, mode);
 }
@@ -315,16 +317,19 @@ int ciar_quantify_verify(const void* draft_logits, const void* radius, const voi
     return run_both(c, ciar::Mode::Fused);
 }
 
-int ciar_stream_rows(const void* draft_logits, const void* radius, const void* target_logits, int with_intervals,
-                     int64_t N, const ciar_params* params, void* workspace, size_t workspace_bytes, void* hip_stream)
+int ciar_stream_rows(const void* draft_logits, const void* radius, const void* target_logits,
+                     const int32_t* draft_ids, const float* u_accept, const float* u_resample, int64_t N,
+                     const ciar_params* params, float* p_lo, float* p_mid, float* p_hi, float* omega, float* sigma,
+                     float* score, uint8_t* flags, uint8_t* accept, int32_t* row_resample_id, int32_t* accept_len,
+                     int32_t* resampled_id, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    if (!target_logits && !with_intervals)
-        return fail(CIAR_EINVAL, "neither target_logits nor with_intervals: nothing to compute");
+    const Call c{draft_logits, radius, target_logits, draft_ids, u_accept, u_resample, N, params, p_lo, p_mid, p_hi, omega,
+                 sigma, score, flags, accept, row_resample_id, accept_len, resampled_id, workspace, workspace_bytes,
+                 static_cast<hipStream_t>(hip_stream)};
+    if (target_logits && !wants_verify(c)) return fail(CIAR_EINVAL, "target_logits given but no verify output");
+    if (!target_logits && wants_verify(c)) return fail(CIAR_EINVAL, "verify outputs need target_logits");
     const ciar::Mode mode = !target_logits ? ciar::Mode::Quantify
-                                           : (with_intervals ? ciar::Mode::Fused : ciar::Mode::Verify);
-    Call c{};
-    c.draft = draft_logits; c.radius = radius; c.target = target_logits; c.N = N; c.params = params;
-    c.workspace = workspace; c.workspace_bytes = workspace_bytes; c.stream = static_cast<hipStream_t>(hip_stream);
+                                           : (wants_intervals(c) ? ciar::Mode::Fused : ciar::Mode::Verify);
     return run_stream(c, mode);
 }
 
@@ -465,22 +470,29 @@ int ciar_quantify_multihead(const void* draft_heads, const void* radius_heads, i
         a.stats = stats + (size_t)h * (size_t)N;
         a.reject_list = ws_ids + (size_t)h * (ids_bytes(N) / 4);
         a.reject_count = a.reject_list;                      // not used by a quantify-only pass
-        hipError_t e = ciar::launch_stream(ciar::Mode::Quantify, params->dtype, a, stream);
-        if (e != hipSuccess) return hip_fail(e, "streaming kernel launch");
         if (strategy == CIAR_VOTING) {
+            // every head is a quantifier of its own: the streaming kernel finishes its rows where it can
             const size_t o = (size_t)h * (size_t)N;
             a.ids = draft_ids;
             a.p_lo = p_lo ? p_lo + o : nullptr; a.p_mid = p_mid ? p_mid + o : nullptr; a.p_hi = p_hi ? p_hi + o : nullptr;
             a.omega = omega ? omega + o : nullptr; a.sigma = sigma ? sigma + o : nullptr;
             a.score = score ? score + o : nullptr;
             a.flags = (head_flags ? head_flags : ws_flags) + o;
-            if (a.radius && !a.ids && (a.p_lo || a.p_hi)) {
-                e = ciar::launch_argmax(params->dtype, a, a.reject_list, stream);
+            if (needs_argmax(a)) {
+                const hipError_t e = ciar::launch_argmax(params->dtype, a, a.reject_list, stream);
                 if (e != hipSuccess) return hip_fail(e, "arg-max kernel launch");
                 a.ids = a.reject_list;
             }
-            e = ciar::launch_finish(ciar::Mode::Quantify, params->dtype, a, params->window, nullptr, nullptr, stream);
+            hipError_t e = ciar::launch_stream(ciar::Mode::Quantify, params->dtype, a, true, stream);
+            if (e != hipSuccess) return hip_fail(e, "streaming kernel launch");
+            const ciar::StreamPlan plan = ciar::plan_stream(ciar::Mode::Quantify, params->dtype, a);
+            e = ciar::launch_finish(ciar::Mode::Quantify, params->dtype, a, plan.can_finish, params->window, nullptr,
+                                    nullptr, stream);
             if (e != hipSuccess) return hip_fail(e, "finishing kernel launch");
+        } else {
+            // Ensemble: only every head's RowStats
+            const hipError_t e = ciar::launch_stream(ciar::Mode::Quantify, params->dtype, a, false, stream);
+            if (e != hipSuccess) return hip_fail(e, "streaming kernel launch");
         }
     }
     if (strategy == CIAR_VOTING) {

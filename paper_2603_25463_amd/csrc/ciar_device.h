@@ -382,6 +382,52 @@ __device__ __forceinline__ RowScore finish_score(const double* s, double S, floa
     return o;
 }
 
+// One row's outputs from its statistics, in fp64 (Eq. uncertainty_score; Algorithm 1's threshold and verification
+// steps): score, flag, the reported token's interval, the accept test in the log domain.  xid = the reported
+// token (-1: the arg-max token, whose logit is st.mc), cx / tx / rawx = its centre logit, verifier logit and raw
+// radius, u = the row's uniform for the accept test.  Returns whether the drafted token is rejected.
+__device__ __forceinline__ bool finish_row(const RowArgs& A, int64_t row, const RowStats& st, float cx, float tx,
+                                           float rawx, float u, bool do_q, bool do_v)
+{
+    const double S = st.S;
+    const float n = st.n;
+    if (do_q) {
+        const RowScore rs = finish_score(st.q, S, st.mode, A, st.kl, st.kw);
+        if (A.omega) A.omega[row] = (float)rs.omega;
+        if (A.sigma) A.sigma[row] = (float)rs.sigma;
+        if (A.score) A.score[row] = (float)rs.score;
+        if (A.flags) A.flags[row] = (uint8_t)(rs.score > A.tau);
+        if (A.p_lo || A.p_mid || A.p_hi) {
+            // e_x exactly as the streaming kernel summed it into S (the arg-max token, the only one whose
+            // probability can approach 1, sits in a wave whose reference is n), so that S - e_x is the
+            // sum of the other tokens to fp64 rounding and 1 - x keeps its relative accuracy as x -> 1:
+            // the lower bound's denominator b + (1-b)(1-x) is that small number when b is small too.
+            const double ex = (double)exp2_ref(cx, n == -INFINITY ? 0.f : n);
+            const double x = ex / S, omx = fmax(0.0, S - ex) / S;
+            double a = A.a, b = A.b;
+            if (A.radius) {
+                // the reported token's own radius (the launcher supplies ids in this mode)
+                const double r = radius_of((double)rawx, A.kappa, A.rmax);
+                a = exp(r); b = exp(-r);
+            }
+            if (A.p_mid) A.p_mid[row] = (float)x;
+            if (A.p_lo) A.p_lo[row] = (float)(rs.alpha_l * b * x / (b + (1.0 - b) * omx));
+            if (A.p_hi) A.p_hi[row] = (float)(rs.alpha_u * a * x / (1.0 + (a - 1.0) * x));
+        }
+    }
+    bool rej = false;
+    if (do_v) {
+        // ln p_x = cx - n ln2 - ln S, ln q_x = tx - nt ln2 - ln Z;  accept iff ln u < min(0, ln q_x - ln p_x)
+        const double lp = ((double)cx - (double)n * kLn2) - log(S);
+        const double lq = ((double)tx - (double)st.nt * kLn2) - log(st.Z);
+        const double lnu = log((double)u);                         // log(0) = -inf: always accepted
+        rej = !(lnu < fmin(0.0, lq - lp));
+        if (A.accept) A.accept[row] = (uint8_t)(!rej);
+        if (A.row_id && !rej) A.row_id[row] = -1;
+    }
+    return rej;
+}
+
 // r = min(kappa Softplus(raw), rmax) in fp32 (see radius_ab for the ln(1 + t) form).
 __device__ __forceinline__ float radius_r(float raw, float kappa, float rmax)
 {

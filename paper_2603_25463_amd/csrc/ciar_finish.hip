@@ -42,54 +42,16 @@ __global__ __launch_bounds__(256) void rowfinish_kernel(const RowArgs A, const i
     int rej = 0;
     if (live) {
         const int V = A.V;
-        const T* crow = static_cast<const T*>(A.draft) + row * A.stride;
         const RowStats st = A.stats[row];
-        const double S = st.S;
-        const float n = st.n;
-
-        int xid = -1;
-        float cx = st.mc;                                          // no ids: the arg-max token is reported
+        float cx = st.mc, tx = 0.f, rawx = 0.f;                    // no ids: the arg-max token is reported
         if (A.ids) {
-            xid = A.ids[row];
+            int xid = A.ids[row];
             xid = xid < 0 ? 0 : (xid >= V ? V - 1 : xid);
-            cx = load_logit(crow, xid);
+            cx = load_logit(static_cast<const T*>(A.draft) + row * A.stride, xid);
+            if (do_v) tx = load_logit(static_cast<const T*>(A.target) + row * A.stride, xid);
+            if (A.radius) rawx = load_logit(static_cast<const T*>(A.radius) + row * A.stride, xid);
         }
-        if (do_q) {
-            const RowScore rs = finish_score(st.q, S, st.mode, A, st.kl, st.kw);
-            if (A.omega) A.omega[row] = (float)rs.omega;
-            if (A.sigma) A.sigma[row] = (float)rs.sigma;
-            if (A.score) A.score[row] = (float)rs.score;
-            if (A.flags) A.flags[row] = (uint8_t)(rs.score > A.tau);
-            if (A.p_lo || A.p_mid || A.p_hi) {
-                // e_x exactly as the streaming kernel summed it into S (the arg-max token, the only one whose
-                // probability can approach 1, sits in a wave whose reference is n), so that S - e_x is the
-                // sum of the other tokens to fp64 rounding and 1 - x keeps its relative accuracy as x -> 1:
-                // the lower bound's denominator b + (1-b)(1-x) is that small number when b is small too.
-                const double ex = (double)exp2_ref(cx, n == -INFINITY ? 0.f : n);
-                const double x = ex / S, omx = fmax(0.0, S - ex) / S;
-                double a = A.a, b = A.b;
-                if (A.radius) {
-                    // the reported token's own radius (the launcher supplies ids in this mode)
-                    const T* rrow = static_cast<const T*>(A.radius) + row * A.stride;
-                    const double r = radius_of((double)load_logit(rrow, xid < 0 ? 0 : xid), A.kappa, A.rmax);
-                    a = exp(r); b = exp(-r);
-                }
-                if (A.p_mid) A.p_mid[row] = (float)x;
-                if (A.p_lo) A.p_lo[row] = (float)(rs.alpha_l * b * x / (b + (1.0 - b) * omx));
-                if (A.p_hi) A.p_hi[row] = (float)(rs.alpha_u * a * x / (1.0 + (a - 1.0) * x));
-            }
-        }
-        if (do_v) {
-            // ln p_x = cx - n ln2 - ln S, ln q_x = tx - nt ln2 - ln Z;  accept iff ln u < min(0, ln q_x - ln p_x)
-            const T* trow = static_cast<const T*>(A.target) + row * A.stride;
-            const float tx = load_logit(trow, xid);
-            const double lp = ((double)cx - (double)n * kLn2) - log(S);
-            const double lq = ((double)tx - (double)st.nt * kLn2) - log(st.Z);
-            const double lnu = log((double)A.u_accept[row]);       // log(0) = -inf: always accepted
-            rej = !(lnu < fmin(0.0, lq - lp));
-            if (A.accept) A.accept[row] = (uint8_t)(!rej);
-            if (A.row_id && !rej) A.row_id[row] = -1;
-        }
+        rej = finish_row(A, row, st, cx, tx, rawx, do_v ? A.u_accept[row] : 0.f, do_q != 0, do_v != 0);
     }
     bool first = false;                                            // first rejection of its window
     if (windows) {
@@ -347,10 +309,11 @@ hipError_t launch_finish_typed(Mode mode, const RowArgs& a, int32_t K, int32_t* 
 
 }  // namespace
 
-hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, int32_t K, int32_t* accept_len,
+hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, bool rows_finished, int32_t K, int32_t* accept_len,
                          int32_t* resampled_id, hipStream_t stream)
 {
     if (args.N <= 0) return hipSuccess;
+    if (rows_finished && mode == Mode::Quantify) return hipSuccess;   // the streaming kernel has written every output
     return dtype == 0 ? launch_finish_typed<float>(mode, args, K, accept_len, resampled_id, stream)
                       : launch_finish_typed<bf16_t>(mode, args, K, accept_len, resampled_id, stream);
 }

@@ -40,6 +40,7 @@ struct RowArgs {
     RowStats* stats;                                 // [N] workspace
     int32_t* reject_list;                            // [N] workspace: rows whose drafted token was rejected
     int32_t* reject_count;                           // workspace: length of that list
+    int32_t  finish;                                 // 1 = the streaming kernel also finishes its rows (quantify only)
     int64_t  N;
     int64_t  stride;            // elements between rows
     int32_t  V;
@@ -72,12 +73,29 @@ inline bool wide_radius(const RowArgs& a)
 // Largest vocabulary the register-resident streaming kernels cover for an element size.
 int max_vocab(int dtype);
 
-// Streaming pass over the rows: statistics and InterFuse sums into args.stats.
-hipError_t launch_stream(Mode mode, int dtype, const RowArgs& args, hipStream_t stream);
+// A quantify-only streaming launch finishes its own rows (score, flag, reported interval) when every workgroup
+// handles at most kMaxRowsPerWg rows: no finishing kernel, no second launch.  (With the verifier row in the same
+// launch the finishing stays in a kernel of its own: at the end of the streaming kernel it costs more than the
+// launch it saves is worth to the kernel's bandwidth figure.)
+constexpr int kMaxRowsPerWg = 128;
 
-// Per-row finishing: score, flag, reported interval, accept test, residual draw of rejected rows, and the
-// window outputs (either may be null) for windows of K rows.
-hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, int32_t K, int32_t* accept_len,
+// How a streaming launch over args.N rows would be shaped.
+struct StreamPlan {
+    unsigned grid;        // workgroups
+    int rows_per_wg;      // ceil(N / grid)
+    bool can_finish;      // the launch is quantify-only and its shape allows the kernel to finish its rows
+};
+StreamPlan plan_stream(Mode mode, int dtype, const RowArgs& args);
+
+// Streaming pass over the rows: statistics and InterFuse sums into args.stats.  With finish_rows (and a plan that
+// allows it, see plan_stream) the kernel also produces the per-row outputs in args; args needs ids and the output
+// pointers then.
+hipError_t launch_stream(Mode mode, int dtype, const RowArgs& args, bool finish_rows, hipStream_t stream);
+
+// What remains after the streaming pass: the per-row finishing unless the streaming kernel has done it
+// (rows_finished), the residual draw of rejected rows, and the window outputs (either may be null) for windows of
+// K rows.
+hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, bool rows_finished, int32_t K, int32_t* accept_len,
                          int32_t* resampled_id, hipStream_t stream);
 
 // accept_len / resampled_id per window of K rows from the per-row results.

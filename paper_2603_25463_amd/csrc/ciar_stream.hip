@@ -72,12 +72,16 @@ constexpr int target_waves()
     return fit < lo ? lo : (fit > 4 ? 4 : fit);
 }
 
-// The interval sums of a row are taken about the values (kl, kw, kc) of the row's first token: sum (gl - kl),
-// sum (gw - kw) and their second moments.  Subtracting the squared mean from a second moment taken about one of
-// the data loses at most a factor V of fp64's 1e-16, however small the spread is against the mean; about the
-// origin a row of equal logits (spread 0, mean > 0) leaves rounding noise of relative size 1e-8 in Sigma, which
-// Omega ~ V multiplies.  Every wave forms the shift itself from that token's e rescaled to its own units, a power
-// of two, so the shifts agree bit for bit once they are back in row units and the waves' sums simply add.
+// The interval sums of a flat row are taken about a shift (kl, kw, kc): sum (gl - kl), sum (gw - kw) and their
+// second moments.  A row of nearly equal logits has a spread far below its mean width: about the origin the
+// difference of the second moment and the squared mean leaves rounding noise of relative size 1e-8 in Sigma,
+// which Omega ~ V multiplies; about a point among the data it loses next to nothing.  "Flat" = the largest
+// probability is at most 2 / V.  Elsewhere the spread is at least ~1 / sqrt(V) of the mean and plain sums do; a
+// shift would even hurt there, because a token far below it keeps only ulp(k) / 2 of absolute accuracy in gl - k,
+// which over a row of small tokens adds up to V * 3e-8 * k.
+// Scalar radius: the shift is the token function at the mean of the row's e_i, S / V.  Tensor radius: the values
+// of the row's first token.  Every wave forms the shift itself in its own units, a power of two away from the
+// others', so the shifts agree bit for bit once they are back in row units and the waves' sums simply add.
 struct Shift { float kl, kw, kc; };
 
 // Pass C for one lane: the shifted InterFuse sums over the lane's tokens.  gl - kl and gw - kw come out of the
@@ -289,6 +293,12 @@ void stream_kernel(const RowArgs A)
     __shared__ double sm_q5[NW * NQ];               // per wave: the interval sums, already in row units
     __shared__ double sm_k[3];                      // the shift the sums are taken about (row units), from wave 0
     __shared__ float  sm_e0;                        // e of the row's first token, in the units of wave 0
+    // Finishing inside this kernel (quantify-only launches with A.finish): the statistics of the rows this workgroup
+    // has streamed and, fetched ahead, what their finishing needs from memory (the reported token's centre logit
+    // and raw radius).
+    constexpr bool CAN_FINISH = DO_Q && !DO_V;
+    __shared__ RowStats sm_rows[CAN_FINISH ? kMaxRowsPerWg : 1];
+    __shared__ float    sm_fx[CAN_FINISH ? kMaxRowsPerWg : 1][2];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int V = A.V;
@@ -357,6 +367,19 @@ void stream_kernel(const RowArgs A)
     // the list of rejected rows that the finishing kernels build starts empty
     if (DO_V && blockIdx.x == 0 && tid == 0) *A.reject_count = 0;
 
+    // Finishing: lane t will finish the t-th row of this workgroup after the last row has been streamed.  What
+    // that needs from memory is requested now, ahead of the first row, and parked in LDS.
+    const bool finish = CAN_FINISH && A.finish;                    // uniform over the grid
+    const int my_rows = finish ? (nrows - (int)blockIdx.x + step - 1) / step : 0;   // <= kMaxRowsPerWg
+    float fx[2] = {0.f, 0.f};
+    if (tid < my_rows && A.ids) {
+        const int64_t r = (int64_t)blockIdx.x + (int64_t)tid * step;
+        int xid = A.ids[r];
+        xid = xid < 0 ? 0 : (xid >= V ? V - 1 : xid);
+        fx[0] = load_logit(static_cast<const T*>(A.draft) + r * A.stride, xid);
+        if constexpr (RAD) fx[1] = load_logit(static_cast<const T*>(A.radius) + r * A.stride, xid);
+    }
+
     // The row index is uniform over the workgroup: keep it in a scalar register.
     // A row's centre logits are loaded and worked on first, its verifier logits second: the centre row
     // carries most of the arithmetic (both of its passes), the verifier row only a short one, so
@@ -364,6 +387,8 @@ void stream_kernel(const RowArgs A)
     int row = __builtin_amdgcn_readfirstlane((int)blockIdx.x);     // the launcher keeps gridDim.x <= N
     u32x4 buf[NVEC];                                               // a row as loaded: centre and verifier row in turn
     load_row(buf, A.draft, row);
+    if (tid < my_rows) { sm_fx[tid][0] = fx[0]; sm_fx[tid][1] = fx[1]; }   // waits for the small loads only: issued first
+    int done = 0;                                                  // rows this workgroup has streamed
 
     for (;;) {
         const int next = __builtin_amdgcn_readfirstlane(row + step);
@@ -448,25 +473,34 @@ void stream_kernel(const RowArgs A)
             // x_i = e_i fw / S: hand fuse_row the partition sum expressed in this wave's units
             const FuseRow fr = fuse_row(fw > 0.0 ? S / fw : 1.0, A.a, A.b);
             double q5[NQ];
-            // The shift: the values of the row's first token.  e0 is 2^up times larger in this wave's units than
-            // in wave 0's; a wave more than 2^64 away from wave 0 takes its sums about 0 and its lane 0 moves them
-            // to the common shift afterwards.
-            const float up = sm_ref[1] - nw;
-            const bool near = fabsf(up) <= 64.f;                   // uniform over the wave; false for inf and nan
-            auto shift_of = [&](float e0, const FuseRow& r) {
+            auto shift_of = [&](float eref, const FuseRow& r) {
                 Shift k;
                 k.kc = 0.f;
                 if constexpr (RAD) {
-                    if constexpr (WIDE) fuse_token_rad_wide(e0, raw0, r, (float)A.kappa, (float)A.rmax, k.kl, k.kw, k.kc);
-                    else fuse_token_rad(e0, raw0, r, (float)A.kappa, (float)A.rmax, k.kl, k.kw);
+                    if constexpr (WIDE) fuse_token_rad_wide(eref, raw0, r, (float)A.kappa, (float)A.rmax, k.kl, k.kw, k.kc);
+                    else fuse_token_rad(eref, raw0, r, (float)A.kappa, (float)A.rmax, k.kl, k.kw);
                 } else {
-                    if constexpr (WIDE) fuse_token_wide(e0, r, k.kl, k.kw, k.kc);
-                    else fuse_token<true>(e0, r, k.kl, k.kw);
+                    if constexpr (WIDE) fuse_token_wide(eref, r, k.kl, k.kw, k.kc);
+                    else fuse_token<true>(eref, r, k.kl, k.kw);
                 }
                 return k;
             };
+            // The common shift of a flat row (see Shift), 0 elsewhere.  A wave whose units are too far from the
+            // row's (scalar radius) or from wave 0's (tensor radius) to form it takes its sums about 0, and its
+            // lane 0 moves them to the common shift afterwards.
+            const bool flat = emax * (double)V <= 2.0 * S;         // uniform over the workgroup
+            bool near = false;
             Shift sh = {0.f, 0.f, 0.f};
-            if (near) sh = shift_of(ldexpf(sm_e0, (int)up), fr);
+            if (flat) {
+                if constexpr (RAD) {
+                    const float up = sm_ref[1] - nw;               // e0 is 2^up times larger in this wave's units
+                    near = fabsf(up) <= 64.f;                      // uniform over the wave; false for inf and nan
+                    if (near) sh = shift_of(ldexpf(sm_e0, (int)up), fr);
+                } else {
+                    near = fw >= 0x1p-64;                          // uniform over the wave
+                    if (near) sh = shift_of((float)(S / (fw * (double)V)), fr);
+                }
+            }
             double kq[3] = {(double)sh.kl, (double)sh.kw, (double)sh.kc};   // fp64 copy (the tiny path sets its own)
             bool tiny = false;
             if constexpr (NVEC == 1) tiny = V <= kTinyVocab;       // uniform
@@ -517,15 +551,25 @@ void stream_kernel(const RowArgs A)
             }
             if (lane == 0) {
                 // to row units (the complements are plain numbers: nothing to rescale)
+                double ku = fw;
                 const double f2 = fw * fw;
                 q5[0] *= fw; q5[1] *= fw; q5[2] *= f2; q5[3] *= f2; q5[4] *= f2;
-                if (!near && !tiny) {
-                    // Rare: this wave's sums are about 0.  Form the common shift in wave 0's units, as wave 0 does,
-                    // and move the sums to it:  with c = 0 - K and n tokens,
-                    //   sum (d - K) = s1 + n c,  sum (d - K)^2 = s2 + 2 c s1 + n c^2,  likewise the cross moment.
-                    const double fw0 = pow2_of(sm_ref[1] - n);
-                    const Shift k0 = shift_of(sm_e0, fuse_row(S / fw0, A.a, A.b));
-                    const double cl = -(double)k0.kl * fw0, cw = -(double)k0.kw * fw0, cc = -(double)k0.kc;
+                if (flat && !near && !tiny) {
+                    // Rare: this wave's sums are about 0.  Form the common shift the long way round, in row units
+                    // (scalar radius) or in wave 0's (tensor radius), and move the sums to it:  with c = 0 - K and
+                    // n tokens,  sum (d - K) = s1 + n c,  sum (d - K)^2 = s2 + 2 c s1 + n c^2,  likewise the cross
+                    // moment.
+                    double fw0 = 1.0;
+                    Shift k0;
+                    if constexpr (RAD) {
+                        fw0 = pow2_of(sm_ref[1] - n);
+                        k0 = shift_of(sm_e0, fuse_row(S / fw0, A.a, A.b));
+                    } else {
+                        k0 = shift_of((float)(S / (double)V), fuse_row(S, A.a, A.b));
+                    }
+                    kq[0] = (double)k0.kl * fw0; kq[1] = (double)k0.kw * fw0; kq[2] = (double)k0.kc;
+                    ku = 1.0;
+                    const double cl = -kq[0], cw = -kq[1], cc = -kq[2];
                     int cnt = 0;                                   // tokens of the row in this wave
 #pragma unroll
                     for (int j = 0; j < NVEC; ++j) cnt += min(max(V - (j * THREADS + wave * 64) * EPV, 0), 64 * EPV);
@@ -542,7 +586,7 @@ void stream_kernel(const RowArgs A)
                 }
 #pragma unroll
                 for (int i = 0; i < NQ; ++i) sm_q5[wave * NQ + i] = q5[i];
-                if (wave == 0) { sm_k[0] = kq[0] * fw; sm_k[1] = kq[1] * fw; sm_k[2] = kq[2]; }
+                if (wave == 0) { sm_k[0] = kq[0] * ku; sm_k[1] = kq[1] * ku; sm_k[2] = kq[2]; }
             }
         }
 
@@ -578,7 +622,8 @@ void stream_kernel(const RowArgs A)
                     if (rt != -INFINITY) Z += sm_Z[w] * pow2_of(rt - nt);
                 }
             }
-            RowStats* st = A.stats + row;
+            RowStats stv;
+            RowStats* const st = &stv;
             st->S = S; st->Z = Z; st->n = n; st->nt = nt; st->mc = mc;
             // the waves' sums are about one common shift (wave 0 left it in row units): they simply add
             double t[NQ];
@@ -608,31 +653,68 @@ void stream_kernel(const RowArgs A)
             st->mode = mode;
 #pragma unroll
             for (int i = 0; i < 5; ++i) st->q[i] = t[i];
+            // with finishing the statistics stay in LDS until the end (lane `done` writes them out then)
+            if (finish) sm_rows[done] = stv;
+            else A.stats[row] = stv;
         }
 
+        ++done;
         if (!has_next) break;
         row = next;
+    }
+
+    // ---- finishing (quantify-only): one lane per row of this workgroup ------------------------------------------
+    if (finish) {
+        __syncthreads();
+        if (tid < my_rows) {
+            const int64_t r = (int64_t)blockIdx.x + (int64_t)tid * step;
+            const RowStats st = sm_rows[tid];
+            A.stats[r] = st;
+            const float cx = A.ids ? sm_fx[tid][0] : st.mc;        // no ids: the arg-max token is reported
+            finish_row(A, r, st, cx, 0.f, sm_fx[tid][1], 0.f, true, false);
+        }
     }
 }
 
 // ---- dispatch ---------------------------------------------------------------------------------------------
 
+// A launch request: with `launch` unset the dispatch below only reports the grid it would use.
+struct StreamLaunch {
+    bool launch;
+    bool finish_rows;      // the caller wants the kernel to finish its rows if the shape allows it
+    hipStream_t stream;
+    StreamPlan plan;       // out
+};
+
+StreamPlan make_plan(int64_t N, int64_t resident)
+{
+    StreamPlan p;
+    p.grid = (unsigned)(N < resident ? N : resident);
+    p.rows_per_wg = (int)((N + p.grid - 1) / p.grid);
+    p.can_finish = p.rows_per_wg <= kMaxRowsPerWg;
+    return p;
+}
+
 template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V, bool RAD, bool WIDE = false>
-hipError_t launch_stream_kernel(const RowArgs& a, hipStream_t s)
+hipError_t launch_stream_kernel(const RowArgs& a, StreamLaunch& L)
 {
     // One wave of resident workgroups, each walking over rows with stride gridDim.x.  The register
     // budget the kernel was compiled for fixes how many fit: target_waves() waves per SIMD, and a
     // workgroup puts THREADS / 256 waves on each of the four SIMDs of a compute unit (a 128-lane one: one
     // wave on two of them).
     constexpr int per_cu = target_waves<T, THREADS, NVEC, RAD>() * 256 / THREADS;
-    const int64_t resident = (int64_t)per_cu * compute_units();
-    const unsigned grid = (unsigned)(a.N < resident ? a.N : resident);
-    hipLaunchKernelGGL((stream_kernel<T, THREADS, NVEC, DO_Q, DO_V, RAD, WIDE>), dim3(grid), dim3(THREADS), 0, s, a);
+    L.plan = make_plan(a.N, (int64_t)per_cu * compute_units());
+    L.plan.can_finish = L.plan.can_finish && DO_Q && !DO_V;
+    if (!L.launch) return hipSuccess;
+    RowArgs b = a;
+    b.finish = (L.finish_rows && L.plan.can_finish) ? 1 : 0;
+    hipLaunchKernelGGL((stream_kernel<T, THREADS, NVEC, DO_Q, DO_V, RAD, WIDE>), dim3(L.plan.grid), dim3(THREADS), 0,
+                       L.stream, b);
     return hipGetLastError();
 }
 
 template <typename T, int THREADS, int NVEC>
-hipError_t launch_stream_cfg(Mode mode, const RowArgs& a, hipStream_t s)
+hipError_t launch_stream_cfg(Mode mode, const RowArgs& a, StreamLaunch& s)
 {
     const bool rad = a.radius != nullptr;
     if (mode != Mode::Verify && wide_radius(a)) {
@@ -654,7 +736,7 @@ hipError_t launch_stream_cfg(Mode mode, const RowArgs& a, hipStream_t s)
 }
 
 template <typename T>
-hipError_t launch_stream_typed(Mode mode, const RowArgs& a, hipStream_t s)
+hipError_t launch_stream_typed(Mode mode, const RowArgs& a, StreamLaunch& s)
 {
     const int vecs = (a.V + Elt<T>::kPerVec - 1) / Elt<T>::kPerVec;   // 16-byte vectors per row
     if (vecs <= 256 * 1)  return launch_stream_cfg<T, 256, 1>(mode, a, s);
@@ -680,11 +762,22 @@ hipError_t launch_stream_typed(Mode mode, const RowArgs& a, hipStream_t s)
 
 int max_vocab(int dtype) { return dtype == 0 ? 1024 * 8 * 4 : 1024 * 8 * 8; }
 
-hipError_t launch_stream(Mode mode, int dtype, const RowArgs& args, hipStream_t stream)
+StreamPlan plan_stream(Mode mode, int dtype, const RowArgs& args)
+{
+    StreamLaunch L{false, false, nullptr, {0u, 0, false}};
+    if (args.N > 0) {
+        if (dtype == 0) (void)launch_stream_typed<float>(mode, args, L);
+        else (void)launch_stream_typed<bf16_t>(mode, args, L);
+    }
+    return L.plan;
+}
+
+hipError_t launch_stream(Mode mode, int dtype, const RowArgs& args, bool finish_rows, hipStream_t stream)
 {
     if (args.N <= 0) return hipSuccess;
-    return dtype == 0 ? launch_stream_typed<float>(mode, args, stream)
-                      : launch_stream_typed<bf16_t>(mode, args, stream);
+    StreamLaunch L{true, finish_rows, stream, {0u, 0, false}};
+    return dtype == 0 ? launch_stream_typed<float>(mode, args, L)
+                      : launch_stream_typed<bf16_t>(mode, args, L);
 }
 
 }  // namespace ciar

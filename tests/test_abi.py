@@ -108,11 +108,14 @@ def test_argument_errors_are_reported_before_any_launch(L):
     assert L.ciar_dense_intervals(FAKE, None, 4, a, None, None, None, None) == EINVAL
     assert L.ciar_dense_intervals(FAKE, FAKE + 8, 4, a, FAKE, None, None, None) == EALIGN     # radius alignment
     # the stages on their own
-    assert L.ciar_stream_rows(FAKE, None, None, 0, 4, a, FAKE, 4096, None) == EINVAL      # nothing to compute
-    assert L.ciar_stream_rows(FAKE, None, FAKE, 1, 4, a, None, 0, None) == EWORK
-    assert L.ciar_stream_rows(None, None, FAKE, 1, 4, a, FAKE, 4096, None) == EINVAL
-    assert L.ciar_stream_rows(FAKE, FAKE, FAKE, 0, 4, a, FAKE, 4096, None) == EINVAL      # radius without intervals
-    assert L.ciar_stream_rows(FAKE, FAKE + 4, FAKE, 1, 4, a, FAKE, 4096, None) == EALIGN  # radius alignment
+    for stage in (L.ciar_stream_rows, L.ciar_finish_rows):
+        assert stage(FAKE, None, None, None, None, None, 4, a, *([None] * 11), FAKE, 4096, None) == EINVAL   # no output
+        assert stage(FAKE, None, None, None, None, None, 4, a, FAKE, *([None] * 10), None, 0, None) == EWORK
+        assert stage(None, None, None, None, None, None, 4, a, FAKE, *([None] * 10), FAKE, 4096, None) == EINVAL
+        assert stage(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 4, a, *([None] * 7), FAKE, None, None, None, FAKE, 4096,
+                     None) == EINVAL                                                 # radius without intervals
+        assert stage(FAKE, FAKE + 4, None, None, None, None, 4, a, FAKE, *([None] * 10), FAKE, 4096,
+                     None) == EALIGN                                                 # radius alignment
     assert L.ciar_finish_rows(FAKE, None, None, FAKE, FAKE, FAKE, 4, a, *([None] * 7), FAKE, FAKE, None, None,
                               FAKE, 4096, None) == EINVAL                            # verify outputs, no target
     assert L.ciar_finish_rows(FAKE, None, FAKE, FAKE, FAKE, FAKE, 4, a, FAKE, *([None] * 10), FAKE, 4096,

@@ -55,8 +55,9 @@ def _run_case(ciar, oracle, draft, target, ids, ua, ur, P, vocab=None, tag="", h
     vonly = ciar.verify(draft, target, ids, ua, ur, P, vocab=vocab, workspace=ws)
     # the launch configuration the benchmark times: the two stages called one after the other
     ws2 = torch.empty_like(ws)
-    ciar.stream_rows(draft, target, True, P, ws2, vocab=vocab, radius=radius)
-    staged = ciar.finish_rows(draft, target, ids, ua, ur, P, ws2, with_intervals=True, vocab=vocab, radius=radius)
+    staged = ciar.stream_rows(draft, target, ids, ua, ur, P, ws2, with_intervals=True, vocab=vocab, radius=radius)
+    staged = ciar.finish_rows(draft, target, ids, ua, ur, P, ws2, with_intervals=True, vocab=vocab, radius=radius,
+                              out=staged)
     torch.cuda.synchronize()
     # the entry points run the same arithmetic: identical decisions, floats equal up to the freedom the compiler
     # has in contracting multiply-adds differently in the fused and the single-purpose kernels (seen only where
