@@ -446,6 +446,7 @@ def test_degenerate_rows(ciar, oracle, dtype):
     """Uniform, one-hot, extreme-magnitude, masked (-inf) and identical draft/target rows."""
     V, K = 16384, 4
     g = torch.Generator(device="cuda").manual_seed(7)
+    torch.manual_seed(77)                                              # the rows below come from the global CPU generator
     rows = []
     rows.append(torch.zeros(V))                                        # uniform
     rows.append(torch.full((V,), 3.25))                                # uniform, shifted
@@ -457,6 +458,8 @@ def test_degenerate_rows(ciar, oracle, dtype):
     r = torch.full((V,), -float("inf")); r[5] = 1.0; r[9000] = 0.5; rows.append(r)   # two live tokens
     r = torch.randn(V) * 0.01; rows.append(r)                          # nearly flat
     r = torch.randn(V) * 10; rows.append(r)                            # very spread
+    r = torch.randn(V) * 10; r[0] = r.max() + 3.0; rows.append(r)      # very spread, the first token the largest
+    r = torch.randn(V) * 0.5; r[0] = 6.0; rows.append(r)               # flat but for a large first token
     c = torch.stack(rows).cuda()
     N = c.shape[0]
     t = c.clone()
@@ -464,10 +467,10 @@ def test_degenerate_rows(ciar, oracle, dtype):
     t[9] = c[9] + 1.0 * torch.randn(V, device="cuda", generator=g)
     t[2] = torch.full((V,), -30.0, device="cuda"); t[2, 100] = 5.0     # target disagrees with a one-hot draft
     c, t = c.to(dtype), t.to(dtype)
-    ids = torch.tensor([0, 5, 77, V - 1, 3, 4, 1, 5, 6, 7], dtype=torch.int32, device="cuda")
+    ids = torch.tensor([0, 5, 77, V - 1, 3, 4, 1, 5, 6, 7, 0, 0], dtype=torch.int32, device="cuda")
     ids[4] = int(torch.argmax(c[4].float())); ids[9] = int(torch.argmax(c[9].float()))
-    ua = torch.tensor([0.0, 0.999, 0.5, 0.3, 0.99, 0.2, 0.7, 0.1, 0.6, 0.999], device="cuda")
-    ur = torch.tensor([0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7, 0.8, 0.9, 1 - 2.0 ** -24], device="cuda")
+    ua = torch.tensor([0.0, 0.999, 0.5, 0.3, 0.99, 0.2, 0.7, 0.1, 0.6, 0.999, 0.4, 0.8], device="cuda")
+    ur = torch.tensor([0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7, 0.8, 0.9, 1 - 2.0 ** -24, 0.35, 0.65], device="cuda")
     for norm in (True, False):
         for kap in (-1.0, 0.0, 3.0):
             P = ciar.Params(confidence=0.9, radius_scale=kap, normalize=norm, window=K, tau=1e-3)
