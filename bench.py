@@ -215,6 +215,10 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=2, help="1..5 (default 2: the headline configuration)")
     ap.add_argument("--copies", type=int, default=8, help="distinct input copies rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="HIP streams the steps rotate through (each with its own workspace and outputs): "
+                         "consecutive batches are independent, so with 2 the streaming kernel of one batch "
+                         "overlaps the finishing kernels of the previous one")
     ap.add_argument("--radius-tensor", action="store_true",
                     help="tensor-radius mode: a raw radius row per position is streamed as well (not the headline)")
     ap.add_argument("--heads", type=int, default=0,
@@ -258,35 +262,43 @@ def main() -> int:
         r0 = wl.make_radius(w, device=dev)
         rads = [r0] + [r0.clone() for _ in range(copies - 1)]
     W = (N + K - 1) // K
-    out = {k: torch.empty(N, dtype=torch.float32, device=dev)
-           for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score")}
-    out["flags"] = torch.empty(N, dtype=torch.uint8, device=dev)
-    out["accept"] = torch.empty(N, dtype=torch.uint8, device=dev)
-    out["row_id"] = torch.empty(N, dtype=torch.int32, device=dev)
-    wout = {"accept_len": torch.empty(W, dtype=torch.int32, device=dev),
-            "resampled_id": torch.empty(W, dtype=torch.int32, device=dev)}
+    nstreams = max(1, args.streams)
+
+    def outputs():
+        o = {k: torch.empty(N, dtype=torch.float32, device=dev)
+             for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score")}
+        o["flags"] = torch.empty(N, dtype=torch.uint8, device=dev)
+        o["accept"] = torch.empty(N, dtype=torch.uint8, device=dev)
+        o["row_id"] = torch.empty(N, dtype=torch.int32, device=dev)
+        o["accept_len"] = torch.empty(W, dtype=torch.int32, device=dev)
+        o["resampled_id"] = torch.empty(W, dtype=torch.int32, device=dev)
+        return o
 
     import ctypes
     from paper_2603_25463_amd.binding import _ptr, _stream, _check
     L = ciar.lib()
     cp = P.to_c(w.draft)
-    stream = torch.cuda.current_stream()
-    sp = _stream(stream)
-    ws = torch.empty(ciar.workspace_bytes(N, cp), dtype=torch.uint8, device=dev)
+    # one lane per stream: its own outputs and workspace (default priority)
+    streams = [torch.cuda.current_stream()] + [torch.cuda.Stream(device=dev) for _ in range(nstreams - 1)]
+    outs = [outputs() for _ in range(nstreams)]
+    wss = [torch.empty(ciar.workspace_bytes(N, cp), dtype=torch.uint8, device=dev) for _ in range(nstreams)]
+    out, stream, sp = outs[0], streams[0], _stream(streams[0])
 
     def step(i: int, ev0=None, ev1=None):
         """One pass of the hot path: streaming kernel, then the two finishing kernels (one stream)."""
         d, t = drafts[i % copies], targets[i % copies]
         rad = rads[i % copies] if rads else None
+        lane = i % nstreams
+        o, ws, st = outs[lane], wss[lane], streams[lane]
         if ev0 is not None:
-            ev0.record(stream)
+            ev0.record(st)
         call = (_ptr(d), _ptr(rad), _ptr(t), _ptr(w.ids), _ptr(w.u_accept), _ptr(w.u_resample), N, ctypes.byref(cp),
-                _ptr(out["p_lo"]), _ptr(out["p_mid"]), _ptr(out["p_hi"]), _ptr(out["omega"]), _ptr(out["sigma"]),
-                _ptr(out["score"]), _ptr(out["flags"]), _ptr(out["accept"]), _ptr(out["row_id"]),
-                _ptr(wout["accept_len"]), _ptr(wout["resampled_id"]), _ptr(ws), ws.numel(), sp)
+                _ptr(o["p_lo"]), _ptr(o["p_mid"]), _ptr(o["p_hi"]), _ptr(o["omega"]), _ptr(o["sigma"]),
+                _ptr(o["score"]), _ptr(o["flags"]), _ptr(o["accept"]), _ptr(o["row_id"]),
+                _ptr(o["accept_len"]), _ptr(o["resampled_id"]), _ptr(ws), ws.numel(), _stream(st))
         _check(L.ciar_stream_rows(*call))
         if ev1 is not None:
-            ev1.record(stream)
+            ev1.record(st)
         _check(L.ciar_finish_rows(*call))
 
     if args.calibrate_copy:
@@ -354,7 +366,7 @@ def main() -> int:
         "config": {"workload": f"cfg{args.workload} {spec.name}: {spec.images} images x {spec.grid}x{spec.grid} = "
                                f"{N} positions, V={V}, {'fp32' if elt == 4 else 'bf16'} logits, window K={K}, "
                                + ("radius tensor N(mu_row, 1), kappa 1, tau 0.30" if rads else "confidence 0.9, tau 0.30"),
-                   "input_copies_rotated": copies, "launches_per_step": 3 if K <= 256 else 4},
+                   "input_copies_rotated": copies, "launches_per_step": 3 if K <= 256 else 4, "streams": nstreams},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None if rads else measured_traffic(spec.name),
                      "kernel": "stream_kernel (every logit row of every position, read once)", "kernel_avg_us": 1e3 * kern_avg_ms,
