@@ -34,10 +34,11 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
     const int V = A.V;
     const bool rad = A.radius != nullptr;
     const bool need_argmax = A.ids == nullptr && (A.p_lo || A.p_mid || A.p_hi);
-    const bool tiny = V <= 64;
+    bool flat_h = true;                                            // this lane's head: a flat row (see below)
 
     if (tid < H) {
         const RowStats st = A.stats[(int64_t)tid * A.N + row];
+        flat_h = (double)exp2_ref(st.mc, st.n == -INFINITY ? 0.f : st.n) * (double)V <= 2.0 * st.S;
         const RowScore rs = finish_score(st.q, st.S, st.mode, A, st.kl, st.kw);
         const double Bc = (rad ? 1.0 : A.b) / st.S, Wc = (rad ? 1.0 : A.a - A.b) / st.S;
         sm_fr[tid] = fuse_row(st.S, A.a, A.b);
@@ -47,7 +48,11 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
         sm_invS[tid] = (float)(1.0 / st.S);
         sm_S[tid] = st.S; sm_al[tid] = rs.alpha_l; sm_au[tid] = rs.alpha_u;
     }
-    __syncthreads();
+    // Token arithmetic in fp64 ("precise") for rows of a handful of tokens and for rows that are flat in every
+    // head (largest probability <= 2 / V): there the widths can agree to 1e-4 and better while their fp32 errors
+    // (~1e-7 each, uncorrelated when the radii differ from token to token) do not, and Omega ~ V multiplies what
+    // is left of the spread.
+    const bool precise = __syncthreads_and(flat_h ? 1 : 0) != 0 || V <= 64;   // uniform; also the barrier
 
     const float kap = (float)A.kappa, rmax = (float)A.rmax;
     const int nvec = (V + EPV - 1) / EPV;
@@ -90,17 +95,15 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
         const T* crow = static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride;
         const T* rrow = static_cast<const T*>(rad ? A.radius : A.draft) + (int64_t)h * head_stride + row * A.stride;
         const float c0 = load_logit(crow, 0), r0 = load_logit(rrow, 0);
-        if (tiny) head_token_tiny(h, c0, r0, KD, KC);
+        if (precise) head_token_tiny(h, c0, r0, KD, KC);
         else head_token(h, c0, r0, sm_fr[h], KD, KC);
     }
     double s1 = 0.0, s2 = 0.0;                                     // sum (D_i - KD), sum (D_i - KD)^2
     double c1 = 0.0, c2 = 0.0, cbig = 0.0;                         // WIDE: sum (C_i - KC), its square, max C_i
     float best = -INFINITY;
     int best_i = INT_MAX;
-    if (tiny) {
-        // A handful of tokens (one vector per lane at most): widths are O(1) and Sigma can be an exact zero
-        // (two tokens), which fp32 token arithmetic cannot resolve to 1e-7; the few tokens are done in fp64.
-        if (tid < nvec) {
+    if (precise) {
+        for (int v = tid; v < nvec; v += 256) {
             double D[EPV], C[EPV];
             float pm[EPV];
 #pragma unroll
@@ -109,16 +112,16 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
                 const gvec c = (gvec)(gbytes)(static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride);
                 const gvec r = (gvec)(gbytes)(static_cast<const T*>(rad ? A.radius : A.draft) +
                                               (int64_t)h * head_stride + row * A.stride);
-                const u32x4 cw4 = c[tid], rw4 = r[tid];
+                const u32x4 cw4 = c[v], rw4 = r[v];
                 float cv[EPV], rv[EPV];
                 E::unpack(cw4, cv);
                 E::unpack(rw4, rv);
                 for (int k = 0; k < EPV; ++k) {
-                    if (tid * EPV + k < V) pm[k] += (float)head_token_tiny(h, cv[k], rv[k], D[k], C[k]);
+                    if (v * EPV + k < V) pm[k] += (float)head_token_tiny(h, cv[k], rv[k], D[k], C[k]);
                 }
             }
             for (int k = 0; k < EPV; ++k) {
-                const int tok = tid * EPV + k;
+                const int tok = v * EPV + k;
                 if (tok < V) {
                     const double d = D[k] - KD;
                     s1 += d;
@@ -133,7 +136,7 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
         }
     }
     constexpr int UB = 16 / EPV;                                   // vectors of a head in flight per lane
-    for (int v0 = tid; !tiny && v0 < nvec; v0 += 256 * UB) {
+    for (int v0 = tid; !precise && v0 < nvec; v0 += 256 * UB) {
         double D[UB][EPV];                                         // fp64 across heads
         double C[WIDE ? UB : 1][EPV];
         float pm[UB][EPV];
