@@ -11,8 +11,9 @@ configuration the headline metric is quoted on.  Eight distinct copies of the in
 so that the 256 MB last-level cache cannot serve a step's 268 MB of logits from the previous one.
 
 Prints ONE JSON line (see the keys below).  `roofline.achieved` is the streaming kernel's
-algorithmic bytes per launch over its mean duration, taken with events on the launch stream
-inside the timed region; `cpu_baseline` is the fp64 oracle timed on the host cores on the same batch.
+algorithmic bytes per launch over its mean duration inside the timed region, taken with two HIP events
+that the kernel's own dispatch records on the launch stream at its start and end
+(ciar_stream_rows_timed); `cpu_baseline` is the fp64 oracle timed on the host cores on the same batch.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--no-cpu-baseline]
 """
@@ -290,15 +291,15 @@ def main() -> int:
         rad = rads[i % copies] if rads else None
         lane = i % nstreams
         o, ws, st = outs[lane], wss[lane], streams[lane]
-        if ev0 is not None:
-            ev0.record(st)
         call = (_ptr(d), _ptr(rad), _ptr(t), _ptr(w.ids), _ptr(w.u_accept), _ptr(w.u_resample), N, ctypes.byref(cp),
                 _ptr(o["p_lo"]), _ptr(o["p_mid"]), _ptr(o["p_hi"]), _ptr(o["omega"]), _ptr(o["sigma"]),
                 _ptr(o["score"]), _ptr(o["flags"]), _ptr(o["accept"]), _ptr(o["row_id"]),
                 _ptr(o["accept_len"]), _ptr(o["resampled_id"]), _ptr(ws), ws.numel(), _stream(st))
-        _check(L.ciar_stream_rows(*call))
-        if ev1 is not None:
-            ev1.record(st)
+        if ev0 is not None:
+            # the kernel's dispatch records the two events itself, at its start and at its end
+            _check(L.ciar_stream_rows_timed(*call, ev0.cuda_event, ev1.cuda_event))
+        else:
+            _check(L.ciar_stream_rows(*call))
         _check(L.ciar_finish_rows(*call))
 
     if args.calibrate_copy:
@@ -311,11 +312,13 @@ def main() -> int:
         step(i)
     torch.cuda.synchronize()
 
-    # The streaming kernel is bracketed by events on every fourth timed step: an event pair costs the
-    # stream about 5 us (two marker packets), which would otherwise be charged to every step.
+    # The streaming kernel's dispatch carries a start and a stop event on every fourth timed step (kept sparse so
+    # that whatever the events cost is not charged to every step).
     every = 4
     ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(0, args.steps, every)]
     ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(0, args.steps, every)]
+    for e in ev0 + ev1:
+        e.record(stream)                         # creates the HIP event behind the object; recorded again below
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):

@@ -188,6 +188,22 @@ int ciar_stream_rows(const void* draft_logits, const void* radius, const void* t
                      int32_t* accept_len, int32_t* resampled_id,
                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Measurement aid: ciar_stream_rows whose streaming-kernel dispatch records two HIP events (hipEvent_t handles,
+ * created by the caller with timing enabled, host pointers; both required) at the kernel's start and at its end,
+ * so that hipEventElapsedTime(start, stop) is the kernel's own duration without the dispatch latency that an
+ * event pair recorded around the call also spans.  N = 0 launches nothing and records nothing.
+ */
+int ciar_stream_rows_timed(const void* draft_logits, const void* radius, const void* target_logits,
+                           const int32_t* draft_ids,
+                           const float* u_accept, const float* u_resample, int64_t N, const ciar_params* params,
+                           float* p_lo, float* p_mid, float* p_hi,
+                           float* omega, float* sigma, float* score, uint8_t* flags,
+                           uint8_t* accept, int32_t* row_resample_id,
+                           int32_t* accept_len, int32_t* resampled_id,
+                           void* workspace, size_t workspace_bytes, void* hip_stream,
+                           void* start_event, void* stop_event);
+
 int ciar_finish_rows(const void* draft_logits, const void* radius, const void* target_logits,
                      const int32_t* draft_ids,
                      const float* u_accept, const float* u_resample, int64_t N, const ciar_params* params,

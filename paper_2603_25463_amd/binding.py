@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
         L.ciar_quantify_verify.argtypes = [vp, vp, vp, vp, vp, vp, i64, pp] + [vp] * 11 + [vp, sz, vp]
         L.ciar_stream_rows.restype = ctypes.c_int
         L.ciar_stream_rows.argtypes = [vp, vp, vp, vp, vp, vp, i64, pp] + [vp] * 11 + [vp, sz, vp]
+        L.ciar_stream_rows_timed.restype = ctypes.c_int
+        L.ciar_stream_rows_timed.argtypes = [vp, vp, vp, vp, vp, vp, i64, pp] + [vp] * 11 + [vp, sz, vp, vp, vp]
         L.ciar_finish_rows.restype = ctypes.c_int
         L.ciar_finish_rows.argtypes = [vp, vp, vp, vp, vp, vp, i64, pp] + [vp] * 11 + [vp, sz, vp]
         L.ciar_window_epilogue.restype = ctypes.c_int

@@ -162,6 +162,7 @@ struct Call {
     float* p_lo; float* p_mid; float* p_hi; float* omega; float* sigma; float* score; uint8_t* flags;
     uint8_t* accept; int32_t* row_id; int32_t* accept_len; int32_t* resampled_id;
     void* workspace; size_t workspace_bytes; hipStream_t stream;
+    hipEvent_t ev_start = nullptr, ev_stop = nullptr;      // ciar_stream_rows_timed
 };
 
 bool wants_intervals(const Call& c)
@@ -231,7 +232,7 @@ int run_stream(const Call& c, ciar::Mode mode)
         if (e != hipSuccess) return hip_fail(e, "arg-max kernel launch");
         a.ids = a.reject_list;
     }
-    const hipError_t e = ciar::launch_stream(mode, c.params->dtype, a, true, c.stream);
+    const hipError_t e = ciar::launch_stream(mode, c.params->dtype, a, true, c.stream, c.ev_start, c.ev_stop);
     if (e != hipSuccess) return hip_fail(e, "streaming kernel launch");
     return CIAR_OK;
 }
@@ -326,6 +327,26 @@ int ciar_stream_rows(const void* draft_logits, const void* radius, const void* t
     const Call c{draft_logits, radius, target_logits, draft_ids, u_accept, u_resample, N, params, p_lo, p_mid, p_hi, omega,
                  sigma, score, flags, accept, row_resample_id, accept_len, resampled_id, workspace, workspace_bytes,
                  static_cast<hipStream_t>(hip_stream)};
+    if (target_logits && !wants_verify(c)) return fail(CIAR_EINVAL, "target_logits given but no verify output");
+    if (!target_logits && wants_verify(c)) return fail(CIAR_EINVAL, "verify outputs need target_logits");
+    const ciar::Mode mode = !target_logits ? ciar::Mode::Quantify
+                                           : (wants_intervals(c) ? ciar::Mode::Fused : ciar::Mode::Verify);
+    return run_stream(c, mode);
+}
+
+int ciar_stream_rows_timed(const void* draft_logits, const void* radius, const void* target_logits,
+                           const int32_t* draft_ids, const float* u_accept, const float* u_resample, int64_t N,
+                           const ciar_params* params, float* p_lo, float* p_mid, float* p_hi, float* omega,
+                           float* sigma, float* score, uint8_t* flags, uint8_t* accept, int32_t* row_resample_id,
+                           int32_t* accept_len, int32_t* resampled_id, void* workspace, size_t workspace_bytes,
+                           void* hip_stream, void* start_event, void* stop_event)
+{
+    if (!start_event || !stop_event) return fail(CIAR_EINVAL, "start_event or stop_event is NULL");
+    Call c{draft_logits, radius, target_logits, draft_ids, u_accept, u_resample, N, params, p_lo, p_mid, p_hi, omega,
+           sigma, score, flags, accept, row_resample_id, accept_len, resampled_id, workspace, workspace_bytes,
+           static_cast<hipStream_t>(hip_stream)};
+    c.ev_start = static_cast<hipEvent_t>(start_event);
+    c.ev_stop = static_cast<hipEvent_t>(stop_event);
     if (target_logits && !wants_verify(c)) return fail(CIAR_EINVAL, "target_logits given but no verify output");
     if (!target_logits && wants_verify(c)) return fail(CIAR_EINVAL, "verify outputs need target_logits");
     const ciar::Mode mode = !target_logits ? ciar::Mode::Quantify

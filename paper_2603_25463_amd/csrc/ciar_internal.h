@@ -90,7 +90,9 @@ StreamPlan plan_stream(Mode mode, int dtype, const RowArgs& args);
 // Streaming pass over the rows: statistics and InterFuse sums into args.stats.  With finish_rows (and a plan that
 // allows it, see plan_stream) the kernel also produces the per-row outputs in args; args needs ids and the output
 // pointers then.
-hipError_t launch_stream(Mode mode, int dtype, const RowArgs& args, bool finish_rows, hipStream_t stream);
+// ev_start / ev_stop (both or neither): events the kernel's dispatch records at its start and at its end.
+hipError_t launch_stream(Mode mode, int dtype, const RowArgs& args, bool finish_rows, hipStream_t stream,
+                         hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
 // What remains after the streaming pass: the per-row finishing unless the streaming kernel has done it
 // (rows_finished), the residual draw of rejected rows, and the window outputs (either may be null) for windows of

@@ -52,6 +52,7 @@
 // issues at the fp32 rate) and combined across lanes with DPP and across waves through LDS in a fixed
 // order, so results are deterministic and the per-row scalars carry ~1e-8 relative error.
 #include "ciar_device.h"
+#include <hip/hip_ext.h>
 
 namespace ciar {
 namespace {
@@ -684,6 +685,7 @@ struct StreamLaunch {
     bool finish_rows;      // the caller wants the kernel to finish its rows if the shape allows it
     hipStream_t stream;
     StreamPlan plan;       // out
+    hipEvent_t ev_start, ev_stop;   // both or neither: recorded by the dispatch at the kernel's start and end
 };
 
 StreamPlan make_plan(int64_t N, int64_t resident)
@@ -708,8 +710,12 @@ hipError_t launch_stream_kernel(const RowArgs& a, StreamLaunch& L)
     if (!L.launch) return hipSuccess;
     RowArgs b = a;
     b.finish = (L.finish_rows && L.plan.can_finish) ? 1 : 0;
-    hipLaunchKernelGGL((stream_kernel<T, THREADS, NVEC, DO_Q, DO_V, RAD, WIDE>), dim3(L.plan.grid), dim3(THREADS), 0,
-                       L.stream, b);
+    if (L.ev_start && L.ev_stop)
+        hipExtLaunchKernelGGL((stream_kernel<T, THREADS, NVEC, DO_Q, DO_V, RAD, WIDE>), dim3(L.plan.grid), dim3(THREADS),
+                              0, L.stream, L.ev_start, L.ev_stop, 0, b);
+    else
+        hipLaunchKernelGGL((stream_kernel<T, THREADS, NVEC, DO_Q, DO_V, RAD, WIDE>), dim3(L.plan.grid), dim3(THREADS), 0,
+                           L.stream, b);
     return hipGetLastError();
 }
 
@@ -764,7 +770,7 @@ int max_vocab(int dtype) { return dtype == 0 ? 1024 * 8 * 4 : 1024 * 8 * 8; }
 
 StreamPlan plan_stream(Mode mode, int dtype, const RowArgs& args)
 {
-    StreamLaunch L{false, false, nullptr, {0u, 0, false}};
+    StreamLaunch L{false, false, nullptr, {0u, 0, false}, nullptr, nullptr};
     if (args.N > 0) {
         if (dtype == 0) (void)launch_stream_typed<float>(mode, args, L);
         else (void)launch_stream_typed<bf16_t>(mode, args, L);
@@ -772,10 +778,11 @@ StreamPlan plan_stream(Mode mode, int dtype, const RowArgs& args)
     return L.plan;
 }
 
-hipError_t launch_stream(Mode mode, int dtype, const RowArgs& args, bool finish_rows, hipStream_t stream)
+hipError_t launch_stream(Mode mode, int dtype, const RowArgs& args, bool finish_rows, hipStream_t stream,
+                         hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     if (args.N <= 0) return hipSuccess;
-    StreamLaunch L{true, finish_rows, stream, {0u, 0, false}};
+    StreamLaunch L{true, finish_rows, stream, {0u, 0, false}, ev_start, ev_stop};
     return dtype == 0 ? launch_stream_typed<float>(mode, args, L)
                       : launch_stream_typed<bf16_t>(mode, args, L);
 }

@@ -28,7 +28,7 @@ def _declared_functions():
 def test_header_declares_the_expected_entry_points():
     names = _declared_functions()
     for n in ("ciar_quantify", "ciar_verify", "ciar_quantify_verify", "ciar_dense_intervals",
-              "ciar_stream_rows", "ciar_finish_rows", "ciar_window_epilogue", "ciar_read_rows", "ciar_interdro_loss", "ciar_quantify_multihead", "ciar_multihead_workspace_bytes",
+              "ciar_stream_rows", "ciar_stream_rows_timed", "ciar_finish_rows", "ciar_window_epilogue", "ciar_read_rows", "ciar_interdro_loss", "ciar_quantify_multihead", "ciar_multihead_workspace_bytes",
               "ciar_workspace_bytes", "ciar_params_default", "ciar_last_error", "ciar_version"):
         assert n in names
 
@@ -108,6 +108,8 @@ def test_argument_errors_are_reported_before_any_launch(L):
     assert L.ciar_dense_intervals(FAKE, None, 4, a, None, None, None, None) == EINVAL
     assert L.ciar_dense_intervals(FAKE, FAKE + 8, 4, a, FAKE, None, None, None) == EALIGN     # radius alignment
     # the stages on their own
+    assert L.ciar_stream_rows_timed(FAKE, None, None, None, None, None, 4, a, FAKE, *([None] * 10), FAKE, 4096, None,
+                                    None, FAKE) == EINVAL                            # an event is missing
     for stage in (L.ciar_stream_rows, L.ciar_finish_rows):
         assert stage(FAKE, None, None, None, None, None, 4, a, *([None] * 11), FAKE, 4096, None) == EINVAL   # no output
         assert stage(FAKE, None, None, None, None, None, 4, a, FAKE, *([None] * 10), None, 0, None) == EWORK
