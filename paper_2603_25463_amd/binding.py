@@ -260,12 +260,19 @@ def _staged(entry, draft, target, ids, u_accept, u_resample, params: Params, wor
 
 def stream_rows(draft, target, ids, u_accept, u_resample, params: Params, workspace: torch.Tensor,
                 with_intervals: bool = True, vocab: int | None = None, stream=None, out: dict | None = None,
-                radius: torch.Tensor | None = None) -> dict:
-    """``ciar_stream_rows``: stage 1, the streaming kernel (which also finishes its rows where the launch shape
-    allows).  Returns the output tensors (allocated here unless passed in ``out``); hand the same dict and the same
-    arguments to ``finish_rows``."""
-    return _staged(lib().ciar_stream_rows, draft, target, ids, u_accept, u_resample, params, workspace,
-                   with_intervals, vocab, stream, out, radius)
+                radius: torch.Tensor | None = None, events=None) -> dict:
+    """``ciar_stream_rows``: stage 1, the streaming kernel (a quantify-only call also finishes its rows where the
+    launch shape allows).  Returns the output tensors (allocated here unless passed in ``out``); hand the same dict
+    and the same arguments to ``finish_rows``.  ``events`` = (start, stop), two ``torch.cuda.Event`` objects with
+    timing enabled that have been recorded at least once (which creates the HIP events behind them):
+    ``ciar_stream_rows_timed``, the kernel's dispatch records them at its start and end."""
+    if events is None:
+        return _staged(lib().ciar_stream_rows, draft, target, ids, u_accept, u_resample, params, workspace,
+                       with_intervals, vocab, stream, out, radius)
+    start, stop = events
+    entry = lambda *a: lib().ciar_stream_rows_timed(*a, start.cuda_event, stop.cuda_event)
+    return _staged(entry, draft, target, ids, u_accept, u_resample, params, workspace, with_intervals, vocab, stream,
+                   out, radius)
 
 
 def finish_rows(draft, target, ids, u_accept, u_resample, params: Params, workspace: torch.Tensor,

@@ -870,6 +870,27 @@ def test_random_parameters_interdro(ciar, oracle, seed):
     _check_dro(g, o, N)
 
 
+def test_timed_stage_records_the_kernel_and_changes_nothing(ciar):
+    """ciar_stream_rows_timed: same results as the untimed stage, and the two events enclose the kernel."""
+    c, t, ids, ua, ur = _random_case(16384, 16384, 512, 8, torch.float32, seed=91)
+    P = ciar.Params(window=8)
+    ws = torch.empty(ciar.workspace_bytes(512, P.to_c(c)), dtype=torch.uint8, device="cuda")
+    say("[timed stage] V=16384 N=512")
+    ref = ciar.stream_rows(c, t, ids, ua, ur, P, ws)
+    ref = ciar.finish_rows(c, t, ids, ua, ur, P, ws, out=ref)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(); e1.record()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        got = ciar.stream_rows(c, t, ids, ua, ur, P, ws, events=(e0, e1))
+        got = ciar.finish_rows(c, t, ids, ua, ur, P, ws, out=got)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        assert 0.002 < ms < 5.0, ms                                    # a kernel over 64 MB: microseconds, not zero
+    for k in ref:
+        assert torch.equal(ref[k], got[k]), k
+
+
 def test_bad_arguments_raise(ciar):
     c = torch.zeros((4, 1024), device="cuda")
     with pytest.raises(ciar.CiarError, match="CIAR_EUNSUPPORTED"):
