@@ -777,6 +777,49 @@ def test_random_parameters(ciar, oracle, seed):
         assert not bad.any(), (name, np.argwhere(bad)[0], gd[bad][0], od[bad][0])
 
 
+@pytest.mark.parametrize("seed", list(range(6)))
+def test_random_parameters_many_rows(ciar, oracle, seed):
+    """Thousands of rows of mixed character and a small vocabulary: every workgroup of the streaming kernel walks
+    over several rows, windows straddle workgroups, and the finishing kernels see long lists of rejected rows."""
+    rng = np.random.default_rng(39000 + seed)
+    dtype = (torch.float32, torch.bfloat16)[seed % 2]
+    epv = 4 if dtype == torch.float32 else 8
+    V = int(rng.integers(40, 2100))
+    stride = -(-V // epv) * epv + epv * int(rng.integers(0, 2))
+    K = int(rng.integers(1, 20))
+    N = int(rng.integers(1500, 9000))
+    gen = torch.Generator(device="cuda").manual_seed(39100 + seed)
+    c = torch.randn((N, stride), generator=gen, device="cuda") * (torch.rand((N, 1), generator=gen, device="cuda") * 3 + 0.05)
+    kinds = torch.randint(0, 6, (N,), generator=gen, device="cuda")
+    peak = torch.randint(0, V, (N,), generator=gen, device="cuda")
+    rows = torch.arange(N, device="cuda")
+    c[rows[kinds == 1], peak[kinds == 1]] += 12.0                       # peaked rows
+    c[kinds == 2, : V // 3] = float("-inf")                             # a third of the tokens masked
+    c[kinds == 3] = 1.5                                                 # constant rows
+    c[kinds == 4] += 70.0                                               # large common offset
+    t = c + float(10.0 ** rng.uniform(-1.5, 0.3)) * torch.randn((N, stride), generator=gen, device="cuda")
+    t = torch.where(torch.isfinite(t), t, c)
+    if stride > V:
+        c[:, V:] = 1e30
+        t[:, V:] = -1e30
+    c, t = c.to(dtype), t.to(dtype)
+    gum = -torch.log(-torch.log(torch.rand((N, V), generator=gen, device="cuda").clamp_(1e-30, 1 - 1e-7)))
+    ids = torch.argmax(c[:, :V].float() + gum, dim=1).to(torch.int32)
+    ua = torch.randint(0, 1 << 24, (N,), generator=gen, device="cuda").float() / (1 << 24)
+    ur = torch.randint(0, 1 << 24, (N,), generator=gen, device="cuda").float() / (1 << 24)
+    raw = _raw_radius(N, stride, V, dtype, seed=39200 + seed) if seed % 3 == 2 else None
+    kw = dict(radius_scale=float(10.0 ** rng.uniform(-1.0, 0.9)), radius_max=float(rng.uniform(1.0, 12.0)),
+              normalize=bool(seed % 4 != 3), window=K)
+    say(f"[random many rows {seed}] V={V} stride={stride} N={N} K={K} {dtype} {kw} "
+        f"radius={'tensor' if raw is not None else 'scalar'}")
+    o0 = oracle.quantify(c.cpu(), ids.cpu().numpy(), _oparams(oracle, ciar.Params(**kw)), vocab=V,
+                         radius=None if raw is None else raw.cpu())
+    tau = float(np.float32(np.median(o0["score"])))
+    _, _, exf, st = _run_case(ciar, oracle, c, t, ids, ua, ur, ciar.Params(tau=tau, **kw), vocab=V,
+                              tag=f"random many rows {seed}", radius=raw)
+    assert exf <= 2 + N // 500 and st["exempt_accept"] <= 2 + N // 1000
+
+
 def _random_shape(rng):
     dtype = (torch.float32, torch.bfloat16)[int(rng.integers(0, 2))]
     epv = 4 if dtype == torch.float32 else 8
