@@ -284,6 +284,10 @@ int ciar_interdro_loss(const void* center_logits, const void* radius, const void
 int ciar_read_rows(const void* draft_logits, const void* target_logits, int64_t N, const ciar_params* params,
                    float* row_sum, void* hip_stream);
 
+/* The same with the kernel's dispatch recording two HIP events at its start and end (see ciar_stream_rows_timed). */
+int ciar_read_rows_timed(const void* draft_logits, const void* target_logits, int64_t N, const ciar_params* params,
+                         float* row_sum, void* hip_stream, void* start_event, void* stop_event);
+
 /*
  * Window epilogue on its own (the last step of ciar_verify / ciar_quantify_verify, which run it when
  * a window output is requested): from the per-row results of N rows,

@@ -78,6 +78,8 @@ def lib() -> ctypes.CDLL:
         L.ciar_interdro_loss.argtypes = [vp, vp, vp, i64, pp] + [ctypes.c_float] * 4 + [vp, vp, vp, vp]
         L.ciar_read_rows.restype = ctypes.c_int
         L.ciar_read_rows.argtypes = [vp, vp, i64, pp, vp, vp]
+        L.ciar_read_rows_timed.restype = ctypes.c_int
+        L.ciar_read_rows_timed.argtypes = [vp, vp, i64, pp, vp, vp, vp, vp]
         L.ciar_last_error.restype = ctypes.c_char_p
         L.ciar_last_error.argtypes = []
         L.ciar_version.restype = ctypes.c_char_p

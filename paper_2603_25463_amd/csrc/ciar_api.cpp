@@ -534,8 +534,28 @@ int ciar_quantify_multihead(const void* draft_heads, const void* radius_heads, i
     return CIAR_OK;
 }
 
+namespace {
+int read_rows(const void* draft_logits, const void* target_logits, int64_t N, const ciar_params* params,
+              float* row_sum, void* hip_stream, hipEvent_t ev_start, hipEvent_t ev_stop);
+}
+
 int ciar_read_rows(const void* draft_logits, const void* target_logits, int64_t N, const ciar_params* params,
                    float* row_sum, void* hip_stream)
+{
+    return read_rows(draft_logits, target_logits, N, params, row_sum, hip_stream, nullptr, nullptr);
+}
+
+int ciar_read_rows_timed(const void* draft_logits, const void* target_logits, int64_t N, const ciar_params* params,
+                         float* row_sum, void* hip_stream, void* start_event, void* stop_event)
+{
+    if (!start_event || !stop_event) return fail(CIAR_EINVAL, "start_event or stop_event is NULL");
+    return read_rows(draft_logits, target_logits, N, params, row_sum, hip_stream, static_cast<hipEvent_t>(start_event),
+                     static_cast<hipEvent_t>(stop_event));
+}
+
+namespace {
+int read_rows(const void* draft_logits, const void* target_logits, int64_t N, const ciar_params* params,
+              float* row_sum, void* hip_stream, hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     Resolved r;
     if (int rc = check_params(params, &r)) return rc;
@@ -549,10 +569,12 @@ int ciar_read_rows(const void* draft_logits, const void* target_logits, int64_t 
     ciar::RowArgs a = base_args(params, r, N);
     a.draft = draft_logits;
     a.target = target_logits;
-    const hipError_t e = ciar::launch_read(params->dtype, a, row_sum, static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = ciar::launch_read(params->dtype, a, row_sum, static_cast<hipStream_t>(hip_stream), ev_start,
+                                           ev_stop);
     if (e != hipSuccess) return hip_fail(e, "read kernel launch");
     return CIAR_OK;
 }
+}  // namespace
 
 const char* ciar_last_error(void) { return g_error; }
 

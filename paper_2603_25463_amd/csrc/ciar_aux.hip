@@ -1,6 +1,7 @@
 // gfx950 kernels that are not steps of the method: the dense [N, V] export of the interval curves (tests,
 // debugging) and the plain streaming read that serves as the bandwidth ceiling in benchmarks.
 #include "ciar_device.h"
+#include <hip/hip_ext.h>
 
 namespace ciar {
 namespace {
@@ -158,12 +159,19 @@ hipError_t launch_dense(int dtype, const RowArgs& args, float* p_lo, float* p_mi
     return hipGetLastError();
 }
 
-hipError_t launch_read(int dtype, const RowArgs& args, float* row_sum, hipStream_t stream)
+hipError_t launch_read(int dtype, const RowArgs& args, float* row_sum, hipStream_t stream, hipEvent_t ev_start,
+                       hipEvent_t ev_stop)
 {
     if (args.N <= 0) return hipSuccess;
     const dim3 grid((unsigned)args.N), block(256);
-    if (dtype == 0) hipLaunchKernelGGL(read_kernel<float>, grid, block, 0, stream, args, row_sum);
-    else hipLaunchKernelGGL(read_kernel<bf16_t>, grid, block, 0, stream, args, row_sum);
+    if (ev_start && ev_stop) {
+        // the dispatch records the two events at the kernel's start and end
+        if (dtype == 0) hipExtLaunchKernelGGL(read_kernel<float>, grid, block, 0, stream, ev_start, ev_stop, 0, args, row_sum);
+        else hipExtLaunchKernelGGL(read_kernel<bf16_t>, grid, block, 0, stream, ev_start, ev_stop, 0, args, row_sum);
+    } else {
+        if (dtype == 0) hipLaunchKernelGGL(read_kernel<float>, grid, block, 0, stream, args, row_sum);
+        else hipLaunchKernelGGL(read_kernel<bf16_t>, grid, block, 0, stream, args, row_sum);
+    }
     return hipGetLastError();
 }
 

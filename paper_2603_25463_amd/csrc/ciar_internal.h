@@ -125,6 +125,7 @@ hipError_t launch_dense(int dtype, const RowArgs& args, float* p_lo, float* p_mi
                         hipStream_t stream);
 
 // Plain streaming read of the rows (args.target may be null): the sum of each row's logits.
-hipError_t launch_read(int dtype, const RowArgs& args, float* row_sum, hipStream_t stream);
+hipError_t launch_read(int dtype, const RowArgs& args, float* row_sum, hipStream_t stream,
+                       hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
 }  // namespace ciar

@@ -28,7 +28,7 @@ def _declared_functions():
 def test_header_declares_the_expected_entry_points():
     names = _declared_functions()
     for n in ("ciar_quantify", "ciar_verify", "ciar_quantify_verify", "ciar_dense_intervals",
-              "ciar_stream_rows", "ciar_stream_rows_timed", "ciar_finish_rows", "ciar_window_epilogue", "ciar_read_rows", "ciar_interdro_loss", "ciar_quantify_multihead", "ciar_multihead_workspace_bytes",
+              "ciar_stream_rows", "ciar_stream_rows_timed", "ciar_finish_rows", "ciar_window_epilogue", "ciar_read_rows", "ciar_read_rows_timed", "ciar_interdro_loss", "ciar_quantify_multihead", "ciar_multihead_workspace_bytes",
               "ciar_workspace_bytes", "ciar_params_default", "ciar_last_error", "ciar_version"):
         assert n in names
 
@@ -148,6 +148,7 @@ def test_argument_errors_are_reported_before_any_launch(L):
     assert L.ciar_read_rows(None, FAKE, 4, a, FAKE, None) == EINVAL
     assert L.ciar_read_rows(FAKE, FAKE + 4, 4, a, FAKE, None) == EALIGN
     assert L.ciar_read_rows(FAKE, None, 0, a, FAKE, None) == 0
+    assert L.ciar_read_rows_timed(FAKE, None, 4, a, FAKE, None, None, None) == EINVAL
     assert L.ciar_window_epilogue(None, FAKE, 4, a, FAKE, FAKE, None) == EINVAL
     assert L.ciar_window_epilogue(FAKE, None, 4, a, FAKE, FAKE, None) == EINVAL
     assert L.ciar_window_epilogue(FAKE, FAKE, 4, a, None, None, None) == EINVAL
