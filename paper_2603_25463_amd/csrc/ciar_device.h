@@ -272,19 +272,19 @@ __device__ __forceinline__ void fuse_token_wide(float e, const FuseRow& r, float
     ec = fmaf(-2.0f * r.omb, x * om, 1.0f) * rc;
 }
 
-// Tensor-radius mode (Sec. 3.2.3, the Interval Head: r = Softplus(raw)): a = e^r, b = e^-r for
-// r = min(kappa Softplus(raw), rmax).  Softplus(raw) = max(raw, 0) + ln(1 + t), t = e^-|raw|;
-// ln(1 + t) = ln(u) t / (u - 1) with u = fl(1 + t): u - 1 is exact, so the rounding of 1 + t cancels in
-// the ratio and small radii (raw << 0) keep their relative accuracy.
-__device__ __forceinline__ void radius_ab(float raw, float kappa, float rmax, float& a, float& b)
+// Tensor-radius mode (Sec. 3.2.3, the Interval Head: r = Softplus(raw)): r = min(kappa Softplus(raw), rmax) in
+// fp32.  Softplus(raw) = max(raw, 0) + ln(1 + t), t = e^-|raw|.  With u = fl(1 + t) and d = u - 1 (exact),
+// ln(1 + t) = ln(u) + ln(1 + (t - d) / u) = ln(u) + (t - d)(2 - u) to 3e-8 relative: |t - d| is at most half an
+// ulp of u and 1/u = 2 - u + d^2/u, so the rounding of 1 + t is put back and small radii (raw << 0, where
+// ln(u) alone would be a multiple of 1.2e-7) keep their relative accuracy.  t below half an ulp of 1: u = 1,
+// ln(u) = 0 and the correction is t itself.
+__device__ __forceinline__ float radius_r(float raw, float kappa, float rmax)
 {
     const float t = __builtin_amdgcn_exp2f(-fabsf(raw) * 1.44269504f);
     const float u = 1.0f + t;
     const float d = u - 1.0f;
-    const float lg = d == 0.f ? t : (__builtin_amdgcn_logf(u) * 0.693147181f) * (t * __builtin_amdgcn_rcpf(d));
-    const float r = fminf(kappa * (fmaxf(raw, 0.f) + lg), rmax);
-    a = __builtin_amdgcn_exp2f(r * 1.44269504f);
-    b = __builtin_amdgcn_rcpf(a);
+    const float lg = fmaf(__builtin_amdgcn_logf(u), 0.693147181f, (t - d) * (2.0f - u));
+    return fminf(kappa * (fmaxf(raw, 0.f) + lg), rmax);
 }
 
 // The same radius in fp64 (one token per row: the reported token's interval).
@@ -294,36 +294,40 @@ __device__ __forceinline__ double radius_of(double raw, double kappa, double rma
     return fmin(kappa * sp, rmax);
 }
 
-// Tensor-radius token: pl = p^l_i S and w = (p^u_i - p^l_i) S in the units of e.
+// Tensor-radius token: pl = p^l_i S and w = (p^u_i - p^l_i) S in the units of e, from a = e^r alone.  With
+// b = 1/a the lower bound's denominator times a is dl = 1 + (a-1)(1-x) (no cancellation: both terms >= 0), and
+//   p^l S = e / dl,   p^u S = a e / du (du = 1 + (a-1) x),   (p^u - p^l) S = (a-1)(a+1) e (1-x) / (du dl),
+// so that neither b nor a second reciprocal is needed.
 __device__ __forceinline__ void fuse_token_rad(float e, float raw, const FuseRow& r, float kappa, float rmax,
                                                float& pl, float& w)
 {
-    float a, b;
-    radius_ab(raw, kappa, rmax, a, b);
+    const float a = __builtin_amdgcn_exp2f(radius_r(raw, kappa, rmax) * 1.44269504f);
+    const float am1 = a - 1.0f;
     const float om = fmaf(e, r.nil, fmaf(e, r.nih, 1.0f));        // 1 - x
     const float x = -e * r.nih;
-    const float du = fmaf(a - 1.0f, x, 1.0f);
-    const float dl = fmaf(om, 1.0f - b, b);
+    const float du = fmaf(am1, x, 1.0f);
+    const float dl = fmaf(am1, om, 1.0f);
     const float g = e * __builtin_amdgcn_rcpf(du * dl);
-    pl = b * (g * du);
-    w = (a - b) * (g * om);
+    pl = g * du;
+    w = (am1 * (a + 1.0f)) * (g * om);
 }
 
-// The same with the complement of the width, ec = 1 - (p^u_i - p^l_i) (see fuse_token_wide).
+// The same with the complement of the width (see fuse_token_wide), in the same units:
+// ec = 1 - (p^u_i - p^l_i) = (a - 2 (a-1) x (1-x)) / (du dl).
 __device__ __forceinline__ void fuse_token_rad_wide(float e, float raw, const FuseRow& r, float kappa, float rmax,
                                                     float& pl, float& w, float& ec)
 {
-    float a, b;
-    radius_ab(raw, kappa, rmax, a, b);
+    const float a = __builtin_amdgcn_exp2f(radius_r(raw, kappa, rmax) * 1.44269504f);
+    const float am1 = a - 1.0f;
     const float om = fmaf(e, r.nil, fmaf(e, r.nih, 1.0f));        // 1 - x
     const float x = -e * r.nih;
-    const float du = fmaf(a - 1.0f, x, 1.0f);
-    const float dl = fmaf(om, 1.0f - b, b);
+    const float du = fmaf(am1, x, 1.0f);
+    const float dl = fmaf(am1, om, 1.0f);
     const float rc = __builtin_amdgcn_rcpf(du * dl);
     const float g = e * rc;
-    pl = b * (g * du);
-    w = (a - b) * (g * om);
-    ec = fmaf(-2.0f * (1.0f - b), x * om, 1.0f) * rc;
+    pl = g * du;
+    w = (am1 * (a + 1.0f)) * (g * om);
+    ec = fmaf(-2.0f * am1, x * om, a) * rc;
 }
 
 // Per-row scalars of the quantifier from the five sums (fp64, one lane).
@@ -426,16 +430,6 @@ __device__ __forceinline__ bool finish_row(const RowArgs& A, int64_t row, const 
         if (A.row_id && !rej) A.row_id[row] = -1;
     }
     return rej;
-}
-
-// r = min(kappa Softplus(raw), rmax) in fp32 (see radius_ab for the ln(1 + t) form).
-__device__ __forceinline__ float radius_r(float raw, float kappa, float rmax)
-{
-    const float t = __builtin_amdgcn_exp2f(-fabsf(raw) * 1.44269504f);
-    const float u = 1.0f + t;
-    const float d = u - 1.0f;
-    const float lg = d == 0.f ? t : (__builtin_amdgcn_logf(u) * 0.693147181f) * (t * __builtin_amdgcn_rcpf(d));
-    return fminf(kappa * (fmaxf(raw, 0.f) + lg), rmax);
 }
 
 // Vocabularies of at most this many tokens take fp64 token arithmetic (see fuse_sums_tiny, dro_row_tiny_kernel).
