@@ -99,6 +99,63 @@ int check_rows(const void* logits, const char* name)
 
 size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
 
+// The width polynomial of a scalar radius (see RowArgs::wpoly).  With alpha = a - 1, beta = 1 - b:
+//   G(x) = (1 - x) / ((1 + alpha x)(1 - beta x)) = 1 + x H(x),   H(x) = (beta - alpha - 1 + alpha beta x) / (same denominator)
+// (H written so that nothing cancels).  P interpolates H at the four Chebyshev nodes of [0, rho]; rho is the
+// largest interval, found by bisection, on which 1 + x P(x) stays within 2e-8 of G relative to G.
+struct WidthPolyFit { double a, b; float c[4]; float x; };
+
+double width_H(double alpha, double beta, double x)
+{
+    return (beta - alpha - 1.0 + alpha * beta * x) / ((1.0 + alpha * x) * (1.0 - beta * x));
+}
+
+// coefficients in s = x / rho and the largest relative error of 1 + x P(x) on (0, rho]
+double width_fit(double alpha, double beta, double rho, double (&c)[4])
+{
+    static const double node[4] = {0.96193976625564337, 0.69134171618254492, 0.30865828381745508,
+                                   0.03806023374435663};    // (1 + cos((2k+1) pi / 8)) / 2
+    double f[4];
+    for (int k = 0; k < 4; ++k) f[k] = width_H(alpha, beta, rho * node[k]);
+    // Newton's divided differences, then the monomial coefficients by Horner expansion
+    for (int lvl = 1; lvl < 4; ++lvl)
+        for (int k = 3; k >= lvl; --k) f[k] = (f[k] - f[k - 1]) / (node[k] - node[k - lvl]);
+    c[0] = f[3]; c[1] = c[2] = c[3] = 0.0;
+    for (int k = 2; k >= 0; --k) {
+        for (int j = 3; j >= 1; --j) c[j] = c[j - 1] - node[k] * c[j];
+        c[0] = f[k] - node[k] * c[0];
+    }
+    double worst = 0.0;
+    for (int i = 1; i <= 96; ++i) {
+        const double sx = (double)i / 96.0, x = rho * sx;
+        const double P = c[0] + sx * (c[1] + sx * (c[2] + sx * c[3]));
+        const double G = 1.0 + x * width_H(alpha, beta, x);
+        const double err = std::fabs(x * (P - width_H(alpha, beta, x))) / G;
+        if (err > worst) worst = err;
+    }
+    return worst;
+}
+
+const WidthPolyFit& width_poly(double a, double b)
+{
+    static thread_local WidthPolyFit last = {-1.0, -1.0, {0.f, 0.f, 0.f, 0.f}, -1.f};
+    if (last.a == a && last.b == b) return last;
+    last.a = a; last.b = b; last.x = -1.f;
+    last.c[0] = last.c[1] = last.c[2] = last.c[3] = 0.f;
+    const double alpha = a - 1.0, beta = 1.0 - b;
+    double lo = 0.0, hi = 0.25, c[4];
+    for (int it = 0; it < 24; ++it) {
+        const double mid = 0.5 * (lo + hi);
+        if (width_fit(alpha, beta, mid, c) <= 2e-8) lo = mid; else hi = mid;
+    }
+    if (lo >= 1e-6 && width_fit(alpha, beta, lo, c) <= 2e-8) {
+        double s = 1.0;
+        for (int j = 0; j < 4; ++j) { last.c[j] = (float)(c[j] * s); s /= lo; }   // back to powers of x
+        last.x = (float)(lo * 0.999);
+    }
+    return last;
+}
+
 ciar::RowArgs base_args(const ciar_params* p, const Resolved& r, int64_t N)
 {
     ciar::RowArgs a;
@@ -123,6 +180,9 @@ ciar::RowArgs base_args(const ciar_params* p, const Resolved& r, int64_t N)
         if (!(xm > 0.0)) xm = 0.0;
     }
     a.capless_xmax = xm;
+    const WidthPolyFit& wf = width_poly(r.a, r.b);
+    for (int j = 0; j < 4; ++j) a.wpoly[j] = wf.c[j];
+    a.wpoly_x = wf.x;
     return a;
 }
 

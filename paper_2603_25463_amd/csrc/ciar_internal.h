@@ -53,6 +53,10 @@ struct RowArgs {
     double   cap_lo;            // 0.99
     double   cap_hi;            // 1.01
     double   capless_xmax;      // rows whose largest probability is below this have inactive caps
+    // Scalar radius: (p^u_i - p^l_i) S / ((a - b) e_i) = 1 + x P(x) with P(x) = sum_j wpoly[j] x^j to 2e-8 relative
+    // for x = e_i / S <= wpoly_x (negative: no such polynomial for this call)
+    float    wpoly[4];
+    float    wpoly_x;
 };
 
 enum class Mode { Quantify, Verify, Fused };

@@ -93,9 +93,19 @@ struct Shift { float kl, kw, kc; };
 // SPLIT = see fuse_parts.
 // MASK = the row does not fill the tile: slots past its end contribute nothing (they hold e = 0, which would
 // otherwise enter as 0 - k).
+//
+// Small probabilities (WIDTH_ONLY instances).  The raw width per unit of e,
+//   G(x) = (1 - x) / ((1 + (a-1) x)(1 - (1-b) x)),   gw = e G(x),
+// is a smooth function of x alone, and almost every token of a large vocabulary has a tiny x.  Where all the
+// tokens that one instruction of the wave covers (64 lanes x one 16-byte vector) stay below the bound x_thr the
+// host has fitted for this call's radius, G comes from a degree-4 polynomial 1 + x P(x) (relative error <= 2e-8,
+// below the rounding of the rational form) instead of three FMAs, a product and a reciprocal: five instruction
+// issues instead of ten.  The test costs half an issue per token (a running maximum and one compare per vector).
+struct WidthPoly { float d0, d1, d2, d3, ethr; };   // gw = e (1 + e (d0 + e (d1 + e (d2 + e d3)))) for e <= ethr
+
 template <int THREADS, int NVEC, int EPV, bool WIDTH_ONLY, bool SPLIT, bool MASK>
-__device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const FuseRow& fr_in, const Shift& sh, int V,
-                                          int tid, double (&q5)[5])
+__device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const FuseRow& fr_in, const WidthPoly& wp,
+                                          const Shift& sh, int V, int tid, double (&q5)[5])
 {
     // The caller branches between several instances of this pass.  The row constants go through an empty asm
     // so that each instance has its own: otherwise the optimiser hoists the sub-expressions the instances share
@@ -108,6 +118,27 @@ __device__ __forceinline__ void fuse_sums(const float (&e)[NVEC * EPV], const Fu
 #pragma unroll
     for (int j = 0; j < NVEC; ++j) {
         if (j * THREADS * EPV >= V) continue;                      // uniform: the chunk holds no token
+        if constexpr (WIDTH_ONLY) {
+            // e >= 0: the order of the floats is the order of their bit patterns (integer maxima need no
+            // canonicalisation of their operands); a negative bound compares below every e
+            int big = __float_as_int(e[j * EPV]);
+#pragma unroll
+            for (int k = 1; k < EPV; ++k) big = max(big, __float_as_int(e[j * EPV + k]));
+            if (__builtin_amdgcn_ballot_w64(big > __float_as_int(wp.ethr)) == 0) {   // uniform over the wave
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) {
+                    const float ek = e[j * EPV + k];
+                    const float G = fmaf(fmaf(fmaf(fmaf(wp.d3, ek, wp.d2), ek, wp.d1), ek, wp.d0), ek, 1.0f);
+                    float sw = fmaf(ek, G, -sh.kw);
+                    if (MASK && (j * THREADS + tid) * EPV + k >= V) sw = 0.f;
+                    const double dw = (double)sw;
+                    a1[k & 1] += dw;
+                    a3[k & 1] = fma(dw, dw, a3[k & 1]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                continue;
+            }
+        }
 #pragma unroll
         for (int k = 0; k < EPV; ++k) {
             float g, du, om;
@@ -502,6 +533,17 @@ void stream_kernel(const RowArgs A)
                     if (near) sh = shift_of((float)(S / (fw * (double)V)), fr);
                 }
             }
+            // the width polynomial of this call's radius in this wave's units (x = e / S)
+            WidthPoly wp = {0.f, 0.f, 0.f, 0.f, -1.f};
+            if constexpr (!RAD && !WIDE) {
+                const float is = -fr.nih, is2 = is * is;
+                wp.d0 = A.wpoly[0] * is; wp.d1 = A.wpoly[1] * is2; wp.d2 = A.wpoly[2] * (is2 * is);
+                wp.d3 = A.wpoly[3] * (is2 * is2);
+                wp.ethr = A.wpoly_x < 0.f ? -1.f : (float)((double)A.wpoly_x * (fw > 0.0 ? S / fw : 1.0));
+                // uniform over the wave: scalar registers (an FMA reads one of them per issue, so d2 stays a vector)
+                auto uniform = [](float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); };
+                wp.d0 = uniform(wp.d0); wp.d1 = uniform(wp.d1); wp.d3 = uniform(wp.d3); wp.ethr = uniform(wp.ethr);
+            }
             double kq[3] = {(double)sh.kl, (double)sh.kw, (double)sh.kc};   // fp64 copy (the tiny path sets its own)
             bool tiny = false;
             if constexpr (NVEC == 1) tiny = V <= kTinyVocab;       // uniform
@@ -534,14 +576,14 @@ void stream_kernel(const RowArgs A)
 #pragma unroll
                 for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
             } else if (capless) {
-                if (partial)    fuse_sums<THREADS, NVEC, EPV, true, true, true>(e, fr, sh, V, tid, q5);
-                else if (split) fuse_sums<THREADS, NVEC, EPV, true, true, false>(e, fr, sh, V, tid, q5);
-                else            fuse_sums<THREADS, NVEC, EPV, true, false, false>(e, fr, sh, V, tid, q5);
+                if (partial)    fuse_sums<THREADS, NVEC, EPV, true, true, true>(e, fr, wp, sh, V, tid, q5);
+                else if (split) fuse_sums<THREADS, NVEC, EPV, true, true, false>(e, fr, wp, sh, V, tid, q5);
+                else            fuse_sums<THREADS, NVEC, EPV, true, false, false>(e, fr, wp, sh, V, tid, q5);
                 q5[1] = wave_sum(q5[1]);
                 q5[3] = wave_sum(q5[3]);
             } else {
-                if (partial) fuse_sums<THREADS, NVEC, EPV, false, true, true>(e, fr, sh, V, tid, q5);
-                else         fuse_sums<THREADS, NVEC, EPV, false, true, false>(e, fr, sh, V, tid, q5);
+                if (partial) fuse_sums<THREADS, NVEC, EPV, false, true, true>(e, fr, wp, sh, V, tid, q5);
+                else         fuse_sums<THREADS, NVEC, EPV, false, true, false>(e, fr, wp, sh, V, tid, q5);
 #pragma unroll
                 for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
             }

@@ -629,6 +629,36 @@ def test_radius_extremes_scalar_mode(ciar, oracle, dtype):
             _run_case(ciar, oracle, c, t, ids, ua, ur, P, tag=f"radius kappa={kap} rmax={rmax}")
 
 
+@pytest.mark.parametrize("V,stride,dtype", [(3000, 3008, torch.float32), (16384, 16384, torch.float32),
+                                            (16384, 16384, torch.bfloat16), (65536, 65536, torch.bfloat16)])
+def test_probabilities_around_the_small_probability_bound(ciar, oracle, V, stride, dtype):
+    """Scalar radius: the kernel evaluates the widths of tokens with small probabilities by a polynomial and the
+    others by the rational form, deciding per 16-byte vector of 64 lanes against a bound that depends on the
+    radius (about 0.02 at confidence 0.9, 0.1 at radius 0.5, 5e-4 at radius 5).  Rows whose probabilities are
+    spread log-uniformly from 1e-5 to 0.3 put tokens on both sides of the bound at every radius, in varying
+    numbers per vector; the background is flat so that the rest of the mass is far below it."""
+    N, K = 24, 4
+    g = torch.Generator().manual_seed(9000 + V)
+    c = 0.05 * torch.randn((N, stride), generator=g)
+    for r in range(N):
+        k = 4 + 9 * r                                                  # tokens lifted out of the background
+        near = k // 2 if r % 3 == 0 else 0                             # ... some of them next to each other
+        pos = torch.cat([torch.arange(near), near + torch.randperm(V - near, generator=g)[: k - near]])
+        p = torch.exp(torch.empty(k).uniform_(float(np.log(1e-5)), float(np.log(0.3)), generator=g))
+        p = p * min(1.0, 0.9 / float(p.sum()))
+        rest = (1.0 - float(p.sum())) / (V - k)                        # probability of a background token
+        c[r, pos] = torch.log(p / rest)
+    c = c.to(dtype).cuda()
+    t = (c.float() + 0.3 * torch.randn(c.shape, generator=torch.Generator(device="cuda").manual_seed(5),
+                                       device="cuda")).to(dtype)
+    ids = torch.randint(0, V, (N,), generator=g, dtype=torch.int32).cuda()
+    ua, ur = torch.rand(N, generator=g).cuda(), torch.rand(N, generator=g).cuda()
+    for kap in (0.1, 0.5, 1.0, 1.645, 2.5, 5.0, 8.0):
+        for norm in (True, False):
+            P = ciar.Params(radius_scale=kap, normalize=norm, window=K, tau=0.01)
+            _run_case(ciar, oracle, c, t, ids, ua, ur, P, vocab=V, tag=f"small-probability bound r={kap}")
+
+
 @pytest.mark.parametrize("V,stride,dtype", [(2, 4, torch.float32), (50, 56, torch.float32), (1000, 1000, torch.float32),
                                             (3000, 3008, torch.float32), (8192, 8192, torch.float32),
                                             (16384, 16384, torch.float32), (32768, 32768, torch.float32),
