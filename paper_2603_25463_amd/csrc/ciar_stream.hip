@@ -369,31 +369,42 @@ void stream_kernel(const RowArgs A)
         }
     };
     // Verifier row statistics of one wave from the row as loaded: nt_w and Z_w = sum 2^(t_i log2e - nt_w).
-    auto verifier_stats = [&](u32x4 (&tb)[NVEC], float& ntw, double& Zw) {
+    // Any integer reference serves as long as no term overflows and the large terms stay normal numbers, so the
+    // sum is first taken about the reference of the centre row's tokens in the same wave (`guess`: verifier
+    // logits follow the device model's), which saves the pass for the maximum; a sum outside [2^-40, 2^100]
+    // (a verifier row far from its centre row, or a wave without tokens: sum 0) is redone about the wave's own
+    // maximum.
+    auto verifier_stats = [&](u32x4 (&tb)[NVEC], float guess, float& ntw, double& Zw) {
         if (partial) {
 #pragma unroll
             for (int j = 0; j < NVEC; ++j) E::mask_tail(tb[j], (j * THREADS + tid) * EPV, V);
         }
-        float mt = -INFINITY;
+        auto sum_about = [&](float nref) {
+            float zacc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int j = 0; j < NVEC; ++j) {
-            float tv[EPV];
-            E::unpack(tb[j], tv);
+            for (int j = 0; j < NVEC; ++j) {
+                float tv[EPV];
+                E::unpack(tb[j], tv);
 #pragma unroll
-            for (int k = 0; k < EPV; ++k) mt = fmaxf(mt, tv[k]);
+                for (int k = 0; k < EPV; ++k) zacc[k & 3] += exp2_ref(tv[k], nref);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            return wave_sum((double)((zacc[0] + zacc[1]) + (zacc[2] + zacc[3])));
+        };
+        ntw = guess == -INFINITY ? 0.f : guess;
+        Zw = sum_about(ntw);
+        if (!(Zw >= 0x1p-40 && Zw <= 0x1p100)) {                   // uniform over the wave; also taken by NaN
+            float mt = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) {
+                float tv[EPV];
+                E::unpack(tb[j], tv);
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) mt = fmaxf(mt, tv[k]);
+            }
+            ntw = ref_of(wave_max(mt));
+            Zw = sum_about(ntw == -INFINITY ? 0.f : ntw);          // an all-masked wave: every term is 2^-inf = 0
         }
-        ntw = ref_of(wave_max(mt));
-        const float nref = ntw == -INFINITY ? 0.f : ntw;           // an all-masked wave: every term is 2^-inf = 0
-        float zacc[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int j = 0; j < NVEC; ++j) {
-            float tv[EPV];
-            E::unpack(tb[j], tv);
-#pragma unroll
-            for (int k = 0; k < EPV; ++k) zacc[k & 3] += exp2_ref(tv[k], nref);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        Zw = wave_sum((double)((zacc[0] + zacc[1]) + (zacc[2] + zacc[3])));
     };
 
     // the list of rejected rows that the finishing kernels build starts empty
@@ -642,7 +653,7 @@ void stream_kernel(const RowArgs A)
                 __builtin_amdgcn_sched_barrier(0);
                 load_row(buf, A.target, row);
             }
-            verifier_stats(buf, ntw, Zw);
+            verifier_stats(buf, nw, ntw, Zw);
             if (lane == 0) { sm_nt[wave] = ntw; sm_Z[wave] = Zw; }
         }
         // the next centre row goes in flight before the barrier and thread 0's bookkeeping

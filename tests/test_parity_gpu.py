@@ -629,6 +629,39 @@ def test_radius_extremes_scalar_mode(ciar, oracle, dtype):
             _run_case(ciar, oracle, c, t, ids, ua, ur, P, tag=f"radius kappa={kap} rmax={rmax}")
 
 
+@pytest.mark.parametrize("V,stride,dtype", [(40, 40, torch.float32), (3000, 3008, torch.float32),
+                                            (16384, 16384, torch.float32), (16384, 16384, torch.bfloat16),
+                                            (65536, 65536, torch.bfloat16)])
+def test_verifier_rows_far_from_their_centre_rows(ciar, oracle, V, stride, dtype):
+    """The kernel sums the verifier row about the reference of the centre row's tokens and falls back to the
+    verifier row's own maximum when that sum leaves the safe range.  Verifier rows that sit hundreds of nats above
+    or below their centre rows, that are much sharper or flatter, and rows where only one stretch of the
+    vocabulary is far off (some waves fall back, others do not) must give the same decisions and draws."""
+    N, K = 24, 4
+    c, t, ids, ua, ur = _random_case(V, stride, N, K, dtype, seed=7000 + V)
+    t = t.float()
+    t[0, :V] += 300.0
+    t[1, :V] -= 300.0
+    t[2, :V] *= 40.0
+    t[3, :V] *= 0.01
+    t[4, :V] = t[4, :V] * 30.0 + 500.0
+    t[5, :V] = t[5, :V] * 30.0 - 500.0
+    lo, hi = V // 3, V // 2
+    t[6, lo:hi] += 120.0                                               # one stretch far above ...
+    t[7, lo:hi] -= 250.0                                               # ... far below its centre tokens
+    t[8, :lo] -= 400.0
+    t[9, 0] += 200.0                                                   # a single verifier token holds the mass
+    t[10, V - 1] += 90.0
+    c = c.float()
+    c[11, :V] += 250.0                                                 # the centre row is the one far off
+    c[12, :V] -= 250.0
+    c[13, lo:hi] += 150.0
+    c, t = c.to(dtype), t.to(dtype)
+    for P in (ciar.Params(window=K, tau=0.01), ciar.Params(radius_scale=0.7, normalize=False, window=K, tau=0.01)):
+        oq, ov, exf, st = _run_case(ciar, oracle, c, t, ids, ua, ur, P, vocab=V, tag="verifier far from centre")
+    assert st["rejected"] >= 4                                         # draws were compared as well
+
+
 @pytest.mark.parametrize("V,stride,dtype", [(3000, 3008, torch.float32), (16384, 16384, torch.float32),
                                             (16384, 16384, torch.bfloat16), (65536, 65536, torch.bfloat16)])
 def test_probabilities_around_the_small_probability_bound(ciar, oracle, V, stride, dtype):
