@@ -514,7 +514,9 @@ void stream_kernel(const RowArgs A)
         }
         if constexpr (DO_Q) {
             // x_i = e_i fw / S: hand fuse_row the partition sum expressed in this wave's units
-            const FuseRow fr = fuse_row(fw > 0.0 ? S / fw : 1.0, A.a, A.b);
+            // (fw is a power of two: the division is a change of exponent)
+            const double Su = nw == -INFINITY ? 1.0 : ldexp(S, (int)fminf(n - nw, 1000.f));   // S / fw
+            const FuseRow fr = fuse_row(Su, A.a, A.b);
             double q5[NQ];
             auto shift_of = [&](float eref, const FuseRow& r) {
                 Shift k;
@@ -541,7 +543,7 @@ void stream_kernel(const RowArgs A)
                     if (near) sh = shift_of(ldexpf(sm_e0, (int)up), fr);
                 } else {
                     near = fw >= 0x1p-64;                          // uniform over the wave
-                    if (near) sh = shift_of((float)(S / (fw * (double)V)), fr);
+                    if (near) sh = shift_of((float)(Su / (double)V), fr);
                 }
             }
             // the width polynomial of this call's radius in this wave's units (x = e / S)
@@ -550,7 +552,7 @@ void stream_kernel(const RowArgs A)
                 const float is = -fr.nih, is2 = is * is;
                 wp.d0 = A.wpoly[0] * is; wp.d1 = A.wpoly[1] * is2; wp.d2 = A.wpoly[2] * (is2 * is);
                 wp.d3 = A.wpoly[3] * (is2 * is2);
-                wp.ethr = A.wpoly_x < 0.f ? -1.f : (float)((double)A.wpoly_x * (fw > 0.0 ? S / fw : 1.0));
+                wp.ethr = A.wpoly_x < 0.f ? -1.f : (float)((double)A.wpoly_x * Su);
                 // uniform over the wave: scalar registers (an FMA reads one of them per issue, so d2 stays a vector)
                 auto uniform = [](float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); };
                 wp.d0 = uniform(wp.d0); wp.d1 = uniform(wp.d1); wp.d3 = uniform(wp.d3); wp.ethr = uniform(wp.ethr);
@@ -566,7 +568,7 @@ void stream_kernel(const RowArgs A)
                         E::zero_tail(buf[0], tid * EPV, V);
                     }
                     // all tokens sit in wave 0, whose lane 0 holds the first one
-                    fuse_sums_tiny<T, EPV, RAD, WIDE>(e, buf[0], fw > 0.0 ? S / fw : 1.0, A.a, A.b, A.kappa, A.rmax,
+                    fuse_sums_tiny<T, EPV, RAD, WIDE>(e, buf[0], Su, A.a, A.b, A.kappa, A.rmax,
                                                       tid * EPV, V, q5, kq);
 #pragma unroll
                     for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
