@@ -150,6 +150,18 @@ __device__ __forceinline__ double wave_sum(double v)
     return __hiloint2double(hi, lo);
 }
 
+// sum over lanes 0..15 (the first DPP row), handed to every lane of the wave
+__device__ __forceinline__ double row16_sum(double v)
+{
+    v = dpp_add<kRowShr1, 0xf>(v);
+    v = dpp_add<kRowShr2, 0xf>(v);
+    v = dpp_add<kRowShr4, 0xf>(v);
+    v = dpp_add<kRowShr8, 0xf>(v);
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), 15);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 15);
+    return __hiloint2double(hi, lo);
+}
+
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ float dpp_max(float v)
 {

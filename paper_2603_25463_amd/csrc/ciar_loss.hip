@@ -136,12 +136,15 @@ __global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* _
             q[0] = mc; q[1] = mt; q[2] = su; q[3] = cu; q[4] = ru; q[5] = sl; q[6] = cl; q[7] = rl;
         }
         __syncthreads();
-#pragma unroll 1
-        for (int w = 0; w < NW; ++w) {
-            const float* q = slot + w * 8;
-            mc = fmaxf(mc, q[0]); mt = fmaxf(mt, q[1]);
-            if (q[2] > su) { su = q[2]; cu = q[3]; ru = q[4]; }
-            if (q[5] > sl) { sl = q[5]; cl = q[6]; rl = q[7]; }
+        // every wave combines the sixteen waves' results across its lanes: lane l takes wave l & 15 (the copies in
+        // the upper lanes change no maximum, and the lowest lane that holds a maximum is the lowest wave)
+        {
+            const float* q = slot + (lane & 15) * 8;
+            mc = wave_max(q[0]); mt = wave_max(q[1]);
+            su = q[2]; cu = q[3]; ru = q[4];
+            sl = q[5]; cl = q[6]; rl = q[7];
+            wave_argmax(su, cu, ru);
+            wave_argmax(sl, cl, rl);
         }
         __syncthreads();                                           // sm_d is reused below
     }
@@ -183,14 +186,10 @@ __global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* _
         for (int i = 0; i < 7; ++i) sm_d[wave * 7 + i] = acc[i];
     }
     __syncthreads();
+    // the sixteen waves' sums, one per lane of the first DPP row, added across that row in every wave
     double tot[7];
 #pragma unroll
-    for (int i = 0; i < 7; ++i) {
-        double v = 0.0;
-#pragma unroll 1
-        for (int w = 0; w < NW; ++w) v += sm_d[w * 7 + i];
-        tot[i] = v;
-    }
+    for (int i = 0; i < 7; ++i) tot[i] = row16_sum(lane < NW ? sm_d[lane * 7 + i] : 0.0);
     __syncthreads();                                               // sm_d is reused below
 
     // pass 3: L1 distances to p_cloud
@@ -218,16 +217,25 @@ __global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* _
         for (int i = 0; i < 3; ++i) sm_d[wave * 7 + i] = l1[i];
     }
     __syncthreads();
-    if (tid == 0) {
-        double L[3] = {0.0, 0.0, 0.0};
-#pragma unroll 1
-        for (int w = 0; w < NW; ++w) { L[0] += sm_d[w * 7]; L[1] += sm_d[w * 7 + 1]; L[2] += sm_d[w * 7 + 2]; }
+    if (wave == 0) {
+        double L[3];
+#pragma unroll
+        for (int i = 0; i < 3; ++i) L[i] = row16_sum(lane < NW ? sm_d[lane * 7 + i] : 0.0);
+        // the four logarithms side by side: lane i takes ln tot[i]
+        const double mine = lane == 0 ? tot[0] : lane == 1 ? tot[1] : lane == 2 ? tot[2] : tot[3];
+        const double lg = log(mine);
+        auto from_lane = [&](int src) {
+            return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(lg), src),
+                                    __builtin_amdgcn_readlane(__double2loint(lg), src));
+        };
+        const double ln_s0 = from_lane(0), ln_s1 = from_lane(1), ln_s2 = from_lane(2), ln_z = from_lane(3);
+        if (lane != 0) return;
         const double Z = tot[3];
         const double pc_c = tot[4] / Z, pc_r = tot[5] / Z, pc_t = tot[6] / Z;
-        const double ce_mid = ((double)mc + log(tot[0])) - pc_c;
-        const double ce_up = (mu + log(tot[1])) - (pc_c + pc_r);
-        const double ce_lo = (ml + log(tot[2])) - (pc_c - pc_r);
-        const double kl = pc_t - ((double)mt + log(Z)) + ce_mid;
+        const double ce_mid = ((double)mc + ln_s0) - pc_c;
+        const double ce_up = (mu + ln_s1) - (pc_c + pc_r);
+        const double ce_lo = (ml + ln_s2) - (pc_c - pc_r);
+        const double kl = pc_t - ((double)mt + ln_z) + ce_mid;
         const int64_t N = A.N;
         terms[0 * N + row] = (float)L[0]; terms[1 * N + row] = (float)L[1]; terms[2 * N + row] = (float)L[2];
         terms[3 * N + row] = (float)ce_mid; terms[4 * N + row] = (float)ce_up; terms[5 * N + row] = (float)ce_lo;
