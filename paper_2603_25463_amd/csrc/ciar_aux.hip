@@ -42,11 +42,11 @@ __global__ __launch_bounds__(256) void dense_kernel(const RowArgs A, float* __re
 
     const FuseRow fr = fuse_row(S, A.a, A.b);
     const T* rad = A.radius ? static_cast<const T*>(A.radius) + row * A.stride : nullptr;
-    const float kap = (float)A.kappa, rmax = (float)A.rmax;
+    const RadiusMode rm = radius_mode(A);
     // gl, gw of one token: p^l = Bc gl, p^u - p^l = Wc gw (tensor-radius mode: Bc = Wc = 1 / S)
     auto token = [&](int i, float& e, float& gl, float& gw) {
         e = exp2_ref(load_logit(c, i), n);
-        if (rad) fuse_token_rad(e, load_logit(rad, i), fr, kap, rmax, gl, gw);
+        if (rad) fuse_token_rad(e, load_logit(rad, i), fr, rm, gl, gw);
         else fuse_token(e, fr, gl, gw);
     };
     double q5[5];

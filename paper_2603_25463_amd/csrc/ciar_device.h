@@ -306,31 +306,41 @@ __device__ __forceinline__ double radius_of(double raw, double kappa, double rma
     return fmin(kappa * sp, rmax);
 }
 
-// Tensor-radius token: pl = p^l_i S and w = (p^u_i - p^l_i) S in the units of e, from a = e^r alone.  With
+// a - 1 = e^r - 1 of a tensor-radius token, r = min(kappa Softplus(raw), rmax); am1_max = e^rmax - 1.
+// UNIT (kappa = 1, the Interval Head as the paper defines it): e^Softplus(raw) = 1 + e^raw, so a - 1 = e^raw, capped:
+// one exponential, no logarithm, and no cancellation in a - 1 however small the radius is.
+template <bool UNIT>
+__device__ __forceinline__ float radius_am1(float raw, float kappa, float rmax, float am1_max)
+{
+    if constexpr (UNIT) return fminf(__builtin_amdgcn_exp2f(fmaf(raw, kLog2eLo, raw * kLog2eHi)), am1_max);
+    else return __builtin_amdgcn_exp2f(radius_r(raw, kappa, rmax) * 1.44269504f) - 1.0f;
+}
+
+// Tensor-radius token: pl = p^l_i S and w = (p^u_i - p^l_i) S in the units of e, from a - 1 alone.  With
 // b = 1/a the lower bound's denominator times a is dl = 1 + (a-1)(1-x) (no cancellation: both terms >= 0), and
 //   p^l S = e / dl,   p^u S = a e / du (du = 1 + (a-1) x),   (p^u - p^l) S = (a-1)(a+1) e (1-x) / (du dl),
 // so that neither b nor a second reciprocal is needed.
+template <bool UNIT>
 __device__ __forceinline__ void fuse_token_rad(float e, float raw, const FuseRow& r, float kappa, float rmax,
-                                               float& pl, float& w)
+                                               float am1_max, float& pl, float& w)
 {
-    const float a = __builtin_amdgcn_exp2f(radius_r(raw, kappa, rmax) * 1.44269504f);
-    const float am1 = a - 1.0f;
+    const float am1 = radius_am1<UNIT>(raw, kappa, rmax, am1_max);
     const float om = fmaf(e, r.nil, fmaf(e, r.nih, 1.0f));        // 1 - x
     const float x = -e * r.nih;
     const float du = fmaf(am1, x, 1.0f);
     const float dl = fmaf(am1, om, 1.0f);
     const float g = e * __builtin_amdgcn_rcpf(du * dl);
     pl = g * du;
-    w = (am1 * (a + 1.0f)) * (g * om);
+    w = (am1 * (am1 + 2.0f)) * (g * om);
 }
 
 // The same with the complement of the width (see fuse_token_wide), in the same units:
 // ec = 1 - (p^u_i - p^l_i) = (a - 2 (a-1) x (1-x)) / (du dl).
+template <bool UNIT>
 __device__ __forceinline__ void fuse_token_rad_wide(float e, float raw, const FuseRow& r, float kappa, float rmax,
-                                                    float& pl, float& w, float& ec)
+                                                    float am1_max, float& pl, float& w, float& ec)
 {
-    const float a = __builtin_amdgcn_exp2f(radius_r(raw, kappa, rmax) * 1.44269504f);
-    const float am1 = a - 1.0f;
+    const float am1 = radius_am1<UNIT>(raw, kappa, rmax, am1_max);
     const float om = fmaf(e, r.nil, fmaf(e, r.nih, 1.0f));        // 1 - x
     const float x = -e * r.nih;
     const float du = fmaf(am1, x, 1.0f);
@@ -338,8 +348,27 @@ __device__ __forceinline__ void fuse_token_rad_wide(float e, float raw, const Fu
     const float rc = __builtin_amdgcn_rcpf(du * dl);
     const float g = e * rc;
     pl = g * du;
-    w = (am1 * (a + 1.0f)) * (g * om);
-    ec = fmaf(-2.0f * am1, x * om, a) * rc;
+    w = (am1 * (am1 + 2.0f)) * (g * om);
+    ec = fmaf(-2.0f * am1, x * om, am1 + 1.0f) * rc;
+}
+
+// The two with the choice made at run time (uniform over a launch).
+struct RadiusMode { bool unit; float kappa, rmax, am1_max; };
+__device__ __forceinline__ RadiusMode radius_mode(const RowArgs& A)
+{
+    return {A.kappa == 1.0, (float)A.kappa, (float)A.rmax, (float)expm1(A.rmax)};
+}
+__device__ __forceinline__ void fuse_token_rad(float e, float raw, const FuseRow& r, const RadiusMode& m, float& pl,
+                                               float& w)
+{
+    if (m.unit) fuse_token_rad<true>(e, raw, r, m.kappa, m.rmax, m.am1_max, pl, w);
+    else fuse_token_rad<false>(e, raw, r, m.kappa, m.rmax, m.am1_max, pl, w);
+}
+__device__ __forceinline__ void fuse_token_rad_wide(float e, float raw, const FuseRow& r, const RadiusMode& m,
+                                                    float& pl, float& w, float& ec)
+{
+    if (m.unit) fuse_token_rad_wide<true>(e, raw, r, m.kappa, m.rmax, m.am1_max, pl, w, ec);
+    else fuse_token_rad_wide<false>(e, raw, r, m.kappa, m.rmax, m.am1_max, pl, w, ec);
 }
 
 // Per-row scalars of the quantifier from the five sums (fp64, one lane).

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
     // is left of the spread.
     const bool precise = __syncthreads_and(flat_h ? 1 : 0) != 0 || V <= 64;   // uniform; also the barrier
 
-    const float kap = (float)A.kappa, rmax = (float)A.rmax;
+    const RadiusMode rm = radius_mode(A);
     const int nvec = (V + EPV - 1) / EPV;
     // One head's share of a token: its width after the head's caps (added to d) and, WIDE, its complement (to c).
     auto head_token = [&](int h, float cval, float rval, const FuseRow& fr, double& d, double& c) {
@@ -62,11 +62,11 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
         float gl, gw;
         if constexpr (WIDE) {
             float ec;
-            if (rad) fuse_token_rad_wide(e, rval, fr, kap, rmax, gl, gw, ec);
+            if (rad) fuse_token_rad_wide(e, rval, fr, rm, gl, gw, ec);
             else fuse_token_wide(e, fr, gl, gw, ec);
             c += (double)ec;
         } else {
-            if (rad) fuse_token_rad(e, rval, fr, kap, rmax, gl, gw);
+            if (rad) fuse_token_rad(e, rval, fr, rm, gl, gw);
             else fuse_token(e, fr, gl, gw);
         }
         d = fma(sm_cw[h], (double)gw, fma(sm_cl[h], (double)gl, d));

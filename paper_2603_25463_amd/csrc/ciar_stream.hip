@@ -250,11 +250,13 @@ __device__ __forceinline__ void fuse_sums_tiny(const float (&e)[EPV], const u32x
 // Pass C in tensor-radius mode: every token has its own a_i, b_i from the raw radius row `rad` (as loaded,
 // padding already zeroed); the sums are of p^l_i S and (p^u_i - p^l_i) S themselves, about the shift sh.
 // WIDE: also the complement sums of fuse_sums_wide.
-template <typename T, int THREADS, int NVEC, bool WIDE>
+// UNIT = the radius scale is 1 (see radius_am1).
+template <typename T, int THREADS, int NVEC, bool WIDE, bool UNIT>
 __device__ __forceinline__ void fuse_sums_rad(const float (&e)[NVEC * Elt<T>::kPerVec], const u32x4 (&rad)[NVEC],
-                                              const FuseRow& fr, float kappa, float rmax, const Shift& sh, int V,
+                                              const FuseRow& fr, const RadiusMode& rm, const Shift& sh, int V,
                                               int tid, double (&q5)[WIDE ? 8 : 5])
 {
+    const float kappa = rm.kappa, rmax = rm.rmax, am1_max = rm.am1_max;
     constexpr int EPV = Elt<T>::kPerVec;
     double a0[2] = {0.0, 0.0}, a1[2] = {0.0, 0.0}, a2[2] = {0.0, 0.0}, a3[2] = {0.0, 0.0}, a4[2] = {0.0, 0.0};
     double c1 = 0.0, c2 = 0.0;
@@ -270,14 +272,14 @@ __device__ __forceinline__ void fuse_sums_rad(const float (&e)[NVEC * Elt<T>::kP
             const bool live = (j * THREADS + tid) * EPV + k < V;
             if constexpr (WIDE) {
                 float ec;
-                fuse_token_rad_wide(e[j * EPV + k], raw[k], fr, kappa, rmax, pl, w, ec);
+                fuse_token_rad_wide<UNIT>(e[j * EPV + k], raw[k], fr, kappa, rmax, am1_max, pl, w, ec);
                 if (live) {
                     const double dc = (double)(ec - sh.kc);
                     c1 += dc; c2 = fma(dc, dc, c2);
                     big = fmaxf(big, ec);
                 }
             } else {
-                fuse_token_rad(e[j * EPV + k], raw[k], fr, kappa, rmax, pl, w);
+                fuse_token_rad<UNIT>(e[j * EPV + k], raw[k], fr, kappa, rmax, am1_max, pl, w);
             }
             const double dl = live ? (double)(pl - sh.kl) : 0.0, dw = live ? (double)(w - sh.kw) : 0.0;
             a0[k & 1] += dl;
@@ -334,6 +336,8 @@ void stream_kernel(const RowArgs A)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int V = A.V;
+    RadiusMode rm = {false, 0.f, 0.f, 0.f};
+    if constexpr (RAD) rm = radius_mode(A);
     const bool partial = V != NVEC * CHUNK;                        // uniform: the row does not fill the tile
     const int last_vec = (V + EPV - 1) / EPV - 1;
     const int nrows = (int)A.N;
@@ -522,8 +526,8 @@ void stream_kernel(const RowArgs A)
                 Shift k;
                 k.kc = 0.f;
                 if constexpr (RAD) {
-                    if constexpr (WIDE) fuse_token_rad_wide(eref, raw0, r, (float)A.kappa, (float)A.rmax, k.kl, k.kw, k.kc);
-                    else fuse_token_rad(eref, raw0, r, (float)A.kappa, (float)A.rmax, k.kl, k.kw);
+                    if constexpr (WIDE) fuse_token_rad_wide(eref, raw0, r, rm, k.kl, k.kw, k.kc);
+                    else fuse_token_rad(eref, raw0, r, rm, k.kl, k.kw);
                 } else {
                     if constexpr (WIDE) fuse_token_wide(eref, r, k.kl, k.kw, k.kc);
                     else fuse_token<true>(eref, r, k.kl, k.kw);
@@ -581,7 +585,8 @@ void stream_kernel(const RowArgs A)
 #pragma unroll
                     for (int j = 0; j < NVEC; ++j) E::zero_tail(buf[j], (j * THREADS + tid) * EPV, V);
                 }
-                fuse_sums_rad<T, THREADS, NVEC, WIDE>(e, buf, fr, (float)A.kappa, (float)A.rmax, sh, V, tid, q5);
+                if (rm.unit) fuse_sums_rad<T, THREADS, NVEC, WIDE, true>(e, buf, fr, rm, sh, V, tid, q5);
+                else         fuse_sums_rad<T, THREADS, NVEC, WIDE, false>(e, buf, fr, rm, sh, V, tid, q5);
 #pragma unroll
                 for (int i = 0; i < 5; ++i) q5[i] = wave_sum(q5[i]);
             } else if constexpr (WIDE) {
