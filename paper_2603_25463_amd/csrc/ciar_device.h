@@ -180,6 +180,16 @@ __device__ __forceinline__ float wave_max(float v)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
+// maximum over lanes 0..15 (the first DPP row), handed to every lane of the wave
+__device__ __forceinline__ float row16_max(float v)
+{
+    v = dpp_max<kRowShr1, 0xf>(v);
+    v = dpp_max<kRowShr2, 0xf>(v);
+    v = dpp_max<kRowShr4, 0xf>(v);
+    v = dpp_max<kRowShr8, 0xf>(v);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 15));
+}
+
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ double dpp_max(double v)
 {

@@ -483,17 +483,30 @@ void stream_kernel(const RowArgs A)
             if (DO_Q && wave == 0) sm_e0 = e[0];
         }
         __syncthreads();
-        float mc = sm_ref[0], n = sm_ref[1];
+        // Combining the waves' results.  With eight waves or more every wave does it across its first lanes (lane
+        // l < NW takes wave l; the other lanes of the DPP row repeat wave 0, which changes no maximum, and add
+        // nothing); with four a short loop is as quick (measured).
+        constexpr bool LANES = NW >= 8;
+        const int src = lane < NW ? lane : 0;
+        float mc, n;
+        double S;                                                  // in units of 2^-n
+        if constexpr (LANES) {
+            const float mc_l = sm_ref[src * 2], n_l = sm_ref[src * 2 + 1];
+            mc = row16_max(mc_l); n = row16_max(n_l);
+            S = row16_sum(lane < NW && n_l != -INFINITY ? sm_S[src] * pow2_of(n_l - n) : 0.0);
+        } else {
+            mc = sm_ref[0]; n = sm_ref[1];
 #pragma unroll
-        for (int w = 1; w < NW; ++w) {
-            mc = fmaxf(mc, sm_ref[w * 2]);
-            n = fmaxf(n, sm_ref[w * 2 + 1]);
-        }
-        double S = 0.0;                                            // in units of 2^-n
+            for (int w = 1; w < NW; ++w) {
+                mc = fmaxf(mc, sm_ref[w * 2]);
+                n = fmaxf(n, sm_ref[w * 2 + 1]);
+            }
+            S = 0.0;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            const float rn = sm_ref[w * 2 + 1];
-            if (rn != -INFINITY) S += sm_S[w] * pow2_of(rn - n);
+            for (int w = 0; w < NW; ++w) {
+                const float rn = sm_ref[w * 2 + 1];
+                if (rn != -INFINITY) S += sm_S[w] * pow2_of(rn - n);
+            }
         }
         const double fw = nw == -INFINITY ? 0.0 : pow2_of(nw - n);     // this wave's e_i are 1/fw too large
 
@@ -669,54 +682,74 @@ void stream_kernel(const RowArgs A)
             if (has_next) load_row(buf, A.draft, next);
         }
 
-        // ---- thread 0 leaves the row's ten numbers for the finishing kernels -------------------------------
+        // ---- wave 0 leaves the row's ten numbers for the finishing kernels -----------------------------------
+        // Sixteen waves: their results are combined across the first lanes as above; fewer: by lane 0 in a loop
+        // (as quick, measured).  Handing this job from wave to wave in turn measured slower.
         __syncthreads();
-        if (tid == 0) {
+        if (wave == 0 && (NW >= 16 || lane == 0)) {
             float nt = -INFINITY;
             double Z = 0.0;                                        // in units of 2^-nt
-            if constexpr (DO_V) {
-#pragma unroll
-                for (int w = 0; w < NW; ++w) nt = fmaxf(nt, sm_nt[w]);
-#pragma unroll
-                for (int w = 0; w < NW; ++w) {
-                    const float rt = sm_nt[w];
-                    if (rt != -INFINITY) Z += sm_Z[w] * pow2_of(rt - nt);
-                }
-            }
-            RowStats stv;
-            RowStats* const st = &stv;
-            st->S = S; st->Z = Z; st->n = n; st->nt = nt; st->mc = mc;
-            // the waves' sums are about one common shift (wave 0 left it in row units): they simply add
             double t[NQ];
 #pragma unroll
             for (int i = 0; i < NQ; ++i) t[i] = 0.0;
             double K[3] = {0.0, 0.0, 0.0};
-            if constexpr (DO_Q) {
-                K[0] = sm_k[0]; K[1] = sm_k[1]; K[2] = sm_k[2];
-#pragma unroll
-                for (int i = 0; i < NQ; ++i) {
-#pragma unroll
-                    for (int w = 0; w < NW; ++w) t[i] = i == 7 ? fmax(t[i], sm_q5[w * NQ + i]) : t[i] + sm_q5[w * NQ + i];
+            if constexpr (DO_Q) { K[0] = sm_k[0]; K[1] = sm_k[1]; K[2] = sm_k[2]; }
+            // the waves' interval sums are about one common shift (wave 0 left it in row units): they simply add
+            if constexpr (NW >= 16) {
+                if constexpr (DO_V) {
+                    const float nt_l = sm_nt[src];
+                    nt = row16_max(nt_l);
+                    Z = row16_sum(lane < NW && nt_l != -INFINITY ? sm_Z[src] * pow2_of(nt_l - nt) : 0.0);
                 }
-            }
-            float mode = (capless && !WIDE) ? kSumsWidthOnly : kSumsFull;
-            if constexpr (WIDE && DO_Q) {
-                // every width above 1/2 and both caps inactive: the finishing kernels read the complement sums
-                if (t[7] < kComplementBelow) {
-                    const RowScore rs = finish_score(t, S, kSumsFull, A, K[0], K[1]);
-                    if (rs.alpha_l == 1.0 && rs.alpha_u == 1.0) {
-                        t[1] = t[5]; t[3] = t[6]; K[1] = K[2];
-                        mode = kSumsComplement;
+                if constexpr (DO_Q) {
+#pragma unroll
+                    for (int i = 0; i < NQ; ++i) {
+                        const double mine = lane < NW ? sm_q5[src * NQ + i] : 0.0;
+                        t[i] = i == 7 ? (double)row16_max((float)mine) : row16_sum(mine);
+                    }
+                }
+            } else {
+                if constexpr (DO_V) {
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) nt = fmaxf(nt, sm_nt[w]);
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) {
+                        const float rt = sm_nt[w];
+                        if (rt != -INFINITY) Z += sm_Z[w] * pow2_of(rt - nt);
+                    }
+                }
+                if constexpr (DO_Q) {
+#pragma unroll
+                    for (int i = 0; i < NQ; ++i) {
+#pragma unroll
+                        for (int w = 0; w < NW; ++w)
+                            t[i] = i == 7 ? fmax(t[i], sm_q5[w * NQ + i]) : t[i] + sm_q5[w * NQ + i];
                     }
                 }
             }
-            st->kl = K[0]; st->kw = K[1];
-            st->mode = mode;
+            if (lane == 0) {
+                RowStats stv;
+                RowStats* const st = &stv;
+                st->S = S; st->Z = Z; st->n = n; st->nt = nt; st->mc = mc;
+                float mode = (capless && !WIDE) ? kSumsWidthOnly : kSumsFull;
+                if constexpr (WIDE && DO_Q) {
+                    // every width above 1/2 and both caps inactive: the finishing kernels read the complement sums
+                    if (t[7] < kComplementBelow) {
+                        const RowScore rs = finish_score(t, S, kSumsFull, A, K[0], K[1]);
+                        if (rs.alpha_l == 1.0 && rs.alpha_u == 1.0) {
+                            t[1] = t[5]; t[3] = t[6]; K[1] = K[2];
+                            mode = kSumsComplement;
+                        }
+                    }
+                }
+                st->kl = K[0]; st->kw = K[1];
+                st->mode = mode;
 #pragma unroll
-            for (int i = 0; i < 5; ++i) st->q[i] = t[i];
-            // with finishing the statistics stay in LDS until the end (lane `done` writes them out then)
-            if (finish) sm_rows[done] = stv;
-            else A.stats[row] = stv;
+                for (int i = 0; i < 5; ++i) st->q[i] = t[i];
+                // with finishing the statistics stay in LDS until the end (lane `done` writes them out then)
+                if (finish) sm_rows[done] = stv;
+                else A.stats[row] = stv;
+            }
         }
 
         ++done;
