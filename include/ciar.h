@@ -101,6 +101,16 @@ typedef struct ciar_params {
 void ciar_params_default(ciar_params* p);
 
 /*
+ * Host only (no GPU work): the polynomial the kernels use for the interval width of small probabilities at
+ * this call's scalar radius r = min(kappa, radius_max), a = e^r, b = e^-r (App. "Proof of Interval Validity":
+ * the InterFuse bounds as functions of the probability x).  For x <= *x_max
+ *   (p^u - p^l) / ((a - b) x) = (1 - x) / ((1 + (a-1) x)(1 - (1-b) x)) = 1 + x (c[0] + c[1] x + c[2] x^2 + c[3] x^3)
+ * to 2e-8 relative.  *x_max < 0: the kernels use no polynomial at this radius.  Exposed so that the fit can be
+ * checked without a GPU.  `coef` (4 floats) and `x_max` are host pointers.  Returns CIAR_OK or CIAR_EINVAL.
+ */
+int ciar_width_polynomial(const ciar_params* params, float* coef, float* x_max);
+
+/*
  * Bytes of device workspace ciar_quantify / ciar_verify / ciar_quantify_verify need for N rows
  * (97 bytes per row, rounded up).  Always a multiple of 256; returns 0 for N <= 0.
  */

@@ -80,6 +80,8 @@ def lib() -> ctypes.CDLL:
         L.ciar_read_rows.argtypes = [vp, vp, i64, pp, vp, vp]
         L.ciar_read_rows_timed.restype = ctypes.c_int
         L.ciar_read_rows_timed.argtypes = [vp, vp, i64, pp, vp, vp, vp, vp]
+        L.ciar_width_polynomial.restype = ctypes.c_int
+        L.ciar_width_polynomial.argtypes = [pp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
         L.ciar_last_error.restype = ctypes.c_char_p
         L.ciar_last_error.argtypes = []
         L.ciar_version.restype = ctypes.c_char_p
@@ -156,6 +158,14 @@ def _like_draft(t, draft, name: str):
     """``target`` / ``radius`` tensors share the layout of the draft logits."""
     if t is not None and (t.dtype != draft.dtype or t.shape != draft.shape or t.stride() != draft.stride()):
         raise ValueError(f"{name} must match draft in dtype, shape and strides")
+
+
+def width_polynomial(cparams: CiarParams):
+    """``ciar_width_polynomial`` (host only): (four coefficients, x_max) for the call's scalar radius."""
+    coef = (ctypes.c_float * 4)()
+    xmax = ctypes.c_float()
+    _check(lib().ciar_width_polynomial(ctypes.byref(cparams), coef, ctypes.byref(xmax)))
+    return [float(v) for v in coef], float(xmax.value)
 
 
 def workspace_bytes(N: int, cparams: CiarParams) -> int:

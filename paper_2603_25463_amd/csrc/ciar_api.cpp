@@ -338,6 +338,17 @@ void ciar_params_default(ciar_params* p)
     p->normalize = 1;
 }
 
+int ciar_width_polynomial(const ciar_params* params, float* coef, float* x_max)
+{
+    if (!coef || !x_max) return fail(CIAR_EINVAL, "coef or x_max is NULL");
+    Resolved r;
+    if (int rc = check_params(params, &r)) return rc;
+    const WidthPolyFit& wf = width_poly(r.a, r.b);
+    for (int j = 0; j < 4; ++j) coef[j] = wf.c[j];
+    *x_max = wf.x;
+    return CIAR_OK;
+}
+
 size_t ciar_workspace_bytes(int64_t N, const ciar_params* /*params*/)
 {
     if (N <= 0) return 0;

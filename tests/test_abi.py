@@ -29,7 +29,7 @@ def test_header_declares_the_expected_entry_points():
     names = _declared_functions()
     for n in ("ciar_quantify", "ciar_verify", "ciar_quantify_verify", "ciar_dense_intervals",
               "ciar_stream_rows", "ciar_stream_rows_timed", "ciar_finish_rows", "ciar_window_epilogue", "ciar_read_rows", "ciar_read_rows_timed", "ciar_interdro_loss", "ciar_quantify_multihead", "ciar_multihead_workspace_bytes",
-              "ciar_workspace_bytes", "ciar_params_default", "ciar_last_error", "ciar_version"):
+              "ciar_workspace_bytes", "ciar_width_polynomial", "ciar_params_default", "ciar_last_error", "ciar_version"):
         assert n in names
 
 
@@ -183,3 +183,55 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "absent.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         binding.lib()
+
+
+# ---- host logic: the fitted width polynomial ---------------------------------------------------------
+
+def _width_poly(L, **kw):
+    coef = (ctypes.c_float * 4)()
+    xmax = ctypes.c_float()
+    p = _params(L, **kw)
+    assert L.ciar_width_polynomial(ctypes.byref(p), coef, ctypes.byref(xmax)) == 0
+    return [float(v) for v in coef], float(xmax.value)
+
+
+@pytest.mark.parametrize("radius", [1e-3, 0.1, 0.5, 1.0, 1.2816, 1.6449, 1.96, 3.0, 5.0, 8.0])
+def test_width_polynomial_matches_the_interval_width(L, radius):
+    """The polynomial the kernels use for small probabilities against the InterFuse width itself
+    (App. "Proof of Interval Validity": p^u = a x / (1 + (a-1) x), p^l = b x / (1 - (1-b) x)), in 40-digit
+    decimal arithmetic: (p^u - p^l) / ((a - b) x) = 1 + x P(x) within 2.5e-8 on (0, x_max], with the float32
+    coefficients the kernels receive; and within 1.5e-7 when the polynomial itself is evaluated in float32."""
+    import decimal
+    import numpy as np
+    D = decimal.Decimal
+    decimal.getcontext().prec = 40
+    coef, xmax = _width_poly(L, radius_scale=radius)
+    assert xmax > 0
+    r = D(float(np.float32(radius)))
+    a, b = r.exp(), (-r).exp()
+    worst = worst32 = D(0)
+    f32 = np.float32
+    for i in range(1, 1501):
+        xf = f32(xmax * i / 1500.0)
+        x = D(float(xf))
+        width = a * x / (1 + (a - 1) * x) - b * x / (1 - (1 - b) * x)
+        G = width / ((a - b) * x)
+        P = sum(D(c) * x ** j for j, c in enumerate(coef))
+        worst = max(worst, abs(1 + x * P - G) / G)
+        h = f32(coef[3])
+        for c in (coef[2], coef[1], coef[0], 1.0):
+            h = f32(f32(h * xf) + f32(c))                            # two roundings per step: an upper bound on the FMA
+        worst32 = max(worst32, abs(D(float(h)) - G) / G)
+    assert worst <= D("2.5e-8"), worst
+    assert worst32 <= D("1.5e-7"), worst32
+
+
+def test_width_polynomial_range_shrinks_with_the_radius_and_ends(L):
+    xs = [_width_poly(L, radius_scale=r)[1] for r in (0.5, 1.0, 2.0, 4.0, 8.0)]
+    assert all(x > 0 for x in xs) and all(x1 > x2 for x1, x2 in zip(xs, xs[1:]))
+    assert 0.015 < _width_poly(L, confidence=0.9)[1] < 0.025          # the benchmark's radius, kappa(0.9) = 1.645
+    assert _width_poly(L, radius_scale=12.0, radius_max=16.0)[1] < 0  # no useful range left: the kernels skip it
+    # the clamp is part of the radius
+    assert _width_poly(L, radius_scale=50.0, radius_max=1.0) == _width_poly(L, radius_scale=1.0)
+    p = _params(L)
+    assert L.ciar_width_polynomial(ctypes.byref(p), None, None) == -1    # CIAR_EINVAL
