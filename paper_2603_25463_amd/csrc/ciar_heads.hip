@@ -2,6 +2,8 @@
 // averages the heads' widths token by token, and the Voting majority.
 #include "ciar_device.h"
 
+#include <type_traits>
+
 namespace ciar {
 namespace {
 
@@ -53,6 +55,8 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
     // (~1e-7 each, uncorrelated when the radii differ from token to token) do not, and Omega ~ V multiplies what
     // is left of the spread.
     const bool precise = __syncthreads_and(flat_h ? 1 : 0) != 0 || V <= 64;   // uniform; also the barrier
+    // no head with an active cap (delta = alpha_u w + (alpha_u - alpha_l) p^l loses its second term): uniform
+    const bool no_lower = __syncthreads_and(tid < H ? (sm_cl[tid] == 0.0 ? 1 : 0) : 1) != 0;
 
     const RadiusMode rm = radius_mode(A);
     const int nvec = (V + EPV - 1) / EPV;
@@ -135,63 +139,101 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
             }
         }
     }
-    constexpr int UB = 16 / EPV;                                   // vectors of a head in flight per lane
-    for (int v0 = tid; !precise && v0 < nvec; v0 += 256 * UB) {
-        double D[UB][EPV];                                         // fp64 across heads
-        double C[WIDE ? UB : 1][EPV];
-        float pm[UB][EPV];
-#pragma unroll
-        for (int u = 0; u < UB; ++u) {
-#pragma unroll
-            for (int k = 0; k < EPV; ++k) {
-                D[u][k] = 0.0; pm[u][k] = 0.f;
-                if constexpr (WIDE) C[u][k] = 0.0;
-            }
-        }
-        for (int h = 0; h < H; ++h) {
-            const gvec c = (gvec)(gbytes)(static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride);
-            const gvec r = (gvec)(gbytes)(static_cast<const T*>(rad ? A.radius : A.draft) + (int64_t)h * head_stride +
-                                          row * A.stride);
-            u32x4 cw4[UB], rw4[UB];
-#pragma unroll
-            for (int u = 0; u < UB; ++u) cw4[u] = c[min(v0 + u * 256, nvec - 1)];
-            if (rad) {
-#pragma unroll
-                for (int u = 0; u < UB; ++u) rw4[u] = r[min(v0 + u * 256, nvec - 1)];
-            }
-            const FuseRow fr = sm_fr[h];
-            const float invS = sm_invS[h];
+    // The sweep proper, specialised on what is uniform over the launch or the row: MODE bit 0 = tensor radius,
+    // bit 1 = unit radius scale (see radius_am1), bit 2 = no head has an active cap (p^l is not needed).
+    // Two 16-byte vectors of a head in flight per lane (fp32; one for bf16): more of them cost registers and
+    // with them a wave per SIMD, which measured slower (four: +4 %, eight: +70 %).
+    constexpr int UB = EPV >= 8 ? 1 : 8 / EPV;
+    auto sweep = [&](auto mode_c) {
+        constexpr int MODE = decltype(mode_c)::value;
+        constexpr bool RADc = (MODE & 1) != 0, UNITc = (MODE & 2) != 0, NOLOW = (MODE & 4) != 0;
+        for (int v0 = tid; v0 < nvec; v0 += 256 * UB) {
+            double D[UB][EPV];                                     // fp64 across heads
+            double C[WIDE ? UB : 1][EPV];
+            float pm[UB][EPV];
 #pragma unroll
             for (int u = 0; u < UB; ++u) {
-                const int tok0 = (v0 + u * 256) * EPV;             // >= V for vectors past the row's end
-                float cv[EPV], rv[EPV];
-                E::unpack(cw4[u], cv);
-                if (rad) E::unpack(rw4[u], rv);
 #pragma unroll
                 for (int k = 0; k < EPV; ++k) {
-                    if (tok0 + k < V) {
-                        const float e = head_token(h, cv[k], rad ? rv[k] : 0.f, fr, D[u][k], C[WIDE ? u : 0][k]);
-                        pm[u][k] = fmaf(e, invS, pm[u][k]);
+                    D[u][k] = 0.0; pm[u][k] = 0.f;
+                    if constexpr (WIDE) C[u][k] = 0.0;
+                }
+            }
+            for (int h = 0; h < H; ++h) {
+                const gvec c = (gvec)(gbytes)(static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride);
+                const gvec r = (gvec)(gbytes)(static_cast<const T*>(RADc ? A.radius : A.draft) +
+                                              (int64_t)h * head_stride + row * A.stride);
+                u32x4 cw4[UB], rw4[UB];
+#pragma unroll
+                for (int u = 0; u < UB; ++u) cw4[u] = c[min(v0 + u * 256, nvec - 1)];
+                if constexpr (RADc) {
+#pragma unroll
+                    for (int u = 0; u < UB; ++u) rw4[u] = r[min(v0 + u * 256, nvec - 1)];
+                }
+                const FuseRow fr = sm_fr[h];
+                const float invS = sm_invS[h], nh = sm_n[h];
+                const double cw = sm_cw[h], cl = sm_cl[h];
+                auto token = [&](float cval, float rval, double& d, double& cc, float& p) {
+                    const float e = exp2_ref(cval, nh);
+                    float gl, gw;
+                    if constexpr (WIDE) {
+                        float ec;
+                        if constexpr (RADc) fuse_token_rad_wide<UNITc>(e, rval, fr, rm.kappa, rm.rmax, rm.am1_max, gl, gw, ec);
+                        else fuse_token_wide(e, fr, gl, gw, ec);
+                        cc += (double)ec;
+                    } else {
+                        if constexpr (RADc) fuse_token_rad<UNITc>(e, rval, fr, rm.kappa, rm.rmax, rm.am1_max, gl, gw);
+                        else fuse_token(e, fr, gl, gw);
                     }
+                    if constexpr (NOLOW) d = fma(cw, (double)gw, d);
+                    else d = fma(cw, (double)gw, fma(cl, (double)gl, d));
+                    p = fmaf(e, invS, p);
+                };
+#pragma unroll
+                for (int u = 0; u < UB; ++u) {
+                    const int tok0 = (v0 + u * 256) * EPV;         // >= V for vectors past the row's end
+                    float cv[EPV], rv[EPV];
+                    E::unpack(cw4[u], cv);
+                    if constexpr (RADc) E::unpack(rw4[u], rv);
+                    if (tok0 + EPV <= V) {                         // a whole vector of tokens: no per-token test
+#pragma unroll
+                        for (int k = 0; k < EPV; ++k) token(cv[k], RADc ? rv[k] : 0.f, D[u][k], C[WIDE ? u : 0][k], pm[u][k]);
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < EPV; ++k) {
+                            if (tok0 + k < V) token(cv[k], RADc ? rv[k] : 0.f, D[u][k], C[WIDE ? u : 0][k], pm[u][k]);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) {
+                    const int tok = (v0 + u * 256) * EPV + k;
+                    if (tok < V) {
+                        const double d = D[u][k] - KD;
+                        s1 += d;
+                        s2 = fma(d, d, s2);
+                        if constexpr (WIDE) {
+                            const double c = C[u][k] - KC;
+                            c1 += c; c2 = fma(c, c, c2); cbig = fmax(cbig, C[u][k]);
+                        }
+                    }
+                    if (need_argmax && tok < V && pm[u][k] > best) { best = pm[u][k]; best_i = tok; }
                 }
             }
         }
-#pragma unroll
-        for (int u = 0; u < UB; ++u) {
-#pragma unroll
-            for (int k = 0; k < EPV; ++k) {
-                const int tok = (v0 + u * 256) * EPV + k;
-                if (tok < V) {
-                    const double d = D[u][k] - KD;
-                    s1 += d;
-                    s2 = fma(d, d, s2);
-                    if constexpr (WIDE) {
-                        const double c = C[u][k] - KC;
-                        c1 += c; c2 = fma(c, c, c2); cbig = fmax(cbig, C[u][k]);
-                    }
-                }
-                if (need_argmax && tok < V && pm[u][k] > best) { best = pm[u][k]; best_i = tok; }
-            }
+    };
+    if (!precise) {
+        const int mode = (rad ? 1 : 0) | (rad && rm.unit ? 2 : 0) | (no_lower ? 4 : 0);
+        switch (mode) {
+        case 0: sweep(std::integral_constant<int, 0>{}); break;
+        case 1: sweep(std::integral_constant<int, 1>{}); break;
+        case 3: sweep(std::integral_constant<int, 3>{}); break;
+        case 4: sweep(std::integral_constant<int, 4>{}); break;
+        case 5: sweep(std::integral_constant<int, 5>{}); break;
+        default: sweep(std::integral_constant<int, 7>{}); break;
         }
     }
     s1 = wave_sum(s1);
