@@ -353,12 +353,15 @@ void stream_kernel(const RowArgs A)
     // The base goes through readfirstlane and the lane index through an empty asm: both are opaque
     // to the optimiser, which otherwise turns the sixteen addresses of a row into sixteen 64-bit
     // induction variables, spills them, and serialises the loads on the reloads.
-    auto load_row = [&](u32x4 (&buf)[NVEC], const void* rows, int r) {
+    // `whole` = false: every lane fetches the row's first vectors only (a few cache lines per wave, results unused).
+    // The quantify-only loop requests its next row this way when there is none: a request under a branch made the
+    // register allocator spill a third of the centre row there (none when the request is unconditional).
+    auto load_row = [&](u32x4 (&buf)[NVEC], const void* rows, int r, bool whole = true) {
         const uint64_t b = (uint64_t)(static_cast<const T*>(rows) + (int64_t)r * A.stride);
         const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
         const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
         const gbytes base = (gbytes)(((uint64_t)hi << 32) | lo);
-        int t = tid;
+        int t = whole ? tid : 0;
         asm volatile("" : "+v"(t));
         if (partial) {
 #pragma unroll
@@ -679,7 +682,11 @@ void stream_kernel(const RowArgs A)
         // the next centre row goes in flight before the barrier and thread 0's bookkeeping
         if constexpr (!EARLY_NEXT) {
             __builtin_amdgcn_sched_barrier(0);
-            if (has_next) load_row(buf, A.draft, next);
+            if constexpr (DO_V) {
+                if (has_next) load_row(buf, A.draft, next);
+            } else {
+                load_row(buf, A.draft, has_next ? next : row, has_next);
+            }
         }
 
         // ---- wave 0 leaves the row's ten numbers for the finishing kernels -----------------------------------
