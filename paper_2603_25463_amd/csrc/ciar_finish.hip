@@ -121,8 +121,10 @@ __global__ __launch_bounds__(THREADS) void resample_kernel(const RowArgs A, cons
         };
         // residuals of one 16-byte vector of each row; tokens past the end of the row are masked to -inf
         auto residuals = [&](u32x4 cr, u32x4 tr, int j, float (&r)[EPV]) {
-            E::mask_tail(cr, (j * THREADS + tid) * EPV, V);
-            E::mask_tail(tr, (j * THREADS + tid) * EPV, V);
+            if ((j + 1) * CHUNK > V) {                             // uniform: only the row's last chunk can hold padding
+                E::mask_tail(cr, (j * THREADS + tid) * EPV, V);
+                E::mask_tail(tr, (j * THREADS + tid) * EPV, V);
+            }
             float cv[EPV], tv[EPV];
             E::unpack(cr, cv);
             E::unpack(tr, tv);
