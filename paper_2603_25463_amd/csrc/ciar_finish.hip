@@ -154,26 +154,35 @@ __global__ __launch_bounds__(THREADS) void resample_kernel(const RowArgs A, cons
             }
         }
         __syncthreads();
-        double R = 0.0;
-        for (int j = 0; j < nch; ++j) {
+        // Every wave locates the crossing chunk across its lanes: lane j < nch holds chunk j's total over the
+        // waves, an inclusive scan over the lanes gives the running sums in token order, a ballot the first chunk
+        // whose running sum exceeds u * R.
+        double tot = 0.0;
+        if (lane < nch) {
 #pragma unroll
-            for (int w = 0; w < NW; ++w) R += sm_e[w * MAXCH + j];
+            for (int w = 0; w < NW; ++w) tot += sm_e[w * MAXCH + lane];
         }
+        const double run = wave_scan(tot);                         // lanes >= nch add nothing
+        auto lane_value = [&](double v, int src) {
+            return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), src),
+                                    __builtin_amdgcn_readlane(__double2loint(v), src));
+        };
+        const double R = lane_value(run, 63);
         int cand = INT_MAX, lastpos = -1;
         if (R > 0.0) {
             // chunk that holds the crossing of u * R (token order = chunk order, then lane order)
             const double thr = u_res * R;
-            int jstar = -1, jlast = 0;
-            double before = 0.0, run = 0.0;
-            for (int j = 0; j < nch; ++j) {
-                double tot = 0.0;
-#pragma unroll
-                for (int w = 0; w < NW; ++w) tot += sm_e[w * MAXCH + j];
-                if (jstar < 0 && run + tot > thr) { jstar = j; before = run; }
-                if (tot > 0.0) jlast = j;
-                if (jstar < 0) run += tot;
+            const unsigned long long cross = __ballot(lane < nch && run > thr);
+            const unsigned long long live = __ballot(lane < nch && tot > 0.0);
+            int jstar;
+            double before;
+            if (cross) {
+                jstar = __builtin_amdgcn_readfirstlane(__ffsll((long long)cross) - 1);
+                before = jstar > 0 ? lane_value(run, jstar - 1) : 0.0;
+            } else {                                               // unreachable for u < 1; keeps the draw valid
+                jstar = __builtin_amdgcn_readfirstlane(live ? 63 - __clzll((long long)live) : 0);
+                before = R;
             }
-            if (jstar < 0) { jstar = jlast; before = run; }        // unreachable for u < 1; keeps the draw valid
             // E2: the lane's residuals inside that chunk, fetched again (cache) and recomputed exactly as in E1
             float r[EPV];
             residuals(load_vec(crow, jstar), load_vec(trow, jstar), jstar, r);
