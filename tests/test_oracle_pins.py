@@ -565,6 +565,25 @@ def test_tensor_radius_two_token_vocabulary_is_the_logistic_sigmoid(oracle):
     assert np.max(np.abs(hi[:, 0] - sps.expit(d + r[:, 1]))) > 1e-3
 
 
+def test_unit_scale_tensor_radius_is_rational_in_the_probability(oracle):
+    """kappa = 1: e^Softplus(raw) = 1 + e^raw exactly, so with E_i = e^raw_i and x_i = softmax(c)_i the bounds are
+    rational functions free of any logarithm: p^u_i = (1 + E_i) x_i / (1 + E_i x_i) and
+    p^l_i = x_i / (1 + E_i (1 - x_i)) (Sec. 3.2.3: r = Softplus(raw); App. "Proof of Interval Validity" with
+    a = e^r, b = 1/a).  Pins the Softplus against its closed form and the pairing of a and b."""
+    rng = np.random.default_rng(43)
+    c = _rows(rng, 40, 37, 2.0)
+    raw = _raw_radius(rng, 40, 37, mu=-1.0, sd=3.0)
+    lo, mid, hi = oracle.dense_intervals(c, oracle.Params(kappa=1.0, radius_max=1e9, normalize=False), radius=raw)
+    x = sps.softmax(c.astype(np.float64), axis=1)
+    E = np.exp(raw.astype(np.float64))
+    np.testing.assert_allclose(mid, x, rtol=1e-13)
+    np.testing.assert_allclose(hi, (1.0 + E) * x / (1.0 + E * x), rtol=1e-12)
+    np.testing.assert_allclose(lo, x / (1.0 + E * (1.0 - x)), rtol=1e-12)
+    # a scale other than 1 is told apart
+    lo2, _, hi2 = oracle.dense_intervals(c, oracle.Params(kappa=1.1, radius_max=1e9, normalize=False), radius=raw)
+    assert np.max(np.abs(hi2 - hi)) > 1e-3 and np.max(np.abs(lo2 - lo)) > 1e-4
+
+
 def test_tensor_radius_equals_softmax_of_the_row_with_one_logit_shifted_by_its_own_radius(oracle):
     """Brute force over tokens with a library softmax; radii and rows differ from row to row (a wrong row
     stride or a transposed radius tensor fails)."""
