@@ -554,26 +554,30 @@ int ciar_quantify_multihead(const void* draft_heads, const void* radius_heads, i
     uint8_t* ws_flags = reinterpret_cast<uint8_t*>(w + (size_t)heads * (stats_bytes(N) + ids_bytes(N)));
     const size_t head_bytes = (size_t)head_stride * (size_t)r.elt;
 
-    // one streaming pass per head: every head's RowStats
-    for (int h = 0; h < heads; ++h) {
-        ciar::RowArgs a = base_args(params, r, N);
-        a.draft = static_cast<const char*>(draft_heads) + (size_t)h * head_bytes;
-        a.radius = radius_heads ? static_cast<const char*>(radius_heads) + (size_t)h * head_bytes : nullptr;
-        a.stats = stats + (size_t)h * (size_t)N;
-        a.reject_list = ws_ids + (size_t)h * (ids_bytes(N) / 4);
-        a.reject_count = a.reject_list;                      // not used by a quantify-only pass
+    // one streaming pass over the rows of all heads ([heads, N] rows, head h at h * head_stride): every head's RowStats
+    {
+        const int64_t rows = (int64_t)heads * N;
+        if (rows > 0x7fffffffLL) return fail(CIAR_EUNSUPPORTED, "heads * N exceeds 2^31 - 1 rows per call");
+        ciar::RowArgs a = base_args(params, r, rows);
+        if (heads > 1) { a.head_rows = N; a.head_stride = head_stride; }
+        a.draft = draft_heads;
+        a.radius = radius_heads;
+        a.stats = stats;
+        a.reject_list = ws_ids;                              // heads * N ints; a quantify-only pass builds no list
+        a.reject_count = a.reject_list;
         if (strategy == CIAR_VOTING) {
-            // every head is a quantifier of its own: the streaming kernel finishes its rows where it can
-            const size_t o = (size_t)h * (size_t)N;
+            // every head is a quantifier of its own: the streaming kernel finishes its rows where it can;
+            // the per-head outputs are [heads, N], which is the order of the rows
             a.ids = draft_ids;
-            a.p_lo = p_lo ? p_lo + o : nullptr; a.p_mid = p_mid ? p_mid + o : nullptr; a.p_hi = p_hi ? p_hi + o : nullptr;
-            a.omega = omega ? omega + o : nullptr; a.sigma = sigma ? sigma + o : nullptr;
-            a.score = score ? score + o : nullptr;
-            a.flags = (head_flags ? head_flags : ws_flags) + o;
+            a.ids_period = heads > 1 ? N : 0;
+            a.p_lo = p_lo; a.p_mid = p_mid; a.p_hi = p_hi;
+            a.omega = omega; a.sigma = sigma; a.score = score;
+            a.flags = head_flags ? head_flags : ws_flags;
             if (needs_argmax(a)) {
                 const hipError_t e = ciar::launch_argmax(params->dtype, a, a.reject_list, stream);
                 if (e != hipSuccess) return hip_fail(e, "arg-max kernel launch");
                 a.ids = a.reject_list;
+                a.ids_period = 0;
             }
             hipError_t e = ciar::launch_stream(ciar::Mode::Quantify, params->dtype, a, true, stream);
             if (e != hipSuccess) return hip_fail(e, "streaming kernel launch");

@@ -103,6 +103,19 @@ __device__ __forceinline__ float load_logit(const T* row, int i)
     else return bits_f((uint32_t)reinterpret_cast<const uint16_t*>(row)[i] << 16);
 }
 
+// Element offset of row r from the start of a logit tensor, and the index of its drafted token (see RowArgs:
+// several heads in one launch).  Rows are counted in 32 bits (the entry points reject more).
+__device__ __forceinline__ int64_t row_offset(const RowArgs& A, int64_t r)
+{
+    if (A.head_rows == 0) return r * A.stride;
+    const uint32_t h = (uint32_t)r / (uint32_t)A.head_rows;
+    return (int64_t)h * A.head_stride + (int64_t)((uint32_t)r - h * (uint32_t)A.head_rows) * A.stride;
+}
+__device__ __forceinline__ int64_t ids_index(const RowArgs& A, int64_t r)
+{
+    return A.ids_period ? (int64_t)((uint32_t)r % (uint32_t)A.ids_period) : r;
+}
+
 // ---- wave reductions (fixed order: deterministic) ----------------------------------------------
 //
 // DPP row shifts and row broadcasts: they run on the vector ALU at full rate, whereas a shuffle

@@ -45,11 +45,12 @@ __global__ __launch_bounds__(256) void rowfinish_kernel(const RowArgs A, const i
         const RowStats st = A.stats[row];
         float cx = st.mc, tx = 0.f, rawx = 0.f;                    // no ids: the arg-max token is reported
         if (A.ids) {
-            int xid = A.ids[row];
+            int xid = A.ids[ids_index(A, row)];
             xid = xid < 0 ? 0 : (xid >= V ? V - 1 : xid);
-            cx = load_logit(static_cast<const T*>(A.draft) + row * A.stride, xid);
-            if (do_v) tx = load_logit(static_cast<const T*>(A.target) + row * A.stride, xid);
-            if (A.radius) rawx = load_logit(static_cast<const T*>(A.radius) + row * A.stride, xid);
+            const int64_t off = row_offset(A, row);
+            cx = load_logit(static_cast<const T*>(A.draft) + off, xid);
+            if (do_v) tx = load_logit(static_cast<const T*>(A.target) + off, xid);
+            if (A.radius) rawx = load_logit(static_cast<const T*>(A.radius) + off, xid);
         }
         rej = finish_row(A, row, st, cx, tx, rawx, do_v ? A.u_accept[row] : 0.f, do_q != 0, do_v != 0);
     }
@@ -247,7 +248,7 @@ __global__ __launch_bounds__(256) void argmax_kernel(const RowArgs A, int32_t* _
     __shared__ int sm_i[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t row = blockIdx.x;
-    const T* c = static_cast<const T*>(A.draft) + row * A.stride;
+    const T* c = static_cast<const T*>(A.draft) + row_offset(A, row);
     float m = -INFINITY;
     int idx = INT_MAX;
     for (int i = tid; i < A.V; i += 256) {

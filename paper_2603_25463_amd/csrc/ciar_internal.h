@@ -43,6 +43,12 @@ struct RowArgs {
     int32_t  finish;                                 // 1 = the streaming kernel also finishes its rows (quantify only)
     int64_t  N;
     int64_t  stride;            // elements between rows
+    // Several heads in one launch (quantify only): the N rows are [heads, head_rows], head h starting head_stride
+    // elements after head h - 1; head_rows = 0: one head.  ids_period > 0: row r reads ids[r % ids_period] (the
+    // heads share one list of drafted tokens).
+    int64_t  head_rows;
+    int64_t  head_stride;
+    int64_t  ids_period;
     int32_t  V;
     int32_t  normalize;
     double   a;                 // e^{+r}   (scalar radius r = min(kappa, rmax))

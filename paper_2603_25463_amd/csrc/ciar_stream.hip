@@ -357,7 +357,7 @@ void stream_kernel(const RowArgs A)
     // The quantify-only loop requests its next row this way when there is none: a request under a branch made the
     // register allocator spill a third of the centre row there (none when the request is unconditional).
     auto load_row = [&](u32x4 (&buf)[NVEC], const void* rows, int r, bool whole = true) {
-        const uint64_t b = (uint64_t)(static_cast<const T*>(rows) + (int64_t)r * A.stride);
+        const uint64_t b = (uint64_t)(static_cast<const T*>(rows) + row_offset(A, r));
         const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
         const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
         const gbytes base = (gbytes)(((uint64_t)hi << 32) | lo);
@@ -424,10 +424,10 @@ void stream_kernel(const RowArgs A)
     float fx[2] = {0.f, 0.f};
     if (tid < my_rows && A.ids) {
         const int64_t r = (int64_t)blockIdx.x + (int64_t)tid * step;
-        int xid = A.ids[r];
+        int xid = A.ids[ids_index(A, r)];
         xid = xid < 0 ? 0 : (xid >= V ? V - 1 : xid);
-        fx[0] = load_logit(static_cast<const T*>(A.draft) + r * A.stride, xid);
-        if constexpr (RAD) fx[1] = load_logit(static_cast<const T*>(A.radius) + r * A.stride, xid);
+        fx[0] = load_logit(static_cast<const T*>(A.draft) + row_offset(A, r), xid);
+        if constexpr (RAD) fx[1] = load_logit(static_cast<const T*>(A.radius) + row_offset(A, r), xid);
     }
 
     // The row index is uniform over the workgroup: keep it in a scalar register.
@@ -444,7 +444,7 @@ void stream_kernel(const RowArgs A)
         const int next = __builtin_amdgcn_readfirstlane(row + step);
         const bool has_next = next < nrows;                        // uniform
         float raw0 = 0.f;                                          // raw radius of the row's first token
-        if constexpr (RAD && DO_Q) raw0 = load_logit(static_cast<const T*>(A.radius) + (int64_t)row * A.stride, 0);
+        if constexpr (RAD && DO_Q) raw0 = load_logit(static_cast<const T*>(A.radius) + row_offset(A, row), 0);
 
         // ---- B: centre row: per-wave max, e_i = 2^(c_i log2e - n_w), S_w -------------------------------
         float e[EPT];
