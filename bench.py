@@ -216,6 +216,8 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=2, help="1..5 (default 2: the headline configuration)")
     ap.add_argument("--copies", type=int, default=8, help="distinct input copies rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mode", choices=("fused", "quantify", "verify"), default="fused",
+                    help="which entry-point pair the step is (default: the fused quantify + verify pass)")
     ap.add_argument("--streams", type=int, default=1,
                     help="HIP streams the steps rotate through (each with its own workspace and outputs): "
                          "consecutive batches are independent, so with 2 the streaming kernel of one batch "
@@ -291,10 +293,17 @@ def main() -> int:
         rad = rads[i % copies] if rads else None
         lane = i % nstreams
         o, ws, st = outs[lane], wss[lane], streams[lane]
-        call = (_ptr(d), _ptr(rad), _ptr(t), _ptr(w.ids), _ptr(w.u_accept), _ptr(w.u_resample), N, ctypes.byref(cp),
-                _ptr(o["p_lo"]), _ptr(o["p_mid"]), _ptr(o["p_hi"]), _ptr(o["omega"]), _ptr(o["sigma"]),
-                _ptr(o["score"]), _ptr(o["flags"]), _ptr(o["accept"]), _ptr(o["row_id"]),
-                _ptr(o["accept_len"]), _ptr(o["resampled_id"]), _ptr(ws), ws.numel(), _stream(st))
+        q = [_ptr(o[k]) for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score", "flags")]
+        v = [_ptr(o[k]) for k in ("accept", "row_id", "accept_len", "resampled_id")]
+        if args.mode == "quantify":              # no verifier row, no verification outputs
+            call = (_ptr(d), _ptr(rad), None, _ptr(w.ids), None, None, N, ctypes.byref(cp), *q, None, None, None, None,
+                    _ptr(ws), ws.numel(), _stream(st))
+        elif args.mode == "verify":              # no quantifier outputs
+            call = (_ptr(d), None, _ptr(t), _ptr(w.ids), _ptr(w.u_accept), _ptr(w.u_resample), N, ctypes.byref(cp),
+                    *([None] * 7), *v, _ptr(ws), ws.numel(), _stream(st))
+        else:
+            call = (_ptr(d), _ptr(rad), _ptr(t), _ptr(w.ids), _ptr(w.u_accept), _ptr(w.u_resample), N,
+                    ctypes.byref(cp), *q, *v, _ptr(ws), ws.numel(), _stream(st))
         if ev0 is not None:
             # the kernel's dispatch records the two events itself, at its start and at its end
             _check(L.ciar_stream_rows_timed(*call, ev0.cuda_event, ev1.cuda_event))
@@ -341,7 +350,7 @@ def main() -> int:
         e.record(stream)
     torch.cuda.synchronize()
     for i in range(60):
-        d, t = drafts[i % copies], targets[i % copies]
+        d, t = drafts[i % copies], (None if args.mode == "quantify" else targets[i % copies])
         if i >= 10:
             _check(L.ciar_read_rows_timed(_ptr(d), _ptr(t), N, ctypes.byref(cp), _ptr(rs), sp,
                                           cev0[i - 10].cuda_event, cev1[i - 10].cuda_event))
@@ -352,13 +361,15 @@ def main() -> int:
     ms_per_step = 1e3 * total_s / args.steps
     kern_ms = sorted(a.elapsed_time(b) for a, b in zip(ev0, ev1))
     kern_avg_ms = sum(kern_ms) / len(kern_ms)
-    bytes_per_launch = N * algorithmic_bytes_per_position(V, elt, 3 if rads else 2)
+    rows_read = (3 if rads else 2) - (1 if args.mode == "quantify" else 0)
+    bytes_per_launch = N * algorithmic_bytes_per_position(V, elt, rows_read)
     achieved = bytes_per_launch / (kern_avg_ms * 1e-3) / 1e9
 
     result = {
-        "metric": "token positions/sec (quantify+verify, V=16384 fp32)" if args.workload == 2 and not rads
-                  else f"token positions/sec (quantify+verify, V={V} {'fp32' if elt == 4 else 'bf16'}"
-                       f"{', tensor radius' if rads else ''})",
+        "metric": "token positions/sec (quantify+verify, V=16384 fp32)"
+                  if args.workload == 2 and not rads and args.mode == "fused"
+                  else f"token positions/sec ({'quantify+verify' if args.mode == 'fused' else args.mode + ' only'}, "
+                       f"V={V} {'fp32' if elt == 4 else 'bf16'}{', tensor radius' if rads else ''})",
         "value": N * args.steps / total_s,
         "unit": "positions/s",
         "n_gpus": 1,
@@ -373,7 +384,9 @@ def main() -> int:
         "config": {"workload": f"cfg{args.workload} {spec.name}: {spec.images} images x {spec.grid}x{spec.grid} = "
                                f"{N} positions, V={V}, {'fp32' if elt == 4 else 'bf16'} logits, window K={K}, "
                                + ("radius tensor N(mu_row, 1), kappa 1, tau 0.30" if rads else "confidence 0.9, tau 0.30"),
-                   "input_copies_rotated": copies, "launches_per_step": 3 if K <= 256 else 4, "streams": nstreams},
+                   "input_copies_rotated": copies, "mode": args.mode,
+                   "launches_per_step": None if args.mode == "quantify" else (3 if K <= 256 else 4),
+                   "streams": nstreams},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None if rads else measured_traffic(spec.name),
                      "kernel": "stream_kernel (every logit row of every position, read once)", "kernel_avg_us": 1e3 * kern_avg_ms,
@@ -382,7 +395,8 @@ def main() -> int:
                      "algorithmic_bytes_per_launch": bytes_per_launch,
                      "plain_read_ceiling": {"kernel": "read_kernel (ciar_read_rows: load both rows, add)",
                                             "avg_us": 1e3 * ceil_ms,
-                                            "gbs": 2 * N * V * elt / (ceil_ms * 1e-3) / 1e9}},
+                                            "gbs": (1 if args.mode == "quantify" else 2) * N * V * elt
+                                                   / (ceil_ms * 1e-3) / 1e9}},
     }
 
     if not args.no_cpu_baseline:
