@@ -89,7 +89,7 @@ def _logits(a) -> np.ndarray:
             a = a.contiguous().view(torch.int16).numpy().view(np.uint16)
         else:
             a = a.contiguous().numpy()
-    assert a.dtype in (np.float32, np.uint16), a.dtype
+    assert a.dtype in (np.float32, np.uint16, np.float64), a.dtype
     assert a.ndim == 2 and a.flags.c_contiguous
     return a
 
@@ -97,7 +97,7 @@ def _logits(a) -> np.ndarray:
 def _cparams(p: Params, logits: np.ndarray, vocab: int | None) -> _CParams:
     V = int(vocab if vocab is not None else logits.shape[1])
     assert 1 <= V <= logits.shape[1]
-    return _CParams(V, 0 if logits.dtype == np.float32 else 1, logits.shape[1],
+    return _CParams(V, {np.dtype(np.float32): 0, np.dtype(np.uint16): 1, np.dtype(np.float64): 2}[logits.dtype], logits.shape[1],
                     float(p.kappa), float(p.confidence), float(p.radius_max), float(p.tau),
                     float(p.lower_cap), float(p.upper_cap), int(bool(p.normalize)), int(p.window))
 
@@ -142,6 +142,39 @@ def quantify(draft, ids, params: Params, vocab: int | None = None, threads: int 
                                       _ptr(out["flags"]), threads or default_threads())
     assert rc == 0
     return out
+
+
+def _bf16_to_f64(a) -> np.ndarray:
+    """bf16 values (torch CPU bfloat16 tensor, or numpy uint16 bit patterns) widened exactly to float64."""
+    if not isinstance(a, np.ndarray):
+        import torch
+        assert isinstance(a, torch.Tensor) and a.device.type == "cpu" and a.dtype == torch.bfloat16
+        a = a.contiguous().view(torch.int16).numpy().view(np.uint16)
+    assert a.dtype == np.uint16
+    return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def interhead_logits(hidden, weight, bias=None):
+    """The Interval Head's two linear maps (Sec. 3.2.1, "Interval Head Architecture": output dimension 2|V|,
+    c_t = Linear_center(h_t), raw radius = Linear_radius(h_t)) in fp64: hidden [N, D] and weight [2V, D] are bf16
+    (widened exactly), bias [2V] or None.  Returns (centre, raw_radius), each [N, V] float64:
+    centre[n, j] = sum_k hidden[n, k] weight[j, k] + bias[j], raw_radius[n, j] likewise with weight row V + j."""
+    h = _bf16_to_f64(hidden)
+    w = _bf16_to_f64(weight)
+    assert h.ndim == 2 and w.ndim == 2 and w.shape[1] == h.shape[1] and w.shape[0] % 2 == 0
+    V = w.shape[0] // 2
+    out = h @ w.T                                                  # numpy's fp64 matrix product is the step
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float64)
+        assert b.shape == (2 * V,)
+        out = out + b[None, :]
+    return np.ascontiguousarray(out[:, :V]), np.ascontiguousarray(out[:, V:])
+
+
+def interhead_quantify(hidden, weight, bias, ids, params: Params, threads: int | None = None):
+    """quantify() on the Interval Head's own fp64 logits: r_i = min(kappa * Softplus(raw_i), radius_max)."""
+    centre, raw = interhead_logits(hidden, weight, bias)
+    return quantify(centre, ids, params, radius=raw, threads=threads)
 
 
 DRO_TERMS = ("l1_mid", "l1_up", "l1_lo", "ce_mid", "ce_up", "ce_lo", "kl")

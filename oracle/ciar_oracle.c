@@ -49,7 +49,7 @@
 
 typedef struct ciar_oracle_params {
     int32_t vocab;        /* V >= 1 */
-    int32_t dtype;        /* 0 = float32 logits, 1 = bfloat16 logits (raw uint16) */
+    int32_t dtype;        /* 0 = float32 logits, 1 = bfloat16 logits (raw uint16), 2 = float64 logits */
     int64_t row_stride;   /* elements between consecutive rows, >= V */
     double  kappa;        /* scalar logit radius before the clamp; if < 0 it is derived from confidence */
     double  confidence;   /* gamma in (0,1), used only when kappa < 0 */
@@ -67,6 +67,9 @@ static double load_logit(const void* base, int32_t dtype, int64_t index)
 {
     if (dtype == 0) {
         return (double)((const float*)base)[index];
+    } else if (dtype == 2) {
+        /* logits already in double precision (the Interval Head's linear maps evaluated in fp64) */
+        return ((const double*)base)[index];
     } else {
         /* bfloat16 is the upper half of an IEEE float32: widening is exact. */
         uint32_t bits = ((uint32_t)((const uint16_t*)base)[index]) << 16;
@@ -271,7 +274,7 @@ int ciar_oracle_dense_intervals(const void* draft, const void* radius, int64_t N
 static const void* head_base(const void* base, int32_t dtype, int64_t head, int64_t head_stride)
 {
     if (!base) return NULL;
-    return (const char*)base + (size_t)head * (size_t)head_stride * (dtype == 0 ? 4u : 2u);
+    return (const char*)base + (size_t)head * (size_t)head_stride * (dtype == 0 ? 4u : dtype == 2 ? 8u : 2u);
 }
 
 /*
