@@ -208,6 +208,107 @@ def bench_interdro(args, torch, ciar, wl, dev) -> int:
     return 0
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 on the matrix cores, published
+
+
+def bench_interhead(args, torch, ciar, wl, dev) -> int:
+    """The Interval Head as a producer: one step = ciar_interhead_quantify on N hidden states (the bf16
+    contraction [N, D] x [D, 2V] on the matrix cores, fp32 logits, then the tensor-radius quantifier on them).
+    N and V are the workload's; D = --hidden; hidden states ~ N(0, 1), weights ~ N(0, 4 / D), radius bias -1.
+    Roofline: the contraction kernel, 2 * N * 2V * D flops per launch against the dense bf16 peak, its duration
+    taken on every fourth step, where the same two kernels run through ciar_interhead_logits_timed +
+    ciar_quantify on the entry point's own workspace layout."""
+    import ctypes
+    from paper_2603_25463_amd.binding import _ptr, _stream, _check, _head_params
+    spec = wl.SPECS[args.workload]
+    N, V, D = spec.rows, spec.vocab, args.hidden
+    g = torch.Generator(device=dev).manual_seed(0xC1A20500 + args.workload)
+    copies = max(1, min(args.copies, 4))
+    hs = [torch.randn((N, D), generator=g, device=dev).bfloat16() for _ in range(copies)]
+    weight = (torch.randn((2 * V, D), generator=g, device=dev) * (2.0 / D ** 0.5)).bfloat16()
+    bias = torch.randn(2 * V, generator=g, device=dev) * 0.5
+    bias[V:] -= 1.0
+    ids = torch.randint(0, V, (N,), generator=g, device=dev, dtype=torch.int32)
+    P = ciar.Params(radius_scale=1.0, tau=0.30)
+    _, _, _, cp = _head_params(hs[0], weight, bias, P, None)
+    L = ciar.lib()
+    need = int(L.ciar_interhead_workspace_bytes(N, ctypes.byref(cp)))
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    lb = (N * V * 4 + 255) // 256 * 256                            # one logit tensor inside the workspace
+    centre = ws[:N * V * 4].view(torch.float32).view(N, V)
+    radius = ws[lb:lb + N * V * 4].view(torch.float32).view(N, V)
+    qws = ws[2 * lb:]
+    out = [torch.empty(N, dtype=torch.float32, device=dev) for _ in range(6)]
+    flags = torch.empty(N, dtype=torch.uint8, device=dev)
+    sp = _stream(torch.cuda.current_stream())
+    q = [_ptr(o) for o in out] + [_ptr(flags)]
+
+    def step(i, ev0=None, ev1=None):
+        h = hs[i % copies]
+        if ev0 is None:
+            _check(L.ciar_interhead_quantify(_ptr(h), _ptr(weight), _ptr(bias), D, _ptr(ids), N, ctypes.byref(cp), *q,
+                                             _ptr(ws), ws.numel(), sp))
+        else:
+            _check(L.ciar_interhead_logits_timed(_ptr(h), _ptr(weight), _ptr(bias), D, N, ctypes.byref(cp),
+                                                 _ptr(centre), _ptr(radius), sp, ev0.cuda_event, ev1.cuda_event))
+            _check(L.ciar_quantify(_ptr(centre), _ptr(radius), _ptr(ids), N, ctypes.byref(cp), *q, _ptr(qws),
+                                   qws.numel(), sp))
+
+    every = 4
+    ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(0, args.steps, every)]
+    ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(0, args.steps, every)]
+    for e in ev0 + ev1:
+        e.record()
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        if i % every == 0:
+            step(i, ev0[i // every], ev1[i // every])
+        else:
+            step(i)
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+    ms = 1e3 * total_s / args.steps
+    kern_ms = [a.elapsed_time(b) for a, b in zip(ev0, ev1)]
+    kavg = sum(kern_ms) / len(kern_ms)
+    flops = 2.0 * N * 2 * V * D
+    achieved = flops / (kavg * 1e-3) / 1e12
+    result = {
+        "metric": f"token positions/sec (Interval Head producer + quantify, D={D}, V={V})",
+        "value": N * args.steps / total_s, "unit": "positions/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"cfg{args.workload} {spec.name} shape: {N} hidden states of width {D} (bf16), "
+                               f"head weight [2 x {V}, {D}] bf16 + fp32 bias, fp32 logits, kappa 1, tau 0.30",
+                   "input_copies_rotated": copies},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "kernel": "interhead_gemm_kernel (the head's two linear maps as one contraction)",
+                     "kernel_avg_us": 1e3 * kavg, "kernel_min_us": 1e3 * min(kern_ms),
+                     "kernel_launches_timed": len(kern_ms), "algorithmic_flops_per_launch": flops},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = min(N, 256)
+        hh, ww, bb = hs[0][:rows].cpu(), weight.cpu(), bias.cpu().numpy()
+        hid = ids[:rows].cpu().numpy()
+        threads = oracle.default_threads()
+        done, c0 = 0, time.perf_counter()
+        while True:
+            oracle.interhead_quantify(hh, ww, bb, hid, oracle.Params(kappa=1.0, tau=0.30), threads=threads)
+            done += rows
+            dt = time.perf_counter() - c0
+            if dt > 10.0:
+                break
+        result["cpu_baseline"] = {"value": done / dt, "unit": "positions/s", "cores": threads, "kind": "oracle",
+                                  "sample": f"the first {rows} positions, repeated for {dt:.1f} s (numpy's fp64 "
+                                            f"matrix product, then the fp64 quantifier)"}
+    print(json.dumps(result))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -229,6 +330,9 @@ def main() -> int:
     ap.add_argument("--strategy", choices=("ensemble", "voting"), default="ensemble")
     ap.add_argument("--interdro", action="store_true",
                     help="time ciar_interdro_loss (forward value of the training loss) instead (not the headline)")
+    ap.add_argument("--interhead", action="store_true",
+                    help="the Interval Head producer: hidden states -> logits (matrix cores) -> quantify")
+    ap.add_argument("--hidden", type=int, default=1280, help="hidden width D of --interhead (multiple of 64)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of known size (reference for hardware counters)")
     args = ap.parse_args()
@@ -250,6 +354,8 @@ def main() -> int:
         return bench_multihead(args, torch, ciar, wl, dev)
     if args.interdro:
         return bench_interdro(args, torch, ciar, wl, dev)
+    if args.interhead:
+        return bench_interhead(args, torch, ciar, wl, dev)
 
     spec = wl.SPECS[args.workload]
     w = wl.make(args.workload, device=dev)

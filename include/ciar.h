@@ -299,6 +299,42 @@ int ciar_read_rows_timed(const void* draft_logits, const void* target_logits, in
                          float* row_sum, void* hip_stream, void* start_event, void* stop_event);
 
 /*
+ * The Interval Head as a producer (Sec. 3.2.1, "Interval Head Architecture": the head's output dimension is
+ * 2 |V|; c_t = Linear_center(h_t), r_t = Softplus(Linear_radius(h_t)), then InterFuse and the score).
+ * The two linear maps run as one bf16 contraction on the matrix cores with fp32 accumulation:
+ *   logits[n, j] = sum_k hidden[n, k] * weight[j, k] + bias[j],   j in [0, 2V)
+ * columns [0, V) are the centre logits, columns [V, 2V) the raw radius (before Softplus).
+ *
+ *   hidden     [N, hidden_dim] bf16   in   hidden states, rows contiguous (row stride hidden_dim)
+ *   weight     [2V, hidden_dim] bf16  in   row j = the weights of output column j (centre rows first)
+ *   bias       [2V] float             in   or NULL (no bias)
+ * The logits are produced in fp32, so params->dtype must be CIAR_F32; params->row_stride is the row stride of the
+ * produced logit rows.  Supported shapes: vocab a multiple of 128, hidden_dim a multiple of 64 (CIAR_EUNSUPPORTED
+ * otherwise); hidden and weight 16-byte aligned.
+ *
+ * ciar_interhead_logits writes the two logit tensors, centre and radius [N, row_stride] float each (both
+ * required), and nothing else; no workspace.
+ *
+ * ciar_interhead_quantify keeps them in the workspace and runs ciar_quantify in tensor-radius mode on them
+ * (radius_scale 1 is the head as the paper writes it); draft_ids and the outputs are ciar_quantify's.  Its
+ * workspace is ciar_interhead_workspace_bytes(N, params) = the two logit tensors + ciar_workspace_bytes.
+ */
+size_t ciar_interhead_workspace_bytes(int64_t N, const ciar_params* params);
+int ciar_interhead_logits(const void* hidden, const void* weight, const float* bias, int32_t hidden_dim, int64_t N,
+                          const ciar_params* params, float* centre, float* radius, void* hip_stream);
+int ciar_interhead_quantify(const void* hidden, const void* weight, const float* bias, int32_t hidden_dim,
+                            const int32_t* draft_ids, int64_t N, const ciar_params* params,
+                            float* p_lo, float* p_mid, float* p_hi,
+                            float* omega, float* sigma, float* score, uint8_t* flags,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ciar_interhead_logits with the contraction kernel's dispatch recording two HIP events at its start and end
+ * (see ciar_stream_rows_timed). */
+int ciar_interhead_logits_timed(const void* hidden, const void* weight, const float* bias, int32_t hidden_dim,
+                                int64_t N, const ciar_params* params, float* centre, float* radius,
+                                void* hip_stream, void* start_event, void* stop_event);
+
+/*
  * Window epilogue on its own (the last step of ciar_verify / ciar_quantify_verify, which run it when
  * a window output is requested): from the per-row results of N rows,
  *   accept_len[w]   = number of leading rows with accept != 0 in window w = rows [wK, min((w+1)K, N))

@@ -4,11 +4,11 @@
 ``workloads`` generates the seeded synthetic inputs; ``build`` compiles ``libciar.so`` for gfx950.
 """
 from .binding import (DRO_LOSSES, DRO_TERMS, ENSEMBLE, VOTING, CiarError, Params, dense_intervals,
-                      finish_rows, interdro_loss, last_error, lib, quantify, quantify_multihead,
+                      finish_rows, interdro_loss, interhead_logits, interhead_quantify, last_error, lib, quantify, quantify_multihead,
                       quantify_verify, read_rows, stream_rows, verify, version, window_epilogue,
                       workspace_bytes)
 
 __all__ = ["DRO_LOSSES", "DRO_TERMS", "ENSEMBLE", "VOTING", "CiarError", "Params", "dense_intervals",
-           "finish_rows", "interdro_loss", "last_error", "lib", "quantify", "quantify_multihead",
+           "finish_rows", "interdro_loss", "interhead_logits", "interhead_quantify", "last_error", "lib", "quantify", "quantify_multihead",
            "quantify_verify", "read_rows", "stream_rows", "verify", "version", "window_epilogue",
            "workspace_bytes"]

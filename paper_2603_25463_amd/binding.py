@@ -80,6 +80,14 @@ def lib() -> ctypes.CDLL:
         L.ciar_read_rows.argtypes = [vp, vp, i64, pp, vp, vp]
         L.ciar_read_rows_timed.restype = ctypes.c_int
         L.ciar_read_rows_timed.argtypes = [vp, vp, i64, pp, vp, vp, vp, vp]
+        L.ciar_interhead_workspace_bytes.restype = sz
+        L.ciar_interhead_workspace_bytes.argtypes = [i64, pp]
+        L.ciar_interhead_logits.restype = ctypes.c_int
+        L.ciar_interhead_logits.argtypes = [vp, vp, vp, ctypes.c_int32, i64, pp, vp, vp, vp]
+        L.ciar_interhead_logits_timed.restype = ctypes.c_int
+        L.ciar_interhead_logits_timed.argtypes = [vp, vp, vp, ctypes.c_int32, i64, pp, vp, vp, vp, vp, vp]
+        L.ciar_interhead_quantify.restype = ctypes.c_int
+        L.ciar_interhead_quantify.argtypes = [vp, vp, vp, ctypes.c_int32, vp, i64, pp] + [vp] * 7 + [vp, sz, vp]
         L.ciar_width_polynomial.restype = ctypes.c_int
         L.ciar_width_polynomial.argtypes = [pp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
         L.ciar_last_error.restype = ctypes.c_char_p
@@ -392,4 +400,69 @@ def interdro_loss(center: torch.Tensor, radius: torch.Tensor | None, cloud: torc
     _check(lib().ciar_interdro_loss(_ptr(center), _ptr(radius), _ptr(cloud), N, ctypes.byref(cp), float(lambda_v),
                                     float(lambda_p), float(lambda_beta), float(alpha), _ptr(o["terms"]),
                                     _ptr(o["weights"]), _ptr(o["losses"]), _stream(stream)))
+    return o
+
+
+def _head_params(hidden: torch.Tensor, weight: torch.Tensor, bias, params: Params, row_stride: int | None):
+    """Checks the Interval Head operands and returns (N, D, V, ciar_params) for fp32 logits of the given stride."""
+    _need_cuda(hidden, weight, bias)
+    if hidden.dtype != torch.bfloat16 or weight.dtype != torch.bfloat16:
+        raise TypeError("hidden and weight must be bfloat16")
+    if hidden.dim() != 2 or weight.dim() != 2 or not hidden.is_contiguous() or not weight.is_contiguous():
+        raise ValueError("hidden [N, D] and weight [2V, D] must be contiguous 2-D tensors")
+    if weight.shape[1] != hidden.shape[1] or weight.shape[0] % 2:
+        raise ValueError("weight must be [2V, D] with D = hidden.shape[1]")
+    N, D, V = hidden.shape[0], hidden.shape[1], weight.shape[0] // 2
+    if bias is not None and (bias.dtype != torch.float32 or bias.shape != (2 * V,) or not bias.is_contiguous()):
+        raise ValueError("bias must be a contiguous float32 tensor of 2V entries")
+    stride = V if row_stride is None else int(row_stride)
+    cp = params.to_c(torch.empty((0, stride), dtype=torch.float32), V)
+    cp.row_stride = stride
+    return N, D, V, cp
+
+
+def interhead_logits(hidden: torch.Tensor, weight: torch.Tensor, bias: torch.Tensor | None, params: Params,
+                     row_stride: int | None = None, stream=None, out: tuple | None = None, events: tuple | None = None):
+    """``ciar_interhead_logits``: (centre, raw radius), float32 [N, row_stride] each (only the first V columns
+    of a row are written).  ``events`` = (start, stop) torch events recorded by the kernel's own dispatch
+    (``ciar_interhead_logits_timed``)."""
+    N, D, V, cp = _head_params(hidden, weight, bias, params, row_stride)
+    if out is None:
+        out = (torch.empty((N, cp.row_stride), dtype=torch.float32, device=hidden.device),
+               torch.empty((N, cp.row_stride), dtype=torch.float32, device=hidden.device))
+    _need_cuda(*out)
+    if events is None:
+        _check(lib().ciar_interhead_logits(_ptr(hidden), _ptr(weight), _ptr(bias), D, N, ctypes.byref(cp),
+                                           _ptr(out[0]), _ptr(out[1]), _stream(stream)))
+    else:
+        _check(lib().ciar_interhead_logits_timed(_ptr(hidden), _ptr(weight), _ptr(bias), D, N, ctypes.byref(cp),
+                                                 _ptr(out[0]), _ptr(out[1]), _stream(stream),
+                                                 events[0].cuda_event, events[1].cuda_event))
+    return out
+
+
+def interhead_workspace_bytes(N: int, cparams: CiarParams) -> int:
+    return int(lib().ciar_interhead_workspace_bytes(int(N), ctypes.byref(cparams)))
+
+
+def interhead_quantify(hidden: torch.Tensor, weight: torch.Tensor, bias: torch.Tensor | None,
+                       ids: torch.Tensor | None, params: Params, row_stride: int | None = None, stream=None,
+                       out: dict | None = None, workspace: torch.Tensor | None = None) -> dict:
+    """``ciar_interhead_quantify``: the Interval Head's contraction, then the tensor-radius quantifier on its
+    logits.  Outputs as ``quantify``."""
+    N, D, V, cp = _head_params(hidden, weight, bias, params, row_stride)
+    _need_cuda(ids)
+    dev = hidden.device
+    need = interhead_workspace_bytes(N, cp)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    _need_cuda(workspace)
+    o = dict(out) if out else {}
+    for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score"):
+        o.setdefault(k, torch.empty(N, dtype=torch.float32, device=dev))
+    o.setdefault("flags", torch.empty(N, dtype=torch.uint8, device=dev))
+    _check(lib().ciar_interhead_quantify(_ptr(hidden), _ptr(weight), _ptr(bias), D, _ptr(ids), N, ctypes.byref(cp),
+                                         _ptr(o["p_lo"]), _ptr(o["p_mid"]), _ptr(o["p_hi"]), _ptr(o["omega"]),
+                                         _ptr(o["sigma"]), _ptr(o["score"]), _ptr(o["flags"]), _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream(stream)))
     return o

@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libciar.so")
-SOURCES = ["ciar_stream.hip", "ciar_finish.hip", "ciar_heads.hip", "ciar_loss.hip", "ciar_aux.hip", "ciar_api.cpp"]
+SOURCES = ["ciar_stream.hip", "ciar_finish.hip", "ciar_heads.hip", "ciar_loss.hip", "ciar_aux.hip", "ciar_interhead.hip", "ciar_api.cpp"]
 HEADERS = ["ciar_internal.h", "ciar_device.h", os.path.join("..", "..", "include", "ciar.h")]
 
 # Packed-FP32 instructions are switched off for every device compile of this library.

@@ -651,6 +651,103 @@ int read_rows(const void* draft_logits, const void* target_logits, int64_t N, co
 }
 }  // namespace
 
+namespace {
+// Validation shared by the Interval Head entry points; fills everything of `h` but the two output tensors.
+int head_args(const void* hidden, const void* weight, const float* bias, int32_t hidden_dim, int64_t N,
+              const ciar_params* params, ciar::HeadArgs* h)
+{
+    Resolved r;
+    if (int rc = check_params(params, &r)) return rc;
+    if (params->dtype != CIAR_F32)
+        return fail(CIAR_EUNSUPPORTED, "the Interval Head produces fp32 logits: params->dtype must be CIAR_F32");
+    if (N < 0) return fail(CIAR_EINVAL, "N is negative");
+    if (N > 0x7fffffffLL) return fail(CIAR_EUNSUPPORTED, "N exceeds 2^31 - 1 rows per call");
+    if (hidden_dim < ciar::kHeadTileDepth || hidden_dim % ciar::kHeadTileDepth != 0)
+        return fail(CIAR_EUNSUPPORTED, "hidden_dim %d is not a positive multiple of %d", hidden_dim, ciar::kHeadTileDepth);
+    if (params->vocab % ciar::kHeadTileCols != 0)
+        return fail(CIAR_EUNSUPPORTED, "params->vocab %d is not a multiple of %d", params->vocab, ciar::kHeadTileCols);
+    if (N > 0) {                                                   // an empty batch reads nothing
+        if (int rc = check_rows(hidden, "hidden")) return rc;
+        if (int rc = check_rows(weight, "weight")) return rc;
+    }
+    std::memset(h, 0, sizeof *h);
+    h->hidden = static_cast<const uint16_t*>(hidden);
+    h->weight = static_cast<const uint16_t*>(weight);
+    h->bias = bias;
+    h->N = N;
+    h->stride = params->row_stride;
+    h->D = hidden_dim;
+    h->V = params->vocab;
+    h->row_tiles = (int32_t)((N + ciar::kHeadTileRows - 1) / ciar::kHeadTileRows);
+    return CIAR_OK;
+}
+
+size_t head_logit_bytes(int64_t N, const ciar_params* p) { return round_up((size_t)N * (size_t)p->row_stride * 4, 256); }
+
+int head_logits(const void* hidden, const void* weight, const float* bias, int32_t hidden_dim, int64_t N,
+                const ciar_params* params, float* centre, float* radius, void* hip_stream, hipEvent_t ev_start,
+                hipEvent_t ev_stop)
+{
+    ciar::HeadArgs h;
+    if (int rc = head_args(hidden, weight, bias, hidden_dim, N, params, &h)) return rc;
+    if (!centre || !radius) return fail(CIAR_EINVAL, "centre or radius is NULL");
+    if (N == 0) return CIAR_OK;
+    h.centre = centre;
+    h.radius = radius;
+    const hipError_t e = ciar::launch_interhead(h, static_cast<hipStream_t>(hip_stream), ev_start, ev_stop);
+    if (e != hipSuccess) return hip_fail(e, "Interval Head kernel launch");
+    return CIAR_OK;
+}
+}  // namespace
+
+size_t ciar_interhead_workspace_bytes(int64_t N, const ciar_params* params)
+{
+    if (N <= 0 || !params || params->row_stride <= 0) return 0;
+    return 2 * head_logit_bytes(N, params) + ciar_workspace_bytes(N, params);
+}
+
+int ciar_interhead_logits(const void* hidden, const void* weight, const float* bias, int32_t hidden_dim, int64_t N,
+                          const ciar_params* params, float* centre, float* radius, void* hip_stream)
+{
+    return head_logits(hidden, weight, bias, hidden_dim, N, params, centre, radius, hip_stream, nullptr, nullptr);
+}
+
+int ciar_interhead_logits_timed(const void* hidden, const void* weight, const float* bias, int32_t hidden_dim,
+                                int64_t N, const ciar_params* params, float* centre, float* radius,
+                                void* hip_stream, void* start_event, void* stop_event)
+{
+    if (!start_event || !stop_event) return fail(CIAR_EINVAL, "start_event or stop_event is NULL");
+    return head_logits(hidden, weight, bias, hidden_dim, N, params, centre, radius, hip_stream,
+                       static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event));
+}
+
+int ciar_interhead_quantify(const void* hidden, const void* weight, const float* bias, int32_t hidden_dim,
+                            const int32_t* draft_ids, int64_t N, const ciar_params* params, float* p_lo, float* p_mid,
+                            float* p_hi, float* omega, float* sigma, float* score, uint8_t* flags, void* workspace,
+                            size_t workspace_bytes, void* hip_stream)
+{
+    ciar::HeadArgs h;
+    if (int rc = head_args(hidden, weight, bias, hidden_dim, N, params, &h)) return rc;
+    if (N == 0) return CIAR_OK;                                    // an empty batch writes nothing
+    if (!(p_lo || p_mid || p_hi || omega || sigma || score || flags))
+        return fail(CIAR_EINVAL, "every output pointer is NULL");
+    const size_t need = ciar_interhead_workspace_bytes(N, params);
+    if (!workspace) return fail(CIAR_EWORKSPACE, "workspace is NULL but %zu bytes are needed", need);
+    if (!aligned16(workspace)) return fail(CIAR_EALIGN, "workspace is not 16-byte aligned");
+    if (workspace_bytes < need)
+        return fail(CIAR_EWORKSPACE, "workspace has %zu bytes, %zu are needed", workspace_bytes, need);
+    char* w = static_cast<char*>(workspace);
+    const size_t lb = head_logit_bytes(N, params);
+    h.centre = reinterpret_cast<float*>(w);
+    h.radius = reinterpret_cast<float*>(w + lb);
+    const hipError_t e = ciar::launch_interhead(h, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail(e, "Interval Head kernel launch");
+    // the quantifier reads the logits the contraction has just written, on the same stream
+    return ciar_quantify(h.centre, h.radius, draft_ids, N, params, p_lo, p_mid, p_hi, omega, sigma, score, flags,
+                         w + 2 * lb, workspace_bytes - 2 * lb, hip_stream);
+}
+
+
 const char* ciar_last_error(void) { return g_error; }
 
 const char* ciar_version(void) { return "0.1.0"; }

@@ -138,4 +138,23 @@ hipError_t launch_dense(int dtype, const RowArgs& args, float* p_lo, float* p_mi
 hipError_t launch_read(int dtype, const RowArgs& args, float* row_sum, hipStream_t stream,
                        hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
+// The Interval Head's two linear maps on the matrix cores: out[n, j] = sum_k hidden[n, k] weight[j, k] + bias[j]
+// for the 2V output columns, bf16 operands, fp32 logits; columns [0, V) -> centre, [V, 2V) -> radius.
+// The kernel's tile: V must be a multiple of kHeadTileCols and D of kHeadTileDepth (the C ABI checks both).
+constexpr int kHeadTileRows = 128, kHeadTileCols = 128, kHeadTileDepth = 64;
+struct HeadArgs {
+    const uint16_t* hidden;     // [N, D] bf16
+    const uint16_t* weight;     // [2V, D] bf16: row j holds the weights of output column j
+    const float*    bias;       // [2V] or null
+    float*          centre;     // [N, stride] out
+    float*          radius;     // [N, stride] out (raw: before Softplus)
+    int64_t         N;
+    int64_t         stride;     // elements between output rows
+    int32_t         D;
+    int32_t         V;
+    int32_t         row_tiles;  // ceil(N / kHeadTileRows)
+};
+hipError_t launch_interhead(const HeadArgs& args, hipStream_t stream, hipEvent_t ev_start = nullptr,
+                            hipEvent_t ev_stop = nullptr);
+
 }  // namespace ciar
