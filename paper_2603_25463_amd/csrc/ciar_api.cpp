@@ -690,8 +690,9 @@ int head_logits(const void* hidden, const void* weight, const float* bias, int32
 {
     ciar::HeadArgs h;
     if (int rc = head_args(hidden, weight, bias, hidden_dim, N, params, &h)) return rc;
-    if (!centre || !radius) return fail(CIAR_EINVAL, "centre or radius is NULL");
     if (N == 0) return CIAR_OK;
+    if (!centre || !radius) return fail(CIAR_EINVAL, "centre or radius is NULL");
+    if (!aligned16(centre) || !aligned16(radius)) return fail(CIAR_EALIGN, "centre or radius is not 16-byte aligned");
     h.centre = centre;
     h.radius = radius;
     const hipError_t e = ciar::launch_interhead(h, static_cast<hipStream_t>(hip_stream), ev_start, ev_stop);

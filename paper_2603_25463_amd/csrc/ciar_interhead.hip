@@ -11,95 +11,205 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t w32x4 __attribute__((ext_vector_type(4)));
 
-// Workgroup tile 128 x 128 x 64, four waves in a 2 x 2 grid, each wave 64 x 64 = 2 x 2 MFMA blocks of 32 x 32.
-constexpr int BM = kHeadTileRows, BN = kHeadTileCols, BK = kHeadTileDepth;
-constexpr int PITCH = BK + 8;          // bf16 per LDS row: 144 B, keeps 16-byte alignment and staggers the banks
-static_assert(BM == 128 && BN == 128 && BK == 64, "the lane mappings below are written for 128 x 128 x 64");
+// Workgroup tile (64 MB) x (64 NB) x 64 with four waves in a 2 x 2 grid, each wave (32 MB) x (32 NB) = MB x NB MFMA
+// blocks of 32 x 32.  MB = NB = 4 (256 x 256, a wave 128 x 128) is the shape for real vocabularies: a wave then
+// reads 8 operand vectors from LDS for 16 matrix instructions, half the LDS traffic per instruction of the
+// 128 x 128 tile (MB = NB = 2), which serves vocabularies that are not a multiple of 256 and very small batches.
+//
+// Operand tiles go from memory straight into LDS (global_load_lds_dwordx4: no staging registers, and a request
+// has the whole multiplication of the previous tile to arrive in).  One such instruction writes the 64 lanes'
+// 16-byte chunks to 1 KiB of consecutive LDS, i.e. eight tile rows of 64 bf16 without padding, so the chunks of a
+// row are stored in swizzled order instead: chunk q of row r sits at position q ^ (r % 8).  The lanes choose which
+// chunk of their row they request accordingly (the eight lanes of a row still cover its 128 bytes), and the 32
+// rows that one operand read touches at the same k fall on different banks.
+constexpr int BK = kHeadTileDepth;
+constexpr int ROWB = BK * 2;            // bytes of a tile row in LDS
+static_assert(BK == 64, "a tile row is eight 16-byte chunks");
+using gptr = const __attribute__((address_space(1))) void*;
+using lptr = __attribute__((address_space(3))) void*;
 
 // Lane layout of v_mfma_f32_32x32x16_bf16: lane l supplies row (A) / column (B) l % 32 with the eight consecutive k
 // 8 (l / 32) .. + 7; accumulator register v of lane l is the element (8 (v / 4) + 4 (l / 32) + v % 4, l % 32).
+template <int MB, int NB>
 __global__ __launch_bounds__(256) void interhead_gemm_kernel(const HeadArgs A)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t sA[BM * PITCH];
-    __shared__ __attribute__((aligned(16))) uint16_t sB[BN * PITCH];
+    constexpr int BM = 64 * MB, BN = 64 * NB;
+    constexpr int CA = BM / 32, CB = BN / 32;                      // load instructions per wave and tile (8 rows each)
+    constexpr int BUF = (BM + BN) * ROWB;                          // bytes of one buffer: the A tile, then the B tile
+    extern __shared__ __attribute__((aligned(1024))) char lds[];   // two buffers
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    // consecutive workgroups take the row tiles of one column tile: the weight tile is fetched from HBM once
-    const int rt = (int)(blockIdx.x % A.row_tiles), ct = (int)(blockIdx.x / A.row_tiles);
+    // Workgroups are handed to the eight XCDs in turn (workgroup b runs on XCD b % 8), and every XCD has an L2 of its
+    // own.  So the tiles are dealt by XCD: XCD x takes the column tiles x, x + 8, ..., and its consecutive
+    // workgroups walk the row tiles of one column tile.  The workgroups that are resident on an XCD together then
+    // share their weight tile (and the few row tiles of hidden states) in that L2.
+    int rt, ct;
+    if (A.col_tiles % 8 == 0) {
+        const int x = (int)(blockIdx.x & 7), local = (int)(blockIdx.x >> 3);
+        rt = local % A.row_tiles;
+        ct = (local / A.row_tiles) * 8 + x;
+    } else {
+        rt = (int)(blockIdx.x % A.row_tiles);
+        ct = (int)(blockIdx.x / A.row_tiles);
+    }
     const int64_t m0 = (int64_t)rt * BM;
     const int n0 = ct * BN;                                        // column of the 2V-wide output
 
-    // staging: a 128 x 64 bf16 tile is 1024 chunks of 16 bytes, four per lane; chunk c = tid + 256 u covers row
-    // c / 8, k 8 (c % 8) .. + 7 (eight lanes read 128 consecutive bytes of a row)
-    w32x4 ra[4], rb[4];
-    auto fetch = [&](int k0) {
+    // Requests: instruction u of wave w covers the tile rows 8 (w + 4 u) .. + 7; lane l asks for row + l / 8 and,
+    // of that row, the chunk that belongs at position l % 8.  Addresses: a uniform base per tile plus one 32-bit
+    // byte offset per instruction (rows past the end of the batch repeat the last row; they are never stored).
+    uint32_t oa[CA], ob[CB];
+    const int rl = lane >> 3, chunk = (lane & 7) ^ rl;
+    const int64_t last = A.N - 1 - m0;                             // >= 0: the tile starts inside the batch
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int c = tid + 256 * u, r = c >> 3, kc = c & 7;
-            int64_t hr = m0 + r;
-            if (hr >= A.N) hr = A.N - 1;                           // rows past the end repeat the last one; never stored
-            ra[u] = *reinterpret_cast<const w32x4*>(A.hidden + hr * A.D + k0 + kc * 8);
-            rb[u] = *reinterpret_cast<const w32x4*>(A.weight + (int64_t)(n0 + r) * A.D + k0 + kc * 8);
-        }
-    };
-    auto stash = [&]() {
+    for (int u = 0; u < CA; ++u) {
+        const int row = 8 * (wave + 4 * u) + rl;
+        oa[u] = (uint32_t)(row <= last ? row : (int)last) * (uint32_t)A.D * 2u + (uint32_t)chunk * 16u;
+    }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int c = tid + 256 * u, r = c >> 3, kc = c & 7;
-            *reinterpret_cast<w32x4*>(&sA[r * PITCH + kc * 8]) = ra[u];
-            *reinterpret_cast<w32x4*>(&sB[r * PITCH + kc * 8]) = rb[u];
-        }
+    for (int u = 0; u < CB; ++u) ob[u] = (uint32_t)(8 * (wave + 4 * u) + rl) * (uint32_t)A.D * 2u + (uint32_t)chunk * 16u;
+    const char* const baseA = reinterpret_cast<const char*>(A.hidden + m0 * A.D);
+    const char* const baseB = reinterpret_cast<const char*>(A.weight + (int64_t)n0 * A.D);
+    auto request = [&](int k0, int buf) {
+        char* const dA = lds + buf * BUF + wave * 8 * ROWB;
+        char* const dB = dA + BM * ROWB;
+#pragma unroll
+        for (int u = 0; u < CA; ++u)
+            __builtin_amdgcn_global_load_lds((gptr)(baseA + k0 * 2 + oa[u]), (lptr)(dA + u * 32 * ROWB), 16, 0, 0);
+#pragma unroll
+        for (int u = 0; u < CB; ++u)
+            __builtin_amdgcn_global_load_lds((gptr)(baseB + k0 * 2 + ob[u]), (lptr)(dB + u * 32 * ROWB), 16, 0, 0);
     };
 
-    f32x16 acc[2][2];
+    f32x16 acc[MB][NB];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NB; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int lrow = lane & 31, lk = (lane >> 5) * 8;
-    fetch(0);
-    for (int k0 = 0; k0 < A.D; k0 += BK) {
-        stash();
-        __syncthreads();
-        if (k0 + BK < A.D) fetch(k0 + BK);                         // lands while this tile is multiplied
+    // Operand reads: lane l reads row l % 32 of each 32-row block; its chunk in slice sl (k 16 sl .. + 15) is
+    // 2 sl + l / 32, stored at position (2 sl) ^ sw with sw = (l / 32) ^ (row % 8).
+    const int lrow = lane & 31, sw = (lane >> 5) ^ (lrow & 7);
+    const int offA = (wm * 32 * MB + lrow) * ROWB, offB = BM * ROWB + (wn * 32 * NB + lrow) * ROWB;
+
+    // Pipeline over the k tiles, one barrier per tile.  A tile is multiplied in four 16-deep slices; the operands
+    // of a slice are read from LDS during the matrix instructions of the slice before (two register sets), early in
+    // it, so that a slice never starts by waiting for LDS.  The next tile is requested into the other buffer at the
+    // start of a tile and awaited (own requests, then the barrier) after the third slice; the fourth slice already
+    // reads the first operands of the next tile.  The other buffer's last reads (for this slice pattern: issued
+    // during the third slice of the previous tile) precede the previous barrier, so the requests may overwrite it.
+    // Past the last tile the request repeats it, so no branch splits the loop body.
+    static_assert(MB == NB && BK == 64, "the slice pattern below is written for square wave tiles, four slices");
+    const int klast = A.D - BK;
+    bf16x8 a[2][MB], b[2][NB];
+    auto operands = [&](const char* tile, int sl, int set) {
+        const int pos = ((2 * sl) ^ sw) * 16;
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 16) {
-            bf16x8 a[2], b[2];
+        for (int i = 0; i < MB; ++i) a[set][i] = *reinterpret_cast<const bf16x8*>(tile + offA + i * 32 * ROWB + pos);
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
-                a[i] = *reinterpret_cast<const bf16x8*>(&sA[(wm * 64 + i * 32 + lrow) * PITCH + kk + lk]);
+        for (int j = 0; j < NB; ++j) b[set][j] = *reinterpret_cast<const bf16x8*>(tile + offB + j * 32 * ROWB + pos);
+    };
+    auto multiply = [&](int set) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-                b[j] = *reinterpret_cast<const bf16x8*>(&sB[(wn * 64 + j * 32 + lrow) * PITCH + kk + lk]);
+        for (int i = 0; i < MB; ++i)
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int j = 0; j < NB; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[set][i], b[set][j], acc[i][j], 0, 0, 0);
+    };
+    // one LDS read after each of the first MB + NB matrix instructions of a slice, the rest of the slice without
+    auto pattern = [&]() {
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int g = 0; g < MB + NB; ++g) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // a matrix instruction
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // an LDS read
         }
-        __syncthreads();                                           // the tile is overwritten next
+        __builtin_amdgcn_sched_group_barrier(0x008, MB * NB - (MB + NB), 0);
+    };
+    request(0, 0);
+    __syncthreads();                                               // waits for the requests, then for the waves
+    operands(lds, 0, 0);
+    int buf = 0;
+    for (int k0 = 0; k0 < A.D; k0 += BK, buf ^= 1) {
+        const char* const cur = lds + buf * BUF;
+        const char* const nxt = lds + (buf ^ 1) * BUF;
+        request(k0 + BK < klast ? k0 + BK : klast, buf ^ 1);
+        __builtin_amdgcn_sched_barrier(0);
+        operands(cur, 1, 1);
+        multiply(0);
+        pattern();
+        operands(cur, 2, 0);
+        multiply(1);
+        pattern();
+        operands(cur, 3, 1);
+        multiply(0);
+        pattern();
+        __syncthreads();                                           // the next tile has arrived in every wave's part
+        operands(nxt, 0, 0);
+        multiply(1);
+        pattern();
     }
 
-    // epilogue: bias, then the tile's half of the head (a tile never straddles V: V is a multiple of BN)
+    // Epilogue: bias, then the tile's half of the head (a tile never straddles V: V is a multiple of BN).  The
+    // accumulators hold columns across lanes and rows across registers; stored as they are, an instruction would
+    // write 128-byte pieces of two rows.  Each wave instead passes its block through LDS, 32 rows at a time (the
+    // operand buffers are free by now), and writes whole row segments of 32 NB floats: 16 bytes per lane.
+    __syncthreads();                                               // every wave has read its last operands
+    constexpr int WCOLS = 32 * NB, SP = WCOLS + 4;                 // staging pitch in floats: rows 4 apart differ in bank
+    float* const stage = reinterpret_cast<float*>(lds) + wave * 32 * SP;
     float* out = n0 < A.V ? A.centre : A.radius;
-    const int cbase = (n0 < A.V ? n0 : n0 - A.V) + wn * 64 + lrow;
+    const int cwave = (n0 < A.V ? n0 : n0 - A.V) + wn * WCOLS;     // first output column of the wave's block
+    float bj[NB];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const float bj = A.bias ? A.bias[n0 + wn * 64 + j * 32 + lrow] : 0.f;
+    for (int j = 0; j < NB; ++j) bj[j] = A.bias ? A.bias[n0 + wn * WCOLS + j * 32 + lrow] : 0.f;
+    constexpr int LPR = WCOLS / 4, RPI = 64 / LPR;                 // lanes per row segment, rows per store instruction
+    const int srow = lane / LPR, scol = (lane % LPR) * 4;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MB; ++i) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t row = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                if (row < A.N) out[row * A.stride + cbase + j * 32] = acc[i][j][v] + bj;
-            }
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                stage[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * SP + j * 32 + lrow] = acc[i][j][v] + bj[j];
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < 32 / RPI; ++t) {
+            const int r = t * RPI + srow;
+            const int64_t row = m0 + wm * 32 * MB + i * 32 + r;
+            const f32x4 val = *reinterpret_cast<const f32x4*>(&stage[r * SP + scol]);
+            if (row < A.N) *reinterpret_cast<f32x4*>(&out[row * A.stride + cwave + scol]) = val;
+        }
+        __syncthreads();
     }
+}
+
+template <int MB, int NB>
+hipError_t launch_tile(const HeadArgs& a, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop)
+{
+    constexpr int BM = 64 * MB, BN = 64 * NB;
+    constexpr size_t lds_bytes = (size_t)2 * (BM + BN) * ROWB;                     // 64 KB or 128 KB of the 160 KB
+    static_assert(lds_bytes <= 160 * 1024, "tile does not fit the LDS of a compute unit");
+    if (lds_bytes > 64 * 1024) {
+        // more than the default limit for dynamic LDS: raise it for this kernel (a per-function attribute; cheap)
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&interhead_gemm_kernel<MB, NB>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+    }
+    HeadArgs args = a;
+    args.row_tiles = (int32_t)((a.N + BM - 1) / BM);
+    args.col_tiles = 2 * a.V / BN;
+    const unsigned grid = (unsigned)args.row_tiles * (unsigned)args.col_tiles;
+    if (ev_start && ev_stop)
+        hipExtLaunchKernelGGL((interhead_gemm_kernel<MB, NB>), dim3(grid), dim3(256), lds_bytes, stream, ev_start,
+                              ev_stop, 0, args);
+    else
+        hipLaunchKernelGGL((interhead_gemm_kernel<MB, NB>), dim3(grid), dim3(256), lds_bytes, stream, args);
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -107,12 +217,9 @@ __global__ __launch_bounds__(256) void interhead_gemm_kernel(const HeadArgs A)
 hipError_t launch_interhead(const HeadArgs& args, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     if (args.N <= 0) return hipSuccess;
-    const unsigned grid = (unsigned)args.row_tiles * (unsigned)(2 * args.V / BN);
-    if (ev_start && ev_stop)
-        hipExtLaunchKernelGGL(interhead_gemm_kernel, dim3(grid), dim3(256), 0, stream, ev_start, ev_stop, 0, args);
-    else
-        hipLaunchKernelGGL(interhead_gemm_kernel, dim3(grid), dim3(256), 0, stream, args);
-    return hipGetLastError();
+    static_assert(kHeadTileCols == 128, "the small tile is the one the C ABI's shape check is written for");
+    if (args.V % 256 == 0 && args.N > 128) return launch_tile<4, 4>(args, stream, ev_start, ev_stop);
+    return launch_tile<2, 2>(args, stream, ev_start, ev_stop);
 }
 
 }  // namespace ciar

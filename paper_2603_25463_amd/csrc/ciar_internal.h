@@ -152,7 +152,8 @@ struct HeadArgs {
     int64_t         stride;     // elements between output rows
     int32_t         D;
     int32_t         V;
-    int32_t         row_tiles;  // ceil(N / kHeadTileRows)
+    int32_t         row_tiles;  // set by the launcher: tiles of the chosen shape along N
+    int32_t         col_tiles;  // and along the 2V output columns
 };
 hipError_t launch_interhead(const HeadArgs& args, hipStream_t stream, hipEvent_t ev_start = nullptr,
                             hipEvent_t ev_stop = nullptr);
