@@ -22,9 +22,11 @@ typedef uint32_t w32x4 __attribute__((ext_vector_type(4)));
 // Operand tiles go from memory straight into LDS (global_load_lds_dwordx4: no staging registers, and a request
 // has the whole multiplication of the previous tile to arrive in).  One such instruction writes the 64 lanes'
 // 16-byte chunks to 1 KiB of consecutive LDS, i.e. eight tile rows of 64 bf16 without padding, so the chunks of a
-// row are stored in swizzled order instead: chunk q of row r sits at position q ^ (r % 8).  The lanes choose which
+// row are stored in swizzled order instead: chunk q of row r sits at position q ^ ((r / 2) % 8).  The lanes choose which
 // chunk of their row they request accordingly (the eight lanes of a row still cover its 128 bytes), and the 32
-// rows that one operand read touches at the same k fall on different banks.
+// rows that one operand read touches at the same k are spread over the banks: a row is 32 banks wide, so the
+// even rows share one half of the 64 banks and the odd rows the other, and any 16 consecutive rows (eight of
+// each kind, with eight different positions) cover every bank once.
 constexpr int BK = kHeadTileDepth;
 constexpr int ROWB = BK * 2;            // bytes of a tile row in LDS
 static_assert(BK == 64, "a tile row is eight 16-byte chunks");
@@ -63,7 +65,7 @@ __global__ __launch_bounds__(256) void interhead_gemm_kernel(const HeadArgs A)
     // of that row, the chunk that belongs at position l % 8.  Addresses: a uniform base per tile plus one 32-bit
     // byte offset per instruction (rows past the end of the batch repeat the last row; they are never stored).
     uint32_t oa[CA], ob[CB];
-    const int rl = lane >> 3, chunk = (lane & 7) ^ rl;
+    const int rl = lane >> 3, chunk = (lane & 7) ^ ((4 * (wave & 1)) | (rl >> 1));   // row = 8 (w + 4 u) + rl: (row / 2) % 8
     const int64_t last = A.N - 1 - m0;                             // >= 0: the tile starts inside the batch
 #pragma unroll
     for (int u = 0; u < CA; ++u) {
@@ -94,17 +96,18 @@ __global__ __launch_bounds__(256) void interhead_gemm_kernel(const HeadArgs A)
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     // Operand reads: lane l reads row l % 32 of each 32-row block; its chunk in slice sl (k 16 sl .. + 15) is
-    // 2 sl + l / 32, stored at position (2 sl) ^ sw with sw = (l / 32) ^ (row % 8).
-    const int lrow = lane & 31, sw = (lane >> 5) ^ (lrow & 7);
+    // 2 sl + l / 32, stored at position (2 sl) ^ sw with sw = (l / 32) ^ ((row / 2) % 8).
+    const int lrow = lane & 31, sw = (lane >> 5) ^ ((lrow >> 1) & 7);
     const int offA = (wm * 32 * MB + lrow) * ROWB, offB = BM * ROWB + (wn * 32 * NB + lrow) * ROWB;
 
     // Pipeline over the k tiles, one barrier per tile.  A tile is multiplied in four 16-deep slices; the operands
     // of a slice are read from LDS during the matrix instructions of the slice before (two register sets), early in
-    // it, so that a slice never starts by waiting for LDS.  The next tile is requested into the other buffer at the
-    // start of a tile and awaited (own requests, then the barrier) after the third slice; the fourth slice already
-    // reads the first operands of the next tile.  The other buffer's last reads (for this slice pattern: issued
-    // during the third slice of the previous tile) precede the previous barrier, so the requests may overwrite it.
-    // Past the last tile the request repeats it, so no branch splits the loop body.
+    // it, so that a slice never starts by waiting for LDS.  The barrier stands after the third slice: by then every
+    // wave holds its last operands of the current tile in registers, so behind the barrier the tile's buffer is
+    // free and the tile after the next is requested into it at once, a whole tile's multiplication ahead of its
+    // use; the fourth slice already reads the first operands of the next tile, whose arrival the barrier has
+    // awaited (own requests, then the other waves).  Past the last tile the requests repeat it, so no branch
+    // splits the loop body; the barrier before the epilogue awaits the last of them.
     static_assert(MB == NB && BK == 64, "the slice pattern below is written for square wave tiles, four slices");
     const int klast = A.D - BK;
     bf16x8 a[2][MB], b[2][NB];
@@ -132,13 +135,14 @@ __global__ __launch_bounds__(256) void interhead_gemm_kernel(const HeadArgs A)
         __builtin_amdgcn_sched_group_barrier(0x008, MB * NB - (MB + NB), 0);
     };
     request(0, 0);
+    request(BK < klast ? BK : klast, 1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();                                               // waits for the requests, then for the waves
     operands(lds, 0, 0);
     int buf = 0;
     for (int k0 = 0; k0 < A.D; k0 += BK, buf ^= 1) {
         const char* const cur = lds + buf * BUF;
         const char* const nxt = lds + (buf ^ 1) * BUF;
-        request(k0 + BK < klast ? k0 + BK : klast, buf ^ 1);
         __builtin_amdgcn_sched_barrier(0);
         operands(cur, 1, 1);
         multiply(0);
@@ -149,7 +153,11 @@ __global__ __launch_bounds__(256) void interhead_gemm_kernel(const HeadArgs A)
         operands(cur, 3, 1);
         multiply(0);
         pattern();
-        __syncthreads();                                           // the next tile has arrived in every wave's part
+        // A wave's own requests are counted by vmcnt; the barrier's fence does not wait for them (they are loads),
+        // so the wait is written out: only then may the other waves read what this wave has requested.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();                                           // the next tile has arrived in every wave's part,
+        request(k0 + 2 * BK < klast ? k0 + 2 * BK : klast, buf);   // and this tile's buffer is free for the one after
         operands(nxt, 0, 0);
         multiply(1);
         pattern();
@@ -159,6 +167,7 @@ __global__ __launch_bounds__(256) void interhead_gemm_kernel(const HeadArgs A)
     // accumulators hold columns across lanes and rows across registers; stored as they are, an instruction would
     // write 128-byte pieces of two rows.  Each wave instead passes its block through LDS, 32 rows at a time (the
     // operand buffers are free by now), and writes whole row segments of 32 NB floats: 16 bytes per lane.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                // the last (repeated) requests have landed
     __syncthreads();                                               // every wave has read its last operands
     constexpr int WCOLS = 32 * NB, SP = WCOLS + 4;                 // staging pitch in floats: rows 4 apart differ in bank
     float* const stage = reinterpret_cast<float*>(lds) + wave * 32 * SP;
