@@ -235,3 +235,42 @@ def test_width_polynomial_range_shrinks_with_the_radius_and_ends(L):
     assert _width_poly(L, radius_scale=50.0, radius_max=1.0) == _width_poly(L, radius_scale=1.0)
     p = _params(L)
     assert L.ciar_width_polynomial(ctypes.byref(p), None, None) == -1    # CIAR_EINVAL
+
+
+def test_interhead_argument_errors_and_workspace(L):
+    """The Interval Head entry points: every argument error returns before any launch; the workspace is the two
+    fp32 logit tensors plus the quantifier's."""
+    from paper_2603_25463_amd.binding import last_error
+    EINVAL, EALIGN, EWORK, EUNSUP = -1, -2, -3, -4
+    p = _params(L)                                                  # V = 1024, stride 1024, fp32
+    a = ctypes.byref(p)
+
+    def logits(params, D=128, N=4, hidden=FAKE, weight=FAKE + 4096, centre=FAKE + 8192, radius=FAKE + 12288):
+        return L.ciar_interhead_logits(hidden, weight, None, D, N, ctypes.byref(params), centre, radius, None)
+
+    def quantify(params, D=128, N=4, out=FAKE + 8192, ws=FAKE + 16384, wsb=1 << 30):
+        return L.ciar_interhead_quantify(FAKE, FAKE + 4096, None, D, None, N, ctypes.byref(params), out, None, None, None,
+                                         None, None, None, ws, wsb, None)
+
+    assert logits(_params(L, dtype=1)) == EUNSUP and "fp32" in last_error()
+    assert logits(p, D=96) == EUNSUP and "hidden_dim" in last_error()
+    assert logits(p, D=0) == EUNSUP
+    assert logits(_params(L, vocab=1000, row_stride=1000)) == EUNSUP and "multiple of 128" in last_error()
+    assert logits(p, N=-1) == EINVAL
+    assert logits(p, hidden=None) == EINVAL and "hidden" in last_error()
+    assert logits(p, weight=FAKE + 4) == EALIGN
+    assert logits(p, centre=None) == EINVAL
+    assert logits(p, radius=FAKE + 12292) == EALIGN
+    assert logits(p, N=0, hidden=None, weight=None, centre=None, radius=None) == 0     # an empty batch reads nothing
+    assert quantify(p, out=None) == EINVAL and "output" in last_error()
+    assert quantify(p, ws=None) == EWORK
+    assert quantify(p, wsb=1024) == EWORK and "needed" in last_error()
+    assert quantify(p, D=100) == EUNSUP
+    assert quantify(p, N=0, ws=None, wsb=0) == 0
+    f = L.ciar_interhead_workspace_bytes
+    assert f(0, a) == 0
+    for N in (1, 130, 2048):
+        assert f(N, a) == 2 * ((N * 1024 * 4 + 255) // 256 * 256) + L.ciar_workspace_bytes(N, a)
+    # the timed form needs both events
+    assert L.ciar_interhead_logits_timed(FAKE, FAKE + 4096, None, 128, 4, a, FAKE + 8192, FAKE + 12288, None, None,
+                                         None) == EINVAL
