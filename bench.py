@@ -16,6 +16,10 @@ that the kernel's own dispatch records on the launch stream at its start and end
 (ciar_stream_rows_timed); `cpu_baseline` is the fp64 oracle timed on the host cores on the same batch.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--no-cpu-baseline]
+
+Other lines of the same form, beyond the headline: --mode quantify | verify, --radius-tensor, --heads H,
+--interdro, and --interhead [--hidden D] (the Interval Head's contraction on the matrix cores, then the
+quantifier: the roofline object is then the contraction's, against the dense bf16 peak).
 """
 from __future__ import annotations
 
