@@ -204,10 +204,15 @@ hipError_t launch_tile(const HeadArgs& a, hipStream_t stream, hipEvent_t ev_star
     constexpr size_t lds_bytes = (size_t)2 * (BM + BN) * ROWB;                     // 64 KB or 128 KB of the 160 KB
     static_assert(lds_bytes <= 160 * 1024, "tile does not fit the LDS of a compute unit");
     if (lds_bytes > 64 * 1024) {
-        // more than the default limit for dynamic LDS: raise it for this kernel (a per-function attribute; cheap)
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&interhead_gemm_kernel<MB, NB>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return e;
+        // more than the default limit for dynamic LDS: raised for this kernel once per process (an attribute of
+        // the function; setting it twice from two threads is harmless)
+        static bool raised = false;
+        if (!raised) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&interhead_gemm_kernel<MB, NB>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
     }
     HeadArgs args = a;
     args.row_tiles = (int32_t)((a.N + BM - 1) / BM);
