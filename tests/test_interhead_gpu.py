@@ -119,6 +119,29 @@ def test_interhead_quantify(ciar, oracle, N, D, V, stride):
         assert torch.equal(got[k], again[k]), k
 
 
+def test_interhead_quantify_at_the_benchmark_shape(ciar, oracle):
+    """2048 positions, V = 16384, D = 1280 (the shape bench.py --interhead times, 256 x 256 tiles over the whole
+    chip): the GPU runs every row, the oracle every eighth one."""
+    N, D, V = 2048, 1280, 16384
+    h, w, b, ids = _case(N, D, V, seed=2048)
+    say(f"[interhead quantify, benchmark shape] N={N} D={D} V={V}")
+    P = ciar.Params(radius_scale=1.0, tau=0.3)
+    got = ciar.interhead_quantify(h.cuda(), w.cuda(), b.cuda(), ids.cuda(), P)
+    torch.cuda.synchronize()
+    rows = np.arange(0, N, 8)
+    hs = h[rows].contiguous()
+    eps = 2.0 ** -24 * float((hs.double().abs() @ w.double().abs().T).max())
+    rtol = 1e-5 + 4 * eps
+    ref = oracle.interhead_quantify(hs, w, b.numpy(), ids.numpy()[rows], oracle.Params(kappa=1.0, tau=0.3))
+    sub = {k: v[torch.as_tensor(rows, device=v.device)] for k, v in got.items()}
+    worst = parity.check_floats(sub, ref, rtol=rtol)
+    say(f"    eps={eps:.2e} rtol={rtol:.2e} worst/bound={worst}")
+    tau = float(np.float32(0.3))
+    diff = np.nonzero(sub["flags"].cpu().numpy() != ref["flags"])[0]
+    for i in diff:
+        assert abs(ref["score"][i] - tau) < 1e-6 + rtol * ref["score"][i], (i, ref["score"][i])
+
+
 def test_interhead_rejects_unsupported_shapes(ciar):
     h = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(ciar.CiarError, match="CIAR_EUNSUPPORTED"):
