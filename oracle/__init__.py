@@ -4,8 +4,13 @@ Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``b
 import this package.  It shares nothing with the HIP library: it compiles its own C file with
 gcc and talks to it through numpy arrays.
 
-Logit arrays are ``numpy.float32`` (dtype code 0) or ``numpy.uint16`` holding raw bfloat16 bits
-(dtype code 1), shape [N, row_stride] or [N, V], C-contiguous.
+Logit arrays are ``numpy.float32`` (dtype code 0), ``numpy.uint16`` holding raw bfloat16 bits
+(dtype code 1) or ``numpy.float64`` (dtype code 2: logits that the oracle itself produced in double
+precision), shape [N, row_stride] or [N, V], C-contiguous.
+
+The Interval Head's two linear maps (``interhead_logits``: Sec. 3.2.1, "Interval Head Architecture") are
+numpy's fp64 matrix product of the exactly widened bf16 operands plus the bias; ``interhead_quantify`` feeds
+those fp64 logits to the quantifier.  Pins: ``tests/test_interhead_oracle_pins.py``.
 """
 from __future__ import annotations
 

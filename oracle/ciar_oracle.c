@@ -29,6 +29,10 @@
  * leg of bench.py may call this file; the product path never does.  It shares no code with
  * the HIP kernels.
  *
+ * The Interval Head's two linear maps that produce the centre and raw-radius logits (Sec. 3.2.1, "Interval Head
+ * Architecture") are evaluated by the Python front end (numpy's fp64 matrix product); their fp64 logits enter the
+ * functions here through the float64 logit type.
+ *
  * Parity pins: every function here is pinned by tests/test_oracle_pins.py (library softmax,
  * logistic sigmoid for V = 2, closed forms for uniform and one-hot rows, the appendix's
  * claims and propositions, brute-force enumeration of the acceptance law for V <= 8).
