@@ -54,6 +54,7 @@ def _logit_bound(h, w, ref):
 SHAPES = [  # N, D, V, row_stride
     (1, 64, 128, 128), (130, 64, 128, 128), (127, 192, 256, 260), (257, 128, 384, 384), (300, 1280, 1024, 1024),
     (128, 4096, 128, 128),
+    (200, 64, 256, 256), (129, 128, 512, 516), (385, 192, 256, 256),     # the large tile with one, two and three k tiles
 ]
 
 
