@@ -12,7 +12,6 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t w32x4 __attribute__((ext_vector_type(4)));
 
 // Workgroup tile (64 MB) x (64 NB) x 64 with four waves in a 2 x 2 grid, each wave (32 MB) x (32 NB) = MB x NB MFMA
 // blocks of 32 x 32.  MB = NB = 4 (256 x 256, a wave 128 x 128) is the shape for real vocabularies: a wave then
@@ -20,7 +19,7 @@ typedef uint32_t w32x4 __attribute__((ext_vector_type(4)));
 // 128 x 128 tile (MB = NB = 2), which serves vocabularies that are not a multiple of 256 and very small batches.
 //
 // Operand tiles go from memory straight into LDS (global_load_lds_dwordx4: no staging registers, and a request
-// has the whole multiplication of the previous tile to arrive in).  One such instruction writes the 64 lanes'
+// has a whole tile's multiplication to arrive in).  One such instruction writes the 64 lanes'
 // 16-byte chunks to 1 KiB of consecutive LDS, i.e. eight tile rows of 64 bf16 without padding, so the chunks of a
 // row are stored in swizzled order instead: chunk q of row r sits at position q ^ ((r / 2) % 8).  The lanes choose which
 // chunk of their row they request accordingly (the eight lanes of a row still cover its 128 bytes), and the 32
