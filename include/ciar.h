@@ -174,6 +174,28 @@ int ciar_quantify_verify(const void* draft_logits, const void* radius, const voi
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * ciar_quantify_verify for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, semantics, kernels and
+ * results as ciar_quantify_verify, without `workspace` / `workspace_bytes`: the per-row statistics, the list of
+ * rejected rows and the per-row results the caller did not ask for live in a buffer that is part of the library's
+ * device image (ciar_workspace_bytes(CIAR_STATIC_MAX_ROWS) = 3.03 MiB on every GPU the library runs on, held
+ * until the process ends).  The call allocates and frees nothing.
+ *   - N > CIAR_STATIC_MAX_ROWS returns CIAR_EWORKSPACE and launches nothing.
+ *   - Every call on a GPU uses that GPU's one buffer: calls that overlap in time on one GPU (different streams,
+ *     different host threads) race on it.  Calls on one stream, or otherwise ordered, are safe; the buffer needs
+ *     no clearing between calls (the one word that must start at zero is cleared by the first kernel of a call).
+ *   - The first call on a device looks the buffer's address up (hipGetSymbolAddress) with that device current.
+ */
+#define CIAR_STATIC_MAX_ROWS 32768
+int ciar_quantify_verify_static(const void* draft_logits, const void* radius, const void* target_logits,
+                                const int32_t* draft_ids, const float* u_accept, const float* u_resample,
+                                int64_t N, const ciar_params* params,
+                                float* p_lo, float* p_mid, float* p_hi,
+                                float* omega, float* sigma, float* score, uint8_t* flags,
+                                uint8_t* accept, int32_t* row_resample_id,
+                                int32_t* accept_len, int32_t* resampled_id, void* hip_stream);
+
+/*
  * The two stages of the calls above, on their own, for callers that want to time them or to put
  * other work between them.  ciar_quantify, ciar_verify and ciar_quantify_verify are exactly
  * ciar_stream_rows followed by ciar_finish_rows (same kernels, same launch configuration).  Both take the

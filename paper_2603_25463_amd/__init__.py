@@ -5,10 +5,10 @@
 """
 from .binding import (DRO_LOSSES, DRO_TERMS, ENSEMBLE, VOTING, CiarError, Params, dense_intervals,
                       finish_rows, interdro_loss, interhead_logits, interhead_quantify, last_error, lib, quantify, quantify_multihead,
-                      quantify_verify, read_rows, stream_rows, verify, version, window_epilogue,
+                      quantify_verify, quantify_verify_static, read_rows, stream_rows, verify, version, window_epilogue,
                       workspace_bytes)
 
 __all__ = ["DRO_LOSSES", "DRO_TERMS", "ENSEMBLE", "VOTING", "CiarError", "Params", "dense_intervals",
            "finish_rows", "interdro_loss", "interhead_logits", "interhead_quantify", "last_error", "lib", "quantify", "quantify_multihead",
-           "quantify_verify", "read_rows", "stream_rows", "verify", "version", "window_epilogue",
+           "quantify_verify", "quantify_verify_static", "read_rows", "stream_rows", "verify", "version", "window_epilogue",
            "workspace_bytes"]

@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.ciar_verify.argtypes = [vp, vp, vp, vp, vp, i64, pp] + [vp] * 4 + [vp, sz, vp]
         L.ciar_quantify_verify.restype = ctypes.c_int
         L.ciar_quantify_verify.argtypes = [vp, vp, vp, vp, vp, vp, i64, pp] + [vp] * 11 + [vp, sz, vp]
+        L.ciar_quantify_verify_static.restype = ctypes.c_int
+        L.ciar_quantify_verify_static.argtypes = [vp, vp, vp, vp, vp, vp, i64, pp] + [vp] * 11 + [vp]
         L.ciar_stream_rows.restype = ctypes.c_int
         L.ciar_stream_rows.argtypes = [vp, vp, vp, vp, vp, vp, i64, pp] + [vp] * 11 + [vp, sz, vp]
         L.ciar_stream_rows_timed.restype = ctypes.c_int
@@ -254,6 +256,25 @@ def quantify_verify(draft, target, ids, u_accept, u_resample, params: Params, vo
         _ptr(o["score"]), _ptr(o["flags"]), _ptr(o["accept"]), _ptr(o["row_id"]), _ptr(o["accept_len"]),
         _ptr(o["resampled_id"]), _ptr(workspace), wsb, _stream(stream)))
     return o
+
+
+STATIC_MAX_ROWS = 32768
+
+
+def quantify_verify_static(draft, target, ids, u_accept, u_resample, params: Params, out: dict,
+                           vocab: int | None = None, stream=None, radius: torch.Tensor | None = None) -> dict:
+    """``ciar_quantify_verify_static``: the fused pass on the library's built-in scratch buffer.  Nothing is
+    allocated here either: ``out`` must carry every output tensor (names as ``quantify_verify``)."""
+    _need_cuda(draft, target, ids, u_accept, u_resample, radius)
+    _like_draft(target, draft, "target")
+    _like_draft(radius, draft, "radius")
+    cp = params.to_c(draft, vocab)
+    g = lambda k: _ptr(out.get(k))
+    _check(lib().ciar_quantify_verify_static(
+        _ptr(draft), _ptr(radius), _ptr(target), _ptr(ids), _ptr(u_accept), _ptr(u_resample), draft.shape[0],
+        ctypes.byref(cp), g("p_lo"), g("p_mid"), g("p_hi"), g("omega"), g("sigma"), g("score"), g("flags"),
+        g("accept"), g("row_id"), g("accept_len"), g("resampled_id"), _stream(stream)))
+    return out
 
 
 def _staged(entry, draft, target, ids, u_accept, u_resample, params: Params, workspace: torch.Tensor,

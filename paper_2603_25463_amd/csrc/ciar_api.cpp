@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 namespace {
 
@@ -319,6 +320,51 @@ int run_both(const Call& c, ciar::Mode mode)
 }
 
 }  // namespace
+
+// ---- the allocation-free variant of the fused call ------------------------------------------------------------
+//
+// The workspace of ciar_quantify_verify_static: one array per GPU the library runs on, held until the process ends.
+// The name below is a host-side stand-in for the device array: host code never passes it anywhere but to
+// hipGetSymbolAddress, and uses the address that call returns for the device that was current.
+namespace {
+
+constexpr int64_t kStaticRows = CIAR_STATIC_MAX_ROWS;
+constexpr size_t static_round(size_t x, size_t m) { return (x + m - 1) / m * m; }
+constexpr size_t kStaticBytes =
+    static_round(static_round((size_t)kStaticRows * sizeof(ciar::RowStats), 16) + 2 * static_round((size_t)kStaticRows * 4, 16) +
+                 16 + (size_t)kStaticRows, 256);
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// The address of `scratch` on the current device (asked once per device, with that device current).
+int static_scratch(void** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(CIAR_EUNSUPPORTED, "device ordinal %d is outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (!p) return fail(CIAR_EHIP, "hipGetSymbolAddress(scratch) returned a null address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return CIAR_OK;
+}
+
+}  // namespace
+
 
 extern "C" {
 
@@ -746,6 +792,28 @@ int ciar_interhead_quantify(const void* hidden, const void* weight, const float*
     // the quantifier reads the logits the contraction has just written, on the same stream
     return ciar_quantify(h.centre, h.radius, draft_ids, N, params, p_lo, p_mid, p_hi, omega, sigma, score, flags,
                          w + 2 * lb, workspace_bytes - 2 * lb, hip_stream);
+}
+
+
+int ciar_quantify_verify_static(const void* draft_logits, const void* radius, const void* target_logits,
+                                const int32_t* draft_ids, const float* u_accept, const float* u_resample, int64_t N,
+                                const ciar_params* params, float* p_lo, float* p_mid, float* p_hi, float* omega,
+                                float* sigma, float* score, uint8_t* flags, uint8_t* accept, int32_t* row_resample_id,
+                                int32_t* accept_len, int32_t* resampled_id, void* hip_stream)
+{
+    if (N > kStaticRows)
+        return fail(CIAR_EWORKSPACE, "N = %lld exceeds CIAR_STATIC_MAX_ROWS = %lld, the rows the built-in scratch "
+                    "buffer holds: use ciar_quantify_verify with a workspace of the caller's", (long long)N,
+                    (long long)kStaticRows);
+    void* ws = nullptr;
+    if (N > 0)
+        if (int rc = static_scratch(&ws)) return rc;
+    // Nothing in the buffer has to start at zero except the length of the list of rejected rows, which the
+    // streaming kernel itself clears; everything else is written before it is read.
+    const Call c{draft_logits, radius, target_logits, draft_ids, u_accept, u_resample, N, params, p_lo, p_mid, p_hi, omega,
+                 sigma, score, flags, accept, row_resample_id, accept_len, resampled_id, ws, kStaticBytes,
+                 static_cast<hipStream_t>(hip_stream)};
+    return run_both(c, ciar::Mode::Fused);
 }
 
 
