@@ -181,6 +181,7 @@ ciar::RowArgs base_args(const ciar_params* p, const Resolved& r, int64_t N)
         if (!(xm > 0.0)) xm = 0.0;
     }
     a.capless_xmax = xm;
+    a.precise_flat = 0;                                            // set by the callers that run the fp64 pass
     const WidthPolyFit& wf = width_poly(r.a, r.b);
     for (int j = 0; j < 4; ++j) a.wpoly[j] = wf.c[j];
     a.wpoly_x = wf.x;
@@ -293,8 +294,15 @@ int run_stream(const Call& c, ciar::Mode mode)
         if (e != hipSuccess) return hip_fail(e, "arg-max kernel launch");
         a.ids = a.reject_list;
     }
-    const hipError_t e = ciar::launch_stream(mode, c.params->dtype, a, true, c.stream, c.ev_start, c.ev_stop);
+    a.precise_flat = mode != ciar::Mode::Verify && ciar::needs_flat_pass(a) ? 1 : 0;
+    hipError_t e = ciar::launch_stream(mode, c.params->dtype, a, true, c.stream, c.ev_start, c.ev_stop);
     if (e != hipSuccess) return hip_fail(e, "streaming kernel launch");
+    if (a.precise_flat) {
+        // flat rows of a call whose widths are not small: their interval sums again, in fp64
+        const ciar::StreamPlan plan = ciar::plan_stream(mode, c.params->dtype, a);
+        e = ciar::launch_flatrows(c.params->dtype, a, plan.can_finish, c.stream);
+        if (e != hipSuccess) return hip_fail(e, "flat-row kernel launch");
+    }
     return CIAR_OK;
 }
 
@@ -625,9 +633,14 @@ int ciar_quantify_multihead(const void* draft_heads, const void* radius_heads, i
                 a.ids = a.reject_list;
                 a.ids_period = 0;
             }
+            a.precise_flat = ciar::needs_flat_pass(a) ? 1 : 0;
             hipError_t e = ciar::launch_stream(ciar::Mode::Quantify, params->dtype, a, true, stream);
             if (e != hipSuccess) return hip_fail(e, "streaming kernel launch");
             const ciar::StreamPlan plan = ciar::plan_stream(ciar::Mode::Quantify, params->dtype, a);
+            if (a.precise_flat) {
+                e = ciar::launch_flatrows(params->dtype, a, plan.can_finish, stream);
+                if (e != hipSuccess) return hip_fail(e, "flat-row kernel launch");
+            }
             e = ciar::launch_finish(ciar::Mode::Quantify, params->dtype, a, plan.can_finish, params->window, nullptr,
                                     nullptr, stream);
             if (e != hipSuccess) return hip_fail(e, "finishing kernel launch");

@@ -401,6 +401,8 @@ struct RowScore { double alpha_l, alpha_u, omega, sigma, score; };
 constexpr float kSumsFull = 0.f;         // all five sums
 constexpr float kSumsWidthOnly = 1.f;    // the caps are known to be inactive; only sum gw, sum gw^2 were accumulated
 constexpr float kSumsComplement = 2.f;   // caps inactive, every width above 1/2: q[1] = sum ec, q[3] = sum ec^2
+constexpr float kSumsDirect = 3.f;       // all five sums, of p^l_i and p^u_i - p^l_i themselves (no row factor)
+constexpr float kSumsFlatPending = 8.f;  // added to the above: a flat row that flatrow_kernel has still to redo
 
 // The sums arrive shifted: s = { sum (gl - kl), sum (gw - kw), sum (gl - kl)^2, sum (gw - kw)^2,
 // sum (gl - kl)(gw - kw) } over the V tokens of the row, where (kl, kw) are the values of one of the row's own
@@ -414,6 +416,7 @@ __device__ __forceinline__ RowScore finish_score(const double* s, double S, floa
     // p^l_i = Bc gl_i and p^u_i - p^l_i = Wc gw_i (tensor-radius mode: the per-token factors are already
     // inside gl and gw)
     const double V = (double)A.V;
+    if (mode >= kSumsFlatPending) mode -= kSumsFlatPending;        // marked, not (yet) redone: the sums are valid as they are
     if (mode == kSumsComplement) {
         // s[1], s[3]: sums of (ec_i - kw) and its square, ec_i = 1 - delta_i:  Omega = V - sum ec,
         // Var(delta) = Var(ec), the latter taken among the small ec_i themselves instead of among numbers that
@@ -426,7 +429,8 @@ __device__ __forceinline__ RowScore finish_score(const double* s, double S, floa
         return o;
     }
     const bool capless = mode == kSumsWidthOnly;
-    const double Bc = (A.radius ? 1.0 : A.b) / S, Wc = (A.radius ? 1.0 : A.a - A.b) / S;
+    const bool direct = mode == kSumsDirect;
+    const double Bc = direct ? 1.0 : (A.radius ? 1.0 : A.b) / S, Wc = direct ? 1.0 : (A.radius ? 1.0 : A.a - A.b) / S;
     const double sum_gl = s[0] + V * kl, sum_gw = s[1] + V * kw;
     // S_l <= 1 <= S_u holds for every radius (p^l_i <= x_i <= p^u_i token by token); the computed sums carry ~1e-7
     // of fp32 token arithmetic and may land on the wrong side of 1 for a one-hot row, which a cap of exactly 1

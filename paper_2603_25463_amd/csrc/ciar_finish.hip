@@ -236,6 +236,93 @@ __global__ __launch_bounds__(THREADS) void resample_kernel(const RowArgs A, cons
     }
 }
 
+// ---- flat rows in fp64 ------------------------------------------------------------------------------------------
+
+// The interval sums of the rows that the streaming kernel has marked as flat (RowStats::mode + kSumsFlatPending;
+// see needs_flat_pass), redone in fp64 from the logits: e_i = exp(c_i - max c) and the radii with fp64 library
+// functions, the InterFuse bounds (App. "Proof of Interval Validity") as they are defined, the five sums about the
+// values of the row's first token.  Lane t of a workgroup looks at row 256 b + t; the marked ones are then taken one
+// after another by the whole workgroup (they are rare: rows of nearly equal logits).  With `finish` the row's
+// quantify outputs are written again as well (launches whose streaming kernel finishes its rows).
+template <typename T>
+__global__ __launch_bounds__(256) void flatrow_kernel(const RowArgs A, const int finish)
+{
+    __shared__ int sm_list[256];
+    __shared__ int sm_count;
+    __shared__ double sm_red[5][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int V = A.V;
+    if (tid == 0) sm_count = 0;
+    __syncthreads();
+    const int64_t mine = (int64_t)blockIdx.x * 256 + tid;
+    if (mine < A.N && A.stats[mine].mode >= kSumsFlatPending) sm_list[atomicAdd(&sm_count, 1)] = tid;
+    __syncthreads();
+    const int count = sm_count;                                    // uniform
+    // (the order of the list varies from run to run, the rows' results do not: each is computed on its own)
+    for (int it = 0; it < count; ++it) {
+        const int64_t row = (int64_t)blockIdx.x * 256 + sm_list[it];
+        const RowStats st = A.stats[row];
+        const T* crow = static_cast<const T*>(A.draft) + row_offset(A, row);
+        const T* rrow = A.radius ? static_cast<const T*>(A.radius) + row_offset(A, row) : nullptr;
+        const double mc = (double)st.mc;
+        // the sum of four per-wave sums, in a fixed order
+        auto block_sums = [&](double (&v)[5], int n) {
+            __syncthreads();                                       // the slots may still be read from the last use
+            for (int i = 0; i < n; ++i) {
+                const double w = wave_sum(v[i]);
+                if (lane == 0) sm_red[i][wave] = w;
+            }
+            __syncthreads();
+            for (int i = 0; i < n; ++i) v[i] = (sm_red[i][0] + sm_red[i][1]) + (sm_red[i][2] + sm_red[i][3]);
+        };
+        double acc[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
+        for (int i = tid; i < V; i += 256) acc[0] += exp((double)load_logit(crow, i) - mc);   // masked token: exp(-inf) = 0
+        block_sums(acc, 1);
+        const double invS = 1.0 / acc[0];
+        auto token = [&](int i, double& pl, double& w) {
+            const double x = exp((double)load_logit(crow, i) - mc) * invS;
+            double a = A.a, b = A.b;
+            if (rrow) {
+                const double r = radius_of((double)load_logit(rrow, i), A.kappa, A.rmax);
+                a = exp(r); b = exp(-r);
+            }
+            const double om = 1.0 - x;                             // a flat row: every x is tiny
+            pl = b * x / (b + (1.0 - b) * om);
+            w = a * x / (1.0 + (a - 1.0) * x) - pl;
+        };
+        double kl, kw;
+        token(0, kl, kw);                                          // every lane forms the same shift
+#pragma unroll
+        for (int i = 0; i < 5; ++i) acc[i] = 0.0;
+        for (int i = tid; i < V; i += 256) {
+            double pl, w;
+            token(i, pl, w);
+            pl -= kl; w -= kw;
+            acc[0] += pl; acc[1] += w;
+            acc[2] = fma(pl, pl, acc[2]); acc[3] = fma(w, w, acc[3]); acc[4] = fma(pl, w, acc[4]);
+        }
+        block_sums(acc, 5);
+        if (tid == 0) {
+            RowStats o = st;
+#pragma unroll
+            for (int i = 0; i < 5; ++i) o.q[i] = acc[i];
+            o.kl = kl; o.kw = kw;
+            o.mode = kSumsDirect;
+            A.stats[row] = o;
+            if (finish) {
+                float cx = st.mc, rawx = 0.f;                      // no ids: the arg-max token is reported
+                if (A.ids) {
+                    int xid = A.ids[ids_index(A, row)];
+                    xid = xid < 0 ? 0 : (xid >= V ? V - 1 : xid);
+                    cx = load_logit(crow, xid);
+                    if (rrow) rawx = load_logit(rrow, xid);
+                }
+                finish_row(A, row, o, cx, 0.f, rawx, 0.f, true, false);
+            }
+        }
+    }
+}
+
 // ---- arg-max token of every row (tensor-radius calls without drafted ids) ----------------------------------
 
 // One workgroup per row: the lowest index that holds the row's largest centre logit.  Only the
@@ -338,6 +425,15 @@ hipError_t launch_windows(const uint8_t* accept, const int32_t* row_id, int64_t 
     const unsigned blocks = (unsigned)((W + 255) / 256);
     hipLaunchKernelGGL(window_kernel, dim3(blocks), dim3(256), 0, stream, accept, row_id, N, K, accept_len,
                        resampled_id);
+    return hipGetLastError();
+}
+
+hipError_t launch_flatrows(int dtype, const RowArgs& args, bool finish_rows, hipStream_t stream)
+{
+    if (args.N <= 0) return hipSuccess;
+    const dim3 grid((unsigned)((args.N + 255) / 256)), block(256);
+    if (dtype == 0) hipLaunchKernelGGL(flatrow_kernel<float>, grid, block, 0, stream, args, finish_rows ? 1 : 0);
+    else hipLaunchKernelGGL(flatrow_kernel<bf16_t>, grid, block, 0, stream, args, finish_rows ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -78,8 +78,10 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
     };
     // The same in fp64 from the fp32 e (rows of a handful of tokens).
     auto head_token_tiny = [&](int h, float cval, float rval, double& d, double& c) {
-        // e as the streaming kernel summed it into S: 1 - x stays accurate as x -> 1
-        const double ed = (double)exp2_ref(cval, sm_n[h]);
+        // A handful of tokens: e as the streaming kernel summed it into S, so that 1 - x stays accurate as x -> 1.
+        // A flat row: the fp64 exponential (every x is tiny; the fp32 one would leave 6e-8 of each width behind,
+        // uncorrelated from token to token, where the widths themselves agree to 1e-6).
+        const double ed = V <= 64 ? (double)exp2_ref(cval, sm_n[h]) : exp((double)cval - (double)sm_n[h] * kLn2);
         const double x = ed / sm_S[h], omx = fmax(0.0, sm_S[h] - ed) / sm_S[h];
         double a = A.a, b = A.b;
         if (rad) {

@@ -20,7 +20,9 @@ struct RowStats {
     float  nt;       // integer-valued reference of the verifier row
     float  mc;       // largest centre logit (the arg-max token's logit)
     float  mode;     // 0 = all five sums; 1 = caps inactive, only q[1], q[3] were accumulated;
-                     // 2 = caps inactive and every width above 1/2: q[1], q[3] hold the sums of 1 - width
+                     // 2 = caps inactive and every width above 1/2: q[1], q[3] hold the sums of 1 - width;
+                     // 3 = the five sums are of p^l_i and p^u_i - p^l_i themselves (written by the fp64 pass over
+                     //     flat rows); + 8 = a flat row that pass has still to visit
 };
 static_assert(sizeof(RowStats) == 88, "RowStats layout");
 
@@ -41,6 +43,8 @@ struct RowArgs {
     int32_t* reject_list;                            // [N] workspace: rows whose drafted token was rejected
     int32_t* reject_count;                           // workspace: length of that list
     int32_t  finish;                                 // 1 = the streaming kernel also finishes its rows (quantify only)
+    int32_t  precise_flat;                           // 1 = the streaming kernel marks flat rows for the fp64 pass (see
+                                                     // needs_flat_pass)
     int64_t  N;
     int64_t  stride;            // elements between rows
     // Several heads in one launch (quantify only): the N rows are [heads, head_rows], head h starting head_stride
@@ -80,6 +84,23 @@ inline bool wide_radius(const RowArgs& a)
     return amax >= 3.0 * (double)a.V;
 }
 
+// Flat rows (largest probability at most 2 / V) whose widths are not small: the widths of such a row can agree to
+// 1e-6 and better while their fp32 rounding errors (~1e-7 of each width, uncorrelated as soon as the logits or
+// radii differ at all) do not, and U = Omega * Sigma multiplies what those errors leave in Sigma by Omega ~ V * width.
+// With uncorrelated errors eps * w per width the score is off by about sqrt(V) * eps * w^2, to be held against its
+// absolute tolerance of 1e-7.  A flat row's widths are at most w_cap = 2 a_max / V (a_max = e^r of the largest
+// radius the call can produce); calls with sqrt(V) * w_cap^2 above 0.01 -- a hundredth of that tolerance at
+// eps = 1e-7 -- mark their flat rows in the streaming kernel and run flatrow_kernel behind it, which redoes those
+// rows' interval sums in fp64 from the logits.  The default scalar radius (a = 5.2) stays far below the bound
+// for every large vocabulary; tensor-radius calls with the default clamp of 10 are above it.
+inline bool needs_flat_pass(const RowArgs& a)
+{
+    const double amax = a.radius ? (a.kappa > 0.0 ? exp(a.rmax) : 1.0) : a.a;
+    double wcap = 2.0 * amax / (double)a.V;
+    if (wcap > 1.0) wcap = 1.0;
+    return a.V > 64 && wcap * wcap * sqrt((double)a.V) > 0.01;
+}
+
 // Largest vocabulary the register-resident streaming kernels cover for an element size.
 int max_vocab(int dtype);
 
@@ -109,6 +130,10 @@ hipError_t launch_stream(Mode mode, int dtype, const RowArgs& args, bool finish_
 // K rows.
 hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, bool rows_finished, int32_t K, int32_t* accept_len,
                          int32_t* resampled_id, hipStream_t stream);
+
+// The fp64 pass over the rows the streaming kernel has marked as flat (see needs_flat_pass): rewrites their
+// RowStats; with finish_rows also their quantify outputs (for launches whose streaming kernel finishes its rows).
+hipError_t launch_flatrows(int dtype, const RowArgs& args, bool finish_rows, hipStream_t stream);
 
 // accept_len / resampled_id per window of K rows from the per-row results.
 hipError_t launch_windows(const uint8_t* accept, const int32_t* row_id, int64_t N, int32_t K,

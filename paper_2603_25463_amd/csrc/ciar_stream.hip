@@ -520,6 +520,7 @@ void stream_kernel(const RowArgs A)
         const double emax = (double)exp2_ref(mc, n);               // the row's largest e_i, in row units
         const bool capless = !A.normalize || (!RAD && emax <= A.capless_xmax * S);
         const bool split = emax > 0.5 * S;                         // some x_i above 1/2: 1 - x needs the two-float 1/S
+        const bool flat = emax * (double)V <= 2.0 * S;             // largest probability <= 2 / V (see Shift)
         if constexpr (EARLY_NEXT) {
             __builtin_amdgcn_sched_barrier(0);
             if (has_next) load_row(buf, A.draft, next);
@@ -553,7 +554,6 @@ void stream_kernel(const RowArgs A)
             // The common shift of a flat row (see Shift), 0 elsewhere.  A wave whose units are too far from the
             // row's (scalar radius) or from wave 0's (tensor radius) to form it takes its sums about 0, and its
             // lane 0 moves them to the common shift afterwards.
-            const bool flat = emax * (double)V <= 2.0 * S;         // uniform over the workgroup
             bool near = false;
             Shift sh = {0.f, 0.f, 0.f};
             if (flat) {
@@ -749,6 +749,8 @@ void stream_kernel(const RowArgs A)
                         }
                     }
                 }
+                // a flat row of a call whose widths are not small: the fp64 pass behind this kernel redoes its sums
+                if (DO_Q && A.precise_flat && flat && V > kTinyVocab) mode += kSumsFlatPending;
                 st->kl = K[0]; st->kw = K[1];
                 st->mode = mode;
 #pragma unroll

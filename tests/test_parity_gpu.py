@@ -282,6 +282,109 @@ def test_tensor_radius_argmax_token_and_dense(ciar, oracle):
             assert np.all(np.abs(gg - oo) <= parity.ATOL + parity.RTOL * np.abs(oo))
 
 
+# ---- flat rows with wide intervals: widths that agree to 1e-6 while Omega ~ V multiplies their spread ----------------
+
+def _flat_rows(V, stride, N, dtype, seed):
+    """Rows that are flat in the centre logits (largest probability <= 2 / V) with raw radii around ln(4 V) (e^r ~ 4 V:
+    every width ~ 0.8) in the variants that leave the least spread: constant centre row with a constant, a nearly
+    constant (noise 1e-6 ... 1e-3) or a slowly varying radius; centre rows flat to 1e-6 / 1e-4 / 1e-2 with the same
+    radii; a row of smaller radii (e^r ~ V / 4)."""
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    c = torch.empty((N, stride), device="cuda")
+    raw = torch.empty((N, stride), device="cuda")
+    tok = torch.arange(stride, device="cuda", dtype=torch.float32)
+    centre = math.log(4.0 * V)
+    for r in range(N):
+        cs = (0.0, 0.0, 0.0, 1e-6, 1e-4, 1e-2)[r % 6]
+        rs = (0.0, 1e-6, 1e-5, 1e-4, 1e-3)[(r // 6) % 5]
+        slow = (r // 30) % 2 == 1
+        rc = centre if (r // 60) % 2 == 0 else math.log(0.25 * V)
+        c[r] = 1.5 + cs * torch.randn(stride, generator=g, device="cuda")
+        if slow:
+            raw[r] = rc + rs * torch.sin(tok * (2 * math.pi / V))
+        else:
+            raw[r] = rc + rs * torch.randn(stride, generator=g, device="cuda")
+    t = c + 0.3 * torch.randn((N, stride), generator=g, device="cuda")
+    if stride > V:
+        c[:, V:] = 1e30
+        t[:, V:] = -1e30
+        raw[:, V:] = float("nan")
+    ids = torch.randint(0, V, (N,), generator=g, device="cuda").to(torch.int32)
+    ua = torch.randint(0, 1 << 24, (N,), generator=g, device="cuda").float() / (1 << 24)
+    ur = torch.randint(0, 1 << 24, (N,), generator=g, device="cuda").float() / (1 << 24)
+    return c.to(dtype), t.to(dtype), raw.to(dtype), ids, ua, ur
+
+
+FLAT_SHAPES = [   # every tile of the streaming kernel, both dtypes, ragged vocabularies and padded strides
+    (1000, 1000, 120, torch.float32), (2048, 2048, 60, torch.float32), (4000, 4000, 60, torch.float32),
+    (8192, 8192, 120, torch.float32), (16384, 16384, 120, torch.float32), (12345, 12348, 3100, torch.float32),
+    (32768, 32768, 36, torch.float32),
+    (2000, 2000, 60, torch.bfloat16), (4096, 4096, 60, torch.bfloat16), (8192, 8192, 60, torch.bfloat16),
+    (16384, 16384, 120, torch.bfloat16), (30000, 30000, 36, torch.bfloat16), (65535, 65536, 36, torch.bfloat16),
+]
+
+
+@pytest.mark.parametrize("V,stride,N,dtype", FLAT_SHAPES)
+def test_flat_rows_with_wide_intervals(ciar, oracle, V, stride, N, dtype):
+    """The regime in which fp32 token arithmetic cannot hold the score's tolerance: all widths of a row O(1) and
+    equal to 1e-6 and better, so that U = Omega * Sigma with Omega ~ 0.8 V needs Sigma to ~1e-11.  The library redoes
+    such rows in fp64 (flatrow_kernel); fused, quantify-only, verify-only and staged calls, tensor and scalar radius."""
+    c, t, raw, ids, ua, ur = _flat_rows(V, stride, N, dtype, seed=7000 + V)
+    for rmax in (16.0, 10.0):
+        P = ciar.Params(radius_scale=1.0, radius_max=rmax, window=8, tau=1e-3)
+        _run_case(ciar, oracle, c, t, ids, ua, ur, P, vocab=V, tag=f"flat rows, tensor radius, V={V} rmax={rmax}",
+                  radius=raw)
+    # the same centre rows under a scalar radius of that size
+    P = ciar.Params(radius_scale=math.log(4.0 * V), radius_max=16.0, window=8, tau=1e-3)
+    _run_case(ciar, oracle, c, t, ids, ua, ur, P, vocab=V, tag=f"flat rows, scalar radius ln(4V), V={V}")
+    P = ciar.Params(radius_scale=math.log(0.25 * V), radius_max=16.0, window=8, tau=1e-3)
+    _run_case(ciar, oracle, c, t, ids, ua, ur, P, vocab=V, tag=f"flat rows, scalar radius ln(V/4), V={V}")
+
+
+def test_flat_rows_take_the_fp64_pass(ciar):
+    """White box: the streaming kernel marks the flat rows of such a call and flatrow_kernel rewrites their
+    statistics (RowStats::mode, the float at byte 84 of each 88-byte record at the start of the workspace, reads 3);
+    rows that are not flat, and calls whose widths are small, keep the streaming kernel's sums (mode 0 ... 2)."""
+    V, N = 4096, 60
+    c, t, raw, ids, ua, ur = _flat_rows(V, V, N, torch.float32, seed=11)
+    c[1] = torch.randn(V, device="cuda") * 2.0                     # an ordinary row among them
+    P = ciar.Params(radius_scale=1.0, radius_max=10.0, window=8, tau=1e-3)
+    ws = torch.zeros(ciar.workspace_bytes(N, P.to_c(c)), dtype=torch.uint8, device="cuda")
+    say("[flat rows] RowStats::mode after a tensor-radius call and after a default scalar call")
+    ciar.quantify(c, ids, P, workspace=ws, radius=raw)
+    torch.cuda.synchronize()
+    mode = ws[:N * 88].view(N, 88)[:, 84:88].contiguous().view(torch.float32).flatten().cpu()
+    assert mode[1] < 3.0 and bool((mode[torch.arange(N) != 1] == 3.0).all()), mode
+    ciar.quantify(c, ids, ciar.Params(confidence=0.9, tau=1e-3), workspace=ws)
+    torch.cuda.synchronize()
+    mode = ws[:N * 88].view(N, 88)[:, 84:88].contiguous().view(torch.float32).flatten().cpu()
+    assert bool((mode < 3.0).all()), mode
+
+
+@pytest.mark.parametrize("V,dtype", [(1000, torch.float32), (16384, torch.float32), (16384, torch.bfloat16)])
+def test_flat_rows_with_wide_intervals_ensemble(ciar, oracle, V, dtype):
+    """The same regime through the Ensemble sweep (rows flat in every head take its fp64 branch) and Voting."""
+    H, N = 3, 60
+    heads = [_flat_rows(V, V, N, dtype, seed=7100 + V + h) for h in range(H)]
+    c = torch.stack([x[0] for x in heads])
+    raw = torch.stack([x[2] for x in heads])
+    ids = heads[0][3]
+    for rad in (raw, None):
+        P = ciar.Params(radius_scale=1.0 if rad is not None else math.log(4.0 * V), radius_max=16.0, tau=1e-3)
+        OP = _oparams(oracle, P)
+        for strat, ostrat in ((ciar.ENSEMBLE, oracle.ENSEMBLE), (ciar.VOTING, oracle.VOTING)):
+            say(f"[flat rows, heads] V={V} {dtype} strategy={strat} radius={'tensor' if rad is not None else 'scalar'}")
+            g = ciar.quantify_multihead(c, ids, P, strat, radius_heads=rad)
+            torch.cuda.synchronize()
+            o = oracle.quantify_multihead(c.cpu(), ids.cpu().numpy(), OP, ostrat,
+                                          radius_heads=None if rad is None else rad.cpu())
+            if strat == ciar.VOTING:
+                o2 = {k: o[k].reshape(-1) for k in parity.FLOAT_KEYS}
+                parity.check_floats({k: g[k].reshape(-1) for k in parity.FLOAT_KEYS}, o2)
+            else:
+                parity.check_floats(g, o)
+
+
 @pytest.mark.parametrize("cfg", [1, 2, 3])
 def test_tensor_radius_workloads(ciar, oracle, cfg):
     """Workloads 1-3 at full size with the synthetic radius head (raw ~ N(mu_row, 1), kappa = 1), at tau = 0.30
