@@ -20,11 +20,11 @@
  *     never synchronises: kernels are enqueued on `hip_stream` (a hipStream_t, NULL = the
  *     default stream) and outputs are valid once the caller has synchronised that stream.
  *   - `workspace` is device scratch of at least ciar_workspace_bytes(N, params) bytes, 16-byte
- *     aligned, owned by the caller.  It carries the per-row statistics from the streaming kernel
- *     to the finishing kernels, the list of rejected rows, and per-row results the caller did not
- *     ask for.  Its contents need
- *     no initialisation and are garbage afterwards; calls that overlap in time on one device
- *     must not share a workspace.
+ *     aligned, owned by the caller.  It carries the per-row statistics, the list of rejected rows
+ *     whose residual draw a second kernel makes, the words in which the rows of a window that spans
+ *     workgroups meet, and per-row results the caller did not ask for.  Its contents need no
+ *     initialisation (counters in it carry a per-launch tag; other contents count as zero) and are
+ *     garbage afterwards; calls that overlap in time on one device must not share a workspace.
  *   - Logits: row-major [N, row_stride] with V <= row_stride, element type `dtype`
  *     (float32, or bfloat16 widened exactly to float32 on load).  Base pointers and
  *     row_stride * sizeof(element) must be multiples of 16 bytes, and the buffer must be
@@ -112,7 +112,7 @@ int ciar_width_polynomial(const ciar_params* params, float* coef, float* x_max);
 
 /*
  * Bytes of device workspace ciar_quantify / ciar_verify / ciar_quantify_verify need for N rows
- * (97 bytes per row, rounded up).  Always a multiple of 256; returns 0 for N <= 0.
+ * (113 bytes per row, rounded up).  Always a multiple of 256; returns 0 for N <= 0.
  */
 size_t ciar_workspace_bytes(int64_t N, const ciar_params* params);
 
@@ -178,12 +178,12 @@ int ciar_quantify_verify(const void* draft_logits, const void* radius, const voi
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, semantics, kernels and
  * results as ciar_quantify_verify, without `workspace` / `workspace_bytes`: the per-row statistics, the list of
  * rejected rows and the per-row results the caller did not ask for live in a buffer that is part of the library's
- * device image (ciar_workspace_bytes(CIAR_STATIC_MAX_ROWS) = 3.03 MiB on every GPU the library runs on, held
+ * device image (ciar_workspace_bytes(CIAR_STATIC_MAX_ROWS) = 3.53 MiB on every GPU the library runs on, held
  * until the process ends).  The call allocates and frees nothing.
  *   - N > CIAR_STATIC_MAX_ROWS returns CIAR_EWORKSPACE and launches nothing.
  *   - Every call on a GPU uses that GPU's one buffer: calls that overlap in time on one GPU (different streams,
  *     different host threads) race on it.  Calls on one stream, or otherwise ordered, are safe; the buffer needs
- *     no clearing between calls (the one word that must start at zero is cleared by the first kernel of a call).
+ *     no clearing between calls (its counters carry the tag of the launch that uses them, see `workspace` above).
  *   - The first call on a device looks the buffer's address up (hipGetSymbolAddress) with that device current.
  */
 #define CIAR_STATIC_MAX_ROWS 32768
@@ -202,14 +202,15 @@ int ciar_quantify_verify_static(const void* draft_logits, const void* radius, co
  * argument list of ciar_quantify_verify and must be given the same arguments: target_logits = NULL with
  * no verify output is a quantify-only call, no quantify output a verify-only call (radius must be NULL).
  *
- * ciar_stream_rows   the streaming kernel: reads every logit row once from HBM and leaves the per-row
- *                    statistics (max-trick references, partition sums, the InterFuse sums) in `workspace`.
- *                    A quantify-only call in which every workgroup of the launch handles at most 128 rows
- *                    (N up to 128 times the number of resident workgroups: 131072 rows and more on this chip)
- *                    also finishes its rows here: p_lo ... flags are complete when the kernel ends.
- * ciar_finish_rows   what remains: the per-row outputs where the streaming kernel has not produced them, the
- *                    residual draw of the rejected rows, and the window outputs.  A quantify-only call whose
- *                    rows the streaming kernel has finished launches nothing here.
+ * ciar_stream_rows   the streaming kernel: reads every logit row once from HBM and writes every per-row output:
+ *                    the quantifier's (p_lo ... flags) and, with a verifier row, the accept bits.  For float32
+ *                    logits of up to 8192 tokens per 256 lanes (V <= 32768) under a scalar radius it also makes the
+ *                    residual draws of the rejected rows, from the registers that still hold both rows, and
+ *                    writes the window outputs; the call is then this one launch.  (Calls whose flat rows need the
+ *                    fp64 pass launch that behind it, see the radius notes above.)
+ * ciar_finish_rows   what remains, if anything: for bfloat16 logits, tensor radii and very wide radii the residual
+ *                    draws of the rejected rows (their rows are read again), and the window outputs where neither
+ *                    kernel could write them (windows longer than 255 rows that span workgroups).
  */
 int ciar_stream_rows(const void* draft_logits, const void* radius, const void* target_logits,
                      const int32_t* draft_ids,

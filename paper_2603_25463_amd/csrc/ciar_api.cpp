@@ -1,5 +1,6 @@
 // C ABI of the library (include/ciar.h): argument validation, parameter resolution, launches.
-// No allocation, no synchronisation, no state besides the thread-local error text.
+// No allocation, no synchronisation; state: the thread-local error text, a launch counter (tags, see next_tag) and,
+// for ciar_quantify_verify_static, the addresses of the built-in scratch buffer.
 #include "../../include/ciar.h"
 #include "ciar_internal.h"
 
@@ -7,6 +8,8 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <atomic>
+#include <chrono>
 #include <mutex>
 
 namespace {
@@ -182,6 +185,8 @@ ciar::RowArgs base_args(const ciar_params* p, const Resolved& r, int64_t N)
     }
     a.capless_xmax = xm;
     a.precise_flat = 0;                                            // set by the callers that run the fp64 pass
+    a.unit = 1;
+    a.window = p->window;
     const WidthPolyFit& wf = width_poly(r.a, r.b);
     for (int j = 0; j < 4; ++j) a.wpoly[j] = wf.c[j];
     a.wpoly_x = wf.x;
@@ -193,17 +198,22 @@ int hip_fail(hipError_t e, const char* what)
     return fail(CIAR_EHIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-// Workspace layout: [N] RowStats | [N] int32 row ids | [N] int32 rejected rows | 16 B counter | [N] uint8 accept bits.
+// Workspace layout: [N] RowStats | [N] int32 row ids | [N] int32 rejected rows | 16 B counter | [N] uint8 accept bits
+// (rounded up to 128 B) | 16 N bytes for the words of windows that span workgroups: window w at byte 16 K w, so that
+// from K = 8 on every window has a 128-byte line of its own (the rows of many windows arrive at once, and atomic
+// operations on one line are served one after another).
 size_t stats_bytes(int64_t N) { return round_up((size_t)N * sizeof(ciar::RowStats), 16); }
 size_t ids_bytes(int64_t N) { return round_up((size_t)N * 4, 16); }
+size_t windows_offset(int64_t N) { return round_up(stats_bytes(N) + 2 * ids_bytes(N) + 16 + (size_t)N, 128); }
 
 void carve(char* w, int64_t N, ciar::RowArgs* a, int32_t** row_ids, uint8_t** accept)
 {
     a->stats = reinterpret_cast<ciar::RowStats*>(w);
     *row_ids = reinterpret_cast<int32_t*>(w + stats_bytes(N));
     a->reject_list = reinterpret_cast<int32_t*>(w + stats_bytes(N) + ids_bytes(N));
-    a->reject_count = reinterpret_cast<int32_t*>(w + stats_bytes(N) + 2 * ids_bytes(N));
+    a->reject_count = reinterpret_cast<unsigned long long*>(w + stats_bytes(N) + 2 * ids_bytes(N));
     *accept = reinterpret_cast<uint8_t*>(w + stats_bytes(N) + 2 * ids_bytes(N) + 16);
+    a->win_words = reinterpret_cast<unsigned long long*>(w + windows_offset(N));
 }
 
 int check_workspace(int64_t N, const ciar_params* p, void* workspace, size_t workspace_bytes)
@@ -275,7 +285,10 @@ int fill(const Call& c, ciar::Mode mode, ciar::RowArgs* a)
     a->row_id = c.row_id;
     // the window outputs are assembled from the per-row accept bits and draws
     if ((c.accept_len || c.resampled_id) && !a->accept) a->accept = ws_accept;
-    if (c.resampled_id && !a->row_id) a->row_id = ws_ids;
+    if ((c.accept_len || c.resampled_id) && !a->row_id) a->row_id = ws_ids;
+    a->window = c.params->window;
+    a->accept_len = c.accept_len;
+    a->resampled_id = c.resampled_id;
     return CIAR_OK;
 }
 
@@ -283,7 +296,19 @@ int fill(const Call& c, ciar::Mode mode, ciar::RowArgs* a)
 // comes from a kernel of its own, into the list of rejected rows (not in use in a quantify-only call).
 bool needs_argmax(const ciar::RowArgs& a) { return a.radius && !a.ids && (a.p_lo || a.p_hi); }
 
-// Stage 1: the streaming kernel; a quantify-only launch also finishes its rows where its shape allows.
+// Tags for the counters the kernels keep in caller memory (see counter_add in ciar_device.h): a different one
+// for every launch of the process, starting from a value that varies from run to run.  (A captured graph replays
+// a launch with its tag: the kernels hand every counter back, with a zero tag, when they are through with it.)
+uint32_t next_tag()
+{
+    static std::atomic<uint32_t> tag{(uint32_t)std::chrono::steady_clock::now().time_since_epoch().count() * 2654435761u};
+    for (;;) {
+        const uint32_t t = tag.fetch_add(1, std::memory_order_relaxed) + 1;
+        if ((t & 0x7fffffffu) != 0) return t;                      // (a zero tag marks a word that has been handed back)
+    }
+}
+
+// Stage 1: the streaming kernel, which also finishes its rows (and the fp64 pass over flat rows where the call needs it).
 int run_stream(const Call& c, ciar::Mode mode)
 {
     ciar::RowArgs a;
@@ -295,6 +320,7 @@ int run_stream(const Call& c, ciar::Mode mode)
         a.ids = a.reject_list;
     }
     a.precise_flat = mode != ciar::Mode::Verify && ciar::needs_flat_pass(a) ? 1 : 0;
+    a.tag = next_tag();
     hipError_t e = ciar::launch_stream(mode, c.params->dtype, a, true, c.stream, c.ev_start, c.ev_stop);
     if (e != hipSuccess) return hip_fail(e, "streaming kernel launch");
     if (a.precise_flat) {
@@ -306,8 +332,7 @@ int run_stream(const Call& c, ciar::Mode mode)
     return CIAR_OK;
 }
 
-// Stage 2: whatever the streaming kernel has left (the per-row finishing for launch shapes it does not cover),
-// the residual draws and the window outputs.
+// Stage 2: the window outputs, where the windows do not lie inside the streaming kernel's workgroups.
 int run_finish(const Call& c, ciar::Mode mode)
 {
     ciar::RowArgs a;
@@ -315,8 +340,8 @@ int run_finish(const Call& c, ciar::Mode mode)
     if (c.N == 0) return CIAR_OK;
     if (needs_argmax(a)) a.ids = a.reject_list;                    // found by stage 1
     const ciar::StreamPlan plan = ciar::plan_stream(mode, c.params->dtype, a);
-    const hipError_t e = ciar::launch_finish(mode, c.params->dtype, a, plan.can_finish, c.params->window,
-                                             c.accept_len, c.resampled_id, c.stream);
+    const hipError_t e = ciar::launch_finish(mode, c.params->dtype, a, plan, c.params->window, c.accept_len,
+                                             c.resampled_id, c.stream);
     if (e != hipSuccess) return hip_fail(e, "finishing kernel launch");
     return CIAR_OK;
 }
@@ -339,8 +364,9 @@ namespace {
 constexpr int64_t kStaticRows = CIAR_STATIC_MAX_ROWS;
 constexpr size_t static_round(size_t x, size_t m) { return (x + m - 1) / m * m; }
 constexpr size_t kStaticBytes =
-    static_round(static_round((size_t)kStaticRows * sizeof(ciar::RowStats), 16) + 2 * static_round((size_t)kStaticRows * 4, 16) +
-                 16 + (size_t)kStaticRows, 256);
+    static_round(static_round(static_round((size_t)kStaticRows * sizeof(ciar::RowStats), 16) +
+                              2 * static_round((size_t)kStaticRows * 4, 16) + 16 + (size_t)kStaticRows, 128) +
+                 16 * (size_t)kStaticRows, 256);      // = ciar_workspace_bytes(kStaticRows)
 
 }  // namespace
 
@@ -406,7 +432,7 @@ int ciar_width_polynomial(const ciar_params* params, float* coef, float* x_max)
 size_t ciar_workspace_bytes(int64_t N, const ciar_params* /*params*/)
 {
     if (N <= 0) return 0;
-    return round_up(stats_bytes(N) + 2 * ids_bytes(N) + 16 + (size_t)N, 256);
+    return round_up(windows_offset(N) + 16 * (size_t)N, 256);
 }
 
 int ciar_quantify(const void* draft_logits, const void* radius, const int32_t* draft_ids, int64_t N,
@@ -618,7 +644,7 @@ int ciar_quantify_multihead(const void* draft_heads, const void* radius_heads, i
         a.radius = radius_heads;
         a.stats = stats;
         a.reject_list = ws_ids;                              // heads * N ints; a quantify-only pass builds no list
-        a.reject_count = a.reject_list;
+        a.reject_count = nullptr;                            // (no verifier row: no list)
         if (strategy == CIAR_VOTING) {
             // every head is a quantifier of its own: the streaming kernel finishes its rows where it can;
             // the per-head outputs are [heads, N], which is the order of the rows
@@ -641,9 +667,6 @@ int ciar_quantify_multihead(const void* draft_heads, const void* radius_heads, i
                 e = ciar::launch_flatrows(params->dtype, a, plan.can_finish, stream);
                 if (e != hipSuccess) return hip_fail(e, "flat-row kernel launch");
             }
-            e = ciar::launch_finish(ciar::Mode::Quantify, params->dtype, a, plan.can_finish, params->window, nullptr,
-                                    nullptr, stream);
-            if (e != hipSuccess) return hip_fail(e, "finishing kernel launch");
         } else {
             // Ensemble: only every head's RowStats
             const hipError_t e = ciar::launch_stream(ciar::Mode::Quantify, params->dtype, a, false, stream);

@@ -175,6 +175,16 @@ __device__ __forceinline__ double row16_sum(double v)
     return __hiloint2double(hi, lo);
 }
 
+// the same for a float
+__device__ __forceinline__ float row16_sum_f(float v)
+{
+    v += __int_as_float(dpp_or<kRowShr1, 0xf>(0, __float_as_int(v)));
+    v += __int_as_float(dpp_or<kRowShr2, 0xf>(0, __float_as_int(v)));
+    v += __int_as_float(dpp_or<kRowShr4, 0xf>(0, __float_as_int(v)));
+    v += __int_as_float(dpp_or<kRowShr8, 0xf>(0, __float_as_int(v)));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 15));
+}
+
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ float dpp_max(float v)
 {
@@ -454,6 +464,36 @@ __device__ __forceinline__ RowScore finish_score(const double* s, double S, floa
     return o;
 }
 
+// The accept test of a drafted token in the log domain, fp64 (Algorithm 1, "Cloud verification"):
+//   ln p_x = cx - n ln2 - ln S,  ln q_x = tx - nt ln2 - ln Z;  accepted iff ln u < min(0, ln q_x - ln p_x).
+// Returns whether the token is rejected.
+__device__ __forceinline__ bool reject_exact(float cx, float tx, float u, float n, float nt, double S, double Z)
+{
+    const double lp = ((double)cx - (double)n * kLn2) - log(S);
+    const double lq = ((double)tx - (double)nt * kLn2) - log(Z);
+    const double lnu = log((double)u);                             // log(0) = -inf: always accepted
+    return !(lnu < fmin(0.0, lq - lp));
+}
+
+// The same test in fp32 with the hardware logarithm, for the streaming kernel, where every wave of a row evaluates
+// it: 1 = accepted, 0 = rejected, -1 = too close to call (then reject_exact decides).  The fp32 evaluation is off by
+// at most ~3e-7 (1 + the sum of the magnitudes of its terms): a hardware logarithm good to an ulp, a handful of
+// roundings at 6e-8; the guard band is thirty times that, and a row falls inside it about once in a few thousand.
+// Anything that is not a number ends up in the band.
+__device__ __forceinline__ int accept_quick(float cx, float tx, float u, float n, float nt, float S, float Z)
+{
+    const float lS = __builtin_amdgcn_logf(S), lZ = __builtin_amdgcn_logf(Z);   // base 2
+    const float lu = __builtin_amdgcn_logf(u);
+    const float d = tx - cx, dn = nt - n;
+    const float ell = fmaf(-(dn + (lZ - lS)), 0.693147181f, d);   // ln q_x - ln p_x
+    const float margin = fminf(0.f, ell) - lu * 0.693147181f;     // > 0: accepted
+    const float guard = 1e-5f * (1.f + fabsf(d) + fabsf(dn) + fabsf(lZ) + fabsf(lS) + fabsf(lu));
+    if (u == 0.f && ell > -INFINITY) return 1;                     // ln 0 = -inf lies below every finite bound
+    if (margin > guard) return 1;
+    if (margin < -guard) return 0;
+    return -1;
+}
+
 // One row's outputs from its statistics, in fp64 (Eq. uncertainty_score; Algorithm 1's threshold and verification
 // steps): score, flag, the reported token's interval, the accept test in the log domain.  xid = the reported
 // token (-1: the arg-max token, whose logit is st.mc), cx / tx / rawx = its centre logit, verifier logit and raw
@@ -489,15 +529,65 @@ __device__ __forceinline__ bool finish_row(const RowArgs& A, int64_t row, const 
     }
     bool rej = false;
     if (do_v) {
-        // ln p_x = cx - n ln2 - ln S, ln q_x = tx - nt ln2 - ln Z;  accept iff ln u < min(0, ln q_x - ln p_x)
-        const double lp = ((double)cx - (double)n * kLn2) - log(S);
-        const double lq = ((double)tx - (double)st.nt * kLn2) - log(st.Z);
-        const double lnu = log((double)u);                         // log(0) = -inf: always accepted
-        rej = !(lnu < fmin(0.0, lq - lp));
+        rej = reject_exact(cx, tx, u, n, st.nt, S, st.Z);
         if (A.accept) A.accept[row] = (uint8_t)(!rej);
         if (A.row_id && !rej) A.row_id[row] = -1;
     }
     return rej;
+}
+
+// A counter in caller memory that needs no initialisation: the high word carries the tag of the launch that uses
+// it (RowArgs::tag, never zero, different for every launch of the process), the low word the count.  A word that
+// carries another tag -- what an earlier call left behind, or whatever the memory held before -- counts as zero.
+// Whoever reads the final count writes a zero word back, so that a replay of the same launch (a captured graph:
+// same tag) starts afresh as well.
+__device__ __forceinline__ uint32_t counter_add(unsigned long long* p, uint32_t tag, uint32_t inc)
+{
+    const unsigned long long fresh = (unsigned long long)tag << 32;
+    unsigned long long seen = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    while ((seen >> 32) != tag) {
+        // claim the word for this launch; whoever loses the exchange finds the tag in place (or tries again)
+        const unsigned long long prev = atomicCAS(p, seen, fresh);
+        seen = prev == seen ? fresh : prev;
+    }
+    return (uint32_t)atomicAdd(p, (unsigned long long)inc);       // the count stays below 2^32: no carry into the tag
+}
+__device__ __forceinline__ uint32_t counter_read(const unsigned long long* p, uint32_t tag)
+{
+    const unsigned long long v = *p;
+    return (v >> 32) == tag ? (uint32_t)v : 0u;
+}
+
+// The rows of a window that spans workgroups meet in one 64-bit word of caller memory, which needs no
+// initialisation and carries everything the window's outputs need, so that no other memory has to be made visible
+// between workgroups:  [63:33] the launch's tag (as in counter_add: a word with another tag is a fresh one),
+// [32:25] rows arrived, [24:17] offset of the first rejected row so far (255: none), [16:0] that row's draw.
+// A run of `rows` consecutive rows of the window that one workgroup has finished arrives with one call: its rows'
+// first rejected offset in the window and that row's draw (id = -1: all accepted).  The call that completes the
+// window returns true with the window's first rejected offset (-1: none) and its draw.
+constexpr int kMaxCountedWindow = 255;
+__device__ __forceinline__ bool window_arrive(unsigned long long* p, uint32_t tag, int rows, int off, int id, int len,
+                                              int& first, int& draw)
+{
+    const unsigned long long t31 = (unsigned long long)(tag & 0x7fffffffu);
+    unsigned long long seen = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (;;) {
+        const unsigned long long cur = (seen >> 33) == t31 ? seen : ((t31 << 33) | (0xffull << 17));
+        const unsigned long long count = ((cur >> 25) & 0xffull) + (unsigned long long)rows;
+        unsigned long long f = (cur >> 17) & 0xffull, d = cur & 0x1ffffull;
+        if (id >= 0 && (unsigned long long)off < f) { f = (unsigned long long)off; d = (unsigned long long)id & 0x1ffffull; }
+        const unsigned long long next = (t31 << 33) | (count << 25) | (f << 17) | d;
+        const unsigned long long prev = atomicCAS(p, seen, next);
+        if (prev == seen) {
+            first = f == 0xffull ? -1 : (int)f;
+            draw = (int)d;
+            if (count != (unsigned long long)len) return false;
+            // complete: hand the word back (a replay of this launch from a captured graph carries the same tag)
+            __hip_atomic_store(p, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return true;
+        }
+        seen = prev;                                               // another row of the window got in between
+    }
 }
 
 // Vocabularies of at most this many tokens take fp64 token arithmetic (see fuse_sums_tiny, dro_row_tiny_kernel).

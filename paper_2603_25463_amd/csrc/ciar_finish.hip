@@ -1,12 +1,10 @@
-// gfx950 kernels of the finishing pass: per-row scalars (score, flag, reported interval, accept test), the
-// residual draw of rejected rows, the window outputs, and the arg-max index for tensor-radius calls
-// without drafted ids.  (Eq. uncertainty_score; Algorithm 1's threshold and verification steps.)
+// gfx950 kernels around the streaming kernel: the fp64 pass over flat rows, the window outputs for launches whose
+// windows do not lie inside one workgroup, and the arg-max index for tensor-radius calls without drafted ids.
+// (Eq. uncertainty_score; Algorithm 1's verification step.)
 #include "ciar_device.h"
 
 namespace ciar {
 namespace {
-
-// ---- the finishing kernels ----------------------------------------------------------------------------------------
 
 // Window w = rows [wK, min((w+1)K, N)): accepted prefix length and the draw of the first rejected row
 // (Algorithm 1: the verified part of a drafted window and the token that replaces the first rejection).
@@ -22,67 +20,10 @@ __device__ __forceinline__ void window_of(const uint8_t* accept, const int32_t* 
         resampled_id[w] = (lo + n < hi) ? row_id[lo + n] : -1;
 }
 
-// One thread per row: RowStats -> the row's outputs, in fp64 (Eq. uncertainty_score; Algorithm 1's threshold
-// and verification steps).  Rejected rows are appended to a list for the residual draw.
-// A workgroup covers `rows_per_block` consecutive rows.  When the window outputs are asked for, that is a
-// multiple of the window length K, so every window lies inside one workgroup: its leader thread counts the
-// accepted prefix from the accept bits the workgroup shares through LDS, and writes -1 for a window
-// without a rejection (the draw of a window with one is written by the residual-draw kernel).
-template <typename T>
-__global__ __launch_bounds__(256) void rowfinish_kernel(const RowArgs A, const int do_q, const int do_v,
-                                                        const int rows_per_block, const int K,
-                                                        int32_t* __restrict__ accept_len,
-                                                        int32_t* __restrict__ resampled_id)
-{
-    __shared__ uint8_t sm_acc[256];
-    const int tid = threadIdx.x;
-    const int64_t row = (int64_t)blockIdx.x * rows_per_block + tid;
-    const bool live = tid < rows_per_block && row < A.N;
-    const bool windows = accept_len || resampled_id;               // uniform over the grid
-    int rej = 0;
-    if (live) {
-        const int V = A.V;
-        const RowStats st = A.stats[row];
-        float cx = st.mc, tx = 0.f, rawx = 0.f;                    // no ids: the arg-max token is reported
-        if (A.ids) {
-            int xid = A.ids[ids_index(A, row)];
-            xid = xid < 0 ? 0 : (xid >= V ? V - 1 : xid);
-            const int64_t off = row_offset(A, row);
-            cx = load_logit(static_cast<const T*>(A.draft) + off, xid);
-            if (do_v) tx = load_logit(static_cast<const T*>(A.target) + off, xid);
-            if (A.radius) rawx = load_logit(static_cast<const T*>(A.radius) + off, xid);
-        }
-        rej = finish_row(A, row, st, cx, tx, rawx, do_v ? A.u_accept[row] : 0.f, do_q != 0, do_v != 0);
-    }
-    bool first = false;                                            // first rejection of its window
-    if (windows) {
-        sm_acc[tid] = (uint8_t)(!rej);
-        __syncthreads();
-        const int lead = tid - tid % K;                            // block starts are multiples of K
-        if (live && tid == lead) {
-            const int64_t left = A.N - row;
-            const int len = (int)(left < K ? left : K);
-            int m = 0;
-            while (m < len && sm_acc[tid + m]) ++m;
-            const int64_t w = row / K;
-            if (accept_len) accept_len[w] = m;
-            if (resampled_id && m == len) resampled_id[w] = -1;
-        }
-        if (rej) {
-            first = true;
-            for (int i = lead; i < tid; ++i) first = first && sm_acc[i] != 0;
-        }
-    }
-    if (rej && A.row_id) {
-        // list entry: the row, bit-complemented when the row's draw is also its window's
-        const int slot = atomicAdd(A.reject_count, 1);
-        if (slot < A.N) A.reject_list[slot] = first ? ~(int32_t)row : (int32_t)row;   // (one entry per row at most)
-    }
-}
-
-// Residual draw of the rejected rows: res_i = max(0, q_i - p_i), inverse CDF in token order.  Workgroups walk
-// over the list of rejected rows; both rows are fetched again (they were read moments ago: mostly from
-// cache), four vectors of each row per lane in flight at once.  A row's draw is a chain of dependent
+// Residual draw of the rejected rows that the streaming kernel has listed instead of drawing them itself (launches
+// whose tiles do not hold both rows in registers: bf16, tensor radius, wide radii): res_i = max(0, q_i - p_i),
+// inverse CDF in token order.  Workgroups walk over the list; both rows are fetched again, four vectors of each
+// row per lane in flight at once.  A row's draw is a chain of dependent
 // steps (list entry, statistics, loads, totals, crossing chunk, scan), so what matters is how many rows
 // a compute unit has in flight: 256-lane workgroups, several per compute unit, unless the launch is so
 // small that most compute units would see no rejected row at all (then 1024 lanes work on each row).
@@ -103,8 +44,10 @@ __global__ __launch_bounds__(THREADS) void resample_kernel(const RowArgs A, cons
     const int V = A.V;
     const int last_vec = (V + EPV - 1) / EPV - 1;
     const int nch = (V + CHUNK - 1) / CHUNK;        // <= MAXCH
-    int count = *A.reject_count;
-    if (count > A.N) count = (int)A.N;
+    // the counter that the streaming kernel claimed for its launch (see counter_add): tag and length of the list
+    const unsigned long long head = *A.reject_count;
+    const uint32_t listed = (uint32_t)head;
+    const int count = listed > (uint32_t)A.N ? (int)A.N : (int)listed;
 
     for (int item = blockIdx.x; item < count; item += gridDim.x) {
         const int32_t entry = A.reject_list[item];
@@ -233,6 +176,12 @@ __global__ __launch_bounds__(THREADS) void resample_kernel(const RowArgs A, cons
             if (entry < 0 && resampled_id) resampled_id[row / K] = id;             // the window's draw is its first rejected row's
         }
         __syncthreads();                                           // the LDS slots are reused by the next row
+    }
+    // The workgroup that is through last hands the two counters back (zero words), so that a replay of the launch
+    // from a captured graph, which carries the same tag, finds them fresh.
+    if (tid == 0 && counter_add(A.reject_count + 1, (uint32_t)(head >> 32), 1u) + 1u == gridDim.x) {
+        __hip_atomic_store(A.reject_count, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(A.reject_count + 1, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -368,53 +317,35 @@ __global__ __launch_bounds__(256) void window_kernel(const uint8_t* __restrict__
 }
 
 }  // namespace
+
 hipError_t launch_windows(const uint8_t* accept, const int32_t* row_id, int64_t N, int32_t K,
                           int32_t* accept_len, int32_t* resampled_id, hipStream_t stream);
-namespace {
 
-template <typename T>
-hipError_t launch_finish_typed(Mode mode, const RowArgs& a, int32_t K, int32_t* accept_len, int32_t* resampled_id,
-                               hipStream_t s)
+hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, const StreamPlan& plan, int32_t K,
+                         int32_t* accept_len, int32_t* resampled_id, hipStream_t stream)
 {
-    // Windows of up to 256 rows are finished inside the two kernels; longer ones by the window kernel.
-    const bool want_windows = mode != Mode::Quantify && (accept_len || resampled_id);
-    const bool inline_windows = want_windows && K <= 256 && (a.row_id || !resampled_id);
-    const int rows_per_block = inline_windows ? (256 / K) * K : 256;
-    const unsigned blocks = (unsigned)((a.N + rows_per_block - 1) / rows_per_block);
-    hipLaunchKernelGGL(rowfinish_kernel<T>, dim3(blocks), dim3(256), 0, s, a, mode != Mode::Verify ? 1 : 0,
-                       mode != Mode::Quantify ? 1 : 0, rows_per_block, K, inline_windows ? accept_len : nullptr,
-                       inline_windows ? resampled_id : nullptr);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || mode == Mode::Quantify) return e;
-    if (a.row_id) {
+    if (args.N <= 0 || mode == Mode::Quantify) return hipSuccess;  // the streaming kernel has written every row's outputs
+    const bool want_windows = accept_len || resampled_id;
+    if (!plan.draws_inline && args.row_id) {
+        // the rows the streaming kernel has listed; windows inside its workgroups get their draw from here too
+        int32_t* const win = want_windows && plan.windows_inline ? resampled_id : nullptr;
         const int64_t cus = compute_units();
-        if (a.N >= 4 * cus) {
+        if (args.N >= 4 * cus) {
             // four 256-lane workgroups per compute unit walk over the rejected rows
-            hipLaunchKernelGGL((resample_kernel<T, 256>), dim3((unsigned)(4 * cus)), dim3(256), 0, s, a, K,
-                               inline_windows ? resampled_id : nullptr);
+            if (dtype == 0) hipLaunchKernelGGL((resample_kernel<float, 256>), dim3((unsigned)(4 * cus)), dim3(256), 0, stream, args, K, win);
+            else hipLaunchKernelGGL((resample_kernel<bf16_t, 256>), dim3((unsigned)(4 * cus)), dim3(256), 0, stream, args, K, win);
         } else {
             // very few rows (less than one rejected row per compute unit): 1024 lanes on each row
-            const unsigned grid = (unsigned)(a.N < cus ? a.N : cus);
-            hipLaunchKernelGGL((resample_kernel<T, 1024>), dim3(grid), dim3(1024), 0, s, a, K,
-                               inline_windows ? resampled_id : nullptr);
+            const unsigned grid = (unsigned)(args.N < cus ? args.N : cus);
+            if (dtype == 0) hipLaunchKernelGGL((resample_kernel<float, 1024>), dim3(grid), dim3(1024), 0, stream, args, K, win);
+            else hipLaunchKernelGGL((resample_kernel<bf16_t, 1024>), dim3(grid), dim3(1024), 0, stream, args, K, win);
         }
-        e = hipGetLastError();
+        const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    if (want_windows && !inline_windows)
-        return launch_windows(a.accept, a.row_id, a.N, K, accept_len, resampled_id, s);
+    if (want_windows && !plan.windows_inline && !plan.windows_counted)
+        return launch_windows(args.accept, args.row_id, args.N, K, accept_len, resampled_id, stream);
     return hipSuccess;
-}
-
-}  // namespace
-
-hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, bool rows_finished, int32_t K, int32_t* accept_len,
-                         int32_t* resampled_id, hipStream_t stream)
-{
-    if (args.N <= 0) return hipSuccess;
-    if (rows_finished && mode == Mode::Quantify) return hipSuccess;   // the streaming kernel has written every output
-    return dtype == 0 ? launch_finish_typed<float>(mode, args, K, accept_len, resampled_id, stream)
-                      : launch_finish_typed<bf16_t>(mode, args, K, accept_len, resampled_id, stream);
 }
 
 hipError_t launch_windows(const uint8_t* accept, const int32_t* row_id, int64_t N, int32_t K,

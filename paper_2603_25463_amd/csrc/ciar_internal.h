@@ -40,9 +40,21 @@ struct RowArgs {
     uint8_t* accept;                                 // [N] or null
     int32_t* row_id;                                 // [N] or null
     RowStats* stats;                                 // [N] workspace
-    int32_t* reject_list;                            // [N] workspace: rows whose drafted token was rejected
-    int32_t* reject_count;                           // workspace: length of that list
+    int32_t* reject_list;                            // [N] workspace: rejected rows whose draw resample_kernel makes
+    unsigned long long* reject_count;                // workspace: length of that list (see counter_add)
+    uint32_t tag;                                    // this launch's tag for such counters
     int32_t  finish;                                 // 1 = the streaming kernel also finishes its rows (quantify only)
+    // Verification inside the streaming kernel: the accept test, the residual draw of rejected rows from the
+    // registers that hold both rows, and the per-row outputs.  A workgroup walks over pieces of `unit` consecutive
+    // rows (unit = window: the kernel also writes the window outputs below; unit = 1: a window kernel follows).
+    int32_t  unit;
+    int32_t  window;                                 // K
+    int32_t* accept_len;                             // [ceil(N / K)] or null
+    int32_t* resampled_id;                           // [ceil(N / K)] or null
+    unsigned long long* win_words;                   // workspace: 16 bytes per row for the words below
+    unsigned long long* win_count;                   // win_words or null: windows that span workgroups are written by
+                                                     // whichever row of theirs is finished last (window w: the word at
+                                                     // byte 16 K w; see window_arrive)
     int32_t  precise_flat;                           // 1 = the streaming kernel marks flat rows for the fp64 pass (see
                                                      // needs_flat_pass)
     int64_t  N;
@@ -104,32 +116,35 @@ inline bool needs_flat_pass(const RowArgs& a)
 // Largest vocabulary the register-resident streaming kernels cover for an element size.
 int max_vocab(int dtype);
 
-// A quantify-only streaming launch finishes its own rows (score, flag, reported interval) when every workgroup
-// handles at most kMaxRowsPerWg rows: no finishing kernel, no second launch.  (With the verifier row in the same
-// launch the finishing stays in a kernel of its own: at the end of the streaming kernel it costs more than the
-// launch it saves is worth to the kernel's bandwidth figure.)
+// The streaming kernel finishes its own rows: after at most kMaxRowsPerWg rows a workgroup turns what it has parked
+// in LDS (statistics, accept decisions, draws) into the rows' outputs, one lane per row, and goes on streaming.
 constexpr int kMaxRowsPerWg = 128;
 
 // How a streaming launch over args.N rows would be shaped.
 struct StreamPlan {
     unsigned grid;        // workgroups
-    int rows_per_wg;      // ceil(N / grid)
-    bool can_finish;      // the launch is quantify-only and its shape allows the kernel to finish its rows
+    int rows_per_wg;      // most rows a workgroup handles
+    bool can_finish;      // the kernel finishes its rows (every output of a row but, unless windows_inline, the windows')
+    int unit;             // consecutive rows a workgroup takes at a time (launches with a verifier row: 1 or the window)
+    bool windows_inline;  // the kernel also writes accept_len / resampled_id (unit == window)
+    bool draws_inline;    // the kernel makes the residual draws of rejected rows itself (else resample_kernel follows)
+    bool windows_counted; // windows span workgroups, and the kernel still writes accept_len / resampled_id (RowArgs::win_count)
 };
-StreamPlan plan_stream(Mode mode, int dtype, const RowArgs& args);
+StreamPlan plan_stream(Mode mode, int dtype, const RowArgs& args, bool finish_rows = true);
 
-// Streaming pass over the rows: statistics and InterFuse sums into args.stats.  With finish_rows (and a plan that
-// allows it, see plan_stream) the kernel also produces the per-row outputs in args; args needs ids and the output
-// pointers then.
+// Streaming pass over the rows: statistics and InterFuse sums into args.stats.  A launch with a verifier row also
+// runs the accept test and the residual draws and writes every per-row output (and the window outputs if
+// plan_stream says windows_inline); a quantify-only launch writes its per-row outputs if finish_rows is set.
+// args needs ids, the uniforms, window and the output pointers accordingly.
 // ev_start / ev_stop (both or neither): events the kernel's dispatch records at its start and at its end.
 hipError_t launch_stream(Mode mode, int dtype, const RowArgs& args, bool finish_rows, hipStream_t stream,
                          hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
-// What remains after the streaming pass: the per-row finishing unless the streaming kernel has done it
-// (rows_finished), the residual draw of rejected rows, and the window outputs (either may be null) for windows of
-// K rows.
-hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, bool rows_finished, int32_t K, int32_t* accept_len,
-                         int32_t* resampled_id, hipStream_t stream);
+// What remains after a streaming pass that has finished its rows: the residual draws of the rejected rows where
+// the streaming kernel has only marked them (plan.draws_inline unset), and the window outputs (either may be null)
+// for windows of K rows unless the streaming kernel has written them too.
+hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, const StreamPlan& plan, int32_t K,
+                         int32_t* accept_len, int32_t* resampled_id, hipStream_t stream);
 
 // The fp64 pass over the rows the streaming kernel has marked as flat (see needs_flat_pass): rewrites their
 // RowStats; with finish_rows also their quantify outputs (for launches whose streaming kernel finishes its rows).

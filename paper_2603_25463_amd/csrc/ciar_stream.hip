@@ -53,6 +53,7 @@
 // order, so results are deterministic and the per-row scalars carry ~1e-8 relative error.
 #include "ciar_device.h"
 #include <hip/hip_ext.h>
+#include <type_traits>
 
 namespace ciar {
 namespace {
@@ -64,7 +65,7 @@ namespace {
 // unit rather than by fetching ahead into a second set of registers: measured on this chip, three or
 // four resident workgroups beat two with a register prefetch of the next row at every vocabulary size.
 // (Tensor-radius mode: the raw radius row sits in registers next to the centre row during the interval pass.)
-template <typename T, int THREADS, int NVEC, bool RAD>
+template <typename T, int THREADS, int NVEC, bool RAD, bool DO_V = false>
 constexpr int target_waves()
 {
     constexpr int ept = NVEC * Elt<T>::kPerVec;                    // one row as floats
@@ -298,9 +299,21 @@ __device__ __forceinline__ void fuse_sums_rad(const float (&e)[NVEC * Elt<T>::kP
     if constexpr (WIDE) { q5[5] = c1; q5[6] = c2; q5[7] = (double)big; }
 }
 
+// Whether a launch with a verifier row makes the residual draws of its rejected rows inside the streaming kernel:
+// where a second row fits in the registers at four waves per SIMD next to the centre row's floats (fp32 tiles of up
+// to 8 vectors per lane, scalar radius).
+template <typename T, int NVEC, bool DO_V, bool RAD, bool WIDE>
+constexpr bool draws_in_stream()
+{
+    return DO_V && !RAD && !WIDE && (NVEC * Elt<T>::kPerVec + NVEC * 4 + 56) * 4 <= 512;
+}
+
+// sm_draw / row_id of a rejected row whose draw is still to be made (by resample_kernel)
+constexpr int kDrawPending = -2;
+
 template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V, bool RAD, bool WIDE>
 __global__ __launch_bounds__(THREADS)
-__attribute__((amdgpu_waves_per_eu(target_waves<T, THREADS, NVEC, RAD>())))
+__attribute__((amdgpu_waves_per_eu(target_waves<T, THREADS, NVEC, RAD, DO_V>())))
 void stream_kernel(const RowArgs A)
 {
     using E = Elt<T>;
@@ -311,28 +324,43 @@ void stream_kernel(const RowArgs A)
     // The verifier row is requested before the interval pass where a second row fits in the registers at
     // four waves per SIMD next to the centre row's floats (fp32 tiles of up to 8 vectors per lane; measured
     // 51 -> 48.6 us on the benchmark); elsewhere it would spill, and it is requested after the pass.
-    constexpr bool EARLY_T = DO_V && !RAD && !WIDE && (EPT + NVEC * 4 + 56) * 4 <= 512;
+    constexpr bool EARLY_T = draws_in_stream<T, NVEC, DO_V, RAD, WIDE>();
     // Quantify-only launches have no verifier row; under the same condition the next centre row is requested
     // before the interval pass instead.
     constexpr bool EARLY_NEXT = !DO_V && !RAD && !WIDE && (EPT + NVEC * 4 + 56) * 4 <= 512;
+    // A rejected row's draw needs both rows.  Where the verifier row is requested early, the centre row's
+    // exponentials simply stay in their registers next to it and the draw is made here (KEEP_E).  Elsewhere (bf16
+    // tiles, tensor radius, wide radii) the two do not fit: such rows are only marked, and resample_kernel
+    // draws them behind this kernel (measured with the draw here and the centre row fetched again: the branch
+    // alone, never taken, cost the bf16 row loop 11 % -- registers and scheduling -- and workload 3 ran 318 against
+    // 285 us per step).
+    constexpr bool KEEP_E = draws_in_stream<T, NVEC, DO_V, RAD, WIDE>();
     constexpr int NQ = WIDE ? 8 : 5;                // interval sums a wave hands over
+    constexpr int NT = NVEC * NW;                   // pieces of a row in token order: (vector j, wave w) -> j NW + w
 
     // Exchange slots.  Two barriers per row order every write against every read: the centre-row
     // slots are written before the first and read between the two, the others are written between the
-    // two and read by thread 0 after the second, before it reaches the next row's first barrier.
-    __shared__ float  sm_ref[NW * 2];               // per wave: max centre logit, n_w
-    __shared__ double sm_S[NW];                     // per wave: S_w
+    // two and read after the second, before the next row's first barrier.
+    // (the centre-row slots exist twice and rows alternate between them: a row's write-up and its draw read them
+    // after the second barrier, when a wave that runs ahead may already be writing the next row's)
+    __shared__ float  sm_ref2[2][NW * 2];           // per wave: max centre logit, n_w
+    __shared__ double sm_S2[2][NW];                 // per wave: S_w
     __shared__ float  sm_nt[NW];                    // per wave: nt_w
     __shared__ double sm_Z[NW];                     // per wave: Z_w
     __shared__ double sm_q5[NW * NQ];               // per wave: the interval sums, already in row units
     __shared__ double sm_k[3];                      // the shift the sums are taken about (row units), from wave 0
     __shared__ float  sm_e0;                        // e of the row's first token, in the units of wave 0
-    // Finishing inside this kernel (quantify-only launches with A.finish): the statistics of the rows this workgroup
-    // has streamed and, fetched ahead, what their finishing needs from memory (the reported token's centre logit
-    // and raw radius).
-    constexpr bool CAN_FINISH = DO_Q && !DO_V;
-    __shared__ RowStats sm_rows[CAN_FINISH ? kMaxRowsPerWg : 1];
-    __shared__ float    sm_fx[CAN_FINISH ? kMaxRowsPerWg : 1][2];
+    // Finishing inside this kernel: the statistics of the rows this workgroup has streamed since its last
+    // finishing step (at most kMaxRowsPerWg of them) and, fetched ahead, what their finishing needs from memory:
+    // the reported token's centre logit, raw radius and verifier logit, the row's two uniforms.
+    __shared__ RowStats sm_rows[kMaxRowsPerWg];
+    __shared__ float    sm_fx[kMaxRowsPerWg][4];    // cx, rawx, tx, u_accept
+    __shared__ float    sm_ur[DO_V ? kMaxRowsPerWg : 1];
+    __shared__ int      sm_draw[DO_V ? kMaxRowsPerWg : 1];   // -1: the drafted token was accepted; else the row's draw
+    __shared__ uint8_t  sm_close[DO_V ? kMaxRowsPerWg : 1];  // the fp32 accept test could not decide the row
+    __shared__ double   sm_tab[DO_V ? NT : 1];      // residual mass of each piece of a rejected row
+    __shared__ float    sm_auxf[DO_V ? NW : 1];
+    __shared__ int      sm_auxi[DO_V ? NW : 1];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int V = A.V;
@@ -414,35 +442,190 @@ void stream_kernel(const RowArgs A)
         }
     };
 
-    // the list of rejected rows that the finishing kernels build starts empty
-    if (DO_V && blockIdx.x == 0 && tid == 0) *A.reject_count = 0;
+    // the list of rows that resample_kernel will draw starts empty: claim its counter for this launch
+    if constexpr (DO_V && !KEEP_E) {
+        if (blockIdx.x == 0 && tid == 0 && A.row_id) {
+            counter_add(A.reject_count, A.tag, 0u);
+            counter_add(A.reject_count + 1, A.tag, 0u);            // (resample_kernel's workgroups count themselves here)
+        }
+    }
 
-    // Finishing: lane t will finish the t-th row of this workgroup after the last row has been streamed.  What
-    // that needs from memory is requested now, ahead of the first row, and parked in LDS.
-    const bool finish = CAN_FINISH && A.finish;                    // uniform over the grid
-    const int my_rows = finish ? (nrows - (int)blockIdx.x + step - 1) / step : 0;   // <= kMaxRowsPerWg
-    float fx[2] = {0.f, 0.f};
-    if (tid < my_rows && A.ids) {
-        const int64_t r = (int64_t)blockIdx.x + (int64_t)tid * step;
-        int xid = A.ids[ids_index(A, r)];
-        xid = xid < 0 ? 0 : (xid >= V ? V - 1 : xid);
-        fx[0] = load_logit(static_cast<const T*>(A.draft) + row_offset(A, r), xid);
-        if constexpr (RAD) fx[1] = load_logit(static_cast<const T*>(A.radius) + row_offset(A, r), xid);
+    // ---- which rows this workgroup takes ---------------------------------------------------------------------
+    // Pieces of `unit` consecutive rows: piece blockIdx.x, blockIdx.x + gridDim.x, ...  (unit = 1, or the window
+    // length when this kernel also writes the window outputs).  The workgroup's rows are numbered L = 0, 1, 2, ...
+    // in the order it streams them; with finishing there are at most `cap` of them (whole pieces; the launcher sizes
+    // the grid accordingly), and after the last one one lane per row finishes it from what is parked in LDS.
+    const bool finish = (DO_V || A.finish) && (DO_Q || DO_V);      // uniform over the grid
+    const int unit = DO_V ? A.unit : 1;
+    const int cap = (kMaxRowsPerWg / unit) * unit;
+    auto row_of = [&](int L) -> int64_t {
+        const int u = L / unit;
+        return ((int64_t)blockIdx.x + (int64_t)u * step) * unit + (L - u * unit);
+    };
+    // What the finishing of rows L0 ... L0 + cap - 1 needs from memory (lane t: row L0 + t), in three steps so that
+    // the first row's own loads can go in between: fetch_ids requests the reported tokens, fetch_scalars (which
+    // waits for them) their logits and the uniforms, park_scalars (which waits for those) leaves them in LDS.
+    struct RowScalars { float cx, rawx, tx, ua, ur; bool live; };
+    auto fetch_ids = [&](int L0) {
+        const int64_t r = row_of(L0 + tid);
+        return (tid < cap && r < nrows && A.ids) ? A.ids[ids_index(A, r)] : 0;
+    };
+    auto fetch_scalars = [&](int L0, int xid) {
+        RowScalars f = {0.f, 0.f, 0.f, 0.f, 0.f, false};
+        const int64_t r = row_of(L0 + tid);
+        if (tid < cap && r < nrows) {
+            f.live = true;
+            if (A.ids) {
+                xid = xid < 0 ? 0 : (xid >= V ? V - 1 : xid);
+                f.cx = load_logit(static_cast<const T*>(A.draft) + row_offset(A, r), xid);
+                if constexpr (RAD) f.rawx = load_logit(static_cast<const T*>(A.radius) + row_offset(A, r), xid);
+                if constexpr (DO_V) f.tx = load_logit(static_cast<const T*>(A.target) + row_offset(A, r), xid);
+            }
+            if constexpr (DO_V) { f.ua = A.u_accept[r]; f.ur = A.u_resample[r]; }
+        }
+        return f;
+    };
+    auto park_scalars = [&](const RowScalars& f) {
+        if (f.live) {
+            sm_fx[tid][0] = f.cx; sm_fx[tid][1] = f.rawx; sm_fx[tid][2] = f.tx; sm_fx[tid][3] = f.ua;
+            if constexpr (DO_V) sm_ur[tid] = f.ur;
+        }
+    };
+    // Finishing of the rows L0 ... L0 + cnt - 1 from what is parked in LDS, two lanes per row in different waves so that
+    // the two halves run side by side: lane i < 128 writes row i's statistics and its quantifier outputs (Eq.
+    // uncertainty_score, the threshold of Algorithm 1), lane 128 + i its verification outputs; with unit == window
+    // also the outputs of the windows (Algorithm 1: the verified prefix of a drafted window and the token that
+    // replaces its first rejection).
+    auto finish_batch = [&](int L0, int cnt) {
+        static_assert(kMaxRowsPerWg == 128 && THREADS >= 256, "two lanes per parked row");
+        __syncthreads();
+        // (the lane index through an empty asm: otherwise the row indices below are the ones fetch_scalars formed
+        // before the first row, kept in registers or spilled for the whole of the row loop)
+        int ft = tid;
+        asm volatile("" : "+v"(ft));
+        const int i = ft & 127;                                    // the parked row this lane works on
+        const bool mine = ft < 256 && i < cnt;
+        const bool qjob = mine && ft < 128, vjob = DO_V && mine && ft >= 128;
+        const int64_t r = row_of(L0 + i);
+        if (qjob) {
+            const RowStats st = sm_rows[i];
+            A.stats[r] = st;
+            if constexpr (DO_Q) {
+                const float cx = A.ids ? sm_fx[i][0] : st.mc;      // no ids: the arg-max token is reported
+                finish_row(A, r, st, cx, 0.f, sm_fx[i][1], 0.f, true, false);
+            }
+        }
+        if constexpr (DO_V) {
+            bool pend = false;                                     // this lane's row still needs its draw
+            if (vjob) {
+                const RowStats& st = sm_rows[i];
+                if constexpr (KEEP_E) {
+                    // the row loop has decided in fp32 and drawn; rows it found too close to call are decided here
+                    if (sm_close[i] && !reject_exact(sm_fx[i][0], sm_fx[i][2], sm_fx[i][3], st.n, st.nt, st.S, st.Z))
+                        sm_draw[i] = -1;                           // accepted after all: the draw does not count
+                } else {
+                    // the accept test (Algorithm 1, "Cloud verification"); a rejected row's draw is resample_kernel's
+                    pend = reject_exact(sm_fx[i][0], sm_fx[i][2], sm_fx[i][3], st.n, st.nt, st.S, st.Z);
+                    sm_draw[i] = pend ? kDrawPending : -1;
+                    pend = pend && A.row_id;
+                }
+            }
+            uint32_t slot = 0;                                     // of this lane's row in the list of pending draws
+            if constexpr (!KEEP_E) {
+                // one addition to the list's counter per wave that has such rows; requested before the barrier, so
+                // that its way to memory and back overlaps with the other half of the finishing
+                const unsigned long long m = __ballot(pend);
+                if (m) {                                           // uniform over the wave
+                    const int leader = __builtin_amdgcn_readfirstlane(__ffsll((long long)m) - 1);
+                    const int l = ft & 63;
+                    uint32_t base = 0;
+                    if (l == leader) base = counter_add(A.reject_count, A.tag, (uint32_t)__popcll(m));
+                    base = (uint32_t)__builtin_amdgcn_readlane((int)base, leader);
+                    slot = base + (uint32_t)__popcll(m & ((1ull << l) - 1ull));
+                }
+            }
+            __syncthreads();                                       // the windows below read their rows' final draws
+            if (vjob) {
+                const int id = sm_draw[i];                         // -1, a draw, or kDrawPending
+                if constexpr (!KEEP_E) {
+                    if (pend && slot < (uint32_t)nrows) {          // (one entry per row at most)
+                        // list entry: the row, bit-complemented when its draw is also its window's (the first
+                        // rejection of a window that lies inside this workgroup)
+                        bool first = unit == A.window && A.resampled_id != nullptr;
+                        for (int k = i - i % unit; first && k < i; ++k) first = sm_draw[k] == -1;
+                        A.reject_list[slot] = first ? ~(int32_t)r : (int32_t)r;
+                    }
+                }
+                if (A.accept) A.accept[r] = (uint8_t)(id == -1);
+                if (A.row_id) A.row_id[r] = id;
+                const int K = A.window;
+                if (unit == K && !A.win_count && (A.accept_len || A.resampled_id) && i % K == 0) {   // pieces start at multiples of K
+                    const int64_t left = nrows - r;
+                    const int len = (int)(left < K ? left : K);
+                    int m = 0;
+                    while (m < len && sm_draw[i + m] == -1) ++m;
+                    if (A.accept_len) A.accept_len[r / K] = m;
+                    // (a pending draw: resample_kernel writes the window's entry when it has drawn that row)
+                    if (A.resampled_id && (m == len || sm_draw[i + m] != kDrawPending))
+                        A.resampled_id[r / K] = m < len ? sm_draw[i + m] : -1;
+                }
+                if constexpr (KEEP_E) {
+                    const int64_t w = r / K, lo = w * K;
+                    if (A.win_count && (i == 0 || r == lo)) {
+                        // A window that spans workgroups: the consecutive rows of it that this workgroup holds arrive
+                        // together in the window's 64-bit word (window_arrive), from the lane of the first of them,
+                        // and the arrival that completes the window writes its outputs.
+                        const int len = (int)(nrows - lo < K ? nrows - lo : K);
+                        int rows = 0, off = 0, mine_id = -1;
+                        for (; i + rows < cnt && r + rows < lo + len; ++rows) {
+                            if (mine_id < 0 && sm_draw[i + rows] >= 0) { mine_id = sm_draw[i + rows]; off = (int)(r + rows - lo); }
+                        }
+                        int first, draw;
+                        if (window_arrive(A.win_count + 2 * lo, A.tag, rows, off, mine_id, len, first, draw)) {
+                            if (A.accept_len) A.accept_len[w] = first < 0 ? len : first;
+                            if (A.resampled_id) A.resampled_id[w] = first < 0 ? -1 : draw;
+                        }
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    };
+
+    // This workgroup's rows: its pieces are whole except possibly the very last piece of the launch.
+    int my_rows;
+    {
+        const int64_t pieces = ((int64_t)nrows + unit - 1) / unit;
+        const int64_t mine = (int64_t)blockIdx.x < pieces ? (pieces - blockIdx.x + step - 1) / step : 0;
+        const bool owns_last = mine > 0 && (pieces - 1 - (int64_t)blockIdx.x) % step == 0;
+        my_rows = (int)(mine * unit - (owns_last ? pieces * unit - nrows : 0));
     }
 
     // The row index is uniform over the workgroup: keep it in a scalar register.
     // A row's centre logits are loaded and worked on first, its verifier logits second: the centre row
     // carries most of the arithmetic (both of its passes), the verifier row only a short one, so
     // little work is left when the last bytes of the launch arrive.
-    int row = __builtin_amdgcn_readfirstlane((int)blockIdx.x);     // the launcher keeps gridDim.x <= N
+    // The launcher sizes the grid so that a workgroup has at most `cap` rows: they are finished after the last one,
+    // when nothing of a row is held in registers any more.
+    constexpr int L0 = 0;
+    const int cnt = min(cap, my_rows);                             // uniform
+    if (cnt <= 0) return;
+    int row = __builtin_amdgcn_readfirstlane((int)row_of(L0));
+    int in_piece = 0;                                              // rows of the current piece already taken
+    const int piece_jump = __builtin_amdgcn_readfirstlane((step - 1) * unit + 1);   // last row of a piece -> first of the next
+    int first_id = 0;
+    if (finish) first_id = fetch_ids(L0);                          // a small load, issued ahead of the first row's
     u32x4 buf[NVEC];                                               // a row as loaded: centre and verifier row in turn
     load_row(buf, A.draft, row);
-    if (tid < my_rows) { sm_fx[tid][0] = fx[0]; sm_fx[tid][1] = fx[1]; }   // waits for the small loads only: issued first
-    int done = 0;                                                  // rows this workgroup has streamed
+    // (the logits of the reported tokens are requested behind the row, once their ids are there, and parked when
+    // they arrive: that waits for the row as well, which the first pass needs anyway)
+    if (finish) park_scalars(fetch_scalars(L0, first_id));
 
-    for (;;) {
-        const int next = __builtin_amdgcn_readfirstlane(row + step);
-        const bool has_next = next < nrows;                        // uniform
+    for (int done = 0;; ++done) {                                  // done = rows of this batch already streamed
+        const bool has_next = done + 1 < cnt;                      // uniform
+        // (the rows are walked without a division: within a piece the next row, at its end the next piece)
+        in_piece = in_piece + 1 == unit ? 0 : in_piece + 1;
+        const int next = __builtin_amdgcn_readfirstlane(has_next ? (in_piece == 0 ? row + piece_jump : row + 1) : row);
         float raw0 = 0.f;                                          // raw radius of the row's first token
         if constexpr (RAD && DO_Q) raw0 = load_logit(static_cast<const T*>(A.radius) + row_offset(A, row), 0);
 
@@ -480,6 +663,8 @@ void stream_kernel(const RowArgs A)
         }
 
         // ---- the waves exchange the centre row's statistics ----------------------------------------------
+        float (&sm_ref)[NW * 2] = sm_ref2[done & 1];
+        double (&sm_S)[NW] = sm_S2[done & 1];
         if (lane == 0) {
             sm_ref[wave * 2] = mcw; sm_ref[wave * 2 + 1] = nw;
             sm_S[wave] = Sw;
@@ -491,26 +676,31 @@ void stream_kernel(const RowArgs A)
         // nothing); with four a short loop is as quick (measured).
         constexpr bool LANES = NW >= 8;
         const int src = lane < NW ? lane : 0;
+        // (by_lanes: across the first lanes of the wave, which must all be active; else in a loop)
+        auto combine_S = [&](auto by_lanes, float& mc, float& n, double& S) {
+            if constexpr (decltype(by_lanes)::value) {
+                const float mc_l = sm_ref[src * 2], n_l = sm_ref[src * 2 + 1];
+                mc = row16_max(mc_l); n = row16_max(n_l);
+                S = row16_sum(lane < NW && n_l != -INFINITY ? sm_S[src] * pow2_of(n_l - n) : 0.0);
+            } else {
+                mc = sm_ref[0]; n = sm_ref[1];
+#pragma unroll
+                for (int w = 1; w < NW; ++w) {
+                    mc = fmaxf(mc, sm_ref[w * 2]);
+                    n = fmaxf(n, sm_ref[w * 2 + 1]);
+                }
+                S = 0.0;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) {
+                    const float rn = sm_ref[w * 2 + 1];
+                    if (rn != -INFINITY) S += sm_S[w] * pow2_of(rn - n);
+                }
+            }
+        };
         float mc, n;
         double S;                                                  // in units of 2^-n
-        if constexpr (LANES) {
-            const float mc_l = sm_ref[src * 2], n_l = sm_ref[src * 2 + 1];
-            mc = row16_max(mc_l); n = row16_max(n_l);
-            S = row16_sum(lane < NW && n_l != -INFINITY ? sm_S[src] * pow2_of(n_l - n) : 0.0);
-        } else {
-            mc = sm_ref[0]; n = sm_ref[1];
-#pragma unroll
-            for (int w = 1; w < NW; ++w) {
-                mc = fmaxf(mc, sm_ref[w * 2]);
-                n = fmaxf(n, sm_ref[w * 2 + 1]);
-            }
-            S = 0.0;
-#pragma unroll
-            for (int w = 0; w < NW; ++w) {
-                const float rn = sm_ref[w * 2 + 1];
-                if (rn != -INFINITY) S += sm_S[w] * pow2_of(rn - n);
-            }
-        }
+        combine_S(std::integral_constant<bool, LANES>{}, mc, n, S);
+        const float Sf = (float)S;                                 // for the accept test (see accept_quick)
         const double fw = nw == -INFINITY ? 0.0 : pow2_of(nw - n);     // this wave's e_i are 1/fw too large
 
         // ---- C: InterFuse sums in this wave's units, rescaled to row units by lane 0 of the wave ---------
@@ -667,9 +857,9 @@ void stream_kernel(const RowArgs A)
             }
         }
 
-        // ---- T: verifier row statistics, per wave; the row is not kept -------------------------------------
+        // ---- T: verifier row statistics, per wave -----------------------------------------------------------
+        float ntw = -INFINITY;                                     // the reference this wave's Z_w is taken about
         if constexpr (DO_V) {
-            float ntw;
             double Zw;
             if constexpr (!EARLY_T) {
                 // no registers to spare next to the interval pass: the verifier row is fetched only now
@@ -679,8 +869,9 @@ void stream_kernel(const RowArgs A)
             verifier_stats(buf, nw, ntw, Zw);
             if (lane == 0) { sm_nt[wave] = ntw; sm_Z[wave] = Zw; }
         }
-        // the next centre row goes in flight before the barrier and thread 0's bookkeeping
-        if constexpr (!EARLY_NEXT) {
+        // The next centre row goes in flight before the barrier and thread 0's bookkeeping -- except where this
+        // kernel makes the draws: there both rows stay in the registers until the accept test has been decided (below).
+        if constexpr (!EARLY_NEXT && !KEEP_E) {
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (DO_V) {
                 if (has_next) load_row(buf, A.draft, next);
@@ -689,43 +880,241 @@ void stream_kernel(const RowArgs A)
             }
         }
 
-        // ---- wave 0 leaves the row's ten numbers for the finishing kernels -----------------------------------
+        __syncthreads();
+
+        // ---- verification of the drafted token, in every wave alike (Algorithm 1, "Cloud verification") ----------
+        // Z and its reference over the waves; the accept test; on a rejection the draw from (q - p)+ by inverse CDF
+        // in token order, from the registers: e[] still holds the centre row's exponentials, buf the verifier row.
+        // Z and its reference over the waves, exactly (fp64): wanted by the lane that writes the row up and by a draw
+        // (by_lanes: across the first lanes of the wave, which must all be active; else in a loop)
+        auto combine_Z = [&](auto by_lanes, float& nt, double& Z) {
+            nt = -INFINITY;
+            Z = 0.0;                                               // in units of 2^-nt
+            if constexpr (decltype(by_lanes)::value) {
+                const float nt_l = sm_nt[src];
+                nt = row16_max(nt_l);
+                Z = row16_sum(lane < NW && nt_l != -INFINITY ? sm_Z[src] * pow2_of(nt_l - nt) : 0.0);
+            } else {
+#pragma unroll
+                for (int w = 0; w < NW; ++w) nt = fmaxf(nt, sm_nt[w]);
+#pragma unroll
+                for (int w = 0; w < NW; ++w) {
+                    const float rt = sm_nt[w];
+                    if (rt != -INFINITY) Z += sm_Z[w] * pow2_of(rt - nt);
+                }
+            }
+        };
+        // (Where resample_kernel makes the draws nothing in this loop depends on the accept test: the lane that
+        // finishes the row evaluates it, in fp64.)
+        if constexpr (DO_V && KEEP_E) {
+            // for the accept test in fp32 a float Z does (every wave evaluates it: kept short)
+            float ntq = -INFINITY, Zq = 0.f;
+            if constexpr (LANES) {
+                const float nt_l = sm_nt[src];
+                ntq = row16_max(nt_l);
+                Zq = row16_sum_f(lane < NW && nt_l != -INFINITY ? ldexpf((float)sm_Z[src], (int)fmaxf(nt_l - ntq, -200.f)) : 0.f);
+            } else {
+#pragma unroll
+                for (int w = 0; w < NW; ++w) ntq = fmaxf(ntq, sm_nt[w]);
+#pragma unroll
+                for (int w = 0; w < NW; ++w) {
+                    const float rt = sm_nt[w];
+                    if (rt != -INFINITY) Zq += ldexpf((float)sm_Z[w], (int)fmaxf(rt - ntq, -200.f));
+                }
+            }
+            const float cx = sm_fx[done][0], tx = sm_fx[done][2], ua = sm_fx[done][3];
+            // 1 = accepted, 0 = rejected, -1 = too close to call in fp32: then the draw is made as well, and the
+            // lane that finishes the row decides in fp64 whether it counts (about one row in a few thousand)
+            const int verdict = accept_quick(cx, tx, ua, n, ntq, Sf, Zq);
+            if (tid == 0) sm_close[done] = (uint8_t)(verdict < 0);
+            if (verdict > 0) {
+                if (tid == 0) sm_draw[done] = -1;
+            } else {
+                // p_i = e_i pfac, q_i = 2^(t_i log2e - ntw) qfac, res_i = max(0, q_i - p_i) rounded to fp32: every
+                // partial sum below is a sum of those floats, so that the totals of the pieces and the running sum
+                // inside the piece that holds u R are sums of the same numbers
+                // (the lane index goes through an empty asm, so that nothing of this branch is computed ahead of the
+                // row loop and kept in registers, or spilled, for all of it)
+                int dt = tid;
+                asm volatile("" : "+v"(dt));
+                const int dlane = dt & 63, dwave = dt >> 6;
+                // the row's scalars again, from the exchange slots (nothing of them is kept in registers for this
+                // branch; the slots are this row's until the next row's second barrier)
+                float dmc, n, nt;
+                double S, Z;
+                combine_S(std::integral_constant<bool, LANES>{}, dmc, n, S);
+                combine_Z(std::integral_constant<bool, LANES>{}, nt, Z);
+                const float nw = sm_ref[dwave * 2 + 1], ntw = sm_nt[dwave];
+                const double fw = nw == -INFINITY ? 0.0 : pow2_of(nw - n);
+                const double pfac = fw / S;
+                float ntref = ntw == -INFINITY ? 0.f : ntw;
+                // (opaque to the optimiser, like e below: it would otherwise keep the streaming passes' conversions
+                // and exponentials of every token alive for this branch, in registers the hot path does not have)
+                asm volatile("" : "+v"(ntref));
+                const double qfac = (ntw == -INFINITY ? 0.0 : pow2_of(ntw - nt)) / Z;
+                auto residuals = [&](int j, float (&r)[EPV]) {
+                    float tv[EPV];
+                    E::unpack(buf[j], tv);
+#pragma unroll
+                    for (int k = 0; k < EPV; ++k) {
+                        float ek = e[j * EPV + k];
+                        asm volatile("" : "+v"(ek));
+                        const double p = __dmul_rn((double)ek, pfac);
+                        r[k] = (float)fmax(fma((double)exp2_ref(tv[k], ntref), qfac, -p), 0.0);
+                    }
+                };
+#pragma unroll
+                for (int j = 0; j < NVEC; ++j) {
+                    double ws = 0.0;
+                    if (j * CHUNK < V) {                           // uniform: the vector holds tokens
+                        float r[EPV];
+                        residuals(j, r);
+                        float s = 0.f;
+#pragma unroll
+                        for (int k = 0; k < EPV; ++k) s += r[k];
+                        ws = wave_sum((double)s);
+                    }
+                    if (dlane == 0) sm_tab[j * NW + dwave] = ws;
+                }
+                __syncthreads();
+                // every wave locates the piece that holds u R: lane l takes piece l (and l + 64), an inclusive scan
+                // over the lanes gives the running sums in token order, a ballot the first one above u R
+                constexpr int PER = (NT + 63) / 64;
+                double tot[PER], run[PER], carry = 0.0;
+                auto lane_value = [&](double v, int from) {
+                    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), from),
+                                            __builtin_amdgcn_readlane(__double2loint(v), from));
+                };
+#pragma unroll
+                for (int p = 0; p < PER; ++p) {
+                    const int idx = p * 64 + dlane;
+                    tot[p] = idx < NT ? sm_tab[idx] : 0.0;
+                    run[p] = wave_scan(tot[p]) + carry;
+                    carry = lane_value(run[p], 63);
+                }
+                const double R = carry;
+                const float ur = sm_ur[done];
+                if (R > 0.0) {
+                    const double thr = (double)ur * R;
+                    int istar = -1;
+                    double before = 0.0;
+                    double prev_end = 0.0;                         // running sum at the end of the part before
+#pragma unroll
+                    for (int p = 0; p < PER; ++p) {
+                        const unsigned long long cross = __ballot(p * 64 + dlane < NT && run[p] > thr);
+                        if (istar < 0 && cross) {
+                            const int l = __builtin_amdgcn_readfirstlane(__ffsll((long long)cross) - 1);
+                            istar = p * 64 + l;
+                            before = l > 0 ? lane_value(run[p], l - 1) : prev_end;
+                        }
+                        prev_end = lane_value(run[p], 63);
+                    }
+                    if (istar < 0) {                               // unreachable for u < 1; keeps the draw valid
+#pragma unroll
+                        for (int p = 0; p < PER; ++p) {
+                            const unsigned long long live = __ballot(p * 64 + dlane < NT && tot[p] > 0.0);
+                            if (live) istar = p * 64 + __builtin_amdgcn_readfirstlane(63 - __clzll((long long)live));
+                        }
+                        before = R;
+                    }
+                    const int wstar = istar % NW, jstar = istar / NW;
+                    if (dwave == wstar) {
+                        int cand = INT_MAX, lastpos = -1;
+#pragma unroll
+                        for (int j = 0; j < NVEC; ++j) {
+                            if (j == jstar) {                      // uniform; the register arrays keep constant indices
+                                float r[EPV];
+                                residuals(j, r);
+                                float s = 0.f;
+#pragma unroll
+                                for (int k = 0; k < EPV; ++k) s += r[k];
+                                const double incl = wave_scan((double)s);
+                                double cum = before + (incl - (double)s);
+                                // smallest token of the piece whose inclusive running sum exceeds u R; tokens without
+                                // residual mass cannot be drawn; lastpos covers a crossing lost to rounding at its end
+                                const int base = (j * THREADS + dt) * EPV;
+#pragma unroll
+                                for (int k = 0; k < EPV; ++k) {
+                                    cum += (double)r[k];
+                                    if (r[k] > 0.f) {
+                                        lastpos = base + k;
+                                        if (cum > thr && cand == INT_MAX) cand = base + k;
+                                    }
+                                }
+                            }
+                        }
+                        cand = wave_min_i(cand);
+                        lastpos = wave_max_i(lastpos);
+                        if (dlane == 0) {
+                            const int id = cand != INT_MAX ? cand : lastpos;
+                            sm_draw[done] = id < 0 ? 0 : id;
+                        }
+                    }
+                } else {
+                    // every residual rounded to zero (q == p to working precision): the draw degenerates to the
+                    // lowest-index arg-max of q, which is that of the verifier logits; practically never taken
+                    float mt = -INFINITY;
+#pragma unroll
+                    for (int j = 0; j < NVEC; ++j) {
+                        float tv[EPV];
+                        E::unpack(buf[j], tv);
+#pragma unroll
+                        for (int k = 0; k < EPV; ++k) mt = fmaxf(mt, tv[k]);
+                    }
+                    mt = wave_max(mt);
+                    if (dlane == 0) sm_auxf[dwave] = mt;
+                    __syncthreads();
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) mt = fmaxf(mt, sm_auxf[w]);
+                    int ci = INT_MAX;
+#pragma unroll
+                    for (int j = 0; j < NVEC; ++j) {
+                        float tv[EPV];
+                        E::unpack(buf[j], tv);
+#pragma unroll
+                        for (int k = 0; k < EPV; ++k) {
+                            const int tok = (j * THREADS + dt) * EPV + k;
+                            if (tv[k] == mt && tok < V) ci = min(ci, tok);
+                        }
+                    }
+                    ci = wave_min_i(ci);
+                    if (dlane == 0) sm_auxi[dwave] = ci;
+                    __syncthreads();
+                    if (dt == 0) {
+                        int c0 = sm_auxi[0];
+#pragma unroll
+                        for (int w = 1; w < NW; ++w) c0 = min(c0, sm_auxi[w]);
+                        sm_draw[done] = c0 == INT_MAX ? 0 : c0;
+                    }
+                }
+            }
+            // both rows are spent: the next centre row goes in flight
+            __builtin_amdgcn_sched_barrier(0);
+            if (has_next) load_row(buf, A.draft, next);
+        }
+
+        // ---- wave 0 leaves the row's ten numbers for the finishing -------------------------------------------------
         // Sixteen waves: their results are combined across the first lanes as above; fewer: by lane 0 in a loop
         // (as quick, measured).  Handing this job from wave to wave in turn measured slower.
-        __syncthreads();
         if (wave == 0 && (NW >= 16 || lane == 0)) {
-            float nt = -INFINITY;
-            double Z = 0.0;                                        // in units of 2^-nt
+            float mc, n, nt = -INFINITY;
+            double S, Z = 0.0;
+            combine_S(std::integral_constant<bool, (NW >= 16)>{}, mc, n, S);
+            if constexpr (DO_V) combine_Z(std::integral_constant<bool, (NW >= 16)>{}, nt, Z);
             double t[NQ];
 #pragma unroll
             for (int i = 0; i < NQ; ++i) t[i] = 0.0;
             double K[3] = {0.0, 0.0, 0.0};
             if constexpr (DO_Q) { K[0] = sm_k[0]; K[1] = sm_k[1]; K[2] = sm_k[2]; }
             // the waves' interval sums are about one common shift (wave 0 left it in row units): they simply add
-            if constexpr (NW >= 16) {
-                if constexpr (DO_V) {
-                    const float nt_l = sm_nt[src];
-                    nt = row16_max(nt_l);
-                    Z = row16_sum(lane < NW && nt_l != -INFINITY ? sm_Z[src] * pow2_of(nt_l - nt) : 0.0);
-                }
-                if constexpr (DO_Q) {
+            if constexpr (DO_Q) {
+                if constexpr (NW >= 16) {
 #pragma unroll
                     for (int i = 0; i < NQ; ++i) {
                         const double mine = lane < NW ? sm_q5[src * NQ + i] : 0.0;
                         t[i] = i == 7 ? (double)row16_max((float)mine) : row16_sum(mine);
                     }
-                }
-            } else {
-                if constexpr (DO_V) {
-#pragma unroll
-                    for (int w = 0; w < NW; ++w) nt = fmaxf(nt, sm_nt[w]);
-#pragma unroll
-                    for (int w = 0; w < NW; ++w) {
-                        const float rt = sm_nt[w];
-                        if (rt != -INFINITY) Z += sm_Z[w] * pow2_of(rt - nt);
-                    }
-                }
-                if constexpr (DO_Q) {
+                } else {
 #pragma unroll
                     for (int i = 0; i < NQ; ++i) {
 #pragma unroll
@@ -740,7 +1129,7 @@ void stream_kernel(const RowArgs A)
                 st->S = S; st->Z = Z; st->n = n; st->nt = nt; st->mc = mc;
                 float mode = (capless && !WIDE) ? kSumsWidthOnly : kSumsFull;
                 if constexpr (WIDE && DO_Q) {
-                    // every width above 1/2 and both caps inactive: the finishing kernels read the complement sums
+                    // every width above 1/2 and both caps inactive: the finishing reads the complement sums
                     if (t[7] < kComplementBelow) {
                         const RowScore rs = finish_score(t, S, kSumsFull, A, K[0], K[1]);
                         if (rs.alpha_l == 1.0 && rs.alpha_u == 1.0) {
@@ -755,28 +1144,16 @@ void stream_kernel(const RowArgs A)
                 st->mode = mode;
 #pragma unroll
                 for (int i = 0; i < 5; ++i) st->q[i] = t[i];
-                // with finishing the statistics stay in LDS until the end (lane `done` writes them out then)
+                // with finishing the statistics stay in LDS until the batch is finished
                 if (finish) sm_rows[done] = stv;
                 else A.stats[row] = stv;
             }
         }
 
-        ++done;
         if (!has_next) break;
         row = next;
     }
-
-    // ---- finishing (quantify-only): one lane per row of this workgroup ------------------------------------------
-    if (finish) {
-        __syncthreads();
-        if (tid < my_rows) {
-            const int64_t r = (int64_t)blockIdx.x + (int64_t)tid * step;
-            const RowStats st = sm_rows[tid];
-            A.stats[r] = st;
-            const float cx = A.ids ? sm_fx[tid][0] : st.mc;        // no ids: the arg-max token is reported
-            finish_row(A, r, st, cx, 0.f, sm_fx[tid][1], 0.f, true, false);
-        }
-    }
+    if (finish) finish_batch(L0, cnt);
 }
 
 // ---- dispatch ---------------------------------------------------------------------------------------------
@@ -784,39 +1161,66 @@ void stream_kernel(const RowArgs A)
 // A launch request: with `launch` unset the dispatch below only reports the grid it would use.
 struct StreamLaunch {
     bool launch;
-    bool finish_rows;      // the caller wants the kernel to finish its rows if the shape allows it
+    bool finish_rows;      // the caller wants the kernel to finish its rows (launches with a verifier row always do)
     hipStream_t stream;
     StreamPlan plan;       // out
     hipEvent_t ev_start, ev_stop;   // both or neither: recorded by the dispatch at the kernel's start and end
 };
 
-StreamPlan make_plan(int64_t N, int64_t resident)
-{
-    StreamPlan p;
-    p.grid = (unsigned)(N < resident ? N : resident);
-    p.rows_per_wg = (int)((N + p.grid - 1) / p.grid);
-    p.can_finish = p.rows_per_wg <= kMaxRowsPerWg;
-    return p;
-}
-
 template <typename T, int THREADS, int NVEC, bool DO_Q, bool DO_V, bool RAD, bool WIDE = false>
 hipError_t launch_stream_kernel(const RowArgs& a, StreamLaunch& L)
 {
-    // One wave of resident workgroups, each walking over rows with stride gridDim.x.  The register
+    // One wave of resident workgroups, each walking over its pieces of rows with stride gridDim.x.  The register
     // budget the kernel was compiled for fixes how many fit: target_waves() waves per SIMD, and a
     // workgroup puts THREADS / 256 waves on each of the four SIMDs of a compute unit (a 128-lane one: one
     // wave on two of them).
-    constexpr int per_cu = target_waves<T, THREADS, NVEC, RAD>() * 256 / THREADS;
-    L.plan = make_plan(a.N, (int64_t)per_cu * compute_units());
-    L.plan.can_finish = L.plan.can_finish && DO_Q && !DO_V;
+    constexpr int per_cu = target_waves<T, THREADS, NVEC, RAD, DO_V>() * 256 / THREADS;
+    const int64_t resident = (int64_t)per_cu * compute_units();
+    const int64_t N = a.N;
+    // (at most kMaxRowsPerWg rows per workgroup: beyond that many rows per resident workgroup the grid grows instead)
+    auto grid_for = [&](int64_t pieces, int64_t per_wg) {
+        const int64_t g = pieces < resident ? pieces : resident, need = (pieces + per_wg - 1) / per_wg;
+        return g > need ? g : need;
+    };
+    const int64_t grid1 = grid_for(N, kMaxRowsPerWg), max1 = (N + grid1 - 1) / grid1;
+    StreamPlan& p = L.plan;
+    p.unit = 1;
+    p.grid = (unsigned)grid1;
+    p.rows_per_wg = (int)max1;
+    p.windows_inline = false;
+    if (DO_V && (a.accept_len || a.resampled_id) && a.window >= 1 && a.window <= kMaxRowsPerWg) {
+        // Whole windows per workgroup, so that the kernel writes the window outputs as well, unless that would leave
+        // the busiest workgroup with noticeably more rows than a row-by-row split (few windows on many compute units)
+        const int64_t K = a.window, units = (N + K - 1) / K;
+        const int64_t gridk = grid_for(units, kMaxRowsPerWg / K), maxk = (units + gridk - 1) / gridk * K;
+        if (maxk <= max1 + max1 / 8) {
+            p.unit = (int)K;
+            p.grid = (unsigned)gridk;
+            p.rows_per_wg = (int)maxk;
+            p.windows_inline = true;
+        }
+    }
+    p.can_finish = DO_V || L.finish_rows;
+    p.draws_inline = draws_in_stream<T, NVEC, DO_V, RAD, WIDE>();
+    // Windows that span workgroups: where this kernel knows every row's draw it can still write the window outputs,
+    // from the lane that finishes a window's last row (one 64-bit word per window in the workspace, see window_arrive).
+    p.windows_counted = p.draws_inline && a.win_words && (a.accept_len || a.resampled_id) && !p.windows_inline && a.window >= 2 &&
+                        a.window <= kMaxCountedWindow;
+    if (p.windows_counted) {
+        // consecutive rows per workgroup (one piece each): a window then meets in as few arrivals as possible
+        p.unit = (int)max1;
+        p.grid = (unsigned)((N + max1 - 1) / max1);
+    }
     if (!L.launch) return hipSuccess;
     RowArgs b = a;
-    b.finish = (L.finish_rows && L.plan.can_finish) ? 1 : 0;
+    b.finish = p.can_finish ? 1 : 0;
+    b.unit = p.unit;
+    b.win_count = p.windows_counted ? a.win_words : nullptr;
     if (L.ev_start && L.ev_stop)
-        hipExtLaunchKernelGGL((stream_kernel<T, THREADS, NVEC, DO_Q, DO_V, RAD, WIDE>), dim3(L.plan.grid), dim3(THREADS),
+        hipExtLaunchKernelGGL((stream_kernel<T, THREADS, NVEC, DO_Q, DO_V, RAD, WIDE>), dim3(p.grid), dim3(THREADS),
                               0, L.stream, L.ev_start, L.ev_stop, 0, b);
     else
-        hipLaunchKernelGGL((stream_kernel<T, THREADS, NVEC, DO_Q, DO_V, RAD, WIDE>), dim3(L.plan.grid), dim3(THREADS), 0,
+        hipLaunchKernelGGL((stream_kernel<T, THREADS, NVEC, DO_Q, DO_V, RAD, WIDE>), dim3(p.grid), dim3(THREADS), 0,
                            L.stream, b);
     return hipGetLastError();
 }
@@ -854,11 +1258,12 @@ hipError_t launch_stream_typed(Mode mode, const RowArgs& a, StreamLaunch& s)
     if (vecs <= 256 * 16) {
         // Few rows: eight waves on a row keep the last rows of the launch short and the grid even; with many
         // rows the four-wave tile has less exchange overhead (measured).  For bf16 the four-wave tile would
-        // hold 128 floats per lane and spill: eight waves always.
+        // hold 128 floats per lane and spill: eight waves always.  The same goes for launches with a verifier
+        // row, which keep both rows in the registers until the accept test is decided.
         if constexpr (sizeof(T) == 2) {
             return launch_stream_cfg<T, 512, 8>(mode, a, s);
         } else {
-            if (a.N < 12 * (int64_t)compute_units()) return launch_stream_cfg<T, 512, 8>(mode, a, s);
+            if (mode != Mode::Quantify || a.N < 12 * (int64_t)compute_units()) return launch_stream_cfg<T, 512, 8>(mode, a, s);
             return launch_stream_cfg<T, 256, 16>(mode, a, s);
         }
     }
@@ -870,9 +1275,9 @@ hipError_t launch_stream_typed(Mode mode, const RowArgs& a, StreamLaunch& s)
 
 int max_vocab(int dtype) { return dtype == 0 ? 1024 * 8 * 4 : 1024 * 8 * 8; }
 
-StreamPlan plan_stream(Mode mode, int dtype, const RowArgs& args)
+StreamPlan plan_stream(Mode mode, int dtype, const RowArgs& args, bool finish_rows)
 {
-    StreamLaunch L{false, false, nullptr, {0u, 0, false}, nullptr, nullptr};
+    StreamLaunch L{false, finish_rows, nullptr, {0u, 0, false, 1, false, false, false}, nullptr, nullptr};
     if (args.N > 0) {
         if (dtype == 0) (void)launch_stream_typed<float>(mode, args, L);
         else (void)launch_stream_typed<bf16_t>(mode, args, L);
@@ -884,7 +1289,7 @@ hipError_t launch_stream(Mode mode, int dtype, const RowArgs& args, bool finish_
                          hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     if (args.N <= 0) return hipSuccess;
-    StreamLaunch L{true, finish_rows, stream, {0u, 0, false}, ev_start, ev_stop};
+    StreamLaunch L{true, finish_rows, stream, {0u, 0, false, 1, false, false, false}, ev_start, ev_stop};
     return dtype == 0 ? launch_stream_typed<float>(mode, args, L)
                       : launch_stream_typed<bf16_t>(mode, args, L);
 }

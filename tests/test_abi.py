@@ -168,7 +168,7 @@ def test_workspace_size(L):
     assert f(0, ctypes.byref(p)) == 0 and f(-5, ctypes.byref(p)) == 0
     for N in (1, 7, 256, 2048, 32768):
         b = f(N, ctypes.byref(p))
-        assert b % 256 == 0 and b >= 97 * N
+        assert b % 256 == 0 and b >= 113 * N
 
 
 def test_version_and_error_strings(L):

@@ -689,19 +689,23 @@ def test_row_counts_around_the_block_sizes(ciar, oracle, N):
               tag=f"row count N={N}")
 
 
-def test_calls_replay_from_a_captured_graph(ciar):
+@pytest.mark.parametrize("dtype,N,K", [(torch.float32, 300, 8), (torch.bfloat16, 300, 8), (torch.float32, 3000, 8),
+                                       (torch.bfloat16, 37, 5)])
+def test_calls_replay_from_a_captured_graph(ciar, dtype, N, K):
     """The library allocates nothing, records no memset and never synchronises, so a call can be captured into
     a HIP graph.  Replays (with eager work and synchronisation between them, and the inputs changed between
-    replays) must reproduce the eager results bit for bit."""
-    c, t, ids, ua, ur = _random_case(16384, 16384, 300, 8, torch.float32, seed=41)
-    c2, t2, *_ = _random_case(16384, 16384, 300, 8, torch.float32, seed=42)
-    say("[graph] V=16384 N=300: capture ciar_quantify_verify, replay 4 times on alternating inputs")
-    P = ciar.Params(tau=0.01)
+    replays) must reproduce the eager results bit for bit.  A replay repeats the launch with the same arguments, the
+    tag of its counters in the workspace included: windows that span workgroups (few rows, fp32), the list of pending
+    draws (bf16) and windows inside workgroups (many rows) all have to start afresh on every replay."""
+    c, t, ids, ua, ur = _random_case(16384, 16384, N, K, dtype, seed=41)
+    c2, t2, *_ = _random_case(16384, 16384, N, K, dtype, seed=42)
+    say(f"[graph] V=16384 N={N} K={K} {dtype}: capture ciar_quantify_verify, replay 4 times on alternating inputs")
+    P = ciar.Params(tau=0.01, window=K)
     ref1 = ciar.quantify_verify(c, t, ids, ua, ur, P)
     ref2 = ciar.quantify_verify(c2, t2, ids, ua, ur, P)
     torch.cuda.synchronize()
     cin, tin = c.clone(), t.clone()
-    ws = torch.empty(ciar.workspace_bytes(300, P.to_c(c)), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(ciar.workspace_bytes(N, P.to_c(c)), dtype=torch.uint8, device="cuda")
     out = {k: torch.empty_like(v) for k, v in ref1.items()}
     side = torch.cuda.Stream()
     g = torch.cuda.CUDAGraph()
