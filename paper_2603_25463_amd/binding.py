@@ -158,6 +158,10 @@ def _check(rc: int):
         raise CiarError(rc, last_error())
 
 
+# public names of the marshalling helpers (bench.py and the tests call the C ABI directly through them)
+ptr, stream_handle, check = _ptr, _stream, _check
+
+
 def _need_cuda(*ts):
     for t in ts:
         if t is not None and not t.is_cuda:
@@ -440,6 +444,9 @@ def _head_params(hidden: torch.Tensor, weight: torch.Tensor, bias, params: Param
     cp = params.to_c(torch.empty((0, stride), dtype=torch.float32), V)
     cp.row_stride = stride
     return N, D, V, cp
+
+
+head_params = _head_params
 
 
 def interhead_logits(hidden: torch.Tensor, weight: torch.Tensor, bias: torch.Tensor | None, params: Params,

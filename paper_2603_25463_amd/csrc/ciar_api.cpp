@@ -198,7 +198,7 @@ int hip_fail(hipError_t e, const char* what)
     return fail(CIAR_EHIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-// Workspace layout: [N] RowStats | [N] int32 row ids | [N] int32 rejected rows | 16 B counter | [N] uint8 accept bits
+// Workspace layout: [N] RowStats | [N] int32 row ids | [N] int32 arg-max tokens | 16 B (unused) | [N] uint8 accept bits
 // (rounded up to 128 B) | 16 N bytes for the words of windows that span workgroups: window w at byte 16 K w, so that
 // from K = 8 on every window has a 128-byte line of its own (the rows of many windows arrive at once, and atomic
 // operations on one line are served one after another).
@@ -211,7 +211,6 @@ void carve(char* w, int64_t N, ciar::RowArgs* a, int32_t** row_ids, uint8_t** ac
     a->stats = reinterpret_cast<ciar::RowStats*>(w);
     *row_ids = reinterpret_cast<int32_t*>(w + stats_bytes(N));
     a->reject_list = reinterpret_cast<int32_t*>(w + stats_bytes(N) + ids_bytes(N));
-    a->reject_count = reinterpret_cast<unsigned long long*>(w + stats_bytes(N) + 2 * ids_bytes(N));
     *accept = reinterpret_cast<uint8_t*>(w + stats_bytes(N) + 2 * ids_bytes(N) + 16);
     a->win_words = reinterpret_cast<unsigned long long*>(w + windows_offset(N));
 }
@@ -286,6 +285,7 @@ int fill(const Call& c, ciar::Mode mode, ciar::RowArgs* a)
     // the window outputs are assembled from the per-row accept bits and draws
     if ((c.accept_len || c.resampled_id) && !a->accept) a->accept = ws_accept;
     if ((c.accept_len || c.resampled_id) && !a->row_id) a->row_id = ws_ids;
+    if (a->row_id && !a->accept) a->accept = ws_accept;           // (resample_kernel finds its rows by their accept bits)
     a->window = c.params->window;
     a->accept_len = c.accept_len;
     a->resampled_id = c.resampled_id;
@@ -296,9 +296,9 @@ int fill(const Call& c, ciar::Mode mode, ciar::RowArgs* a)
 // comes from a kernel of its own, into the list of rejected rows (not in use in a quantify-only call).
 bool needs_argmax(const ciar::RowArgs& a) { return a.radius && !a.ids && (a.p_lo || a.p_hi); }
 
-// Tags for the counters the kernels keep in caller memory (see counter_add in ciar_device.h): a different one
-// for every launch of the process, starting from a value that varies from run to run.  (A captured graph replays
-// a launch with its tag: the kernels hand every counter back, with a zero tag, when they are through with it.)
+// Tags for the words the streaming kernel keeps in caller memory (see window_arrive in ciar_device.h): a different
+// one for every launch of the process, starting from a value that varies from run to run.  (A captured graph replays
+// a launch with its tag: the kernel hands every word back, with a zero tag, when a window is complete.)
 uint32_t next_tag()
 {
     static std::atomic<uint32_t> tag{(uint32_t)std::chrono::steady_clock::now().time_since_epoch().count() * 2654435761u};
@@ -632,7 +632,6 @@ int ciar_quantify_multihead(const void* draft_heads, const void* radius_heads, i
     ciar::RowStats* stats = reinterpret_cast<ciar::RowStats*>(w);
     int32_t* ws_ids = reinterpret_cast<int32_t*>(w + (size_t)heads * stats_bytes(N));
     uint8_t* ws_flags = reinterpret_cast<uint8_t*>(w + (size_t)heads * (stats_bytes(N) + ids_bytes(N)));
-    const size_t head_bytes = (size_t)head_stride * (size_t)r.elt;
 
     // one streaming pass over the rows of all heads ([heads, N] rows, head h at h * head_stride): every head's RowStats
     {
@@ -644,7 +643,6 @@ int ciar_quantify_multihead(const void* draft_heads, const void* radius_heads, i
         a.radius = radius_heads;
         a.stats = stats;
         a.reject_list = ws_ids;                              // heads * N ints; a quantify-only pass builds no list
-        a.reject_count = nullptr;                            // (no verifier row: no list)
         if (strategy == CIAR_VOTING) {
             // every head is a quantifier of its own: the streaming kernel finishes its rows where it can;
             // the per-head outputs are [heads, N], which is the order of the rows

@@ -536,31 +536,10 @@ __device__ __forceinline__ bool finish_row(const RowArgs& A, int64_t row, const 
     return rej;
 }
 
-// A counter in caller memory that needs no initialisation: the high word carries the tag of the launch that uses
-// it (RowArgs::tag, never zero, different for every launch of the process), the low word the count.  A word that
-// carries another tag -- what an earlier call left behind, or whatever the memory held before -- counts as zero.
-// Whoever reads the final count writes a zero word back, so that a replay of the same launch (a captured graph:
-// same tag) starts afresh as well.
-__device__ __forceinline__ uint32_t counter_add(unsigned long long* p, uint32_t tag, uint32_t inc)
-{
-    const unsigned long long fresh = (unsigned long long)tag << 32;
-    unsigned long long seen = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    while ((seen >> 32) != tag) {
-        // claim the word for this launch; whoever loses the exchange finds the tag in place (or tries again)
-        const unsigned long long prev = atomicCAS(p, seen, fresh);
-        seen = prev == seen ? fresh : prev;
-    }
-    return (uint32_t)atomicAdd(p, (unsigned long long)inc);       // the count stays below 2^32: no carry into the tag
-}
-__device__ __forceinline__ uint32_t counter_read(const unsigned long long* p, uint32_t tag)
-{
-    const unsigned long long v = *p;
-    return (v >> 32) == tag ? (uint32_t)v : 0u;
-}
-
 // The rows of a window that spans workgroups meet in one 64-bit word of caller memory, which needs no
 // initialisation and carries everything the window's outputs need, so that no other memory has to be made visible
-// between workgroups:  [63:33] the launch's tag (as in counter_add: a word with another tag is a fresh one),
+// between workgroups:  [63:33] the launch's tag (RowArgs::tag, never zero, different for every launch of the process: a
+// word with another tag -- what an earlier call left behind, or whatever the memory held before -- is a fresh one),
 // [32:25] rows arrived, [24:17] offset of the first rejected row so far (255: none), [16:0] that row's draw.
 // A run of `rows` consecutive rows of the window that one workgroup has finished arrives with one call: its rows'
 // first rejected offset in the window and that row's draw (id = -1: all accepted).  The call that completes the
@@ -570,7 +549,9 @@ __device__ __forceinline__ bool window_arrive(unsigned long long* p, uint32_t ta
                                               int& first, int& draw)
 {
     const unsigned long long t31 = (unsigned long long)(tag & 0x7fffffffu);
-    unsigned long long seen = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // The first exchange assumes a fresh word, which window_claim has normally left there at the start of the
+    // kernel: the trip to memory and back that reading the word first would cost is the tail of the kernel.
+    unsigned long long seen = (t31 << 33) | (0xffull << 17);
     for (;;) {
         const unsigned long long cur = (seen >> 33) == t31 ? seen : ((t31 << 33) | (0xffull << 17));
         const unsigned long long count = ((cur >> 25) & 0xffull) + (unsigned long long)rows;
@@ -587,6 +568,18 @@ __device__ __forceinline__ bool window_arrive(unsigned long long* p, uint32_t ta
             return true;
         }
         seen = prev;                                               // another row of the window got in between
+    }
+}
+
+// Makes a window's word a fresh one of this launch ahead of its rows' arrivals (an optimisation only: window_arrive
+// copes with whatever it finds).
+__device__ __forceinline__ void window_claim(unsigned long long* p, uint32_t tag)
+{
+    const unsigned long long t31 = (unsigned long long)(tag & 0x7fffffffu), fresh = (t31 << 33) | (0xffull << 17);
+    unsigned long long seen = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    while ((seen >> 33) != t31) {
+        const unsigned long long prev = atomicCAS(p, seen, fresh);
+        seen = prev == seen ? fresh : prev;
     }
 }
 

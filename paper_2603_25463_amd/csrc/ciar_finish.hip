@@ -20,13 +20,19 @@ __device__ __forceinline__ void window_of(const uint8_t* accept, const int32_t* 
         resampled_id[w] = (lo + n < hi) ? row_id[lo + n] : -1;
 }
 
-// Residual draw of the rejected rows that the streaming kernel has listed instead of drawing them itself (launches
-// whose tiles do not hold both rows in registers: bf16, tensor radius, wide radii): res_i = max(0, q_i - p_i),
-// inverse CDF in token order.  Workgroups walk over the list; both rows are fetched again, four vectors of each
-// row per lane in flight at once.  A row's draw is a chain of dependent
-// steps (list entry, statistics, loads, totals, crossing chunk, scan), so what matters is how many rows
-// a compute unit has in flight: 256-lane workgroups, several per compute unit, unless the launch is so
-// small that most compute units would see no rejected row at all (then 1024 lanes work on each row).
+// Residual draw of the rejected rows (accept bit 0) of launches whose streaming kernel does not draw them itself (launches whose tiles do not hold both rows in registers: bf16, tensor radius, wide radii):
+// res_i = max(0, q_i - p_i), inverse CDF in token order; both rows are fetched again, four vectors of each row per
+// lane in flight at once.  A row's draw is a chain of dependent steps (statistics, loads, totals, crossing chunk,
+// scan), so what matters is how many rows a compute unit has in flight: 256-lane workgroups, several per compute
+// unit, unless the launch is so small that most compute units would see no rejected row at all (then 1024 lanes
+// work on each row).
+// Which workgroup draws which row is settled without a list and without atomic operations (a counter that every
+// workgroup of a launch adds to is served one addition after another: a thousand of them cost ~20 us at the end of
+// a kernel).  Up to kRankAllRows rows every workgroup reads all the marks, 4096 at a time, ranks the marked rows
+// in row order and takes ranks g, g + G, ...: the rows are dealt out evenly whatever their pattern.  Beyond that a
+// workgroup takes the marked rows of its own slice of N / G consecutive rows (many rows per slice: even enough).
+constexpr int kRankAllRows = 65536;
+
 template <typename T, int THREADS>
 __global__ __launch_bounds__(THREADS) void resample_kernel(const RowArgs A, const int K, int32_t* __restrict__ resampled_id)
 {
@@ -36,22 +42,59 @@ __global__ __launch_bounds__(THREADS) void resample_kernel(const RowArgs A, cons
     constexpr int CHUNK = THREADS * EPV;
     constexpr int MAXCH = 8192 / THREADS;           // chunks of CHUNK tokens a row can have (supported vocabularies)
     constexpr int UB = 4;                           // chunks of each row in flight per lane
+    constexpr int SCAN = 4096, MPL = SCAN / THREADS;   // marks read per step of the search, and per lane
 
     __shared__ double sm_e[NW * MAXCH + NW];
     __shared__ int    sm_i[NW * 2];
+    __shared__ int    sm_mine[SCAN];                // the rows of a step that this workgroup draws
+    __shared__ int    sm_wcount[NW];
+    __shared__ int    sm_nmine;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int V = A.V;
     const int last_vec = (V + EPV - 1) / EPV - 1;
     const int nch = (V + CHUNK - 1) / CHUNK;        // <= MAXCH
-    // the counter that the streaming kernel claimed for its launch (see counter_add): tag and length of the list
-    const unsigned long long head = *A.reject_count;
-    const uint32_t listed = (uint32_t)head;
-    const int count = listed > (uint32_t)A.N ? (int)A.N : (int)listed;
+    const int64_t N = A.N;
+    const int G = (int)gridDim.x, g = (int)blockIdx.x;
+    const bool rank_all = N <= kRankAllRows;        // uniform over the grid
+    const int64_t slice = (N + G - 1) / G;
+    const int64_t lo_row = rank_all ? 0 : (int64_t)g * slice;
+    const int64_t hi_row = rank_all ? N : (lo_row + slice < N ? lo_row + slice : N);
+    int ranked = 0;                                 // marked rows before this step (rank_all)
 
-    for (int item = blockIdx.x; item < count; item += gridDim.x) {
-        const int32_t entry = A.reject_list[item];
-        const int64_t row = entry < 0 ? ~entry : entry;
+    for (int64_t s0 = lo_row; s0 < hi_row; s0 += SCAN) {
+    // ---- this step's marks: lane t looks at rows s0 + t MPL ... s0 + t MPL + MPL - 1 ------------------------------
+    unsigned mask = 0;
+#pragma unroll
+    for (int k = 0; k < MPL; ++k) {
+        const int64_t r = s0 + (int64_t)tid * MPL + k;
+        if (r < hi_row && A.accept[r] == 0) mask |= 1u << k;
+    }
+    const int mine_cnt = __popc(mask);
+    const int incl = (int)wave_scan((double)mine_cnt);             // exact: small integers
+    if (lane == 63) sm_wcount[wave] = incl;
+    if (tid == 0) sm_nmine = 0;
+    __syncthreads();
+    int before = ranked + incl - mine_cnt, total = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        if (w < wave) before += sm_wcount[w];
+        total += sm_wcount[w];
+    }
+    for (int k = 0; k < MPL; ++k) {
+        if (mask & (1u << k)) {
+            const int row = (int)(s0 + (int64_t)tid * MPL + k);
+            if (!rank_all) sm_mine[atomicAdd(&sm_nmine, 1)] = row;          // (any order: each row is drawn on its own)
+            else if (before % G == g) sm_mine[atomicAdd(&sm_nmine, 1)] = row;
+            ++before;
+        }
+    }
+    ranked += total;
+    __syncthreads();
+    const int count = sm_nmine;                                    // uniform
+
+    for (int item = 0; item < count; ++item) {
+        const int64_t row = sm_mine[item];
         const T* crow = static_cast<const T*>(A.draft) + row * A.stride;
         const T* trow = static_cast<const T*>(A.target) + row * A.stride;
         const RowStats st = A.stats[row];
@@ -173,15 +216,17 @@ __global__ __launch_bounds__(THREADS) void resample_kernel(const RowArgs A, cons
             int id = (c0 != INT_MAX) ? c0 : l0;
             if (id < 0) id = 0;
             A.row_id[row] = id;
-            if (entry < 0 && resampled_id) resampled_id[row / K] = id;             // the window's draw is its first rejected row's
+            if (resampled_id) {
+                // the window's draw is its first rejected row's: the rows before this one in its window (inside one
+                // workgroup of the streaming kernel, which has written -1 for a window without rejection)
+                bool first = true;
+                for (int64_t r = row - row % K; first && r < row; ++r) first = A.accept[r] != 0;
+                if (first) resampled_id[row / K] = id;
+            }
         }
         __syncthreads();                                           // the LDS slots are reused by the next row
     }
-    // The workgroup that is through last hands the two counters back (zero words), so that a replay of the launch
-    // from a captured graph, which carries the same tag, finds them fresh.
-    if (tid == 0 && counter_add(A.reject_count + 1, (uint32_t)(head >> 32), 1u) + 1u == gridDim.x) {
-        __hip_atomic_store(A.reject_count, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(A.reject_count + 1, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();                                               // sm_mine is rewritten by the next step
     }
 }
 
@@ -326,7 +371,7 @@ hipError_t launch_finish(Mode mode, int dtype, const RowArgs& args, const Stream
 {
     if (args.N <= 0 || mode == Mode::Quantify) return hipSuccess;  // the streaming kernel has written every row's outputs
     const bool want_windows = accept_len || resampled_id;
-    if (!plan.draws_inline && args.row_id) {
+    if (!plan.draws_inline && args.row_id && args.accept) {
         // the rows the streaming kernel has listed; windows inside its workgroups get their draw from here too
         int32_t* const win = want_windows && plan.windows_inline ? resampled_id : nullptr;
         const int64_t cus = compute_units();

@@ -40,9 +40,9 @@ struct RowArgs {
     uint8_t* accept;                                 // [N] or null
     int32_t* row_id;                                 // [N] or null
     RowStats* stats;                                 // [N] workspace
-    int32_t* reject_list;                            // [N] workspace: rejected rows whose draw resample_kernel makes
-    unsigned long long* reject_count;                // workspace: length of that list (see counter_add)
-    uint32_t tag;                                    // this launch's tag for such counters
+    int32_t* reject_list;                            // [N] workspace ints (the arg-max tokens of a tensor-radius call
+                                                     // without drafted ids)
+    uint32_t tag;                                    // this launch's tag for the window words (see window_arrive)
     int32_t  finish;                                 // 1 = the streaming kernel also finishes its rows (quantify only)
     // Verification inside the streaming kernel: the accept test, the residual draw of rejected rows from the
     // registers that hold both rows, and the per-row outputs.  A workgroup walks over pieces of `unit` consecutive

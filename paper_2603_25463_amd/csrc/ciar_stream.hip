@@ -442,14 +442,6 @@ void stream_kernel(const RowArgs A)
         }
     };
 
-    // the list of rows that resample_kernel will draw starts empty: claim its counter for this launch
-    if constexpr (DO_V && !KEEP_E) {
-        if (blockIdx.x == 0 && tid == 0 && A.row_id) {
-            counter_add(A.reject_count, A.tag, 0u);
-            counter_add(A.reject_count + 1, A.tag, 0u);            // (resample_kernel's workgroups count themselves here)
-        }
-    }
-
     // ---- which rows this workgroup takes ---------------------------------------------------------------------
     // Pieces of `unit` consecutive rows: piece blockIdx.x, blockIdx.x + gridDim.x, ...  (unit = 1, or the window
     // length when this kernel also writes the window outputs).  The workgroup's rows are numbered L = 0, 1, 2, ...
@@ -516,7 +508,6 @@ void stream_kernel(const RowArgs A)
             }
         }
         if constexpr (DO_V) {
-            bool pend = false;                                     // this lane's row still needs its draw
             if (vjob) {
                 const RowStats& st = sm_rows[i];
                 if constexpr (KEEP_E) {
@@ -525,37 +516,13 @@ void stream_kernel(const RowArgs A)
                         sm_draw[i] = -1;                           // accepted after all: the draw does not count
                 } else {
                     // the accept test (Algorithm 1, "Cloud verification"); a rejected row's draw is resample_kernel's
-                    pend = reject_exact(sm_fx[i][0], sm_fx[i][2], sm_fx[i][3], st.n, st.nt, st.S, st.Z);
-                    sm_draw[i] = pend ? kDrawPending : -1;
-                    pend = pend && A.row_id;
-                }
-            }
-            uint32_t slot = 0;                                     // of this lane's row in the list of pending draws
-            if constexpr (!KEEP_E) {
-                // one addition to the list's counter per wave that has such rows; requested before the barrier, so
-                // that its way to memory and back overlaps with the other half of the finishing
-                const unsigned long long m = __ballot(pend);
-                if (m) {                                           // uniform over the wave
-                    const int leader = __builtin_amdgcn_readfirstlane(__ffsll((long long)m) - 1);
-                    const int l = ft & 63;
-                    uint32_t base = 0;
-                    if (l == leader) base = counter_add(A.reject_count, A.tag, (uint32_t)__popcll(m));
-                    base = (uint32_t)__builtin_amdgcn_readlane((int)base, leader);
-                    slot = base + (uint32_t)__popcll(m & ((1ull << l) - 1ull));
+                    sm_draw[i] = reject_exact(sm_fx[i][0], sm_fx[i][2], sm_fx[i][3], st.n, st.nt, st.S, st.Z)
+                                     ? kDrawPending : -1;
                 }
             }
             __syncthreads();                                       // the windows below read their rows' final draws
             if (vjob) {
                 const int id = sm_draw[i];                         // -1, a draw, or kDrawPending
-                if constexpr (!KEEP_E) {
-                    if (pend && slot < (uint32_t)nrows) {          // (one entry per row at most)
-                        // list entry: the row, bit-complemented when its draw is also its window's (the first
-                        // rejection of a window that lies inside this workgroup)
-                        bool first = unit == A.window && A.resampled_id != nullptr;
-                        for (int k = i - i % unit; first && k < i; ++k) first = sm_draw[k] == -1;
-                        A.reject_list[slot] = first ? ~(int32_t)r : (int32_t)r;
-                    }
-                }
                 if (A.accept) A.accept[r] = (uint8_t)(id == -1);
                 if (A.row_id) A.row_id[r] = id;
                 const int K = A.window;
@@ -571,13 +538,17 @@ void stream_kernel(const RowArgs A)
                 }
                 if constexpr (KEEP_E) {
                     const int64_t w = r / K, lo = w * K;
-                    if (A.win_count && (i == 0 || r == lo)) {
-                        // A window that spans workgroups: the consecutive rows of it that this workgroup holds arrive
-                        // together in the window's 64-bit word (window_arrive), from the lane of the first of them,
-                        // and the arrival that completes the window writes its outputs.
+                    if (A.win_count && (i % unit == 0 || r == lo)) {
+                        // A window that spans workgroups: the consecutive rows of it that this workgroup holds (one
+                        // row where the rows are dealt out singly: measured the fastest for such launches, 58.8 us per
+                        // step on workload 2 against 63.2 us with four consecutive rows per workgroup, whose two
+                        // arrivals per window cost less than their memory access pattern loses) arrive together in the
+                        // window's 64-bit word (window_arrive), from the lane of the first of them, and the arrival
+                        // that completes the window writes its outputs.
                         const int len = (int)(nrows - lo < K ? nrows - lo : K);
+                        const int piece_end = i - i % unit + unit;
                         int rows = 0, off = 0, mine_id = -1;
-                        for (; i + rows < cnt && r + rows < lo + len; ++rows) {
+                        for (; i + rows < cnt && i + rows < piece_end && r + rows < lo + len; ++rows) {
                             if (mine_id < 0 && sm_draw[i + rows] >= 0) { mine_id = sm_draw[i + rows]; off = (int)(r + rows - lo); }
                         }
                         int first, draw;
@@ -620,6 +591,13 @@ void stream_kernel(const RowArgs A)
     // (the logits of the reported tokens are requested behind the row, once their ids are there, and parked when
     // they arrive: that waits for the row as well, which the first pass needs anyway)
     if (finish) park_scalars(fetch_scalars(L0, first_id));
+    if constexpr (KEEP_E) {
+        // windows that span workgroups: claim the words this workgroup's rows will arrive in (see window_arrive)
+        if (A.win_count && tid < cnt) {
+            const int64_t r = row_of(L0 + tid), lo = r / A.window * A.window;
+            if (tid % unit == 0 || r == lo) window_claim(A.win_count + 2 * lo, A.tag);
+        }
+    }
 
     for (int done = 0;; ++done) {                                  // done = rows of this batch already streamed
         const bool has_next = done + 1 < cnt;                      // uniform
@@ -1206,11 +1184,7 @@ hipError_t launch_stream_kernel(const RowArgs& a, StreamLaunch& L)
     // from the lane that finishes a window's last row (one 64-bit word per window in the workspace, see window_arrive).
     p.windows_counted = p.draws_inline && a.win_words && (a.accept_len || a.resampled_id) && !p.windows_inline && a.window >= 2 &&
                         a.window <= kMaxCountedWindow;
-    if (p.windows_counted) {
-        // consecutive rows per workgroup (one piece each): a window then meets in as few arrivals as possible
-        p.unit = (int)max1;
-        p.grid = (unsigned)((N + max1 - 1) / max1);
-    }
+
     if (!L.launch) return hipSuccess;
     RowArgs b = a;
     b.finish = p.can_finish ? 1 : 0;
