@@ -35,6 +35,9 @@
  *   - 0 <= draft_ids[i] < V and uniforms in [0, 1) are preconditions (ids are clamped into
  *     range on the device so a bad id cannot fault).
  *   - Output pointers may be NULL to skip that output, where stated.
+ *   - HIP keeps a last-error state per host thread.  An entry point that launches kernels reads and resets it
+ *     before its first launch (so that an error left by an earlier, unrelated call is not reported as this
+ *     call's) and after each launch.
  *   - Return value: a ciar_status.  On any error nothing has been launched and
  *     ciar_last_error() describes the problem.  N == 0 is valid and launches nothing.
  *   - Supported vocabulary: 1 <= V <= 32768 (float32) or 65536 (bfloat16).

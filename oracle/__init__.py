@@ -63,7 +63,9 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
+        # (CIAR_ORACLE_LIB: a library built elsewhere from a copy of the source -- the mutation test plants mistakes in
+        # such copies and checks that the pins catch them)
+        lib = ctypes.CDLL(os.environ.get("CIAR_ORACLE_LIB") or build())
         vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         pp = ctypes.POINTER(_CParams)
         lib.ciar_oracle_kappa.restype = ctypes.c_double

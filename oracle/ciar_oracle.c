@@ -163,7 +163,8 @@ static double row_exponentials(const void* logits, const ciar_oracle_params* P, 
 /* InterFuse bounds for the whole row, normalised if requested.
  * In: e[i], S and the sum over the others of the largest token (see row_rest), the raw radius tensor (NULL:
  * scalar mode) and the row.  Out: pl[i], pu[i] (the final, possibly scaled, bounds).
- * The defining equations have sum_{j != i} exp(o_j) in the denominator. */
+ * The appendix prints the denominators as S - e_i + e_i e^{-/+ r_i}; S - e_i equals the sum over the other tokens,
+ * which is what row_rest forms directly for the largest token (the one token for which the subtraction cancels). */
 static void row_interfuse(const double* e, double S, const row_rest* rest, const ciar_oracle_params* P,
                           const void* radius, int64_t row, double* pl, double* pu)
 {

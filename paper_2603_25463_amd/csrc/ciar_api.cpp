@@ -198,6 +198,11 @@ int hip_fail(hipError_t e, const char* what)
     return fail(CIAR_EHIP, "%s: %s", what, hipGetErrorString(e));
 }
 
+// The launchers report hipGetLastError() after a launch.  HIP keeps that state per host thread and a successful call
+// does not reset it, so an error left by an earlier, unrelated call of the thread is discarded before the first
+// launch of an entry point: what is reported afterwards is this call's.
+void discard_stale_hip_error() { (void)hipGetLastError(); }
+
 // Workspace layout: [N] RowStats | [N] int32 row ids | [N] int32 arg-max tokens | 16 B (unused) | [N] uint8 accept bits
 // (rounded up to 128 B) | 16 N bytes for the words of windows that span workgroups: window w at byte 16 K w, so that
 // from K = 8 on every window has a 128-byte line of its own (the rows of many windows arrive at once, and atomic
@@ -314,6 +319,7 @@ int run_stream(const Call& c, ciar::Mode mode)
     ciar::RowArgs a;
     if (int rc = fill(c, mode, &a)) return rc;
     if (c.N == 0) return CIAR_OK;
+    discard_stale_hip_error();
     if (needs_argmax(a)) {
         const hipError_t e = ciar::launch_argmax(c.params->dtype, a, a.reject_list, c.stream);
         if (e != hipSuccess) return hip_fail(e, "arg-max kernel launch");
@@ -339,6 +345,7 @@ int run_finish(const Call& c, ciar::Mode mode)
     if (int rc = fill(c, mode, &a)) return rc;
     if (c.N == 0) return CIAR_OK;
     if (needs_argmax(a)) a.ids = a.reject_list;                    // found by stage 1
+    discard_stale_hip_error();
     const ciar::StreamPlan plan = ciar::plan_stream(mode, c.params->dtype, a);
     const hipError_t e = ciar::launch_finish(mode, c.params->dtype, a, plan, c.params->window, c.accept_len,
                                              c.resampled_id, c.stream);
@@ -536,6 +543,7 @@ int ciar_window_epilogue(const uint8_t* accept, const int32_t* row_resample_id, 
     if (resampled_id && !row_resample_id)
         return fail(CIAR_EINVAL, "row_resample_id is NULL but resampled_id is requested");
     if (N == 0) return CIAR_OK;
+    discard_stale_hip_error();
     hipError_t e = ciar::launch_windows(accept, row_resample_id, N, params->window, accept_len, resampled_id,
                                         static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return hip_fail(e, "window kernel launch");
@@ -557,6 +565,7 @@ int ciar_dense_intervals(const void* draft_logits, const void* radius, int64_t N
     a.draft = draft_logits;
     a.radius = radius;
     if (N == 0) return CIAR_OK;
+    discard_stale_hip_error();
     hipError_t e = ciar::launch_dense(params->dtype, a, p_lo, p_mid, p_hi, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return hip_fail(e, "dense kernel launch");
     return CIAR_OK;
@@ -582,6 +591,7 @@ int ciar_interdro_loss(const void* center_logits, const void* radius, const void
     a.draft = center_logits;
     a.radius = radius;
     a.target = cloud_logits;
+    discard_stale_hip_error();
     const hipError_t e = ciar::launch_dro(params->dtype, a, row_terms, lambda_v, lambda_p, lambda_beta, alpha, weights,
                                           losses, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return hip_fail(e, "loss kernel launch");
@@ -628,6 +638,7 @@ int ciar_quantify_multihead(const void* draft_heads, const void* radius_heads, i
         return fail(CIAR_EWORKSPACE, "workspace has %zu bytes, %zu are needed", workspace_bytes, need);
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    discard_stale_hip_error();
     char* w = static_cast<char*>(workspace);
     ciar::RowStats* stats = reinterpret_cast<ciar::RowStats*>(w);
     int32_t* ws_ids = reinterpret_cast<int32_t*>(w + (size_t)heads * stats_bytes(N));
@@ -724,6 +735,7 @@ int read_rows(const void* draft_logits, const void* target_logits, int64_t N, co
     ciar::RowArgs a = base_args(params, r, N);
     a.draft = draft_logits;
     a.target = target_logits;
+    discard_stale_hip_error();
     const hipError_t e = ciar::launch_read(params->dtype, a, row_sum, static_cast<hipStream_t>(hip_stream), ev_start,
                                            ev_stop);
     if (e != hipSuccess) return hip_fail(e, "read kernel launch");
@@ -775,6 +787,7 @@ int head_logits(const void* hidden, const void* weight, const float* bias, int32
     if (!aligned16(centre) || !aligned16(radius)) return fail(CIAR_EALIGN, "centre or radius is not 16-byte aligned");
     h.centre = centre;
     h.radius = radius;
+    discard_stale_hip_error();
     const hipError_t e = ciar::launch_interhead(h, static_cast<hipStream_t>(hip_stream), ev_start, ev_stop);
     if (e != hipSuccess) return hip_fail(e, "Interval Head kernel launch");
     return CIAR_OK;
@@ -821,6 +834,7 @@ int ciar_interhead_quantify(const void* hidden, const void* weight, const float*
     const size_t lb = head_logit_bytes(N, params);
     h.centre = reinterpret_cast<float*>(w);
     h.radius = reinterpret_cast<float*>(w + lb);
+    discard_stale_hip_error();
     const hipError_t e = ciar::launch_interhead(h, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return hip_fail(e, "Interval Head kernel launch");
     // the quantifier reads the logits the contraction has just written, on the same stream
@@ -842,8 +856,8 @@ int ciar_quantify_verify_static(const void* draft_logits, const void* radius, co
     void* ws = nullptr;
     if (N > 0)
         if (int rc = static_scratch(&ws)) return rc;
-    // Nothing in the buffer has to start at zero except the length of the list of rejected rows, which the
-    // streaming kernel itself clears; everything else is written before it is read.
+    // Nothing in the buffer has to be cleared between calls: the window words carry the tag of the launch that wrote
+    // them (and are handed back as zeros), everything else is written before it is read.
     const Call c{draft_logits, radius, target_logits, draft_ids, u_accept, u_resample, N, params, p_lo, p_mid, p_hi, omega,
                  sigma, score, flags, accept, row_resample_id, accept_len, resampled_id, ws, kStaticBytes,
                  static_cast<hipStream_t>(hip_stream)};

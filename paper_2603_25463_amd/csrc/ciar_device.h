@@ -6,6 +6,7 @@
 #include "ciar_internal.h"
 
 #include <limits.h>
+#include <atomic>
 #include <math.h>
 
 namespace ciar {
@@ -586,19 +587,20 @@ __device__ __forceinline__ void window_claim(unsigned long long* p, uint32_t tag
 // Vocabularies of at most this many tokens take fp64 token arithmetic (see fuse_sums_tiny, dro_row_tiny_kernel).
 constexpr int kTinyVocab = 64;
 
-// Compute units of the current device (asked once per device, then cached).
+// Compute units of the current device (asked once per device, then cached; the cache is a relaxed atomic per device:
+// two threads that ask at once both write the same number).
 inline int compute_units()
 {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
-    static int cache[64] = {0};
-    if (cache[dev] == 0) {
-        int cus = 0;
+    static std::atomic<int> cache[64];
+    int cus = cache[dev].load(std::memory_order_relaxed);
+    if (cus == 0) {
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
             cus = 256;
-        cache[dev] = cus;
+        cache[dev].store(cus, std::memory_order_relaxed);
     }
-    return cache[dev];
+    return cus;
 }
 
 }  // namespace

@@ -3,6 +3,7 @@
 //   out[n, j] = sum_k hidden[n, k] * weight[j, k] + bias[j],   j in [0, 2V)
 // bf16 operands, fp32 accumulation on the matrix cores (v_mfma_f32_32x32x16_bf16), fp32 logits out: columns
 // [0, V) go to the centre rows, [V, 2V) to the raw-radius rows, which the tensor-radius quantifier reads next.
+#include <mutex>
 #include "ciar_internal.h"
 #include <hip/hip_ext.h>
 
@@ -203,14 +204,18 @@ hipError_t launch_tile(const HeadArgs& a, hipStream_t stream, hipEvent_t ev_star
     constexpr size_t lds_bytes = (size_t)2 * (BM + BN) * ROWB;                     // 64 KB or 128 KB of the 160 KB
     static_assert(lds_bytes <= 160 * 1024, "tile does not fit the LDS of a compute unit");
     if (lds_bytes > 64 * 1024) {
-        // more than the default limit for dynamic LDS: raised for this kernel once per process (an attribute of
-        // the function; setting it twice from two threads is harmless)
-        static bool raised = false;
-        if (!raised) {
+        // more than the default limit for dynamic LDS: raised for this kernel once per device (an attribute of the
+        // function on the device that is current)
+        static std::mutex mu;
+        static bool raised[64] = {};
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+        std::lock_guard<std::mutex> lock(mu);
+        if (!raised[dev]) {
             const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&interhead_gemm_kernel<MB, NB>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
             if (e != hipSuccess) return e;
-            raised = true;
+            raised[dev] = true;
         }
     }
     HeadArgs args = a;
