@@ -639,6 +639,19 @@ int ciar_quantify_multihead(const void* draft_heads, const void* radius_heads, i
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     discard_stale_hip_error();
+    if (strategy == CIAR_ENSEMBLE) {
+        // a few heads with a scalar radius whose rows fit the registers together: one sweep, every row read once
+        ciar::RowArgs a = base_args(params, r, N);
+        a.draft = draft_heads;
+        a.radius = radius_heads;
+        a.ids = draft_ids;
+        a.p_lo = p_lo; a.p_mid = p_mid; a.p_hi = p_hi; a.omega = omega; a.sigma = sigma; a.score = score; a.flags = flags;
+        if (ciar::ensemble_fused_fits(params->dtype, a, heads)) {
+            const hipError_t e = ciar::launch_ensemble_fused(params->dtype, a, heads, head_stride, stream);
+            if (e != hipSuccess) return hip_fail(e, "ensemble kernel launch");
+            return CIAR_OK;
+        }
+    }
     char* w = static_cast<char*>(workspace);
     ciar::RowStats* stats = reinterpret_cast<ciar::RowStats*>(w);
     int32_t* ws_ids = reinterpret_cast<int32_t*>(w + (size_t)heads * stats_bytes(N));

@@ -2,6 +2,7 @@
 // averages the heads' widths token by token, and the Voting majority.
 #include "ciar_device.h"
 
+#include <mutex>
 #include <type_traits>
 
 namespace ciar {
@@ -310,6 +311,379 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
     }
 }
 
+// Values that are the same in every lane of a wave, moved to scalar registers.
+__device__ __forceinline__ float uniform_f(float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); }
+__device__ __forceinline__ double uniform_d(double v)
+{
+    const long long b = __double_as_longlong(v);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+__device__ __forceinline__ FuseRow uniform_fr(FuseRow r)
+{
+    r.cu = uniform_f(r.cu); r.nih = uniform_f(r.nih); r.nil = uniform_f(r.nil); r.b = uniform_f(r.b); r.omb = uniform_f(r.omb);
+    return r;
+}
+// 2^k as a double for an integer-valued float k of either sign (clamped to what a double holds)
+__device__ __forceinline__ double pow2_any(float k) { return ldexp(1.0, (int)fminf(fmaxf(k, -1000.f), 1000.f)); }
+
+// Ensemble in one sweep, for up to kFusedHeads heads with a scalar radius whose rows fit a 512-lane workgroup
+// (32 elements of a row per lane): every head's row of a position is read from memory once.  A workgroup takes one
+// position at a time and two workgroups share a compute unit, one waiting for its rows while the other computes.
+// The exponentials of two heads stay in registers; a third head's go through LDS (64 KiB per workgroup, each lane
+// writing and reading its own slots), because three rows and the working set do not fit 128 registers.
+// Per position:
+//   1. as each head's row arrives: per-wave maximum, e_i = 2^(c_i log2e - n_w) in place of the logits, S_w;
+//      -- barrier: the waves exchange (max, n_w, S_w) of every head --
+//   2. every wave forms each head's S and reference.  Heads whose largest probability is below the host's bound
+//      have inactive caps; if some head may have an active cap, every head's sums of p^l and of the widths are
+//      taken first (one more exchange), which gives the caps.
+//   3. D_i = sum_h delta_{h,i} token by token, sum (D_i - K), sum (D_i - K)^2 about the D of the position's first
+//      token;  -- barrier --  thread 0 writes the position's outputs.
+// Token arithmetic is fp32 throughout: calls whose flat rows need fp64 tokens (needs_flat_pass: wide intervals on
+// nearly uniform rows) are not taken by this kernel, see ensemble_fused_fits.
+constexpr int kFusedHeads = 3;
+constexpr int kFusedThreads = 512;
+constexpr int kFusedWaves = kFusedThreads / 64;
+
+template <typename T, int NVEC, int H, bool ARGMAX>
+__global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4)))
+void ensemble_fused_kernel(const RowArgs A, const int64_t head_stride)
+{
+    using E = Elt<T>;
+    constexpr int EPV = E::kPerVec, EPT = NVEC * EPV, NW = kFusedWaves;
+    constexpr int RH = H < 3 ? H : 2;                              // heads whose exponentials stay in registers
+    constexpr bool LH = H == 3;                                    // the third head's go through LDS
+    extern __shared__ u32x4 sm_e2[];                               // LH: [EPT / 4][kFusedThreads]
+    __shared__ float sm_ref[H][NW][2];                             // per head and wave: largest logit, reference n_w
+    __shared__ double sm_S[H][NW];                                 // S_w in units of 2^-n_w
+    __shared__ double sm_cap[H][NW][2];                            // sum gl, sum gw of a wave, in row units of e
+    __shared__ double sm_red[2][NW];
+    __shared__ double sm_Sh[H], sm_alh[H], sm_auh[H];              // per head, for the loops over a run-time h
+    __shared__ float sm_nh[H];
+    __shared__ float sm_pm[NW];
+    __shared__ int sm_pi[NW];
+
+    // (the wave's index lives in a scalar register and the lane's index is asked for again for every position: no
+    // vector register is held for them)
+    const int wave_s = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int V = A.V;
+    const int nvec = (V + EPV - 1) / EPV;
+    const bool partial = V < NVEC * kFusedThreads * EPV;           // the row does not fill the tile
+
+    for (int64_t row = blockIdx.x; row < A.N; row += gridDim.x) {
+        // (the lane's offsets are formed anew for every position: hoisted out of the loop they would occupy registers
+        // for the whole kernel)
+        // (likewise the radius constants: what is derived from them is cheap, and uniform)
+        uint32_t ones = ~0u;
+        double ra = A.a, rb = A.b;
+        asm volatile("" : "+s"(ones), "+s"(ra), "+s"(rb));
+        const int lane = (int)__builtin_amdgcn_mbcnt_hi(ones, __builtin_amdgcn_mbcnt_lo(ones, 0u));
+        const int wave = wave_s, t = wave_s * 64 + lane;
+        // one head's row of this position goes in flight (a scalar base address and a 32-bit lane offset)
+        auto request = [&](u32x4 (&buf)[NVEC], int h) {
+            const uint64_t b = (uint64_t)(static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride);
+            const uint32_t blo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+            const uint32_t bhi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+            const gbytes base = (gbytes)(((uint64_t)bhi << 32) | blo);
+            if (partial) {
+#pragma unroll
+                for (int j = 0; j < NVEC; ++j) {
+                    const uint32_t off = (uint32_t)min(j * kFusedThreads + t, nvec - 1) * 16u;
+                    buf[j] = __builtin_nontemporal_load((gvec)(base + off));
+                }
+            } else {
+                const uint32_t off = (uint32_t)t * 16u;
+#pragma unroll
+                for (int j = 0; j < NVEC; ++j)
+                    buf[j] = __builtin_nontemporal_load((gvec)(base + (uint64_t)j * (kFusedThreads * 16u) + off));
+            }
+        };
+        // ---- 1: a head's row as it arrives: per-wave maximum, exponentials about the wave's integer reference, S_w
+        auto stats = [&](u32x4 (&buf)[NVEC], float (&e)[EPT], int h, float& emax_w) -> float {
+            if (partial) {
+#pragma unroll
+                for (int j = 0; j < NVEC; ++j) E::mask_tail(buf[j], (j * kFusedThreads + t) * EPV, V);
+            }
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) E::unpack(buf[j], &e[j * EPV]);
+            float ml = e[0];
+#pragma unroll
+            for (int i = 1; i < EPT; ++i) ml = fmaxf(ml, e[i]);
+            const float mw = wave_max(ml);
+            const float nw = ref_of(mw);
+            const float nref = nw == -INFINITY ? 0.f : nw;
+            double sacc = 0.0;                                     // (one accumulator: registers are scarcer here than issue slots)
+#pragma unroll
+            for (int j = 0; j < NVEC; ++j) {
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) {
+                    e[j * EPV + k] = exp2_ref(e[j * EPV + k], nref);
+                    sacc += (double)e[j * EPV + k];
+                }
+                __builtin_amdgcn_sched_barrier(0);                 // keep the working set to one vector at a time
+            }
+            const double Sw = wave_sum(sacc);
+            if (lane == 0) { sm_ref[h][wave][0] = mw; sm_ref[h][wave][1] = nw; sm_S[h][wave] = Sw; }
+            emax_w = uniform_f(exp2_ref(mw, nref));                // the wave's largest e_i, in its own units
+            return uniform_f(nw);
+        };
+        float e[RH][EPT];
+        float nwv[H], emw[H];
+        if constexpr (LH) {
+            // the third head first: its exponentials leave for LDS, and the second head's row is requested into
+            // the registers that this frees
+            u32x4 b0[NVEC];
+            {
+                u32x4 b2[NVEC];
+                request(b2, 2);
+                request(b0, 0);
+                float e2[EPT];
+                nwv[2] = stats(b2, e2, 2, emw[2]);
+#pragma unroll
+                for (int q = 0; q < EPT / 4; ++q) {
+                    u32x4 w;
+                    w.x = __float_as_uint(e2[q * 4]); w.y = __float_as_uint(e2[q * 4 + 1]);
+                    w.z = __float_as_uint(e2[q * 4 + 2]); w.w = __float_as_uint(e2[q * 4 + 3]);
+                    sm_e2[q * kFusedThreads + t] = w;
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            nwv[0] = stats(b0, e[0], 0, emw[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            u32x4 b1[NVEC];
+            request(b1, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            nwv[1] = stats(b1, e[1], 1, emw[1]);
+        } else {
+            u32x4 buf[RH][NVEC];
+#pragma unroll
+            for (int h = 0; h < RH; ++h) request(buf[h], h);
+#pragma unroll
+            for (int h = 0; h < RH; ++h) nwv[h] = stats(buf[h], e[h], h, emw[h]);
+        }
+        // element i of head h as this lane holds it
+        auto e_of = [&](int h, int i, const u32x4& from_lds) -> float {
+            if (h < RH) return e[h][i];
+            const int c = i & 3;
+            return __uint_as_float(c == 0 ? from_lds.x : c == 1 ? from_lds.y : c == 2 ? from_lds.z : from_lds.w);
+        };
+        __syncthreads();
+        // ---- 2: every head's S and reference; which heads can have an active cap ---------------------------------
+        double S[H];                                               // in units of 2^-n
+        float n[H];
+        bool all_capless = true, any_split = false;
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+            float mc = sm_ref[h][0][0], nn = sm_ref[h][0][1];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) { mc = fmaxf(mc, sm_ref[h][w][0]); nn = fmaxf(nn, sm_ref[h][w][1]); }
+            double s = 0.0;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const float rn = sm_ref[h][w][1];
+                if (rn != -INFINITY) s += sm_S[h][w] * pow2_of(rn - nn);
+            }
+            S[h] = uniform_d(s); n[h] = uniform_f(nn);
+            const double emax = (double)exp2_ref(uniform_f(mc), n[h]);
+            all_capless = all_capless && (!A.normalize || emax <= A.capless_xmax * S[h]);
+            any_split = any_split || emax > 0.5 * S[h];
+            __builtin_amdgcn_sched_barrier(0);                     // one head at a time: the LDS reads of all heads at once
+                                                                   // would need registers that hold the rows
+        }
+        // this wave's units: its e_i are 2^(n - n_w) times the row's, and so is the partition sum it divides by
+        double Sw_units[H];
+#pragma unroll
+        for (int h = 0; h < H; ++h)
+            Sw_units[h] = nwv[h] != -INFINITY ? uniform_d(S[h] * pow2_any(n[h] - nwv[h])) : 1.0;
+        double al[H], au[H];
+#pragma unroll
+        for (int h = 0; h < H; ++h) { al[h] = 1.0; au[h] = 1.0; }
+        if (!all_capless) {                                        // uniform over the workgroup
+            // sum p^l and sum of the widths of every head -> that head's caps
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                const FuseRow fr = uniform_fr(fuse_row(Sw_units[h], ra, rb));
+                double g0 = 0.0, g1 = 0.0;
+#pragma unroll
+                for (int q = 0; q < EPT / 4; ++q) {
+                    u32x4 w = {0u, 0u, 0u, 0u};
+                    if (h >= RH) w = sm_e2[q * kFusedThreads + t];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        float gl, gw;
+                        fuse_token(e_of(h, q * 4 + c, w), fr, gl, gw);
+                        g0 += (double)gl; g1 += (double)gw;        // (a slot past the row's end holds e = 0: gl = gw = 0)
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // back to row units of e: a power of two
+                const double fw = nwv[h] != -INFINITY ? pow2_of(nwv[h] - n[h]) : 0.0;
+                g0 = wave_sum(g0) * fw; g1 = wave_sum(g1) * fw;
+                if (lane == 0) { sm_cap[h][wave][0] = g0; sm_cap[h][wave][1] = g1; }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                double sgl = 0.0, sgw = 0.0;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) { sgl += sm_cap[h][w][0]; sgw += sm_cap[h][w][1]; }
+                const double Sl = fmin(1.0, rb / S[h] * sgl), Su = fmax(1.0, rb / S[h] * sgl + (ra - rb) / S[h] * sgw);
+                if (A.normalize) { al[h] = uniform_d(fmin(1.0, A.cap_lo / Sl)); au[h] = uniform_d(fmax(1.0, A.cap_hi / Su)); }
+            }
+        }
+        if (t == 0) {
+#pragma unroll
+            for (int h = 0; h < H; ++h) { sm_Sh[h] = S[h]; sm_nh[h] = n[h]; sm_alh[h] = al[h]; sm_auh[h] = au[h]; }
+        }
+        // The sums over the tokens are taken about the D of the position's first token (every lane forms the same
+        // number, from the logits in memory and the row's constants).
+        double KD = 0.0;
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+            const T* crow = static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride;
+            const float e0 = exp2_ref(load_logit(crow, 0), n[h]);
+            float gl, gw;
+            fuse_token(e0, fuse_row(S[h], ra, rb), gl, gw);
+            KD = fma(au[h] * (ra - rb) / S[h], (double)gw, fma((au[h] - al[h]) * rb / S[h], (double)gl, KD));
+        }
+        KD = uniform_d(KD);
+        double s1 = 0.0, s2 = 0.0;
+        float best = -INFINITY;
+        int best_i = INT_MAX;
+        {
+            // ---- 3: D_i in this wave's units of every head ---------------------------------------------------------
+            FuseRow fr[H];
+            double cw[H], cl[H];
+            float invS[H];
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                fr[h] = uniform_fr(fuse_row(Sw_units[h], ra, rb));
+                cw[h] = uniform_d(au[h] * (ra - rb) / Sw_units[h]);
+                cl[h] = uniform_d((au[h] - al[h]) * rb / Sw_units[h]);
+                invS[h] = uniform_f((float)(1.0 / Sw_units[h]));
+            }
+            // Specialised on what is uniform over the position or the wave: NOLOW = no head has an active cap (delta = w:
+            // p^l is not needed), SPLIT = some probability above 1/2 (1 - x needs the two-float 1/S, see fuse_parts),
+            // POLY = every token this wave holds, in every head, is small enough for the width polynomial that the host
+            // has fitted for the call's radius (gw = e (1 + x P(x)), see RowArgs::wpoly): five FMAs instead of the
+            // rational form with its reciprocal.
+            float pd[H][4];
+            bool poly = all_capless && A.wpoly_x >= 0.f;
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                const float is = -fr[h].nih, is2 = is * is;
+                pd[h][0] = uniform_f(A.wpoly[0] * is); pd[h][1] = uniform_f(A.wpoly[1] * is2);
+                pd[h][2] = uniform_f(A.wpoly[2] * (is2 * is)); pd[h][3] = uniform_f(A.wpoly[3] * (is2 * is2));
+                poly = poly && (double)emw[h] <= (double)A.wpoly_x * Sw_units[h];
+            }
+            auto sweep = [&](auto nolow_c, auto split_c, auto poly_c) {
+                constexpr bool NOLOW = decltype(nolow_c)::value, SPLIT = decltype(split_c)::value;
+                constexpr bool POLY = decltype(poly_c)::value;
+#pragma unroll
+                for (int q = 0; q < EPT / 4; ++q) {
+                    const int j = q * 4 / EPV;
+                    if (j * kFusedThreads * EPV >= V) continue;      // uniform: the chunk holds no token
+                    u32x4 w = {0u, 0u, 0u, 0u};
+                    if constexpr (LH) w = sm_e2[q * kFusedThreads + t];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const int i = q * 4 + c;
+                        double D = 0.0;
+                        float pm = 0.f;
+#pragma unroll
+                        for (int h = 0; h < H; ++h) {
+                            const float eh = e_of(h, i, w);
+                            if constexpr (POLY) {
+                                const float G = fmaf(fmaf(fmaf(fmaf(pd[h][3], eh, pd[h][2]), eh, pd[h][1]), eh, pd[h][0]), eh, 1.0f);
+                                D = fma(cw[h], (double)(eh * G), D);
+                            } else {
+                                float g, du, om;
+                                fuse_parts<SPLIT>(eh, fr[h], g, du, om);
+                                D = fma(cw[h], (double)(g * om), D);
+                                if constexpr (!NOLOW) D = fma(cl[h], (double)(g * du), D);
+                            }
+                            if (ARGMAX) pm = fmaf(eh, invS[h], pm);
+                        }
+                        // A slot past the row's end holds e = 0 in every head: D = 0 exactly, so it adds -KD and KD^2
+                        // to the two sums, which thread 0 takes out again (the number of such slots is known); its mean
+                        // probability 0 never wins the arg-max (strict comparison, and the lane's real tokens come first).
+                        const double d = D - KD;
+                        s1 += d;
+                        s2 = fma(d, d, s2);
+                        if (ARGMAX && pm > best) { best = pm; best_i = (j * kFusedThreads + t) * EPV + (i - j * EPV); }
+                        if (c & 1) __builtin_amdgcn_sched_barrier(0);  // two tokens at a time: bounded working set
+                    }
+                }
+            };
+            using yes = std::integral_constant<bool, true>;
+            using no = std::integral_constant<bool, false>;
+            if (poly) sweep(yes{}, no{}, yes{});                    // (uniform over the wave)
+            else if (all_capless) { if (any_split) sweep(yes{}, yes{}, no{}); else sweep(yes{}, no{}, no{}); }
+            else { if (any_split) sweep(no{}, yes{}, no{}); else sweep(no{}, no{}, no{}); }
+        }
+        s1 = wave_sum(s1);
+        s2 = wave_sum(s2);
+        if (lane == 0) { sm_red[0][wave] = s1; sm_red[1][wave] = s2; }
+        if (ARGMAX) {
+            // each lane walked its tokens in ascending order, so it holds its lowest index of its maximum
+            const float wm = wave_max(best);
+            const int wi = wave_min_i(best == wm ? best_i : INT_MAX);
+            if (lane == 0) { sm_pm[wave] = wm; sm_pi[wave] = wi; }
+        }
+        __syncthreads();
+        if (t == 0) {
+            int Vr = V;
+            asm volatile("" : "+s"(Vr));                           // (so that its conversion stays in this block)
+            const double Hd = (double)H, Vd = (double)Vr;
+            double t1 = 0.0, t2 = 0.0;
+            for (int w = 0; w < NW; ++w) { t1 += sm_red[0][w]; t2 += sm_red[1][w]; }
+            {
+                // the slots of the tile past the row's end (chunks that hold no token at all were skipped)
+                const int chunks = (Vr + kFusedThreads * EPV - 1) / (kFusedThreads * EPV);
+                const double pad = (double)(chunks * kFusedThreads * EPV - Vr);
+                t1 += pad * KD;
+                t2 -= pad * KD * KD;
+            }
+            const double omega = (t1 + Vd * KD) / Hd;
+            const double var = fmax(0.0, t2 - t1 * t1 / Vd) / (Hd * Hd * Vd);
+            const double sigma = sqrt(var), score = omega * sigma;
+            if (A.omega) A.omega[row] = (float)omega;
+            if (A.sigma) A.sigma[row] = (float)sigma;
+            if (A.score) A.score[row] = (float)score;
+            if (A.flags) A.flags[row] = (uint8_t)(score > A.tau);
+            if (A.p_lo || A.p_mid || A.p_hi) {
+                int xid;
+                if (A.ids) {
+                    xid = A.ids[row];
+                    xid = xid < 0 ? 0 : (xid >= V ? V - 1 : xid);
+                } else {
+                    float rm = sm_pm[0];
+                    for (int w = 1; w < NW; ++w) rm = fmaxf(rm, sm_pm[w]);
+                    xid = INT_MAX;
+                    for (int w = 0; w < NW; ++w) if (sm_pm[w] == rm && sm_pi[w] < xid) xid = sm_pi[w];
+                    if (xid == INT_MAX) xid = 0;
+                }
+                double lo = 0.0, mid = 0.0, hi = 0.0;
+#pragma nounroll
+                for (int h = 0; h < H; ++h) {
+                    const T* crow = static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride;
+                    const double Sh = sm_Sh[h];
+                    const double ex = (double)exp2_ref(load_logit(crow, xid), sm_nh[h]);
+                    const double x = ex / Sh, omx = fmax(0.0, Sh - ex) / Sh;
+                    mid += x;
+                    lo += sm_alh[h] * rb * x / (rb + (1.0 - rb) * omx);
+                    hi += sm_auh[h] * ra * x / (1.0 + (ra - 1.0) * x);
+                }
+                if (A.p_lo) A.p_lo[row] = (float)(lo / Hd);
+                if (A.p_mid) A.p_mid[row] = (float)(mid / Hd);
+                if (A.p_hi) A.p_hi[row] = (float)(hi / Hd);
+            }
+        }
+        // (the next position's first barrier separates this read of sm_red / sm_pm from their next writes)
+    }
+}
+
 // Voting: flags[row] = strict majority of head_flags[h][row].
 __global__ __launch_bounds__(256) void vote_kernel(const uint8_t* __restrict__ head_flags, int H, int64_t N,
                                                    uint8_t* __restrict__ flags)
@@ -337,6 +711,71 @@ hipError_t launch_ensemble(int dtype, const RowArgs& args, int heads, int64_t he
         else hipLaunchKernelGGL((ensemble_kernel<bf16_t, false>), grid, block, 0, stream, args, heads, head_stride);
     }
     return hipGetLastError();
+}
+
+bool ensemble_fused_fits(int dtype, const RowArgs& args, int heads)
+{
+    if (args.radius || wide_radius(args) || needs_flat_pass(args) || heads < 1 || heads > kFusedHeads || args.V <= 64) return false;
+    const int epv = dtype == 0 ? 4 : 8;
+    const int nvec = (args.V + epv - 1) / epv;
+    const int per_lane = (nvec + kFusedThreads - 1) / kFusedThreads * epv;   // elements of one head's row per lane
+    return per_lane <= 32;
+}
+
+namespace {
+template <typename T, int NVEC, int H>
+hipError_t launch_ensemble_fused_heads(const RowArgs& a, int64_t head_stride, hipStream_t stream)
+{
+    const int64_t resident = 2 * (int64_t)compute_units();
+    const dim3 grid((unsigned)(a.N < resident ? a.N : resident)), block(kFusedThreads);
+    const bool argmax = a.ids == nullptr && (a.p_lo || a.p_mid || a.p_hi);
+    // the third head's exponentials: 4 bytes x elements per lane x lanes (64 KiB for the largest tile), above the
+    // default limit on dynamic LDS together with the static arrays: raised once per device and instance
+    constexpr unsigned lds = H == 3 ? NVEC * Elt<T>::kPerVec * kFusedThreads * 4u : 0u;
+    if (lds) {
+        static std::mutex guard;
+        static bool raised[2][64] = {};
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+        std::lock_guard<std::mutex> lock(guard);
+        if (!raised[argmax ? 1 : 0][dev]) {
+            const hipError_t e = argmax
+                ? hipFuncSetAttribute(reinterpret_cast<const void*>(&ensemble_fused_kernel<T, NVEC, H, true>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
+                : hipFuncSetAttribute(reinterpret_cast<const void*>(&ensemble_fused_kernel<T, NVEC, H, false>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            raised[argmax ? 1 : 0][dev] = true;
+        }
+    }
+    if (argmax) hipLaunchKernelGGL((ensemble_fused_kernel<T, NVEC, H, true>), grid, block, lds, stream, a, head_stride);
+    else hipLaunchKernelGGL((ensemble_fused_kernel<T, NVEC, H, false>), grid, block, lds, stream, a, head_stride);
+    return hipGetLastError();
+}
+template <typename T, int NVEC>
+hipError_t launch_ensemble_fused_cfg(const RowArgs& a, int heads, int64_t head_stride, hipStream_t stream)
+{
+    static_assert(kFusedHeads == 3, "one instance per number of heads");
+    if (heads == 1) return launch_ensemble_fused_heads<T, NVEC, 1>(a, head_stride, stream);
+    if (heads == 2) return launch_ensemble_fused_heads<T, NVEC, 2>(a, head_stride, stream);
+    return launch_ensemble_fused_heads<T, NVEC, 3>(a, head_stride, stream);
+}
+}  // namespace
+
+hipError_t launch_ensemble_fused(int dtype, const RowArgs& args, int heads, int64_t head_stride, hipStream_t stream)
+{
+    if (args.N <= 0) return hipSuccess;
+    if (!ensemble_fused_fits(dtype, args, heads)) return hipErrorInvalidValue;
+    const int epv = dtype == 0 ? 4 : 8;
+    const int nvec = (args.V + epv - 1) / epv;
+    const int per_lane = (nvec + kFusedThreads - 1) / kFusedThreads;
+    if (dtype == 0) {
+        if (per_lane <= 2) return launch_ensemble_fused_cfg<float, 2>(args, heads, head_stride, stream);
+        if (per_lane <= 4) return launch_ensemble_fused_cfg<float, 4>(args, heads, head_stride, stream);
+        return launch_ensemble_fused_cfg<float, 8>(args, heads, head_stride, stream);
+    }
+    if (per_lane <= 2) return launch_ensemble_fused_cfg<bf16_t, 2>(args, heads, head_stride, stream);
+    return launch_ensemble_fused_cfg<bf16_t, 4>(args, heads, head_stride, stream);
 }
 
 hipError_t launch_vote(const uint8_t* head_flags, int heads, int64_t N, uint8_t* flags, hipStream_t stream)

@@ -164,6 +164,10 @@ hipError_t launch_dro(int dtype, const RowArgs& args, float* terms, double lambd
 int max_heads();
 // Ensemble: token-wise mean of the heads' curves -> the [N] outputs in args.
 hipError_t launch_ensemble(int dtype, const RowArgs& args, int heads, int64_t head_stride, hipStream_t stream);
+// Ensemble in one sweep (no streaming pass before it, no RowStats): a few heads with a scalar radius whose rows of a
+// position fit one workgroup's registers together; every row is read once.  args as for launch_ensemble.
+bool ensemble_fused_fits(int dtype, const RowArgs& args, int heads);
+hipError_t launch_ensemble_fused(int dtype, const RowArgs& args, int heads, int64_t head_stride, hipStream_t stream);
 // Voting: flags[row] = strict majority of head_flags[h * N + row].
 hipError_t launch_vote(const uint8_t* head_flags, int heads, int64_t N, uint8_t* flags, hipStream_t stream);
 

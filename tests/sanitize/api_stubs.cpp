@@ -91,6 +91,16 @@ hipError_t launch_ensemble(int, const RowArgs& a, int heads, int64_t, hipStream_
     touch(a.stats, (size_t)heads * N);
     return hipSuccess;
 }
+// (the one-sweep route is taken for a few heads with a scalar radius, as in the library)
+bool ensemble_fused_fits(int, const RowArgs& a, int heads) { return !a.radius && heads <= 3 && a.V > 64 && a.V <= 16384; }
+hipError_t launch_ensemble_fused(int, const RowArgs& a, int, int64_t, hipStream_t)
+{
+    ++stubs::launches; stubs::last_args = a;
+    const size_t N = (size_t)a.N;
+    touch(a.p_lo, N); touch(a.p_mid, N); touch(a.p_hi, N); touch(a.omega, N); touch(a.sigma, N); touch(a.score, N);
+    touch(a.flags, N);
+    return hipSuccess;
+}
 hipError_t launch_vote(const uint8_t* head_flags, int heads, int64_t N, uint8_t* flags, hipStream_t)
 {
     ++stubs::launches;

@@ -471,6 +471,47 @@ def test_multihead_ensemble_and_voting(ciar, oracle, H, V, stride, N, dtype, ten
         assert np.all(same | near)
 
 
+ONE_SWEEP_CASES = [  # H, V, stride, N, dtype: every tile of the one-sweep Ensemble kernel, ragged vocabularies, N above its grid
+    (1, 4097, 4100, 40, torch.float32), (2, 8192, 8192, 70, torch.float32), (3, 8200, 8200, 33, torch.float32),
+    (2, 16384, 16384, 1100, torch.float32), (3, 16381, 16384, 25, torch.float32), (3, 130, 132, 700, torch.float32),
+    (3, 16384, 16384, 30, torch.bfloat16), (2, 9000, 9000, 30, torch.bfloat16), (1, 16384, 16384, 600, torch.bfloat16),
+    (3, 4099, 4104, 41, torch.bfloat16),
+]
+
+
+@pytest.mark.parametrize("H,V,stride,N,dtype", ONE_SWEEP_CASES)
+def test_ensemble_one_sweep_special_rows(ciar, oracle, H, V, stride, N, dtype):
+    """The one-sweep Ensemble kernel (a few heads, scalar radius) on the rows its branches are for: nearly one-hot
+    rows in one head or in all (active caps, probabilities above 1/2), rows with masked tokens, ordinary rows whose
+    tokens are all small (the width polynomial) next to peaked ones, with and without drafted ids, three radii."""
+    heads = _head_stack(H, V, stride, N, torch.float32, seed=7000 + V + H)
+    g = torch.Generator(device="cuda").manual_seed(11)
+    rows = torch.arange(N, device="cuda")
+    tok = torch.randint(0, V, (N,), generator=g, device="cuda")
+    heads[0, rows[1::5], tok[1::5]] += 25.0                 # one head nearly one-hot
+    heads[:, rows[2::5], tok[2::5]] += 30.0                 # every head nearly one-hot, the same token
+    heads[H - 1, rows[3::5], tok[3::5]] += 12.0             # a strong peak in the last head only
+    heads[:, rows[4::10], : max(1, V // 3)] = float("-inf")  # masked tokens
+    if stride > V:
+        heads[:, :, V:] = 1e30
+    heads = heads.to(dtype).contiguous()
+    ids = torch.randint(0, V, (N,), generator=g, device="cuda").to(torch.int32)
+    ids[2::5] = tok[2::5].to(torch.int32)                    # the reported token is the dominant one there
+    hh = heads.cpu()
+    for kw in (dict(confidence=0.9), dict(radius_scale=0.3), dict(radius_scale=2.5, normalize=False)):
+        say(f"[one-sweep ensemble] H={H} V={V} stride={stride} N={N} {dtype} {kw}")
+        o0 = oracle.quantify_multihead(hh, ids.cpu().numpy(), _oparams(oracle, ciar.Params(**kw)), oracle.ENSEMBLE, vocab=V)
+        tau = float(np.float32(np.median(o0["score"])))
+        P = ciar.Params(tau=tau, **kw)
+        OP = _oparams(oracle, P)
+        for with_ids in (True, False):
+            ge = ciar.quantify_multihead(heads, ids if with_ids else None, P, ciar.ENSEMBLE, vocab=V)
+            torch.cuda.synchronize()
+            oe = oracle.quantify_multihead(hh, ids.cpu().numpy() if with_ids else None, OP, oracle.ENSEMBLE, vocab=V)
+            parity.check_floats(ge, oe)
+            parity.check_flags(ge["flags"], oe, float(np.float32(tau)))
+
+
 # ---- Inter-DRO loss, forward (Sec. 3.2.3) -------------------------------------------------------------------
 
 def _check_dro(g, o, N):
