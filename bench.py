@@ -197,14 +197,14 @@ def bench_interdro(args, torch, ciar, wl, dev) -> int:
         "metric": f"token positions/sec (Inter-DRO loss forward, V={V} {'fp32' if elt == 4 else 'bf16'})",
         "value": N * args.steps / total_s, "unit": "positions/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f32" if elt == 4 else "bf16", "data": "synthetic",
         "config": {"workload": f"cfg{args.workload} {spec.name}: {N} positions, V={V}, "
                                f"{'fp32' if elt == 4 else 'bf16'} centre / raw radius / cloud logits, kappa 1, "
                                f"lambda_v 1, lambda_p 1, lambda_beta 0.5, alpha 1",
                    "input_copies_rotated": copies},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "whole call: dro_row_kernel + dro_batch_kernel", "kernel_avg_us": 1e3 * ms,
+                     "kernel": "whole call: dro_row_stream_kernel (dro_row_kernel for rows of 8 vectors per lane) + dro_batch_kernel", "kernel_avg_us": 1e3 * ms,
                      "algorithmic_bytes_per_launch": bytes_per_call},
     }
     if not args.no_cpu_baseline:

@@ -2,6 +2,8 @@
 // equations): per-row terms, batch softmax weights and the batch reduction.
 #include "ciar_device.h"
 
+#include <mutex>
+
 namespace ciar {
 namespace {
 
@@ -19,6 +21,16 @@ __device__ __forceinline__ float exp_rel(float c, float r, float cs, float rs, f
     return __builtin_amdgcn_exp2f(fmaf(d, kLog2eLo, d * kLog2eHi));
 }
 
+// r = min(kappa Softplus(raw), rmax) to ~1e-7 absolute (radius_r keeps small radii accurate relative to themselves, which
+// the interval widths need; here the radius only shifts logits, and the shorter form saves six instructions per token):
+// Softplus(raw) = max(raw, 0) + ln(1 + e^-|raw|).
+__device__ __forceinline__ float radius_abs(float raw, float kappa, float rmax)
+{
+    const float t = __builtin_amdgcn_exp2f(-fabsf(raw) * 1.44269504f);
+    const float sp = fmaf(__builtin_amdgcn_logf(1.0f + t), 0.693147181f, fmaxf(raw, 0.f));
+    return fminf(kappa * sp, rmax);
+}
+
 // e^(x - m) for a row of plain logits.
 __device__ __forceinline__ float exp_rel(float x, float m)
 {
@@ -33,49 +45,55 @@ __device__ __forceinline__ float exp_rel(float x, float m)
 //   CE(p_cloud, softmax(o)) = (max o + ln S_o) - (sum_i et_i o_i) / Z,
 //   KL(p_cloud || p_mid)    = (sum_i et_i t_i) / Z - (max t + ln Z) + CE(p_cloud, p_mid).
 // terms[k * N + row], k = 0..6: L1(mid), L1(up), L1(lo), CE(mid), CE(up), CE(lo), KL.
+// Workgroup barrier for data exchanged through LDS only: waits for this wave's LDS operations and joins the barrier.
+// __syncthreads() would also wait for every outstanding global load (its fence covers all memory), and with it for
+// the next row that dro_row_stream_kernel has in flight while it works on the current one.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// One row's totals (see dro_finish_row) from the three rows as loaded (lane t holds 16-byte vectors j * 1024 + t;
+// vectors past the end of the row hold copies of its last vector and are masked here), left in fin[kDroTotals] (LDS)
+// by lane 0.  Called by every lane of a 1024-lane workgroup; sm_d: 7 doubles per wave of LDS scratch.  Ends with every
+// lane past the last read of sm_d except wave 0's.
 template <typename T, int NVEC>
-__global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* __restrict__ terms)
+__device__ __forceinline__ void dro_row_compute(const RowArgs& A, double* fin,
+                                                u32x4 (&cw)[NVEC], u32x4 (&tw)[NVEC], u32x4 (&rw)[NVEC], double* sm_d,
+                                                const int tid)
 {
     using E = Elt<T>;
     constexpr int EPV = E::kPerVec, THREADS = 1024, NW = 16;
-    __shared__ double sm_d[NW * 7];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t row = blockIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
     const int V = A.V;
-    const int last_vec = (V + EPV - 1) / EPV - 1;
     const bool rad = A.radius != nullptr;                          // uniform
     const float kap = (float)A.kappa, rmax = (float)A.rmax;
     const float r0 = (float)fmin(A.kappa, A.rmax);                 // the scalar radius
-
-    const gbytes cb = (gbytes)(static_cast<const T*>(A.draft) + row * A.stride);
-    const gbytes tb = (gbytes)(static_cast<const T*>(A.target) + row * A.stride);
-    const gbytes rb = (gbytes)(static_cast<const T*>(rad ? A.radius : A.draft) + row * A.stride);
-    u32x4 cw[NVEC], tw[NVEC], rw[NVEC];
+    if (V < NVEC * THREADS * EPV) {                                // uniform: the row does not fill the tile
 #pragma unroll
-    for (int j = 0; j < NVEC; ++j) {
-        const uint32_t off = (uint32_t)min(j * THREADS + tid, last_vec) * 16u;
-        cw[j] = __builtin_nontemporal_load((gvec)(cb + off));     // every row is used once: stream past the caches
-        tw[j] = __builtin_nontemporal_load((gvec)(tb + off));
-        if (rad) rw[j] = __builtin_nontemporal_load((gvec)(rb + off));
-    }
-#pragma unroll
-    for (int j = 0; j < NVEC; ++j) {
-        const int base = (j * THREADS + tid) * EPV;
-        E::mask_tail(cw[j], base, V);
-        E::mask_tail(tw[j], base, V);
-        if (rad) E::zero_tail(rw[j], base, V);
+        for (int j = 0; j < NVEC; ++j) {
+            const int base = (j * THREADS + tid) * EPV;
+            E::mask_tail(cw[j], base, V);
+            E::mask_tail(tw[j], base, V);
+            if (rad) E::zero_tail(rw[j], base, V);
+        }
     }
     // The radii are formed once (Softplus costs about as much as the rest of a pass) and kept as floats where
     // the registers allow: up to 32 tokens per lane.  Beyond that they are recomputed in every pass.
     constexpr bool CACHE_R = NVEC * EPV <= 32;
     float rc[CACHE_R ? NVEC * EPV : 1];
     if constexpr (CACHE_R) {
+        if (rad) {                                                 // (one branch for the row, not one per token)
 #pragma unroll
-        for (int j = 0; j < NVEC; ++j) {
-            float rv[EPV];
-            if (rad) E::unpack(rw[j], rv);
+            for (int j = 0; j < NVEC; ++j) {
+                float rv[EPV];
+                E::unpack(rw[j], rv);
 #pragma unroll
-            for (int k = 0; k < EPV; ++k) rc[j * EPV + k] = rad ? radius_r(rv[k], kap, rmax) : r0;
+                for (int k = 0; k < EPV; ++k) rc[j * EPV + k] = radius_abs(rv[k], kap, rmax);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NVEC * EPV; ++i) rc[i] = r0;
         }
     }
     // element k of vector j: centre logit, radius, cloud logit
@@ -88,7 +106,7 @@ __global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* _
             r = rc[j * EPV + k];
         } else {
             r = r0;
-            if (rad) { E::unpack(rw[j], rv); r = radius_r(rv[k], kap, rmax); }
+            if (rad) { E::unpack(rw[j], rv); r = radius_abs(rv[k], kap, rmax); }
         }
     };
     // The three passes recompute the radius and the sums c +- r from the rows as loaded.  Passing the row
@@ -101,10 +119,12 @@ __global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* _
             if (!CACHE_R && rad) asm volatile("" : "+v"(rw[j]));
         }
     };
-    // pass 1: the four maxima; for c + r and c - r also the (c, r) of the token that carries the maximum
-    float mc = -INFINITY, mt = -INFINITY;
-    float su = -INFINITY, cu = 0.f, ru = 0.f;                      // max of c + r and its token
-    float sl = -INFINITY, cl = 0.f, rl = 0.f;                      // max of c - r and its token
+    // pass 1: the maxima of c and of the cloud logits, the largest and the smallest radius.  The partition sums of
+    // c + r and c - r are taken about (max c, max r) and (max c, min r): every exponent (c - max c) +- (r - r*) is
+    // then <= 0, and the token that carries max c has an exponent of at least -r_max (the radii lie in [0, r_max],
+    // r_max <= 16), so the sums neither overflow nor vanish.  Any reference serves in
+    // CE = (reference + ln S) - sum p_cloud o as long as S is taken about the same one.
+    float mc = -INFINITY, mt = -INFINITY, rhi = -INFINITY, rlo = INFINITY;
 #pragma unroll
     for (int j = 0; j < NVEC; ++j) {
 #pragma unroll
@@ -112,41 +132,48 @@ __global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* _
             float c, r, t;
             element(j, k, c, r, t);
             mc = fmaxf(mc, c); mt = fmaxf(mt, t);
-            const float s1 = c + r, s2 = c - r;
-            if (s1 > su) { su = s1; cu = c; ru = r; }
-            if (s2 > sl) { sl = s2; cl = c; rl = r; }
+            rhi = fmaxf(rhi, r); rlo = fminf(rlo, r);
         }
     }
+    // LDS for the reductions over the workgroup (see pass 2 for the scheme: quad sums by DPP, then transposed through
+    // LDS so that one short reduction serves all quantities at once)
+    __shared__ __attribute__((aligned(16))) double sm_w[NW][8][16];   // per wave: [quantity][quad]
+    __shared__ __attribute__((aligned(16))) double sm_x[8][16];       // [quantity][wave]
+    float cu, ru, cl, rl;
     {
-        // wave: the lowest lane that holds the wave's maximum hands over its token
-        auto wave_argmax = [&](float& sv, float& cv, float& rv) {
-            const float w = wave_max(sv);
-            const unsigned long long b = __ballot(sv == w);
-            const int src = b ? __ffsll((long long)b) - 1 : 0;
-            cv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cv), src));
-            rv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(rv), src));
-            sv = w;
+        // the four maxima over the workgroup: quads by DPP, the 16 quad maxima of each quantity through LDS into one
+        // DPP row each (lanes 16 q ... 16 q + 15 take quantity q), one row reduction for all four; the same again
+        // over the sixteen waves.  (Four wave-wide DPP maxima, twice, cost ~240 instructions.)
+        float m4[4] = {mc, mt, rhi, -rlo};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            m4[i] = dpp_max<0xB1, 0xf>(m4[i]);
+            m4[i] = dpp_max<0x4E, 0xf>(m4[i]);
+        }
+        float* fw = reinterpret_cast<float*>(&sm_w[wave][0][0]);   // [4][16] floats of this wave
+        __shared__ float sm_m[4 * 16];                             // [quantity][wave], this step's own (no barrier behind it)
+        float* fx = sm_m;
+        if ((lane & 3) == 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) fw[i * 16 + (lane >> 2)] = m4[i];
+        }
+        auto row_max = [](float v) {                               // lane 15 of each DPP row: the row's maximum
+            v = dpp_max<kRowShr1, 0xf>(v);
+            v = dpp_max<kRowShr2, 0xf>(v);
+            v = dpp_max<kRowShr4, 0xf>(v);
+            v = dpp_max<kRowShr8, 0xf>(v);
+            return v;
         };
-        mc = wave_max(mc); mt = wave_max(mt);
-        wave_argmax(su, cu, ru);
-        wave_argmax(sl, cl, rl);
-        float* slot = reinterpret_cast<float*>(sm_d);              // 8 floats per wave (sm_d holds 7 doubles per wave)
-        if (lane == 0) {
-            float* q = slot + wave * 8;
-            q[0] = mc; q[1] = mt; q[2] = su; q[3] = cu; q[4] = ru; q[5] = sl; q[6] = cl; q[7] = rl;
-        }
-        __syncthreads();
-        // every wave combines the sixteen waves' results across its lanes: lane l takes wave l & 15 (the copies in
-        // the upper lanes change no maximum, and the lowest lane that holds a maximum is the lowest wave)
-        {
-            const float* q = slot + (lane & 15) * 8;
-            mc = wave_max(q[0]); mt = wave_max(q[1]);
-            su = q[2]; cu = q[3]; ru = q[4];
-            sl = q[5]; cl = q[6]; rl = q[7];
-            wave_argmax(su, cu, ru);
-            wave_argmax(sl, cl, rl);
-        }
-        __syncthreads();                                           // sm_d is reused below
+        float v = row_max(fw[lane]);                               // (= fw[(lane >> 4) * 16 + (lane & 15)])
+        if ((lane & 15) == 15) fx[(lane >> 4) * 16 + wave] = v;
+        lds_barrier();
+        v = row_max(fx[lane]);
+        mc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 15));
+        mt = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 31));
+        rhi = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 47));
+        rlo = -__int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+        // (sm_m is written again in the next row's pass 1, with the barriers of passes 2 and 3 in between)
+        cu = mc; cl = mc; ru = rhi; rl = rlo;
     }
     // a row without a live token: any finite reference will do (every exponential is 0)
     if (mc == -INFINITY) mc = 0.f;
@@ -155,92 +182,280 @@ __global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* _
     auto uniform = [](float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); };
     mc = uniform(mc); mt = uniform(mt);
     cu = uniform(cu); ru = uniform(ru); cl = uniform(cl); rl = uniform(rl);
-    const double mu = (double)cu + (double)ru, ml = (double)cl - (double)rl;   // the two maxima, exact
 
-    // pass 2: partition sums and the p_cloud-weighted sums of c, r and the cloud logits
+    // pass 2: partition sums and the p_cloud-weighted sums of the exponents.  With d = o - reference (<= 0 for every
+    // token) and e = exp(d):   CE(p_cloud, softmax(o)) = ln S_o - (sum_i et_i d_i) / Z,   both terms non-negative, so
+    // the cross-entropies lose nothing to cancellation whatever the size of the logits; likewise the entropy of p_cloud,
+    // H = ln Z - (sum_i et_i dt_i) / Z, and KL(p_cloud || p_mid) = CE(p_cloud, p_mid) - H.
+    // With at most 16 tokens per lane the four exponentials of every token are kept for pass 3 (the rows themselves
+    // are not needed again), and the eight sums are first taken per lane in fp32: a lane's 16 terms round to ~1e-7 of
+    // the lane's sum, independently in 1024 lanes, which leaves a few 1e-9 of a total; across lanes and waves the sums
+    // run in fp64.
+    constexpr bool CACHE_E = NVEC * EPV <= 16;
+    constexpr int NE = CACHE_E ? NVEC * EPV : 1;
+    float em[NE], eu[NE], el[NE], ec[NE];
     fresh();
-    double acc[7] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};          // S_mid, S_up, S_lo, Z, sum et c, sum et r, sum et t
+    double acc[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};     // S_mid, S_up, S_lo, Z, sum et d_mid, d_up, d_lo, d_t
+    float s32[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    auto exp_of = [](float d) { return __builtin_amdgcn_exp2f(fmaf(d, kLog2eLo, d * kLog2eHi)); };
 #pragma unroll
     for (int j = 0; j < NVEC; ++j) {
 #pragma unroll
         for (int k = 0; k < EPV; ++k) {
             float c, r, t;
             element(j, k, c, r, t);
-            const float et = exp_rel(t, mt);
-            acc[0] += (double)exp_rel(c, mc);
-            acc[1] += (double)exp_rel(c, r, cu, ru, 1.f);
-            acc[2] += (double)exp_rel(c, r, cl, rl, -1.f);
-            acc[3] += (double)et;
-            if (et > 0.f) {                                        // a token the cloud rules out weighs nothing
-                acc[4] = fma((double)et, (double)c, acc[4]);
-                acc[5] = fma((double)et, (double)r, acc[5]);
-                acc[6] = fma((double)et, (double)t, acc[6]);
+            // (each difference is exact for tokens near the reference and rounded relative to itself elsewhere:
+            // c + r is never rounded to fp32)
+            const float d0 = c - mc, d1 = d0 + (r - ru), d2 = d0 - (r - rl), dt = t - mt;
+            const float e0 = exp_of(d0), e1 = exp_of(d1), e2 = exp_of(d2), et = exp_of(dt);
+            // a token the cloud rules out weighs nothing, whatever its logits are (0 x inf would be NaN)
+            const bool live = et > 0.f;
+            const float w0 = live ? d0 : 0.f, w1 = live ? d1 : 0.f, w2 = live ? d2 : 0.f, wt = live ? dt : 0.f;
+            if constexpr (CACHE_E) {
+                em[j * EPV + k] = e0; eu[j * EPV + k] = e1; el[j * EPV + k] = e2; ec[j * EPV + k] = et;
+                s32[0] += e0; s32[1] += e1; s32[2] += e2; s32[3] += et;
+                s32[4] = fmaf(et, w0, s32[4]); s32[5] = fmaf(et, w1, s32[5]);
+                s32[6] = fmaf(et, w2, s32[6]); s32[7] = fmaf(et, wt, s32[7]);
+            } else {
+                acc[0] += (double)e0; acc[1] += (double)e1; acc[2] += (double)e2; acc[3] += (double)et;
+                acc[4] = fma((double)et, (double)w0, acc[4]); acc[5] = fma((double)et, (double)w1, acc[5]);
+                acc[6] = fma((double)et, (double)w2, acc[6]); acc[7] = fma((double)et, (double)wt, acc[7]);
             }
             if (k & 1) __builtin_amdgcn_sched_barrier(0);          // two tokens at a time: bounded working set
         }
     }
+    if constexpr (CACHE_E) {
 #pragma unroll
-    for (int i = 0; i < 7; ++i) acc[i] = wave_sum(acc[i]);
-    if (lane == 0) {
-#pragma unroll
-        for (int i = 0; i < 7; ++i) sm_d[wave * 7 + i] = acc[i];
+        for (int i = 0; i < 8; ++i) acc[i] = (double)s32[i];
     }
-    __syncthreads();
-    // the sixteen waves' sums, one per lane of the first DPP row, added across that row in every wave
-    double tot[7];
+    // The eight sums over the workgroup.  A DPP reduction of one double over a wave is ~36 instructions, and with 16
+    // tokens per lane eight of them (and eight more across the waves) weighed more than the tokens' own arithmetic.
+    // Instead: two DPP steps leave every quad's sum in its lanes; the quad leaders put them into LDS, quantity by
+    // quantity; lane l then takes two of the 16 quad sums of quantity l / 8 (one 16-byte read) and three butterfly
+    // steps over its group of eight lanes finish the wave's sums of all quantities at once.  Across the waves the same
+    // two last steps run on the sixteen wave sums.
+    const int grp = lane >> 3, part = lane & 7;
+    auto group8_total = [](double a) {
+        a = dpp_add<0xB1, 0xf>(a);                                 // lane ^ 1  (quad_perm 1,0,3,2)
+        a = dpp_add<0x4E, 0xf>(a);                                 // lane ^ 2  (quad_perm 2,3,0,1)
+        a = dpp_add<0x141, 0xf>(a);                                // the other quad of the eight (row_half_mirror)
+        return a;
+    };
 #pragma unroll
-    for (int i = 0; i < 7; ++i) tot[i] = row16_sum(lane < NW ? sm_d[lane * 7 + i] : 0.0);
-    __syncthreads();                                               // sm_d is reused below
+    for (int i = 0; i < 8; ++i) {
+        acc[i] = dpp_add<0xB1, 0xf>(acc[i]);
+        acc[i] = dpp_add<0x4E, 0xf>(acc[i]);
+    }
+    if ((lane & 3) == 0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sm_w[wave][i][lane >> 2] = acc[i];
+    }
+    {
+        // (the wave reads what its own lanes have written: LDS operations of a wave complete in order)
+        const double* pr = &sm_w[wave][grp][2 * part];
+        const double a = group8_total(pr[0] + pr[1]);
+        if (part == 0) sm_x[grp][wave] = a;
+    }
+    lds_barrier();
+    double tot[8];
+    {
+        const double* pr = &sm_x[grp][2 * part];
+        const double a = group8_total(pr[0] + pr[1]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            tot[i] = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(a), 8 * i),
+                                      __builtin_amdgcn_readlane(__double2loint(a), 8 * i));
+    }
+    // (sm_x is written again only after the next barriers: pass 3's exchange uses sm_d)
 
     // pass 3: L1 distances to p_cloud
-    const float is0 = (float)(1.0 / tot[0]), is1 = (float)(1.0 / tot[1]), is2 = (float)(1.0 / tot[2]),
-                iz = (float)(1.0 / tot[3]);
+    // (the hardware reciprocal is good to one ulp: a common factor 1 +- 1e-7 on a row's probabilities)
+    const float is0 = __builtin_amdgcn_rcpf((float)tot[0]), is1 = __builtin_amdgcn_rcpf((float)tot[1]),
+                is2 = __builtin_amdgcn_rcpf((float)tot[2]), iz = __builtin_amdgcn_rcpf((float)tot[3]);
     double l1[3] = {0.0, 0.0, 0.0};
-    fresh();
+    if constexpr (CACHE_E) {
+        float a32[3] = {0.f, 0.f, 0.f};                            // (per lane in fp32, as above)
 #pragma unroll
-    for (int j = 0; j < NVEC; ++j) {
+        for (int i = 0; i < NE; ++i) {
+            const float pc = ec[i] * iz;
+            a32[0] += fabsf(em[i] * is0 - pc);
+            a32[1] += fabsf(eu[i] * is1 - pc);
+            a32[2] += fabsf(el[i] * is2 - pc);
+        }
 #pragma unroll
-        for (int k = 0; k < EPV; ++k) {
-            float c, r, t;
-            element(j, k, c, r, t);
-            const float pc = exp_rel(t, mt) * iz;
-            l1[0] += (double)fabsf(exp_rel(c, mc) * is0 - pc);
-            l1[1] += (double)fabsf(exp_rel(c, r, cu, ru, 1.f) * is1 - pc);
-            l1[2] += (double)fabsf(exp_rel(c, r, cl, rl, -1.f) * is2 - pc);
-            if (k & 1) __builtin_amdgcn_sched_barrier(0);
+        for (int i = 0; i < 3; ++i) l1[i] = (double)a32[i];
+    } else {
+        fresh();
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) {
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) {
+                float c, r, t;
+                element(j, k, c, r, t);
+                const float pc = exp_rel(t, mt) * iz;
+                l1[0] += (double)fabsf(exp_rel(c, mc) * is0 - pc);
+                l1[1] += (double)fabsf(exp_rel(c, r, cu, ru, 1.f) * is1 - pc);
+                l1[2] += (double)fabsf(exp_rel(c, r, cl, rl, -1.f) * is2 - pc);
+                if (k & 1) __builtin_amdgcn_sched_barrier(0);
+            }
         }
     }
+    // The three distances are sums of non-negative terms and are wanted to 1e-5 of themselves: fp32 across the lanes
+    // (a DPP step of a float is one instruction, of a double five).
+    {
+        float* slot = reinterpret_cast<float*>(sm_d);              // [3][NW] floats
 #pragma unroll
-    for (int i = 0; i < 3; ++i) l1[i] = wave_sum(l1[i]);
-    if (lane == 0) {
-#pragma unroll
-        for (int i = 0; i < 3; ++i) sm_d[wave * 7 + i] = l1[i];
+        for (int i = 0; i < 3; ++i) {
+            float v = (float)l1[i];
+            v += __int_as_float(dpp_or<kRowShr1, 0xf>(0, __float_as_int(v)));
+            v += __int_as_float(dpp_or<kRowShr2, 0xf>(0, __float_as_int(v)));
+            v += __int_as_float(dpp_or<kRowShr4, 0xf>(0, __float_as_int(v)));
+            v += __int_as_float(dpp_or<kRowShr8, 0xf>(0, __float_as_int(v)));
+            v += __int_as_float(dpp_or<kRowBcast15, 0xa>(0, __float_as_int(v)));
+            v += __int_as_float(dpp_or<kRowBcast31, 0xc>(0, __float_as_int(v)));
+            if (lane == 63) slot[i * NW + wave] = v;
+        }
     }
-    __syncthreads();
+    lds_barrier();
     if (wave == 0) {
         double L[3];
+        const float* slot = reinterpret_cast<const float*>(sm_d);
 #pragma unroll
-        for (int i = 0; i < 3; ++i) L[i] = row16_sum(lane < NW ? sm_d[lane * 7 + i] : 0.0);
-        // the four logarithms side by side: lane i takes ln tot[i]
-        const double mine = lane == 0 ? tot[0] : lane == 1 ? tot[1] : lane == 2 ? tot[2] : tot[3];
-        const double lg = log(mine);
-        auto from_lane = [&](int src) {
-            return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(lg), src),
-                                    __builtin_amdgcn_readlane(__double2loint(lg), src));
-        };
-        const double ln_s0 = from_lane(0), ln_s1 = from_lane(1), ln_s2 = from_lane(2), ln_z = from_lane(3);
-        if (lane != 0) return;
-        const double Z = tot[3];
-        const double pc_c = tot[4] / Z, pc_r = tot[5] / Z, pc_t = tot[6] / Z;
-        const double ce_mid = ((double)mc + ln_s0) - pc_c;
-        const double ce_up = (mu + ln_s1) - (pc_c + pc_r);
-        const double ce_lo = (ml + ln_s2) - (pc_c - pc_r);
-        const double kl = pc_t - ((double)mt + ln_z) + ce_mid;
-        const int64_t N = A.N;
-        terms[0 * N + row] = (float)L[0]; terms[1 * N + row] = (float)L[1]; terms[2 * N + row] = (float)L[2];
-        terms[3 * N + row] = (float)ce_mid; terms[4 * N + row] = (float)ce_up; terms[5 * N + row] = (float)ce_lo;
-        terms[6 * N + row] = (float)kl;
+        for (int i = 0; i < 3; ++i) L[i] = (double)row16_sum_f(lane < NW ? slot[i * NW + lane] : 0.f);
+        // the row's totals, for dro_finish_row: S_mid, S_up, S_lo, Z, the four p_cloud-weighted sums of exponents (times Z),
+        // the three L1 distances
+        if (lane == 0) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) fin[i] = tot[i];
+            fin[8] = L[0]; fin[9] = L[1]; fin[10] = L[2];
+        }
     }
+}
+
+// The seven terms of a row from its totals (kDroTotals doubles, as dro_row_compute leaves them).  One lane per row.
+// Kept out of the row loop of dro_row_stream_kernel: the constants of the fp64 logarithm would otherwise be hoisted to
+// the top of that loop and live in registers (or in scratch memory) through all of it.
+constexpr int kDroTotals = 11;
+__device__ __forceinline__ void dro_finish_row(const RowArgs& A, float* __restrict__ terms, const int64_t row,
+                                               const double* fin)
+{
+    const double Z = fin[3];
+    const double ce_mid = log(fin[0]) - fin[4] / Z;
+    const double ce_up = log(fin[1]) - fin[5] / Z;
+    const double ce_lo = log(fin[2]) - fin[6] / Z;
+    const double kl = ce_mid - (log(Z) - fin[7] / Z);              // cross-entropy minus the entropy of p_cloud
+    const int64_t N = A.N;
+    terms[0 * N + row] = (float)fin[8]; terms[1 * N + row] = (float)fin[9]; terms[2 * N + row] = (float)fin[10];
+    terms[3 * N + row] = (float)ce_mid; terms[4 * N + row] = (float)ce_up; terms[5 * N + row] = (float)ce_lo;
+    terms[6 * N + row] = (float)kl;
+}
+
+template <typename T, int NVEC>
+__global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* __restrict__ terms)
+{
+    constexpr int THREADS = 1024, NW = 16;
+    __shared__ double sm_d[NW * 7];
+    const int tid = threadIdx.x;
+    const int64_t row = blockIdx.x;
+    const int last_vec = (A.V + Elt<T>::kPerVec - 1) / Elt<T>::kPerVec - 1;
+    const bool rad = A.radius != nullptr;                          // uniform
+    const gbytes cb = (gbytes)(static_cast<const T*>(A.draft) + row * A.stride);
+    const gbytes tb = (gbytes)(static_cast<const T*>(A.target) + row * A.stride);
+    const gbytes rb = (gbytes)(static_cast<const T*>(rad ? A.radius : A.draft) + row * A.stride);
+    u32x4 cw[NVEC], tw[NVEC], rw[NVEC];
+#pragma unroll
+    for (int j = 0; j < NVEC; ++j) {
+        const uint32_t off = (uint32_t)min(j * THREADS + tid, last_vec) * 16u;
+        cw[j] = __builtin_nontemporal_load((gvec)(cb + off));     // every row is used once: stream past the caches
+        tw[j] = __builtin_nontemporal_load((gvec)(tb + off));
+        if (rad) rw[j] = __builtin_nontemporal_load((gvec)(rb + off));
+    }
+    __shared__ double sm_fin[kDroTotals];
+    dro_row_compute<T, NVEC>(A, sm_fin, cw, tw, rw, sm_d, tid);
+    if (tid == 0) dro_finish_row(A, terms, row, sm_fin);           // (the lane that has written the totals)
+}
+
+constexpr int kDroRowsPerWg = 64;                                  // most rows a workgroup of dro_row_stream_kernel takes
+
+// The same with the next row on its way while a row is worked on.  One 1024-lane workgroup per compute unit walks
+// over rows blockIdx.x, blockIdx.x + gridDim.x, ...; the three rows of a position and the working set leave no
+// registers to fetch ahead into, and a second workgroup does not fit a compute unit, so the centre and cloud rows of
+// the NEXT position are loaded straight into LDS (global_load_lds_dwordx4: the data of lane l of a wave lands 16 l
+// bytes behind the LDS address the wave names; no register is held while the load is in flight) and the raw-radius
+// row into the NVEC registers that the current radius row has left.  Every lane reads back only the slots that its own
+// wave's loads have written, so the hand-over needs the wave's own vmcnt(0) and no barrier.
+// Dynamic LDS: 2 x NVEC x 16 KiB (NVEC <= 4).
+template <typename T, int NVEC>
+__global__ __launch_bounds__(1024) void dro_row_stream_kernel(const RowArgs A, float* __restrict__ terms)
+{
+    constexpr int THREADS = 1024, NW = 16;
+    extern __shared__ u32x4 sm_rows[];                             // [2][NVEC][THREADS]: next centre row, next cloud row
+    __shared__ double sm_d[NW * 7];
+    __shared__ double sm_fin[kDroRowsPerWg][kDroTotals];           // the totals of this workgroup's rows
+    const int tid = threadIdx.x;
+    const int wave_s = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int last_vec = (A.V + Elt<T>::kPerVec - 1) / Elt<T>::kPerVec - 1;
+    const bool rad = A.radius != nullptr;                          // uniform
+    using lds_ptr = __attribute__((address_space(3))) void*;
+    using glb_ptr = const __attribute__((address_space(1))) void*;
+
+    // the centre and cloud rows of `row` go on their way to LDS
+    auto request_rows = [&](int64_t row, int tid) {
+        const gbytes cb = (gbytes)(static_cast<const T*>(A.draft) + row * A.stride);
+        const gbytes tb = (gbytes)(static_cast<const T*>(A.target) + row * A.stride);
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) {
+            const uint32_t off = (uint32_t)min(j * THREADS + tid, last_vec) * 16u;
+            __builtin_amdgcn_global_load_lds((glb_ptr)(cb + off), (lds_ptr)(sm_rows + (0 * NVEC + j) * THREADS + wave_s * 64), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((glb_ptr)(tb + off), (lds_ptr)(sm_rows + (1 * NVEC + j) * THREADS + wave_s * 64), 16, 0, 0);
+        }
+    };
+    auto request_radius = [&](int64_t row, u32x4 (&rn)[NVEC], int tid) {
+        const gbytes rb = (gbytes)(static_cast<const T*>(A.radius) + row * A.stride);
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) {
+            const uint32_t off = (uint32_t)min(j * THREADS + tid, last_vec) * 16u;
+            rn[j] = __builtin_nontemporal_load((gvec)(rb + off));
+        }
+    };
+    u32x4 rnext[NVEC];
+#pragma unroll
+    for (int j = 0; j < NVEC; ++j) rnext[j] = u32x4{0u, 0u, 0u, 0u};
+    int64_t row = blockIdx.x;
+    int done = 0;                                                  // rows of this workgroup finished so far (<= kDroRowsPerWg)
+    if (row < A.N) {
+        request_rows(row, tid);
+        if (rad) request_radius(row, rnext, tid);
+    }
+    for (; row < A.N; row += gridDim.x) {
+        // this wave's loads have landed (its slots of the two rows in LDS, and the radius registers)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // (the lane's index is made opaque once per row: the LDS addresses derived from it are cheap to form again, and
+        // hoisted out of this loop they would hold a dozen registers through all of it)
+        int t = tid;
+        asm volatile("" : "+v"(t));
+        u32x4 cw[NVEC], tw[NVEC], rw[NVEC];
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) {
+            cw[j] = sm_rows[(0 * NVEC + j) * THREADS + t];
+            tw[j] = sm_rows[(1 * NVEC + j) * THREADS + t];
+            rw[j] = rnext[j];
+        }
+        // the slots are free again once they have been read: the next position's rows go in flight now
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        const int64_t next = row + gridDim.x;
+        if (next < A.N) {
+            request_rows(next, t);
+            if (rad) request_radius(next, rnext, t);
+        }
+        dro_row_compute<T, NVEC>(A, sm_fin[done], cw, tw, rw, sm_d, t);
+        // (no barrier here: what wave 0 still reads of sm_d is written again only in the next row's pass 3, two
+        // barriers on)
+        ++done;
+    }
+    // one lane per row turns the totals into the row's terms
+    __syncthreads();
+    if (tid < done) dro_finish_row(A, terms, (int64_t)blockIdx.x + (int64_t)tid * gridDim.x, sm_fin[tid]);
 }
 
 // The same terms for a handful of tokens (V <= kTinyVocab): one thread per row, fp64 throughout.  With so few
@@ -292,56 +507,96 @@ __global__ __launch_bounds__(256) void dro_row_tiny_kernel(const RowArgs A, floa
 }
 
 // Batch stage: w_n = softmax_n(alpha CE_n(p_lo)), DRO = sum w CE(p_lo), batch means of the anchor and alignment
-// terms.  One workgroup; losses = { centre, upper, lower, DRO, total }.
-__global__ __launch_bounds__(1024) void dro_batch_kernel(const float* __restrict__ terms, int64_t N, double lambda_v,
-                                                         double lambda_p, double lambda_beta, double alpha,
-                                                         float* __restrict__ weights, float* __restrict__ losses)
+// terms.  One workgroup of 256 lanes; losses = { centre, upper, lower, DRO, total }.  One fp64 exponential per row:
+// the unnormalised weight is parked in `weights` (when the caller wants them) and scaled by the normaliser in a last
+// pass by the lane that wrote it.
+__global__ __launch_bounds__(256) void dro_batch_kernel(const float* __restrict__ terms, int64_t N, double lambda_v,
+                                                        double lambda_p, double lambda_beta, double alpha,
+                                                        float* __restrict__ weights, float* __restrict__ losses)
 {
-    constexpr int NW = 16;
-    __shared__ double sm[NW * 4];
+    constexpr int NW = 4, T = 256;
+    __shared__ double sm[NW * 5];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* ce_lo = terms + 5 * N;
-    auto block_sum = [&](double v, int slot) -> double {
-        v = wave_sum(v);
-        if (lane == 0) sm[wave * 4 + slot] = v;
-        __syncthreads();
-        double t = 0.0;
-        for (int w = 0; w < NW; ++w) t += sm[w * 4 + slot];
-        __syncthreads();
-        return t;
-    };
     float mxf = -INFINITY;
     double c = 0.0, u = 0.0, l = 0.0;
-    for (int64_t n = tid; n < N; n += 1024) {
+    for (int64_t n = tid; n < N; n += T) {
         mxf = fmaxf(mxf, (float)(alpha * (double)ce_lo[n]));
         c += lambda_v * terms[n] + lambda_p * terms[3 * N + n] + lambda_beta * terms[6 * N + n];
         u += lambda_v * terms[N + n] + lambda_p * terms[4 * N + n];
         l += lambda_v * terms[2 * N + n] + lambda_p * terms[5 * N + n];
     }
     mxf = wave_max(mxf);
-    if (lane == 0) sm[wave * 4] = (double)mxf;
+    if (lane == 0) sm[wave] = (double)mxf;
     __syncthreads();
     double mx = sm[0];
-    for (int w = 1; w < NW; ++w) mx = fmax(mx, sm[w * 4]);
+    for (int w = 1; w < NW; ++w) mx = fmax(mx, sm[w]);
     __syncthreads();
-    c = block_sum(c, 0); u = block_sum(u, 1); l = block_sum(l, 2);
-    double den = 0.0;
-    for (int64_t n = tid; n < N; n += 1024) den += exp(alpha * (double)ce_lo[n] - mx);
-    den = block_sum(den, 3);
-    double dro = 0.0;
-    for (int64_t n = tid; n < N; n += 1024) {
-        const double w = exp(alpha * (double)ce_lo[n] - mx) / den;
-        if (weights) weights[n] = (float)w;
-        dro = fma(w, (double)ce_lo[n], dro);
+    double den = 0.0, num = 0.0;
+    for (int64_t n = tid; n < N; n += T) {
+        const double ce = (double)ce_lo[n];
+        const double e = exp(alpha * ce - mx);
+        den += e;
+        num = fma(e, ce, num);
+        if (weights) weights[n] = (float)e;                        // scaled below
     }
-    dro = block_sum(dro, 0);
+    c = wave_sum(c); u = wave_sum(u); l = wave_sum(l); den = wave_sum(den); num = wave_sum(num);
+    if (lane == 0) { sm[wave * 5] = c; sm[wave * 5 + 1] = u; sm[wave * 5 + 2] = l; sm[wave * 5 + 3] = den; sm[wave * 5 + 4] = num; }
+    __syncthreads();
+    double tot[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    for (int w = 0; w < NW; ++w)
+        for (int i = 0; i < 5; ++i) tot[i] += sm[w * 5 + i];
+    if (weights) {
+        // float(e) / den in fp64 rounds e twice (once to float above): 6e-8 relative, far inside the weights' tolerance
+        const double inv = 1.0 / tot[3];
+        for (int64_t n = tid; n < N; n += T) weights[n] = (float)((double)weights[n] * inv);
+    }
     if (tid == 0 && losses) {
-        const double Nd = (double)N;
-        losses[0] = (float)(c / Nd); losses[1] = (float)(u / Nd); losses[2] = (float)(l / Nd); losses[3] = (float)dro;
-        losses[4] = (float)(c / Nd + u / Nd + l / Nd + dro);
+        const double Nd = (double)N, dro = tot[4] / tot[3];
+        losses[0] = (float)(tot[0] / Nd); losses[1] = (float)(tot[1] / Nd); losses[2] = (float)(tot[2] / Nd);
+        losses[3] = (float)dro;
+        losses[4] = (float)(tot[0] / Nd + tot[1] / Nd + tot[2] / Nd + dro);
     }
 }
 
+}  // namespace
+
+namespace {
+template <typename T, int NVEC>
+hipError_t launch_dro_stream_cfg(const RowArgs& a, float* terms, hipStream_t stream)
+{
+    constexpr unsigned lds = 2u * NVEC * 1024u * 16u;
+    if (lds > 48u * 1024u) {
+        // above the default limit on dynamic LDS: raised once per device and instance
+        static std::mutex guard;
+        static bool raised[64] = {};
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+        std::lock_guard<std::mutex> lock(guard);
+        if (!raised[dev]) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dro_row_stream_kernel<T, NVEC>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            raised[dev] = true;
+        }
+    }
+    // one workgroup per compute unit; more of them (taking their turn) when that would give a workgroup more than
+    // kDroRowsPerWg rows
+    int64_t g = compute_units();
+    const int64_t need = (a.N + kDroRowsPerWg - 1) / kDroRowsPerWg;
+    if (g < need) g = need;
+    if (g > a.N) g = a.N;
+    const dim3 grid((unsigned)g), block(1024);
+    hipLaunchKernelGGL((dro_row_stream_kernel<T, NVEC>), grid, block, lds, stream, a, terms);
+    return hipGetLastError();
+}
+template <typename T>
+hipError_t launch_dro_stream(int nvec, const RowArgs& a, float* terms, hipStream_t stream)
+{
+    if (nvec == 1) return launch_dro_stream_cfg<T, 1>(a, terms, stream);
+    if (nvec == 2) return launch_dro_stream_cfg<T, 2>(a, terms, stream);
+    return launch_dro_stream_cfg<T, 4>(a, terms, stream);
+}
 }  // namespace
 
 hipError_t launch_dro(int dtype, const RowArgs& args, float* terms, double lambda_v, double lambda_p,
@@ -360,6 +615,12 @@ hipError_t launch_dro(int dtype, const RowArgs& args, float* terms, double lambd
         const dim3 tgrid((unsigned)((args.N + 255) / 256)), tblock(256);
         if (dtype == 0) hipLaunchKernelGGL(dro_row_tiny_kernel<float>, tgrid, tblock, 0, stream, args, terms);
         else hipLaunchKernelGGL(dro_row_tiny_kernel<bf16_t>, tgrid, tblock, 0, stream, args, terms);
+    } else if (vecs <= 4096 && args.N > (int64_t)compute_units()) {
+        // more rows than compute units: persistent workgroups that fetch the next row through LDS
+        const int nv = vecs <= 1024 ? 1 : vecs <= 2048 ? 2 : 4;
+        const hipError_t e = dtype == 0 ? launch_dro_stream<float>(nv, args, terms, stream)
+                                        : launch_dro_stream<bf16_t>(nv, args, terms, stream);
+        if (e != hipSuccess) return e;
     } else if (vecs <= 1024) CIAR_DRO_LAUNCH(1);
     else if (vecs <= 2048) CIAR_DRO_LAUNCH(2);
     else if (vecs <= 4096) CIAR_DRO_LAUNCH(4);
@@ -368,7 +629,7 @@ hipError_t launch_dro(int dtype, const RowArgs& args, float* terms, double lambd
 #undef CIAR_DRO_LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || (!weights && !losses)) return e;
-    hipLaunchKernelGGL(dro_batch_kernel, dim3(1), dim3(1024), 0, stream, terms, args.N, lambda_v, lambda_p,
+    hipLaunchKernelGGL(dro_batch_kernel, dim3(1), dim3(256), 0, stream, terms, args.N, lambda_v, lambda_p,
                        lambda_beta, alpha, weights, losses);
     return hipGetLastError();
 }
