@@ -45,6 +45,7 @@ __global__ __launch_bounds__(THREADS) void resample_kernel(const RowArgs A, cons
     constexpr int SCAN = 4096, MPL = SCAN / THREADS;   // marks read per step of the search, and per lane
 
     __shared__ double sm_e[NW * MAXCH + NW];
+    __shared__ __attribute__((aligned(16))) double sm_q[NW][8][16];   // per wave: [chunk of the group][quad]
     __shared__ int    sm_i[NW * 2];
     __shared__ int    sm_mine[SCAN];                // the rows of a step that this workgroup draws
     __shared__ int    sm_wcount[NW];
@@ -61,14 +62,34 @@ __global__ __launch_bounds__(THREADS) void resample_kernel(const RowArgs A, cons
     const int64_t lo_row = rank_all ? 0 : (int64_t)g * slice;
     const int64_t hi_row = rank_all ? N : (lo_row + slice < N ? lo_row + slice : N);
     int ranked = 0;                                 // marked rows before this step (rank_all)
+    // (a step starts at a multiple of SCAN rows behind lo_row, a lane at a multiple of MPL rows behind that)
+    const bool marks_aligned = ((reinterpret_cast<uintptr_t>(A.accept) + (uintptr_t)lo_row) & 15u) == 0;
 
     for (int64_t s0 = lo_row; s0 < hi_row; s0 += SCAN) {
     // ---- this step's marks: lane t looks at rows s0 + t MPL ... s0 + t MPL + MPL - 1 ------------------------------
     unsigned mask = 0;
+    const int64_t r_first = s0 + (int64_t)tid * MPL;
+    if (marks_aligned && r_first + MPL <= hi_row) {
+        // the lane's MPL accept bytes in one load; they are 0 or 1 (this call's streaming kernel wrote them), so
+        // ~w & 0x01010101 has a bit per rejected row, which one multiplication gathers into four adjacent bits
+        const uint32_t* w = reinterpret_cast<const uint32_t*>(A.accept + r_first);
+        uint32_t words[MPL / 4];
+        if constexpr (MPL == 16) {
+            const u32x4 v = *reinterpret_cast<const u32x4*>(w);
+            words[0] = v.x; words[1] = v.y; words[2] = v.z; words[3] = v.w;
+        } else {
 #pragma unroll
-    for (int k = 0; k < MPL; ++k) {
-        const int64_t r = s0 + (int64_t)tid * MPL + k;
-        if (r < hi_row && A.accept[r] == 0) mask |= 1u << k;
+            for (int i = 0; i < MPL / 4; ++i) words[i] = w[i];
+        }
+#pragma unroll
+        for (int i = 0; i < MPL / 4; ++i)
+            mask |= ((((~words[i]) & 0x01010101u) * 0x01020408u) >> 24 & 0xfu) << (4 * i);
+    } else {
+#pragma unroll
+        for (int k = 0; k < MPL; ++k) {
+            const int64_t r = r_first + k;
+            if (r < hi_row && A.accept[r] == 0) mask |= 1u << k;
+        }
     }
     const int mine_cnt = __popc(mask);
     const int incl = (int)wave_scan((double)mine_cnt);             // exact: small integers
@@ -98,7 +119,7 @@ __global__ __launch_bounds__(THREADS) void resample_kernel(const RowArgs A, cons
         const T* crow = static_cast<const T*>(A.draft) + row * A.stride;
         const T* trow = static_cast<const T*>(A.target) + row * A.stride;
         const RowStats st = A.stats[row];
-        const double invS = 1.0 / st.S, invZ = 1.0 / st.Z;
+        const float invSf = (float)(1.0 / st.S), invZf = (float)(1.0 / st.Z);
         const float n = st.n, nt = st.nt;
         const double u_res = (double)A.u_resample[row];
 
@@ -115,30 +136,55 @@ __global__ __launch_bounds__(THREADS) void resample_kernel(const RowArgs A, cons
             float cv[EPV], tv[EPV];
             E::unpack(cr, cv);
             E::unpack(tr, tv);
+            // q - p in fp32: the product e / S is rounded once (6e-8 of p, below the ~1e-7 of p and of q that the fp32
+            // exponentials carry anyway) and the FMA forms the difference from the exact product et / Z
 #pragma unroll
-            for (int k = 0; k < EPV; ++k) {
-                const double q = (double)exp2_ref(tv[k], nt) * invZ;
-                const double p = (double)exp2_ref(cv[k], n) * invS;
-                r[k] = (float)fmax(q - p, 0.0);
-            }
+            for (int k = 0; k < EPV; ++k)
+                r[k] = fmaxf(fmaf(exp2_ref(tv[k], nt), invZf, -(exp2_ref(cv[k], n) * invSf)), 0.f);
         };
-        // E1: workgroup totals of the residual over each chunk of CHUNK tokens, UB chunks of each row in flight
-        for (int j0 = 0; j0 < nch; j0 += UB) {
-            u32x4 cb[UB], tb[UB];
+        // E1: workgroup totals of the residual over each chunk of CHUNK tokens, eight chunks at a time (UB of each row
+        // in flight).  The eight lane sums are reduced over the wave together: two DPP steps leave every quad's sums
+        // in its lanes, the quad leaders put them into LDS chunk by chunk, lane l takes two of the 16 quad sums of chunk
+        // l / 8 and three butterfly steps over its eight lanes finish all eight totals (one DPP reduction of a double
+        // over a wave per chunk cost three times as many instructions).
+        for (int j0 = 0; j0 < nch; j0 += 8) {
+            double ls[8];
 #pragma unroll
-            for (int u = 0; u < UB; ++u) { cb[u] = load_vec(crow, j0 + u); tb[u] = load_vec(trow, j0 + u); }
+            for (int half = 0; half < 8 / UB; ++half) {
+                u32x4 cb[UB], tb[UB];
 #pragma unroll
-            for (int u = 0; u < UB; ++u) {
-                if (j0 + u < nch) {                                // uniform
-                    float r[EPV];
-                    residuals(cb[u], tb[u], j0 + u, r);
-                    float s = 0.f;
+                for (int u = 0; u < UB; ++u) {
+                    cb[u] = load_vec(crow, j0 + half * UB + u);
+                    tb[u] = load_vec(trow, j0 + half * UB + u);
+                }
 #pragma unroll
-                    for (int k = 0; k < EPV; ++k) s += r[k];
-                    const double ws = wave_sum((double)s);
-                    if (lane == 0) sm_e[wave * MAXCH + j0 + u] = ws;
+                for (int u = 0; u < UB; ++u) {
+                    float sacc = 0.f;
+                    if (j0 + half * UB + u < nch) {                // uniform
+                        float r[EPV];
+                        residuals(cb[u], tb[u], j0 + half * UB + u, r);
+#pragma unroll
+                        for (int k = 0; k < EPV; ++k) sacc += r[k];
+                    }
+                    ls[half * UB + u] = (double)sacc;
                 }
             }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                ls[i] = dpp_add<0xB1, 0xf>(ls[i]);                 // lane ^ 1  (quad_perm 1,0,3,2)
+                ls[i] = dpp_add<0x4E, 0xf>(ls[i]);                 // lane ^ 2  (quad_perm 2,3,0,1)
+            }
+            if ((lane & 3) == 0) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) sm_q[wave][i][lane >> 2] = ls[i];
+            }
+            // (the wave reads what its own lanes have written: LDS operations of a wave complete in order)
+            const double* pr = &sm_q[wave][lane >> 3][2 * (lane & 7)];
+            double a = pr[0] + pr[1];
+            a = dpp_add<0xB1, 0xf>(a);
+            a = dpp_add<0x4E, 0xf>(a);
+            a = dpp_add<0x141, 0xf>(a);                            // the other quad of the eight (row_half_mirror)
+            if ((lane & 7) == 0 && j0 + (lane >> 3) < nch) sm_e[wave * MAXCH + j0 + (lane >> 3)] = a;
         }
         __syncthreads();
         // Every wave locates the crossing chunk across its lanes: lane j < nch holds chunk j's total over the
