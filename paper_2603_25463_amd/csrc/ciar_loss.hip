@@ -269,9 +269,12 @@ __device__ __forceinline__ void dro_row_compute(const RowArgs& A, double* fin,
     // (sm_x is written again only after the next barriers: pass 3's exchange uses sm_d)
 
     // pass 3: L1 distances to p_cloud
-    // (the hardware reciprocal is good to one ulp: a common factor 1 +- 1e-7 on a row's probabilities)
-    const float is0 = __builtin_amdgcn_rcpf((float)tot[0]), is1 = __builtin_amdgcn_rcpf((float)tot[1]),
-                is2 = __builtin_amdgcn_rcpf((float)tot[2]), iz = __builtin_amdgcn_rcpf((float)tot[3]);
+    // (hardware reciprocal plus one Newton step: as good as the rounding of the sum to fp32, without an fp64 division)
+    auto recip = [](double S) {
+        const float s = (float)S, r = __builtin_amdgcn_rcpf(s);
+        return fmaf(r, fmaf(-s, r, 1.0f), r);
+    };
+    const float is0 = recip(tot[0]), is1 = recip(tot[1]), is2 = recip(tot[2]), iz = recip(tot[3]);
     double l1[3] = {0.0, 0.0, 0.0};
     if constexpr (CACHE_E) {
         float a32[3] = {0.f, 0.f, 0.f};                            // (per lane in fp32, as above)

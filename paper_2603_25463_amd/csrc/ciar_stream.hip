@@ -625,7 +625,10 @@ void stream_kernel(const RowArgs A)
             // S is accumulated in fp64 from the first add: on a nearly one-hot row the bounds of the top
             // token react to a relative error in S about five times over, and on a two-token row Sigma is
             // a difference of two nearly equal widths; even one fp32 add of two comparable terms (6e-8)
-            // shows there (measured against the fp64 definition).
+            // shows there (measured against the fp64 definition).  Adding the tokens of a 16-byte vector pairwise in
+            // fp32 first (fp64 only across vectors: 0.9 instructions less per token) was tried and fails parity: where a
+            // cap is active Omega = alpha_u S_u - alpha_l S_l is a small difference of numbers near 1 (0.022 from
+            // 1.012 - 0.99 in the failing case), which multiplies the 1e-8 that a dominant token's vector loses by 45.
             const float nref = nw == -INFINITY ? 0.f : nw;
             double sacc[2] = {0.0, 0.0};
 #pragma unroll
