@@ -20,10 +20,10 @@
  *     never synchronises: kernels are enqueued on `hip_stream` (a hipStream_t, NULL = the
  *     default stream) and outputs are valid once the caller has synchronised that stream.
  *   - `workspace` is device scratch of at least ciar_workspace_bytes(N, params) bytes, 16-byte
- *     aligned, owned by the caller.  It carries the per-row statistics, the list of rejected rows
- *     whose residual draw a second kernel makes, the words in which the rows of a window that spans
- *     workgroups meet, and per-row results the caller did not ask for.  Its contents need no
- *     initialisation (counters in it carry a per-launch tag; other contents count as zero) and are
+ *     aligned, owned by the caller.  It carries the per-row statistics, the words in which the
+ *     rows of a window that spans workgroups meet, and per-row results the caller did not ask for
+ *     but a later kernel or a window output needs.  Its contents need no initialisation (the window
+ *     words carry a per-launch tag; everything else is written before it is read) and are
  *     garbage afterwards; calls that overlap in time on one device must not share a workspace.
  *   - Logits: row-major [N, row_stride] with V <= row_stride, element type `dtype`
  *     (float32, or bfloat16 widened exactly to float32 on load).  Base pointers and

@@ -298,7 +298,7 @@ int fill(const Call& c, ciar::Mode mode, ciar::RowArgs* a)
 }
 
 // Tensor mode reports the arg-max token's interval with that token's own radius: without drafted ids the index
-// comes from a kernel of its own, into the list of rejected rows (not in use in a quantify-only call).
+// comes from a kernel of its own, into a workspace array of N ints.
 bool needs_argmax(const ciar::RowArgs& a) { return a.radius && !a.ids && (a.p_lo || a.p_hi); }
 
 // Tags for the words the streaming kernel keeps in caller memory (see window_arrive in ciar_device.h): a different

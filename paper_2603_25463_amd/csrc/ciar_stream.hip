@@ -1,22 +1,20 @@
 // gfx950 streaming kernel of the CIAR quantify + verify pass (this file), with an overview of the pass.
 //
-// The pass is split so that the kernel that touches the V-wide rows is pure streaming arithmetic
-// (rowfinish_kernel and resample_kernel live in ciar_finish.hip):
-//
-//   stream_kernel   reads every logit row exactly once from HBM and leaves ten numbers per row
-//                   (RowStats).  A workgroup of 256 lanes (512 or 1024 for large vocabularies or few
-//                   rows) owns one row at a time and walks over rows blockIdx.x, blockIdx.x +
-//                   gridDim.x, ...  The grid is exactly the workgroups that are resident at once (four
-//                   waves per SIMD): while one workgroup waits for its row, the others compute, which
-//                   keeps the memory system busy without a second set of row registers.  Loads are
-//                   interleaved over the workgroup so that every load instruction of a wave covers
-//                   1 KiB of consecutive memory, and non-temporal (every logit is used once).
-//                   Nothing V-wide is ever written back.
-//   rowfinish_kernel  one thread per row turns RowStats into the row's outputs in fp64 (caps, Omega,
-//                   Sigma, U, flag, interval of the reported token, accept test) and appends rejected
-//                   rows to a list.
-//   resample_kernel workgroups walk over that list (~1 row in 8) and run the residual draw, re-reading
-//                   the two rows.
+//   stream_kernel   reads every logit row exactly once from HBM.  A workgroup of 256 lanes (512 or 1024 for large
+//                   vocabularies or few rows) owns one row at a time and walks over rows blockIdx.x, blockIdx.x +
+//                   gridDim.x, ...  The grid is the workgroups that are resident at once (four waves per SIMD;
+//                   more, taking their turn, when a workgroup would otherwise get more than kMaxRowsPerWg rows):
+//                   while one workgroup waits for its row, the others compute, which keeps the memory system busy
+//                   without a second set of row registers.  Loads are interleaved over the workgroup so that every
+//                   load instruction of a wave covers 1 KiB of consecutive memory, and non-temporal (every logit is
+//                   used once).  Nothing V-wide is ever written back.
+//                   What a row leaves behind (its statistics, the accept verdict, the draw of a rejected row) is
+//                   parked in LDS, and after its last row the workgroup turns that into the rows' outputs, two
+//                   lanes per row in fp64 (finish_batch): caps, Omega, Sigma, U, flag, the interval of the reported
+//                   token, the exact accept test, the window outputs.  A call whose rows fit this scheme is this
+//                   one launch.
+//   resample_kernel (ciar_finish.hip) draws for the rejected rows of launches whose tiles cannot keep both rows in
+//                   registers (bf16, the 16-vector fp32 tile, tensor and wide radii), re-reading the two rows.
 //
 // The centre row has to be resident between its statistics pass and its interval pass: the InterFuse
 // bounds need the partition sum S of the complete row before the first bound can be formed (App.
@@ -40,7 +38,7 @@
 //      registers allow, else after it): per-wave maximum, Z_w = sum 2^(t_i log2e - nt_w)   (max-trick)
 //   -- barrier: the waves exchange their interval sums and (nt_w, Z_w); thread 0 writes RowStats --
 //
-// rowfinish_kernel / resample_kernel, per row (Eq. uncertainty_score; Algorithm 1's threshold and verification steps):
+// finishing lanes / residual draw, per row (Eq. uncertainty_score; Algorithm 1's threshold and verification steps):
 //   delta_i = alpha_u w_i + (alpha_u - alpha_l) p^l_i once the 0.99 / 1.01 caps alpha_l, alpha_u are
 //   known, so Omega = sum delta_i, Sigma^2 = (sum delta_i^2) / V - (Omega / V)^2, U = Omega * Sigma
 //   follow from the five sums without a second sweep over the row; flag = U > tau;
