@@ -2,6 +2,7 @@
 // equations): per-row terms, batch softmax weights and the batch reduction.
 #include "ciar_device.h"
 
+#include <cfloat>
 #include <mutex>
 
 namespace ciar {
@@ -9,12 +10,10 @@ namespace {
 
 // ---- Inter-DRO loss, forward (Sec. 3.2.3: anchor, DRO and alignment equations) -----------------------------
 
-// e^((c + r) - (c* + r*)) for the token (c*, r*) that carries the row maximum of c + r, formed as
-// (c - c*) + (r - r*): each difference is exact for tokens near the maximum and rounded relative to itself
-// elsewhere, so c + r is never rounded to fp32.  That rounding, 6e-8 |c + r|, is a relative error of the same
-// size in the token's probability, and for logits of magnitude ~30 it shows as ~1e-6 absolute in a cross-entropy
-// (the difference of max + ln S and the p_cloud-weighted mean logit) and in an L1 distance.  The largest token
-// contributes exactly 1 to S.  sign = +1 for c + r, -1 for c - r.
+// e^((c + sign r) - (c* + sign r*)) about a reference pair (c*, r*), formed as (c - c*) + sign (r - r*): each
+// difference is exact for tokens near the reference and rounded relative to itself elsewhere, so c + r is never
+// rounded to fp32.  That rounding, 6e-8 |c + r|, would be a relative error of the same size in the token's
+// probability, and for logits of magnitude ~30 it shows as ~1e-6 absolute in a cross-entropy and in an L1 distance.
 __device__ __forceinline__ float exp_rel(float c, float r, float cs, float rs, float sign)
 {
     const float d = fmaf(sign, r - rs, c - cs);
@@ -38,11 +37,16 @@ __device__ __forceinline__ float exp_rel(float x, float m)
     return __builtin_amdgcn_exp2f(fmaf(d, kLog2eLo, d * kLog2eHi));
 }
 
+// Stand-in for a centre logit of -inf inside dro_row_compute: -2^100, a bf16 and an fp32 number whose multiples by
+// log2(e) and differences from any logit stay finite.
+constexpr float kRuledOut = -1267650600228229401496703205376.0f;
+constexpr uint32_t kRuledOutBits = 0xf1800000u;                    // (its upper half is the bf16 number)
+
 // Per-row terms of the loss.  One 1024-lane workgroup per row holds the centre, raw-radius and cloud rows as
-// loaded (12 registers per vector) and makes three passes over them: the four maxima (of c, c + r, c - r and
-// the cloud logits), the four partition sums together with sum p_cloud o for the cross-entropies, and the
-// three L1 distances, which need all four normalisers.  With e = exp(o - max o):
-//   CE(p_cloud, softmax(o)) = (max o + ln S_o) - (sum_i et_i o_i) / Z,
+// loaded (12 registers per vector) and makes three passes over them: the maxima of the centre and the cloud logits
+// and a reference radius, the four partition sums together with the p_cloud-weighted sums of the exponents for the
+// cross-entropies, and the three L1 distances, which need all four normalisers.  With e = exp(o - reference):
+//   CE(p_cloud, softmax(o)) = (reference + ln S_o) - (sum_i et_i o_i) / Z,
 //   KL(p_cloud || p_mid)    = (sum_i et_i t_i) / Z - (max t + ln Z) + CE(p_cloud, p_mid).
 // terms[k * N + row], k = 0..6: L1(mid), L1(up), L1(lo), CE(mid), CE(up), CE(lo), KL.
 // Workgroup barrier for data exchanged through LDS only: waits for this wave's LDS operations and joins the barrier.
@@ -57,8 +61,13 @@ __device__ __forceinline__ void lds_barrier()
 // vectors past the end of the row hold copies of its last vector and are masked here), left in fin[kDroTotals] (LDS)
 // by lane 0.  Called by every lane of a 1024-lane workgroup; sm_d: 7 doubles per wave of LDS scratch.  Ends with every
 // lane past the last read of sm_d except wave 0's.
+// The radius parameters as the row arithmetic takes them: floats, formed by the host, so that they arrive in scalar
+// registers with the kernel arguments.  (Converted from RowArgs' doubles inside a kernel they are loop invariants that
+// the optimiser holds in vector registers, or spills, through the whole row loop.)
+struct DroRadius { float kappa, rmax, scalar; };                   // scalar = min(kappa, rmax), the radius without a tensor
+
 template <typename T, int NVEC>
-__device__ __forceinline__ void dro_row_compute(const RowArgs& A, double* fin,
+__device__ __forceinline__ void dro_row_compute(const RowArgs& A, const DroRadius R, double* fin,
                                                 u32x4 (&cw)[NVEC], u32x4 (&tw)[NVEC], u32x4 (&rw)[NVEC], double* sm_d,
                                                 const int tid)
 {
@@ -67,8 +76,8 @@ __device__ __forceinline__ void dro_row_compute(const RowArgs& A, double* fin,
     const int lane = tid & 63, wave = tid >> 6;
     const int V = A.V;
     const bool rad = A.radius != nullptr;                          // uniform
-    const float kap = (float)A.kappa, rmax = (float)A.rmax;
-    const float r0 = (float)fmin(A.kappa, A.rmax);                 // the scalar radius
+    auto uniform = [](float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); };
+    const float kap = R.kappa, rmax = R.rmax, r0 = R.scalar;
     if (V < NVEC * THREADS * EPV) {                                // uniform: the row does not fill the tile
 #pragma unroll
         for (int j = 0; j < NVEC; ++j) {
@@ -119,32 +128,78 @@ __device__ __forceinline__ void dro_row_compute(const RowArgs& A, double* fin,
             if (!CACHE_R && rad) asm volatile("" : "+v"(rw[j]));
         }
     };
-    // pass 1: the maxima of c and of the cloud logits, the largest and the smallest radius.  The partition sums of
-    // c + r and c - r are taken about (max c, max r) and (max c, min r): every exponent (c - max c) +- (r - r*) is
-    // then <= 0, and the token that carries max c has an exponent of at least -r_max (the radii lie in [0, r_max],
-    // r_max <= 16), so the sums neither overflow nor vanish.  Any reference serves in
-    // CE = (reference + ln S) - sum p_cloud o as long as S is taken about the same one.
-    float mc = -INFINITY, mt = -INFINITY, rhi = -INFINITY, rlo = INFINITY;
+    // pass 1: the maxima of c and of the cloud logits, and a reference radius r* for the sums of c + r and c - r: the
+    // radius of a token at (or within 2^-11 of) the maximum of c.  Any reference gives the same cross-entropy
+    //   CE = ln S - (sum_i et_i d_i) / Z,   S and the d_i taken about the same one,
+    // but its two terms cancel down from the size of the dominant token's exponent, and the weighted sum is rounded
+    // per lane in fp32: with r* the radius of that very token its exponent is ~0 in all three distributions (where
+    // the cloud puts its weight elsewhere, the cross-entropy is large and the rounding small beside it).  The
+    // exponents are then (c - max c) +- (r - r*) <= r_max <= 16: nothing overflows, and the token at the maximum
+    // keeps every partition sum above ~1.
+    // r* comes out of the same maximum: the key of a token is its centre logit with the low 12 mantissa bits replaced
+    // by the radius in 1/128ths (the low bits of r + 2^16), so the largest key carries the radius of a largest logit.
+    auto key_of = [](float c, float r) {
+        return __uint_as_float((__float_as_uint(c) & 0xFFFFF000u) | (__float_as_uint(r + 65536.0f) & 0x00000FFFu));
+    };
+    // (the keys are ordered as floats, none is a NaN: plain v_max_f32, without the quieting of its operands that
+    // fmaxf adds for values the compiler knows nothing about)
+    auto key_max = [](float a, float b, float c) {
+        float m;
+        asm("v_max3_f32 %0, %1, %2, %3" : "=v"(m) : "v"(a), "v"(b), "v"(c));
+        return m;
+    };
+    float mc = -INFINITY, mt = -INFINITY, key = -FLT_MAX;
+    float c_least = INFINITY;                                      // (this lane's smallest centre logit: see pass 2)
 #pragma unroll
     for (int j = 0; j < NVEC; ++j) {
 #pragma unroll
-        for (int k = 0; k < EPV; ++k) {
-            float c, r, t;
+        for (int k = 0; k < EPV; k += 2) {
+            float c, r, t, c2, r2, t2;
             element(j, k, c, r, t);
-            mc = fmaxf(mc, c); mt = fmaxf(mt, t);
-            rhi = fmaxf(rhi, r); rlo = fminf(rlo, r);
+            element(j, k + 1, c2, r2, t2);
+            mc = fmaxf(fmaxf(mc, c), c2); mt = fmaxf(fmaxf(mt, t), t2);
+            c_least = fminf(fminf(c_least, c), c2);
+            key = key_max(key, key_of(c, r), key_of(c2, r2));
+        }
+    }
+    // Does any lane of this wave hold a centre logit of -inf (a token the device rules out, or the masked tail)?  Its
+    // key would be a NaN, and in pass 2 its exponent times a cloud weight of 0 another.  Such a wave (only such a wave)
+    // puts kRuledOut, a finite number far below any logit, in the place of -inf in the row as it holds it and forms its
+    // key again; pass 2 then sees finite numbers only.  (A logit of exactly kRuledOut counts as ruled out.)
+    const bool wave_c_finite = __builtin_amdgcn_ballot_w64(c_least == -INFINITY) == 0;
+    if (!wave_c_finite) {
+        key = -FLT_MAX;
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) {
+            uint32_t* w = reinterpret_cast<uint32_t*>(&cw[j]);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if constexpr (EPV == 4) {
+                    if (w[q] == 0xff800000u) w[q] = kRuledOutBits;
+                } else {                                           // two bf16 numbers to a word
+                    if ((w[q] & 0x0000ffffu) == 0x0000ff80u) w[q] = (w[q] & 0xffff0000u) | (kRuledOutBits >> 16);
+                    if ((w[q] & 0xffff0000u) == 0xff800000u) w[q] = (w[q] & 0x0000ffffu) | kRuledOutBits;
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < EPV; k += 2) {
+                float c, r, t, c2, r2, t2;
+                element(j, k, c, r, t);
+                element(j, k + 1, c2, r2, t2);
+                key = key_max(key, key_of(c, r), key_of(c2, r2));
+            }
         }
     }
     // LDS for the reductions over the workgroup (see pass 2 for the scheme: quad sums by DPP, then transposed through
     // LDS so that one short reduction serves all quantities at once)
     __shared__ __attribute__((aligned(16))) double sm_w[NW][8][16];   // per wave: [quantity][quad]
     __shared__ __attribute__((aligned(16))) double sm_x[8][16];       // [quantity][wave]
-    float cu, ru, cl, rl;
+    float rref;
     {
         // the four maxima over the workgroup: quads by DPP, the 16 quad maxima of each quantity through LDS into one
         // DPP row each (lanes 16 q ... 16 q + 15 take quantity q), one row reduction for all four; the same again
         // over the sixteen waves.  (Four wave-wide DPP maxima, twice, cost ~240 instructions.)
-        float m4[4] = {mc, mt, rhi, -rlo};
+        float m4[4] = {mc, mt, key, 0.f};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             m4[i] = dpp_max<0xB1, 0xf>(m4[i]);
@@ -170,34 +225,55 @@ __device__ __forceinline__ void dro_row_compute(const RowArgs& A, double* fin,
         v = row_max(fx[lane]);
         mc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 15));
         mt = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 31));
-        rhi = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 47));
-        rlo = -__int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+        rref = (float)(__builtin_amdgcn_readlane(__float_as_int(v), 47) & 0xFFF) * (1.0f / 128.0f);
         // (sm_m is written again in the next row's pass 1, with the barriers of passes 2 and 3 in between)
-        cu = mc; cl = mc; ru = rhi; rl = rlo;
     }
     // a row without a live token: any finite reference will do (every exponential is 0)
     if (mc == -INFINITY) mc = 0.f;
     if (mt == -INFINITY) mt = 0.f;
     // the references are the same in every lane: keep them in scalar registers
-    auto uniform = [](float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); };
-    mc = uniform(mc); mt = uniform(mt);
-    cu = uniform(cu); ru = uniform(ru); cl = uniform(cl); rl = uniform(rl);
+    mc = uniform(mc); mt = uniform(mt); rref = uniform(rref);
 
-    // pass 2: partition sums and the p_cloud-weighted sums of the exponents.  With d = o - reference (<= 0 for every
-    // token) and e = exp(d):   CE(p_cloud, softmax(o)) = ln S_o - (sum_i et_i d_i) / Z,   both terms non-negative, so
-    // the cross-entropies lose nothing to cancellation whatever the size of the logits; likewise the entropy of p_cloud,
-    // H = ln Z - (sum_i et_i dt_i) / Z, and KL(p_cloud || p_mid) = CE(p_cloud, p_mid) - H.
+    // pass 2: partition sums and the p_cloud-weighted sums of the exponents.  With d = o - reference and e = exp(d):
+    //   CE(p_cloud, softmax(o)) = ln S_o - (sum_i et_i d_i) / Z;
+    // for the centre and the cloud's own distribution the reference is the row maximum, d <= 0 and both terms are
+    // non-negative, so nothing is lost to cancellation whatever the size of the logits (for c + r and c - r see
+    // pass 1); likewise the entropy of p_cloud, H = ln Z - (sum_i et_i dt_i) / Z, and
+    // KL(p_cloud || p_mid) = CE(p_cloud, p_mid) - H.
     // With at most 16 tokens per lane the four exponentials of every token are kept for pass 3 (the rows themselves
-    // are not needed again), and the eight sums are first taken per lane in fp32: a lane's 16 terms round to ~1e-7 of
-    // the lane's sum, independently in 1024 lanes, which leaves a few 1e-9 of a total; across lanes and waves the sums
-    // run in fp64.
+    // are not needed again).  The partition sums run in fp64 from the first add: in a row with one dominant token the
+    // lane that holds it carries nearly all of S, so a lane sum kept in fp32 would round S itself to 6e-8, and ln S
+    // with it -- as much as a whole cross-entropy of such a row may be off.  The four weighted sums of exponents are
+    // taken per lane in fp32 (the dominant token has exponent 0 and adds nothing to them; what a lane's rounding
+    // leaves is ~1e-7 of that lane's share of a cross-entropy), and in fp64 across lanes and waves.
     constexpr bool CACHE_E = NVEC * EPV <= 16;
     constexpr int NE = CACHE_E ? NVEC * EPV : 1;
     float em[NE], eu[NE], el[NE], ec[NE];
     fresh();
     double acc[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};     // S_mid, S_up, S_lo, Z, sum et d_mid, d_up, d_lo, d_t
     float s32[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    auto exp_of = [](float d) { return __builtin_amdgcn_exp2f(fmaf(d, kLog2eLo, d * kLog2eHi)); };
+    // (x log2(e) from the two-piece constant: a single fp32 constant is off by 2e-8 of itself, the same way for every
+    // token, which would tilt a distribution over logits ~10 apart by 2e-7)
+    auto log2e_times = [](float d) { return fmaf(d, kLog2eLo, d * kLog2eHi); };
+    // A token the cloud rules out (et = 0) weighs nothing in the weighted sums, whatever its logits are; but 0 x -inf
+    // would be NaN.  So the products are formed from finite numbers: kRuledOut stands for a centre logit of -inf (see
+    // pass 1) and dt has a floor of -1e30; neither changes an exponential (2^-1e30 = 0 = 2^-inf).  What that would
+    // lose -- a token that the device rules out and the cloud does not makes the cross-entropies and KL infinite --
+    // is looked for beforehand, by the waves that hold such a logit.
+    bool ce_infinite = false;
+    if (!wave_c_finite) {
+#pragma unroll
+        for (int j = 0; j < NVEC; ++j) {
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) {
+                float c, r, t;
+                element(j, k, c, r, t);
+                ce_infinite |= c == kRuledOut && __builtin_amdgcn_exp2f(log2e_times(t - mt)) > 0.f;
+            }
+        }
+    }
+    // The exponents are taken to base 2 once, x = d log2(e), and the weighted sums run over x (dro_finish_row
+    // multiplies them by ln 2); x_up and x_lo are x_mid +- (r - r*) log2(e).
 #pragma unroll
     for (int j = 0; j < NVEC; ++j) {
 #pragma unroll
@@ -206,27 +282,36 @@ __device__ __forceinline__ void dro_row_compute(const RowArgs& A, double* fin,
             element(j, k, c, r, t);
             // (each difference is exact for tokens near the reference and rounded relative to itself elsewhere:
             // c + r is never rounded to fp32)
-            const float d0 = c - mc, d1 = d0 + (r - ru), d2 = d0 - (r - rl), dt = t - mt;
-            const float e0 = exp_of(d0), e1 = exp_of(d1), e2 = exp_of(d2), et = exp_of(dt);
-            // a token the cloud rules out weighs nothing, whatever its logits are (0 x inf would be NaN)
-            const bool live = et > 0.f;
-            const float w0 = live ? d0 : 0.f, w1 = live ? d1 : 0.f, w2 = live ? d2 : 0.f, wt = live ? dt : 0.f;
+            const float x0 = log2e_times(c - mc), xa = log2e_times(r - rref), x1 = x0 + xa, x2 = x0 - xa;
+            const float xt = log2e_times(fmaxf(t - mt, -1e30f));
+            const float e0 = __builtin_amdgcn_exp2f(x0), e1 = __builtin_amdgcn_exp2f(x1);
+            const float e2 = __builtin_amdgcn_exp2f(x2), et = __builtin_amdgcn_exp2f(xt);
             if constexpr (CACHE_E) {
                 em[j * EPV + k] = e0; eu[j * EPV + k] = e1; el[j * EPV + k] = e2; ec[j * EPV + k] = et;
-                s32[0] += e0; s32[1] += e1; s32[2] += e2; s32[3] += et;
-                s32[4] = fmaf(et, w0, s32[4]); s32[5] = fmaf(et, w1, s32[5]);
-                s32[6] = fmaf(et, w2, s32[6]); s32[7] = fmaf(et, wt, s32[7]);
+                acc[0] += (double)e0; acc[1] += (double)e1; acc[2] += (double)e2; acc[3] += (double)et;
+                s32[4] = fmaf(et, x0, s32[4]); s32[5] = fmaf(et, x1, s32[5]);
+                s32[6] = fmaf(et, x2, s32[6]); s32[7] = fmaf(et, xt, s32[7]);
             } else {
                 acc[0] += (double)e0; acc[1] += (double)e1; acc[2] += (double)e2; acc[3] += (double)et;
-                acc[4] = fma((double)et, (double)w0, acc[4]); acc[5] = fma((double)et, (double)w1, acc[5]);
-                acc[6] = fma((double)et, (double)w2, acc[6]); acc[7] = fma((double)et, (double)wt, acc[7]);
+                acc[4] = fma((double)et, (double)x0, acc[4]); acc[5] = fma((double)et, (double)x1, acc[5]);
+                acc[6] = fma((double)et, (double)x2, acc[6]); acc[7] = fma((double)et, (double)xt, acc[7]);
             }
             if (k & 1) __builtin_amdgcn_sched_barrier(0);          // two tokens at a time: bounded working set
         }
     }
-    if constexpr (CACHE_E) {
+    if (ce_infinite) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = (double)s32[i];
+        for (int i = 4; i < 7; ++i) { s32[i] = -INFINITY; acc[i] = -INFINITY; }
+    }
+    if constexpr (CACHE_E) {
+        // (the weighted sums of a quad in fp32 as well: one instruction per DPP step of a float, five of a double)
+#pragma unroll
+        for (int i = 4; i < 8; ++i) {
+            float v = s32[i];
+            v += __int_as_float(dpp_or<0xB1, 0xf>(0, __float_as_int(v)));
+            v += __int_as_float(dpp_or<0x4E, 0xf>(0, __float_as_int(v)));
+            acc[i] = (double)v;
+        }
     }
     // The eight sums over the workgroup.  A DPP reduction of one double over a wave is ~36 instructions, and with 16
     // tokens per lane eight of them (and eight more across the waves) weighed more than the tokens' own arithmetic.
@@ -242,7 +327,7 @@ __device__ __forceinline__ void dro_row_compute(const RowArgs& A, double* fin,
         return a;
     };
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < (CACHE_E ? 4 : 8); ++i) {
         acc[i] = dpp_add<0xB1, 0xf>(acc[i]);
         acc[i] = dpp_add<0x4E, 0xf>(acc[i]);
     }
@@ -268,22 +353,27 @@ __device__ __forceinline__ void dro_row_compute(const RowArgs& A, double* fin,
     }
     // (sm_x is written again only after the next barriers: pass 3's exchange uses sm_d)
 
-    // pass 3: L1 distances to p_cloud
-    // (hardware reciprocal plus one Newton step: as good as the rounding of the sum to fp32, without an fp64 division)
-    auto recip = [](double S) {
-        const float s = (float)S, r = __builtin_amdgcn_rcpf(s);
-        return fmaf(r, fmaf(-s, r, 1.0f), r);
-    };
-    const float is0 = recip(tot[0]), is1 = recip(tot[1]), is2 = recip(tot[2]), iz = recip(tot[3]);
+    // pass 3: L1 distances to p_cloud.  With rho = S / Z,  |e / S - et / Z| = |e - rho et| / S:  the difference is one
+    // fused multiply-add on the exponentials as they are, rounded once at its own (small) size, so tokens that carry
+    // most of both distributions cancel to the last bit and what remains is rho's rounding to fp32, at most 6e-8 of
+    // a distance of at most 2.  (A product e * (1/S) rounded on its own would leave that much per factor and per term.)
+    // The division by S is left to dro_finish_row.
+    float rho[3];
+    {
+        // 1 / Z: hardware reciprocal and one Newton step in fp64 (~1e-14), no fp64 division
+        const double z = tot[3], r0 = (double)__builtin_amdgcn_rcpf((float)z);
+        const double rz = fma(r0, fma(-z, r0, 1.0), r0);
+#pragma unroll
+        for (int i = 0; i < 3; ++i) rho[i] = (float)(tot[i] * rz);
+    }
     double l1[3] = {0.0, 0.0, 0.0};
     if constexpr (CACHE_E) {
-        float a32[3] = {0.f, 0.f, 0.f};                            // (per lane in fp32, as above)
+        float a32[3] = {0.f, 0.f, 0.f};                            // (per lane in fp32: sums of non-negative terms)
 #pragma unroll
         for (int i = 0; i < NE; ++i) {
-            const float pc = ec[i] * iz;
-            a32[0] += fabsf(em[i] * is0 - pc);
-            a32[1] += fabsf(eu[i] * is1 - pc);
-            a32[2] += fabsf(el[i] * is2 - pc);
+            a32[0] += fabsf(fmaf(-ec[i], rho[0], em[i]));
+            a32[1] += fabsf(fmaf(-ec[i], rho[1], eu[i]));
+            a32[2] += fabsf(fmaf(-ec[i], rho[2], el[i]));
         }
 #pragma unroll
         for (int i = 0; i < 3; ++i) l1[i] = (double)a32[i];
@@ -295,10 +385,10 @@ __device__ __forceinline__ void dro_row_compute(const RowArgs& A, double* fin,
             for (int k = 0; k < EPV; ++k) {
                 float c, r, t;
                 element(j, k, c, r, t);
-                const float pc = exp_rel(t, mt) * iz;
-                l1[0] += (double)fabsf(exp_rel(c, mc) * is0 - pc);
-                l1[1] += (double)fabsf(exp_rel(c, r, cu, ru, 1.f) * is1 - pc);
-                l1[2] += (double)fabsf(exp_rel(c, r, cl, rl, -1.f) * is2 - pc);
+                const float et = exp_rel(t, mt);
+                l1[0] += (double)fabsf(fmaf(-et, rho[0], exp_rel(c, mc)));
+                l1[1] += (double)fabsf(fmaf(-et, rho[1], exp_rel(c, r, mc, rref, 1.f)));
+                l1[2] += (double)fabsf(fmaf(-et, rho[2], exp_rel(c, r, mc, rref, -1.f)));
                 if (k & 1) __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -326,7 +416,7 @@ __device__ __forceinline__ void dro_row_compute(const RowArgs& A, double* fin,
 #pragma unroll
         for (int i = 0; i < 3; ++i) L[i] = (double)row16_sum_f(lane < NW ? slot[i * NW + lane] : 0.f);
         // the row's totals, for dro_finish_row: S_mid, S_up, S_lo, Z, the four p_cloud-weighted sums of exponents (times Z),
-        // the three L1 distances
+        // the three L1 distances (times S_mid, S_up, S_lo)
         if (lane == 0) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) fin[i] = tot[i];
@@ -342,19 +432,20 @@ constexpr int kDroTotals = 11;
 __device__ __forceinline__ void dro_finish_row(const RowArgs& A, float* __restrict__ terms, const int64_t row,
                                                const double* fin)
 {
-    const double Z = fin[3];
-    const double ce_mid = log(fin[0]) - fin[4] / Z;
-    const double ce_up = log(fin[1]) - fin[5] / Z;
-    const double ce_lo = log(fin[2]) - fin[6] / Z;
-    const double kl = ce_mid - (log(Z) - fin[7] / Z);              // cross-entropy minus the entropy of p_cloud
+    const double Z = fin[3], ln2_Z = kLn2 / Z;                     // (the weighted sums are over base-2 exponents)
+    const double ce_mid = log(fin[0]) - fin[4] * ln2_Z;
+    const double ce_up = log(fin[1]) - fin[5] * ln2_Z;
+    const double ce_lo = log(fin[2]) - fin[6] * ln2_Z;
+    const double kl = ce_mid - (log(Z) - fin[7] * ln2_Z);          // cross-entropy minus the entropy of p_cloud
     const int64_t N = A.N;
-    terms[0 * N + row] = (float)fin[8]; terms[1 * N + row] = (float)fin[9]; terms[2 * N + row] = (float)fin[10];
+    terms[0 * N + row] = (float)(fin[8] / fin[0]); terms[1 * N + row] = (float)(fin[9] / fin[1]);
+    terms[2 * N + row] = (float)(fin[10] / fin[2]);
     terms[3 * N + row] = (float)ce_mid; terms[4 * N + row] = (float)ce_up; terms[5 * N + row] = (float)ce_lo;
     terms[6 * N + row] = (float)kl;
 }
 
 template <typename T, int NVEC>
-__global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* __restrict__ terms)
+__global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, const DroRadius R, float* __restrict__ terms)
 {
     constexpr int THREADS = 1024, NW = 16;
     __shared__ double sm_d[NW * 7];
@@ -374,7 +465,7 @@ __global__ __launch_bounds__(1024) void dro_row_kernel(const RowArgs A, float* _
         if (rad) rw[j] = __builtin_nontemporal_load((gvec)(rb + off));
     }
     __shared__ double sm_fin[kDroTotals];
-    dro_row_compute<T, NVEC>(A, sm_fin, cw, tw, rw, sm_d, tid);
+    dro_row_compute<T, NVEC>(A, R, sm_fin, cw, tw, rw, sm_d, tid);
     if (tid == 0) dro_finish_row(A, terms, row, sm_fin);           // (the lane that has written the totals)
 }
 
@@ -389,7 +480,8 @@ constexpr int kDroRowsPerWg = 64;                                  // most rows 
 // wave's loads have written, so the hand-over needs the wave's own vmcnt(0) and no barrier.
 // Dynamic LDS: 2 x NVEC x 16 KiB (NVEC <= 4).
 template <typename T, int NVEC>
-__global__ __launch_bounds__(1024) void dro_row_stream_kernel(const RowArgs A, float* __restrict__ terms)
+__global__ __launch_bounds__(1024) void dro_row_stream_kernel(const RowArgs A, const DroRadius R,
+                                                              float* __restrict__ terms)
 {
     constexpr int THREADS = 1024, NW = 16;
     extern __shared__ u32x4 sm_rows[];                             // [2][NVEC][THREADS]: next centre row, next cloud row
@@ -424,13 +516,16 @@ __global__ __launch_bounds__(1024) void dro_row_stream_kernel(const RowArgs A, f
     u32x4 rnext[NVEC];
 #pragma unroll
     for (int j = 0; j < NVEC; ++j) rnext[j] = u32x4{0u, 0u, 0u, 0u};
-    int64_t row = blockIdx.x;
+    // (rows are counted in 32 bits -- the entry point takes no more than 2^31 - 1, and row + gridDim.x stays below 2^32:
+    // a 64-bit comparison of two scalars is a vector instruction that wants one of them in vector registers, for good)
+    const uint32_t n_rows = (uint32_t)A.N;
+    uint32_t row = blockIdx.x;
     int done = 0;                                                  // rows of this workgroup finished so far (<= kDroRowsPerWg)
-    if (row < A.N) {
+    if (row < n_rows) {
         request_rows(row, tid);
         if (rad) request_radius(row, rnext, tid);
     }
-    for (; row < A.N; row += gridDim.x) {
+    for (; row < n_rows; row += gridDim.x) {
         // this wave's loads have landed (its slots of the two rows in LDS, and the radius registers)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         // (the lane's index is made opaque once per row: the LDS addresses derived from it are cheap to form again, and
@@ -446,12 +541,12 @@ __global__ __launch_bounds__(1024) void dro_row_stream_kernel(const RowArgs A, f
         }
         // the slots are free again once they have been read: the next position's rows go in flight now
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        const int64_t next = row + gridDim.x;
-        if (next < A.N) {
+        const uint32_t next = row + gridDim.x;
+        if (next < n_rows) {
             request_rows(next, t);
             if (rad) request_radius(next, rnext, t);
         }
-        dro_row_compute<T, NVEC>(A, sm_fin[done], cw, tw, rw, sm_d, t);
+        dro_row_compute<T, NVEC>(A, R, sm_fin[done], cw, tw, rw, sm_d, t);
         // (no barrier here: what wave 0 still reads of sm_d is written again only in the next row's pass 3, two
         // barriers on)
         ++done;
@@ -590,7 +685,8 @@ hipError_t launch_dro_stream_cfg(const RowArgs& a, float* terms, hipStream_t str
     if (g < need) g = need;
     if (g > a.N) g = a.N;
     const dim3 grid((unsigned)g), block(1024);
-    hipLaunchKernelGGL((dro_row_stream_kernel<T, NVEC>), grid, block, lds, stream, a, terms);
+    const DroRadius R = {(float)a.kappa, (float)a.rmax, (float)fmin(a.kappa, a.rmax)};
+    hipLaunchKernelGGL((dro_row_stream_kernel<T, NVEC>), grid, block, lds, stream, a, R, terms);
     return hipGetLastError();
 }
 template <typename T>
@@ -609,10 +705,11 @@ hipError_t launch_dro(int dtype, const RowArgs& args, float* terms, double lambd
     const int epv = dtype == 0 ? 4 : 8;
     const int vecs = (args.V + epv - 1) / epv;
     const dim3 grid((unsigned)args.N), block(1024);
+    const DroRadius R = {(float)args.kappa, (float)args.rmax, (float)fmin(args.kappa, args.rmax)};
 #define CIAR_DRO_LAUNCH(NV)                                                                             \
     do {                                                                                                \
-        if (dtype == 0) hipLaunchKernelGGL((dro_row_kernel<float, NV>), grid, block, 0, stream, args, terms);   \
-        else hipLaunchKernelGGL((dro_row_kernel<bf16_t, NV>), grid, block, 0, stream, args, terms);              \
+        if (dtype == 0) hipLaunchKernelGGL((dro_row_kernel<float, NV>), grid, block, 0, stream, args, R, terms);   \
+        else hipLaunchKernelGGL((dro_row_kernel<bf16_t, NV>), grid, block, 0, stream, args, R, terms);           \
     } while (0)
     if (args.V <= kTinyVocab) {
         const dim3 tgrid((unsigned)((args.N + 255) / 256)), tblock(256);

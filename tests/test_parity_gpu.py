@@ -559,6 +559,72 @@ def test_interdro_loss(ciar, oracle, V, stride, N, dtype, tensor_radius):
     _check_dro(g, o, N)
 
 
+# More rows than the chip has compute units: the loss then runs in its persistent row kernel (rows strided over the
+# workgroups, the next row fetched while one is summed).  N = 16700 is above 64 rows per workgroup on 256 units, where
+# the grid grows instead; 257 leaves all but one workgroup a single row; the vocabularies cover each vector count, a
+# ragged tail and padded strides.
+DRO_MANY_ROWS = [
+    (70, 72, 16700, torch.float32), (1000, 1000, 257, torch.float32), (4100, 4104, 300, torch.float32),
+    (8192, 8192, 513, torch.float32), (16381, 16384, 290, torch.float32), (520, 520, 3000, torch.bfloat16),
+    (8200, 8200, 300, torch.bfloat16), (16384, 16384, 261, torch.bfloat16), (32768, 32768, 259, torch.bfloat16),
+]
+
+
+@pytest.mark.parametrize("V,stride,N,dtype", DRO_MANY_ROWS)
+@pytest.mark.parametrize("tensor_radius", [True, False])
+def test_interdro_loss_many_rows(ciar, oracle, V, stride, N, dtype, tensor_radius):
+    c, t, *_ = _random_case(V, stride, N, 4, dtype, seed=6500 + V)
+    if stride > V:
+        t[:, V:] = 1e30
+    raw = _raw_radius(N, stride, V, dtype, seed=6600 + V) if tensor_radius else None
+    gen = torch.Generator(device="cpu").manual_seed(6700 + V)
+    rows = torch.randint(0, N, (7,), generator=gen)
+    cols = torch.randint(0, V, (7,), generator=gen)
+    t[rows.cuda(), cols.cuda()] = float("-inf")                      # tokens the cloud rules out, in scattered rows
+    t[N - 1, V - 1] = float("-inf")
+    say(f"[interdro many rows] V={V} stride={stride} N={N} {dtype} radius={'tensor' if tensor_radius else 'scalar'}")
+    lam = (0.9, 0.6, 1.1, 1.5)
+    P = ciar.Params(radius_scale=1.0 if tensor_radius else 0.6)
+    g = ciar.interdro_loss(c, raw, t, P, *lam, vocab=V)
+    torch.cuda.synchronize()
+    o = oracle.interdro_loss(c.cpu(), None if raw is None else raw.cpu(), t.cpu(),
+                             _OP(oracle, kappa=P.radius_scale), *lam, vocab=V)
+    _check_dro(g, o, N)
+
+
+@pytest.mark.parametrize("V,N,dtype", [(1000, 40, torch.float32), (4100, 300, torch.float32), (16384, 270, torch.float32),
+                                       (16384, 300, torch.bfloat16), (40000, 7, torch.bfloat16)])
+def test_interdro_tokens_the_device_rules_out(ciar, oracle, V, N, dtype):
+    """Centre logits of -inf.  Where the cloud rules the same tokens out the terms stay finite and match; a row in which
+    the cloud keeps such a token has infinite cross-entropies and KL (its L1 distances stay finite)."""
+    c, t, *_ = _random_case(V, V, N, 4, dtype, seed=6900 + V)
+    raw = _raw_radius(N, V, V, dtype, seed=6950 + V)
+    gen = torch.Generator(device="cpu").manual_seed(6990 + V)
+    dead = torch.randint(0, V, (N, 9), generator=gen).cuda()
+    rows = torch.arange(N, device="cuda")[:, None]
+    c[rows, dead] = float("-inf")
+    t[rows, dead] = float("-inf")
+    c[:, V - 3:] = float("-inf")                                     # a masked tail, as a padded vocabulary has
+    t[:, V - 3:] = float("-inf")
+    infinite = torch.arange(N) % 5 == 2
+    t[infinite.cuda(), dead[infinite.cuda(), 0]] = 0.5               # the cloud keeps one of them
+    say(f"[interdro ruled out] V={V} N={N} {dtype}")
+    lam = (1.0, 1.0, 1.0, 1.0)
+    P = ciar.Params(radius_scale=1.0)
+    g = ciar.interdro_loss(c, raw, t, P, *lam, vocab=V)
+    torch.cuda.synchronize()
+    o = oracle.interdro_loss(c.cpu(), raw.cpu(), t.cpu(), _OP(oracle, kappa=1.0), *lam, vocab=V)
+    terms = g["terms"].cpu().numpy().astype(np.float64)
+    inf = infinite.numpy()
+    for i, k in enumerate(("l1_mid", "l1_up", "l1_lo", "ce_mid", "ce_up", "ce_lo", "kl")):
+        ok = np.ones(N, bool) if i < 3 else ~inf
+        assert np.all(np.isfinite(o[k][ok])) and np.all(np.isfinite(terms[i][ok])), k
+        err = np.abs(terms[i][ok] - o[k][ok])
+        assert np.all(err <= parity.ATOL + parity.RTOL * np.abs(o[k][ok])), (k, float(err.max()))
+        if i >= 3:
+            assert np.all(np.isposinf(o[k][inf])) and np.all(np.isposinf(terms[i][inf])), k
+
+
 def test_interdro_loss_on_a_workload(ciar, oracle):
     """The benchmark workload's rows as (centre, cloud) pairs with the synthetic radius head, every row."""
     from paper_2603_25463_amd import workloads as wl
