@@ -574,14 +574,13 @@ __device__ __forceinline__ bool window_arrive(unsigned long long* p, uint32_t ta
 
 // Makes a window's word a fresh one of this launch ahead of its rows' arrivals (an optimisation only: window_arrive
 // copes with whatever it finds).
-__device__ __forceinline__ void window_claim(unsigned long long* p, uint32_t tag)
+// `seen` = what the caller has read in the word (an atomic load issued early, so that its trip to memory is over).
+// One exchange whose outcome is not awaited: if it fails, another workgroup has claimed the word or arrived in it in
+// the meantime, and the word is what it should be.
+__device__ __forceinline__ void window_claim(unsigned long long* p, uint32_t tag, unsigned long long seen)
 {
     const unsigned long long t31 = (unsigned long long)(tag & 0x7fffffffu), fresh = (t31 << 33) | (0xffull << 17);
-    unsigned long long seen = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    while ((seen >> 33) != t31) {
-        const unsigned long long prev = atomicCAS(p, seen, fresh);
-        seen = prev == seen ? fresh : prev;
-    }
+    if ((seen >> 33) != t31) (void)atomicCAS(p, seen, fresh);
 }
 
 // Vocabularies of at most this many tokens take fp64 token arithmetic (see fuse_sums_tiny, dro_row_tiny_kernel).

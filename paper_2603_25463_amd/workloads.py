@@ -26,7 +26,7 @@ The five workloads are the ones the benchmark definition names (rows = images x 
 """
 from __future__ import annotations
 
-from dataclasses import dataclass, field
+from dataclasses import dataclass, field, replace
 
 import numpy as np
 import torch
@@ -137,10 +137,15 @@ def _uniform24(n: int, gen: torch.Generator, device) -> torch.Tensor:
     return bits.to(torch.float32) * (1.0 / (1 << 24))
 
 
-def make(cfg: int, device="cpu", rows: int | None = None, seed: int | None = None) -> Workload:
+def make(cfg: int, device="cpu", rows: int | None = None, seed: int | None = None,
+         images: int | None = None) -> Workload:
     """Generate workload ``cfg`` (1..5).  ``rows`` truncates to the first rows (whole chunks of
-    noise are still drawn per 256-row block, so a truncated workload is a prefix of the full one)."""
+    noise are still drawn per 256-row block, so a truncated workload is a prefix of the full one).
+    ``images`` replaces the number of images of the recipe (a larger or smaller batch of the same kind of rows:
+    another seeded batch, not an extension of the named one)."""
     spec = SPECS[cfg]
+    if images is not None and int(images) != spec.images:
+        spec = replace(spec, images=int(images), name=f"{spec.name}x{int(images)}img")
     seed = base_seed(cfg) if seed is None else seed
     device = torch.device(device)
     N_full, V = spec.rows, spec.vocab
