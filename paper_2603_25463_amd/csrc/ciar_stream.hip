@@ -835,8 +835,12 @@ void stream_kernel(const RowArgs A)
                     ku = 1.0;
                     const double cl = -kq[0], cw = -kq[1], cc = -kq[2];
                     int cnt = 0;                                   // tokens of the row in this wave
+                    // (from an opaque copy of the wave's index: the count does not change from row to row, and hoisted
+                    // out of the row loop it is kept in registers, or spilled, for all of it)
+                    int wv = wave;
+                    asm volatile("" : "+v"(wv));
 #pragma unroll
-                    for (int j = 0; j < NVEC; ++j) cnt += min(max(V - (j * THREADS + wave * 64) * EPV, 0), 64 * EPV);
+                    for (int j = 0; j < NVEC; ++j) cnt += min(max(V - (j * THREADS + wv * 64) * EPV, 0), 64 * EPV);
                     const double nn = (double)cnt;
                     q5[4] += cl * q5[1] + cw * (q5[0] + nn * cl);
                     q5[2] += cl * (2.0 * q5[0] + nn * cl);
