@@ -357,6 +357,7 @@ void stream_kernel(const RowArgs A)
     __shared__ int      sm_draw[DO_V ? kMaxRowsPerWg : 1];   // -1: the drafted token was accepted; else the row's draw
     __shared__ uint8_t  sm_close[DO_V ? kMaxRowsPerWg : 1];  // the fp32 accept test could not decide the row
     __shared__ double   sm_tab[DO_V ? NT : 1];      // residual mass of each piece of a rejected row
+    __shared__ __attribute__((aligned(16))) double sm_quad[KEEP_E && NVEC == 8 ? NW : 1][8][16];   // a draw's quad sums
     __shared__ float    sm_auxf[DO_V ? NW : 1];
     __shared__ int      sm_auxi[DO_V ? NW : 1];
 
@@ -947,12 +948,15 @@ void stream_kernel(const RowArgs A)
                 combine_Z(std::integral_constant<bool, LANES>{}, nt, Z);
                 const float nw = sm_ref[dwave * 2 + 1], ntw = sm_nt[dwave];
                 const double fw = nw == -INFINITY ? 0.0 : pow2_of(nw - n);
-                const double pfac = fw / S;
+                // q - p in fp32, as resample_kernel forms it: the product e / S is rounded once (6e-8 of p, below the ~1e-7
+                // of p and of q that the fp32 exponentials carry anyway) and the FMA takes the difference from the exact
+                // product of the verifier's exponential and 1 / Z
+                const float pfac = (float)(fw / S);
                 float ntref = ntw == -INFINITY ? 0.f : ntw;
                 // (opaque to the optimiser, like e below: it would otherwise keep the streaming passes' conversions
                 // and exponentials of every token alive for this branch, in registers the hot path does not have)
                 asm volatile("" : "+v"(ntref));
-                const double qfac = (ntw == -INFINITY ? 0.0 : pow2_of(ntw - nt)) / Z;
+                const float qfac = (float)((ntw == -INFINITY ? 0.0 : pow2_of(ntw - nt)) / Z);
                 auto residuals = [&](int j, float (&r)[EPV]) {
                     float tv[EPV];
                     E::unpack(buf[j], tv);
@@ -960,22 +964,41 @@ void stream_kernel(const RowArgs A)
                     for (int k = 0; k < EPV; ++k) {
                         float ek = e[j * EPV + k];
                         asm volatile("" : "+v"(ek));
-                        const double p = __dmul_rn((double)ek, pfac);
-                        r[k] = (float)fmax(fma((double)exp2_ref(tv[k], ntref), qfac, -p), 0.0);
+                        r[k] = fmaxf(fmaf(exp2_ref(tv[k], ntref), qfac, -(ek * pfac)), 0.f);
                     }
                 };
+                // Piece totals.  Eight vectors per lane: the eight lane sums are reduced over the wave together -- two DPP
+                // steps leave every quad's sum in its lanes, the quad leaders put it into LDS vector by vector, then lane l
+                // takes two of the 16 quad sums of vector l / 8 and three butterfly steps over its eight lanes finish all
+                // eight totals (a DPP reduction of one double over a wave is ~36 instructions: eight of them were a third
+                // of a draw).  Fewer vectors: one reduction each.
 #pragma unroll
                 for (int j = 0; j < NVEC; ++j) {
-                    double ws = 0.0;
+                    float sj = 0.f;
                     if (j * CHUNK < V) {                           // uniform: the vector holds tokens
                         float r[EPV];
                         residuals(j, r);
-                        float s = 0.f;
 #pragma unroll
-                        for (int k = 0; k < EPV; ++k) s += r[k];
-                        ws = wave_sum((double)s);
+                        for (int k = 0; k < EPV; ++k) sj += r[k];
                     }
-                    if (dlane == 0) sm_tab[j * NW + dwave] = ws;
+                    if constexpr (NVEC == 8) {
+                        double q = (double)sj;
+                        q = dpp_add<0xB1, 0xf>(q);                 // lane ^ 1  (quad_perm 1,0,3,2)
+                        q = dpp_add<0x4E, 0xf>(q);                 // lane ^ 2  (quad_perm 2,3,0,1)
+                        if ((dlane & 3) == 0) sm_quad[dwave][j][dlane >> 2] = q;
+                    } else {
+                        const double ws = wave_sum((double)sj);
+                        if (dlane == 0) sm_tab[j * NW + dwave] = ws;
+                    }
+                }
+                if constexpr (NVEC == 8) {
+                    // (the wave reads what its own lanes have written: LDS operations of a wave complete in order)
+                    const double* pr = &sm_quad[dwave][dlane >> 3][2 * (dlane & 7)];
+                    double t2 = pr[0] + pr[1];
+                    t2 = dpp_add<0xB1, 0xf>(t2);
+                    t2 = dpp_add<0x4E, 0xf>(t2);
+                    t2 = dpp_add<0x141, 0xf>(t2);                  // the other quad of the eight (row_half_mirror)
+                    if ((dlane & 7) == 0) sm_tab[(dlane >> 3) * NW + dwave] = t2;
                 }
                 __syncthreads();
                 // every wave locates the piece that holds u R: lane l takes piece l (and l + 64), an inclusive scan
