@@ -164,6 +164,31 @@ __device__ __forceinline__ double wave_sum(double v)
     return __hiloint2double(hi, lo);
 }
 
+// Three sums over the wave at once, handed to every lane, in two steps so that the values need not be there at the same
+// time.  wave_sum3_put: two DPP steps leave every quad's sum in its lanes and the quad leaders put it into row `which`
+// of the wave's 48 slots of LDS.  wave_sum3_get: lane l < 48 takes slot l and one reduction over each row of 16 lanes
+// finishes all three (a wave's LDS operations complete in order: no barrier).  ~45 instructions where three
+// reductions of one double each are ~110, and nothing is held in registers between the two steps.
+__device__ __forceinline__ void wave_sum3_put(double v, double* slots, int which, int lane)
+{
+    v = dpp_add<0xB1, 0xf>(v);                     // lane ^ 1  (quad_perm 1,0,3,2)
+    v = dpp_add<0x4E, 0xf>(v);                     // lane ^ 2  (quad_perm 2,3,0,1)
+    if ((lane & 3) == 0) slots[16 * which + (lane >> 2)] = v;
+}
+__device__ __forceinline__ void wave_sum3_get(const double* slots, int lane, double& a, double& b, double& c)
+{
+    double x = slots[lane < 48 ? lane : 0];
+    x = lane < 48 ? x : 0.0;
+    x = dpp_add<kRowShr1, 0xf>(x);
+    x = dpp_add<kRowShr2, 0xf>(x);
+    x = dpp_add<kRowShr4, 0xf>(x);
+    x = dpp_add<kRowShr8, 0xf>(x);
+    const int lo = __double2loint(x), hi = __double2hiint(x);
+    a = __hiloint2double(__builtin_amdgcn_readlane(hi, 15), __builtin_amdgcn_readlane(lo, 15));
+    b = __hiloint2double(__builtin_amdgcn_readlane(hi, 31), __builtin_amdgcn_readlane(lo, 31));
+    c = __hiloint2double(__builtin_amdgcn_readlane(hi, 47), __builtin_amdgcn_readlane(lo, 47));
+}
+
 // sum over lanes 0..15 (the first DPP row), handed to every lane of the wave
 __device__ __forceinline__ double row16_sum(double v)
 {

@@ -333,6 +333,11 @@ void stream_kernel(const RowArgs A)
     // alone, never taken, cost the bf16 row loop 11 % -- registers and scheduling -- and workload 3 ran 318 against
     // 285 us per step).
     constexpr bool KEEP_E = draws_in_stream<T, NVEC, DO_V, RAD, WIDE>();
+    // Fused launches on bf16 rows with a scalar radius: the two interval sums of a row whose caps are inactive and the
+    // verifier row's partition sum are reduced over the wave together (wave_sum3) once the verifier row has been summed.
+    // (These instances are bound by their vector instructions: workload 5 1951 -> 1905 us.  The fp32 instances, which
+    // wait for memory, measured 1 % slower with it and keep one reduction per sum.)
+    constexpr bool BATCH3 = DO_Q && DO_V && !RAD && !WIDE && sizeof(T) == 2;
     constexpr int NQ = WIDE ? 8 : 5;                // interval sums a wave hands over
     constexpr int NT = NVEC * NW;                   // pieces of a row in token order: (vector j, wave w) -> j NW + w
 
@@ -346,6 +351,7 @@ void stream_kernel(const RowArgs A)
     __shared__ float  sm_nt[NW];                    // per wave: nt_w
     __shared__ double sm_Z[NW];                     // per wave: Z_w
     __shared__ double sm_q5[NW * NQ];               // per wave: the interval sums, already in row units
+    __shared__ double sm_red[BATCH3 ? NW : 1][48];  // per wave: the slots of wave_sum3
     __shared__ double sm_k[3];                      // the shift the sums are taken about (row units), from wave 0
     __shared__ float  sm_e0;                        // e of the row's first token, in the units of wave 0
     // Finishing inside this kernel: the statistics of the rows this workgroup has streamed since its last
@@ -361,7 +367,11 @@ void stream_kernel(const RowArgs A)
     __shared__ float    sm_auxf[DO_V ? NW : 1];
     __shared__ int      sm_auxi[DO_V ? NW : 1];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // (uniform over the wave; bf16 instances keep it in a scalar register, so that nothing indexed by it -- the waves'
+    // exchange slots in LDS -- is held in vector registers across the row loop: they have none to spare.  The fp32
+    // instances measured 1 % slower that way.)
+    const int wave = sizeof(T) == 2 ? __builtin_amdgcn_readfirstlane(tid >> 6) : tid >> 6;
     const int V = A.V;
     RadiusMode rm = {false, 0.f, 0.f, 0.f};
     if constexpr (RAD) rm = radius_mode(A);
@@ -408,25 +418,27 @@ void stream_kernel(const RowArgs A)
     // logits follow the device model's), which saves the pass for the maximum; a sum outside [2^-40, 2^100]
     // (a verifier row far from its centre row, or a wave without tokens: sum 0) is redone about the wave's own
     // maximum.
-    auto verifier_stats = [&](u32x4 (&tb)[NVEC], float guess, float& ntw, double& Zw) {
+    auto verifier_mask = [&](u32x4 (&tb)[NVEC]) {
         if (partial) {
 #pragma unroll
             for (int j = 0; j < NVEC; ++j) E::mask_tail(tb[j], (j * THREADS + tid) * EPV, V);
         }
-        auto sum_about = [&](float nref) {
-            float zacc[4] = {0.f, 0.f, 0.f, 0.f};
+    };
+    // (the lane's share of the sum about the reference nref)
+    auto verifier_lane_sum = [&](u32x4 (&tb)[NVEC], float nref) {
+        float zacc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int j = 0; j < NVEC; ++j) {
-                float tv[EPV];
-                E::unpack(tb[j], tv);
+        for (int j = 0; j < NVEC; ++j) {
+            float tv[EPV];
+            E::unpack(tb[j], tv);
 #pragma unroll
-                for (int k = 0; k < EPV; ++k) zacc[k & 3] += exp2_ref(tv[k], nref);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            return wave_sum((double)((zacc[0] + zacc[1]) + (zacc[2] + zacc[3])));
-        };
-        ntw = guess == -INFINITY ? 0.f : guess;
-        Zw = sum_about(ntw);
+            for (int k = 0; k < EPV; ++k) zacc[k & 3] += exp2_ref(tv[k], nref);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        return (double)((zacc[0] + zacc[1]) + (zacc[2] + zacc[3]));
+    };
+    // (the sum about the guess was out of range: about the wave's own maximum)
+    auto verifier_redo = [&](u32x4 (&tb)[NVEC], float& ntw, double& Zw) {
         if (!(Zw >= 0x1p-40 && Zw <= 0x1p100)) {                   // uniform over the wave; also taken by NaN
             float mt = -INFINITY;
 #pragma unroll
@@ -437,8 +449,14 @@ void stream_kernel(const RowArgs A)
                 for (int k = 0; k < EPV; ++k) mt = fmaxf(mt, tv[k]);
             }
             ntw = ref_of(wave_max(mt));
-            Zw = sum_about(ntw == -INFINITY ? 0.f : ntw);          // an all-masked wave: every term is 2^-inf = 0
+            Zw = wave_sum(verifier_lane_sum(tb, ntw == -INFINITY ? 0.f : ntw));   // an all-masked wave: every term is 2^-inf = 0
         }
+    };
+    auto verifier_stats = [&](u32x4 (&tb)[NVEC], float guess, float& ntw, double& Zw) {
+        verifier_mask(tb);
+        ntw = guess == -INFINITY ? 0.f : guess;
+        Zw = wave_sum(verifier_lane_sum(tb, ntw));
+        verifier_redo(tb, ntw, Zw);
     };
 
     // ---- which rows this workgroup takes ---------------------------------------------------------------------
@@ -721,11 +739,19 @@ void stream_kernel(const RowArgs A)
             load_row(buf, A.target, row);
             __builtin_amdgcn_sched_barrier(0);
         }
+        float ntw = -INFINITY;                                     // the reference this wave's Z_w is taken about
+        bool lane_sums = false;                                    // uniform: q5[1], q5[3] are still the lanes' own sums
         if constexpr (DO_Q) {
             // x_i = e_i fw / S: hand fuse_row the partition sum expressed in this wave's units
             // (fw is a power of two: the division is a change of exponent)
             const double Su = nw == -INFINITY ? 1.0 : ldexp(S, (int)fminf(n - nw, 1000.f));   // S / fw
-            const FuseRow fr = fuse_row(Su, A.a, A.b);
+            // (the call's a, b and polynomial bound through opaque copies in scalar registers: what is derived from
+            // them -- a - 1, 1 - b, the bound as a double -- is then formed here, an instruction each, instead of ahead
+            // of the row loop, where it is kept in vector registers, or spilled, for all of it)
+            double ra = A.a, rb = A.b;
+            float wpx = A.wpoly_x;
+            if constexpr (sizeof(T) == 2) asm volatile("" : "+s"(ra), "+s"(rb), "+s"(wpx));   // (fp32 instances: no gain, measured)
+            const FuseRow fr = fuse_row(Su, ra, rb);
             double q5[NQ];
             auto shift_of = [&](float eref, const FuseRow& r) {
                 Shift k;
@@ -760,7 +786,7 @@ void stream_kernel(const RowArgs A)
                 const float is = -fr.nih, is2 = is * is;
                 wp.d0 = A.wpoly[0] * is; wp.d1 = A.wpoly[1] * is2; wp.d2 = A.wpoly[2] * (is2 * is);
                 wp.d3 = A.wpoly[3] * (is2 * is2);
-                wp.ethr = A.wpoly_x < 0.f ? -1.f : (float)((double)A.wpoly_x * Su);
+                wp.ethr = wpx < 0.f ? -1.f : (float)((double)wpx * Su);
                 // uniform over the wave: scalar registers (an FMA reads one of them per issue, so d2 stays a vector)
                 auto uniform = [](float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); };
                 wp.d0 = uniform(wp.d0); wp.d1 = uniform(wp.d1); wp.d3 = uniform(wp.d3); wp.ethr = uniform(wp.ethr);
@@ -801,8 +827,18 @@ void stream_kernel(const RowArgs A)
                 if (partial)    fuse_sums<THREADS, NVEC, EPV, true, true, true>(e, fr, wp, sh, V, tid, q5);
                 else if (split) fuse_sums<THREADS, NVEC, EPV, true, true, false>(e, fr, wp, sh, V, tid, q5);
                 else            fuse_sums<THREADS, NVEC, EPV, true, false, false>(e, fr, wp, sh, V, tid, q5);
-                q5[1] = wave_sum(q5[1]);
-                q5[3] = wave_sum(q5[3]);
+                if constexpr (BATCH3) {
+                    // reduced below, together with the verifier row's sum; until then the quads' sums wait in LDS
+                    // (slot addresses from an opaque copy of the lane index: hoisted out of the row loop they are spilled)
+                    lane_sums = true;
+                    int ol = tid;
+                    asm volatile("" : "+v"(ol));
+                    wave_sum3_put(q5[1], sm_red[ol >> 6], 0, ol & 63);
+                    wave_sum3_put(q5[3], sm_red[ol >> 6], 1, ol & 63);
+                } else {
+                    q5[1] = wave_sum(q5[1]);
+                    q5[3] = wave_sum(q5[3]);
+                }
             } else {
                 if (partial) fuse_sums<THREADS, NVEC, EPV, false, true, true>(e, fr, wp, sh, V, tid, q5);
                 else         fuse_sums<THREADS, NVEC, EPV, false, true, false>(e, fr, wp, sh, V, tid, q5);
@@ -813,6 +849,27 @@ void stream_kernel(const RowArgs A)
                 q5[5] = wave_sum(q5[5]);
                 q5[6] = wave_sum(q5[6]);
                 q5[7] = (double)wave_max((float)q5[7]);
+            }
+            if constexpr (BATCH3) {
+                // ---- T (these instances): verifier row statistics, per wave ----------------------------------------
+                if constexpr (!EARLY_T) {
+                    // no registers to spare next to the interval pass: the verifier row is fetched only now
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_row(buf, A.target, row);
+                }
+                verifier_mask(buf);
+                ntw = nw == -INFINITY ? 0.f : nw;
+                double Zw = verifier_lane_sum(buf, ntw);
+                if (lane_sums) {
+                    int ol = tid;
+                    asm volatile("" : "+v"(ol));
+                    wave_sum3_put(Zw, sm_red[ol >> 6], 2, ol & 63);
+                    wave_sum3_get(sm_red[ol >> 6], ol & 63, q5[1], q5[3], Zw);
+                } else {
+                    Zw = wave_sum(Zw);
+                }
+                verifier_redo(buf, ntw, Zw);
+                if (lane == 0) { sm_nt[wave] = ntw; sm_Z[wave] = Zw; }
             }
             if (lane == 0) {
                 // to row units (the complements are plain numbers: nothing to rescale)
@@ -860,8 +917,7 @@ void stream_kernel(const RowArgs A)
         }
 
         // ---- T: verifier row statistics, per wave -----------------------------------------------------------
-        float ntw = -INFINITY;                                     // the reference this wave's Z_w is taken about
-        if constexpr (DO_V) {
+        if constexpr (DO_V && !BATCH3) {
             double Zw;
             if constexpr (!EARLY_T) {
                 // no registers to spare next to the interval pass: the verifier row is fetched only now
