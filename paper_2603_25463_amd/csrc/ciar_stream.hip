@@ -512,6 +512,9 @@ void stream_kernel(const RowArgs A)
         // before the first row, kept in registers or spilled for the whole of the row loop)
         int ft = tid;
         asm volatile("" : "+v"(ft));
+        // (likewise the piece length: the divisions by it below otherwise start from what the prologue formed)
+        int unit_f = unit;
+        asm volatile("" : "+s"(unit_f));
         const int i = ft & 127;                                    // the parked row this lane works on
         const bool mine = ft < 256 && i < cnt;
         const bool qjob = mine && ft < 128, vjob = DO_V && mine && ft >= 128;
@@ -551,20 +554,24 @@ void stream_kernel(const RowArgs A)
                 const int id = sm_draw[i];                         // -1, a draw, or kDrawPending
                 if (A.accept) A.accept[r] = (uint8_t)(id == -1);
                 if (A.row_id) A.row_id[r] = id;
-                const int K = A.window;
-                if (unit == K && !A.win_count && (A.accept_len || A.resampled_id) && i % K == 0) {   // pieces start at multiples of K
+                // (an opaque copy: the reciprocal that the divisions by K below start from is otherwise the one the
+                // workgroup formed for its claim ahead of the first row, kept -- spilled -- through the whole row loop)
+                int K = A.window;
+                asm volatile("" : "+s"(K));
+                if (unit_f == K && !A.win_count && (A.accept_len || A.resampled_id) && i % K == 0) {   // pieces start at multiples of K
                     const int64_t left = nrows - r;
                     const int len = (int)(left < K ? left : K);
                     int m = 0;
                     while (m < len && sm_draw[i + m] == -1) ++m;
-                    if (A.accept_len) A.accept_len[r / K] = m;
+                    const uint32_t w = (uint32_t)r / (uint32_t)K;
+                    if (A.accept_len) A.accept_len[w] = m;
                     // (a pending draw: resample_kernel writes the window's entry when it has drawn that row)
                     if (A.resampled_id && (m == len || sm_draw[i + m] != kDrawPending))
-                        A.resampled_id[r / K] = m < len ? sm_draw[i + m] : -1;
+                        A.resampled_id[w] = m < len ? sm_draw[i + m] : -1;
                 }
                 if constexpr (KEEP_E) {
-                    const int64_t w = r / K, lo = w * K;
-                    if (A.win_count && (i % unit == 0 || r == lo)) {
+                    const int64_t w = (int64_t)((uint32_t)r / (uint32_t)K), lo = w * K;
+                    if (A.win_count && (i % unit_f == 0 || r == lo)) {
                         // A window that spans workgroups: the consecutive rows of it that this workgroup holds (one
                         // row where the rows are dealt out singly: measured the fastest for such launches, 58.8 us per
                         // step on workload 2 against 63.2 us with four consecutive rows per workgroup, whose two
@@ -572,7 +579,7 @@ void stream_kernel(const RowArgs A)
                         // window's 64-bit word (window_arrive), from the lane of the first of them, and the arrival
                         // that completes the window writes its outputs.
                         const int len = (int)(nrows - lo < K ? nrows - lo : K);
-                        const int piece_end = i - i % unit + unit;
+                        const int piece_end = i - i % unit_f + unit_f;
                         int rows = 0, off = 0, mine_id = -1;
                         for (; i + rows < cnt && i + rows < piece_end && r + rows < lo + len; ++rows) {
                             if (mine_id < 0 && sm_draw[i + rows] >= 0) { mine_id = sm_draw[i + rows]; off = (int)(r + rows - lo); }
@@ -592,10 +599,13 @@ void stream_kernel(const RowArgs A)
     // This workgroup's rows: its pieces are whole except possibly the very last piece of the launch.
     int my_rows;
     {
-        const int64_t pieces = ((int64_t)nrows + unit - 1) / unit;
-        const int64_t mine = (int64_t)blockIdx.x < pieces ? (pieces - blockIdx.x + step - 1) / step : 0;
-        const bool owns_last = mine > 0 && (pieces - 1 - (int64_t)blockIdx.x) % step == 0;
-        my_rows = (int)(mine * unit - (owns_last ? pieces * unit - nrows : 0));
+        // (in 32 bits: the entry points take fewer than 2^31 rows, and a 64-bit division is ~150 scalar instructions in
+        // a chain -- three of them stood between the start of the kernel and its first request for a row)
+        const uint32_t b = blockIdx.x, un = (uint32_t)unit, st = (uint32_t)step;
+        const uint32_t pieces = ((uint32_t)nrows + un - 1u) / un;
+        const uint32_t mine = b < pieces ? (pieces - b + st - 1u) / st : 0u;
+        const bool owns_last = mine > 0u && (pieces - 1u - b) % st == 0u;
+        my_rows = (int)(mine * un - (owns_last ? pieces * un - (uint32_t)nrows : 0u));
     }
 
     // The row index is uniform over the workgroup: keep it in a scalar register.
@@ -616,7 +626,8 @@ void stream_kernel(const RowArgs A)
     unsigned long long claim_seen = 0;
     if constexpr (KEEP_E) {
         if (A.win_count && tid < cnt) {
-            const int64_t r = row_of(L0 + tid), lo = r / A.window * A.window;
+            const int64_t r = row_of(L0 + tid);
+            const int64_t lo = (int64_t)((uint32_t)r / (uint32_t)A.window * (uint32_t)A.window);
             if (tid % unit == 0 || r == lo) {
                 claim_word = A.win_count + 2 * lo;
                 claim_seen = __hip_atomic_load(claim_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
