@@ -629,6 +629,21 @@ def main() -> int:
                 o["cpu_baseline"] = r["cpu_baseline"]
             others.append(o)
         result["other_workloads"] = others
+        # The same steps dealt to two HIP streams in turn (each with its own outputs and workspace): consecutive batches
+        # are independent, so one launch's start and end overlap the other's streaming.  Throughput of the pair, not
+        # the latency of a step; the headline above stays the single-stream figure.
+        import copy
+        torch.cuda.empty_cache()
+        a2 = copy.copy(args)
+        a2.streams = 2
+        r = run_workload(a2, torch, ciar, wl, dev, 2, args.steps, args.warmup, args.copies, 2.0)
+        result["two_streams"] = {"workload": r["config"]["workload"], "streams": 2, "value": r["value"], "unit": r["unit"],
+                                 "steps": r["steps"], "ms_per_step": r["ms_per_step"],
+                                 "step_achieved": r["roofline"]["step_achieved"], "step_frac": r["roofline"]["step_frac"],
+                                 "input_copies_rotated": r["config"]["input_copies_rotated"]}
+        if "parity" in r:
+            result["two_streams"]["parity"] = r["parity"]
+            failed = failed or r["parity"]["mismatches"] != 0
         # The benchmark recipe in a batch eight times as large (64 images = 16384 positions, 2.1 GB of logits per
         # step): what the call sustains once a launch is long against its own start and end.  The 2048 positions of
         # the headline are 4 rows per resident workgroup, and a plain read of them reaches 6.2 of the 8 TB/s.

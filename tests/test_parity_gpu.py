@@ -787,6 +787,34 @@ def test_results_are_deterministic_and_stream_ordered(ciar):
         assert torch.equal(a[k], b[k]), k
 
 
+@pytest.mark.parametrize("dtype,V", [(torch.float32, 16384), (torch.bfloat16, 8192)])
+def test_calls_overlap_on_two_streams(ciar, dtype, V):
+    """Consecutive batches are independent: calls on two streams, each with its own outputs and workspace, may be in
+    flight together (bench.py's two-stream figure).  Every call must reproduce what the same batch gives on its own,
+    bit for bit -- windows that span workgroups meet in words of the call's own workspace, tagged per launch."""
+    N, K = 1024, 8
+    P = ciar.Params(confidence=0.9, window=K, tau=0.01)
+    batches = [_random_case(V, V, N, K, dtype, seed=900 + b, sigma=0.4) for b in range(2)]
+    refs = [ciar.quantify_verify(*b, P) for b in batches]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    wss = [torch.empty(ciar.workspace_bytes(N, P.to_c(batches[0][0])), dtype=torch.uint8, device="cuda") for _ in range(2)]
+    outs = [{k: torch.empty_like(v) for k, v in refs[0].items()} for _ in range(2)]
+    for rep in range(12):
+        for o in outs:
+            for v in o.values():
+                v.fill_(0)
+        torch.cuda.synchronize()
+        for lane in (0, 1):
+            b = (lane + rep) % 2                                   # the batches swap streams from round to round
+            ciar.quantify_verify(*batches[b], P, out=outs[lane], workspace=wss[lane], stream=streams[lane])
+        torch.cuda.synchronize()
+        for lane in (0, 1):
+            ref = refs[(lane + rep) % 2]
+            for k in ref:
+                assert torch.equal(outs[lane][k], ref[k]), (rep, lane, k)
+
+
 @pytest.mark.parametrize("N", [1, 2, 7, 255, 256, 257, 511, 513, 1025])
 def test_row_counts_around_the_block_sizes(ciar, oracle, N):
     """Row counts below, at and just above the finishing kernels' 256-row workgroups and the streaming
