@@ -43,3 +43,18 @@ def test_small_workload_and_radius_are_seeded_and_well_formed():
     r1, r2 = wl.make_radius(a), wl.make_radius(b)
     assert torch.equal(r1, r2) and r1.shape == a.draft.shape and r1.dtype == a.draft.dtype
     assert torch.isfinite(r1).all() and abs(float(r1.mean())) < 1.5
+
+
+def test_workload_with_another_number_of_images():
+    """`images` changes the batch size of a recipe and nothing else (bench.py's `sustained` entry and --images)."""
+    import torch
+    from paper_2603_25463_amd import workloads as wl
+    a = wl.make(2, device="cpu", rows=512, images=2)
+    b = wl.make(2, device="cpu", rows=512, images=2)
+    assert a.spec.images == 2 and a.spec.rows == 512 and a.spec.vocab == 16384 and a.spec.window == 8
+    assert a.draft.shape == (512, 16384) and a.draft.dtype == torch.float32
+    assert torch.equal(a.draft, b.draft) and torch.equal(a.ids, b.ids)
+    # the recipe's structure: peaked rows come in aligned 4 x 4 blocks of the 16 x 16 grid
+    pk = torch.from_numpy(a.peaked).reshape(2, 4, 4, 4, 4)        # image, block row, row in block, block col, col in block
+    assert (pk == pk[:, :, :1, :, :1]).all()
+    assert wl.make(2, device="cpu", rows=8, images=8).spec is wl.SPECS[2]
