@@ -20,7 +20,8 @@ __device__ __forceinline__ void window_of(const uint8_t* accept, const int32_t* 
         resampled_id[w] = (lo + n < hi) ? row_id[lo + n] : -1;
 }
 
-// Residual draw of the rejected rows (accept bit 0) of launches whose streaming kernel does not draw them itself (launches whose tiles do not hold both rows in registers: bf16, tensor radius, wide radii):
+// Residual draw of the rejected rows (accept bit 0) of launches whose streaming kernel does not draw them itself
+// (launches whose tiles do not hold both rows in registers: bf16, the 16-vector fp32 tile, wide radii):
 // res_i = max(0, q_i - p_i), inverse CDF in token order; both rows are fetched again, four vectors of each row per
 // lane in flight at once.  A row's draw is a chain of dependent steps (statistics, loads, totals, crossing chunk,
 // scan), so what matters is how many rows a compute unit has in flight: 256-lane workgroups, several per compute

@@ -14,7 +14,7 @@
 //                   token, the exact accept test, the window outputs.  A call whose rows fit this scheme is this
 //                   one launch.
 //   resample_kernel (ciar_finish.hip) draws for the rejected rows of launches whose tiles cannot keep both rows in
-//                   registers (bf16, the 16-vector fp32 tile, tensor and wide radii), re-reading the two rows.
+//                   registers (bf16, the 16-vector fp32 tile, wide radii), re-reading the two rows.
 //
 // The centre row has to be resident between its statistics pass and its interval pass: the InterFuse
 // bounds need the partition sum S of the complete row before the first bound can be formed (App.
@@ -297,13 +297,21 @@ __device__ __forceinline__ void fuse_sums_rad(const float (&e)[NVEC * Elt<T>::kP
     if constexpr (WIDE) { q5[5] = c1; q5[6] = c2; q5[7] = (double)big; }
 }
 
-// Whether a launch with a verifier row makes the residual draws of its rejected rows inside the streaming kernel:
-// where a second row fits in the registers at four waves per SIMD next to the centre row's floats (fp32 tiles of up
-// to 8 vectors per lane, scalar radius).
+// Whether a second row fits in the registers at four waves per SIMD next to the centre row's floats (fp32 tiles of
+// up to 8 vectors per lane) ...
+// ... during the interval pass, so that the verifier row can be requested ahead of it (scalar radius: with a radius
+// tensor that place is taken by the raw radius row);
+template <typename T, int NVEC, bool DO_V, bool RAD, bool WIDE>
+constexpr bool second_row_early()
+{
+    return DO_V && !RAD && !WIDE && (NVEC * Elt<T>::kPerVec + NVEC * 4 + 56) * 4 <= 512;
+}
+// ... behind it, so that a launch with a verifier row makes the residual draws of its rejected rows inside the
+// streaming kernel (scalar or tensor radius: by then the verifier row has taken the raw radius row's place).
 template <typename T, int NVEC, bool DO_V, bool RAD, bool WIDE>
 constexpr bool draws_in_stream()
 {
-    return DO_V && !RAD && !WIDE && (NVEC * Elt<T>::kPerVec + NVEC * 4 + 56) * 4 <= 512;
+    return DO_V && !WIDE && (NVEC * Elt<T>::kPerVec + NVEC * 4 + 56) * 4 <= 512;
 }
 
 // sm_draw / row_id of a rejected row whose draw is still to be made (by resample_kernel)
@@ -322,13 +330,13 @@ void stream_kernel(const RowArgs A)
     // The verifier row is requested before the interval pass where a second row fits in the registers at
     // four waves per SIMD next to the centre row's floats (fp32 tiles of up to 8 vectors per lane; measured
     // 51 -> 48.6 us on the benchmark); elsewhere it would spill, and it is requested after the pass.
-    constexpr bool EARLY_T = draws_in_stream<T, NVEC, DO_V, RAD, WIDE>();
+    constexpr bool EARLY_T = second_row_early<T, NVEC, DO_V, RAD, WIDE>();
     // Quantify-only launches have no verifier row; under the same condition the next centre row is requested
     // before the interval pass instead.
     constexpr bool EARLY_NEXT = !DO_V && !RAD && !WIDE && (EPT + NVEC * 4 + 56) * 4 <= 512;
-    // A rejected row's draw needs both rows.  Where the verifier row is requested early, the centre row's
-    // exponentials simply stay in their registers next to it and the draw is made here (KEEP_E).  Elsewhere (bf16
-    // tiles, tensor radius, wide radii) the two do not fit: such rows are only marked, and resample_kernel
+    // A rejected row's draw needs both rows.  Where two rows fit, the centre row's exponentials simply stay in their
+    // registers next to the verifier row and the draw is made here (KEEP_E).  Elsewhere (bf16 tiles, the 16-vector
+    // fp32 tile, wide radii) the two do not fit: such rows are only marked, and resample_kernel
     // draws them behind this kernel (measured with the draw here and the centre row fetched again: the branch
     // alone, never taken, cost the bf16 row loop 11 % -- registers and scheduling -- and workload 3 ran 318 against
     // 285 us per step).
