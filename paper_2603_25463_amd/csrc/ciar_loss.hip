@@ -608,12 +608,12 @@ __global__ __launch_bounds__(256) void dro_row_tiny_kernel(const RowArgs A, floa
 // terms.  One workgroup of 256 lanes; losses = { centre, upper, lower, DRO, total }.  One fp64 exponential per row:
 // the unnormalised weight is parked in `weights` (when the caller wants them) and scaled by the normaliser in a last
 // pass by the lane that wrote it.
-__global__ __launch_bounds__(256) void dro_batch_kernel(const float* __restrict__ terms, int64_t N, double lambda_v,
+__global__ __launch_bounds__(1024) void dro_batch_kernel(const float* __restrict__ terms, int64_t N, double lambda_v,
                                                         double lambda_p, double lambda_beta, double alpha,
                                                         float* __restrict__ weights, float* __restrict__ losses)
 {
-    constexpr int NW = 4, T = 256;
-    __shared__ double sm[NW * 5];
+    constexpr int NW = 16, T = 1024;                                // (a single workgroup: the kernel is a chain of two
+    __shared__ double sm[NW * 5];                                  // reductions over the rows, as short as its lanes are many)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* ce_lo = terms + 5 * N;
     float mxf = -INFINITY;
@@ -729,7 +729,7 @@ hipError_t launch_dro(int dtype, const RowArgs& args, float* terms, double lambd
 #undef CIAR_DRO_LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || (!weights && !losses)) return e;
-    hipLaunchKernelGGL(dro_batch_kernel, dim3(1), dim3(256), 0, stream, terms, args.N, lambda_v, lambda_p,
+    hipLaunchKernelGGL(dro_batch_kernel, dim3(1), dim3(1024), 0, stream, terms, args.N, lambda_v, lambda_p,
                        lambda_beta, alpha, weights, losses);
     return hipGetLastError();
 }
