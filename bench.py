@@ -330,7 +330,7 @@ ORACLE_SAMPLE_ROWS = 2048      # rows of a workload the oracle is run on (parity
 
 
 def run_workload(args, torch, ciar, wl, dev, workload: int, steps: int, warmup: int, copies: int, cpu_seconds: float,
-                 images: int | None = None):
+                 images: int | None = None, sweep=()):
     """Times `steps` passes of the hot path over workload `workload` and checks the last pass against the oracle.
     Returns the dict of one JSON line (without the other workloads)."""
     import ctypes
@@ -364,6 +364,7 @@ def run_workload(args, torch, ciar, wl, dev, workload: int, steps: int, warmup: 
 
     L = ciar.lib()
     cp = P.to_c(w.draft)
+    cps = {"cp": cp}                             # the parameters the steps run with (the confidence sweep swaps them)
     # one lane per stream: its own outputs and workspace (default priority)
     streams = [torch.cuda.current_stream()] + [torch.cuda.Stream(device=dev) for _ in range(nstreams - 1)]
     outs = [outputs() for _ in range(nstreams)]
@@ -379,14 +380,14 @@ def run_workload(args, torch, ciar, wl, dev, workload: int, steps: int, warmup: 
         q = [_ptr(o[k]) for k in ("p_lo", "p_mid", "p_hi", "omega", "sigma", "score", "flags")]
         v = [_ptr(o[k]) for k in ("accept", "row_id", "accept_len", "resampled_id")]
         if args.mode == "quantify":              # no verifier row, no verification outputs
-            call = (_ptr(d), _ptr(rad), None, _ptr(w.ids), None, None, N, ctypes.byref(cp), *q, None, None, None, None,
+            call = (_ptr(d), _ptr(rad), None, _ptr(w.ids), None, None, N, ctypes.byref(cps["cp"]), *q, None, None, None, None,
                     _ptr(ws), ws.numel(), _stream(st))
         elif args.mode == "verify":              # no quantifier outputs
-            call = (_ptr(d), None, _ptr(t), _ptr(w.ids), _ptr(w.u_accept), _ptr(w.u_resample), N, ctypes.byref(cp),
+            call = (_ptr(d), None, _ptr(t), _ptr(w.ids), _ptr(w.u_accept), _ptr(w.u_resample), N, ctypes.byref(cps["cp"]),
                     *([None] * 7), *v, _ptr(ws), ws.numel(), _stream(st))
         else:
             call = (_ptr(d), _ptr(rad), _ptr(t), _ptr(w.ids), _ptr(w.u_accept), _ptr(w.u_resample), N,
-                    ctypes.byref(cp), *q, *v, _ptr(ws), ws.numel(), _stream(st))
+                    ctypes.byref(cps["cp"]), *q, *v, _ptr(ws), ws.numel(), _stream(st))
         if ev0 is not None:
             # the kernel's dispatch records the two events itself, at its start and at its end
             _check(L.ciar_stream_rows_timed(*call, ev0.cuda_event, ev1.cuda_event))
@@ -428,6 +429,20 @@ def run_workload(args, torch, ciar, wl, dev, workload: int, steps: int, warmup: 
     t1 = time.perf_counter()
     total_s = t1 - t0
     last = {k: v.clone() for k, v in outs[(steps - 1) % nstreams].items()}   # what the last timed step wrote
+    # other interval confidences on the same rows (workload 5's sweep): shorter runs of the same loop, timing only
+    # (parity at every confidence of the sweep is the test suite's: test_workload_full_size)
+    swept = []
+    for conf in sweep:
+        cps["cp"] = ciar.Params(confidence=conf, tau=0.30, window=K).to_c(w.draft)
+        for i in range(4):
+            step(i)
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for i in range(max(1, steps // 2)):
+            step(i)
+        torch.cuda.synchronize()
+        swept.append({"confidence": conf, "ms_per_step": 1e3 * (time.perf_counter() - c0) / max(1, steps // 2)})
+    cps["cp"] = cp
 
     # The ceiling the streaming kernel is held against: a plain read-and-add of the same rows through
     # ciar_read_rows_timed, same rotation of copies, its dispatch recording the events too (outside the timed
@@ -500,6 +515,8 @@ def run_workload(args, torch, ciar, wl, dev, workload: int, steps: int, warmup: 
                                                    / (ceil_ms * 1e-3) / 1e9}},
     }
 
+    if swept:
+        result["confidence_sweep"] = swept
     if args.no_cpu_baseline:
         return result
     # ---- the oracle on the same rows: parity of what was timed, then its own speed -----------------------------
@@ -615,13 +632,16 @@ def main() -> int:
         others = []
         for cfg in (1, 3, 4, 5):
             torch.cuda.empty_cache()
-            r = run_workload(args, torch, ciar, wl, dev, cfg, 200 if cfg == 1 else 100, 10, 8 if cfg == 1 else 2, 4.0)
+            r = run_workload(args, torch, ciar, wl, dev, cfg, 200 if cfg == 1 else 100, 10, 8 if cfg == 1 else 2, 4.0,
+                             sweep=(0.8, 0.95) if cfg == 5 else ())
             rf = r["roofline"]
             o = {"workload": r["config"]["workload"], "dtype": r["dtype"], "value": r["value"], "unit": r["unit"],
                  "steps": r["steps"], "ms_per_step": r["ms_per_step"], "stream_kernel_us": rf["kernel_avg_us"],
                  "kernel_frac": rf["frac"], "step_frac": rf["step_frac"],
                  "plain_read_us": rf["plain_read_ceiling"]["avg_us"], "launches_per_step": r["config"]["launches_per_step"],
                  "input_copies_rotated": r["config"]["input_copies_rotated"]}
+            if "confidence_sweep" in r:
+                o["confidence_sweep"] = r["confidence_sweep"]
             if "parity" in r:
                 o["parity"] = r["parity"]
                 failed = failed or r["parity"]["mismatches"] != 0
