@@ -207,11 +207,11 @@ int ciar_quantify_verify_static(const void* draft_logits, const void* radius, co
  *
  * ciar_stream_rows   the streaming kernel: reads every logit row once from HBM and writes every per-row output:
  *                    the quantifier's (p_lo ... flags) and, with a verifier row, the accept bits.  For float32
- *                    logits of up to 8192 tokens per 256 lanes (V <= 32768) under a scalar radius it also makes the
+ *                    logits (V <= 32768) under a scalar or tensor radius that is not very wide it also makes the
  *                    residual draws of the rejected rows, from the registers that still hold both rows, and
  *                    writes the window outputs; the call is then this one launch.  (Calls whose flat rows need the
  *                    fp64 pass launch that behind it, see the radius notes above.)
- * ciar_finish_rows   what remains, if anything: for bfloat16 logits, tensor radii and very wide radii the residual
+ * ciar_finish_rows   what remains, if anything: for bfloat16 logits and very wide radii the residual
  *                    draws of the rejected rows (their rows are read again), and the window outputs where neither
  *                    kernel could write them (windows longer than 255 rows that span workgroups).
  */
