@@ -47,7 +47,7 @@ constexpr uint32_t kRuledOutBits = 0xf1800000u;                    // (its upper
 // and a reference radius, the four partition sums together with the p_cloud-weighted sums of the exponents for the
 // cross-entropies, and the three L1 distances, which need all four normalisers.  With e = exp(o - reference):
 //   CE(p_cloud, softmax(o)) = (reference + ln S_o) - (sum_i et_i o_i) / Z,
-//   KL(p_cloud || p_mid)    = (sum_i et_i t_i) / Z - (max t + ln Z) + CE(p_cloud, p_mid).
+//   KL(p_cloud || p_mid)    = ln S_mid - ln Z + (sum_i et_i ((t_i - max t) - (c_i - max c))) / Z.
 // terms[k * N + row], k = 0..6: L1(mid), L1(up), L1(lo), CE(mid), CE(up), CE(lo), KL.
 // Workgroup barrier for data exchanged through LDS only: waits for this wave's LDS operations and joins the barrier.
 // __syncthreads() would also wait for every outstanding global load (its fence covers all memory), and with it for
@@ -239,7 +239,8 @@ __device__ __forceinline__ void dro_row_compute(const RowArgs& A, const DroRadiu
     // for the centre and the cloud's own distribution the reference is the row maximum, d <= 0 and both terms are
     // non-negative, so nothing is lost to cancellation whatever the size of the logits (for c + r and c - r see
     // pass 1); likewise the entropy of p_cloud, H = ln Z - (sum_i et_i dt_i) / Z, and
-    // KL(p_cloud || p_mid) = CE(p_cloud, p_mid) - H.
+    // KL(p_cloud || p_mid) = CE(p_cloud, p_mid) - H = ln S - ln Z + (sum_i et_i (dt_i - d_i)) / Z: the fourth weighted
+    // sum is taken over the differences dt_i - d_i, so that a small KL is not the difference of two large sums.
     // With at most 16 tokens per lane the four exponentials of every token are kept for pass 3 (the rows themselves
     // are not needed again).  The partition sums run in fp64 from the first add: in a row with one dominant token the
     // lane that holds it carries nearly all of S, so a lane sum kept in fp32 would round S itself to 6e-8, and ln S
@@ -290,11 +291,11 @@ __device__ __forceinline__ void dro_row_compute(const RowArgs& A, const DroRadiu
                 em[j * EPV + k] = e0; eu[j * EPV + k] = e1; el[j * EPV + k] = e2; ec[j * EPV + k] = et;
                 acc[0] += (double)e0; acc[1] += (double)e1; acc[2] += (double)e2; acc[3] += (double)et;
                 s32[4] = fmaf(et, x0, s32[4]); s32[5] = fmaf(et, x1, s32[5]);
-                s32[6] = fmaf(et, x2, s32[6]); s32[7] = fmaf(et, xt, s32[7]);
+                s32[6] = fmaf(et, x2, s32[6]); s32[7] = fmaf(et, xt - x0, s32[7]);
             } else {
                 acc[0] += (double)e0; acc[1] += (double)e1; acc[2] += (double)e2; acc[3] += (double)et;
                 acc[4] = fma((double)et, (double)x0, acc[4]); acc[5] = fma((double)et, (double)x1, acc[5]);
-                acc[6] = fma((double)et, (double)x2, acc[6]); acc[7] = fma((double)et, (double)xt, acc[7]);
+                acc[6] = fma((double)et, (double)x2, acc[6]); acc[7] = fma((double)et, (double)(xt - x0), acc[7]);
             }
             if (k & 1) __builtin_amdgcn_sched_barrier(0);          // two tokens at a time: bounded working set
         }
@@ -302,6 +303,7 @@ __device__ __forceinline__ void dro_row_compute(const RowArgs& A, const DroRadiu
     if (ce_infinite) {
 #pragma unroll
         for (int i = 4; i < 7; ++i) { s32[i] = -INFINITY; acc[i] = -INFINITY; }
+        s32[7] = INFINITY; acc[7] = INFINITY;                      // KL is infinite with the cross-entropies
     }
     if constexpr (CACHE_E) {
         // (the weighted sums of a quad in fp32 as well: one instruction per DPP step of a float, five of a double)
@@ -355,25 +357,32 @@ __device__ __forceinline__ void dro_row_compute(const RowArgs& A, const DroRadiu
 
     // pass 3: L1 distances to p_cloud.  With rho = S / Z,  |e / S - et / Z| = |e - rho et| / S:  the difference is one
     // fused multiply-add on the exponentials as they are, rounded once at its own (small) size, so tokens that carry
-    // most of both distributions cancel to the last bit and what remains is rho's rounding to fp32, at most 6e-8 of
-    // a distance of at most 2.  (A product e * (1/S) rounded on its own would leave that much per factor and per term.)
+    // most of both distributions cancel to the last bit.  rho is carried as two floats (a second multiply-add takes the
+    // low part): rounded to one float it is off by up to 6e-8 of itself, which moves every term the same way -- up to
+    // 6e-8 of the weight the cloud puts where the two distributions differ in one direction, and for a peaked row whose
+    // distance is small that was the whole absolute tolerance (a seeded random case: distance 4.0e-4, off by 1.06e-7).
+    // (A product e * (1/S) rounded on its own would leave that much per factor and per term.)
     // The division by S is left to dro_finish_row.
-    float rho[3];
+    float rho[3], rlo[3];
     {
         // 1 / Z: hardware reciprocal and one Newton step in fp64 (~1e-14), no fp64 division
         const double z = tot[3], r0 = (double)__builtin_amdgcn_rcpf((float)z);
         const double rz = fma(r0, fma(-z, r0, 1.0), r0);
 #pragma unroll
-        for (int i = 0; i < 3; ++i) rho[i] = (float)(tot[i] * rz);
+        for (int i = 0; i < 3; ++i) {
+            const double rr = tot[i] * rz;
+            rho[i] = (float)rr;
+            rlo[i] = (float)(rr - (double)rho[i]);
+        }
     }
     double l1[3] = {0.0, 0.0, 0.0};
     if constexpr (CACHE_E) {
         float a32[3] = {0.f, 0.f, 0.f};                            // (per lane in fp32: sums of non-negative terms)
 #pragma unroll
         for (int i = 0; i < NE; ++i) {
-            a32[0] += fabsf(fmaf(-ec[i], rho[0], em[i]));
-            a32[1] += fabsf(fmaf(-ec[i], rho[1], eu[i]));
-            a32[2] += fabsf(fmaf(-ec[i], rho[2], el[i]));
+            a32[0] += fabsf(fmaf(-ec[i], rlo[0], fmaf(-ec[i], rho[0], em[i])));
+            a32[1] += fabsf(fmaf(-ec[i], rlo[1], fmaf(-ec[i], rho[1], eu[i])));
+            a32[2] += fabsf(fmaf(-ec[i], rlo[2], fmaf(-ec[i], rho[2], el[i])));
         }
 #pragma unroll
         for (int i = 0; i < 3; ++i) l1[i] = (double)a32[i];
@@ -386,9 +395,9 @@ __device__ __forceinline__ void dro_row_compute(const RowArgs& A, const DroRadiu
                 float c, r, t;
                 element(j, k, c, r, t);
                 const float et = exp_rel(t, mt);
-                l1[0] += (double)fabsf(fmaf(-et, rho[0], exp_rel(c, mc)));
-                l1[1] += (double)fabsf(fmaf(-et, rho[1], exp_rel(c, r, mc, rref, 1.f)));
-                l1[2] += (double)fabsf(fmaf(-et, rho[2], exp_rel(c, r, mc, rref, -1.f)));
+                l1[0] += (double)fabsf(fmaf(-et, rlo[0], fmaf(-et, rho[0], exp_rel(c, mc))));
+                l1[1] += (double)fabsf(fmaf(-et, rlo[1], fmaf(-et, rho[1], exp_rel(c, r, mc, rref, 1.f))));
+                l1[2] += (double)fabsf(fmaf(-et, rlo[2], fmaf(-et, rho[2], exp_rel(c, r, mc, rref, -1.f))));
                 if (k & 1) __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -436,7 +445,11 @@ __device__ __forceinline__ void dro_finish_row(const RowArgs& A, float* __restri
     const double ce_mid = log(fin[0]) - fin[4] * ln2_Z;
     const double ce_up = log(fin[1]) - fin[5] * ln2_Z;
     const double ce_lo = log(fin[2]) - fin[6] * ln2_Z;
-    const double kl = ce_mid - (log(Z) - fin[7] * ln2_Z);          // cross-entropy minus the entropy of p_cloud
+    // KL = CE(p_cloud, p_mid) - H(p_cloud) = ln S - ln Z + sum_i p_cloud_i (dt_i - d_i): the last sum is taken over the
+    // differences token by token (fin[7]), so that a cloud row close to the centre row -- a small KL, the difference of two
+    // cross-entropy-sized numbers -- keeps its accuracy (a seeded random case missed the absolute bound by a quarter
+    // with the two sums taken separately)
+    const double kl = (log(fin[0]) - log(Z)) + fin[7] * ln2_Z;
     const int64_t N = A.N;
     terms[0 * N + row] = (float)(fin[8] / fin[0]); terms[1 * N + row] = (float)(fin[9] / fin[1]);
     terms[2 * N + row] = (float)(fin[10] / fin[2]);
@@ -608,12 +621,15 @@ __global__ __launch_bounds__(256) void dro_row_tiny_kernel(const RowArgs A, floa
 // terms.  One workgroup of 256 lanes; losses = { centre, upper, lower, DRO, total }.  One fp64 exponential per row:
 // the unnormalised weight is parked in `weights` (when the caller wants them) and scaled by the normaliser in a last
 // pass by the lane that wrote it.
-__global__ __launch_bounds__(1024) void dro_batch_kernel(const float* __restrict__ terms, int64_t N, double lambda_v,
+template <int T>
+__global__ __launch_bounds__(T) void dro_batch_kernel(const float* __restrict__ terms, int64_t N, double lambda_v,
                                                         double lambda_p, double lambda_beta, double alpha,
                                                         float* __restrict__ weights, float* __restrict__ losses)
 {
-    constexpr int NW = 16, T = 1024;                                // (a single workgroup: the kernel is a chain of two
-    __shared__ double sm[NW * 5];                                  // reductions over the rows, as short as its lanes are many)
+    // (a single workgroup: a chain of two reductions over the rows, as short as its lanes are many.  1024 lanes leave
+    // the fp64 exponential 128 registers and it spills a little: worth it only for many rows.)
+    constexpr int NW = T / 64;
+    __shared__ double sm[NW * 5];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* ce_lo = terms + 5 * N;
     float mxf = -INFINITY;
@@ -729,8 +745,12 @@ hipError_t launch_dro(int dtype, const RowArgs& args, float* terms, double lambd
 #undef CIAR_DRO_LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || (!weights && !losses)) return e;
-    hipLaunchKernelGGL(dro_batch_kernel, dim3(1), dim3(1024), 0, stream, terms, args.N, lambda_v, lambda_p,
-                       lambda_beta, alpha, weights, losses);
+    if (args.N > 8192)
+        hipLaunchKernelGGL(dro_batch_kernel<1024>, dim3(1), dim3(1024), 0, stream, terms, args.N, lambda_v, lambda_p,
+                           lambda_beta, alpha, weights, losses);
+    else
+        hipLaunchKernelGGL(dro_batch_kernel<512>, dim3(1), dim3(512), 0, stream, terms, args.N, lambda_v, lambda_p,
+                           lambda_beta, alpha, weights, losses);
     return hipGetLastError();
 }
 
