@@ -98,18 +98,24 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
     // numbers): the spread of a row whose widths all agree is then 0 instead of the rounding noise that the
     // difference of two large moments leaves.
     double KD = 0.0, KC = 0.0;
-    for (int h = 0; h < H; ++h) {
-        const T* crow = static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride;
-        const T* rrow = static_cast<const T*>(rad ? A.radius : A.draft) + (int64_t)h * head_stride + row * A.stride;
-        const float c0 = load_logit(crow, 0), r0 = load_logit(rrow, 0);
-        if (precise) head_token_tiny(h, c0, r0, KD, KC);
-        else head_token(h, c0, r0, sm_fr[h], KD, KC);
-    }
+    auto first_token = [&](bool in_fp64) {
+        KD = 0.0; KC = 0.0;
+        for (int h = 0; h < H; ++h) {
+            const T* crow = static_cast<const T*>(A.draft) + (int64_t)h * head_stride + row * A.stride;
+            const T* rrow = static_cast<const T*>(rad ? A.radius : A.draft) + (int64_t)h * head_stride + row * A.stride;
+            const float c0 = load_logit(crow, 0), r0 = load_logit(rrow, 0);
+            if (in_fp64) head_token_tiny(h, c0, r0, KD, KC);
+            else head_token(h, c0, r0, sm_fr[h], KD, KC);
+        }
+    };
+    first_token(precise);
     double s1 = 0.0, s2 = 0.0;                                     // sum (D_i - KD), sum (D_i - KD)^2
     double c1 = 0.0, c2 = 0.0, cbig = 0.0;                         // WIDE: sum (C_i - KC), its square, max C_i
     float best = -INFINITY;
     int best_i = INT_MAX;
-    if (precise) {
+    auto precise_sweep = [&]() {
+        s1 = 0.0; s2 = 0.0; c1 = 0.0; c2 = 0.0; cbig = 0.0;
+        best = -INFINITY; best_i = INT_MAX;
         for (int v = tid; v < nvec; v += 256) {
             double D[EPV], C[EPV];
             float pm[EPV];
@@ -141,7 +147,8 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
                 if (need_argmax && tok < V && pm[k] > best) { best = pm[k]; best_i = tok; }
             }
         }
-    }
+    };
+    if (precise) precise_sweep();
     // The sweep proper, specialised on what is uniform over the launch or the row: MODE bit 0 = tensor radius,
     // bit 1 = unit radius scale (see radius_am1), bit 2 = no head has an active cap (p^l is not needed).
     // Two 16-byte vectors of a head in flight per lane (fp32; one for bf16): more of them cost registers and
@@ -239,22 +246,50 @@ __global__ __launch_bounds__(256) void ensemble_kernel(const RowArgs A, const in
         default: sweep(std::integral_constant<int, 7>{}); break;
         }
     }
-    s1 = wave_sum(s1);
-    s2 = wave_sum(s2);
-    if (lane == 0) { sm_red[0][wave] = s1; sm_red[1][wave] = s2; }
-    if constexpr (WIDE) {
-        c1 = wave_sum(c1);
-        c2 = wave_sum(c2);
-        cbig = (double)wave_max((float)cbig);
-        if (lane == 0) { sm_red[2][wave] = c1; sm_red[3][wave] = c2; sm_red[4][wave] = cbig; }
+    auto reduce = [&]() {
+        s1 = wave_sum(s1);
+        s2 = wave_sum(s2);
+        if (lane == 0) { sm_red[0][wave] = s1; sm_red[1][wave] = s2; }
+        if constexpr (WIDE) {
+            c1 = wave_sum(c1);
+            c2 = wave_sum(c2);
+            cbig = (double)wave_max((float)cbig);
+            if (lane == 0) { sm_red[2][wave] = c1; sm_red[3][wave] = c2; sm_red[4][wave] = cbig; }
+        }
+        if (need_argmax) {
+            // each lane walked its tokens in ascending order, so it holds its lowest index of its maximum
+            const float wm = wave_max(best);
+            const int wi = wave_min_i(best == wm ? best_i : INT_MAX);
+            if (lane == 0) { sm_pm[wave] = wm; sm_pi[wave] = wi; }
+        }
+        __syncthreads();
+    };
+    reduce();
+    if (!precise) {
+        // A row whose averaged widths agree to better than a hundredth of their mean although it is not flat in the
+        // centre logits (heads whose widths crowd against 1 averaged with heads whose widths are next to nothing: every
+        // D_i is about the same number): the ~1e-7 that fp32 token arithmetic leaves in each width is then no longer
+        // small against the spread, and Omega multiplies what it does to Sigma (a seeded random case with a
+        // tensor radius of scale 17: score off by 2e-5 of itself).  Such rows -- rare -- are swept again in fp64.
+        // Every lane takes the same decision from the same numbers.
+        const double t1 = (sm_red[0][0] + sm_red[0][1]) + (sm_red[0][2] + sm_red[0][3]);
+        const double t2 = (sm_red[1][0] + sm_red[1][1]) + (sm_red[1][2] + sm_red[1][3]);
+        const double Vd = (double)V, mean = (t1 + Vd * KD) / Vd, varD = fmax(0.0, t2 - t1 * t1 / Vd) / Vd;
+        bool tight = varD < 1e-4 * mean * mean;
+        if constexpr (WIDE) {
+            // (not where the complement sums are read: they resolve exactly this case on their own)
+            const double ub = fmax(fmax(sm_red[4][0], sm_red[4][1]), fmax(sm_red[4][2], sm_red[4][3]));
+            bool plain = ub < kComplementBelow * (double)H;
+            for (int h = 0; h < H; ++h) plain = plain && sm_al[h] == 1.0 && sm_au[h] == 1.0;
+            tight = tight && !plain;
+        }
+        if (tight) {
+            __syncthreads();                                       // sm_red is read by every lane above
+            first_token(true);
+            precise_sweep();
+            reduce();
+        }
     }
-    if (need_argmax) {
-        // each lane walked its tokens in ascending order, so it holds its lowest index of its maximum
-        const float wm = wave_max(best);
-        const int wi = wave_min_i(best == wm ? best_i : INT_MAX);
-        if (lane == 0) { sm_pm[wave] = wm; sm_pi[wave] = wi; }
-    }
-    __syncthreads();
     if (tid == 0) {
         const double t1 = (sm_red[0][0] + sm_red[0][1]) + (sm_red[0][2] + sm_red[0][3]);
         const double t2 = (sm_red[1][0] + sm_red[1][1]) + (sm_red[1][2] + sm_red[1][3]);

@@ -1136,9 +1136,22 @@ def _random_shape(rng):
     return dtype, V, stride
 
 
+@pytest.mark.parametrize("seed", [10812])
+def test_random_parameters_multihead_found_cases(ciar, oracle, seed):
+    """A case that a long run of the random sweep below found.  10812: two heads under a radius tensor of scale 17, one
+    with widths next to 1 and one with widths next to nothing, so that every averaged width is about 1/2 and their
+    spread 2e-4 of that: the fp32 token arithmetic of the Ensemble sweep left the score 2e-5 off (such rows are now
+    swept again in fp64)."""
+    _random_multihead_case(ciar, oracle, seed)
+
+
 @pytest.mark.parametrize("seed", list(range(int(os.environ.get("CIAR_RANDOM_CASES", "16")))))
 def test_random_parameters_multihead(ciar, oracle, seed):
     """Ensemble and Voting with the number of heads, the shapes and the quantifier's parameters drawn at random."""
+    _random_multihead_case(ciar, oracle, seed)
+
+
+def _random_multihead_case(ciar, oracle, seed):
     rng = np.random.default_rng(19000 + seed)
     dtype, V, stride = _random_shape(rng)
     H = int(rng.integers(1, 9))
