@@ -1136,6 +1136,28 @@ def _random_shape(rng):
     return dtype, V, stride
 
 
+@pytest.mark.parametrize("seed", list(range(int(os.environ.get("CIAR_RANDOM_BATCHES", "6")))))
+def test_random_batches(ciar, oracle, seed):
+    """Whole batches of random size (one row to several thousand: one row per workgroup up to many, windows inside
+    workgroups and across them, the last one ragged), window length, vocabulary (every tile), dtype and radius mode,
+    every entry point against the oracle.  The threshold sits at the median score of a first pass."""
+    rng = np.random.default_rng(39000 + seed)
+    dtype = (torch.float32, torch.bfloat16)[int(rng.integers(0, 2))]
+    V = int(rng.choice([257, 1024, 4096, 8192, 16384, 32768 if dtype == torch.float32 else 65536]))
+    N = int(min(max(1, round(2.0 ** rng.uniform(0.0, 13.0))), max(1, 30_000_000 // V)))
+    K = int(rng.choice([1, 2, 3, 4, 8, 16, 37, 255, 300]))
+    stride = -(-V // 8) * 8                                        # rows are 16-byte aligned in either dtype
+    c, t, ids, ua, ur = _random_case(V, stride, N, K, dtype, seed=39100 + seed, sigma=float(10.0 ** rng.uniform(-1.5, 0.3)))
+    raw = _raw_radius(N, stride, V, dtype, seed=39200 + seed) if rng.integers(0, 3) == 0 else None
+    kw = dict(confidence=float(rng.choice([0.8, 0.9, 0.95])), window=K)
+    if raw is not None:
+        kw["radius_scale"] = 1.0
+    o0 = oracle.quantify(c.cpu(), ids.cpu().numpy(), _oparams(oracle, ciar.Params(tau=0.3, **kw)),
+                         radius=None if raw is None else raw.cpu())
+    tau = float(np.float32(np.median(np.asarray(o0["score"], dtype=np.float64))))
+    _run_case(ciar, oracle, c, t, ids, ua, ur, ciar.Params(tau=tau, **kw), vocab=V, tag=f"random batch {seed}", radius=raw)
+
+
 @pytest.mark.parametrize("seed", [10812])
 def test_random_parameters_multihead_found_cases(ciar, oracle, seed):
     """A case that a long run of the random sweep below found.  10812: two heads under a radius tensor of scale 17, one
