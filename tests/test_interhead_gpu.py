@@ -75,6 +75,31 @@ def test_interhead_logits(ciar, oracle, N, D, V, stride):
         assert np.all(g[:, V:] == 7.0), f"{name}: padding between rows was written"
 
 
+@pytest.mark.parametrize("seed", list(range(int(__import__("os").environ.get("CIAR_RANDOM_CASES", "8")))))
+def test_interhead_logits_random_shapes(ciar, oracle, seed):
+    """Batch size, hidden width (1 to 20 k tiles), vocabulary (both tiles: multiples of 128 and of 256) and output stride
+    drawn at random; small integer operands, so that every partial sum is exact in fp32 and the kernel must match the
+    fp64 product bit for bit whatever the shape."""
+    rng = np.random.default_rng(49000 + seed)
+    N = int(rng.integers(1, 700))
+    D = 64 * int(rng.integers(1, 21))
+    V = 128 * int(rng.integers(1, 9))
+    stride = V + 4 * int(rng.integers(0, 3))
+    g = torch.Generator().manual_seed(49100 + seed)
+    h = torch.randint(-3, 4, (N, D), generator=g).to(torch.bfloat16)
+    w = torch.randint(-2, 3, (2 * V, D), generator=g).to(torch.bfloat16)
+    b = torch.randint(-5, 6, (2 * V,), generator=g).to(torch.float32) if rng.integers(0, 2) else None
+    say(f"[interhead random {seed}] N={N} D={D} V={V} stride={stride} bias={b is not None}")
+    out = (torch.full((N, stride), 7.0, device="cuda"), torch.full((N, stride), 7.0, device="cuda"))
+    c, r = ciar.interhead_logits(h.cuda(), w.cuda(), None if b is None else b.cuda(), ciar.Params(), row_stride=stride, out=out)
+    torch.cuda.synchronize()
+    oc, orr = oracle.interhead_logits(h, w, None if b is None else b.numpy())
+    for got, ref, name in ((c, oc, "centre"), (r, orr, "radius")):
+        gg = got.cpu().numpy().astype(np.float64)
+        assert np.array_equal(gg[:, :V], ref), (name, np.unravel_index(np.argmax(np.abs(gg[:, :V] - ref)), ref.shape))
+        assert np.all(gg[:, V:] == 7.0), f"{name}: padding between rows was written"
+
+
 def test_interhead_logits_without_bias_and_exact_integers(ciar, oracle):
     """Small integer operands: every product and partial sum is exact in fp32, so the kernel must match bit for bit
     (any wrong lane, row or column mapping of the matrix instruction shows as a wrong integer)."""
