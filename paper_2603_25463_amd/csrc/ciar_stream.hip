@@ -653,6 +653,9 @@ void stream_kernel(const RowArgs A)
         if (claim_word) window_claim(claim_word, A.tag, claim_seen);
     }
 
+    if constexpr (THREADS < 1024) {
+        if (cnt > 1) __builtin_amdgcn_s_setprio(3);                // (see "Wave priority by progress" at the end of the loop)
+    }
     for (int done = 0;; ++done) {                                  // done = rows of this batch already streamed
         const bool has_next = done + 1 < cnt;                      // uniform
         // (the rows are walked without a division: within a piece the next row, at its end the next piece)
@@ -1251,6 +1254,22 @@ void stream_kernel(const RowArgs A)
 
         if (!has_next) break;
         row = next;
+        // Wave priority by progress (set here for the next row; the first row runs at priority 3): the workgroups of a compute unit are served oldest first, so the one that was
+        // dispatched first runs at full speed and the others on what it leaves (a timeline of the benchmark launch: the
+        // first workgroup of every compute unit took 7.5 us per row and ended at 39 us, the second 12 us per row and ended
+        // at 49 us, alone on its compute unit for the last 10 us).  A workgroup therefore runs the first quarter of its
+        // rows at priority 3, the second at 2, ...: whoever is behind is served first, and the workgroups of a compute
+        // unit end together (benchmark 55.6 -> 52.8 us per step, workload 4 347 -> 328 us, workload 3 276 -> 257 us).
+        // Not where a compute unit holds one workgroup only (1024 lanes), and not for a single row.
+        if constexpr (THREADS < 1024) {
+            if (cnt > 1) {
+                // (uniform; floor(4 done / cnt) without a division: compares and shifts on scalar registers)
+                if ((done + 1) < ((cnt + 3) >> 2)) __builtin_amdgcn_s_setprio(3);
+                else if ((done + 1) < ((cnt + 1) >> 1)) __builtin_amdgcn_s_setprio(2);
+                else if ((done + 1) < ((3 * cnt + 3) >> 2)) __builtin_amdgcn_s_setprio(1);
+                else __builtin_amdgcn_s_setprio(0);
+            }
+        }
     }
     if (finish) finish_batch(L0, cnt);
 }
