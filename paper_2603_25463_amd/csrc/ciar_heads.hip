@@ -406,7 +406,18 @@ void ensemble_fused_kernel(const RowArgs A, const int64_t head_stride)
     const int nvec = (V + EPV - 1) / EPV;
     const bool partial = V < NVEC * kFusedThreads * EPV;           // the row does not fill the tile
 
-    for (int64_t row = blockIdx.x; row < A.N; row += gridDim.x) {
+    // Wave priority by progress, as in the streaming kernel: the two workgroups of a compute unit are served oldest
+    // first; the one behind gets the higher priority, so that they end together.  (32-bit row arithmetic: scalar.)
+    const uint32_t n_rows = (uint32_t)A.N, g_step = gridDim.x;
+    const uint32_t my_cnt = blockIdx.x < n_rows ? (n_rows - blockIdx.x + g_step - 1u) / g_step : 0u;
+    uint32_t done = 0;
+    for (int64_t row = blockIdx.x; row < A.N; row += gridDim.x, ++done) {
+        if (my_cnt > 1u) {
+            if (done < ((my_cnt + 3u) >> 2)) __builtin_amdgcn_s_setprio(3);
+            else if (done < ((my_cnt + 1u) >> 1)) __builtin_amdgcn_s_setprio(2);
+            else if (done < ((3u * my_cnt + 3u) >> 2)) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
+        }
         // (the lane's offsets are formed anew for every position: hoisted out of the loop they would occupy registers
         // for the whole kernel)
         // (likewise the radius constants: what is derived from them is cheap, and uniform)
