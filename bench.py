@@ -2,10 +2,10 @@
 """Benchmark of the CIAR quantify+verify hot path on one MI355X.
 
 A *step* is one pass of the whole hot path over one batch of synthetic logits already resident
-in HBM: the streaming kernel (softmax statistics and the InterFuse sums of both rows), the
-finishing kernels (per-row scalars: U = Omega * Sigma, flag, accept test; then the residual draw of the
-rejected rows; both also write the window outputs), enqueued through the library's stage entry points
-(the same kernels and launch configuration as ciar_quantify_verify).  The workload is the
+in HBM: softmax statistics and the InterFuse sums of both rows, the per-row scalars (U = Omega * Sigma, flag,
+accept test), the residual draw of the rejected rows and the window outputs -- for the benchmark shape one launch
+of the streaming kernel -- enqueued through the library's stage entry points (the same kernels and launch
+configuration as ciar_quantify_verify).  The workload is the
 "256x256-class batch" (8 images x 16x16 = 2048 positions, V = 16384, fp32, K = 8), the
 configuration the headline metric is quoted on.  Eight distinct copies of the inputs are rotated
 so that the 256 MB last-level cache cannot serve a step's 268 MB of logits from the previous one.
@@ -20,6 +20,9 @@ that the kernel's own dispatch records on the launch stream at its start and end
 The outputs of the last timed step are checked against the oracle on the same rows under the parity rules of
 tests/parity.py (`parity` in the line; a mismatch makes the run fail), and the other four workloads are timed in
 short runs of the same kind (`other_workloads`), each with its own parity check on a 2048-row sample.
+`two_streams` is the headline's steps dealt to two streams in turn (throughput of two batches in flight),
+`sustained` the benchmark recipe with 64 images per step (--images 64): what the call sustains once a launch is
+long against its own start and end.
 
 Other lines of the same form, beyond the headline: --mode quantify | verify, --radius-tensor, --heads H,
 --interdro, and --interhead [--hidden D] (the Interval Head's contraction on the matrix cores, then the
