@@ -10,14 +10,23 @@ namespace {
 
 // ---- Inter-DRO loss, forward (Sec. 3.2.3: anchor, DRO and alignment equations) -----------------------------
 
-// e^((c + sign r) - (c* + sign r*)) about a reference pair (c*, r*), formed as (c - c*) + sign (r - r*): each
-// difference is exact for tokens near the reference and rounded relative to itself elsewhere, so c + r is never
+// The distributions over c + r and c - r are taken about a reference pair (cs, rs) from the differences c - cs and
+// r - rs: each is exact for tokens near the reference and rounded relative to itself elsewhere, so c + r is never
 // rounded to fp32.  That rounding, 6e-8 |c + r|, would be a relative error of the same size in the token's
 // probability, and for logits of magnitude ~30 it shows as ~1e-6 absolute in a cross-entropy and in an L1 distance.
-__device__ __forceinline__ float exp_rel(float c, float r, float cs, float rs, float sign)
+//
+// The exponentials of c + r and c - r are formed as products, e^(c - cs) e^(r - rs) and e^(c - cs) e^-(r - rs), not from
+// the sums of the exponents: where the radius is the same for every token of a row (scalar mode, or a row clamped at
+// r_max) r - rs is one number, and adding it to exponents of one binade rounds them all the same way -- by up to half
+// an ulp of that binade, another amount in the next one.  That tilts the distribution between the binades by up to
+// ~3e-7 of the mass they hold, upwards for c + r and downwards for c - r, and showed as 1.7e-7 absolute in an L1
+// distance of 6e-3 (a seeded random case).  As products the three distributions of such a row agree to the rounding
+// of single tokens.  |r - rs| <= r_max <= 16: the factors stay within 2^+-24.
+struct RadiusFactors { float up, lo; };
+__device__ __forceinline__ RadiusFactors radius_factors(float r, float rs)
 {
-    const float d = fmaf(sign, r - rs, c - cs);
-    return __builtin_amdgcn_exp2f(fmaf(d, kLog2eLo, d * kLog2eHi));
+    const float d = r - rs, x = fmaf(d, kLog2eLo, d * kLog2eHi);
+    return {__builtin_amdgcn_exp2f(x), __builtin_amdgcn_exp2f(-x)};
 }
 
 // r = min(kappa Softplus(raw), rmax) to ~1e-7 absolute (radius_r keeps small radii accurate relative to themselves, which
@@ -274,7 +283,8 @@ __device__ __forceinline__ void dro_row_compute(const RowArgs& A, const DroRadiu
         }
     }
     // The exponents are taken to base 2 once, x = d log2(e), and the weighted sums run over x (dro_finish_row
-    // multiplies them by ln 2); x_up and x_lo are x_mid +- (r - r*) log2(e).
+    // multiplies them by ln 2); x_up and x_lo are x_mid +- xa, xa = (r - r*) log2(e), so their weighted sums are those
+    // of x_mid and xa added and subtracted.
 #pragma unroll
     for (int j = 0; j < NVEC; ++j) {
 #pragma unroll
@@ -283,22 +293,30 @@ __device__ __forceinline__ void dro_row_compute(const RowArgs& A, const DroRadiu
             element(j, k, c, r, t);
             // (each difference is exact for tokens near the reference and rounded relative to itself elsewhere:
             // c + r is never rounded to fp32)
-            const float x0 = log2e_times(c - mc), xa = log2e_times(r - rref), x1 = x0 + xa, x2 = x0 - xa;
+            const float x0 = log2e_times(c - mc), xa = log2e_times(r - rref);
             const float xt = log2e_times(fmaxf(t - mt, -1e30f));
-            const float e0 = __builtin_amdgcn_exp2f(x0), e1 = __builtin_amdgcn_exp2f(x1);
-            const float e2 = __builtin_amdgcn_exp2f(x2), et = __builtin_amdgcn_exp2f(xt);
+            // (the exponentials of c + r and c - r are products: see radius_factors)
+            const float e0 = __builtin_amdgcn_exp2f(x0), et = __builtin_amdgcn_exp2f(xt);
+            const float e1 = e0 * __builtin_amdgcn_exp2f(xa), e2 = e0 * __builtin_amdgcn_exp2f(-xa);
             if constexpr (CACHE_E) {
                 em[j * EPV + k] = e0; eu[j * EPV + k] = e1; el[j * EPV + k] = e2; ec[j * EPV + k] = et;
                 acc[0] += (double)e0; acc[1] += (double)e1; acc[2] += (double)e2; acc[3] += (double)et;
-                s32[4] = fmaf(et, x0, s32[4]); s32[5] = fmaf(et, x1, s32[5]);
-                s32[6] = fmaf(et, x2, s32[6]); s32[7] = fmaf(et, xt - x0, s32[7]);
+                s32[4] = fmaf(et, x0, s32[4]); s32[5] = fmaf(et, xa, s32[5]);
+                s32[7] = fmaf(et, xt - x0, s32[7]);
             } else {
                 acc[0] += (double)e0; acc[1] += (double)e1; acc[2] += (double)e2; acc[3] += (double)et;
-                acc[4] = fma((double)et, (double)x0, acc[4]); acc[5] = fma((double)et, (double)x1, acc[5]);
-                acc[6] = fma((double)et, (double)x2, acc[6]); acc[7] = fma((double)et, (double)(xt - x0), acc[7]);
+                acc[4] = fma((double)et, (double)x0, acc[4]); acc[5] = fma((double)et, (double)xa, acc[5]);
+                acc[7] = fma((double)et, (double)(xt - x0), acc[7]);
             }
             if (k & 1) __builtin_amdgcn_sched_barrier(0);          // two tokens at a time: bounded working set
         }
+    }
+    // the sums over x_up = x_mid + xa and x_lo = x_mid - xa from the sums over x_mid and xa
+    {
+        const float sa = s32[5];
+        s32[5] = s32[4] + sa; s32[6] = s32[4] - sa;
+        const double da = acc[5];
+        acc[5] = acc[4] + da; acc[6] = acc[4] - da;
     }
     if (ce_infinite) {
 #pragma unroll
@@ -394,10 +412,11 @@ __device__ __forceinline__ void dro_row_compute(const RowArgs& A, const DroRadiu
             for (int k = 0; k < EPV; ++k) {
                 float c, r, t;
                 element(j, k, c, r, t);
-                const float et = exp_rel(t, mt);
-                l1[0] += (double)fabsf(fmaf(-et, rlo[0], fmaf(-et, rho[0], exp_rel(c, mc))));
-                l1[1] += (double)fabsf(fmaf(-et, rlo[1], fmaf(-et, rho[1], exp_rel(c, r, mc, rref, 1.f))));
-                l1[2] += (double)fabsf(fmaf(-et, rlo[2], fmaf(-et, rho[2], exp_rel(c, r, mc, rref, -1.f))));
+                const float et = exp_rel(t, mt), e0 = exp_rel(c, mc);
+                const RadiusFactors f = radius_factors(r, rref);
+                l1[0] += (double)fabsf(fmaf(-et, rlo[0], fmaf(-et, rho[0], e0)));
+                l1[1] += (double)fabsf(fmaf(-et, rlo[1], fmaf(-et, rho[1], e0 * f.up)));
+                l1[2] += (double)fabsf(fmaf(-et, rlo[2], fmaf(-et, rho[2], e0 * f.lo)));
                 if (k & 1) __builtin_amdgcn_sched_barrier(0);
             }
         }

@@ -75,7 +75,7 @@ def test_interhead_logits(ciar, oracle, N, D, V, stride):
         assert np.all(g[:, V:] == 7.0), f"{name}: padding between rows was written"
 
 
-@pytest.mark.parametrize("seed", list(range(int(__import__("os").environ.get("CIAR_RANDOM_CASES", "8")))))
+@pytest.mark.parametrize("seed", [int(__import__("os").environ.get("CIAR_RANDOM_FIRST", "0")) + k for k in range(int(__import__("os").environ.get("CIAR_RANDOM_CASES", "8")))])
 def test_interhead_logits_random_shapes(ciar, oracle, seed):
     """Batch size, hidden width (1 to 20 k tiles), vocabulary (both tiles: multiples of 128 and of 256) and output stride
     drawn at random; small integer operands, so that every partial sum is exact in fp32 and the kernel must match the
