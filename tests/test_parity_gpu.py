@@ -65,16 +65,14 @@ def _run_case(ciar, oracle, draft, target, ids, ua, ur, P, vocab=None, tag="", h
     staged = ciar.finish_rows(draft, target, ids, ua, ur, P, ws2, with_intervals=True, vocab=vocab, radius=radius,
                               out=staged)
     torch.cuda.synchronize()
-    # the entry points run the same arithmetic: identical decisions, floats equal up to the freedom the compiler
-    # has in contracting multiply-adds differently in the fused and the single-purpose kernels (seen only where
-    # Sigma is rounding noise, ~1e-25)
+    # the entry points run the same arithmetic: floats equal up to the freedom the compiler has in contracting
+    # multiply-adds differently in the fused and the single-purpose kernels (seen only where Sigma is rounding
+    # noise, ~1e-25); the two stages launch the fused call's own kernels: identical outputs
     for k in parity.FLOAT_KEYS:
         d = (fused[k].double() - qonly[k].double()).abs()
         assert bool((d <= 1e-6 * qonly[k].double().abs() + 1e-12).all()), \
             (k, int(d.argmax()), fused[k][d.argmax()].item(), qonly[k][d.argmax()].item())
     assert torch.equal(fused["flags"], qonly["flags"])
-    for k in ("accept", "row_id", "accept_len", "resampled_id"):
-        assert torch.equal(fused[k], vonly[k]), k
     for k in fused:
         assert torch.equal(fused[k], staged[k]), k
 
@@ -85,8 +83,23 @@ def _run_case(ciar, oracle, draft, target, ids, ua, ur, P, vocab=None, tag="", h
     ov = oracle.verify(dh, th, idh, uah, urh, OP, vocab=vocab)
     worst = parity.check_floats(fused, oq)
     ex_flag = parity.check_flags(fused["flags"], oq, float(np.float32(P.tau)))
-    st = parity.check_verify(fused, ov, uah, urh, P.window,
-                             residual_cdf=lambda r: oracle.residual_cdf(dh, th, r, OP, vocab=vocab))
+    cdf = lambda r: oracle.residual_cdf(dh, th, r, OP, vocab=vocab)
+    st = parity.check_verify(fused, ov, uah, urh, P.window, residual_cdf=cdf)
+    # The verify-only call runs other kernel instances than the fused call, and not always the same route to a draw
+    # (in the streaming kernel from fp32 residuals, or in resample_kernel): it is held to the oracle like the fused
+    # call, and to the fused call's decisions row by row wherever the oracle's margin to the decision is not below
+    # the exemption's -- a threshold within 1e-7 R of a token boundary may fall to either side in either of them.
+    parity.check_verify(vonly, ov, uah, urh, P.window, residual_cdf=cdf)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        close = np.abs(np.log(uah.astype(np.float64)) - np.minimum(0.0, ov["log_ratio"])) < parity.MARGIN
+    close |= (ov["accept"] == 0) & (ov["res_margin"] < parity.MARGIN)
+    far = torch.from_numpy(~close).to(fused["accept"].device)
+    for k in ("accept", "row_id"):
+        assert torch.equal(fused[k][far], vonly[k][far]), k
+    K = P.window
+    far_w = torch.from_numpy(np.array([not close[w * K:(w + 1) * K].any() for w in range(-(-N // K))], bool)).to(far.device)
+    for k in ("accept_len", "resampled_id"):
+        assert torch.equal(fused[k][far_w], vonly[k][far_w]), k
     say(f"   worst err/bound {max(worst.values()):.3f}; flagged {int(oq['flags'].sum())}/{N}; "
         f"exempt flag/accept/resample = {ex_flag}/{st['exempt_accept']}/{st['exempt_resample']}; "
         f"rejected {st['rejected']}")
@@ -1162,6 +1175,16 @@ def test_random_batches(ciar, oracle, seed):
                          radius=None if raw is None else raw.cpu())
     tau = float(np.float32(np.median(np.asarray(o0["score"], dtype=np.float64))))
     _run_case(ciar, oracle, c, t, ids, ua, ur, ciar.Params(tau=tau, **kw), vocab=V, tag=f"random batch {seed}", radius=raw)
+
+
+@pytest.mark.parametrize("seed", [201046])
+def test_random_batches_found_cases(ciar, oracle, seed):
+    """A batch that a long run of the sweep above found (bf16, V = 4096, tensor radius).  Row 1465 is rejected and its
+    u_res R lies 5e-8 R above the lower edge of the oracle's token, behind a stretch of tokens without residual mass:
+    the fused call and the verify-only call, both inside the margin band, drew different tokens (1662 and 1671; the
+    oracle 1672), and the test then demanded that the entry points agree on every row.  They are now compared with
+    each other where the oracle's margin is not below the exemption's, and each with the oracle under the margin rule."""
+    test_random_batches(ciar, oracle, seed)
 
 
 @pytest.mark.parametrize("seed", [10812])
