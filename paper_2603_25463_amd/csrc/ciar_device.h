@@ -430,6 +430,9 @@ __device__ __forceinline__ void fuse_token_rad_wide(float e, float raw, const Fu
     else fuse_token_rad_wide<false>(e, raw, r, m.kappa, m.rmax, m.am1_max, pl, w, ec);
 }
 
+// Vocabularies of at most this many tokens take fp64 token arithmetic (see fuse_sums_tiny, dro_row_tiny_kernel).
+constexpr int kTinyVocab = 64;
+
 // Per-row scalars of the quantifier from the five sums (fp64, one lane).
 struct RowScore { double alpha_l, alpha_u, omega, sigma, score; };
 
@@ -530,7 +533,39 @@ __device__ __forceinline__ bool finish_row(const RowArgs& A, int64_t row, const 
     const double S = st.S;
     const float n = st.n;
     if (do_q) {
-        const RowScore rs = finish_score(st.q, S, st.mode, A, st.kl, st.kw);
+        double q[5] = {st.q[0], st.q[1], st.q[2], st.q[3], st.q[4]};
+        // The token above 1/2 of a row whose caps can be active, once more in fp64.  Where a cap is active
+        // Omega = alpha_u S_u - alpha_l S_l is a small difference of numbers near 1, and on a nearly one-hot row S_l is
+        // little more than that token's lower bound: its fp32 evaluation in the streaming kernel (a hardware reciprocal
+        // of a rounded product and three more roundings) leaves ~2e-7 of it, the whole absolute tolerance of an Omega of
+        // 0.01 (a seeded random case: 2.04e-7 off).  At most one token of a row is above 1/2: the row's largest, whose
+        // wave has the row's reference, so its e and the fp32 values that the scalar-radius pass has added to the sums
+        // can be formed again here, by the same instructions, and exchanged for the fp64 values.  (Plain sums only:
+        // such a row is not flat.  Tensor-radius, wide-radius and tiny-vocabulary rows come from other passes.)
+        // (the call's constants through an empty asm: what is derived from them here is otherwise formed at the top of
+        // the calling kernel and kept -- in the streaming kernel: spilled -- through its row loop)
+        double fa = A.a, fb = A.b;
+        int fv = A.V;
+        asm volatile("" : "+s"(fa), "+s"(fb), "+s"(fv));
+        if (st.mode == kSumsFull && A.normalize && !A.radius && fv > kTinyVocab && fa < 3.0 * (double)fv &&
+            st.kl == 0.0 && st.kw == 0.0) {
+            const float etop = exp2_ref(st.mc, n == -INFINITY ? 0.f : n);
+            if ((double)etop > 0.5 * S) {
+                const double ed = (double)etop, invS = 1.0 / S;
+                const double x = ed * invS, om = fmax(0.0, S - ed) * invS;      // 1 - x from the sum of the other tokens
+                const double du = 1.0 + (fa - 1.0) * x, dl = fb + (1.0 - fb) * om;
+                const double gl = ed / dl, gw = gl * om / du;
+                float g, duf, omf;
+                fuse_parts<true>(etop, fuse_row(S, fa, fb), g, duf, omf);
+                const double glf = (double)(g * duf), gwf = (double)(g * omf);
+                q[0] += gl - glf;
+                q[1] += gw - gwf;
+                q[2] += gl * gl - glf * glf;
+                q[3] += gw * gw - gwf * gwf;
+                q[4] += gl * gw - glf * gwf;
+            }
+        }
+        const RowScore rs = finish_score(q, S, st.mode, A, st.kl, st.kw);
         if (A.omega) A.omega[row] = (float)rs.omega;
         if (A.sigma) A.sigma[row] = (float)rs.sigma;
         if (A.score) A.score[row] = (float)rs.score;
@@ -607,9 +642,6 @@ __device__ __forceinline__ void window_claim(unsigned long long* p, uint32_t tag
     const unsigned long long t31 = (unsigned long long)(tag & 0x7fffffffu), fresh = (t31 << 33) | (0xffull << 17);
     if ((seen >> 33) != t31) (void)atomicCAS(p, seen, fresh);
 }
-
-// Vocabularies of at most this many tokens take fp64 token arithmetic (see fuse_sums_tiny, dro_row_tiny_kernel).
-constexpr int kTinyVocab = 64;
 
 // Compute units of the current device (asked once per device, then cached; the cache is a relaxed atomic per device:
 // two threads that ask at once both write the same number).

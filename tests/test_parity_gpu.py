@@ -1035,6 +1035,15 @@ def _archetype_rows(N, V, stride, dtype, rng, dev_gen):
     return c
 
 
+@pytest.mark.parametrize("seed", [511620])
+def test_random_parameters_found_cases(ciar, oracle, seed):
+    """A case that a long run of the sweep below found.  511620 (V = 101, bf16, scalar radius 1.75): a nearly one-hot row
+    with both caps active, Omega = cap_hi - cap_lo = 0.01; the fp32 lower bound of the token above 1/2 left S_l 2e-7
+    off, which the cap then no longer absorbed: Omega 2.04e-7 off against a bound of 2.00e-7.  The finishing lane now
+    exchanges that token's fp32 values for fp64 ones."""
+    test_random_parameters(ciar, oracle, seed)
+
+
 @pytest.mark.parametrize("seed", _sweep_seeds("CIAR_RANDOM_CASES", 32))
 def test_random_parameters(ciar, oracle, seed):
     """Vocabulary, stride, dtype, window, radius mode, scale, clamp, caps and normalisation drawn at random (seeded),
